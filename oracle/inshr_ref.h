@@ -1,0 +1,102 @@
+/*
+ * inshr_ref -- CPU oracle for the checkpoint-compressor hot path (TEST INFRASTRUCTURE ONLY).
+ *
+ * A plain, slow, single-threaded C implementation of what the path computes, written from the
+ * paper's definitions: magnitude ranking (Sec. 4.1), prune / protect / quantize partition
+ * (Sec. 4.2), non-uniform bins with one centre per bin (Sec. 4.4, frequency-only reading with
+ * one centre update), the search for the most compact configuration that meets the error
+ * threshold (Sec. 5), cyclic delta of integer codes (Sec. 6, "Calculating Delta") and the
+ * regrouping by the previous checkpoint's bucket (Sec. 6, "Parameter Rearrangement",
+ * Algorithms 5 and 6).
+ *
+ * Nothing in the product path may include, link or call this file.  It shares no code with the
+ * HIP implementation.  All pointers are HOST pointers.  All order comparisons are made on
+ * integer images of the floats (see inshr_ref.c), sums are fp64 in ascending index order.
+ *
+ * Parity pins live in tests/test_oracle_*.py (closed forms, library sort/searchsorted,
+ * pure-Python brute force, invariants).  No function here is "parity unpinned".
+ */
+#ifndef INSHR_REF_H
+#define INSHR_REF_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    INSHR_REF_OK = 0,
+    INSHR_REF_E_ARG = -1,       /* null pointer, n == 0, n >= 2^32 */
+    INSHR_REF_E_CONFIG = -2,    /* bits outside 1..8 or prune_ppm + outlier_ppm >= 1e6 */
+    INSHR_REF_E_NONFINITE = -3, /* NaN or Inf in the input */
+    INSHR_REF_E_SHAPE = -5
+};
+
+typedef struct {
+    uint8_t bits;         /* K = 1 << bits bins, 1..8 */
+    uint32_t prune_ppm;   /* pruning fraction x 1e6   */
+    uint32_t outlier_ppm; /* protection fraction x 1e6 */
+} inshr_ref_config;
+
+typedef struct {
+    double sse;   /* sum over pruned of x^2 + sum over quantized of (x - centre)^2 */
+    double sumsq; /* sum over all of x^2 */
+    uint64_t n_pruned, n_outlier, n_kept;
+    uint64_t cost_bits; /* n_kept*bits + 32*n_outlier + 32*K */
+} inshr_ref_score;
+
+typedef struct {
+    uint64_t n_pruned, n_outlier, n_kept;
+    uint32_t sym_bits;          /* bits + 1 */
+    uint32_t tau_prune_bits;    /* magnitude image (bits & 0x7fffffff) of the prune threshold   */
+    uint32_t tau_outlier_bits;  /* magnitude image of the protection threshold                 */
+    double sse, sumsq;
+} inshr_ref_qinfo;
+
+/* Quantize one tensor with one configuration.
+ *   sym        [n]      out: symbol per element, 0 pruned, 1 protected, 2+bin quantized
+ *   boundaries [K-1]    out: interior bin boundaries t_1..t_{K-1} as floats
+ *   codebook   [K]      out: one centre per bin
+ *   out_idx/out_val [n_outlier_cap] out: protected (index ascending, original value); may be NULL
+ *                       when the configuration protects nothing; capacity floor(n*ppm/1e6)
+ */
+int inshr_ref_quantize(const float *x, uint64_t n, const inshr_ref_config *cfg, uint16_t *sym,
+                       float *boundaries, float *codebook, uint32_t *out_idx, float *out_val,
+                       inshr_ref_qinfo *info);
+
+/* Score every configuration of a grid independently and choose (Sec. 5): among configurations
+ * with sse/sumsq <= eps the least cost_bits, ties to the lowest grid index; if none, the least
+ * sse and *feasible = 0.  scores may be NULL. */
+int inshr_ref_search(const float *x, uint64_t n, const inshr_ref_config *grid, uint32_t n_cfg,
+                     double eps, uint32_t *best, uint8_t *feasible, inshr_ref_score *scores);
+
+/* Decode symbols back to floats: 0 -> +0.0, 1 -> listed original value, 2+b -> codebook[b]. */
+int inshr_ref_dequantize(const uint16_t *sym, uint64_t n, uint32_t bits, const float *codebook,
+                         const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,
+                         float *xhat);
+
+/* Cyclic delta of symbols and regrouping by the previous checkpoint's symbol.
+ *   delta     [n]  out: d[i] = (s_prev[i] - s_cur[i]) mod B, B = max(K_prev,K_cur) + 2 (may be NULL)
+ *   perm      [n]  out: indices in stable order of s_prev (may be NULL)
+ *   group_off [(1<<bits_prev)+3] out: group_off[g] = #{i : s_prev[i] < g}
+ *   stream    [n]  out: stream[r] = d[perm[r]]
+ */
+int inshr_ref_delta(const uint16_t *s_prev, uint32_t bits_prev, const uint16_t *s_cur,
+                    uint32_t bits_cur, uint64_t n, uint16_t *delta, uint32_t *perm,
+                    uint64_t *group_off, uint16_t *stream);
+
+/* Inverse of the regrouping + delta (Algorithm 6 with the sign of the delta formula):
+ * walks positions in index order and pops the next delta of the previous symbol's group. */
+int inshr_ref_reconstruct(const uint16_t *s_prev, uint32_t bits_prev, uint32_t bits_cur,
+                          uint64_t n, const uint64_t *group_off, const uint16_t *stream,
+                          uint16_t *s_cur);
+
+/* Little-endian bit stream: value i occupies bits [i*w, (i+1)*w) of the u64 word array,
+ * tail zero-padded.  words must hold ceil(n*w/64) entries. */
+int inshr_ref_pack(const uint16_t *v, uint64_t n, uint32_t w, uint64_t *words);
+int inshr_ref_unpack(const uint64_t *words, uint64_t n, uint32_t w, uint16_t *v);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

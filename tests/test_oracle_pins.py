@@ -1,0 +1,376 @@
+"""Pins of the CPU oracle against things other than itself: closed forms, numpy's sort /
+searchsorted, a pure-Python brute force written independently from the definitions, and
+invariants.  Each test is chosen so that a plausible slip in oracle/inshr_ref.c (dropped term,
+wrong sign or index, strict vs non-strict compare) fails it.  CPU only."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2306_11800_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------------------------
+# helpers that do NOT call the oracle
+# ---------------------------------------------------------------------------------------------
+
+def f32(v):
+    return float(np.float32(v))
+
+
+def brute_quantize(x, bits, p_ppm, o_ppm):
+    """Independent pure-Python statement of the definitions (sorted(), linear scans)."""
+    xs = [f32(v) + 0.0 for v in x]  # +0.0 turns -0.0 into +0.0
+    n = len(xs)
+    K = 2 ** bits
+    n_p = n * p_ppm // 10 ** 6
+    n_o = n * o_ppm // 10 ** 6
+    mags = sorted(abs(v) for v in xs)
+    tau_p, tau_o = mags[n_p], mags[n - 1 - n_o]
+    cls = ["p" if abs(v) < tau_p else ("o" if abs(v) > tau_o else "k") for v in xs]
+    Y = sorted(v for v, c in zip(xs, cls) if c == "k")
+    M = len(Y)
+    t = [Y[j * M // K] for j in range(1, K)]
+    sym, members = [], [[] for _ in range(K)]
+    for v, c in zip(xs, cls):
+        if c == "p":
+            sym.append(0)
+        elif c == "o":
+            sym.append(1)
+        else:
+            b = sum(1 for tj in t if tj <= v)
+            sym.append(2 + b)
+            members[b].append(v)
+    cb = []
+    for k in range(K):
+        if members[k]:
+            s = 0.0
+            for v in members[k]:
+                s += v
+            cb.append(f32(s / len(members[k])))
+        else:
+            cb.append(Y[0] if k == 0 else t[k - 1])
+    sse = 0.0
+    sumsq = 0.0
+    for v, s in zip(xs, sym):
+        sumsq += v * v
+        if s == 0:
+            sse += v * v
+        elif s >= 2:
+            sse += (v - cb[s - 2]) ** 2
+    n_out = sum(1 for s in sym if s == 1)
+    n_kept = sum(1 for s in sym if s >= 2)
+    return dict(sym=sym, t=t, cb=cb, sse=sse, sumsq=sumsq, n_pruned=sym.count(0), n_outlier=n_out,
+                n_kept=n_kept, cost=n_kept * bits + 32 * n_out + 32 * K, tau_p=tau_p, tau_o=tau_o)
+
+
+def brute_search(x, grid, eps):
+    rows = [brute_quantize(x, *g) for g in grid]
+    feas = [i for i, r in enumerate(rows)
+            if (r["sse"] / r["sumsq"] if r["sumsq"] > 0 else 0.0) <= eps]
+    if feas:
+        best = min(feas, key=lambda i: (rows[i]["cost"], i))
+        return best, 1, rows
+    best = min(range(len(rows)), key=lambda i: (rows[i]["sse"], i))
+    return best, 0, rows
+
+
+TINY_GRID = synth.make_grid([1, 2, 3, 8], [0.0, 0.1, 0.3, 0.5], [0.0, 0.001, 0.05, 0.2])
+
+
+def tiny_cases():
+    rng = np.random.default_rng(7)
+    cases = {
+        "n1": np.array([0.5], np.float32),
+        "n2": np.array([-1.0, 2.0], np.float32),
+        "const": np.full(13, 0.25, np.float32),
+        "zeros": np.zeros(9, np.float32),
+        "negzero_mix": np.array([0.0, -0.0, 1.0, -1.0, -0.0, 2.0, 0.0], np.float32),
+        "ties": np.array([1, 1, 1, 2, 2, -3, -3, -3, -3, 0, 0, 5], np.float32),
+        "ramp": np.arange(1, 65, dtype=np.float32),
+        "denorm": np.array([1e-45, -1e-45, 3e-39, -2e-39, 1e-38, 0.0, 1.0], np.float32),
+        "normal64": rng.normal(0, 0.02, 64).astype(np.float32),
+        "normal37": rng.normal(0, 1.0, 37).astype(np.float32),
+        "heavy50": (0.01 * rng.standard_t(3, 50)).astype(np.float32),
+        "few_distinct": rng.choice(np.array([-0.5, 0.1, 0.1, 0.7, 0.0], np.float32), 40),
+    }
+    return cases
+
+
+# ---------------------------------------------------------------------------------------------
+# brute force on tiny tensors: every configuration, every output
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", list(tiny_cases().keys()))
+def test_brute_force_tiny(name):
+    x = tiny_cases()[name]
+    for cfg in TINY_GRID:
+        b = brute_quantize(x, *cfg)
+        q = ref.quantize(x, cfg)
+        assert q["sym"].tolist() == b["sym"], (name, cfg)
+        assert [f32(v) for v in q["boundaries"]] == b["t"], (name, cfg)
+        assert [f32(v) for v in q["codebook"]] == b["cb"], (name, cfg)
+        assert q["n_pruned"] == b["n_pruned"] and q["n_outlier"] == b["n_outlier"]
+        assert q["n_kept"] == b["n_kept"]
+        assert q["sse"] == pytest.approx(b["sse"], rel=1e-12, abs=0.0)
+        assert q["sumsq"] == pytest.approx(b["sumsq"], rel=1e-12, abs=0.0)
+        assert f32(np.array([q["tau_prune_bits"]], np.uint32).view(np.float32)[0]) == b["tau_p"]
+        assert f32(np.array([q["tau_outlier_bits"]], np.uint32).view(np.float32)[0]) == b["tau_o"]
+    for eps in (-1.0, 0.0, 1e-3, 1e-2, 0.3, 10.0):  # -1: nothing feasible, ties on sse
+        best, feas, scores = ref.search(x, TINY_GRID, eps)
+        bb, bf, rows = brute_search(x, TINY_GRID, eps)
+        assert (best, feas) == (bb, bf), (name, eps)
+        for s, r in zip(scores, rows):
+            assert s["cost_bits"] == r["cost"]
+            assert s["n_kept"] == r["n_kept"]
+            assert s["sse"] == pytest.approx(r["sse"], rel=1e-12, abs=0.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# special case = textbook equal-frequency binning, against numpy's sort / searchsorted
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+def test_equal_frequency_binning_matches_numpy(bits):
+    x, _ = synth.config0(seed=3, n=50_000)
+    K = 1 << bits
+    q = ref.quantize(x, (bits, 0, 0))
+    srt = np.sort(x)
+    t = srt[(np.arange(1, K, dtype=np.int64) * x.size) // K]
+    assert np.array_equal(q["boundaries"].view(np.uint32), t.view(np.uint32))
+    codes = np.searchsorted(t, x, side="right")
+    assert np.array_equal(q["sym"], (codes + 2).astype(np.uint16))
+    # centres = per-bin means in fp64, rounded once to fp32
+    sums = np.bincount(codes, weights=x.astype(np.float64), minlength=K)
+    cnt = np.bincount(codes, minlength=K)
+    assert cnt.min() > 0
+    np.testing.assert_allclose(q["codebook"], (sums / cnt).astype(np.float32), rtol=1e-7)
+    xhat = (sums / cnt).astype(np.float32)[codes].astype(np.float64)
+    assert q["sse"] == pytest.approx(float(((x.astype(np.float64) - xhat) ** 2).sum()), rel=1e-9)
+    assert q["n_pruned"] == 0 and q["n_outlier"] == 0 and q["n_kept"] == x.size
+
+
+def test_thresholds_match_numpy_order_statistics():
+    x, _ = synth.config0(seed=5, n=40_000)
+    a = np.sort(np.abs(x))
+    for p_ppm, o_ppm in [(100000, 1000), (300000, 0), (0, 50000), (400000, 100), (999000, 999)]:
+        n_p = x.size * p_ppm // 10 ** 6
+        n_o = x.size * o_ppm // 10 ** 6
+        q = ref.quantize(x, (3, p_ppm, o_ppm))
+        tp, to = a[n_p], a[x.size - 1 - n_o]
+        assert q["tau_prune_bits"] == int(np.array([tp]).view(np.uint32)[0])
+        assert q["tau_outlier_bits"] == int(np.array([to]).view(np.uint32)[0])
+        pr = np.abs(x) < tp
+        ou = np.abs(x) > to
+        assert np.array_equal(q["sym"] == 0, pr)
+        assert np.array_equal(q["sym"] == 1, ou)
+        # continuous data: magnitudes distinct -> counts are exactly the floor counts
+        assert q["n_pruned"] == n_p and q["n_outlier"] == n_o
+        assert np.array_equal(q["outlier_idx"], np.nonzero(ou)[0].astype(np.uint32))
+        assert np.array_equal(q["outlier_val"].view(np.uint32), x[ou].view(np.uint32))
+        # kept values are binned by rank: populations are the floor differences
+        kept = np.sort(x[~pr & ~ou])
+        M = kept.size
+        K = 8
+        pop = np.bincount(q["sym"][q["sym"] >= 2] - 2, minlength=K)
+        expect = [(j + 1) * M // K - j * M // K for j in range(K)]
+        assert pop.tolist() == expect
+        t = kept[(np.arange(1, K) * M) // K]
+        assert np.array_equal(q["boundaries"].view(np.uint32), t.view(np.uint32))
+
+
+# ---------------------------------------------------------------------------------------------
+# closed form: the ramp 1..N (fixture derived by hand from the formulas, not from the oracle)
+# ---------------------------------------------------------------------------------------------
+
+def test_closed_form_ramp():
+    with open(os.path.join(GOLDEN, "ramp_closed_form.json")) as f:
+        gold = json.load(f)
+    for case in gold["cases"]:
+        N, bits = case["N"], case["bits"]
+        K = 1 << bits
+        m = N // K
+        x = np.arange(1, N + 1, dtype=np.float32)
+        q = ref.quantize(x, (bits, 0, 0))
+        assert q["boundaries"].tolist() == case["boundaries"]
+        assert q["codebook"].tolist() == case["codebook"]
+        assert q["sse"] == pytest.approx(case["sse"], rel=1e-13)
+        # and the formulas themselves
+        assert case["boundaries"] == [float(j * m + 1) for j in range(1, K)]
+        assert case["codebook"] == [k * m + (m + 1) / 2 for k in range(K)]
+        assert case["sse"] == K * m * (m * m - 1) / 12
+        assert np.array_equal(q["sym"], (np.arange(N) // m + 2).astype(np.uint16))
+
+
+def test_bins_equal_two_to_the_bits():
+    # the paper equates 8 bins with 3 bits (System Overview): K = 2**bits levels + prune + protect
+    x = np.arange(1, 1025, dtype=np.float32)
+    for bits in range(1, 9):
+        q = ref.quantize(x, (bits, 0, 0))
+        assert q["codebook"].size == 2 ** bits
+        assert q["sym"].max() == 2 ** bits + 1 and q["sym"].min() == 2
+        assert q["sym_bits"] == bits + 1
+
+
+# ---------------------------------------------------------------------------------------------
+# invariants
+# ---------------------------------------------------------------------------------------------
+
+def test_decode_invariants_and_optimal_centres():
+    x, _ = synth.config0(seed=11, n=30_000)
+    x[::1000] = 0.0
+    x[1::1000] = -0.0
+    for cfg in [(2, 100000, 1000), (4, 300000, 1000), (8, 0, 0), (3, 0, 1000)]:
+        bits = cfg[0]
+        K = 1 << bits
+        q = ref.quantize(x, cfg)
+        s = q["sym"]
+        assert s.max() < K + 2
+        xh = ref.dequantize(s, bits, q["codebook"], q["outlier_idx"], q["outlier_val"])
+        assert np.all(xh[s == 0].view(np.uint32) == 0)                       # pruned -> +0.0 exactly
+        assert np.array_equal(xh[s == 1].view(np.uint32), x[s == 1].view(np.uint32))  # bit-exact
+        mag = np.abs(x)
+        tp = np.array([q["tau_prune_bits"]], np.uint32).view(np.float32)[0]
+        to = np.array([q["tau_outlier_bits"]], np.uint32).view(np.float32)[0]
+        assert mag[s == 0].max(initial=-1) < tp <= mag[s >= 2].min()
+        assert mag[s >= 2].max() <= to < mag[s == 1].min(initial=np.inf)
+        # every decoded kept value lies inside its bin's span
+        t = q["boundaries"]
+        lo = np.concatenate([[-np.inf], t])
+        hi = np.concatenate([t, [np.inf]])
+        kept = s >= 2
+        b = s[kept].astype(int) - 2
+        assert np.all(x[kept] >= lo[b]) and np.all(x[kept] < hi[b])
+        assert np.all(xh[kept] >= lo[b]) and np.all(xh[kept] <= hi[b])
+        # sse equals the decoded error
+        err = float(((x.astype(np.float64) - xh.astype(np.float64)) ** 2).sum())
+        assert q["sse"] == pytest.approx(err, rel=1e-9)
+        # the mean minimises the squared error of a fixed partition: +-1 ulp does not lower it
+        for k in range(0, K, max(1, K // 8)):
+            mem = x[kept][b == k].astype(np.float64)
+            if mem.size == 0:
+                continue
+            c = q["codebook"][k]
+            base = ((mem - float(c)) ** 2).sum()
+            for c2 in (np.nextafter(c, np.float32(np.inf)), np.nextafter(c, np.float32(-np.inf))):
+                assert ((mem - float(c2)) ** 2).sum() >= base * (1 - 1e-12)
+
+
+def test_sse_non_increasing_in_bits():
+    # floor(j*M/2^b) = floor((j*2^(8-b))*M/2^8): coarser boundaries are a subset of finer ones,
+    # so refining the bins cannot raise the error (up to the fp32 rounding of the centres)
+    x = (0.02 * np.random.default_rng(2).standard_t(4, 20_000)).astype(np.float32)
+    for p, o in [(0, 0), (100000, 1000), (300000, 0)]:
+        prev = None
+        tprev = None
+        for bits in range(1, 9):
+            q = ref.quantize(x, (bits, p, o))
+            if prev is not None:
+                assert q["sse"] <= prev * (1 + 1e-9)
+                assert set(tprev.view(np.uint32).tolist()) <= set(q["boundaries"].view(np.uint32).tolist())
+            prev, tprev = q["sse"], q["boundaries"]
+
+
+def test_few_distinct_values_zero_error():
+    vals = np.array([-2.0, -0.5, 0.25, 3.0], np.float32)
+    x = np.repeat(vals, 25)
+    np.random.default_rng(0).shuffle(x)
+    q = ref.quantize(x, (2, 0, 0))
+    assert q["sse"] == 0.0
+    assert sorted(q["codebook"].tolist()) == vals.tolist()
+
+
+def test_constant_tensor_never_wiped_out():
+    x = np.full(1000, -0.125, np.float32)
+    for cfg in [(1, 500000, 400000), (8, 0, 0), (3, 999999, 0)]:
+        q = ref.quantize(x, cfg)
+        assert q["n_kept"] == 1000 and q["sse"] == 0.0
+        assert np.all(q["sym"] == (1 << cfg[0]) + 1)  # all boundaries equal -> last bin
+
+
+def test_errors():
+    x = np.ones(8, np.float32)
+    with pytest.raises(ref.RefError) as e:
+        ref.quantize(x, (0, 0, 0))
+    assert e.value.code == -2
+    with pytest.raises(ref.RefError) as e:
+        ref.quantize(x, (9, 0, 0))
+    assert e.value.code == -2
+    with pytest.raises(ref.RefError) as e:
+        ref.quantize(x, (4, 600000, 400000))
+    assert e.value.code == -2
+    for bad in (np.nan, np.inf, -np.inf):
+        y = x.copy()
+        y[3] = bad
+        with pytest.raises(ref.RefError) as e:
+            ref.quantize(y, (4, 0, 0))
+        assert e.value.code == -3
+        with pytest.raises(ref.RefError) as e:
+            ref.search(y, [(4, 0, 0)], 0.1)
+        assert e.value.code == -3
+
+
+# ---------------------------------------------------------------------------------------------
+# delta + regrouping
+# ---------------------------------------------------------------------------------------------
+
+def test_delta_properties():
+    rng = np.random.default_rng(4)
+    for bp, bc in [(3, 3), (2, 8), (8, 2), (4, 5), (1, 1)]:
+        n = 5000
+        sp = rng.integers(0, (1 << bp) + 2, n).astype(np.uint16)
+        sc = rng.integers(0, (1 << bc) + 2, n).astype(np.uint16)
+        B = max(1 << bp, 1 << bc) + 2
+        d = ref.delta(sp, bp, sc, bc)
+        assert np.array_equal(d["delta"], ((sp.astype(int) - sc.astype(int)) % B).astype(np.uint16))
+        assert d["delta"].max() < B
+        order = np.argsort(sp, kind="stable")
+        assert np.array_equal(d["perm"], order.astype(np.uint32))
+        assert sorted(d["perm"].tolist()) == list(range(n))            # bijection
+        goff = np.concatenate([[0], np.cumsum(np.bincount(sp, minlength=(1 << bp) + 2))])
+        assert np.array_equal(d["group_off"], goff.astype(np.uint64))
+        assert np.array_equal(d["stream"], d["delta"][order])
+        back = ref.reconstruct(sp, bp, bc, d["group_off"], d["stream"])
+        assert np.array_equal(back, sc)
+        assert d["delta_bits"] == max(bp, bc) + 1 and (1 << d["delta_bits"]) >= B
+    same = ref.delta(sp, bp, sp, bp)
+    assert not same["stream"].any() and not same["delta"].any()
+
+
+def test_delta_groups_by_hand():
+    # previous symbols 2,0,2,1,0 ; current 3,0,2,1,2 ; one bit -> K=2, B=4
+    sp = np.array([2, 0, 2, 1, 0], np.uint16)
+    sc = np.array([3, 0, 2, 1, 2], np.uint16)
+    d = ref.delta(sp, 1, sc, 1)
+    assert d["delta"].tolist() == [3, 0, 0, 0, 2]
+    assert d["perm"].tolist() == [1, 4, 3, 0, 2]
+    assert d["group_off"].tolist() == [0, 2, 3, 5, 5]
+    assert d["stream"].tolist() == [0, 2, 0, 3, 0]
+
+
+def test_pack_unpack_against_numpy_bits():
+    rng = np.random.default_rng(9)
+    for w in range(1, 10):
+        for n in (1, 63, 64, 65, 1000):
+            v = rng.integers(0, 1 << w, n).astype(np.uint16)
+            words = ref.pack(v, w)
+            bits = ((v[:, None] >> np.arange(w)) & 1).astype(np.uint8).ravel()
+            pad = (-bits.size) % 64
+            bits = np.concatenate([bits, np.zeros(pad, np.uint8)])
+            expect = np.packbits(bits, bitorder="little").view("<u8")
+            assert np.array_equal(words, expect)
+            assert np.array_equal(ref.unpack(words, n, w), v)
+
+
+def test_consecutive_checkpoints_mostly_same_bin():
+    # Sec. 6: most parameters stay in their bucket between adjacent checkpoints
+    x0, x1 = synth.config0(seed=0, n=100_000)
+    q0 = ref.quantize(x0, (4, 100000, 1000))
+    q1 = ref.quantize(x1, (4, 100000, 1000))
+    d = ref.delta(q0["sym"], 4, q1["sym"], 4)
+    assert (d["stream"] == 0).mean() > 0.6
