@@ -1,0 +1,152 @@
+/*
+ * inshr.h -- C ABI of the MI355X checkpoint-compressor hot path.
+ *
+ * Three operations on fp32 tensors that live in device memory, following the paper's statement
+ * of the problem (System Overview: a configuration goes in; integer codes, bin centres and
+ * protected values come out; previous and current codes give delta groups):
+ *
+ *   inshr_search    Quantization Config Manager (Sec. 5): score every configuration of a grid on
+ *                   every tensor in one sweep and pick, per tensor, the most compact one whose
+ *                   relative squared error stays within eps.
+ *   inshr_quantize  Quantizer (Sec. 4): prune / protect / quantize partition by magnitude
+ *                   (Sec. 4.1-4.2) with exact quantile thresholds (Sec. 4.3, alpha -> 0),
+ *                   K = 2^bits equal-frequency bins and one centre per bin (Sec. 4.4), emitted as
+ *                   bit-packed symbols + codebook + protected-value list.
+ *   inshr_delta     Delta Encoder (Sec. 6): cyclic difference of symbols against the previous
+ *                   checkpoint, regrouped by the previous checkpoint's symbol (Algorithm 5).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative INSHR_E_* code; nothing aborts or throws.
+ *     Outputs are undefined after an error.
+ *   - "device" pointers are HIP device allocations on the context's GPU, "host" pointers are
+ *     ordinary host memory.  The caller allocates and owns every buffer; the library never frees
+ *     caller memory and keeps no caller pointer after a call returns.
+ *   - All work is enqueued on the context's stream.  inshr_search and inshr_quantize return
+ *     after that work has completed (they read small results back); inshr_delta returns after
+ *     enqueueing, use inshr_sync before reading its outputs on the host.
+ *   - Calls on one context must not overlap in time (the context owns scratch memory).
+ *   - Order comparisons use integer images of the floats: -0.0 counts as +0.0, denormals are
+ *     ordinary values, NaN / Inf are rejected with INSHR_E_NONFINITE.
+ *   - Symbols: 0 = pruned, 1 = protected, 2 + bin = quantized.  A symbol stream is a little-endian
+ *     bit stream in u64 words: symbol i occupies bits [i*w, (i+1)*w), tail bits are zero.
+ */
+#ifndef INSHR_H
+#define INSHR_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    INSHR_OK = 0,
+    INSHR_E_ARG = -1,       /* null / misaligned pointer, n == 0, n >= 2^32, zero counts          */
+    INSHR_E_CONFIG = -2,    /* bits outside 1..8, prune_ppm + outlier_ppm >= 1e6, grid too large  */
+    INSHR_E_NONFINITE = -3, /* NaN or Inf found in a tensor                                       */
+    INSHR_E_CAPACITY = -4,  /* a caller buffer or the context scratch is too small                */
+    INSHR_E_SHAPE = -5,     /* prev.n != cur.n, or reuse requested without a matching search      */
+    INSHR_E_DEVICE = -6,    /* a HIP call failed; inshr_last_device_error gives its text          */
+    INSHR_E_INTERNAL = -7   /* a self-check inside the kernels failed (a bug, never bad input)    */
+};
+
+/* Most distinct (prune_ppm, outlier_ppm) pairs, and most distinct values of either, in one grid. */
+#define INSHR_MAX_PAIRS 31
+#define INSHR_MAX_FRACTIONS 16
+
+typedef struct inshr_ctx inshr_ctx; /* opaque: one device, one stream, scratch memory */
+
+/* device: HIP device ordinal.  hip_stream: a hipStream_t or NULL for the default stream.
+ * scratch_bytes: device scratch the context may allocate (0 = a default sized from free memory);
+ * tensors are processed in sub-batches that fit it. */
+int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch_bytes);
+void inshr_destroy(inshr_ctx *ctx);
+const char *inshr_strerror(int code);
+const char *inshr_last_device_error(const inshr_ctx *ctx);
+int inshr_sync(inshr_ctx *ctx);
+
+typedef struct {
+    uint8_t bits;         /* 1..8; K = 1 << bits bins                               */
+    uint32_t prune_ppm;   /* pruning fraction x 1e6 (floor(n*ppm/1e6) smallest |x|)  */
+    uint32_t outlier_ppm; /* protection fraction x 1e6 (largest |x|); sum < 1e6      */
+} inshr_config;
+
+typedef struct {
+    const float *data; /* device, 4-byte aligned, read-only, caller-owned */
+    uint64_t n;        /* 1 <= n < 2^32 */
+} inshr_tensor;
+
+typedef struct {
+    double sse;   /* sum_pruned x^2 + sum_quantized (x - centre)^2, fp64 */
+    double sumsq; /* sum_all x^2 */
+    uint64_t n_pruned, n_outlier, n_kept;
+    uint64_t cost_bits; /* n_kept*bits + 32*n_outlier + 32*K: payload model used to rank configs */
+} inshr_score;
+
+/* Score all n_cfg configurations on each of n_tensors tensors (Sec. 5).
+ *   best     host [n_tensors]: chosen grid index.  Feasible = sse/sumsq <= eps (0/0 counts as 0);
+ *            among feasible the least cost_bits, ties to the lowest index; if none is feasible
+ *            the least sse (ties lowest index) and feasible = 0.
+ *   feasible host [n_tensors]
+ *   scores   host [n_tensors * n_cfg] row-major by tensor, or NULL. */
+int inshr_search(inshr_ctx *ctx, const inshr_tensor *tensors, uint32_t n_tensors,
+                 const inshr_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
+                 uint8_t *feasible, inshr_score *scores);
+
+typedef struct {
+    /* caller-allocated device buffers */
+    uint64_t *packed;       /* symbol stream, packed_words words (inshr_quantize_bound)          */
+    uint64_t packed_words;
+    float *codebook;        /* >= 256 floats; first K are written                                 */
+    float *boundaries;      /* >= 255 floats or NULL; first K-1 interior bin boundaries           */
+    uint32_t *outlier_idx;  /* protected indices, ascending; capacity outlier_cap (may be NULL    */
+    float *outlier_val;     /*   when outlier_cap == 0); original values, bit-exact               */
+    uint64_t outlier_cap;
+    /* filled by the call (host side) */
+    uint64_t n_pruned, n_outlier, n_kept;
+    uint32_t sym_bits;      /* bits + 1 */
+    float tau_prune;        /* pruned    <=> |x| <  tau_prune   */
+    float tau_outlier;      /* protected <=> |x| >  tau_outlier */
+} inshr_quantized;
+
+/* Sizes of the buffers inshr_quantize needs for a tensor of n elements. */
+int inshr_quantize_bound(uint64_t n, const inshr_config *cfg, uint64_t *packed_words,
+                         uint64_t *outlier_cap);
+
+#define INSHR_REUSE_SEARCH 1u /* thresholds / boundaries / centres come from the last inshr_search
+                                 on this context, which must have covered exactly these tensors
+                                 (same pointers, sizes, order) and contained each cfg[i] in its
+                                 grid; the data must not have changed since */
+
+/* Quantize tensors[i] with cfg[i] into out[i] (arrays of n_tensors entries, host). */
+int inshr_quantize(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
+                   inshr_quantized *out, uint32_t n_tensors, uint32_t flags);
+
+typedef struct {
+    const uint64_t *packed; /* device symbol stream */
+    uint32_t sym_bits;      /* bits + 1 */
+    uint8_t bits;
+    uint64_t n;
+} inshr_codes;
+
+typedef struct {
+    uint64_t *packed;       /* device, packed_words words (inshr_delta_bound): stream e[r]        */
+    uint64_t packed_words;
+    uint64_t *group_off;    /* device, (1 << prev.bits) + 3 entries: #{i : s_prev[i] < g}          */
+    uint32_t *perm;         /* device [n] or NULL: perm[r] = index of the r-th regrouped element   */
+    uint32_t delta_bits;    /* filled: max(prev.bits, cur.bits) + 1                                */
+} inshr_delta_out;
+
+int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t *packed_words);
+
+/* d[i] = (s_prev[i] - s_cur[i]) mod B, B = max(K_prev, K_cur) + 2; elements are regrouped in the
+ * stable order of s_prev (Algorithm 5): e[r] = d[perm[r]].  Arrays have n_tensors entries (host).
+ * prev_perm: NULL, or host array of n_tensors device pointers (entries may be NULL) holding the
+ * permutation of a previous call for the same prev codes; when given it is used instead of being
+ * recomputed. */
+int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *prev_perm,
+                const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

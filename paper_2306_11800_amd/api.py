@@ -1,0 +1,258 @@
+"""Thin Python binding of the C ABI in include/inshr.h (argument marshalling only).
+
+Every step of search / quantize / delta runs in the HIP kernels of libinshr.so.  torch is used for
+device memory and streams.  There is no CPU fallback: loading fails loudly when the library has
+not been built (python -m paper_2306_11800_amd.build or __graft_entry__.build()).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libinshr.so")
+
+EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
+           "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_delta_bound", "inshr_delta"]
+
+INSHR_REUSE_SEARCH = 1
+
+
+class CConfig(C.Structure):
+    _fields_ = [("bits", C.c_uint8), ("prune_ppm", C.c_uint32), ("outlier_ppm", C.c_uint32)]
+
+
+class CTensor(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("n", C.c_uint64)]
+
+
+class CScore(C.Structure):
+    _fields_ = [("sse", C.c_double), ("sumsq", C.c_double), ("n_pruned", C.c_uint64),
+                ("n_outlier", C.c_uint64), ("n_kept", C.c_uint64), ("cost_bits", C.c_uint64)]
+
+
+class CQuantized(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("codebook", C.c_void_p),
+                ("boundaries", C.c_void_p), ("outlier_idx", C.c_void_p), ("outlier_val", C.c_void_p),
+                ("outlier_cap", C.c_uint64), ("n_pruned", C.c_uint64), ("n_outlier", C.c_uint64),
+                ("n_kept", C.c_uint64), ("sym_bits", C.c_uint32), ("tau_prune", C.c_float),
+                ("tau_outlier", C.c_float)]
+
+
+class CCodes(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("sym_bits", C.c_uint32), ("bits", C.c_uint8),
+                ("n", C.c_uint64)]
+
+
+class CDeltaOut(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("group_off", C.c_void_p),
+                ("perm", C.c_void_p), ("delta_bits", C.c_uint32)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libinshr.so; raise if it is missing (the product path never falls back to the CPU)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_11800_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    lib.inshr_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_uint64]
+    lib.inshr_destroy.argtypes = [C.c_void_p]
+    lib.inshr_destroy.restype = None
+    lib.inshr_strerror.argtypes = [C.c_int]
+    lib.inshr_strerror.restype = C.c_char_p
+    lib.inshr_last_device_error.argtypes = [C.c_void_p]
+    lib.inshr_last_device_error.restype = C.c_char_p
+    lib.inshr_sync.argtypes = [C.c_void_p]
+    lib.inshr_search.argtypes = [C.c_void_p, C.POINTER(CTensor), C.c_uint32, C.POINTER(CConfig),
+                                 C.c_uint32, C.c_double, C.POINTER(C.c_uint32),
+                                 C.POINTER(C.c_uint8), C.POINTER(CScore)]
+    lib.inshr_quantize_bound.argtypes = [C.c_uint64, C.POINTER(CConfig), C.POINTER(C.c_uint64),
+                                         C.POINTER(C.c_uint64)]
+    lib.inshr_quantize.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
+                                   C.POINTER(CQuantized), C.c_uint32, C.c_uint32]
+    lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
+    lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
+                                C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
+    _lib = lib
+    return lib
+
+
+class InshrError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"inshr error {code}: {text}")
+        self.code = code
+
+
+@dataclass
+class Quantized:
+    """Device-side result of quantizing one tensor."""
+    n: int
+    bits: int
+    sym_bits: int
+    packed: torch.Tensor        # int64 words (bit pattern of u64)
+    codebook: torch.Tensor      # float32 [K]
+    boundaries: torch.Tensor    # float32 [K-1]
+    outlier_idx: torch.Tensor   # int32 (bit pattern of u32) [n_outlier]
+    outlier_val: torch.Tensor   # float32 [n_outlier]
+    n_pruned: int
+    n_outlier: int
+    n_kept: int
+    tau_prune: float
+    tau_outlier: float
+
+
+@dataclass
+class Delta:
+    n: int
+    delta_bits: int
+    packed: torch.Tensor        # int64 words
+    group_off: torch.Tensor     # int64 [(1 << bits_prev) + 3]
+    perm: Optional[torch.Tensor]  # int32 (bit pattern of u32) [n] or None
+
+
+def _tensor_array(tensors: Sequence[torch.Tensor]):
+    arr = (CTensor * len(tensors))()
+    for i, t in enumerate(tensors):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous float32 CUDA tensors")
+        arr[i] = CTensor(t.data_ptr(), t.numel())
+    return arr
+
+
+def _config_array(cfgs):
+    arr = (CConfig * len(cfgs))()
+    for i, (b, p, o) in enumerate(cfgs):
+        arr[i] = CConfig(int(b), int(p), int(o))
+    return arr
+
+
+class Context:
+    """One device + one stream + scratch memory (inshr_ctx)."""
+
+    def __init__(self, device: Optional[torch.device] = None, scratch_bytes: int = 0):
+        self.lib = load_library()
+        self.device = torch.device(device if device is not None else "cuda:0")
+        idx = self.device.index if self.device.index is not None else 0
+        self.stream = torch.cuda.current_stream(self.device)
+        h = C.c_void_p()
+        rc = self.lib.inshr_create(C.byref(h), idx, C.c_void_p(self.stream.cuda_stream), scratch_bytes)
+        if rc:
+            raise InshrError(rc, self.lib.inshr_strerror(rc).decode())
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.inshr_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc:
+            text = self.lib.inshr_strerror(rc).decode()
+            extra = self.lib.inshr_last_device_error(self.h).decode()
+            raise InshrError(rc, text + (f" ({extra})" if extra and rc in (-6, -7, -4) else ""))
+
+    def sync(self):
+        self._check(self.lib.inshr_sync(self.h))
+
+    # -- inshr_search ---------------------------------------------------------------------
+    def search(self, tensors: Sequence[torch.Tensor], grid, eps: float, want_scores: bool = True):
+        """Returns (best[list of int], feasible[list of int], scores or None) where scores is a
+        ctypes array of CScore of length len(tensors) * len(grid), row-major by tensor."""
+        ta = _tensor_array(tensors)
+        ga = _config_array(grid)
+        nT, nC = len(tensors), len(grid)
+        best = (C.c_uint32 * nT)()
+        feas = (C.c_uint8 * nT)()
+        scores = (CScore * (nT * nC))() if want_scores else None
+        self._check(self.lib.inshr_search(self.h, ta, nT, ga, nC, float(eps), best, feas, scores))
+        return list(best), list(feas), scores
+
+    # -- inshr_quantize -------------------------------------------------------------------
+    def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False) -> List[Quantized]:
+        nT = len(tensors)
+        ta = _tensor_array(tensors)
+        ca = _config_array(cfgs)
+        qa = (CQuantized * nT)()
+        bufs = []
+        for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
+            words, cap = C.c_uint64(), C.c_uint64()
+            self._check(self.lib.inshr_quantize_bound(t.numel(), C.byref(ca[i]), C.byref(words), C.byref(cap)))
+            K = 1 << int(cfg[0])
+            packed = torch.empty(words.value, dtype=torch.int64, device=t.device)
+            cb = torch.empty(256, dtype=torch.float32, device=t.device)
+            bd = torch.empty(255, dtype=torch.float32, device=t.device)
+            oi = torch.empty(max(cap.value, 1), dtype=torch.int32, device=t.device)
+            ov = torch.empty(max(cap.value, 1), dtype=torch.float32, device=t.device)
+            qa[i].packed = packed.data_ptr()
+            qa[i].packed_words = words.value
+            qa[i].codebook = cb.data_ptr()
+            qa[i].boundaries = bd.data_ptr()
+            qa[i].outlier_idx = oi.data_ptr()
+            qa[i].outlier_val = ov.data_ptr()
+            qa[i].outlier_cap = cap.value
+            bufs.append((packed, cb, bd, oi, ov, K))
+        self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, INSHR_REUSE_SEARCH if reuse_search else 0))
+        out = []
+        for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
+            packed, cb, bd, oi, ov, K = bufs[i]
+            no = int(qa[i].n_outlier)
+            out.append(Quantized(n=t.numel(), bits=int(cfg[0]), sym_bits=int(qa[i].sym_bits),
+                                 packed=packed, codebook=cb[:K], boundaries=bd[:K - 1],
+                                 outlier_idx=oi[:no], outlier_val=ov[:no],
+                                 n_pruned=int(qa[i].n_pruned), n_outlier=no, n_kept=int(qa[i].n_kept),
+                                 tau_prune=float(qa[i].tau_prune), tau_outlier=float(qa[i].tau_outlier)))
+        return out
+
+    # -- inshr_delta ----------------------------------------------------------------------
+    def delta(self, prev: Sequence[Quantized], cur: Sequence[Quantized], want_perm: bool = False,
+              prev_perm: Optional[Sequence[Optional[torch.Tensor]]] = None,
+              out: Optional[List[Delta]] = None) -> List[Delta]:
+        """Enqueues the delta of every (prev[i], cur[i]); call sync() before reading on the host.
+        `out` may carry pre-allocated Delta buffers of a previous call with the same shapes."""
+        nT = len(prev)
+        pa = (CCodes * nT)()
+        ca = (CCodes * nT)()
+        oa = (CDeltaOut * nT)()
+        pp = (C.c_void_p * nT)() if prev_perm is not None else None
+        res: List[Delta] = []
+        for i, (p, c) in enumerate(zip(prev, cur)):
+            pa[i] = CCodes(p.packed.data_ptr(), p.sym_bits, p.bits, p.n)
+            ca[i] = CCodes(c.packed.data_ptr(), c.sym_bits, c.bits, c.n)
+            words = C.c_uint64()
+            rc = self.lib.inshr_delta_bound(C.byref(pa[i]), C.byref(ca[i]), C.byref(words))
+            self._check(rc)
+            if out is not None:
+                d = out[i]
+            else:
+                dev = p.packed.device
+                d = Delta(n=p.n, delta_bits=max(p.bits, c.bits) + 1,
+                          packed=torch.empty(words.value, dtype=torch.int64, device=dev),
+                          group_off=torch.empty((1 << p.bits) + 3, dtype=torch.int64, device=dev),
+                          perm=torch.empty(p.n, dtype=torch.int32, device=dev) if want_perm else None)
+            oa[i].packed = d.packed.data_ptr()
+            oa[i].packed_words = d.packed.numel()
+            oa[i].group_off = d.group_off.data_ptr()
+            oa[i].perm = d.perm.data_ptr() if d.perm is not None else None
+            if pp is not None:
+                pp[i] = prev_perm[i].data_ptr() if prev_perm[i] is not None else None
+            res.append(d)
+        self._check(self.lib.inshr_delta(self.h, pa, pp, ca, oa, nT))
+        for i in range(nT):
+            res[i].delta_bits = int(oa[i].delta_bits)
+        return res

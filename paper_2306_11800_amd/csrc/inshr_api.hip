@@ -1,0 +1,608 @@
+// Host side of the C ABI (include/inshr.h): argument checks, work partition, scratch memory and
+// kernel sequencing.  No arithmetic of the method runs here.
+#include "../../include/inshr.h"
+#include "inshr_launch.h"
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace inshr;
+
+namespace {
+
+struct DevBuf { // grow-only device allocation
+    void *p = nullptr;
+    size_t cap = 0;
+};
+
+struct HostBuf { // grow-only pinned host allocation
+    void *p = nullptr;
+    size_t cap = 0;
+};
+
+} // namespace
+
+struct inshr_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    uint64_t scratch_limit = 0;
+    int n_cu = 256;
+    int wg_per_cu = 2;
+    std::string last_err;
+
+    DevBuf search_mem; // everything a search leaves behind for inshr_quantize
+    DevBuf aux_mem;    // quantize descriptors, delta scratch
+    HostBuf h_up;      // staging for descriptor uploads
+    HostBuf h_down;    // staging for result downloads
+
+    // state of the last search
+    bool have_search = false;
+    Batch batch{};
+    GridDesc grid{};
+    std::vector<inshr_config> grid_cfgs;
+    std::vector<inshr_tensor> tensors;
+    size_t ts_off = 0, scores_off = 0;
+};
+
+namespace {
+
+#define HIPCHK(ctx, call)                                                                         \
+    do {                                                                                          \
+        hipError_t e__ = (call);                                                                  \
+        if (e__ != hipSuccess) {                                                                  \
+            (ctx)->last_err = std::string(#call) + ": " + hipGetErrorString(e__);                 \
+            return INSHR_E_DEVICE;                                                                \
+        }                                                                                         \
+    } while (0)
+
+int ensure_dev(inshr_ctx *c, DevBuf &b, size_t bytes)
+{
+    if (bytes <= b.cap) return INSHR_OK;
+    if (c->scratch_limit && bytes > c->scratch_limit) return INSHR_E_CAPACITY;
+    if (b.p) HIPCHK(c, hipFree(b.p));
+    b.p = nullptr;
+    b.cap = 0;
+    hipError_t e = hipMalloc(&b.p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->last_err = std::string("hipMalloc of scratch: ") + hipGetErrorString(e);
+        b.p = nullptr;
+        return INSHR_E_CAPACITY;
+    }
+    b.cap = bytes;
+    return INSHR_OK;
+}
+
+int ensure_host(inshr_ctx *c, HostBuf &b, size_t bytes)
+{
+    if (bytes <= b.cap) return INSHR_OK;
+    if (b.p) HIPCHK(c, hipHostFree(b.p));
+    b.p = nullptr;
+    b.cap = 0;
+    HIPCHK(c, hipHostMalloc(&b.p, bytes, hipHostMallocDefault));
+    b.cap = bytes;
+    return INSHR_OK;
+}
+
+struct Carver { // lays sub-buffers out in one allocation, 256-byte aligned
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        size_t o = off;
+        off = (off + bytes + 255) & ~(size_t)255;
+        return o;
+    }
+};
+
+int check_config(const inshr_config &c)
+{
+    if (c.bits < 1 || c.bits > 8) return INSHR_E_CONFIG;
+    if ((uint64_t)c.prune_ppm + (uint64_t)c.outlier_ppm >= 1000000ull) return INSHR_E_CONFIG;
+    return INSHR_OK;
+}
+
+int build_grid(const inshr_config *grid, uint32_t n_cfg, double eps, GridDesc &g)
+{
+    if (n_cfg == 0 || n_cfg > (uint32_t)MAX_CFG) return INSHR_E_CONFIG;
+    memset(&g, 0, sizeof(g));
+    g.n_cfg = n_cfg;
+    g.eps = eps;
+    for (uint32_t i = 0; i < n_cfg; i++) {
+        int rc = check_config(grid[i]);
+        if (rc) return rc;
+        uint32_t ip = 0, io = 0;
+        for (ip = 0; ip < g.n_p; ip++)
+            if (g.p_ppm[ip] == grid[i].prune_ppm) break;
+        if (ip == g.n_p) {
+            if (g.n_p == (uint32_t)MAX_FRAC) return INSHR_E_CONFIG;
+            g.p_ppm[g.n_p++] = grid[i].prune_ppm;
+        }
+        for (io = 0; io < g.n_o; io++)
+            if (g.o_ppm[io] == grid[i].outlier_ppm) break;
+        if (io == g.n_o) {
+            if (g.n_o == (uint32_t)MAX_FRAC) return INSHR_E_CONFIG;
+            g.o_ppm[g.n_o++] = grid[i].outlier_ppm;
+        }
+        uint32_t q = 0;
+        for (q = 0; q < g.n_pairs; q++)
+            if (g.pair_p[q] == ip && g.pair_o[q] == io) break;
+        if (q == g.n_pairs) {
+            if (g.n_pairs == (uint32_t)MAX_PAIRS) return INSHR_E_CONFIG;
+            g.pair_p[q] = ip;
+            g.pair_o[q] = io;
+            g.n_pairs++;
+        }
+        g.cfg_pair[i] = q;
+        g.cfg_bits[i] = grid[i].bits;
+    }
+    return INSHR_OK;
+}
+
+int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const inshr_config *grid,
+               uint32_t n_cfg, double eps)
+{
+    c->have_search = false;
+    if (!tensors || !grid || nT == 0) return INSHR_E_ARG;
+    GridDesc g;
+    int rc = build_grid(grid, n_cfg, eps, g);
+    if (rc) return rc;
+    uint64_t total_tiles = 0, total_n = 0;
+    for (uint32_t t = 0; t < nT; t++) {
+        if (!tensors[t].data || tensors[t].n == 0 || tensors[t].n >= (1ull << 32)) return INSHR_E_ARG;
+        if ((uintptr_t)tensors[t].data & 3u) return INSHR_E_ARG;
+        total_tiles += (tensors[t].n + TILE - 1) / TILE;
+        total_n += tensors[t].n;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->stream)); // staging buffers may be in flight (inshr_delta)
+
+    // work partition: tiles are dealt out evenly to workgroups in order
+    const int n_wg = (int)std::min<uint64_t>(total_tiles, (uint64_t)c->n_cu * c->wg_per_cu);
+    std::vector<TDesc> td(nT);
+    std::vector<u64> wg_tile0(n_wg + 1);
+    std::vector<u32> wg_fu0(n_wg);
+    std::vector<std::vector<u32>> t_units(nT);
+    {
+        u64 tile = 0, pool = 0;
+        for (uint32_t t = 0; t < nT; t++) {
+            td[t].data = tensors[t].data;
+            td[t].n = tensors[t].n;
+            td[t].tile0 = tile;
+            td[t].pool_thr = pool;
+            td[t].pool_cand = pool + tensors[t].n;
+            td[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
+            td[t].pad = 0;
+            tile += (tensors[t].n + TILE - 1) / TILE;
+            pool += 2 * tensors[t].n;
+        }
+        for (int w = 0; w <= n_wg; w++) wg_tile0[w] = total_tiles * (u64)w / (u64)n_wg;
+        u32 units = 0;
+        uint32_t t = 0;
+        for (int w = 0; w < n_wg; w++) {
+            wg_fu0[w] = units;
+            const u64 lo = wg_tile0[w], hi = wg_tile0[w + 1];
+            if (lo >= hi) continue;
+            while (t + 1 < nT && td[t + 1].tile0 <= lo) t++;
+            uint32_t tt = t;
+            while (true) {
+                t_units[tt].push_back(units++);
+                const u64 t_end = (tt + 1 < nT) ? td[tt + 1].tile0 : total_tiles;
+                if (t_end >= hi) break;
+                tt++;
+            }
+        }
+        // device layout
+        Carver cv;
+        const size_t o_td = cv.take(sizeof(TDesc) * nT);
+        const size_t o_gd = cv.take(sizeof(GridDesc));
+        const size_t o_wt = cv.take(sizeof(u64) * (n_wg + 1));
+        const size_t o_wf = cv.take(sizeof(u32) * n_wg);
+        const size_t o_tfo = cv.take(sizeof(u32) * (nT + 1));
+        const size_t o_tfi = cv.take(sizeof(u32) * units);
+        const size_t up_bytes = cv.off;
+        const size_t o_ts = cv.take(sizeof(TState) * nT);
+        const size_t o_h1 = cv.take((size_t)nT * L1_BINS * 4);
+        const size_t o_h2 = cv.take((size_t)nT * L2_BINS * 4);
+        const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
+        const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
+        const size_t o_bmp = cv.take((size_t)nT * 512 * 4);
+        const size_t o_bi = cv.take((size_t)nT * L2_BINS * 4);
+        const size_t o_cur = cv.take((size_t)nT * CURSOR_STRIDE * 4);
+        const size_t o_tb = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_tr = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_tk = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_to = cv.take((size_t)total_tiles * MAX_FRAC * 4);
+        const size_t o_tf = cv.take((size_t)total_tiles * 4);
+        const size_t o_sq = cv.take((size_t)units * SQ_STRIDE * 8);
+        const size_t o_ed = cv.take((size_t)nT * MAX_EDGES * 4);
+        const size_t o_sl = cv.take((size_t)nT * (L2_BINS + 64) * 2);
+        const size_t o_pe = cv.take((size_t)nT * MAX_PAIRS * 260 * 2);
+        const size_t o_mc = cv.take((size_t)units * MAX_EDGES * 4);
+        const size_t o_ms = cv.take((size_t)units * MAX_EDGES * 8);
+        const size_t o_cb = cv.take((size_t)nT * n_cfg * CB_STRIDE * 4);
+        const size_t o_sc = cv.take((size_t)nT * n_cfg * sizeof(Score));
+        const size_t o_bt = cv.take((size_t)nT * n_cfg * CB_STRIDE * 8);
+        const size_t o_pool = cv.take((size_t)pool * 4);
+        rc = ensure_dev(c, c->search_mem, cv.off);
+        if (rc) return rc;
+        rc = ensure_host(c, c->h_up, up_bytes);
+        if (rc) return rc;
+        char *hb = (char *)c->h_up.p;
+        char *db = (char *)c->search_mem.p;
+        memcpy(hb + o_td, td.data(), sizeof(TDesc) * nT);
+        memcpy(hb + o_gd, &g, sizeof(GridDesc));
+        memcpy(hb + o_wt, wg_tile0.data(), sizeof(u64) * (n_wg + 1));
+        memcpy(hb + o_wf, wg_fu0.data(), sizeof(u32) * n_wg);
+        {
+            u32 *tfo = (u32 *)(hb + o_tfo), *tfi = (u32 *)(hb + o_tfi);
+            u32 k = 0;
+            for (uint32_t tt = 0; tt < nT; tt++) {
+                tfo[tt] = k;
+                for (u32 u : t_units[tt]) tfi[k++] = u;
+            }
+            tfo[nT] = k;
+        }
+        HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemsetAsync(db + o_ts, 0, zero_end - o_ts, c->stream));
+
+        Batch &bt = c->batch;
+        bt.td = (const TDesc *)(db + o_td);
+        bt.gd = (const GridDesc *)(db + o_gd);
+        bt.wg_tile0 = (const u64 *)(db + o_wt);
+        bt.wg_fu0 = (const u32 *)(db + o_wf);
+        bt.t_fu_off = (const u32 *)(db + o_tfo);
+        bt.t_fu_ids = (const u32 *)(db + o_tfi);
+        bt.nT = (int)nT;
+        bt.n_wg = n_wg;
+        bt.n_pairs = g.n_pairs;
+        bt.n_cfg = n_cfg;
+        bt.n_tiles = total_tiles;
+        Bufs &B = bt.bufs;
+        B.ts = (TState *)(db + o_ts);
+        B.hist1 = (u32 *)(db + o_h1);
+        B.hist2 = (u32 *)(db + o_h2);
+        B.table2 = (u32 *)(db + o_tab);
+        B.bitmap = (u32 *)(db + o_bmp);
+        B.binfo = (u32 *)(db + o_bi);
+        B.cursor2 = (u32 *)(db + o_cur);
+        B.tgt_bin = (u32 *)(db + o_tb);
+        B.tgt_res = (u32 *)(db + o_tr);
+        B.tgt_key = (u32 *)(db + o_tk);
+        B.pool = (u32 *)(db + o_pool);
+        B.tile_out = (u32 *)(db + o_to);
+        B.tile_off = (u32 *)(db + o_tf);
+        B.sq_part = (double *)(db + o_sq);
+        B.edges = (u32 *)(db + o_ed);
+        B.sl = (u16 *)(db + o_sl);
+        B.pair_eidx = (u16 *)(db + o_pe);
+        B.mom_cnt = (u32 *)(db + o_mc);
+        B.mom_sx = (double *)(db + o_ms);
+        B.codebook = (float *)(db + o_cb);
+        B.scores = (Score *)(db + o_sc);
+        B.bin_term = (double *)(db + o_bt);
+        c->ts_off = o_ts;
+        c->scores_off = o_sc;
+    }
+    HIPCHK(c, launch_select(c->batch, c->stream));
+    HIPCHK(c, launch_score(c->batch, c->stream));
+
+    // results: per-tensor state and scores
+    const size_t ts_bytes = sizeof(TState) * nT, sc_bytes = sizeof(Score) * (size_t)nT * n_cfg;
+    rc = ensure_host(c, c->h_down, ts_bytes + sc_bytes);
+    if (rc) return rc;
+    char *db = (char *)c->search_mem.p;
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + c->ts_off, ts_bytes, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync((char *)c->h_down.p + ts_bytes, db + c->scores_off, sc_bytes,
+                             hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const TState *hts = (const TState *)c->h_down.p;
+    for (uint32_t t = 0; t < nT; t++) {
+        if (hts[t].nonfinite) return INSHR_E_NONFINITE;
+    }
+    for (uint32_t t = 0; t < nT; t++) {
+        if (hts[t].internal_err) {
+            c->last_err = "kernel self-check failed on tensor " + std::to_string(t) + ", code " +
+                          std::to_string(hts[t].internal_err);
+            return INSHR_E_INTERNAL;
+        }
+    }
+    c->grid = g;
+    c->grid_cfgs.assign(grid, grid + n_cfg);
+    c->tensors.assign(tensors, tensors + nT);
+    c->have_search = true;
+    return INSHR_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch_bytes)
+{
+    if (!out) return INSHR_E_ARG;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return INSHR_E_DEVICE;
+    inshr_ctx *c = new inshr_ctx();
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    c->scratch_limit = scratch_bytes;
+    hipDeviceProp_t pr;
+    if (hipSetDevice(device) != hipSuccess || hipGetDeviceProperties(&pr, device) != hipSuccess) {
+        delete c;
+        return INSHR_E_DEVICE;
+    }
+    c->n_cu = pr.multiProcessorCount > 0 ? pr.multiProcessorCount : 256;
+    if (const char *e = getenv("INSHR_WG_PER_CU")) {
+        int v = atoi(e);
+        if (v >= 1 && v <= 16) c->wg_per_cu = v;
+    }
+    *out = c;
+    return INSHR_OK;
+}
+
+void inshr_destroy(inshr_ctx *c)
+{
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    if (c->search_mem.p) (void)hipFree(c->search_mem.p);
+    if (c->aux_mem.p) (void)hipFree(c->aux_mem.p);
+    if (c->h_up.p) (void)hipHostFree(c->h_up.p);
+    if (c->h_down.p) (void)hipHostFree(c->h_down.p);
+    delete c;
+}
+
+const char *inshr_strerror(int code)
+{
+    switch (code) {
+    case INSHR_OK: return "ok";
+    case INSHR_E_ARG: return "bad argument";
+    case INSHR_E_CONFIG: return "bad configuration or grid too large";
+    case INSHR_E_NONFINITE: return "NaN or Inf in a tensor";
+    case INSHR_E_CAPACITY: return "buffer or scratch too small";
+    case INSHR_E_SHAPE: return "shape mismatch";
+    case INSHR_E_DEVICE: return "HIP error";
+    case INSHR_E_INTERNAL: return "internal self-check failed";
+    default: return "unknown error";
+    }
+}
+
+const char *inshr_last_device_error(const inshr_ctx *c) { return c ? c->last_err.c_str() : ""; }
+
+int inshr_sync(inshr_ctx *c)
+{
+    if (!c) return INSHR_E_ARG;
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return INSHR_OK;
+}
+
+int inshr_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t n_tensors,
+                 const inshr_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
+                 uint8_t *feasible, inshr_score *scores)
+{
+    if (!c || !best || !feasible) return INSHR_E_ARG;
+    int rc = run_search(c, tensors, n_tensors, grid, n_cfg, eps);
+    if (rc) return rc;
+    const TState *hts = (const TState *)c->h_down.p;
+    const Score *hsc = (const Score *)((const char *)c->h_down.p + sizeof(TState) * n_tensors);
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        best[t] = hts[t].best;
+        feasible[t] = (uint8_t)hts[t].feasible;
+    }
+    if (scores) {
+        static_assert(sizeof(Score) == sizeof(inshr_score), "score layout");
+        memcpy(scores, hsc, sizeof(Score) * (size_t)n_tensors * n_cfg);
+    }
+    return INSHR_OK;
+}
+
+int inshr_quantize_bound(uint64_t n, const inshr_config *cfg, uint64_t *packed_words,
+                         uint64_t *outlier_cap)
+{
+    if (!cfg || n == 0 || n >= (1ull << 32)) return INSHR_E_ARG;
+    int rc = check_config(*cfg);
+    if (rc) return rc;
+    if (packed_words) *packed_words = (n * (uint64_t)(cfg->bits + 1) + 63) / 64;
+    if (outlier_cap) *outlier_cap = n * (uint64_t)cfg->outlier_ppm / 1000000ull;
+    return INSHR_OK;
+}
+
+static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quantized *out,
+                               const uint32_t *which, uint32_t n_sel)
+{
+    // which[k] = position in the search batch of the k-th tensor to quantize (cfg / out indexed by k)
+    const uint32_t nT = (uint32_t)c->batch.nT;
+    std::vector<QDesc> qd(nT);
+    for (auto &q : qd) memset(&q, 0, sizeof(q));
+    for (uint32_t k = 0; k < n_sel; k++) {
+        const uint32_t t = which[k];
+        uint32_t gi = 0;
+        for (gi = 0; gi < c->grid.n_cfg; gi++)
+            if (c->grid_cfgs[gi].bits == cfg[k].bits && c->grid_cfgs[gi].prune_ppm == cfg[k].prune_ppm &&
+                c->grid_cfgs[gi].outlier_ppm == cfg[k].outlier_ppm)
+                break;
+        if (gi == c->grid.n_cfg) return INSHR_E_SHAPE;
+        uint64_t words = 0, cap = 0;
+        inshr_quantize_bound(c->tensors[t].n, &cfg[k], &words, &cap);
+        if (!out[k].packed || !out[k].codebook || out[k].packed_words < words) return INSHR_E_CAPACITY;
+        if (out[k].outlier_cap && (!out[k].outlier_idx || !out[k].outlier_val)) return INSHR_E_ARG;
+        qd[t].packed = (unsigned long long *)out[k].packed;
+        qd[t].codebook = out[k].codebook;
+        qd[t].boundaries = out[k].boundaries;
+        qd[t].out_idx = out[k].outlier_idx;
+        qd[t].out_val = out[k].outlier_val;
+        qd[t].out_cap = out[k].outlier_cap;
+        qd[t].cfg = gi;
+        qd[t].tslot = t;
+    }
+    Carver cv;
+    const size_t o_qd = cv.take(sizeof(QDesc) * nT);
+    const size_t o_qi = cv.take(sizeof(QInfo) * nT);
+    int rc = ensure_dev(c, c->aux_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, sizeof(QDesc) * nT);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_down, sizeof(QInfo) * nT);
+    if (rc) return rc;
+    char *db = (char *)c->aux_mem.p;
+    HIPCHK(c, hipStreamSynchronize(c->stream)); // staging buffers may be in flight (inshr_delta)
+    memcpy(c->h_up.p, qd.data(), sizeof(QDesc) * nT);
+    HIPCHK(c, hipMemcpyAsync(db + o_qd, c->h_up.p, sizeof(QDesc) * nT, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, launch_quantize(c->batch, (const QDesc *)(db + o_qd), (QInfo *)(db + o_qi), c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_qi, sizeof(QInfo) * nT, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const QInfo *qi = (const QInfo *)c->h_down.p;
+    int result = INSHR_OK;
+    for (uint32_t k = 0; k < n_sel; k++) {
+        const QInfo &r = qi[which[k]];
+        out[k].n_pruned = r.n_pruned;
+        out[k].n_outlier = r.n_outlier;
+        out[k].n_kept = r.n_kept;
+        out[k].sym_bits = cfg[k].bits + 1u;
+        uint32_t tp = r.tau_p, to = r.tau_o;
+        memcpy(&out[k].tau_prune, &tp, 4);
+        memcpy(&out[k].tau_outlier, &to, 4);
+        if (r.flags & 1u) {
+            c->last_err = "protected-value count self-check failed";
+            result = INSHR_E_INTERNAL;
+        } else if ((r.flags & 2u) && result == INSHR_OK) {
+            result = INSHR_E_CAPACITY;
+        }
+    }
+    return result;
+}
+
+int inshr_quantize(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config *cfg,
+                   inshr_quantized *out, uint32_t n_tensors, uint32_t flags)
+{
+    if (!c || !tensors || !cfg || !out || n_tensors == 0) return INSHR_E_ARG;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        int rc = check_config(cfg[t]);
+        if (rc) return rc;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    if (flags & INSHR_REUSE_SEARCH) {
+        if (!c->have_search || c->tensors.size() != n_tensors) return INSHR_E_SHAPE;
+        std::vector<uint32_t> which(n_tensors);
+        for (uint32_t t = 0; t < n_tensors; t++) {
+            if (c->tensors[t].data != tensors[t].data || c->tensors[t].n != tensors[t].n) return INSHR_E_SHAPE;
+            which[t] = t;
+        }
+        return quantize_with_state(c, cfg, out, which.data(), n_tensors);
+    }
+    // stand-alone: one internal single-configuration search per distinct configuration
+    std::vector<char> done(n_tensors, 0);
+    for (uint32_t t0 = 0; t0 < n_tensors; t0++) {
+        if (done[t0]) continue;
+        std::vector<inshr_tensor> sub;
+        std::vector<inshr_config> subcfg;
+        std::vector<uint32_t> idx;
+        for (uint32_t t = t0; t < n_tensors; t++) {
+            if (!done[t] && cfg[t].bits == cfg[t0].bits && cfg[t].prune_ppm == cfg[t0].prune_ppm &&
+                cfg[t].outlier_ppm == cfg[t0].outlier_ppm) {
+                done[t] = 1;
+                sub.push_back(tensors[t]);
+                subcfg.push_back(cfg[t]);
+                idx.push_back(t);
+            }
+        }
+        int rc = run_search(c, sub.data(), (uint32_t)sub.size(), &cfg[t0], 1, 0.0);
+        if (rc) return rc;
+        std::vector<inshr_quantized> subout(sub.size());
+        std::vector<uint32_t> which(sub.size());
+        for (size_t k = 0; k < sub.size(); k++) {
+            subout[k] = out[idx[k]];
+            which[k] = (uint32_t)k;
+        }
+        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), (uint32_t)sub.size());
+        for (size_t k = 0; k < sub.size(); k++) out[idx[k]] = subout[k];
+        if (rc) return rc;
+    }
+    return INSHR_OK;
+}
+
+int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t *packed_words)
+{
+    if (!prev || !cur || !packed_words) return INSHR_E_ARG;
+    if (prev->n != cur->n) return INSHR_E_SHAPE;
+    if (prev->bits < 1 || prev->bits > 8 || cur->bits < 1 || cur->bits > 8) return INSHR_E_CONFIG;
+    const uint32_t wB = (uint32_t)std::max(prev->bits, cur->bits) + 1u;
+    *packed_words = (prev->n * (uint64_t)wB + 63) / 64;
+    return INSHR_OK;
+}
+
+int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *prev_perm,
+                const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors)
+{
+    if (!c || !prev || !cur || !out || n_tensors == 0) return INSHR_E_ARG;
+    std::vector<DDesc> dd(n_tensors);
+    std::vector<u64> chunk_tile0;
+    u64 dtile = 0, chunk = 0;
+    bool any_scatter = false, any_gather = false;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        uint64_t words = 0;
+        int rc = inshr_delta_bound(&prev[t], &cur[t], &words);
+        if (rc) return rc;
+        const uint64_t n = prev[t].n;
+        if (n == 0 || n >= (1ull << 32) || !prev[t].packed || !cur[t].packed) return INSHR_E_ARG;
+        if (prev[t].sym_bits != prev[t].bits + 1u || cur[t].sym_bits != cur[t].bits + 1u) return INSHR_E_CONFIG;
+        if (!out[t].packed || !out[t].group_off || out[t].packed_words < words) return INSHR_E_CAPACITY;
+        DDesc &d = dd[t];
+        memset(&d, 0, sizeof(d));
+        d.prev = (const unsigned long long *)prev[t].packed;
+        d.cur = (const unsigned long long *)cur[t].packed;
+        d.out = (unsigned long long *)out[t].packed;
+        d.group_off = out[t].group_off;
+        d.perm = out[t].perm;
+        d.prev_perm = prev_perm ? prev_perm[t] : nullptr;
+        d.n = n;
+        d.out_words = words;
+        d.wp = prev[t].sym_bits;
+        d.wc = cur[t].sym_bits;
+        d.Kp = 1u << prev[t].bits;
+        const uint32_t Kc = 1u << cur[t].bits;
+        d.B = std::max(d.Kp, Kc) + 2u;
+        d.wB = (uint32_t)std::max(prev[t].bits, cur[t].bits) + 1u;
+        out[t].delta_bits = d.wB;
+        d.dtile0 = dtile;
+        d.chunk0 = chunk;
+        const u64 nt = (n + DELTA_TILE - 1) / DELTA_TILE;
+        d.n_chunks = (nt + DELTA_CHUNK - 1) / DELTA_CHUNK;
+        for (u64 k = 0; k < d.n_chunks; k++) chunk_tile0.push_back(dtile + k * DELTA_CHUNK);
+        dtile += nt;
+        chunk += d.n_chunks;
+        if (d.prev_perm)
+            any_gather = true;
+        else
+            any_scatter = true;
+    }
+    chunk_tile0.push_back(dtile);
+    HIPCHK(c, hipSetDevice(c->device));
+    Carver cv;
+    const size_t o_dd = cv.take(sizeof(DDesc) * n_tensors);
+    const size_t o_ct = cv.take(sizeof(u64) * chunk_tile0.size());
+    const size_t up_bytes = cv.off;
+    const size_t o_th = cv.take((size_t)dtile * DELTA_SS * 2);
+    const size_t o_ck = cv.take((size_t)chunk * DELTA_SS * 4);
+    int rc = ensure_dev(c, c->aux_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, up_bytes);
+    if (rc) return rc;
+    // the staging buffer may still be in flight from an earlier asynchronous delta call
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    char *hb = (char *)c->h_up.p, *db = (char *)c->aux_mem.p;
+    memcpy(hb + o_dd, dd.data(), sizeof(DDesc) * n_tensors);
+    memcpy(hb + o_ct, chunk_tile0.data(), sizeof(u64) * chunk_tile0.size());
+    HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, launch_delta((const DDesc *)(db + o_dd), (int)n_tensors, dtile, chunk,
+                           (const u64 *)(db + o_ct), (u16 *)(db + o_th), (u32 *)(db + o_ck),
+                           any_scatter, any_gather, c->stream));
+    return INSHR_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,258 @@
+// Shared device-side definitions of the hot path: integer images of floats, the two-level
+// binning of keys, per-tensor state records and wavefront helpers.  gfx950 only (64-wide waves).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef uint16_t u16;
+
+namespace inshr {
+
+// ------------------------------------------------------------------------------------------
+// sizes
+// ------------------------------------------------------------------------------------------
+constexpr int TILE = 16384;         // elements per tile: 1024 threads x 4 float4
+constexpr int BLOCK = 1024;         // threads per streaming workgroup
+constexpr int L1_SHIFT = 17;        // first-level bin = key >> 17 (sign, exponent, 6 mantissa bits)
+constexpr int L1_BINS = 32768;
+constexpr int L1_MAGBINS = 16384;   // first-level bins of the magnitude (fold of the two signs)
+constexpr int COARSE_SHIFT = 20;    // second level: table indexed by key >> 20 ...
+constexpr int COARSE = 4096;        // ... gives (base, depth) of a run of 2^depth bins
+constexpr int L2_BINS = 32768;      // most second-level bins (LDS-resident counters)
+constexpr int MAX_FRAC = 8;         // distinct prune fractions, distinct protect fractions
+constexpr int MAX_THR = 2 * MAX_FRAC;
+constexpr int MAX_PAIRS = 15;       // distinct (prune, protect) pairs in a grid
+constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits use a subset
+constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 = 3885 fits)
+constexpr int MAX_CFG = 256;
+constexpr u32 INACTIVE = 0xFFFFFFFFu;
+constexpr u32 RESOLVED = 0xFFFFFFFEu;
+constexpr u32 ZERO_KEY = 0x80000000u;
+
+// ------------------------------------------------------------------------------------------
+// integer images (Sec. 4.1: ranking by magnitude; all order comparisons are made on these)
+// ------------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ u32 canon_bits(u32 b) { return b == 0x80000000u ? 0u : b; }
+__host__ __device__ __forceinline__ u32 key_of_bits(u32 b)
+{
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__host__ __device__ __forceinline__ u32 mag_of_key(u32 k)
+{
+    return (k & 0x80000000u) ? (k & 0x7fffffffu) : (~k & 0x7fffffffu);
+}
+__host__ __device__ __forceinline__ u32 bits_of_key(u32 k)
+{
+    return (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+}
+__host__ __device__ __forceinline__ bool key_is_neg(u32 k) { return (k & 0x80000000u) == 0; }
+// keys of +m and -m for a magnitude image m (m == 0 maps both to ZERO_KEY's neighbourhood)
+__host__ __device__ __forceinline__ u32 key_pos(u32 m) { return 0x80000000u + m; }
+__host__ __device__ __forceinline__ u32 key_neg(u32 m) { return 0x7fffffffu - m; }
+
+// second-level bin of a key: table entry = base << 5 | depth
+__host__ __device__ __forceinline__ u32 l2_bin(u32 key, u32 entry)
+{
+    u32 d = entry & 31u;
+    return (entry >> 5) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
+}
+
+// ------------------------------------------------------------------------------------------
+// per-tensor records
+// ------------------------------------------------------------------------------------------
+struct TDesc {           // one tensor of a batch
+    const float *data;
+    u64 n;
+    u64 tile0;           // first tile of this tensor in the batch-wide tile numbering
+    u64 pool_thr;        // this tensor's region of the gather pool for threshold buckets (u32 units)
+    u64 pool_cand;       // ... and for the elements of active bins
+    u32 aligned16;       // data pointer is 16-byte aligned (float4 loads allowed)
+    u32 pad;
+};
+
+struct GridDesc {        // the configuration grid, decomposed
+    u32 n_cfg, n_pairs, n_p, n_o;
+    u32 p_ppm[MAX_FRAC], o_ppm[MAX_FRAC];     // distinct fractions
+    u32 pair_p[MAX_PAIRS], pair_o[MAX_PAIRS]; // indices into p_ppm / o_ppm
+    u32 cfg_pair[MAX_CFG];
+    u32 cfg_bits[MAX_CFG];
+    double eps;
+};
+
+struct TState {
+    u32 nonfinite;
+    u32 internal_err;
+    u64 n_neg, n_zero;                 // strictly negative values; exact zeros (after -0 -> +0)
+    // thresholds: index t < n_p is the prune threshold of p_ppm[t], t >= n_p the protect
+    // threshold of o_ppm[t - n_p]
+    u32 n_thr;
+    u32 thr_bucket[MAX_THR];
+    u64 thr_res[MAX_THR];              // rank inside the bucket, magnitude order, zeros first
+    u32 thr_mag[MAX_THR];              // result: magnitude image of the threshold
+    u64 thr_lt_neg[MAX_THR], thr_lt_pos[MAX_THR]; // #{mag < tau} by sign
+    u64 thr_gt_neg[MAX_THR], thr_gt_pos[MAX_THR]; // #{mag > tau} by sign
+    // buckets: distinct first-level magnitude bins that hold a threshold
+    u32 n_buckets;
+    u32 bucket_magbin[MAX_THR];
+    u64 bucket_below_neg[MAX_THR], bucket_below_pos[MAX_THR];
+    u32 bucket_cnt_neg[MAX_THR], bucket_cnt_pos[MAX_THR];
+    u64 bucket_off[MAX_THR];           // offset into this tensor's threshold-candidate region
+    u32 bucket_cursor[MAX_THR];
+    // second level
+    u32 nb2;                           // bins in use
+    u32 zbin;                          // bin that holds ZERO_KEY
+    u64 cand_total;
+    // pairs
+    u64 pair_An[MAX_PAIRS], pair_Mn[MAX_PAIRS], pair_Pn[MAX_PAIRS], pair_Pp[MAX_PAIRS];
+    u64 pair_M[MAX_PAIRS], pair_Ap[MAX_PAIRS];
+    // scoring
+    u32 n_edges;
+    double sumsq;                      // sum of x^2
+    double thr_sumsq[MAX_THR];         // prune: sum x^2 over mag < tau; protect: over mag > tau
+    u32 best, feasible;
+};
+
+struct Score {           // mirrors inshr_score
+    double sse, sumsq;
+    u64 n_pruned, n_outlier, n_kept, cost_bits;
+};
+
+// ------------------------------------------------------------------------------------------
+// wavefront helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ u32 wave_sum(u32 v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ u32 wave_or(u32 v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ u32 wave_and(u32 v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v &= __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// k-th smallest (0-based) of a[0..c) under the order of keys (by_mag == false) or of their
+// magnitudes (by_mag == true); one wavefront, all lanes return the value.  Radix select from the
+// highest bit that differs; lists of up to 1024 values are held in registers.
+__device__ inline u32 wave_select(const u32 *a, u32 c, u32 k, bool by_mag)
+{
+    const u32 lane = threadIdx.x & 63u;
+    u32 r[16];
+    const bool cached = c <= 1024u;
+    u32 vo = 0u, va = 0xFFFFFFFFu;
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            u32 idx = lane + 64u * i;
+            u32 v = 0u;
+            if (idx < c) {
+                v = a[idx];
+                if (by_mag) v = mag_of_key(v);
+                vo |= v;
+                va &= v;
+            }
+            r[i] = v;
+        }
+    } else {
+        for (u32 i = lane; i < c; i += 64u) {
+            u32 v = a[i];
+            if (by_mag) v = mag_of_key(v);
+            vo |= v;
+            va &= v;
+        }
+    }
+    vo = wave_or(vo);
+    va = wave_and(va);
+    u32 diff = vo ^ va;
+    if (diff == 0u) return va;
+    int hb = 31 - __clz(diff);
+    u32 pref = va & ~((2u << hb) - 1u); // bits above hb are common to all
+    for (int b = hb; b >= 0; b--) {
+        const u32 himask = ~((2u << b) - 1u);
+        const u32 bit = 1u << b;
+        u32 cnt = 0u;
+        if (cached) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                u32 idx = lane + 64u * i;
+                cnt += (idx < c && ((r[i] ^ pref) & himask) == 0u && (r[i] & bit) == 0u) ? 1u : 0u;
+            }
+        } else {
+            for (u32 i = lane; i < c; i += 64u) {
+                u32 v = a[i];
+                if (by_mag) v = mag_of_key(v);
+                cnt += (((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
+            }
+        }
+        cnt = wave_sum(cnt);
+        if (k >= cnt) {
+            k -= cnt;
+            pref |= bit;
+        }
+    }
+    return pref;
+}
+
+// Exclusive scan of in[0..n) (n <= 32 * BLOCK) into out[0..n], out[n] = total; whole workgroup of
+// BLOCK threads; tmp is LDS scratch of BLOCK/64 + 1 words.  in/out may alias only if equal.
+__device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
+{
+    const int t = threadIdx.x;
+    const int per = (n + BLOCK - 1) / BLOCK;
+    const int lo = t * per;
+    u32 s = 0;
+    for (int i = 0; i < per; i++) {
+        int idx = lo + i;
+        if (idx < n) s += in[idx];
+    }
+    // inclusive scan of s across the wave
+    u32 inc = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        u32 v = __shfl_up(inc, o);
+        if ((t & 63) >= o) inc += v;
+    }
+    if ((t & 63) == 63) tmp[t >> 6] = inc;
+    __syncthreads();
+    if (t == 0) {
+        u32 run = 0;
+        for (int w = 0; w < BLOCK / 64; w++) {
+            u32 v = tmp[w];
+            tmp[w] = run;
+            run += v;
+        }
+        tmp[BLOCK / 64] = run;
+    }
+    __syncthreads();
+    u32 base = tmp[t >> 6] + inc - s;
+    for (int i = 0; i < per; i++) {
+        int idx = lo + i;
+        if (idx < n) {
+            u32 v = in[idx];
+            out[idx] = base;
+            base += v;
+        }
+    }
+    u32 total = tmp[BLOCK / 64];
+    if (t == 0) out[n] = total;
+    __syncthreads();
+    return total;
+}
+
+} // namespace inshr

@@ -1,0 +1,138 @@
+// Batch description shared by the kernels' translation units and the host API.
+#pragma once
+#include "inshr_dev.h"
+
+namespace inshr {
+
+constexpr int CURSOR_STRIDE = L2_BINS + 64; // per-tensor stride of the gather cursors
+constexpr int TGT_STRIDE = 4096;            // per-tensor stride of boundary targets (15 * 255 fits)
+constexpr int SQ_STRIDE = MAX_FRAC + 1;     // partial sums of squares per (workgroup, tensor) unit
+constexpr int CB_STRIDE = 256;              // codebook entries per configuration
+
+struct Bufs { // device pointers, indexed by the tensor's position in the batch unless noted
+    TState *ts;
+    u32 *hist1;     // [nT][32768]
+    u32 *table2;    // [nT][4096]
+    u32 *bitmap;    // [nT][512]
+    u32 *hist2;     // [nT][32768]
+    u32 *binfo;     // [nT][32768] offset of an active bin's elements in the gather pool, or INACTIVE
+    u32 *cursor2;   // [nT][CURSOR_STRIDE]
+    u32 *tgt_bin;   // [nT][TGT_STRIDE] boundary j of pair q at q*255 + j-1
+    u32 *tgt_res;
+    u32 *tgt_key;   // results: boundary keys
+    u32 *pool;      // gathered keys
+    u32 *tile_out;  // [tiles][MAX_FRAC] protected values per tile and protect fraction
+    double *sq_part; // [units][SQ_STRIDE]
+    // scoring
+    u32 *edges;     // [nT][MAX_EDGES] merged, sorted, distinct edge keys
+    u16 *sl;        // [nT][32768 + 64] edges below each second-level bin
+    u16 *pair_eidx; // [nT][MAX_PAIRS][260] index of each pair's edges in the merged list
+    u32 *mom_cnt;   // [units][MAX_EDGES]
+    double *mom_sx; // [units][MAX_EDGES]
+    float *codebook; // [nT][n_cfg][CB_STRIDE]
+    Score *scores;  // [nT][n_cfg]
+    double *bin_term; // [nT][n_cfg][CB_STRIDE] per-bin 2cS - nc^2
+    u32 *tile_off;  // [tiles] exclusive prefix of protected values per tensor (quantize)
+};
+
+struct Batch {
+    const TDesc *td;     // device
+    const GridDesc *gd;  // device
+    const u64 *wg_tile0; // device [n_wg + 1]
+    const u32 *wg_fu0;   // device [n_wg] first (workgroup, tensor) unit of each workgroup
+    const u32 *t_fu_off; // device [nT + 1] CSR of the units that touch each tensor ...
+    const u32 *t_fu_ids; // device         ... in ascending workgroup order
+    int nT;
+    int n_wg;
+    u32 n_pairs, n_cfg;
+    u64 n_tiles;
+    Bufs bufs;
+};
+
+struct QDesc { // one tensor of a quantize call (indexed like the batch)
+    unsigned long long *packed; // NULL: tensor not part of the call
+    float *codebook;
+    float *boundaries;
+    u32 *out_idx;
+    float *out_val;
+    u64 out_cap;
+    u32 cfg;   // index into the grid of the search state
+    u32 tslot;
+};
+struct QInfo {
+    u64 n_pruned, n_outlier, n_kept;
+    u32 tau_p, tau_o, flags, pad;
+};
+
+struct DDesc { // one tensor of a delta call
+    const unsigned long long *prev, *cur;
+    unsigned long long *out;
+    u64 *group_off;
+    u32 *perm;
+    const u32 *prev_perm;
+    u64 n, out_words;
+    u64 dtile0, chunk0, n_chunks;
+    u32 wp, wc, Kp, B, wB, pad;
+};
+constexpr int DELTA_TILE = 16384;
+constexpr int DELTA_CHUNK = 64;
+constexpr int DELTA_SS = 264;
+
+hipError_t launch_select(const Batch &bt, hipStream_t s);
+hipError_t launch_score(const Batch &bt, hipStream_t s);
+hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStream_t s);
+hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
+                        const u64 *chunk_tile0, u16 *tile_hist, u32 *chunk_tot, bool any_scatter,
+                        bool any_gather, hipStream_t s);
+
+// ------------------------------------------------------------------------------------------
+// tile iteration shared by the streaming kernels
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int find_tensor(const TDesc *td, int nT, u64 tile)
+{
+    int lo = 0, hi = nT - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (td[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// v[4*j + c] = element 4*(tid + 1024*j) + c of the tile; returns the mask of valid entries
+__device__ __forceinline__ u32 load_tile(const TDesc &d, u64 e0, u32 cnt, float (&v)[16])
+{
+    const float *p = d.data + e0;
+    const u32 tid = threadIdx.x;
+    if (cnt == (u32)TILE && d.aligned16) {
+        const float4 *p4 = reinterpret_cast<const float4 *>(p);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            float4 q = p4[tid + 1024u * j];
+            v[4 * j + 0] = q.x;
+            v[4 * j + 1] = q.y;
+            v[4 * j + 2] = q.z;
+            v[4 * j + 3] = q.w;
+        }
+        return 0xFFFFu;
+    }
+    u32 mask = 0u;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            u32 idx = 4u * (tid + 1024u * j) + c;
+            float x = 0.0f;
+            if (idx < cnt) {
+                x = p[idx];
+                mask |= 1u << (4 * j + c);
+            }
+            v[4 * j + c] = x;
+        }
+    }
+    return mask;
+}
+
+} // namespace inshr

@@ -1,0 +1,555 @@
+// Exact thresholds and bin boundaries (Sec. 4.2-4.4) by two counting sweeps and one gathering
+// sweep over the tensors; every launch covers all tensors of a batch.
+//
+//   sweep 1  k_hist<1>     LDS histogram of key >> 17 (32768 bins), zero / negative counts,
+//                          NaN / Inf detection
+//   k_plan1                per tensor: first-level magnitude bin ("bucket") of every prune /
+//                          protect threshold rank; a key -> bin table whose bins hold about
+//                          n / 32768 elements each
+//   sweep 2  k_hist<2>     LDS histogram over the table's bins; elements of threshold buckets are
+//                          gathered
+//   k_thr_select           exact thresholds and class counts from the gathered buckets
+//   k_plan2                exact rank of every boundary of every (prune, protect) pair -> its bin;
+//                          only those bins are "active"
+//   sweep 3  k_gather      elements of active bins are gathered bin by bin; sums of squares;
+//                          protected-value counts per tile
+//   k_bnd_select           exact boundary = residual-rank element of its bin
+#include "inshr_launch.h"
+
+namespace inshr {
+
+// ------------------------------------------------------------------------------------------
+// sweeps 1 and 2: histograms
+// ------------------------------------------------------------------------------------------
+template <int LEVEL>
+__global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, int nT,
+                                                const u64 *__restrict__ wg_tile0, Bufs B)
+{
+    extern __shared__ u32 smem[];
+    u32 *h = smem;           // 32768 counters
+    u32 *T = smem + L2_BINS; // LEVEL 2: 4096 table entries
+    u32 *bm = T + COARSE;    // LEVEL 2: 512-word bitmap of bucket magnitude bins
+    __shared__ u32 s_bmag[MAX_THR];
+    __shared__ u64 s_boff[MAX_THR];
+    __shared__ u32 s_nb;
+
+    const u32 tid = threadIdx.x;
+    for (int i = tid; i < L2_BINS; i += BLOCK) h[i] = 0u;
+    const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
+    if (tile_lo >= tile_hi) return;
+    int t = find_tensor(td, nT, tile_lo);
+    u64 tile = tile_lo;
+    while (tile < tile_hi) {
+        const TDesc d = td[t];
+        const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
+        const u64 t_end = d.tile0 + n_tiles_t;
+        const u64 stop = t_end < tile_hi ? t_end : tile_hi;
+        TState *st = B.ts + t;
+        if (LEVEL == 2) {
+            for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+            for (int i = tid; i < 512; i += BLOCK) bm[i] = B.bitmap[(size_t)t * 512 + i];
+            if (tid < MAX_THR) {
+                s_bmag[tid] = st->bucket_magbin[tid];
+                s_boff[tid] = d.pool_thr + st->bucket_off[tid];
+            }
+            if (tid == 0) s_nb = st->n_buckets;
+        }
+        __syncthreads();
+        u32 c_neg = 0u, c_zero = 0u, c_bad = 0u;
+        for (; tile < stop; tile++) {
+            const u64 e0 = (tile - d.tile0) * (u64)TILE;
+            const u64 rem = d.n - e0;
+            const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+            float v[16];
+            const u32 mask = load_tile(d, e0, cnt, v);
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                if (!((mask >> i) & 1u)) continue;
+                const u32 b = canon_bits(__float_as_uint(v[i]));
+                const u32 key = key_of_bits(b);
+                if (LEVEL == 1) {
+                    c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
+                    c_neg += (b >> 31);
+                    c_zero += (b == 0u) ? 1u : 0u;
+                    atomicAdd(&h[key >> L1_SHIFT], 1u);
+                } else {
+                    atomicAdd(&h[l2_bin(key, T[key >> COARSE_SHIFT])], 1u);
+                    const u32 m17 = (b & 0x7fffffffu) >> L1_SHIFT;
+                    if (((bm[m17 >> 5] >> (m17 & 31u)) & 1u) && b != 0u) {
+                        const u32 nb = s_nb;
+                        for (u32 q = 0; q < nb; q++) {
+                            if (s_bmag[q] == m17) {
+                                u32 pos = atomicAdd(&st->bucket_cursor[q], 1u);
+                                B.pool[s_boff[q] + pos] = key;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // flush this tensor's counts
+        u32 *gh = (LEVEL == 1 ? B.hist1 : B.hist2) + (size_t)t * L2_BINS;
+        for (int i = tid; i < L2_BINS; i += BLOCK) {
+            u32 c = h[i];
+            if (c) {
+                atomicAdd(&gh[i], c);
+                h[i] = 0u;
+            }
+        }
+        if (LEVEL == 1) {
+            c_neg = wave_sum(c_neg);
+            c_zero = wave_sum(c_zero);
+            c_bad = wave_sum(c_bad);
+            if ((tid & 63u) == 0u) {
+                if (c_neg) atomicAdd((unsigned long long *)&st->n_neg, (unsigned long long)c_neg);
+                if (c_zero) atomicAdd((unsigned long long *)&st->n_zero, (unsigned long long)c_zero);
+                if (c_bad) atomicOr(&st->nonfinite, 1u);
+            }
+        }
+        __syncthreads();
+        t++;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// plan 1: threshold buckets and the second-level table
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ u32 depth_for(u32 nc, u64 target)
+{
+    u32 d = 0;
+    while (d < 20u && (u64)nc > (target << d)) d++;
+    return d;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
+                                                 const GridDesc *__restrict__ gd, Bufs B)
+{
+    extern __shared__ u32 smem[];
+    u32 *A = smem;                    // [16385] magnitude-bin counts -> exclusive prefix
+    u32 *Bn = smem + (L1_MAGBINS + 4); // [16385] negative counts -> exclusive prefix
+    u32 *nc = Bn + (L1_MAGBINS + 4);  // [4097] per coarse prefix
+    __shared__ u32 tmp[BLOCK / 64 + 1];
+    __shared__ u32 s_j[MAX_THR];
+    __shared__ u64 s_res[MAX_THR];
+
+    const int t = blockIdx.x;
+    const u32 tid = threadIdx.x;
+    const u64 n = td[t].n;
+    TState *st = B.ts + t;
+    const u32 *h1 = B.hist1 + (size_t)t * L1_BINS;
+    for (int j = tid; j < L1_MAGBINS; j += BLOCK) {
+        u32 cn = h1[L1_MAGBINS - 1 - j], cp = h1[L1_MAGBINS + j];
+        A[j] = cn + cp;
+        Bn[j] = cn;
+    }
+    for (int c = tid; c < COARSE; c += BLOCK) {
+        u32 s = 0;
+        for (int i = 0; i < 8; i++) s += h1[8 * c + i];
+        nc[c] = s;
+    }
+    __syncthreads();
+    u32 total = block_excl_scan(A, A, L1_MAGBINS, tmp);
+    block_excl_scan(Bn, Bn, L1_MAGBINS, tmp);
+    if (tid == 0 && (u64)total != n) atomicOr(&st->internal_err, 1u);
+
+    const u32 n_p = gd->n_p, n_o = gd->n_o, n_thr = n_p + n_o;
+    if (tid < n_thr) {
+        u64 R;
+        if (tid < n_p)
+            R = n * (u64)gd->p_ppm[tid] / 1000000ull;
+        else
+            R = n - 1ull - n * (u64)gd->o_ppm[tid - n_p] / 1000000ull;
+        // first i in [0, 16384] with A[i] > R
+        int lo = 0, hi = L1_MAGBINS;
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if ((u64)A[mid] > R)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        int j = lo - 1;
+        s_j[tid] = (u32)j;
+        s_res[tid] = R - (u64)A[j];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 nb = 0;
+        u64 off = 0;
+        st->n_thr = n_thr;
+        for (u32 q = 0; q < n_thr; q++) {
+            u32 j = s_j[q];
+            u32 found = nb;
+            for (u32 k = 0; k < nb; k++)
+                if (st->bucket_magbin[k] == j) found = k;
+            if (found == nb) {
+                st->bucket_magbin[nb] = j;
+                st->bucket_below_neg[nb] = Bn[j];
+                st->bucket_below_pos[nb] = A[j] - Bn[j];
+                u32 cn = h1[L1_MAGBINS - 1 - j], cp = h1[L1_MAGBINS + j];
+                st->bucket_cnt_neg[nb] = cn;
+                st->bucket_cnt_pos[nb] = cp;
+                st->bucket_off[nb] = off;
+                st->bucket_cursor[nb] = 0u;
+                off += (u64)cn + cp;
+                nb++;
+            }
+            st->thr_bucket[q] = found;
+            st->thr_res[q] = s_res[q];
+        }
+        st->n_buckets = nb;
+    }
+    u32 *bmp = B.bitmap + (size_t)t * 512;
+    for (int i = tid; i < 512; i += BLOCK) bmp[i] = 0u;
+    __syncthreads();
+    if (tid < n_thr) atomicOr(&bmp[s_j[tid] >> 5], 1u << (s_j[tid] & 31u));
+
+    // second-level table: smallest target population whose bin total fits
+    u64 lo = 1, hi = n;
+    while (lo < hi) {
+        u64 mid = lo + ((hi - lo) >> 1);
+        u32 s = 0;
+        for (int c = tid; c < COARSE; c += BLOCK) s += nc[c] ? (1u << depth_for(nc[c], mid)) : 1u;
+        s = wave_sum(s);
+        __syncthreads();
+        if ((tid & 63u) == 0u) tmp[tid >> 6] = s;
+        __syncthreads();
+        u32 tot = 0;
+        for (int w = 0; w < BLOCK / 64; w++) tot += tmp[w];
+        if (tot <= (u32)L2_BINS)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    __syncthreads();
+    u32 *cnt = A; // reuse: bins per coarse prefix
+    for (int c = tid; c < COARSE; c += BLOCK) cnt[c] = nc[c] ? (1u << depth_for(nc[c], lo)) : 1u;
+    __syncthreads();
+    u32 nb2 = block_excl_scan(cnt, Bn, COARSE, tmp); // Bn[c] = base
+    u32 *tab = B.table2 + (size_t)t * COARSE;
+    for (int c = tid; c < COARSE; c += BLOCK) {
+        u32 d = nc[c] ? depth_for(nc[c], lo) : 0u;
+        tab[c] = (Bn[c] << 5) | d;
+    }
+    if (tid == 0) {
+        st->nb2 = nb2;
+        st->zbin = Bn[ZERO_KEY >> COARSE_SHIFT];
+        if (nb2 > (u32)L2_BINS) atomicOr(&st->internal_err, 2u);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// exact thresholds from the gathered buckets (one wavefront per threshold)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_thr_select(const TDesc *__restrict__ td, Bufs B)
+{
+    const int t = blockIdx.x / MAX_THR;
+    const u32 q = blockIdx.x % MAX_THR;
+    TState *st = B.ts + t;
+    if (q >= st->n_thr) return;
+    const u32 lane = threadIdx.x;
+    const u32 bq = st->thr_bucket[q];
+    const u32 mb = st->bucket_magbin[bq];
+    const u32 *list = B.pool + td[t].pool_thr + st->bucket_off[bq];
+    const u32 c = st->bucket_cursor[bq];
+    const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
+    const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
+    if (lane == 0 && (u64)c != expect) atomicOr(&st->internal_err, 4u);
+    const u64 res = st->thr_res[q];
+    u32 tau = 0u;
+    if (res >= zeros) {
+        if (res - zeros >= (u64)c) {
+            if (lane == 0) atomicOr(&st->internal_err, 8u);
+            return;
+        }
+        tau = wave_select(list, c, (u32)(res - zeros), true);
+    }
+    u32 ln = 0, lp = 0, gn = 0, gp = 0;
+    for (u32 i = lane; i < c; i += 64u) {
+        u32 k = list[i];
+        u32 m = mag_of_key(k);
+        bool neg = key_is_neg(k);
+        ln += (m < tau && neg) ? 1u : 0u;
+        lp += (m < tau && !neg) ? 1u : 0u;
+        gn += (m > tau && neg) ? 1u : 0u;
+        gp += (m > tau && !neg) ? 1u : 0u;
+    }
+    ln = wave_sum(ln);
+    lp = wave_sum(lp);
+    gn = wave_sum(gn);
+    gp = wave_sum(gp);
+    if (lane == 0) {
+        const u64 n = td[t].n, n_neg = st->n_neg, n_pos = n - n_neg;
+        st->thr_mag[q] = tau;
+        st->thr_lt_neg[q] = st->bucket_below_neg[bq] + ln;
+        st->thr_lt_pos[q] = st->bucket_below_pos[bq] + lp + ((mb == 0u && tau > 0u) ? zeros : 0ull);
+        st->thr_gt_neg[q] = n_neg - st->bucket_below_neg[bq] - st->bucket_cnt_neg[bq] + gn;
+        st->thr_gt_pos[q] = n_pos - st->bucket_below_pos[bq] - st->bucket_cnt_pos[bq] + gp;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// plan 2: boundary ranks -> active bins
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
+                                                 const GridDesc *__restrict__ gd, Bufs B)
+{
+    extern __shared__ u32 smem[];
+    u32 *cum = smem; // [nb2 + 1]
+    __shared__ u32 tmp[BLOCK / 64 + 1];
+    __shared__ u64 sAn[MAX_PAIRS], sMn[MAX_PAIRS], sPP[MAX_PAIRS], sM[MAX_PAIRS];
+
+    const int t = blockIdx.x;
+    const u32 tid = threadIdx.x;
+    const u64 n = td[t].n;
+    TState *st = B.ts + t;
+    const u32 nb2 = st->nb2;
+    const u32 zbin = st->zbin;
+    const u64 n_zero = st->n_zero;
+    const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+    u32 *binfo = B.binfo + (size_t)t * L2_BINS;
+    u32 *cur = B.cursor2 + (size_t)t * CURSOR_STRIDE;
+    const u32 n_pairs = gd->n_pairs, n_p = gd->n_p;
+
+    u32 total = block_excl_scan(h2, cum, (int)nb2, tmp);
+    if (tid == 0 && (u64)total != n) atomicOr(&st->internal_err, 16u);
+    if (tid < n_pairs) {
+        const u32 tp = gd->pair_p[tid], to = n_p + gd->pair_o[tid];
+        const u64 n_neg = st->n_neg, n_pos = n - n_neg;
+        const u64 Pn = st->thr_lt_neg[tp], Pp = st->thr_lt_pos[tp];
+        const u64 An = st->thr_gt_neg[to], Ap = st->thr_gt_pos[to];
+        const u64 Mn = n_neg - An - Pn, Mp = n_pos - Ap - Pp;
+        st->pair_An[tid] = An;
+        st->pair_Ap[tid] = Ap;
+        st->pair_Pn[tid] = Pn;
+        st->pair_Pp[tid] = Pp;
+        st->pair_Mn[tid] = Mn;
+        st->pair_M[tid] = Mn + Mp;
+        sAn[tid] = An;
+        sMn[tid] = Mn;
+        sPP[tid] = Pn + Pp;
+        sM[tid] = Mn + Mp;
+        if (Mn + Mp == 0ull || Mn > n || Mp > n) atomicOr(&st->internal_err, 32u);
+    }
+    for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = 0u;
+    __syncthreads();
+    const u32 TG = n_pairs * NB8;
+    u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
+    u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
+    u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
+    for (u32 i = tid; i < TG; i += BLOCK) {
+        const u32 q = i / NB8, j = i % NB8 + 1u;
+        const u64 M = sM[q];
+        const u64 k = (u64)j * M / 256ull;
+        const u64 r = (k < sMn[q]) ? sAn[q] + k : sAn[q] + sPP[q] + k;
+        // first index in [0, nb2] with cum[idx] > r
+        u32 lo = 0, hi = nb2;
+        while (lo < hi) {
+            u32 mid = (lo + hi) >> 1;
+            if ((u64)cum[mid] > r)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        if (r >= n || lo == 0u) {
+            atomicOr(&st->internal_err, 64u);
+            tb[i] = RESOLVED;
+            tk[i] = 0u;
+            continue;
+        }
+        u32 bin = lo - 1u;
+        u64 res = r - (u64)cum[bin];
+        if (bin == zbin && res < n_zero) {
+            tb[i] = RESOLVED;
+            tr[i] = 0u;
+            tk[i] = ZERO_KEY;
+        } else {
+            if (bin == zbin) res -= n_zero;
+            tb[i] = bin;
+            tr[i] = (u32)res;
+            binfo[bin] = 1u;
+        }
+    }
+    __syncthreads();
+    for (u32 i = tid; i < nb2; i += BLOCK)
+        cur[i] = binfo[i] ? (h2[i] - ((i == zbin) ? (u32)n_zero : 0u)) : 0u;
+    __syncthreads();
+    u32 ctot = block_excl_scan(cur, cur, (int)nb2, tmp);
+    for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = binfo[i] ? cur[i] : INACTIVE;
+    __syncthreads();
+    for (u32 i = tid; i <= nb2; i += BLOCK) cur[i] = 0u;
+    if (tid == 0) st->cand_total = ctot;
+}
+
+// ------------------------------------------------------------------------------------------
+// sweep 3: gather the elements of active bins; sums of squares; protected counts per tile
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, int nT,
+                                                  const u64 *__restrict__ wg_tile0,
+                                                  const u32 *__restrict__ wg_fu0,
+                                                  const GridDesc *__restrict__ gd, Bufs B)
+{
+    extern __shared__ u32 smem[];
+    u32 *binfo = smem;          // 32768
+    u32 *T = smem + L2_BINS;    // 4096
+    __shared__ u32 s_tau_o[MAX_FRAC];
+    __shared__ u32 s_oc[MAX_FRAC];
+    __shared__ double s_red[BLOCK / 64];
+
+    const u32 tid = threadIdx.x;
+    const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
+    if (tile_lo >= tile_hi) return;
+    const u32 n_p = gd->n_p, n_o = gd->n_o;
+    int t = find_tensor(td, nT, tile_lo);
+    const int t_first = t;
+    u64 tile = tile_lo;
+    while (tile < tile_hi) {
+        const TDesc d = td[t];
+        const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
+        const u64 t_end = d.tile0 + n_tiles_t;
+        const u64 stop = t_end < tile_hi ? t_end : tile_hi;
+        TState *st = B.ts + t;
+        const u32 *gb = B.binfo + (size_t)t * L2_BINS;
+        const u32 nb2 = st->nb2;
+        for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = gb[i];
+        for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+        if (tid < MAX_FRAC) {
+            s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
+            s_oc[tid] = 0u;
+        }
+        __syncthreads();
+        u32 tau_o_min = 0x7fffffffu;
+        for (u32 o = 0; o < n_o; o++) tau_o_min = min(tau_o_min, s_tau_o[o]);
+        u32 *cur = B.cursor2 + (size_t)t * CURSOR_STRIDE;
+        u32 *cand = B.pool + d.pool_cand;
+        double q_tot = 0.0;
+        double q_out[MAX_FRAC];
+#pragma unroll
+        for (int o = 0; o < MAX_FRAC; o++) q_out[o] = 0.0;
+        for (; tile < stop; tile++) {
+            const u64 e0 = (tile - d.tile0) * (u64)TILE;
+            const u64 rem = d.n - e0;
+            const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+            float v[16];
+            const u32 mask = load_tile(d, e0, cnt, v);
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                if (!((mask >> i) & 1u)) continue;
+                const u32 b = canon_bits(__float_as_uint(v[i]));
+                const u32 key = key_of_bits(b);
+                const double xd = (double)v[i];
+                q_tot = fma(xd, xd, q_tot);
+                if (b != 0u) {
+                    const u32 off = binfo[l2_bin(key, T[key >> COARSE_SHIFT])];
+                    if (off != INACTIVE) {
+                        u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
+                        u32 pos = atomicAdd(&cur[bin], 1u);
+                        cand[off + pos] = key;
+                    }
+                }
+                const u32 m = b & 0x7fffffffu;
+                if (m > tau_o_min) {
+#pragma unroll
+                    for (int o = 0; o < MAX_FRAC; o++) {
+                        if (o < (int)n_o && m > s_tau_o[o]) {
+                            q_out[o] = fma(xd, xd, q_out[o]);
+                            atomicAdd(&s_oc[o], 1u);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            if (tid < MAX_FRAC) {
+                B.tile_out[tile * MAX_FRAC + tid] = s_oc[tid];
+                s_oc[tid] = 0u;
+            }
+            __syncthreads();
+        }
+        // flush partial sums of this (workgroup, tensor) unit in a fixed order
+        const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
+        double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
+#pragma unroll
+        for (int o = 0; o <= MAX_FRAC; o++) {
+            if (o > (int)n_o) break;
+            double x = (o == 0) ? q_tot : q_out[o == 0 ? 0 : o - 1];
+            x = wave_sum_f64(x);
+            if ((tid & 63u) == 0u) s_red[tid >> 6] = x;
+            __syncthreads();
+            if (tid == 0) {
+                double s = 0.0;
+                for (int w = 0; w < BLOCK / 64; w++) s += s_red[w];
+                part[o] = s;
+            }
+            __syncthreads();
+        }
+        t++;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// exact boundaries: residual-rank element of the boundary's bin (one wavefront per boundary)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_bnd_select(const TDesc *__restrict__ td, int nT, u32 TG,
+                                                    Bufs B)
+{
+    const u64 gid = (u64)blockIdx.x * 4u + (threadIdx.x >> 6);
+    const int t = (int)(gid / TG);
+    const u32 i = (u32)(gid % TG);
+    if (t >= nT) return;
+    TState *st = B.ts + t;
+    const u32 bin = B.tgt_bin[(size_t)t * TGT_STRIDE + i];
+    if (bin == RESOLVED) return;
+    const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
+    const u32 off = B.binfo[(size_t)t * L2_BINS + bin];
+    const u32 c = B.cursor2[(size_t)t * CURSOR_STRIDE + bin];
+    const u32 expect = B.hist2[(size_t)t * L2_BINS + bin] - ((bin == st->zbin) ? (u32)st->n_zero : 0u);
+    if (off == INACTIVE || c != expect || res >= c) {
+        if ((threadIdx.x & 63u) == 0u) atomicOr(&st->internal_err, 128u);
+        return;
+    }
+    u32 key = wave_select(B.pool + td[t].pool_cand + off, c, res, false);
+    if ((threadIdx.x & 63u) == 0u) B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
+}
+
+// ------------------------------------------------------------------------------------------
+// launch wrappers
+// ------------------------------------------------------------------------------------------
+constexpr int SM_HIST1 = L2_BINS * 4;
+constexpr int SM_HIST2 = (L2_BINS + COARSE + 512) * 4;
+constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
+constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
+constexpr int SM_GATHER = (L2_BINS + COARSE) * 4;
+
+static bool g_attr_done = false;
+static hipError_t set_attrs()
+{
+    if (g_attr_done) return hipSuccess;
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void *)k_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST1))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST2))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_gather, hipFuncAttributeMaxDynamicSharedMemorySize, SM_GATHER))) return e;
+    g_attr_done = true;
+    return hipSuccess;
+}
+
+hipError_t launch_select(const Batch &bt, hipStream_t s)
+{
+    hipError_t e = set_attrs();
+    if (e) return e;
+    const Bufs &B = bt.bufs;
+    k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, B);
+    k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B);
+    k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, B);
+    k_thr_select<<<bt.nT * MAX_THR, 64, 0, s>>>(bt.td, B);
+    k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B);
+    k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B);
+    const u32 TG = bt.n_pairs * NB8;
+    const u64 waves = (u64)bt.nT * TG;
+    k_bnd_select<<<(unsigned)((waves + 3) / 4), 256, 0, s>>>(bt.td, bt.nT, TG, B);
+    return hipGetLastError();
+}
+
+} // namespace inshr

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Bit-exact on thresholds, boundaries, symbols, protected lists, permutations,
+delta streams, counts and chosen configurations; 1e-6 relative on centres and error sums (plus an
+absolute floor of 1e-12 * sumsq on error sums, the fp64 rounding of sumsq - sum_bins(...))."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2306_11800_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2306_11800_amd import api
+    c = api.Context(torch.device("cuda:0"))
+    yield c
+    c.close()
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+
+
+def u64(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def check_scores(gscores, nC, ti, x, grid, eps, gbest, gfeas):
+    rbest, rfeas, rsc = ref.search(x, grid, eps)
+    border = False
+    for g in range(nC):
+        s, r = gscores[ti * nC + g], rsc[g]
+        assert (s.n_pruned, s.n_outlier, s.n_kept, s.cost_bits) == \
+            (r["n_pruned"], r["n_outlier"], r["n_kept"], r["cost_bits"]), (ti, grid[g])
+        assert abs(s.sumsq - r["sumsq"]) <= REL * r["sumsq"], (ti, grid[g])
+        assert abs(s.sse - r["sse"]) <= REL * r["sse"] + 1e-12 * r["sumsq"], (ti, grid[g], s.sse, r["sse"])
+        if r["sumsq"] > 0 and abs(r["sse"] / r["sumsq"] - eps) <= 4 * REL * eps:
+            border = True
+    if not border:
+        assert (gbest, gfeas) == (rbest, rfeas), (ti, gbest, rbest)
+    return rbest
+
+
+def check_quantized(q, x, cfg):
+    r = ref.quantize(x, cfg)
+    bits = cfg[0]
+    assert q.sym_bits == bits + 1
+    assert (q.n_pruned, q.n_outlier, q.n_kept) == (r["n_pruned"], r["n_outlier"], r["n_kept"])
+    assert np.float32(q.tau_prune).view(np.uint32) == r["tau_prune_bits"]
+    assert np.float32(q.tau_outlier).view(np.uint32) == r["tau_outlier_bits"]
+    assert np.array_equal(u32(q.boundaries), r["boundaries"].view(np.uint32)), cfg
+    want = ref.pack(r["sym"], bits + 1)
+    got = u64(q.packed)
+    if not np.array_equal(got, want):
+        gs = ref.unpack(got, x.size, bits + 1)
+        bad = np.nonzero(gs != r["sym"])[0]
+        raise AssertionError(f"symbols differ at {bad[:10]} ({bad.size} of {x.size}) cfg={cfg}: "
+                             f"{gs[bad[:10]]} vs {r['sym'][bad[:10]]}")
+    assert np.array_equal(u32(q.outlier_idx), r["outlier_idx"])
+    assert np.array_equal(u32(q.outlier_val), r["outlier_val"].view(np.uint32))
+    cb = q.codebook.cpu().numpy()
+    np.testing.assert_allclose(cb, r["codebook"], rtol=REL, atol=0)
+    return r
+
+
+def check_delta(d, rp, bp, rc, bc, want_perm):
+    rd = ref.delta(rp["sym"], bp, rc["sym"], bc)
+    assert d.delta_bits == rd["delta_bits"]
+    assert np.array_equal(u64(d.group_off), rd["group_off"])
+    want = ref.pack(rd["stream"], rd["delta_bits"])
+    got = u64(d.packed)
+    if not np.array_equal(got, want):
+        gs = ref.unpack(got, rp["sym"].size, rd["delta_bits"])
+        bad = np.nonzero(gs != rd["stream"])[0]
+        raise AssertionError(f"delta stream differs at {bad[:10]} ({bad.size}): {gs[bad[:10]]} vs "
+                             f"{rd['stream'][bad[:10]]}")
+    if want_perm:
+        assert np.array_equal(u32(d.perm), rd["perm"])
+
+
+def run_pipeline(ctx, prevs, curs, grid, eps, want_perm=True, check_all_cfg_quantize=False):
+    """search + quantize(prev), search + quantize(cur), delta; everything checked against the oracle."""
+    nC = len(grid)
+    results = []
+    for xs in (prevs, curs):
+        ts = [dev(x) for x in xs]
+        best, feas, scores = ctx.search(ts, grid, eps)
+        chosen = []
+        for ti, x in enumerate(xs):
+            rb = check_scores(scores, nC, ti, x, grid, eps, best[ti], feas[ti])
+            chosen.append(grid[rb])
+        qs = ctx.quantize(ts, chosen, reuse_search=True)
+        refs = [check_quantized(q, x, c) for q, x, c in zip(qs, xs, chosen)]
+        if check_all_cfg_quantize:
+            for g in grid:
+                qg = ctx.quantize(ts, [g] * len(ts), reuse_search=True)
+                for q, x in zip(qg, xs):
+                    check_quantized(q, x, g)
+        results.append((qs, refs, chosen))
+    (qp, rp, cp), (qc, rc, cc) = results
+    ds = ctx.delta(qp, qc, want_perm=want_perm)
+    ctx.sync()
+    for i, d in enumerate(ds):
+        check_delta(d, rp[i], cp[i][0], rc[i], cc[i][0], want_perm)
+    return results, ds
+
+
+def test_config0_small_grid(ctx):
+    prev, cur = synth.config0(seed=0, n=1 << 20)
+    run_pipeline(ctx, [prev], [cur], synth.grid_small(), synth.EPS_DEFAULT)
+
+
+def test_every_config_quantizes_identically(ctx):
+    prev, cur = synth.config0(seed=1, n=200_003)
+    run_pipeline(ctx, [prev], [cur], synth.grid_small(), synth.EPS_DEFAULT, check_all_cfg_quantize=True)
+
+
+def test_full_grid_ragged_batch(ctx):
+    rng = np.random.default_rng(5)
+    sizes = [1, 2, 63, 64, 65, 255, 256, 257, 1000, 4096, 16383, 16384, 16385, 50_000, 300_001]
+    prevs = [(0.02 * rng.standard_t(4, n)).astype(np.float32) for n in sizes]
+    curs = [(p + rng.normal(0, 1e-4, p.size)).astype(np.float32) for p in prevs]
+    run_pipeline(ctx, prevs, curs, synth.grid_full(), synth.EPS_DEFAULT)
+
+
+def test_degenerate_tensors(ctx):
+    rng = np.random.default_rng(6)
+    n = 40_000
+    zeros95 = rng.normal(0, 1e-3, n).astype(np.float32)
+    zeros95[rng.random(n) < 0.95] = 0.0
+    negz = zeros95.copy()
+    negz[::7] = -0.0
+    few = rng.choice(np.array([-0.5, 0.1, 0.1, 0.7, 0.0, 3.0], np.float32), n)
+    prevs = [np.full(5000, 0.25, np.float32), np.zeros(3000, np.float32), zeros95, negz, few,
+             np.arange(1, 4097, dtype=np.float32),
+             np.array([1e-45, -1e-45, 3e-39, -2e-39, 1e-38, 0.0, 1.0] * 50, np.float32),
+             np.abs(rng.normal(0, 1e-6, n)).astype(np.float32)]
+    curs = [p.copy() for p in prevs]
+    curs[2] = (zeros95 + (rng.random(n) < 0.01) * rng.normal(0, 1e-3, n)).astype(np.float32)
+    curs[4] = rng.choice(np.array([-0.5, 0.1, 0.7, 0.0, 3.0], np.float32), n)
+    run_pipeline(ctx, prevs, curs, synth.grid_small(), synth.EPS_DEFAULT)
+
+
+def test_standalone_quantize_matches_reuse(ctx):
+    prev, _ = synth.config0(seed=2, n=150_000)
+    x2 = (0.02 * np.random.default_rng(3).standard_t(4, 70_001)).astype(np.float32)
+    ts = [dev(prev), dev(x2)]
+    cfgs = [(4, 100000, 1000), (8, 0, 0)]
+    qs = ctx.quantize(ts, cfgs, reuse_search=False)
+    for q, x, c in zip(qs, [prev, x2], cfgs):
+        check_quantized(q, x, c)
+    # the same through a search over a grid that contains both
+    grid = synth.grid_small()
+    ctx.search(ts, grid, synth.EPS_DEFAULT)
+    qr = ctx.quantize(ts, cfgs, reuse_search=True)
+    for a, b in zip(qs, qr):
+        assert torch.equal(a.packed, b.packed)
+        assert torch.equal(a.boundaries, b.boundaries)
+        assert torch.equal(a.outlier_idx, b.outlier_idx)
+        np.testing.assert_allclose(a.codebook.cpu().numpy(), b.codebook.cpu().numpy(), rtol=REL)
+
+
+def test_delta_unequal_bits_and_given_permutation(ctx):
+    prev, cur = synth.config0(seed=4, n=123_457)
+    tp, tc = [dev(prev)], [dev(cur)]
+    for cp, cc in [((2, 100000, 1000), (8, 0, 0)), ((8, 300000, 1000), (3, 0, 0)), ((1, 0, 0), (1, 0, 0))]:
+        qp = ctx.quantize(tp, [cp])
+        qc = ctx.quantize(tc, [cc])
+        rp, rc = ref.quantize(prev, cp), ref.quantize(cur, cc)
+        d = ctx.delta(qp, qc, want_perm=True)
+        ctx.sync()
+        check_delta(d[0], rp, cp[0], rc, cc[0], True)
+        # previous permutation handed back: same stream
+        d2 = ctx.delta(qp, qc, want_perm=False, prev_perm=[d[0].perm])
+        ctx.sync()
+        assert torch.equal(d2[0].packed, d[0].packed)
+        assert torch.equal(d2[0].group_off, d[0].group_off)
+    # delta(prev, prev) is all zero
+    qp = ctx.quantize(tp, [(4, 100000, 1000)])
+    d = ctx.delta(qp, qp)
+    ctx.sync()
+    assert not d[0].packed.any()
+
+
+def test_errors(ctx):
+    from paper_2306_11800_amd import api
+    x = np.ones(1000, np.float32)
+    for bad in (np.nan, np.inf):
+        y = x.copy()
+        y[17] = bad
+        with pytest.raises(api.InshrError) as e:
+            ctx.search([dev(y)], synth.grid_small(), 0.01)
+        assert e.value.code == -3
+    with pytest.raises(api.InshrError) as e:
+        ctx.search([dev(x)], [(9, 0, 0)], 0.01)
+    assert e.value.code == -2
+    with pytest.raises(api.InshrError) as e:
+        ctx.search([dev(x)], [(4, 600000, 400000)], 0.01)
+    assert e.value.code == -2
+    with pytest.raises(api.InshrError) as e:
+        ctx.quantize([dev(x)], [(4, 0, 0)], reuse_search=True)  # no matching search (last one failed)
+    assert e.value.code == -5
+    # still usable afterwards
+    best, feas, _ = ctx.search([dev(x)], synth.grid_small(), 0.01)
+    assert feas == [1]
+
+
+def test_deterministic_bytes(ctx):
+    prev, cur = synth.config0(seed=9, n=300_000)
+    outs = []
+    for _ in range(2):
+        ts = [dev(prev)]
+        ctx.search(ts, synth.grid_small(), 0.01)
+        q = ctx.quantize(ts, [(4, 100000, 1000)], reuse_search=True)[0]
+        outs.append((q.packed.clone(), q.boundaries.clone(), q.outlier_idx.clone()))
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
