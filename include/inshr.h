@@ -50,14 +50,15 @@ enum {
 };
 
 /* Most distinct (prune_ppm, outlier_ppm) pairs, and most distinct values of either, in one grid. */
-#define INSHR_MAX_PAIRS 31
-#define INSHR_MAX_FRACTIONS 16
+#define INSHR_MAX_PAIRS 15
+#define INSHR_MAX_FRACTIONS 8
 
 typedef struct inshr_ctx inshr_ctx; /* opaque: one device, one stream, scratch memory */
 
 /* device: HIP device ordinal.  hip_stream: a hipStream_t or NULL for the default stream.
- * scratch_bytes: device scratch the context may allocate (0 = a default sized from free memory);
- * tensors are processed in sub-batches that fit it. */
+ * scratch_bytes: largest single device allocation the context may make for its scratch (0 = no
+ * limit).  A search over tensors of N elements in total needs about 8*N bytes plus about 1.5 MB per
+ * tensor; a call that needs more than the limit returns INSHR_E_CAPACITY. */
 int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch_bytes);
 void inshr_destroy(inshr_ctx *ctx);
 const char *inshr_strerror(int code);
@@ -145,6 +146,19 @@ int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t 
  * recomputed. */
 int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *prev_perm,
                 const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors);
+
+/* Per-kernel timing for benchmarks (not part of the method): when enabled, every kernel launch of
+ * this process is bracketed by HIP events on its stream.  inshr_profile(ctx, 1) clears the totals
+ * and starts recording, inshr_profile(ctx, 0) stops.  inshr_profile_read synchronises the stream
+ * and returns the accumulated time and launch count per kernel name (*n = number of names; at most
+ * cap entries are written to out, which may be NULL to query the count). */
+typedef struct {
+    char name[32];
+    double total_ms;
+    uint64_t launches;
+} inshr_kernel_time;
+int inshr_profile(inshr_ctx *ctx, int enable);
+int inshr_profile_read(inshr_ctx *ctx, inshr_kernel_time *out, uint32_t cap, uint32_t *n);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
-           "inshr_delta_bound", "inshr_delta"]
+           "inshr_delta_bound", "inshr_delta", "inshr_profile", "inshr_profile_read"]
 
 INSHR_REUSE_SEARCH = 1
 
@@ -47,6 +47,10 @@ class CQuantized(C.Structure):
 class CCodes(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("sym_bits", C.c_uint32), ("bits", C.c_uint8),
                 ("n", C.c_uint64)]
+
+
+class CKernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("total_ms", C.c_double), ("launches", C.c_uint64)]
 
 
 class CDeltaOut(C.Structure):
@@ -83,6 +87,9 @@ def load_library() -> C.CDLL:
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
+    lib.inshr_profile.argtypes = [C.c_void_p, C.c_int]
+    lib.inshr_profile_read.argtypes = [C.c_void_p, C.POINTER(CKernelTime), C.c_uint32,
+                                       C.POINTER(C.c_uint32)]
     _lib = lib
     return lib
 
@@ -170,6 +177,17 @@ class Context:
     def sync(self):
         self._check(self.lib.inshr_sync(self.h))
 
+    def profile(self, enable: bool):
+        self._check(self.lib.inshr_profile(self.h, 1 if enable else 0))
+
+    def profile_read(self):
+        """{kernel name: (total ms, launches)} since profile(True)."""
+        n = C.c_uint32()
+        arr = (CKernelTime * 64)()
+        self._check(self.lib.inshr_profile_read(self.h, arr, 64, C.byref(n)))
+        return {arr[i].name.decode(): (arr[i].total_ms, int(arr[i].launches))
+                for i in range(min(n.value, 64))}
+
     # -- inshr_search ---------------------------------------------------------------------
     def search(self, tensors: Sequence[torch.Tensor], grid, eps: float, want_scores: bool = True):
         """Returns (best[list of int], feasible[list of int], scores or None) where scores is a
@@ -184,7 +202,10 @@ class Context:
         return list(best), list(feas), scores
 
     # -- inshr_quantize -------------------------------------------------------------------
-    def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False) -> List[Quantized]:
+    def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False,
+                 out: Optional[List[Quantized]] = None) -> List[Quantized]:
+        """`out` may carry the Quantized objects of an earlier call on tensors of the same sizes;
+        their device buffers (allocated at full capacity) are then written again."""
         nT = len(tensors)
         ta = _tensor_array(tensors)
         ca = _config_array(cfgs)
@@ -194,13 +215,18 @@ class Context:
             words, cap = C.c_uint64(), C.c_uint64()
             self._check(self.lib.inshr_quantize_bound(t.numel(), C.byref(ca[i]), C.byref(words), C.byref(cap)))
             K = 1 << int(cfg[0])
-            packed = torch.empty(words.value, dtype=torch.int64, device=t.device)
-            cb = torch.empty(256, dtype=torch.float32, device=t.device)
-            bd = torch.empty(255, dtype=torch.float32, device=t.device)
-            oi = torch.empty(max(cap.value, 1), dtype=torch.int32, device=t.device)
-            ov = torch.empty(max(cap.value, 1), dtype=torch.float32, device=t.device)
+            if out is not None:
+                packed, cb, bd, oi, ov = out[i]._bufs
+                if packed.numel() < words.value or oi.numel() < cap.value:
+                    raise ValueError("pre-allocated buffers are too small")
+            else:
+                packed = torch.empty(words.value, dtype=torch.int64, device=t.device)
+                cb = torch.empty(256, dtype=torch.float32, device=t.device)
+                bd = torch.empty(255, dtype=torch.float32, device=t.device)
+                oi = torch.empty(max(cap.value, 1), dtype=torch.int32, device=t.device)
+                ov = torch.empty(max(cap.value, 1), dtype=torch.float32, device=t.device)
             qa[i].packed = packed.data_ptr()
-            qa[i].packed_words = words.value
+            qa[i].packed_words = packed.numel()
             qa[i].codebook = cb.data_ptr()
             qa[i].boundaries = bd.data_ptr()
             qa[i].outlier_idx = oi.data_ptr()
@@ -208,16 +234,19 @@ class Context:
             qa[i].outlier_cap = cap.value
             bufs.append((packed, cb, bd, oi, ov, K))
         self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, INSHR_REUSE_SEARCH if reuse_search else 0))
-        out = []
+        res = []
         for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
             packed, cb, bd, oi, ov, K = bufs[i]
             no = int(qa[i].n_outlier)
-            out.append(Quantized(n=t.numel(), bits=int(cfg[0]), sym_bits=int(qa[i].sym_bits),
-                                 packed=packed, codebook=cb[:K], boundaries=bd[:K - 1],
-                                 outlier_idx=oi[:no], outlier_val=ov[:no],
-                                 n_pruned=int(qa[i].n_pruned), n_outlier=no, n_kept=int(qa[i].n_kept),
-                                 tau_prune=float(qa[i].tau_prune), tau_outlier=float(qa[i].tau_outlier)))
-        return out
+            w = int(qa[i].sym_bits)
+            q = Quantized(n=t.numel(), bits=int(cfg[0]), sym_bits=w,
+                          packed=packed[:(t.numel() * w + 63) // 64], codebook=cb[:K],
+                          boundaries=bd[:K - 1], outlier_idx=oi[:no], outlier_val=ov[:no],
+                          n_pruned=int(qa[i].n_pruned), n_outlier=no, n_kept=int(qa[i].n_kept),
+                          tau_prune=float(qa[i].tau_prune), tau_outlier=float(qa[i].tau_outlier))
+            q._bufs = (packed, cb, bd, oi, ov)
+            res.append(q)
+        return res
 
     # -- inshr_delta ----------------------------------------------------------------------
     def delta(self, prev: Sequence[Quantized], cur: Sequence[Quantized], want_perm: bool = False,
@@ -245,6 +274,8 @@ class Context:
                           packed=torch.empty(words.value, dtype=torch.int64, device=dev),
                           group_off=torch.empty((1 << p.bits) + 3, dtype=torch.int64, device=dev),
                           perm=torch.empty(p.n, dtype=torch.int32, device=dev) if want_perm else None)
+            if d.packed.numel() < words.value:
+                raise ValueError("pre-allocated delta buffer is too small")
             oa[i].packed = d.packed.data_ptr()
             oa[i].packed_words = d.packed.numel()
             oa[i].group_off = d.group_off.data_ptr()

@@ -47,7 +47,61 @@ struct inshr_ctx {
     size_t ts_off = 0, scores_off = 0;
 };
 
+// ------------------------------------------------------------------------------------------
+// optional per-kernel timing (HIP events on the launch stream)
+// ------------------------------------------------------------------------------------------
 namespace {
+struct ProfState {
+    bool on = false;
+    std::vector<hipEvent_t> pool;       // event pairs, reused
+    std::vector<const char *> pending;  // name of each recorded pair
+    std::vector<std::string> names;
+    std::vector<double> total_ms;
+    std::vector<uint64_t> launches;
+} g_prof;
+} // namespace
+
+namespace inshr {
+void prof_begin(const char *name, hipStream_t s)
+{
+    if (!g_prof.on) return;
+    const size_t k = g_prof.pending.size();
+    while (g_prof.pool.size() < 2 * (k + 1)) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        g_prof.pool.push_back(e);
+    }
+    g_prof.pending.push_back(name);
+    (void)hipEventRecord(g_prof.pool[2 * k], s);
+}
+void prof_end(hipStream_t s)
+{
+    if (!g_prof.on || g_prof.pending.empty()) return;
+    const size_t k = g_prof.pending.size() - 1;
+    (void)hipEventRecord(g_prof.pool[2 * k + 1], s);
+}
+} // namespace inshr
+
+namespace {
+
+void prof_collect()
+{
+    for (size_t k = 0; k < g_prof.pending.size(); k++) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.pool[2 * k], g_prof.pool[2 * k + 1]) != hipSuccess) continue;
+        size_t i = 0;
+        for (; i < g_prof.names.size(); i++)
+            if (g_prof.names[i] == g_prof.pending[k]) break;
+        if (i == g_prof.names.size()) {
+            g_prof.names.push_back(g_prof.pending[k]);
+            g_prof.total_ms.push_back(0.0);
+            g_prof.launches.push_back(0);
+        }
+        g_prof.total_ms[i] += ms;
+        g_prof.launches[i]++;
+    }
+    g_prof.pending.clear();
+}
 
 #define HIPCHK(ctx, call)                                                                         \
     do {                                                                                          \
@@ -378,6 +432,37 @@ int inshr_sync(inshr_ctx *c)
     if (!c) return INSHR_E_ARG;
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    return INSHR_OK;
+}
+
+int inshr_profile(inshr_ctx *c, int enable)
+{
+    if (!c) return INSHR_E_ARG;
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    prof_collect();
+    g_prof.on = enable != 0;
+    if (enable) {
+        g_prof.names.clear();
+        g_prof.total_ms.clear();
+        g_prof.launches.clear();
+    }
+    return INSHR_OK;
+}
+
+int inshr_profile_read(inshr_ctx *c, inshr_kernel_time *out, uint32_t cap, uint32_t *n)
+{
+    if (!c || !n) return INSHR_E_ARG;
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    prof_collect();
+    *n = (uint32_t)g_prof.names.size();
+    for (uint32_t i = 0; i < *n && i < cap && out; i++) {
+        memset(&out[i], 0, sizeof(out[i]));
+        strncpy(out[i].name, g_prof.names[i].c_str(), sizeof(out[i].name) - 1);
+        out[i].total_ms = g_prof.total_ms[i];
+        out[i].launches = g_prof.launches[i];
+    }
     return INSHR_OK;
 }
 

@@ -345,14 +345,14 @@ hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
                         const u64 *chunk_tile0, u16 *tile_hist, u32 *chunk_tot, bool any_scatter,
                         bool any_gather, hipStream_t s)
 {
-    k_dhist<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist);
-    k_dchunk<<<(unsigned)n_chunks, SS, 0, s>>>(dd, nT, chunk_tile0, tile_hist, chunk_tot);
-    k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot);
+    PROF("k_dhist", s, k_dhist<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist));
+    PROF("k_dchunk", s, k_dchunk<<<(unsigned)n_chunks, SS, 0, s>>>(dd, nT, chunk_tile0, tile_hist, chunk_tot));
+    PROF("k_dgroups", s, k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot));
     if (any_scatter) {
-        k_dzero<<<dim3(64, nT), 256, 0, s>>>(dd, nT);
-        k_dscatter<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist, chunk_tot);
+        PROF("k_dzero", s, k_dzero<<<dim3(64, nT), 256, 0, s>>>(dd, nT));
+        PROF("k_dscatter", s, k_dscatter<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist, chunk_tot));
     }
-    if (any_gather) k_dgather<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT);
+    if (any_gather) PROF("k_dgather", s, k_dgather<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT));
     return hipGetLastError();
 }
 

@@ -78,6 +78,16 @@ constexpr int DELTA_TILE = 16384;
 constexpr int DELTA_CHUNK = 64;
 constexpr int DELTA_SS = 264;
 
+// Optional per-kernel timing with HIP events on the launch stream (off by default).
+void prof_begin(const char *name, hipStream_t s);
+void prof_end(hipStream_t s);
+#define PROF(name, s, ...)                                                                        \
+    do {                                                                                          \
+        prof_begin(name, s);                                                                      \
+        __VA_ARGS__;                                                                              \
+        prof_end(s);                                                                              \
+    } while (0)
+
 hipError_t launch_select(const Batch &bt, hipStream_t s);
 hipError_t launch_score(const Batch &bt, hipStream_t s);
 hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStream_t s);

@@ -200,8 +200,8 @@ hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStrea
         if (e) return e;
         attr = true;
     }
-    k_qprep<<<bt.nT, BLOCK, (L2_BINS + 4) * 4, s>>>(bt.td, bt.gd, qd, qi, bt.bufs);
-    k_quant<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs);
+    PROF("k_qprep", s, k_qprep<<<bt.nT, BLOCK, (L2_BINS + 4) * 4, s>>>(bt.td, bt.gd, qd, qi, bt.bufs));
+    PROF("k_quant", s, k_quant<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs));
     return hipGetLastError();
 }
 

@@ -321,9 +321,9 @@ hipError_t launch_score(const Batch &bt, hipStream_t s)
         g_attr_done = true;
     }
     const Bufs &B = bt.bufs;
-    k_plan3<<<bt.nT, BLOCK, SM_PLAN3, s>>>(bt.gd, B);
-    k_score<<<bt.n_wg, BLOCK, SM_SCORE, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B);
-    k_final<<<bt.nT, BLOCK, SM_FINAL, s>>>(bt.td, bt.gd, bt.t_fu_off, bt.t_fu_ids, B);
+    PROF("k_plan3", s, k_plan3<<<bt.nT, BLOCK, SM_PLAN3, s>>>(bt.gd, B));
+    PROF("k_score", s, k_score<<<bt.n_wg, BLOCK, SM_SCORE, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
+    PROF("k_final", s, k_final<<<bt.nT, BLOCK, SM_FINAL, s>>>(bt.td, bt.gd, bt.t_fu_off, bt.t_fu_ids, B));
     return hipGetLastError();
 }
 

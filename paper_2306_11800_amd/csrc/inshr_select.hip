@@ -540,15 +540,15 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     hipError_t e = set_attrs();
     if (e) return e;
     const Bufs &B = bt.bufs;
-    k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, B);
-    k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B);
-    k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, B);
-    k_thr_select<<<bt.nT * MAX_THR, 64, 0, s>>>(bt.td, B);
-    k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B);
-    k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B);
+    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
+    PROF("k_plan1", s, k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
+    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
+    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, 64, 0, s>>>(bt.td, B));
+    PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
+    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     const u32 TG = bt.n_pairs * NB8;
     const u64 waves = (u64)bt.nT * TG;
-    k_bnd_select<<<(unsigned)((waves + 3) / 4), 256, 0, s>>>(bt.td, bt.nT, TG, B);
+    PROF("k_bnd_select", s, k_bnd_select<<<(unsigned)((waves + 3) / 4), 256, 0, s>>>(bt.td, bt.nT, TG, B));
     return hipGetLastError();
 }
 
