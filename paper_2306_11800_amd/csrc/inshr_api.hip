@@ -31,6 +31,7 @@ struct inshr_ctx {
     uint64_t scratch_limit = 0;
     int n_cu = 256;
     int wg_per_cu = 2;
+    bool lds_ordered = false; // same-address LDS atomics return in lane order (checked at creation)
     std::string last_err;
 
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
@@ -394,6 +395,22 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
         int v = atoi(e);
         if (v >= 1 && v <= 16) c->wg_per_cu = v;
     }
+    // the delta kernels have a fast path that needs same-address LDS atomics to be served in lane
+    // order; it is used only if this device passes the check (INSHR_DELTA_SLOTS=1 forces it off)
+    {
+        u32 *viol = nullptr;
+        u32 h = 1;
+        if (hipMalloc(&viol, 4) == hipSuccess) {
+            if (hipMemsetAsync(viol, 0, 4, c->stream) == hipSuccess &&
+                launch_lds_order_check(viol, c->stream) == hipSuccess &&
+                hipMemcpyAsync(&h, viol, 4, hipMemcpyDeviceToHost, c->stream) == hipSuccess &&
+                hipStreamSynchronize(c->stream) == hipSuccess)
+                c->lds_ordered = (h == 0);
+            (void)hipFree(viol);
+        }
+        if (const char *e = getenv("INSHR_DELTA_SLOTS"))
+            if (atoi(e) != 0) c->lds_ordered = false;
+    }
     *out = c;
     return INSHR_OK;
 }
@@ -626,9 +643,9 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
 {
     if (!c || !prev || !cur || !out || n_tensors == 0) return INSHR_E_ARG;
     std::vector<DDesc> dd(n_tensors);
-    std::vector<u64> chunk_tile0;
+    std::vector<u32> chunk_tensor;
     u64 dtile = 0, chunk = 0;
-    bool any_scatter = false, any_gather = false;
+    bool any_scatter = false, any_gather = false, any_perm = false;
     for (uint32_t t = 0; t < n_tensors; t++) {
         uint64_t words = 0;
         int rc = inshr_delta_bound(&prev[t], &cur[t], &words);
@@ -658,21 +675,21 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
         d.chunk0 = chunk;
         const u64 nt = (n + DELTA_TILE - 1) / DELTA_TILE;
         d.n_chunks = (nt + DELTA_CHUNK - 1) / DELTA_CHUNK;
-        for (u64 k = 0; k < d.n_chunks; k++) chunk_tile0.push_back(dtile + k * DELTA_CHUNK);
+        for (u64 k = 0; k < d.n_chunks; k++) chunk_tensor.push_back(t);
         dtile += nt;
         chunk += d.n_chunks;
         if (d.prev_perm)
             any_gather = true;
+        else if (d.perm)
+            any_perm = true;
         else
             any_scatter = true;
     }
-    chunk_tile0.push_back(dtile);
     HIPCHK(c, hipSetDevice(c->device));
     Carver cv;
     const size_t o_dd = cv.take(sizeof(DDesc) * n_tensors);
-    const size_t o_ct = cv.take(sizeof(u64) * chunk_tile0.size());
+    const size_t o_ct = cv.take(sizeof(u32) * chunk_tensor.size());
     const size_t up_bytes = cv.off;
-    const size_t o_th = cv.take((size_t)dtile * DELTA_SS * 2);
     const size_t o_ck = cv.take((size_t)chunk * DELTA_SS * 4);
     int rc = ensure_dev(c, c->aux_mem, cv.off);
     if (rc) return rc;
@@ -682,11 +699,11 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
     HIPCHK(c, hipStreamSynchronize(c->stream));
     char *hb = (char *)c->h_up.p, *db = (char *)c->aux_mem.p;
     memcpy(hb + o_dd, dd.data(), sizeof(DDesc) * n_tensors);
-    memcpy(hb + o_ct, chunk_tile0.data(), sizeof(u64) * chunk_tile0.size());
+    memcpy(hb + o_ct, chunk_tensor.data(), sizeof(u32) * chunk_tensor.size());
     HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, launch_delta((const DDesc *)(db + o_dd), (int)n_tensors, dtile, chunk,
-                           (const u64 *)(db + o_ct), (u16 *)(db + o_th), (u32 *)(db + o_ck),
-                           any_scatter, any_gather, c->stream));
+                           (const u32 *)(db + o_ct), (u32 *)(db + o_ck), any_scatter, any_perm,
+                           any_gather, c->lds_ordered, c->stream));
     return INSHR_OK;
 }
 

@@ -2,20 +2,29 @@
 // the stable order of the previous checkpoint's symbol (Algorithm 5) and bit-packed.
 //
 // The regrouping is a stable partition into at most 258 groups:
-//   k_dhist     per tile of 16384 elements: population of every previous symbol
-//   k_dchunk    per chunk of 64 tiles: totals;  k_dgroups: per tensor: group offsets and the start
-//               of every chunk inside every group
-//   k_dscatter  per tile: stable rank of every element inside (tile, group) from wavefront ballots
-//               (each wave owns 1024 consecutive elements, 64 consecutive elements per step), the
-//               tile's elements are laid out group by group in LDS and each group's run is written
-//               to its place in the packed stream (whole words stored, the two end words OR-ed in)
+//   k_dhist     per chunk (64 tiles of 12288 elements): population of every previous symbol
+//   k_dgroups   per tensor: group offsets and the start of every chunk inside every group
+//   k_dscatter  one workgroup of 12 waves per chunk walks its tiles in order.  Per tile each wave
+//               owns 1024 consecutive elements, 64 consecutive elements per step.  Equal symbols of
+//               a step find each other by OR-ing their lane bit into the symbol's LDS slot, which
+//               gives the stable rank inside the step; per-(wave, symbol) counters carry it across
+//               steps and waves.  The tile's deltas are laid out group by group as a bit stream in
+//               LDS, and each group's run is copied to its place in the packed output with a funnel
+//               shift (whole words stored, the words shared with neighbouring runs OR-ed into the
+//               zeroed output).
 #include "inshr_launch.h"
 
 namespace inshr {
 
-constexpr int DTILE = 16384;
-constexpr int DCHUNK = 64;     // tiles per chunk
-constexpr int SS = 264;        // symbol stride (258 symbols at most)
+constexpr int DTILE = DELTA_TILE;   // elements per tile = 1024 per wave of the scatter workgroup
+constexpr int DCHUNK = DELTA_CHUNK; // tiles per chunk
+constexpr int SS = DELTA_SS;        // symbol stride (258 symbols at most)
+constexpr int NWAVE = DTILE / 1024; // waves of a scatter workgroup (two workgroups share a CU)
+constexpr int DBLOCK = NWAVE * 64;
+constexpr int TWORDS = DTILE * 9 / 64;            // most packed u64 words of one tile
+constexpr u64 CHUNK_ELEMS = (u64)DTILE * DCHUNK;  // 786432, a multiple of 16384
+constexpr int HTILE = 16384;                      // step of the counting and gathering kernels
+static_assert(CHUNK_ELEMS % HTILE == 0, "chunks are whole counting steps");
 
 __device__ __forceinline__ u32 lds_extract(const u32 *W, u32 idx, u32 w)
 {
@@ -25,91 +34,45 @@ __device__ __forceinline__ u32 lds_extract(const u32 *W, u32 idx, u32 w)
     return (u32)(two >> sh) & ((1u << w) - 1u);
 }
 
-// lanes of this wave that hold the same symbol (among valid lanes)
-__device__ __forceinline__ u64 wave_peers(u32 sym, u32 w, bool valid)
+// population of every previous symbol in one chunk
+__global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
+                                                 const u32 *__restrict__ chunk_tensor,
+                                                 u32 *__restrict__ chunk_tot)
 {
-    u64 peers = __ballot(valid);
-    for (u32 b = 0; b < w; b++) {
-        const bool bit = (sym >> b) & 1u;
-        const u64 m = __ballot(bit);
-        peers &= bit ? m : ~m;
-    }
-    return peers;
-}
-
-__device__ __forceinline__ int find_dtensor(const DDesc *dd, int nT, u64 tile)
-{
-    int lo = 0, hi = nT - 1;
-    while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (dd[mid].dtile0 <= tile)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    return lo;
-}
-
-// stage the packed words of elements [e0, e0 + cnt) (e0 a multiple of 64) into LDS as u32 words
-__device__ __forceinline__ void stage_words(const unsigned long long *src, u64 e0, u32 cnt, u32 w,
-                                            u32 *dst)
-{
-    const u64 w0 = e0 * w / 64u; // exact: e0 is a multiple of 64
-    const u32 nw = (cnt * w + 63u) >> 6;
-    for (u32 k = threadIdx.x; k < nw; k += BLOCK) {
-        unsigned long long x = src[w0 + k];
-        dst[2 * k] = (u32)x;
-        dst[2 * k + 1] = (u32)(x >> 32);
-    }
-    if (threadIdx.x < 2) dst[2 * nw + threadIdx.x] = 0u;
-}
-
-__global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd, int nT,
-                                                 u16 *__restrict__ tile_hist)
-{
-    __shared__ u32 P[DTILE * 9 / 32 + 4];
-    __shared__ u32 cntw[BLOCK / 64][SS];
-    const u64 tile = blockIdx.x;
-    const int t = find_dtensor(dd, nT, tile);
-    const DDesc d = dd[t];
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u64 e0 = (tile - d.dtile0) * (u64)DTILE;
-    const u64 rem = d.n - e0;
-    const u32 cnt = rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
+    __shared__ u32 P[HTILE * 9 / 32 + 4];
+    __shared__ u32 hw[BLOCK / 64][SS];
+    const u64 chunk = blockIdx.x;
+    const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
+    const u32 tid = threadIdx.x, wave = tid >> 6;
     const u32 S = d.Kp + 2u;
-    stage_words(d.prev, e0, cnt, d.wp, P);
-    for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&cntw[0][0])[k] = 0u;
-    __syncthreads();
-    for (u32 r = 0; r < 16u; r++) {
-        const u32 idx = wave * 1024u + r * 64u + lane;
-        const bool valid = idx < cnt;
-        const u32 sym = valid ? lds_extract(P, idx, d.wp) : 0u;
-        const u64 peers = wave_peers(sym, d.wp, valid);
-        if (valid && sym < S) {
-            const u32 rank = __popcll(peers & ((1ull << lane) - 1ull));
-            if (rank == 0u) cntw[wave][sym] += __popcll(peers);
+    const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
+    const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
+    const GLOBAL_AS unsigned long long *src = gptr(d.prev);
+    for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
+    for (u64 e0 = c0; e0 < c1; e0 += HTILE) {
+        const u32 cnt = (c1 - e0 < (u64)HTILE) ? (u32)(c1 - e0) : (u32)HTILE;
+        __syncthreads();
+        const u64 w0 = e0 * d.wp / 64u; // exact: e0 is a multiple of 64
+        const u32 nw = (cnt * d.wp + 63u) >> 6;
+        for (u32 k = tid; k < nw; k += BLOCK) {
+            unsigned long long x = src[w0 + k];
+            P[2 * k] = (u32)x;
+            P[2 * k + 1] = (u32)(x >> 32);
+        }
+        if (tid < 2) P[2 * nw + tid] = 0u;
+        __syncthreads();
+        for (u32 idx = tid; idx < cnt; idx += BLOCK) {
+            const u32 sym = lds_extract(P, idx, d.wp);
+            if (sym < S) atomicAdd(&hw[wave][sym], 1u);
         }
     }
     __syncthreads();
-    for (u32 g = tid; g < S; g += BLOCK) {
+    for (u32 g = tid; g < SS; g += BLOCK) {
         u32 s = 0;
-        for (int wv = 0; wv < BLOCK / 64; wv++) s += cntw[wv][g];
-        tile_hist[tile * SS + g] = (u16)s; // <= 16384
+        if (g < S)
+            for (int wv = 0; wv < BLOCK / 64; wv++) s += hw[wv][g];
+        chunk_tot[chunk * SS + g] = s;
     }
-}
-
-// totals of each chunk of 64 tiles
-__global__ __launch_bounds__(SS) void k_dchunk(const DDesc *__restrict__ dd, int nT,
-                                               const u64 *__restrict__ chunk_tile0, // [n_chunks + 1] first tile of each chunk
-                                               const u16 *__restrict__ tile_hist,
-                                               u32 *__restrict__ chunk_tot)
-{
-    const u64 c = blockIdx.x;
-    const u64 t0 = chunk_tile0[c], t1 = chunk_tile0[c + 1];
-    const u32 g = threadIdx.x;
-    u32 s = 0;
-    for (u64 tile = t0; tile < t1; tile++) s += tile_hist[tile * SS + g];
-    chunk_tot[c * SS + g] = s;
 }
 
 // per tensor: group offsets; chunk_tot becomes the start of each chunk inside its group
@@ -132,227 +95,369 @@ __global__ __launch_bounds__(SS) void k_dgroups(const DDesc *__restrict__ dd,
     if (g == 0) {
         u64 acc = 0;
         for (u32 k = 0; k < S; k++) {
-            d.group_off[k] = acc;
+            gptr(d.group_off)[k] = acc;
             acc += tot[k];
         }
-        d.group_off[S] = acc;
+        gptr(d.group_off)[S] = acc;
     }
 }
 
-__global__ __launch_bounds__(BLOCK) void k_dscatter(const DDesc *__restrict__ dd, int nT,
-                                                    const u16 *__restrict__ tile_hist,
-                                                    const u32 *__restrict__ chunk_tot)
+// words of one tile's packed symbols held in registers (prefetch of the next tile)
+struct TileWords {
+    unsigned long long w[3];
+};
+__device__ __forceinline__ TileWords fetch_words(const GLOBAL_AS unsigned long long *src, u64 e0,
+                                                 u32 cnt, u32 w)
 {
-    __shared__ u32 P[DTILE * 9 / 32 + 4];
-    __shared__ u32 C[DTILE * 9 / 32 + 4];
-    __shared__ u32 wst[BLOCK / 64][SS];     // counts, then local start of (wave, symbol)
-    __shared__ u32 lbase[SS + 1];           // local start of each symbol's run
-    __shared__ u32 gcnt[SS];                // tile population per symbol
-    __shared__ u64 gbase[SS];               // global stream position of each run
-    __shared__ u32 woff[SS + 1];            // first work item (output word) of each run
-    __shared__ u16 sd[DTILE];               // deltas in regrouped order
-    __shared__ u16 si[DTILE];               // local indices in regrouped order
+    TileWords t;
+    const u64 w0 = e0 * w / 64u; // exact: e0 is a multiple of 64
+    const u32 nw = (cnt * w + 63u) >> 6;
+#pragma unroll
+    for (int k = 0; k < 3; k++) {
+        const u32 i = threadIdx.x + k * DBLOCK;
+        t.w[k] = (i < nw) ? src[w0 + i] : 0ull;
+    }
+    return t;
+}
+__device__ __forceinline__ void store_words(const TileWords &t, u32 cnt, u32 w, u32 *dst)
+{
+    const u32 nw = (cnt * w + 63u) >> 6; // <= TWORDS < 3 * DBLOCK
+#pragma unroll
+    for (int k = 0; k < 3; k++) {
+        const u32 i = threadIdx.x + k * DBLOCK;
+        if (i <= nw) { // one zero word of padding after the last
+            dst[2 * i] = (u32)t.w[k];
+            dst[2 * i + 1] = (u32)(t.w[k] >> 32);
+        }
+    }
+}
+static_assert(TWORDS + 1 <= 3 * DBLOCK, "three words per thread cover a tile");
 
-    const u64 tile = blockIdx.x;
-    const int t = find_dtensor(dd, nT, tile);
-    const DDesc d = dd[t];
+// word j of a run: c symbols of wB bits that start at bit `src0` of the LDS stream go to global
+// stream position gbv
+__device__ __forceinline__ void emit_word(const unsigned long long *bits,
+                                          GLOBAL_AS unsigned long long *out, u32 j, u32 s0, u64 Wf,
+                                          u32 nbits, int src0)
+{
+    const int rel = (int)(j * 64u) - (int)s0; // run-relative bit of the word's bit 0
+    const int lo = rel < 0 ? 0 : rel;
+    const int hi = (rel + 64 < (int)nbits) ? rel + 64 : (int)nbits;
+    const int sb = src0 + rel;
+    unsigned long long val;
+    if (sb >= 0) {
+        const u32 wd = (u32)sb >> 6, sh = (u32)sb & 63u;
+        val = bits[wd] >> sh;
+        if (sh) val |= bits[wd + 1u] << (64u - sh);
+    } else {
+        val = bits[0] << (u32)(-sb);
+    }
+    const u32 a = (u32)(lo - rel), b = (u32)(hi - rel); // keep bits [a, b) of val
+    unsigned long long m = (b >= 64u) ? ~0ull : ((1ull << b) - 1ull);
+    m &= ~((1ull << a) - 1ull);
+    val &= m;
+    if (a == 0u && b == 64u)
+        out[Wf + j] = val;
+    else if (val)
+        __hip_atomic_fetch_or(out + (Wf + j), val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr u32 SHORT_RUN = 16; // runs of up to this many output words are copied by one thread
+
+// ORDERED: same-address LDS atomics with return are served in ascending lane order on this device
+// (checked by k_lds_order_check before the library relies on it); one returning add then ranks an
+// element.  Otherwise equal symbols of a step find each other through the slot array.
+template <bool PERM, bool ORDERED>
+__global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict__ dd,
+                                                     const u32 *__restrict__ chunk_tensor,
+                                                     const u32 *__restrict__ chunk_tot)
+{
+    __shared__ u32 P[DTILE * 9 / 32 + 8];
+    __shared__ u32 C[DTILE * 9 / 32 + 8];
+    // slot[wave][symbol]: lanes of the wave's current step that hold the symbol (sweep 1);
+    // the same memory then holds the tile's regrouped deltas as a bit stream (sweep 2, output)
+    __shared__ unsigned long long slot[ORDERED ? TWORDS + 2 : NWAVE * SS];
+    __shared__ u32 wst[NWAVE][SS]; // counts, then local start of (wave, symbol) in the tile's layout
+    __shared__ u32 lbase[SS];      // local start of each symbol's run
+    __shared__ u32 gcnt[SS];       // tile population per symbol
+    __shared__ u32 gb[SS];         // stream position of each group's next run (n < 2^32)
+    __shared__ u32 wtot[8];
+    __shared__ u16 si[PERM ? DTILE : 1]; // local indices in regrouped order
+    unsigned long long *bits = slot;
+    static_assert(NWAVE * SS >= TWORDS + 2, "bit stream fits the slot array");
+
+
+    const u64 chunk = blockIdx.x;
+    const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
     if (d.prev_perm) return; // this tensor's regrouping is given: k_dgather writes its stream
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u64 lt = tile - d.dtile0;
-    const u64 e0 = lt * (u64)DTILE;
-    const u64 rem = d.n - e0;
-    const u32 cnt = rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
-    const u32 S = d.Kp + 2u, Bm = d.B, wB = d.wB;
-    stage_words(d.prev, e0, cnt, d.wp, P);
-    stage_words(d.cur, e0, cnt, d.wc, C);
-    for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&wst[0][0])[k] = 0u;
-    __syncthreads();
-    // population of (wave, symbol)
-    for (u32 r = 0; r < 16u; r++) {
-        const u32 idx = wave * 1024u + r * 64u + lane;
-        const bool valid = idx < cnt;
-        const u32 sym = valid ? lds_extract(P, idx, d.wp) : 0u;
-        const u64 peers = wave_peers(sym, d.wp, valid);
-        if (valid && sym < S) {
-            const u32 rank = __popcll(peers & ((1ull << lane) - 1ull));
-            if (rank == 0u) wst[wave][sym] += __popcll(peers);
-        }
-    }
-    __syncthreads();
-    // global start of this tile's run of every symbol; totals
+    if (PERM != (d.perm != nullptr)) return;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const u32 S = d.Kp + 2u, Bm = d.B, wB = d.wB, wp = d.wp, wc = d.wc;
+    const u64 n_tiles = (d.n + DTILE - 1) / DTILE;
+    const u64 lt0 = (chunk - d.chunk0) * DCHUNK;
+    const u64 lt1 = (lt0 + DCHUNK < n_tiles) ? lt0 + DCHUNK : n_tiles;
+    GLOBAL_AS unsigned long long *out = gptr(d.out);
     if (tid < S) {
-        const u32 g = tid;
-        u32 s = 0;
-        for (int wv = 0; wv < BLOCK / 64; wv++) s += wst[wv][g];
-        gcnt[g] = s;
-        const u64 chunk = d.chunk0 + lt / DCHUNK;
-        u64 base = d.group_off[g] + chunk_tot[chunk * SS + g];
-        const u64 first = d.dtile0 + (lt / DCHUNK) * DCHUNK;
-        for (u64 tl = first; tl < tile; tl++) base += tile_hist[tl * SS + g];
-        gbase[g] = base;
+        gb[tid] = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
+        gcnt[tid] = 0u;
     }
-    __syncthreads();
-    if (tid == 0) {
-        u32 acc = 0, wacc = 0;
-        for (u32 g = 0; g < S; g++) {
-            lbase[g] = acc;
-            woff[g] = wacc;
-            const u32 c = gcnt[g];
-            if (c) {
-                const u64 fb = gbase[g] * wB, lb = (gbase[g] + c) * wB;
-                wacc += (u32)(((lb - 1) >> 6) - (fb >> 6) + 1);
+    const u64 ltmask = (1ull << lane) - 1ull;
+    const unsigned long long lanebit = 1ull << lane;
+
+    auto tile_cnt = [&](u64 lt) -> u32 {
+        const u64 rem = d.n - lt * (u64)DTILE;
+        return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
+    };
+    for (u64 lt = lt0; lt < lt1; lt++) {
+        const u64 e0 = lt * (u64)DTILE;
+        const u32 cnt = tile_cnt(lt);
+        __syncthreads();
+        if (tid < S) gb[tid] += gcnt[tid]; // the previous tile's runs have been written
+        store_words(fetch_words(gptr(d.prev), e0, cnt, wp), cnt, wp, P);
+        store_words(fetch_words(gptr(d.cur), e0, cnt, wc), cnt, wc, C);
+        for (u32 k = tid; k < (ORDERED ? TWORDS + 2 : NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
+        for (u32 k = tid; k < SS * NWAVE; k += DBLOCK) (&wst[0][0])[k] = 0u;
+        __syncthreads();
+        // sweep 1: stable rank of every element among the equal symbols of its wave's 1024 elements
+        u32 reg[16];
+        unsigned long long *myslot = slot + wave * SS;
+        u32 ebase = wave * 1024u + lane;
+        asm volatile("" : "+v"(ebase)); // keeps the 32 per-step LDS addresses from being hoisted
+                                        // out of the tile loop and spilled
+#pragma unroll
+        for (u32 r = 0; r < 16u; r++) {
+            const u32 idx = ebase + r * 64u;
+            const bool valid = idx < cnt;
+            u32 sp = S, sc = 0u; // lanes past the end share the unused symbol S
+            if (valid) {
+                sp = lds_extract(P, idx, wp);
+                sc = lds_extract(C, idx, wc);
+                if (sp >= S) sp = S - 1u; // never for a well-formed stream
             }
-            acc += c;
-        }
-        lbase[S] = acc;
-        woff[S] = wacc;
-    }
-    __syncthreads();
-    if (tid < S) {
-        u32 run = lbase[tid];
-        for (int wv = 0; wv < BLOCK / 64; wv++) {
-            u32 c = wst[wv][tid];
-            wst[wv][tid] = run;
-            run += c;
-        }
-    }
-    __syncthreads();
-    // stable ranks and regrouped layout
-    for (u32 r = 0; r < 16u; r++) {
-        const u32 idx = wave * 1024u + r * 64u + lane;
-        const bool valid = idx < cnt;
-        const u32 sp = valid ? lds_extract(P, idx, d.wp) : 0u;
-        const u64 peers = wave_peers(sp, d.wp, valid);
-        if (valid && sp < S) {
-            const u32 sc = lds_extract(C, idx, d.wc);
-            const u32 rank = __popcll(peers & ((1ull << lane) - 1ull));
-            const u32 old = wst[wave][sp];
-            if (rank == 0u) wst[wave][sp] = old + __popcll(peers);
-            const u32 L = old + rank;
+            u32 within; // elements of this wave with the same symbol and a lower index
+            if (ORDERED) {
+                within = atomicAdd(&wst[wave][sp], 1u);
+            } else {
+                atomicOr(&myslot[sp], lanebit);
+                const unsigned long long peers = myslot[sp];
+                const u32 rank = __popcll(peers & ltmask);
+                const u32 old = wst[wave][sp];
+                if (rank == 0u) {
+                    myslot[sp] = 0ull;
+                    wst[wave][sp] = old + (u32)__popcll(peers);
+                }
+                within = old + rank;
+            }
             u32 dv = sp + Bm - sc;
             if (dv >= Bm) dv -= Bm;
-            sd[L] = (u16)dv;
-            si[L] = (u16)idx;
+            reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
         }
-    }
-    __syncthreads();
-    // write the runs: one work item per (run, output word)
-    const u32 n_items = woff[S];
-    for (u32 it = tid; it < n_items; it += BLOCK) {
-        u32 lo = 0, hi = S - 1u; // last g with woff[g] <= it and gcnt[g] > 0
-        while (lo < hi) {
-            u32 mid = (lo + hi + 1u) >> 1;
-            if (woff[mid] <= it)
-                lo = mid;
-            else
-                hi = mid - 1u;
+        __syncthreads();
+        // counts -> positions: population of each symbol, exclusive scan over symbols, start of
+        // every (wave, symbol)
+        u32 tot = 0, pre = 0;
+        if (tid < S) {
+#pragma unroll
+            for (int wv = 0; wv < NWAVE; wv++) tot += wst[wv][tid];
         }
-        // woff is flat over empty runs; lo is the last index with woff <= it, which is non-empty
-        // unless followed by equal entries; step back to the run that owns the item
-        u32 g = lo;
-        while (gcnt[g] == 0u) g--;
-        const u64 gb = gbase[g];
-        const u64 fb = gb * wB, lb = (gb + gcnt[g]) * wB;
-        const u64 W = (fb >> 6) + (it - woff[g]);
-        const u64 wlo = W << 6, whi = wlo + 64u;
-        const u64 a = fb > wlo ? fb : wlo, b = lb < whi ? lb : whi;
-        const u64 ra = a / wB, rb = (b - 1u) / wB;
-        unsigned long long word = 0ull;
-        for (u64 rr = ra; rr <= rb; rr++) {
-            const unsigned long long val = sd[lbase[g] + (u32)(rr - gb)];
-            const long long bp = (long long)(rr * wB) - (long long)wlo;
-            word |= (bp >= 0) ? (val << bp) : (val >> (-bp));
-        }
-        if (a == wlo && b == whi)
-            d.out[W] = word;
-        else if (word)
-            atomicOr(&d.out[W], word);
-    }
-    if (d.perm) {
-        for (u32 L = tid; L < cnt; L += BLOCK) {
-            u32 lo = 0, hi = S - 1u; // last g with lbase[g] <= L
-            while (lo < hi) {
-                u32 mid = (lo + hi + 1u) >> 1;
-                if (lbase[mid] <= L)
-                    lo = mid;
-                else
-                    hi = mid - 1u;
+        if (tid < 320u) { // waves 0..4 hold the 258 symbols
+            u32 inc = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                u32 v = __shfl_up(inc, o);
+                if ((int)lane >= o) inc += v;
             }
-            u32 g = lo;
-            while (gcnt[g] == 0u) g--;
-            d.perm[gbase[g] + (L - lbase[g])] = (u32)(e0 + si[L]);
+            pre = inc - tot;
+            if (lane == 63u) wtot[wave] = inc;
+        }
+        __syncthreads();
+        if (tid < S) {
+            u32 base = pre;
+            for (u32 w2 = 0; w2 < wave; w2++) base += wtot[w2];
+            gcnt[tid] = tot;
+            lbase[tid] = base;
+            u32 cwv[NWAVE];
+#pragma unroll
+            for (int wv = 0; wv < NWAVE; wv++) cwv[wv] = wst[wv][tid];
+#pragma unroll
+            for (int wv = 0; wv < NWAVE; wv++) {
+                wst[wv][tid] = base;
+                base += cwv[wv];
+            }
+        }
+        __syncthreads();
+        // sweep 2: the tile's deltas, group by group, as a bit stream (all slots are zero again)
+#pragma unroll
+        for (u32 r = 0; r < 16u; r++) {
+            const u32 v = reg[r];
+            if (v >> 31) {
+                const u32 sp = v & 511u, dv = (v >> 19) & 511u;
+                const u32 L = wst[wave][sp] + ((v >> 9) & 1023u);
+                if (dv) {
+                    const u32 bo = L * wB;
+                    const u32 word = bo >> 6, sh = bo & 63u;
+                    atomicOr(&bits[word], (unsigned long long)dv << sh);
+                    if (sh + wB > 64u) atomicOr(&bits[word + 1u], (unsigned long long)dv >> (64u - sh));
+                }
+                if (PERM) si[L] = (u16)(wave * 1024u + r * 64u + lane);
+            }
+        }
+        __syncthreads();
+        // copy each group's run to its place in the output stream: short runs one thread each,
+        // long runs one wave each
+        if (tid < S) {
+            const u32 c = gcnt[tid];
+            if (c) {
+                const u64 fb = (u64)gb[tid] * wB;
+                const u32 s0 = (u32)(fb & 63u), nbits = c * wB;
+                const u32 nW = (s0 + nbits + 63u) >> 6;
+                if (nW <= SHORT_RUN) {
+                    const int src0 = (int)(lbase[tid] * wB);
+                    for (u32 j = 0; j < nW; j++) emit_word(bits, out, j, s0, fb >> 6, nbits, src0);
+                    if (PERM)
+                        for (u32 i = 0; i < c; i++)
+                            gptr(d.perm)[gb[tid] + i] = (u32)(e0 + si[lbase[tid] + i]);
+                }
+            }
+        }
+        for (u32 g = wave; g < S; g += NWAVE) {
+            const u32 c = gcnt[g];
+            if (c == 0u) continue;
+            const u64 fb = (u64)gb[g] * wB;
+            const u32 s0 = (u32)(fb & 63u), nbits = c * wB;
+            const u32 nW = (s0 + nbits + 63u) >> 6;
+            if (nW <= SHORT_RUN) continue;
+            const int src0 = (int)(lbase[g] * wB);
+            for (u32 j = lane; j < nW; j += 64u) emit_word(bits, out, j, s0, fb >> 6, nbits, src0);
+            if (PERM)
+                for (u32 i = lane; i < c; i += 64u)
+                    gptr(d.perm)[gb[g] + i] = (u32)(e0 + si[lbase[g] + i]);
         }
     }
 }
 
 // regrouping given: e[r] = d[perm[r]] by gathering
-__global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd, int nT)
+__global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
+                                                   const u32 *__restrict__ chunk_tensor)
 {
     __shared__ unsigned long long pk[256 * 9];
-    const u64 tile = blockIdx.x;
-    const int t = find_dtensor(dd, nT, tile);
-    const DDesc d = dd[t];
+    const u64 chunk = blockIdx.x;
+    const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
     if (!d.prev_perm) return;
     const u32 tid = threadIdx.x;
-    const u64 r0 = (tile - d.dtile0) * (u64)DTILE;
-    const u64 rem = d.n - r0;
-    const u32 cnt = rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     const u32 wB = d.wB, Bm = d.B;
-    for (u32 k = tid; k < 256u * wB; k += BLOCK) pk[k] = 0ull;
-    __syncthreads();
-    for (u32 j = 0; j < 16u; j++) {
-        const u32 l = tid + j * BLOCK;
-        if (l >= cnt) break;
-        const u64 i = d.prev_perm[r0 + l];
-        u32 sym[2];
-        for (int which = 0; which < 2; which++) {
-            const unsigned long long *src = which ? d.cur : d.prev;
-            const u32 w = which ? d.wc : d.wp;
-            const u64 off = i * w;
-            const u64 wd = off >> 6;
-            const u32 sh = (u32)(off & 63u);
-            unsigned long long x = src[wd] >> sh;
-            if (sh + w > 64u) x |= src[wd + 1] << (64u - sh);
-            sym[which] = (u32)x & ((1u << w) - 1u);
+    const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
+    const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
+    for (u64 r0 = c0; r0 < c1; r0 += HTILE) {
+        const u32 cnt = (c1 - r0 < (u64)HTILE) ? (u32)(c1 - r0) : (u32)HTILE;
+        __syncthreads();
+        for (u32 k = tid; k < 256u * wB; k += BLOCK) pk[k] = 0ull;
+        __syncthreads();
+        for (u32 j = 0; j < 16u; j++) {
+            const u32 l = tid + j * BLOCK;
+            if (l >= cnt) break;
+            const u64 i = gptr(d.prev_perm)[r0 + l];
+            u32 sym[2];
+            for (int which = 0; which < 2; which++) {
+                const GLOBAL_AS unsigned long long *src = which ? gptr(d.cur) : gptr(d.prev);
+                const u32 w = which ? d.wc : d.wp;
+                const u64 off = i * w;
+                const u64 wd = off >> 6;
+                const u32 sh = (u32)(off & 63u);
+                unsigned long long x = src[wd] >> sh;
+                if (sh + w > 64u) x |= src[wd + 1] << (64u - sh);
+                sym[which] = (u32)x & ((1u << w) - 1u);
+            }
+            u32 dv = sym[0] + Bm - sym[1];
+            if (dv >= Bm) dv -= Bm;
+            const u32 bitoff = l * wB;
+            const u32 word = bitoff >> 6, shf = bitoff & 63u;
+            if (dv) {
+                atomicOr(&pk[word], (unsigned long long)dv << shf);
+                if (shf + wB > 64u) atomicOr(&pk[word + 1u], (unsigned long long)dv >> (64u - shf));
+            }
         }
-        u32 dv = sym[0] + Bm - sym[1];
-        if (dv >= Bm) dv -= Bm;
-        const u32 bitoff = l * wB;
-        const u32 word = bitoff >> 6, shf = bitoff & 63u;
-        if (dv) {
-            atomicOr(&pk[word], (unsigned long long)dv << shf);
-            if (shf + wB > 64u) atomicOr(&pk[word + 1u], (unsigned long long)dv >> (64u - shf));
-        }
+        __syncthreads();
+        const u32 n_words = (cnt * wB + 63u) >> 6;
+        GLOBAL_AS unsigned long long *dst = gptr(d.out) + r0 * wB / 64u;
+        for (u32 k = tid; k < n_words; k += BLOCK) dst[k] = pk[k];
     }
-    __syncthreads();
-    const u32 n_words = (cnt * wB + 63u) >> 6;
-    unsigned long long *dst = d.out + r0 * wB / 64u;
-    for (u32 k = tid; k < n_words; k += BLOCK) dst[k] = pk[k];
 }
 
-__global__ void k_dzero(const DDesc *__restrict__ dd, int nT)
+// clears the packed outputs that k_dscatter ORs into
+__global__ __launch_bounds__(256) void k_dzero(const DDesc *__restrict__ dd,
+                                               const u32 *__restrict__ chunk_tensor)
 {
-    // clears the packed outputs that k_dscatter ORs into (one block row per tensor)
-    const int t = blockIdx.y;
-    const DDesc d = dd[t];
+    const u64 chunk = blockIdx.x;
+    const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
     if (d.prev_perm) return;
-    for (u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x; k < d.out_words;
-         k += (u64)gridDim.x * blockDim.x)
-        d.out[k] = 0ull;
+    // this chunk's share of the output words (by position, not by content)
+    const u64 per = (d.out_words + d.n_chunks - 1) / d.n_chunks;
+    const u64 k0 = (chunk - d.chunk0) * per;
+    const u64 k1 = (k0 + per < d.out_words) ? k0 + per : d.out_words;
+    for (u64 k = k0 + threadIdx.x; k < k1; k += blockDim.x) gptr(d.out)[k] = 0ull;
+}
+
+// 1 if same-address LDS atomics with return are served in ascending lane order, for every pattern
+// tried: all lanes on one address, few addresses, many addresses, with inactive lanes
+__global__ __launch_bounds__(256) void k_lds_order_check(u32 *__restrict__ violations)
+{
+    __shared__ u32 cnt[4][SS];
+    const u32 lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    for (u32 i = threadIdx.x; i < 4 * SS; i += 256) (&cnt[0][0])[i] = 0u;
+    __syncthreads();
+    u32 bad = 0;
+    const u32 mods[6] = {1u, 2u, 5u, 18u, 66u, 258u};
+    for (u32 t = 0; t < 600u; t++) {
+        u32 x = lane * 7919u + t * 104729u + blockIdx.x * 31u + wave * 977u;
+        x ^= x >> 16;
+        x *= 0x7feb352du;
+        x ^= x >> 15;
+        x *= 0x846ca68bu;
+        x ^= x >> 16;
+        const u32 sym = x % mods[t % 6u];
+        const bool active = ((x >> 20) & 7u) != 0u;
+        const u32 before = cnt[wave][sym];
+        u32 got = 0;
+        if (active) got = atomicAdd(&cnt[wave][sym], 1u);
+        u64 peers = __ballot(active);
+        for (int b = 0; b < 9; b++) {
+            const bool bit = (sym >> b) & 1u;
+            const u64 m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const u32 rank = __popcll(peers & ((1ull << lane) - 1ull));
+        if (active && got != before + rank) bad++;
+    }
+    if (bad) atomicAdd(violations, bad);
+}
+
+hipError_t launch_lds_order_check(u32 *violations, hipStream_t s)
+{
+    k_lds_order_check<<<64, 256, 0, s>>>(violations);
+    return hipGetLastError();
 }
 
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
-                        const u64 *chunk_tile0, u16 *tile_hist, u32 *chunk_tot, bool any_scatter,
-                        bool any_gather, hipStream_t s)
+                        const u32 *chunk_tensor, u32 *chunk_tot, bool any_scatter, bool any_perm,
+                        bool any_gather, bool lds_ordered, hipStream_t s)
 {
-    PROF("k_dhist", s, k_dhist<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist));
-    PROF("k_dchunk", s, k_dchunk<<<(unsigned)n_chunks, SS, 0, s>>>(dd, nT, chunk_tile0, tile_hist, chunk_tot));
+    PROF("k_dhist", s, k_dhist<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
     PROF("k_dgroups", s, k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot));
+    if (any_scatter || any_perm)
+        PROF("k_dzero", s, k_dzero<<<(unsigned)n_chunks, 256, 0, s>>>(dd, chunk_tensor));
     if (any_scatter) {
-        PROF("k_dzero", s, k_dzero<<<dim3(64, nT), 256, 0, s>>>(dd, nT));
-        PROF("k_dscatter", s, k_dscatter<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT, tile_hist, chunk_tot));
+        if (lds_ordered)
+            PROF("k_dscatter", s, k_dscatter<false, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+        else
+            PROF("k_dscatter_slots", s, k_dscatter<false, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
     }
-    if (any_gather) PROF("k_dgather", s, k_dgather<<<(unsigned)n_dtiles, BLOCK, 0, s>>>(dd, nT));
+    if (any_perm) {
+        if (lds_ordered)
+            PROF("k_dscatter_perm", s, k_dscatter<true, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+        else
+            PROF("k_dscatter_perm_slots", s, k_dscatter<true, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+    }
+    if (any_gather) PROF("k_dgather", s, k_dgather<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor));
     return hipGetLastError();
 }
 

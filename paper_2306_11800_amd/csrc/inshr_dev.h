@@ -8,7 +8,18 @@ typedef uint32_t u32;
 typedef uint64_t u64;
 typedef uint16_t u16;
 
+// Pointers that reach a kernel through a descriptor in memory are generic to the compiler and
+// would be accessed with FLAT instructions, whose completion is tracked together with LDS traffic;
+// every such pointer is device memory, so it is cast to the global address space before use.
+#define GLOBAL_AS __attribute__((address_space(1)))
+
 namespace inshr {
+
+template <class T>
+__device__ __forceinline__ GLOBAL_AS T *gptr(T *p)
+{
+    return (GLOBAL_AS T *)p;
+}
 
 // ------------------------------------------------------------------------------------------
 // sizes

@@ -74,7 +74,7 @@ struct DDesc { // one tensor of a delta call
     u64 dtile0, chunk0, n_chunks;
     u32 wp, wc, Kp, B, wB, pad;
 };
-constexpr int DELTA_TILE = 16384;
+constexpr int DELTA_TILE = 12288;
 constexpr int DELTA_CHUNK = 64;
 constexpr int DELTA_SS = 264;
 
@@ -92,8 +92,9 @@ hipError_t launch_select(const Batch &bt, hipStream_t s);
 hipError_t launch_score(const Batch &bt, hipStream_t s);
 hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStream_t s);
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
-                        const u64 *chunk_tile0, u16 *tile_hist, u32 *chunk_tot, bool any_scatter,
-                        bool any_gather, hipStream_t s);
+                        const u32 *chunk_tensor, u32 *chunk_tot, bool any_scatter, bool any_perm,
+                        bool any_gather, bool lds_ordered, hipStream_t s);
+hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
 // tile iteration shared by the streaming kernels
@@ -114,13 +115,14 @@ __device__ __forceinline__ int find_tensor(const TDesc *td, int nT, u64 tile)
 // v[4*j + c] = element 4*(tid + 1024*j) + c of the tile; returns the mask of valid entries
 __device__ __forceinline__ u32 load_tile(const TDesc &d, u64 e0, u32 cnt, float (&v)[16])
 {
-    const float *p = d.data + e0;
+    const GLOBAL_AS float *p = gptr(d.data) + e0;
     const u32 tid = threadIdx.x;
     if (cnt == (u32)TILE && d.aligned16) {
-        const float4 *p4 = reinterpret_cast<const float4 *>(p);
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const GLOBAL_AS f4 *p4 = (const GLOBAL_AS f4 *)p;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            float4 q = p4[tid + 1024u * j];
+            const f4 q = p4[tid + 1024u * j];
             v[4 * j + 0] = q.x;
             v[4 * j + 1] = q.y;
             v[4 * j + 2] = q.z;

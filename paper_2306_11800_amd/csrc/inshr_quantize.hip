@@ -42,9 +42,9 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
     const u32 sh = 8u - bits;
     if (q.boundaries)
         for (u32 j = 1 + tid; j < K; j += BLOCK)
-            q.boundaries[j - 1] = __uint_as_float(bits_of_key(tk[(j << sh) - 1u]));
+            gptr(q.boundaries)[j - 1] = __uint_as_float(bits_of_key(tk[(j << sh) - 1u]));
     const float *cb = B.codebook + ((size_t)t * gd->n_cfg + g) * CB_STRIDE;
-    for (u32 k = tid; k < K; k += BLOCK) q.codebook[k] = cb[k];
+    for (u32 k = tid; k < K; k += BLOCK) gptr(q.codebook)[k] = cb[k];
     if (tid == 0) {
         QInfo r;
         r.n_pruned = st->pair_Pn[pair] + st->pair_Pp[pair];
@@ -174,8 +174,8 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                         if ((omask >> i) & 1u) {
                             const u64 pos = obase + r;
                             if (pos < q.out_cap) {
-                                q.out_idx[pos] = (u32)(e0 + 4u * (tid + 1024u * j) + c);
-                                q.out_val[pos] = v[i];
+                                gptr(q.out_idx)[pos] = (u32)(e0 + 4u * (tid + 1024u * j) + c);
+                                gptr(q.out_val)[pos] = v[i];
                             }
                             r++;
                         }
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                 }
             }
             __syncthreads();
-            unsigned long long *dst = q.packed + (tile - d.tile0) * (u64)(256u * w);
+            GLOBAL_AS unsigned long long *dst = gptr(q.packed) + (tile - d.tile0) * (u64)(256u * w);
             for (u32 k = tid; k < n_words; k += BLOCK) dst[k] = pk[k];
             __syncthreads();
         }
