@@ -63,11 +63,11 @@ __host__ __device__ __forceinline__ bool key_is_neg(u32 k) { return (k & 0x80000
 __host__ __device__ __forceinline__ u32 key_pos(u32 m) { return 0x80000000u + m; }
 __host__ __device__ __forceinline__ u32 key_neg(u32 m) { return 0x7fffffffu - m; }
 
-// second-level bin of a key: table entry = base << 5 | depth
+// second-level bin of a key: table entry = flag << 31 | base << 5 | depth
 __host__ __device__ __forceinline__ u32 l2_bin(u32 key, u32 entry)
 {
     u32 d = entry & 31u;
-    return (entry >> 5) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
+    return ((entry & 0x7fffffffu) >> 5) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
 }
 
 // ------------------------------------------------------------------------------------------

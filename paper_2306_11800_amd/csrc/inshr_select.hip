@@ -21,24 +21,50 @@ namespace inshr {
 // ------------------------------------------------------------------------------------------
 // sweeps 1 and 2: histograms
 // ------------------------------------------------------------------------------------------
+constexpr int STAGE_CAP = 128; // gathered keys a wave holds back before it reserves space for them
+
+// A wave writes its staged keys to their buckets: one reservation per bucket present.
+__device__ __forceinline__ void flush_stage(const u32 *skey, const unsigned char *sq, u32 n, u32 nb,
+                                            const u64 *boff, u32 *cursor, u32 *pool)
+{
+    const u32 lane = threadIdx.x & 63u;
+    for (u32 base = 0; base < n; base += 64u) {
+        const u32 i = base + lane;
+        const bool have = i < n;
+        const u32 key = have ? skey[i] : 0u;
+        const u32 q = have ? sq[i] : 0xFFu;
+        for (u32 b = 0; b < nb; b++) {
+            const u64 m = __ballot(have && q == b);
+            if (m == 0ull) continue;
+            u32 start = 0;
+            if (lane == (u32)__ffsll((unsigned long long)m) - 1u) start = atomicAdd(&cursor[b], (u32)__popcll(m));
+            start = __shfl(start, __ffsll((unsigned long long)m) - 1);
+            if (have && q == b) pool[boff[b] + start + __popcll(m & ((1ull << lane) - 1ull))] = key;
+        }
+    }
+}
+
 template <int LEVEL>
 __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, int nT,
                                                 const u64 *__restrict__ wg_tile0, Bufs B)
 {
     extern __shared__ u32 smem[];
-    u32 *h = smem;           // 32768 counters
-    u32 *T = smem + L2_BINS; // LEVEL 2: 4096 table entries
-    u32 *bm = T + COARSE;    // LEVEL 2: 512-word bitmap of bucket magnitude bins
+    u32 *h = smem;                 // 32768 counters
+    u32 *T = smem + L2_BINS;       // LEVEL 2: 4096 table entries (bit 31: prefix holds a bucket)
+    u32 *skey = T + COARSE;        // LEVEL 2: [16][STAGE_CAP] staged keys per wave
+    unsigned char *sq = reinterpret_cast<unsigned char *>(skey + (BLOCK / 64) * STAGE_CAP);
     __shared__ u32 s_bmag[MAX_THR];
     __shared__ u64 s_boff[MAX_THR];
     __shared__ u32 s_nb;
 
-    const u32 tid = threadIdx.x;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     for (int i = tid; i < L2_BINS; i += BLOCK) h[i] = 0u;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     int t = find_tensor(td, nT, tile_lo);
     u64 tile = tile_lo;
+    u32 *wkey = skey + wave * STAGE_CAP;
+    unsigned char *wq = sq + wave * STAGE_CAP;
     while (tile < tile_hi) {
         const TDesc d = td[t];
         const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
@@ -47,7 +73,6 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         TState *st = B.ts + t;
         if (LEVEL == 2) {
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
-            for (int i = tid; i < 512; i += BLOCK) bm[i] = B.bitmap[(size_t)t * 512 + i];
             if (tid < MAX_THR) {
                 s_bmag[tid] = st->bucket_magbin[tid];
                 s_boff[tid] = d.pool_thr + st->bucket_off[tid];
@@ -56,6 +81,7 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         }
         __syncthreads();
         u32 c_neg = 0u, c_zero = 0u, c_bad = 0u;
+        u32 n_staged = 0u; // wave-uniform
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
@@ -64,29 +90,44 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             const u32 mask = load_tile(d, e0, cnt, v);
 #pragma unroll
             for (int i = 0; i < 16; i++) {
-                if (!((mask >> i) & 1u)) continue;
+                const bool valid = (mask >> i) & 1u;
                 const u32 b = canon_bits(__float_as_uint(v[i]));
                 const u32 key = key_of_bits(b);
                 if (LEVEL == 1) {
-                    c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
-                    c_neg += (b >> 31);
-                    c_zero += (b == 0u) ? 1u : 0u;
-                    atomicAdd(&h[key >> L1_SHIFT], 1u);
+                    if (valid) {
+                        c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
+                        c_neg += (b >> 31);
+                        c_zero += (b == 0u) ? 1u : 0u;
+                        atomicAdd(&h[key >> L1_SHIFT], 1u);
+                    }
                 } else {
-                    atomicAdd(&h[l2_bin(key, T[key >> COARSE_SHIFT])], 1u);
-                    const u32 m17 = (b & 0x7fffffffu) >> L1_SHIFT;
-                    if (((bm[m17 >> 5] >> (m17 & 31u)) & 1u) && b != 0u) {
+                    const u32 entry = T[key >> COARSE_SHIFT];
+                    if (valid) atomicAdd(&h[l2_bin(key, entry)], 1u);
+                    // elements of a threshold's first-level magnitude bin are gathered
+                    u32 q = 0xFFu;
+                    if (valid && (entry >> 31) && b != 0u) {
+                        const u32 m17 = (b & 0x7fffffffu) >> L1_SHIFT;
                         const u32 nb = s_nb;
-                        for (u32 q = 0; q < nb; q++) {
-                            if (s_bmag[q] == m17) {
-                                u32 pos = atomicAdd(&st->bucket_cursor[q], 1u);
-                                B.pool[s_boff[q] + pos] = key;
-                            }
+                        for (u32 k = 0; k < nb; k++)
+                            if (s_bmag[k] == m17) q = k;
+                    }
+                    const u64 cm = __ballot(q != 0xFFu);
+                    if (cm) {
+                        if (q != 0xFFu) {
+                            const u32 pos = n_staged + __popcll(cm & ((1ull << lane) - 1ull));
+                            wkey[pos] = key;
+                            wq[pos] = (unsigned char)q;
+                        }
+                        n_staged += (u32)__popcll(cm);
+                        if (n_staged >= 64u) {
+                            flush_stage(wkey, wq, n_staged, s_nb, s_boff, st->bucket_cursor, B.pool);
+                            n_staged = 0u;
                         }
                     }
                 }
             }
         }
+        if (LEVEL == 2 && n_staged) flush_stage(wkey, wq, n_staged, s_nb, s_boff, st->bucket_cursor, B.pool);
         __syncthreads();
         // flush this tensor's counts
         u32 *gh = (LEVEL == 1 ? B.hist1 : B.hist2) + (size_t)t * L2_BINS;
@@ -200,10 +241,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
         }
         st->n_buckets = nb;
     }
-    u32 *bmp = B.bitmap + (size_t)t * 512;
-    for (int i = tid; i < 512; i += BLOCK) bmp[i] = 0u;
     __syncthreads();
-    if (tid < n_thr) atomicOr(&bmp[s_j[tid] >> 5], 1u << (s_j[tid] & 31u));
 
     // second-level table: smallest target population whose bin total fits
     u64 lo = 1, hi = n;
@@ -230,7 +268,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     u32 *tab = B.table2 + (size_t)t * COARSE;
     for (int c = tid; c < COARSE; c += BLOCK) {
         u32 d = nc[c] ? depth_for(nc[c], lo) : 0u;
-        tab[c] = (Bn[c] << 5) | d;
+        // bit 31: this 12-bit key prefix contains the first-level magnitude bin of a threshold
+        u32 flag = 0u;
+        for (u32 q = 0; q < n_thr; q++) {
+            const u32 j3 = s_j[q] >> 3;
+            if ((u32)c == 0x800u + j3 || (u32)c == 0x7FFu - j3) flag = 0x80000000u;
+        }
+        tab[c] = flag | (Bn[c] << 5) | d;
     }
     if (tid == 0) {
         st->nb2 = nb2;
@@ -240,52 +284,112 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
 }
 
 // ------------------------------------------------------------------------------------------
-// exact thresholds from the gathered buckets (one wavefront per threshold)
+// exact thresholds from the gathered buckets (one workgroup per threshold)
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_thr_select(const TDesc *__restrict__ td, Bufs B)
+constexpr int TSEL = 256;
+
+// k-th smallest magnitude of list[0..c); all magnitudes share their bits above bit 16.
+// Two counting rounds over 9 and 8 bits with an LDS histogram.
+__device__ inline u32 block_select_mag(const u32 *list, u32 c, u32 k, u32 *hist /*[512]*/, u32 *sh)
 {
+    const u32 tid = threadIdx.x;
+    u32 prefix = 0u; // chosen bits so far (of the low 17)
+    for (int round = 0; round < 2; round++) {
+        const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
+        for (u32 i = tid; i < 512u; i += TSEL) hist[i] = 0u;
+        __syncthreads();
+        for (u32 i = tid; i < c; i += TSEL) {
+            const u32 m = mag_of_key(list[i]) & 0x1FFFFu;
+            if (round == 0 || (m >> 8) == prefix) atomicAdd(&hist[(m >> shift) & (nbin - 1u)], 1u);
+        }
+        __syncthreads();
+        if (tid < 64u) { // 8 bins per lane
+            u32 loc[8], s = 0;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                loc[j] = hist[tid * 8u + j];
+                s += loc[j];
+            }
+            u32 inc = s;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                u32 v = __shfl_up(inc, o);
+                if ((int)tid >= o) inc += v;
+            }
+            u32 run = inc - s;
+            if (k >= run && k < inc) {
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    if (k >= run && k < run + loc[j]) {
+                        sh[0] = tid * 8u + j;
+                        sh[1] = k - run;
+                    }
+                    run += loc[j];
+                }
+            }
+        }
+        __syncthreads();
+        prefix = (round == 0) ? sh[0] : ((prefix << 8) | sh[0]);
+        k = sh[1];
+        __syncthreads();
+    }
+    return prefix; // low 17 bits of the answer
+}
+
+__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td, Bufs B)
+{
+    __shared__ u32 hist[512];
+    __shared__ u32 sh[2];
+    __shared__ u32 red[4][TSEL / 64];
     const int t = blockIdx.x / MAX_THR;
     const u32 q = blockIdx.x % MAX_THR;
     TState *st = B.ts + t;
     if (q >= st->n_thr) return;
-    const u32 lane = threadIdx.x;
+    const u32 tid = threadIdx.x;
     const u32 bq = st->thr_bucket[q];
     const u32 mb = st->bucket_magbin[bq];
     const u32 *list = B.pool + td[t].pool_thr + st->bucket_off[bq];
     const u32 c = st->bucket_cursor[bq];
     const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
     const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
-    if (lane == 0 && (u64)c != expect) atomicOr(&st->internal_err, 4u);
+    if (tid == 0 && (u64)c != expect) atomicOr(&st->internal_err, 4u);
     const u64 res = st->thr_res[q];
     u32 tau = 0u;
     if (res >= zeros) {
         if (res - zeros >= (u64)c) {
-            if (lane == 0) atomicOr(&st->internal_err, 8u);
+            if (tid == 0) atomicOr(&st->internal_err, 8u);
             return;
         }
-        tau = wave_select(list, c, (u32)(res - zeros), true);
+        tau = (mb << L1_SHIFT) | block_select_mag(list, c, (u32)(res - zeros), hist, sh);
     }
-    u32 ln = 0, lp = 0, gn = 0, gp = 0;
-    for (u32 i = lane; i < c; i += 64u) {
+    u32 cn[4] = {0, 0, 0, 0};
+    for (u32 i = tid; i < c; i += TSEL) {
         u32 k = list[i];
         u32 m = mag_of_key(k);
         bool neg = key_is_neg(k);
-        ln += (m < tau && neg) ? 1u : 0u;
-        lp += (m < tau && !neg) ? 1u : 0u;
-        gn += (m > tau && neg) ? 1u : 0u;
-        gp += (m > tau && !neg) ? 1u : 0u;
+        cn[0] += (m < tau && neg) ? 1u : 0u;
+        cn[1] += (m < tau && !neg) ? 1u : 0u;
+        cn[2] += (m > tau && neg) ? 1u : 0u;
+        cn[3] += (m > tau && !neg) ? 1u : 0u;
     }
-    ln = wave_sum(ln);
-    lp = wave_sum(lp);
-    gn = wave_sum(gn);
-    gp = wave_sum(gp);
-    if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        u32 x = wave_sum(cn[j]);
+        if ((tid & 63u) == 0u) red[j][tid >> 6] = x;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 s4[4];
+        for (int j = 0; j < 4; j++) {
+            s4[j] = 0;
+            for (int w = 0; w < TSEL / 64; w++) s4[j] += red[j][w];
+        }
         const u64 n = td[t].n, n_neg = st->n_neg, n_pos = n - n_neg;
         st->thr_mag[q] = tau;
-        st->thr_lt_neg[q] = st->bucket_below_neg[bq] + ln;
-        st->thr_lt_pos[q] = st->bucket_below_pos[bq] + lp + ((mb == 0u && tau > 0u) ? zeros : 0ull);
-        st->thr_gt_neg[q] = n_neg - st->bucket_below_neg[bq] - st->bucket_cnt_neg[bq] + gn;
-        st->thr_gt_pos[q] = n_pos - st->bucket_below_pos[bq] - st->bucket_cnt_pos[bq] + gp;
+        st->thr_lt_neg[q] = st->bucket_below_neg[bq] + s4[0];
+        st->thr_lt_pos[q] = st->bucket_below_pos[bq] + s4[1] + ((mb == 0u && tau > 0u) ? zeros : 0ull);
+        st->thr_gt_neg[q] = n_neg - st->bucket_below_neg[bq] - st->bucket_cnt_neg[bq] + s4[2];
+        st->thr_gt_pos[q] = n_pos - st->bucket_below_pos[bq] - st->bucket_cnt_pos[bq] + s4[3];
     }
 }
 
@@ -516,7 +620,7 @@ __global__ __launch_bounds__(256) void k_bnd_select(const TDesc *__restrict__ td
 // launch wrappers
 // ------------------------------------------------------------------------------------------
 constexpr int SM_HIST1 = L2_BINS * 4;
-constexpr int SM_HIST2 = (L2_BINS + COARSE + 512) * 4;
+constexpr int SM_HIST2 = (L2_BINS + COARSE + (BLOCK / 64) * STAGE_CAP) * 4 + (BLOCK / 64) * STAGE_CAP;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_GATHER = (L2_BINS + COARSE) * 4;
@@ -543,7 +647,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
     PROF("k_plan1", s, k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
     PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
-    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, 64, 0, s>>>(bt.td, B));
+    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     const u32 TG = bt.n_pairs * NB8;
