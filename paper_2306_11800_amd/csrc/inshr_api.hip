@@ -263,7 +263,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_h2 = cv.take((size_t)nT * L2_BINS * 4);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
-        const size_t o_bmp = cv.take((size_t)nT * 512 * 4);
+        const size_t o_us = cv.take((size_t)units * 8);
+        const size_t o_ut = cv.take((size_t)units * 4);
         const size_t o_bi = cv.take((size_t)nT * L2_BINS * 4);
         const size_t o_cur = cv.take((size_t)nT * CURSOR_STRIDE * 4);
         const size_t o_tb = cv.take((size_t)nT * TGT_STRIDE * 4);
@@ -320,7 +321,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.hist1 = (u32 *)(db + o_h1);
         B.hist2 = (u32 *)(db + o_h2);
         B.table2 = (u32 *)(db + o_tab);
-        B.bitmap = (u32 *)(db + o_bmp);
+        B.unit_start = (u64 *)(db + o_us);
+        B.unit_thr = (u32 *)(db + o_ut);
         B.binfo = (u32 *)(db + o_bi);
         B.cursor2 = (u32 *)(db + o_cur);
         B.tgt_bin = (u32 *)(db + o_tb);

@@ -63,11 +63,16 @@ __host__ __device__ __forceinline__ bool key_is_neg(u32 k) { return (k & 0x80000
 __host__ __device__ __forceinline__ u32 key_pos(u32 m) { return 0x80000000u + m; }
 __host__ __device__ __forceinline__ u32 key_neg(u32 m) { return 0x7fffffffu - m; }
 
-// second-level bin of a key: table entry = flag << 31 | base << 5 | depth
+// second-level bin of a key: table entry = bucket mask << 20 | base << 5 | depth.  Bit 20 + s of
+// the entry says that first-level bin s of the 8 under this 12-bit key prefix holds a threshold.
 __host__ __device__ __forceinline__ u32 l2_bin(u32 key, u32 entry)
 {
     u32 d = entry & 31u;
-    return ((entry & 0x7fffffffu) >> 5) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
+    return ((entry >> 5) & 0x7fffu) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
+}
+__host__ __device__ __forceinline__ bool in_threshold_bucket(u32 key, u32 entry)
+{
+    return (entry >> (20u + ((key >> L1_SHIFT) & 7u))) & 1u;
 }
 
 // ------------------------------------------------------------------------------------------

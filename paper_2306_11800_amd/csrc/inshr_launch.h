@@ -13,7 +13,8 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     TState *ts;
     u32 *hist1;     // [nT][32768]
     u32 *table2;    // [nT][4096]
-    u32 *bitmap;    // [nT][512]
+    u64 *unit_start; // [units] first element of each (workgroup, tensor) unit inside its tensor
+    u32 *unit_thr;   // [units] threshold-bucket keys the unit gathered
     u32 *hist2;     // [nT][32768]
     u32 *binfo;     // [nT][32768] offset of an active bin's elements in the gather pool, or INACTIVE
     u32 *cursor2;   // [nT][CURSOR_STRIDE]

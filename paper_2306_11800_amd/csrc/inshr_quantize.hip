@@ -65,6 +65,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                                                  const QDesc *__restrict__ qd_by_tensor, Bufs B)
 {
     __shared__ u32 bnd[256];
+    __shared__ u16 ctab[COARSE]; // per 12-bit key prefix: boundaries below it | boundaries up to its end << 8
     __shared__ unsigned long long pk[256 * 9];
     __shared__ u32 wtot[4][BLOCK / 64];
     __shared__ u32 wbase[4][BLOCK / 64];
@@ -94,6 +95,16 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         __syncthreads();
         if (tid < 256u) bnd[tid] = (tid + 1u < K) ? tk[((tid + 1u) << sh) - 1u] : 0xFFFFFFFFu;
         __syncthreads();
+        for (u32 c = tid; c < (u32)COARSE; c += BLOCK) {
+            const u32 first = c << COARSE_SHIFT, last = first | ((1u << COARSE_SHIFT) - 1u);
+            u32 lo = 0u, hi = 0u; // lo = #{t < first}, hi = #{t <= last}
+            for (u32 step = K >> 1; step > 0u; step >>= 1) {
+                if (bnd[lo + step - 1u] < first) lo += step;
+                if (bnd[hi + step - 1u] <= last) hi += step;
+            }
+            ctab[c] = (u16)(lo | (hi << 8));
+        }
+        __syncthreads();
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
@@ -122,9 +133,15 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                             omask |= 1u << i;
                         } else {
                             const u32 key = key_of_bits(b);
-                            u32 lo = 0u;
-                            for (u32 step = K >> 1; step > 0u; step >>= 1)
-                                if (bnd[lo + step - 1u] <= key) lo += step;
+                            const u32 e = ctab[key >> COARSE_SHIFT];
+                            u32 lo = e & 255u, hi = e >> 8;
+                            while (lo < hi) { // bin = #{t <= key}, known to lie in [lo, hi]
+                                const u32 mid = (lo + hi) >> 1;
+                                if (bnd[mid] <= key)
+                                    lo = mid + 1u;
+                                else
+                                    hi = mid;
+                            }
                             s = 2u + lo;
                         }
                     }

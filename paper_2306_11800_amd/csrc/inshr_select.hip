@@ -21,67 +21,40 @@ namespace inshr {
 // ------------------------------------------------------------------------------------------
 // sweeps 1 and 2: histograms
 // ------------------------------------------------------------------------------------------
-constexpr int STAGE_CAP = 128; // gathered keys a wave holds back before it reserves space for them
-
-// A wave writes its staged keys to their buckets: one reservation per bucket present.
-__device__ __forceinline__ void flush_stage(const u32 *skey, const unsigned char *sq, u32 n, u32 nb,
-                                            const u64 *boff, u32 *cursor, u32 *pool)
-{
-    const u32 lane = threadIdx.x & 63u;
-    for (u32 base = 0; base < n; base += 64u) {
-        const u32 i = base + lane;
-        const bool have = i < n;
-        const u32 key = have ? skey[i] : 0u;
-        const u32 q = have ? sq[i] : 0xFFu;
-        for (u32 b = 0; b < nb; b++) {
-            const u64 m = __ballot(have && q == b);
-            if (m == 0ull) continue;
-            u32 start = 0;
-            if (lane == (u32)__ffsll((unsigned long long)m) - 1u) start = atomicAdd(&cursor[b], (u32)__popcll(m));
-            start = __shfl(start, __ffsll((unsigned long long)m) - 1);
-            if (have && q == b) pool[boff[b] + start + __popcll(m & ((1ull << lane) - 1ull))] = key;
-        }
-    }
-}
-
 template <int LEVEL>
 __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, int nT,
-                                                const u64 *__restrict__ wg_tile0, Bufs B)
+                                                const u64 *__restrict__ wg_tile0,
+                                                const u32 *__restrict__ wg_fu0, Bufs B)
 {
     extern __shared__ u32 smem[];
     u32 *h = smem;                 // 32768 counters
-    u32 *T = smem + L2_BINS;       // LEVEL 2: 4096 table entries (bit 31: prefix holds a bucket)
-    u32 *skey = T + COARSE;        // LEVEL 2: [16][STAGE_CAP] staged keys per wave
-    unsigned char *sq = reinterpret_cast<unsigned char *>(skey + (BLOCK / 64) * STAGE_CAP);
-    __shared__ u32 s_bmag[MAX_THR];
-    __shared__ u64 s_boff[MAX_THR];
-    __shared__ u32 s_nb;
+    u32 *T = smem + L2_BINS;       // LEVEL 2: 4096 table entries
+    __shared__ u32 s_gathered; // LEVEL 2: keys this workgroup has gathered from the current tensor
 
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 tid = threadIdx.x, lane = tid & 63u;
     for (int i = tid; i < L2_BINS; i += BLOCK) h[i] = 0u;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     int t = find_tensor(td, nT, tile_lo);
+    const int t_first = t;
     u64 tile = tile_lo;
-    u32 *wkey = skey + wave * STAGE_CAP;
-    unsigned char *wq = sq + wave * STAGE_CAP;
     while (tile < tile_hi) {
         const TDesc d = td[t];
         const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
         const u64 t_end = d.tile0 + n_tiles_t;
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
+        // Elements of the thresholds' first-level magnitude bins are gathered into a region of the
+        // pool that belongs to this workgroup alone: it starts at the workgroup's first element of
+        // the tensor and cannot outgrow the workgroup's share, so no global counter is needed.
+        const u64 unit_start = (tile - d.tile0) * (u64)TILE;
+        u32 *gdst = B.pool + d.pool_thr + unit_start;
         if (LEVEL == 2) {
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
-            if (tid < MAX_THR) {
-                s_bmag[tid] = st->bucket_magbin[tid];
-                s_boff[tid] = d.pool_thr + st->bucket_off[tid];
-            }
-            if (tid == 0) s_nb = st->n_buckets;
+            if (tid == 0) s_gathered = 0u;
         }
         __syncthreads();
         u32 c_neg = 0u, c_zero = 0u, c_bad = 0u;
-        u32 n_staged = 0u; // wave-uniform
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
@@ -104,30 +77,18 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                     const u32 entry = T[key >> COARSE_SHIFT];
                     if (valid) atomicAdd(&h[l2_bin(key, entry)], 1u);
                     // elements of a threshold's first-level magnitude bin are gathered
-                    u32 q = 0xFFu;
-                    if (valid && (entry >> 31) && b != 0u) {
-                        const u32 m17 = (b & 0x7fffffffu) >> L1_SHIFT;
-                        const u32 nb = s_nb;
-                        for (u32 k = 0; k < nb; k++)
-                            if (s_bmag[k] == m17) q = k;
-                    }
-                    const u64 cm = __ballot(q != 0xFFu);
+                    const bool cand = valid && in_threshold_bucket(key, entry) && b != 0u;
+                    const u64 cm = __ballot(cand);
                     if (cm) {
-                        if (q != 0xFFu) {
-                            const u32 pos = n_staged + __popcll(cm & ((1ull << lane) - 1ull));
-                            wkey[pos] = key;
-                            wq[pos] = (unsigned char)q;
-                        }
-                        n_staged += (u32)__popcll(cm);
-                        if (n_staged >= 64u) {
-                            flush_stage(wkey, wq, n_staged, s_nb, s_boff, st->bucket_cursor, B.pool);
-                            n_staged = 0u;
-                        }
+                        u32 base = 0u;
+                        if (lane == (u32)__ffsll((unsigned long long)cm) - 1u)
+                            base = atomicAdd(&s_gathered, (u32)__popcll(cm));
+                        base = __shfl(base, __ffsll((unsigned long long)cm) - 1);
+                        if (cand) gdst[base + __popcll(cm & ((1ull << lane) - 1ull))] = key;
                     }
                 }
             }
         }
-        if (LEVEL == 2 && n_staged) flush_stage(wkey, wq, n_staged, s_nb, s_boff, st->bucket_cursor, B.pool);
         __syncthreads();
         // flush this tensor's counts
         u32 *gh = (LEVEL == 1 ? B.hist1 : B.hist2) + (size_t)t * L2_BINS;
@@ -137,6 +98,11 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 atomicAdd(&gh[i], c);
                 h[i] = 0u;
             }
+        }
+        if (LEVEL == 2 && tid == 0) {
+            const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
+            B.unit_start[fu] = unit_start;
+            B.unit_thr[fu] = s_gathered;
         }
         if (LEVEL == 1) {
             c_neg = wave_sum(c_neg);
@@ -268,11 +234,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     u32 *tab = B.table2 + (size_t)t * COARSE;
     for (int c = tid; c < COARSE; c += BLOCK) {
         u32 d = nc[c] ? depth_for(nc[c], lo) : 0u;
-        // bit 31: this 12-bit key prefix contains the first-level magnitude bin of a threshold
+        // bits 20..27: which of the 8 first-level bins under this key prefix hold a threshold
+        // (magnitude bin j is first-level key bin 16384 + j for positive, 16383 - j for negative)
         u32 flag = 0u;
         for (u32 q = 0; q < n_thr; q++) {
-            const u32 j3 = s_j[q] >> 3;
-            if ((u32)c == 0x800u + j3 || (u32)c == 0x7FFu - j3) flag = 0x80000000u;
+            const u32 kp = (u32)L1_MAGBINS + s_j[q], kn = (u32)L1_MAGBINS - 1u - s_j[q];
+            if ((kp >> 3) == (u32)c) flag |= 1u << (20u + (kp & 7u));
+            if ((kn >> 3) == (u32)c) flag |= 1u << (20u + (kn & 7u));
         }
         tab[c] = flag | (Bn[c] << 5) | d;
     }
@@ -286,11 +254,23 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 // exact thresholds from the gathered buckets (one workgroup per threshold)
 // ------------------------------------------------------------------------------------------
-constexpr int TSEL = 256;
+constexpr int TSEL = 1024;
 
-// k-th smallest magnitude of list[0..c); all magnitudes share their bits above bit 16.
-// Two counting rounds over 9 and 8 bits with an LDS histogram.
-__device__ inline u32 block_select_mag(const u32 *list, u32 c, u32 k, u32 *hist /*[512]*/, u32 *sh)
+// The gathered keys of a tensor lie in one fragment per (workgroup, tensor) unit, all buckets
+// mixed; a threshold looks at the keys whose magnitude falls in its own bucket.
+struct Fragments {
+    const u32 *pool;      // tensor's gather region
+    const u64 *start;     // per unit: first element of the fragment
+    const u32 *count;     // per unit: keys in the fragment
+    const u32 *ids;       // units of this tensor
+    u32 n_units;
+};
+
+// k-th smallest magnitude among the gathered keys of magnitude bin mb (all share the bits above
+// bit 16).  Two counting rounds over 9 and 8 bits with an LDS histogram.  Returns the low 17 bits;
+// *seen = number of keys of the bin that were found.
+__device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *hist /*[512]*/,
+                                       u32 *sh, u32 *seen)
 {
     const u32 tid = threadIdx.x;
     u32 prefix = 0u; // chosen bits so far (of the low 17)
@@ -298,9 +278,23 @@ __device__ inline u32 block_select_mag(const u32 *list, u32 c, u32 k, u32 *hist 
         const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
         for (u32 i = tid; i < 512u; i += TSEL) hist[i] = 0u;
         __syncthreads();
-        for (u32 i = tid; i < c; i += TSEL) {
-            const u32 m = mag_of_key(list[i]) & 0x1FFFFu;
-            if (round == 0 || (m >> 8) == prefix) atomicAdd(&hist[(m >> shift) & (nbin - 1u)], 1u);
+        for (u32 u = 0; u < f.n_units; u++) {
+            const u32 fu = f.ids[u];
+            const u32 *list = f.pool + f.start[fu];
+            const u32 c = f.count[fu];
+            for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
+                u32 kk[4];
+#pragma unroll
+                for (int j = 0; j < 4; j++) kk[j] = (i0 + j * TSEL < c) ? list[i0 + j * TSEL] : 0u;
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const u32 mag = mag_of_key(kk[j]);
+                    if (i0 + j * TSEL >= c || (mag >> L1_SHIFT) != mb) continue;
+                    const u32 m = mag & 0x1FFFFu;
+                    if (round == 0 || (m >> 8) == prefix)
+                        atomicAdd(&hist[(m >> shift) & (nbin - 1u)], 1u);
+                }
+            }
         }
         __syncthreads();
         if (tid < 64u) { // 8 bins per lane
@@ -317,6 +311,7 @@ __device__ inline u32 block_select_mag(const u32 *list, u32 c, u32 k, u32 *hist 
                 if ((int)tid >= o) inc += v;
             }
             u32 run = inc - s;
+            if (round == 0 && tid == 63u) *seen = inc;
             if (k >= run && k < inc) {
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
@@ -333,13 +328,16 @@ __device__ inline u32 block_select_mag(const u32 *list, u32 c, u32 k, u32 *hist 
         k = sh[1];
         __syncthreads();
     }
-    return prefix; // low 17 bits of the answer
+    return prefix;
 }
 
-__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td, Bufs B)
+__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td,
+                                                     const u32 *__restrict__ t_fu_off,
+                                                     const u32 *__restrict__ t_fu_ids, Bufs B)
 {
     __shared__ u32 hist[512];
     __shared__ u32 sh[2];
+    __shared__ u32 s_seen;
     __shared__ u32 red[4][TSEL / 64];
     const int t = blockIdx.x / MAX_THR;
     const u32 q = blockIdx.x % MAX_THR;
@@ -348,29 +346,45 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
     const u32 tid = threadIdx.x;
     const u32 bq = st->thr_bucket[q];
     const u32 mb = st->bucket_magbin[bq];
-    const u32 *list = B.pool + td[t].pool_thr + st->bucket_off[bq];
-    const u32 c = st->bucket_cursor[bq];
+    Fragments f;
+    f.pool = B.pool + td[t].pool_thr;
+    f.start = B.unit_start;
+    f.count = B.unit_thr;
+    f.ids = t_fu_ids + t_fu_off[t];
+    f.n_units = t_fu_off[t + 1] - t_fu_off[t];
     const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
     const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
-    if (tid == 0 && (u64)c != expect) atomicOr(&st->internal_err, 4u);
     const u64 res = st->thr_res[q];
     u32 tau = 0u;
     if (res >= zeros) {
-        if (res - zeros >= (u64)c) {
+        if (res - zeros >= expect) {
             if (tid == 0) atomicOr(&st->internal_err, 8u);
             return;
         }
-        tau = (mb << L1_SHIFT) | block_select_mag(list, c, (u32)(res - zeros), hist, sh);
+        tau = (mb << L1_SHIFT) | block_select_mag(f, mb, (u32)(res - zeros), hist, sh, &s_seen);
+        if (tid == 0 && (u64)s_seen != expect) atomicOr(&st->internal_err, 4u);
     }
     u32 cn[4] = {0, 0, 0, 0};
-    for (u32 i = tid; i < c; i += TSEL) {
-        u32 k = list[i];
-        u32 m = mag_of_key(k);
-        bool neg = key_is_neg(k);
-        cn[0] += (m < tau && neg) ? 1u : 0u;
-        cn[1] += (m < tau && !neg) ? 1u : 0u;
-        cn[2] += (m > tau && neg) ? 1u : 0u;
-        cn[3] += (m > tau && !neg) ? 1u : 0u;
+    for (u32 u = 0; u < f.n_units; u++) {
+        const u32 fu = f.ids[u];
+        const u32 *list = f.pool + f.start[fu];
+        const u32 c = f.count[fu];
+        for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
+            u32 kk[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) kk[j] = (i0 + j * TSEL < c) ? list[i0 + j * TSEL] : 0u;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const u32 k = kk[j];
+                const u32 m = mag_of_key(k);
+                if (i0 + j * TSEL >= c || (m >> L1_SHIFT) != mb) continue;
+                const bool neg = key_is_neg(k);
+                cn[0] += (m < tau && neg) ? 1u : 0u;
+                cn[1] += (m < tau && !neg) ? 1u : 0u;
+                cn[2] += (m > tau && neg) ? 1u : 0u;
+                cn[3] += (m > tau && !neg) ? 1u : 0u;
+            }
+        }
     }
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -620,7 +634,7 @@ __global__ __launch_bounds__(256) void k_bnd_select(const TDesc *__restrict__ td
 // launch wrappers
 // ------------------------------------------------------------------------------------------
 constexpr int SM_HIST1 = L2_BINS * 4;
-constexpr int SM_HIST2 = (L2_BINS + COARSE + (BLOCK / 64) * STAGE_CAP) * 4 + (BLOCK / 64) * STAGE_CAP;
+constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_GATHER = (L2_BINS + COARSE) * 4;
@@ -644,10 +658,10 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     hipError_t e = set_attrs();
     if (e) return e;
     const Bufs &B = bt.bufs;
-    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
+    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
     PROF("k_plan1", s, k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
-    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, B));
-    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, B));
+    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
+    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     const u32 TG = bt.n_pairs * NB8;
