@@ -257,10 +257,12 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_wf = cv.take(sizeof(u32) * n_wg);
         const size_t o_tfo = cv.take(sizeof(u32) * (nT + 1));
         const size_t o_tfi = cv.take(sizeof(u32) * units);
+        const size_t o_fut = cv.take(sizeof(u32) * units);
         const size_t up_bytes = cv.off;
         const size_t o_ts = cv.take(sizeof(TState) * nT);
         const size_t o_h1 = cv.take((size_t)nT * L1_BINS * 4);
         const size_t o_h2 = cv.take((size_t)nT * L2_BINS * 4);
+        const size_t o_ngt = cv.take(256);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
         const size_t o_us = cv.take((size_t)units * 8);
@@ -281,6 +283,16 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_cb = cv.take((size_t)nT * n_cfg * CB_STRIDE * 4);
         const size_t o_sc = cv.take((size_t)nT * n_cfg * sizeof(Score));
         const size_t o_bt = cv.take((size_t)nT * n_cfg * CB_STRIDE * 8);
+        const size_t o_uc = cv.take((size_t)units * 4);
+        const size_t o_abm = cv.take((size_t)nT * (L2_BINS / 32) * 4);
+        const size_t o_bg = cv.take((size_t)nT * L2_BINS * 2);
+        const size_t o_go = cv.take((size_t)nT * MAX_GROUPS * 4);
+        const size_t o_ge = cv.take((size_t)nT * MAX_GROUPS * 4);
+        const size_t o_gc = cv.take((size_t)nT * MAX_GROUPS * 4);
+        const size_t o_tgg = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_tkl = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_tkh = cv.take((size_t)nT * TGT_STRIDE * 4);
+        const size_t o_gl = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_pool = cv.take((size_t)pool * 4);
         rc = ensure_dev(c, c->search_mem, cv.off);
         if (rc) return rc;
@@ -300,6 +312,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
                 for (u32 u : t_units[tt]) tfi[k++] = u;
             }
             tfo[nT] = k;
+            u32 *fut = (u32 *)(hb + o_fut);
+            for (uint32_t tt = 0; tt < nT; tt++)
+                for (u32 u : t_units[tt]) fut[u] = tt;
         }
         HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, hipMemsetAsync(db + o_ts, 0, zero_end - o_ts, c->stream));
@@ -311,6 +326,11 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         bt.wg_fu0 = (const u32 *)(db + o_wf);
         bt.t_fu_off = (const u32 *)(db + o_tfo);
         bt.t_fu_ids = (const u32 *)(db + o_tfi);
+        bt.fu_tensor = (const u32 *)(db + o_fut);
+        bt.grp_list = (u32 *)(db + o_gl);
+        bt.n_grp_total = (u32 *)(db + o_ngt);
+        bt.n_units = (int)units;
+        bt.n_bucket_blocks = c->n_cu * 2;
         bt.nT = (int)nT;
         bt.n_wg = n_wg;
         bt.n_pairs = g.n_pairs;
@@ -329,6 +349,16 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.tgt_res = (u32 *)(db + o_tr);
         B.tgt_key = (u32 *)(db + o_tk);
         B.pool = (u32 *)(db + o_pool);
+        B.pool2 = B.pool;
+        B.unit_cand = (u32 *)(db + o_uc);
+        B.active_bits = (u32 *)(db + o_abm);
+        B.bin_group = (u16 *)(db + o_bg);
+        B.grp_off = (u32 *)(db + o_go);
+        B.grp_end = (u32 *)(db + o_ge);
+        B.grp_cur = (u32 *)(db + o_gc);
+        B.tgt_grp = (u32 *)(db + o_tgg);
+        B.tgt_klo = (u32 *)(db + o_tkl);
+        B.tgt_khi = (u32 *)(db + o_tkh);
         B.tile_out = (u32 *)(db + o_to);
         B.tile_off = (u32 *)(db + o_tf);
         B.sq_part = (double *)(db + o_sq);

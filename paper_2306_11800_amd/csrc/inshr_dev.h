@@ -38,6 +38,8 @@ constexpr int MAX_PAIRS = 15;       // distinct (prune, protect) pairs in a grid
 constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits use a subset
 constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 = 3885 fits)
 constexpr int MAX_CFG = 256;
+constexpr int GROUP_SHIFT = 14;     // gathered keys per group of active bins: about 2^14
+constexpr int MAX_GROUPS = 4096;    // groups per tensor (the shift grows for huge tensors)
 constexpr u32 INACTIVE = 0xFFFFFFFFu;
 constexpr u32 RESOLVED = 0xFFFFFFFEu;
 constexpr u32 ZERO_KEY = 0x80000000u;
@@ -120,6 +122,7 @@ struct TState {
     u32 nb2;                           // bins in use
     u32 zbin;                          // bin that holds ZERO_KEY
     u64 cand_total;
+    u32 n_groups, gshift;
     // pairs
     u64 pair_An[MAX_PAIRS], pair_Mn[MAX_PAIRS], pair_Pn[MAX_PAIRS], pair_Pp[MAX_PAIRS];
     u64 pair_M[MAX_PAIRS], pair_Ap[MAX_PAIRS];

@@ -21,7 +21,17 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *tgt_bin;   // [nT][TGT_STRIDE] boundary j of pair q at q*255 + j-1
     u32 *tgt_res;
     u32 *tgt_key;   // results: boundary keys
-    u32 *pool;      // gathered keys
+    u32 *pool;      // gathered keys: per tensor a threshold region and an active-bin region, n each
+    u32 *pool2;     // same layout; the threshold region is reused for the keys in bin-group order
+    u32 *unit_cand; // [units] active-bin keys the unit gathered
+    u32 *active_bits; // [nT][1024] bitmap of active bins
+    u16 *bin_group; // [nT][32768] group of each active bin
+    u32 *grp_off;   // [nT][MAX_GROUPS] first / one-past-last position of each group in bin order
+    u32 *grp_end;
+    u32 *grp_cur;   // [nT][MAX_GROUPS] keys placed so far
+    u32 *tgt_grp;   // [nT][TGT_STRIDE] group, first and last key of each boundary's bin
+    u32 *tgt_klo;
+    u32 *tgt_khi;
     u32 *tile_out;  // [tiles][MAX_FRAC] protected values per tile and protect fraction
     double *sq_part; // [units][SQ_STRIDE]
     // scoring
@@ -43,8 +53,13 @@ struct Batch {
     const u32 *wg_fu0;   // device [n_wg] first (workgroup, tensor) unit of each workgroup
     const u32 *t_fu_off; // device [nT + 1] CSR of the units that touch each tensor ...
     const u32 *t_fu_ids; // device         ... in ascending workgroup order
+    const u32 *fu_tensor; // device [units] tensor of each unit
+    u32 *grp_list;       // device [nT * MAX_GROUPS] (tensor << 12 | group) of every group
+    u32 *n_grp_total;    // device
     int nT;
     int n_wg;
+    int n_units;
+    int n_bucket_blocks;
     u32 n_pairs, n_cfg;
     u64 n_tiles;
     Bufs bufs;

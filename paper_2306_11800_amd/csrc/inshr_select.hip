@@ -408,7 +408,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
 }
 
 // ------------------------------------------------------------------------------------------
-// plan 2: boundary ranks -> active bins
+// plan 2: boundary ranks -> active bins -> groups of active bins
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
                                                  const GridDesc *__restrict__ gd, Bufs B)
@@ -420,12 +420,14 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
 
     const int t = blockIdx.x;
     const u32 tid = threadIdx.x;
-    const u64 n = td[t].n;
+    const TDesc d = td[t];
+    const u64 n = d.n;
     TState *st = B.ts + t;
     const u32 nb2 = st->nb2;
     const u32 zbin = st->zbin;
     const u64 n_zero = st->n_zero;
     const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+    const u32 *tab = B.table2 + (size_t)t * COARSE;
     u32 *binfo = B.binfo + (size_t)t * L2_BINS;
     u32 *cur = B.cursor2 + (size_t)t * CURSOR_STRIDE;
     const u32 n_pairs = gd->n_pairs, n_p = gd->n_p;
@@ -490,14 +492,70 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         }
     }
     __syncthreads();
+    // gathered population of every bin in bin order -> offset of the bin in that order
     for (u32 i = tid; i < nb2; i += BLOCK)
         cur[i] = binfo[i] ? (h2[i] - ((i == zbin) ? (u32)n_zero : 0u)) : 0u;
     __syncthreads();
-    u32 ctot = block_excl_scan(cur, cur, (int)nb2, tmp);
-    for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = binfo[i] ? cur[i] : INACTIVE;
+    const u32 ctot = block_excl_scan(cur, cur, (int)nb2, tmp);
+    // groups: runs of active bins of about 2^gshift gathered keys; at most MAX_GROUPS per tensor
+    u32 gshift = GROUP_SHIFT;
+    while ((ctot >> gshift) >= (u32)MAX_GROUPS) gshift++;
+    const u32 n_groups = ctot ? ((ctot - 1u) >> gshift) + 1u : 0u;
+    u32 *goff = B.grp_off + d.tile0 * 0 + (size_t)t * MAX_GROUPS;
+    u32 *gend = B.grp_end + (size_t)t * MAX_GROUPS;
+    u32 *gcur = B.grp_cur + (size_t)t * MAX_GROUPS;
+    for (u32 g = tid; g < (u32)MAX_GROUPS; g += BLOCK) {
+        goff[g] = 0xFFFFFFFFu;
+        gend[g] = 0u;
+        gcur[g] = 0u;
+    }
     __syncthreads();
-    for (u32 i = tid; i <= nb2; i += BLOCK) cur[i] = 0u;
-    if (tid == 0) st->cand_total = ctot;
+    u32 *abm = B.active_bits + (size_t)t * (L2_BINS / 32);
+    u16 *gtab = B.bin_group + (size_t)t * L2_BINS;
+    for (u32 i = tid; i < (u32)L2_BINS / 32; i += BLOCK) abm[i] = 0u;
+    __syncthreads();
+    for (u32 i = tid; i < nb2; i += BLOCK) {
+        if (binfo[i]) {
+            const u32 c = h2[i] - ((i == zbin) ? (u32)n_zero : 0u);
+            const u32 g = cur[i] >> gshift;
+            atomicMin(&goff[g], cur[i]);
+            atomicMax(&gend[g], cur[i] + c);
+            atomicOr(&abm[i >> 5], 1u << (i & 31u));
+            gtab[i] = (u16)g;
+            binfo[i] = cur[i]; // offset of the bin's keys once they are in bin order
+        } else {
+            binfo[i] = INACTIVE;
+            gtab[i] = 0xFFFFu;
+        }
+    }
+    __syncthreads();
+    // per target: its group and the key range of its bin
+    u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
+    u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
+    u32 *thi = B.tgt_khi + (size_t)t * TGT_STRIDE;
+    for (u32 i = tid; i < TG; i += BLOCK) {
+        const u32 bin = tb[i];
+        if (bin == RESOLVED) continue;
+        tg[i] = gtab[bin];
+        // last 12-bit prefix whose first bin is <= bin
+        u32 lo = 0, hi = COARSE - 1;
+        while (lo < hi) {
+            u32 mid = (lo + hi + 1) >> 1;
+            if (((tab[mid] >> 5) & 0x7fffu) <= bin)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        const u32 e = tab[lo], dd = e & 31u, sub = bin - ((e >> 5) & 0x7fffu);
+        const u32 klo = (lo << COARSE_SHIFT) | (sub << (COARSE_SHIFT - dd));
+        tlo[i] = klo;
+        thi[i] = klo + ((1u << (COARSE_SHIFT - dd)) - 1u);
+    }
+    if (tid == 0) {
+        st->cand_total = ctot;
+        st->n_groups = n_groups;
+        st->gshift = gshift;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -508,14 +566,14 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
                                                   const u32 *__restrict__ wg_fu0,
                                                   const GridDesc *__restrict__ gd, Bufs B)
 {
-    extern __shared__ u32 smem[];
-    u32 *binfo = smem;          // 32768
-    u32 *T = smem + L2_BINS;    // 4096
+    __shared__ u32 abm[L2_BINS / 32]; // active bins
+    __shared__ u32 T[COARSE];
     __shared__ u32 s_tau_o[MAX_FRAC];
     __shared__ u32 s_oc[MAX_FRAC];
+    __shared__ u32 s_gathered;
     __shared__ double s_red[BLOCK / 64];
 
-    const u32 tid = threadIdx.x;
+    const u32 tid = threadIdx.x, lane = tid & 63u;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     const u32 n_p = gd->n_p, n_o = gd->n_o;
@@ -528,19 +586,20 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         const u64 t_end = d.tile0 + n_tiles_t;
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
-        const u32 *gb = B.binfo + (size_t)t * L2_BINS;
-        const u32 nb2 = st->nb2;
-        for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = gb[i];
+        for (u32 i = tid; i < (u32)L2_BINS / 32; i += BLOCK) abm[i] = B.active_bits[(size_t)t * (L2_BINS / 32) + i];
         for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         if (tid < MAX_FRAC) {
             s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
             s_oc[tid] = 0u;
         }
+        if (tid == 0) s_gathered = 0u;
         __syncthreads();
         u32 tau_o_min = 0x7fffffffu;
         for (u32 o = 0; o < n_o; o++) tau_o_min = min(tau_o_min, s_tau_o[o]);
-        u32 *cur = B.cursor2 + (size_t)t * CURSOR_STRIDE;
-        u32 *cand = B.pool + d.pool_cand;
+        // keys of active bins go to a region of the pool that belongs to this workgroup alone
+        // (it starts at the workgroup's first element of the tensor), in arrival order
+        const u64 unit_start = (tile - d.tile0) * (u64)TILE;
+        u32 *gdst = B.pool + d.pool_cand + unit_start;
         double q_tot = 0.0;
         double q_out[MAX_FRAC];
 #pragma unroll
@@ -553,21 +612,23 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
             const u32 mask = load_tile(d, e0, cnt, v);
 #pragma unroll
             for (int i = 0; i < 16; i++) {
-                if (!((mask >> i) & 1u)) continue;
+                const bool valid = (mask >> i) & 1u;
                 const u32 b = canon_bits(__float_as_uint(v[i]));
                 const u32 key = key_of_bits(b);
                 const double xd = (double)v[i];
-                q_tot = fma(xd, xd, q_tot);
-                if (b != 0u) {
-                    const u32 off = binfo[l2_bin(key, T[key >> COARSE_SHIFT])];
-                    if (off != INACTIVE) {
-                        u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
-                        u32 pos = atomicAdd(&cur[bin], 1u);
-                        cand[off + pos] = key;
-                    }
+                q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
+                const u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
+                const bool cand = valid && b != 0u && ((abm[bin >> 5] >> (bin & 31u)) & 1u);
+                const u64 cm = __ballot(cand);
+                if (cm) {
+                    u32 base = 0u;
+                    if (lane == (u32)__ffsll((unsigned long long)cm) - 1u)
+                        base = atomicAdd(&s_gathered, (u32)__popcll(cm));
+                    base = __shfl(base, __ffsll((unsigned long long)cm) - 1);
+                    if (cand) gdst[base + __popcll(cm & ((1ull << lane) - 1ull))] = key;
                 }
                 const u32 m = b & 0x7fffffffu;
-                if (m > tau_o_min) {
+                if (valid && m > tau_o_min) {
 #pragma unroll
                     for (int o = 0; o < MAX_FRAC; o++) {
                         if (o < (int)n_o && m > s_tau_o[o]) {
@@ -586,6 +647,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         }
         // flush partial sums of this (workgroup, tensor) unit in a fixed order
         const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
+        if (tid == 0) B.unit_cand[fu] = s_gathered;
         double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
 #pragma unroll
         for (int o = 0; o <= MAX_FRAC; o++) {
@@ -606,28 +668,189 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
 }
 
 // ------------------------------------------------------------------------------------------
-// exact boundaries: residual-rank element of the boundary's bin (one wavefront per boundary)
+// gathered keys -> groups of consecutive active bins (one workgroup per (workgroup, tensor) unit)
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_bnd_select(const TDesc *__restrict__ td, int nT, u32 TG,
-                                                    Bufs B)
+constexpr int SPLIT_PER = 8; // keys per thread per step
+
+__global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
+                                                 const u32 *__restrict__ fu_tensor, Bufs B)
 {
-    const u64 gid = (u64)blockIdx.x * 4u + (threadIdx.x >> 6);
-    const int t = (int)(gid / TG);
-    const u32 i = (u32)(gid % TG);
-    if (t >= nT) return;
-    TState *st = B.ts + t;
-    const u32 bin = B.tgt_bin[(size_t)t * TGT_STRIDE + i];
-    if (bin == RESOLVED) return;
-    const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
-    const u32 off = B.binfo[(size_t)t * L2_BINS + bin];
-    const u32 c = B.cursor2[(size_t)t * CURSOR_STRIDE + bin];
-    const u32 expect = B.hist2[(size_t)t * L2_BINS + bin] - ((bin == st->zbin) ? (u32)st->n_zero : 0u);
-    if (off == INACTIVE || c != expect || res >= c) {
-        if ((threadIdx.x & 63u) == 0u) atomicOr(&st->internal_err, 128u);
-        return;
+    extern __shared__ u32 smem[];
+    u32 *T = smem;                                   // [4096]
+    u32 *gcount = T + COARSE;                        // [MAX_GROUPS]
+    u32 *gbase = gcount + MAX_GROUPS;                // [MAX_GROUPS]
+    u16 *gtab = reinterpret_cast<u16 *>(gbase + MAX_GROUPS); // [32768]
+
+    const u32 fu = blockIdx.x;
+    const int t = (int)fu_tensor[fu];
+    const u32 tid = threadIdx.x;
+    const TDesc d = td[t];
+    const TState *st = B.ts + t;
+    const u32 c = B.unit_cand[fu];
+    if (c == 0u) return;
+    const u32 nb2 = st->nb2, G = st->n_groups;
+    const u32 *src = B.pool + d.pool_cand + B.unit_start[fu];
+    u32 *dst = B.pool2 + d.pool_thr; // the tensor's second region, one key per slot in bin-group order
+    const u32 *goff = B.grp_off + (size_t)t * MAX_GROUPS;
+    u32 *gcur = B.grp_cur + (size_t)t * MAX_GROUPS;
+    for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+    for (u32 i = tid; i < nb2; i += BLOCK) gtab[i] = B.bin_group[(size_t)t * L2_BINS + i];
+    for (u32 g = tid; g < G; g += BLOCK) gcount[g] = 0u;
+    __syncthreads();
+    for (u32 base = 0; base < c; base += BLOCK * SPLIT_PER) {
+        u32 key[SPLIT_PER], gr[SPLIT_PER]; // group << 16 | rank inside (step, group)
+#pragma unroll
+        for (int j = 0; j < SPLIT_PER; j++) {
+            const u32 i = base + tid + j * BLOCK;
+            key[j] = (i < c) ? src[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < SPLIT_PER; j++) {
+            const u32 i = base + tid + j * BLOCK;
+            gr[j] = 0xFFFFFFFFu;
+            if (i < c) {
+                const u32 g = gtab[l2_bin(key[j], T[key[j] >> COARSE_SHIFT])];
+                if (g < G) gr[j] = (g << 16) | atomicAdd(&gcount[g], 1u); // at most 8192 keys per step
+            }
+        }
+        __syncthreads();
+        for (u32 g = tid; g < G; g += BLOCK) {
+            const u32 k = gcount[g];
+            if (k) {
+                gbase[g] = goff[g] + atomicAdd(&gcur[g], k);
+                gcount[g] = 0u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < SPLIT_PER; j++) {
+            const u32 i = base + tid + j * BLOCK;
+            if (i < c && gr[j] != 0xFFFFFFFFu) dst[gbase[gr[j] >> 16] + (gr[j] & 0xFFFFu)] = key[j];
+        }
+        __syncthreads();
     }
-    u32 key = wave_select(B.pool + td[t].pool_cand + off, c, res, false);
-    if ((threadIdx.x & 63u) == 0u) B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
+}
+
+// ------------------------------------------------------------------------------------------
+// exact boundaries: residual-rank element of the boundary's bin, searched in the bin's group
+// ------------------------------------------------------------------------------------------
+constexpr int BUCKET_CAP = 24576; // keys of a group held in LDS
+constexpr int MATCH_REGS = 32;    // keys of one bin a lane can hold
+
+// k-th smallest of the keys in [klo, khi] among a[0..n) (LDS or global); one wavefront.
+// *found = number of keys in the range.  Lane-local registers hold the matches when they fit,
+// otherwise every round rescans the list.
+__device__ inline u32 wave_select_range(const u32 *a, u32 n, u32 klo, u32 khi, u32 k, u32 *found)
+{
+    const u32 lane = threadIdx.x & 63u;
+    u32 r[MATCH_REGS];
+    u32 mine = 0u;
+    u32 vo = 0u, va = 0xFFFFFFFFu;
+    for (u32 i = lane; i < n; i += 64u) {
+        const u32 v = a[i];
+        if (v >= klo && v <= khi) {
+#pragma unroll
+            for (int s = 0; s < MATCH_REGS; s++)
+                if (s == (int)mine) r[s] = v;
+            mine++;
+            vo |= v;
+            va &= v;
+        }
+    }
+    const u32 total = wave_sum(mine);
+    *found = total;
+    const bool fits = __ballot(mine > (u32)MATCH_REGS) == 0ull;
+    vo = wave_or(vo);
+    va = wave_and(va);
+    if (total == 0u) return 0u;
+    const u32 diff = vo ^ va;
+    if (diff == 0u) return va;
+    const int hb = 31 - __clz(diff);
+    u32 pref = va & ~((2u << hb) - 1u);
+    for (int b = hb; b >= 0; b--) {
+        const u32 himask = ~((2u << b) - 1u), bit = 1u << b;
+        u32 cnt = 0u;
+        if (fits) {
+#pragma unroll
+            for (int s = 0; s < MATCH_REGS; s++)
+                cnt += (s < (int)mine && ((r[s] ^ pref) & himask) == 0u && (r[s] & bit) == 0u) ? 1u : 0u;
+        } else {
+            for (u32 i = lane; i < n; i += 64u) {
+                const u32 v = a[i];
+                cnt += (v >= klo && v <= khi && ((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
+            }
+        }
+        cnt = wave_sum(cnt);
+        if (k >= cnt) {
+            k -= cnt;
+            pref |= bit;
+        }
+    }
+    return pref;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT, u32 TG,
+                                                  const u32 *__restrict__ grp_list,
+                                                  const u32 *__restrict__ n_grp_total, Bufs B)
+{
+    extern __shared__ u32 smem[];
+    u32 *keys = smem;                 // [BUCKET_CAP]
+    __shared__ u32 tlist[TGT_STRIDE]; // targets of this group
+    __shared__ u32 s_nt;
+
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 total = *n_grp_total;
+    for (u32 idx = blockIdx.x; idx < total; idx += gridDim.x) {
+        const u32 packed = grp_list[idx];
+        const int t = (int)(packed >> 12);
+        const u32 g = packed & 0xFFFu;
+        TState *st = B.ts + t;
+        const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
+        const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
+        __syncthreads();
+        if (tid == 0) s_nt = 0u;
+        __syncthreads();
+        if (gend <= goff) continue; // no keys in this window of the order
+        const u32 n = gend - goff;
+        const u32 *src = B.pool2 + td[t].pool_thr + goff;
+        const bool in_lds = n <= (u32)BUCKET_CAP;
+        if (in_lds)
+            for (u32 i = tid; i < n; i += BLOCK) keys[i] = src[i];
+        const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
+        const u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
+        for (u32 i = tid; i < TG; i += BLOCK)
+            if (tb[i] != RESOLVED && tg[i] == g) tlist[atomicAdd(&s_nt, 1u)] = i;
+        __syncthreads();
+        const u32 nt = s_nt;
+        const u32 *list = in_lds ? keys : src;
+        for (u32 k = wave; k < nt; k += BLOCK / 64) {
+            const u32 i = tlist[k];
+            const u32 bin = tb[i];
+            const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
+            const u32 klo = B.tgt_klo[(size_t)t * TGT_STRIDE + i], khi = B.tgt_khi[(size_t)t * TGT_STRIDE + i];
+            const u32 expect = B.hist2[(size_t)t * L2_BINS + bin] - ((bin == st->zbin) ? (u32)st->n_zero : 0u);
+            u32 found = 0u;
+            // the zero key is never gathered: it is excluded from the range when the bin holds it
+            const u32 key = wave_select_range(list, n, klo == ZERO_KEY ? klo + 1u : klo, khi, res, &found);
+            if (lane == 0u) {
+                if (found != expect || res >= found)
+                    atomicOr(&st->internal_err, 128u);
+                else
+                    B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
+            }
+        }
+    }
+}
+
+// list of all (tensor, group) pairs of the batch
+__global__ void k_group_list(int nT, Bufs B, u32 *grp_list, u32 *n_grp_total)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nT) return;
+    const u32 G = B.ts[t].n_groups;
+    if (G == 0u) return;
+    const u32 at = atomicAdd(n_grp_total, G);
+    for (u32 g = 0; g < G; g++) grp_list[at + g] = ((u32)t << 12) | g;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -637,7 +860,8 @@ constexpr int SM_HIST1 = L2_BINS * 4;
 constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
-constexpr int SM_GATHER = (L2_BINS + COARSE) * 4;
+constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
+constexpr int SM_BUCKET = BUCKET_CAP * 4;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
@@ -648,7 +872,8 @@ static hipError_t set_attrs()
     if ((e = hipFuncSetAttribute((const void *)k_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
-    if ((e = hipFuncSetAttribute((const void *)k_gather, hipFuncAttributeMaxDynamicSharedMemorySize, SM_GATHER))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_bucket, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
     g_attr_done = true;
     return hipSuccess;
 }
@@ -663,10 +888,11 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
     PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
-    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
+    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
+    PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
+    PROF("k_split", s, k_split<<<bt.n_units, BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     const u32 TG = bt.n_pairs * NB8;
-    const u64 waves = (u64)bt.nT * TG;
-    PROF("k_bnd_select", s, k_bnd_select<<<(unsigned)((waves + 3) / 4), 256, 0, s>>>(bt.td, bt.nT, TG, B));
+    PROF("k_bucket", s, k_bucket<<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
     return hipGetLastError();
 }
 
