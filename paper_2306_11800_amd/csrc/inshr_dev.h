@@ -12,6 +12,7 @@ typedef uint16_t u16;
 // would be accessed with FLAT instructions, whose completion is tracked together with LDS traffic;
 // every such pointer is device memory, so it is cast to the global address space before use.
 #define GLOBAL_AS __attribute__((address_space(1)))
+#define LDS_AS __attribute__((address_space(3)))
 
 namespace inshr {
 
@@ -38,7 +39,7 @@ constexpr int MAX_PAIRS = 15;       // distinct (prune, protect) pairs in a grid
 constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits use a subset
 constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 = 3885 fits)
 constexpr int MAX_CFG = 256;
-constexpr int GROUP_SHIFT = 14;     // gathered keys per group of active bins: about 2^14
+constexpr int GROUP_SHIFT = 13;     // gathered keys per group of active bins: about 2^13
 constexpr int MAX_GROUPS = 4096;    // groups per tensor (the shift grows for huge tensors)
 constexpr u32 INACTIVE = 0xFFFFFFFFu;
 constexpr u32 RESOLVED = 0xFFFFFFFEu;
@@ -169,7 +170,8 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // k-th smallest (0-based) of a[0..c) under the order of keys (by_mag == false) or of their
 // magnitudes (by_mag == true); one wavefront, all lanes return the value.  Radix select from the
 // highest bit that differs; lists of up to 1024 values are held in registers.
-__device__ inline u32 wave_select(const u32 *a, u32 c, u32 k, bool by_mag)
+template <class Ptr>
+__device__ inline u32 wave_select(Ptr a, u32 c, u32 k, bool by_mag)
 {
     const u32 lane = threadIdx.x & 63u;
     u32 r[16];

@@ -734,35 +734,47 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 // exact boundaries: residual-rank element of the boundary's bin, searched in the bin's group
 // ------------------------------------------------------------------------------------------
-constexpr int BUCKET_CAP = 24576; // keys of a group held in LDS
-constexpr int MATCH_REGS = 32;    // keys of one bin a lane can hold
+constexpr int BUCKET_CAP = 16384;  // keys of a group held in LDS
+constexpr int MATCH_CAP = 1024;    // keys of one bin a wave sets aside in LDS
 
 // k-th smallest of the keys in [klo, khi] among a[0..n) (LDS or global); one wavefront.
-// *found = number of keys in the range.  Lane-local registers hold the matches when they fit,
-// otherwise every round rescans the list.
-__device__ inline u32 wave_select_range(const u32 *a, u32 n, u32 klo, u32 khi, u32 k, u32 *found)
+// *found = number of keys in the range.  The keys of the range are set aside in the wave's LDS
+// scratch when they fit there (then a register-resident radix select finishes); otherwise every
+// round of the radix select rescans the list.
+template <class Ptr>
+__device__ inline u32 wave_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, LDS_AS u32 *scratch,
+                                        u32 *found)
 {
     const u32 lane = threadIdx.x & 63u;
-    u32 r[MATCH_REGS];
-    u32 mine = 0u;
+    u32 total = 0u; // wave-uniform
     u32 vo = 0u, va = 0xFFFFFFFFu;
-    for (u32 i = lane; i < n; i += 64u) {
-        const u32 v = a[i];
-        if (v >= klo && v <= khi) {
+    for (u32 i0 = 0; i0 < n; i0 += 256u) {
+        u32 v[4];
+        bool in[4];
 #pragma unroll
-            for (int s = 0; s < MATCH_REGS; s++)
-                if (s == (int)mine) r[s] = v;
-            mine++;
-            vo |= v;
-            va &= v;
+        for (int j = 0; j < 4; j++) {
+            const u32 i = i0 + lane + 64u * j;
+            v[j] = (i < n) ? a[i] : 0u;
+            in[j] = (i < n) && v[j] >= klo && v[j] <= khi;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const u64 m = __ballot(in[j]);
+            if (m == 0ull) continue;
+            if (in[j]) {
+                const u32 pos = total + __popcll(m & ((1ull << lane) - 1ull));
+                if (pos < (u32)MATCH_CAP) scratch[pos] = v[j];
+                vo |= v[j];
+                va &= v[j];
+            }
+            total += (u32)__popcll(m);
         }
     }
-    const u32 total = wave_sum(mine);
     *found = total;
-    const bool fits = __ballot(mine > (u32)MATCH_REGS) == 0ull;
+    if (total == 0u) return 0u;
+    if (total <= (u32)MATCH_CAP) return wave_select((const LDS_AS u32 *)scratch, total, k, false);
     vo = wave_or(vo);
     va = wave_and(va);
-    if (total == 0u) return 0u;
     const u32 diff = vo ^ va;
     if (diff == 0u) return va;
     const int hb = 31 - __clz(diff);
@@ -770,14 +782,12 @@ __device__ inline u32 wave_select_range(const u32 *a, u32 n, u32 klo, u32 khi, u
     for (int b = hb; b >= 0; b--) {
         const u32 himask = ~((2u << b) - 1u), bit = 1u << b;
         u32 cnt = 0u;
-        if (fits) {
+        for (u32 i0 = 0; i0 < n; i0 += 256u) {
 #pragma unroll
-            for (int s = 0; s < MATCH_REGS; s++)
-                cnt += (s < (int)mine && ((r[s] ^ pref) & himask) == 0u && (r[s] & bit) == 0u) ? 1u : 0u;
-        } else {
-            for (u32 i = lane; i < n; i += 64u) {
-                const u32 v = a[i];
-                cnt += (v >= klo && v <= khi && ((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
+            for (int j = 0; j < 4; j++) {
+                const u32 i = i0 + lane + 64u * j;
+                const u32 v = (i < n) ? a[i] : 0u;
+                cnt += (i < n && v >= klo && v <= khi && ((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
             }
         }
         cnt = wave_sum(cnt);
@@ -789,14 +799,82 @@ __device__ inline u32 wave_select_range(const u32 *a, u32 n, u32 klo, u32 khi, u
     return pref;
 }
 
+// k-th smallest of the keys in [klo, khi] (khi - klo + 1 a power of two) among a[0..n), by the whole
+// workgroup: radix select, 8 bits per round, LDS histogram.  *found = keys in the range (in sh[2]).
+template <class Ptr>
+__device__ inline u32 block_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, bool skip_zero,
+                                         u32 *hist /*[256]*/, u32 *sh /*[3]*/)
+{
+    const u32 tid = threadIdx.x;
+    int R = __popc(khi - klo); // bits that vary inside the range
+    u32 P = 0u;                // chosen high part of (key - klo)
+    bool first = true;
+    while (R > 0) {
+        const int w = R < 8 ? R : 8;
+        for (u32 i = tid; i < 256u; i += BLOCK) hist[i] = 0u;
+        __syncthreads();
+        for (u32 i0 = 0; i0 < n; i0 += 4u * BLOCK) {
+            u32 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) v[j] = (i0 + tid + j * BLOCK < n) ? a[i0 + tid + j * BLOCK] : 0u;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                if (i0 + tid + j * BLOCK >= n || v[j] < klo || v[j] > khi) continue;
+                if (skip_zero && v[j] == ZERO_KEY) continue;
+                const u32 rel = v[j] - klo;
+                if (!first && (rel >> R) != P) continue;
+                atomicAdd(&hist[(rel >> (R - w)) & ((1u << w) - 1u)], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < 64u) { // 4 bins per lane
+            u32 loc[4], s = 0;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                loc[j] = hist[tid * 4u + j];
+                s += loc[j];
+            }
+            u32 inc = s;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                u32 v = __shfl_up(inc, o);
+                if ((int)tid >= o) inc += v;
+            }
+            u32 run = inc - s;
+            if (first && tid == 63u) sh[2] = inc;
+            if (k >= run && k < inc) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    if (k >= run && k < run + loc[j]) {
+                        sh[0] = tid * 4u + j;
+                        sh[1] = k - run;
+                    }
+                    run += loc[j];
+                }
+            }
+        }
+        __syncthreads();
+        P = first ? sh[0] : ((P << w) | sh[0]);
+        k = sh[1];
+        R -= w;
+        first = false;
+        __syncthreads();
+    }
+    return klo + P;
+}
+
 __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT, u32 TG,
                                                   const u32 *__restrict__ grp_list,
                                                   const u32 *__restrict__ n_grp_total, Bufs B)
 {
     extern __shared__ u32 smem[];
     u32 *keys = smem;                 // [BUCKET_CAP]
-    __shared__ u32 tlist[TGT_STRIDE]; // targets of this group
-    __shared__ u32 s_nt;
+    u32 *scratch = smem + BUCKET_CAP; // [16][MATCH_CAP]
+    __shared__ u32 tlist[TGT_STRIDE]; // targets of this group: small bins from the front, large
+                                      // bins from the back
+    __shared__ u32 s_nt, s_nl;
+    __shared__ u32 hist[256];
+    __shared__ u32 sh[3];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 total = *n_grp_total;
@@ -808,7 +886,10 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
         const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
         const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
         __syncthreads();
-        if (tid == 0) s_nt = 0u;
+        if (tid == 0) {
+            s_nt = 0u;
+            s_nl = 0u;
+        }
         __syncthreads();
         if (gend <= goff) continue; // no keys in this window of the order
         const u32 n = gend - goff;
@@ -818,22 +899,52 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
             for (u32 i = tid; i < n; i += BLOCK) keys[i] = src[i];
         const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
         const u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
-        for (u32 i = tid; i < TG; i += BLOCK)
-            if (tb[i] != RESOLVED && tg[i] == g) tlist[atomicAdd(&s_nt, 1u)] = i;
+        const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+        const u32 zbin = st->zbin, nz = (u32)st->n_zero;
+        for (u32 i = tid; i < TG; i += BLOCK) {
+            const u32 bin = tb[i];
+            if (bin != RESOLVED && tg[i] == g) {
+                const u32 pop = h2[bin] - (bin == zbin ? nz : 0u);
+                if (pop <= (u32)MATCH_CAP)
+                    tlist[atomicAdd(&s_nt, 1u)] = i;
+                else
+                    tlist[TGT_STRIDE - 1u - atomicAdd(&s_nl, 1u)] = i;
+            }
+        }
         __syncthreads();
-        const u32 nt = s_nt;
-        const u32 *list = in_lds ? keys : src;
+        const u32 nt = s_nt, nl = s_nl;
+        // boundaries in small bins: one wave each
+        LDS_AS u32 *wscratch = (LDS_AS u32 *)(scratch + wave * MATCH_CAP);
         for (u32 k = wave; k < nt; k += BLOCK / 64) {
             const u32 i = tlist[k];
             const u32 bin = tb[i];
             const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
             const u32 klo = B.tgt_klo[(size_t)t * TGT_STRIDE + i], khi = B.tgt_khi[(size_t)t * TGT_STRIDE + i];
-            const u32 expect = B.hist2[(size_t)t * L2_BINS + bin] - ((bin == st->zbin) ? (u32)st->n_zero : 0u);
+            const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
             u32 found = 0u;
             // the zero key is never gathered: it is excluded from the range when the bin holds it
-            const u32 key = wave_select_range(list, n, klo == ZERO_KEY ? klo + 1u : klo, khi, res, &found);
+            const u32 kl = (klo == ZERO_KEY) ? klo + 1u : klo;
+            const u32 key = in_lds ? wave_select_range((const LDS_AS u32 *)keys, n, kl, khi, res, wscratch, &found)
+                                   : wave_select_range((const GLOBAL_AS u32 *)src, n, kl, khi, res, wscratch, &found);
             if (lane == 0u) {
                 if (found != expect || res >= found)
+                    atomicOr(&st->internal_err, 128u);
+                else
+                    B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
+            }
+        }
+        // boundaries in large bins: the whole workgroup, one after the other
+        for (u32 k = 0; k < nl; k++) {
+            __syncthreads();
+            const u32 i = tlist[TGT_STRIDE - 1u - k];
+            const u32 bin = tb[i];
+            const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
+            const u32 klo = B.tgt_klo[(size_t)t * TGT_STRIDE + i], khi = B.tgt_khi[(size_t)t * TGT_STRIDE + i];
+            const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
+            const u32 key = in_lds ? block_select_range((const LDS_AS u32 *)keys, n, klo, khi, res, klo == ZERO_KEY, hist, sh)
+                                   : block_select_range((const GLOBAL_AS u32 *)src, n, klo, khi, res, klo == ZERO_KEY, hist, sh);
+            if (tid == 0u) {
+                if (sh[2] != expect || res >= expect)
                     atomicOr(&st->internal_err, 128u);
                 else
                     B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
@@ -861,7 +972,7 @@ constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
-constexpr int SM_BUCKET = BUCKET_CAP * 4;
+constexpr int SM_BUCKET = (BUCKET_CAP + (BLOCK / 64) * MATCH_CAP) * 4;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
