@@ -133,39 +133,19 @@ __device__ __forceinline__ void store_words(const TileWords &t, u32 cnt, u32 w, 
 }
 static_assert(TWORDS + 1 <= 3 * DBLOCK, "three words per thread cover a tile");
 
-// word j of a run: c symbols of wB bits that start at bit `src0` of the LDS stream go to global
-// stream position gbv
-__device__ __forceinline__ void emit_word(const unsigned long long *bits,
-                                          GLOBAL_AS unsigned long long *out, u32 j, u32 s0, u64 Wf,
-                                          u32 nbits, int src0)
-{
-    const int rel = (int)(j * 64u) - (int)s0; // run-relative bit of the word's bit 0
-    const int lo = rel < 0 ? 0 : rel;
-    const int hi = (rel + 64 < (int)nbits) ? rel + 64 : (int)nbits;
-    const int sb = src0 + rel;
-    unsigned long long val;
-    if (sb >= 0) {
-        const u32 wd = (u32)sb >> 6, sh = (u32)sb & 63u;
-        val = bits[wd] >> sh;
-        if (sh) val |= bits[wd + 1u] << (64u - sh);
-    } else {
-        val = bits[0] << (u32)(-sb);
-    }
-    const u32 a = (u32)(lo - rel), b = (u32)(hi - rel); // keep bits [a, b) of val
-    unsigned long long m = (b >= 64u) ? ~0ull : ((1ull << b) - 1ull);
-    m &= ~((1ull << a) - 1ull);
-    val &= m;
-    if (a == 0u && b == 64u)
-        out[Wf + j] = val;
-    else if (val)
-        __hip_atomic_fetch_or(out + (Wf + j), val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-constexpr u32 SHORT_RUN = 16; // runs of up to this many output words are copied by one thread
+// Words of the LDS image of one tile's output: every group's run starts at the bit of its first
+// stream word that the stream position dictates, so LDS word k is stream word dbase[g] + k.  A run
+// of b bits touches at most b / 64 + 2 words.
+constexpr int BWORDS = TWORDS + 2 * SS + 2;
 
 // ORDERED: same-address LDS atomics with return are served in ascending lane order on this device
 // (checked by k_lds_order_check before the library relies on it); one returning add then ranks an
 // element.  Otherwise equal symbols of a step find each other through the slot array.
+//
+// Stream words that lie wholly inside one chunk's part of one group are written with plain stores:
+// the trailing partial word of a group's run is carried in LDS to the next tile of the chunk.  Only
+// the words at the two ends of a (chunk, group) run are shared with other workgroups; those are
+// OR-ed into words that k_dzero cleared.
 template <bool PERM, bool ORDERED>
 __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict__ dd,
                                                      const u32 *__restrict__ chunk_tensor,
@@ -174,17 +154,22 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     __shared__ u32 P[DTILE * 9 / 32 + 8];
     __shared__ u32 C[DTILE * 9 / 32 + 8];
     // slot[wave][symbol]: lanes of the wave's current step that hold the symbol (sweep 1);
-    // the same memory then holds the tile's regrouped deltas as a bit stream (sweep 2, output)
-    __shared__ unsigned long long slot[ORDERED ? TWORDS + 2 : NWAVE * SS];
-    __shared__ u32 wst[NWAVE][SS]; // counts, then local start of (wave, symbol) in the tile's layout
-    __shared__ u32 lbase[SS];      // local start of each symbol's run
+    // the same memory then holds the image of the tile's output words (sweep 2, output)
+    __shared__ unsigned long long slot[ORDERED ? BWORDS : NWAVE * SS];
+    __shared__ u32 wst[NWAVE][SS];  // counts, then bit position in the image of (wave, symbol)
+    __shared__ u32 wel[PERM ? NWAVE : 1][SS]; // local regrouped index of (wave, symbol)
+    __shared__ u32 wstart[512];     // first image word of each group's run; [S] = words in use
+    __shared__ unsigned long long dbase[SS]; // image word k of group g is stream word dbase[g] + k
+    __shared__ unsigned long long carry[SS], ncarry[SS]; // partial trailing word of the group
+    __shared__ u32 own[SS], nown[SS]; // the group's current stream word belongs to this chunk alone
+    __shared__ u32 tailp[SS];      // this tile's run of the group ends inside a word
+    __shared__ u32 lbase[PERM ? SS : 1]; // local regrouped index of each group's run
     __shared__ u32 gcnt[SS];       // tile population per symbol
     __shared__ u32 gb[SS];         // stream position of each group's next run (n < 2^32)
-    __shared__ u32 wtot[8];
+    __shared__ u32 wtot[8], etot[8];
     __shared__ u16 si[PERM ? DTILE : 1]; // local indices in regrouped order
     unsigned long long *bits = slot;
-    static_assert(NWAVE * SS >= TWORDS + 2, "bit stream fits the slot array");
-
+    static_assert(NWAVE * SS >= BWORDS, "output image fits the slot array");
 
     const u64 chunk = blockIdx.x;
     const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
@@ -192,14 +177,19 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     if (PERM != (d.perm != nullptr)) return;
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 S = d.Kp + 2u, Bm = d.B, wB = d.wB, wp = d.wp, wc = d.wc;
+    const u32 step0 = 1u << (31 - __clz(S - 1u)); // first stride of the search over wstart[0..S)
     const u64 n_tiles = (d.n + DTILE - 1) / DTILE;
     const u64 lt0 = (chunk - d.chunk0) * DCHUNK;
     const u64 lt1 = (lt0 + DCHUNK < n_tiles) ? lt0 + DCHUNK : n_tiles;
     GLOBAL_AS unsigned long long *out = gptr(d.out);
     if (tid < S) {
-        gb[tid] = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
+        const u32 g0 = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
+        gb[tid] = g0;
         gcnt[tid] = 0u;
+        carry[tid] = 0ull;
+        own[tid] = ((((u64)g0 * wB) & 63u) == 0u) ? 1u : 0u;
     }
+    if (tid < 512u) wstart[tid] = 0xFFFFFFFFu;
     const u64 ltmask = (1ull << lane) - 1ull;
     const unsigned long long lanebit = 1ull << lane;
 
@@ -211,10 +201,14 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
         __syncthreads();
-        if (tid < S) gb[tid] += gcnt[tid]; // the previous tile's runs have been written
+        if (tid < S && gcnt[tid]) { // the previous tile's runs have been written
+            gb[tid] += gcnt[tid];
+            carry[tid] = ncarry[tid];
+            own[tid] = nown[tid];
+        }
         store_words(fetch_words(gptr(d.prev), e0, cnt, wp), cnt, wp, P);
         store_words(fetch_words(gptr(d.cur), e0, cnt, wc), cnt, wc, C);
-        for (u32 k = tid; k < (ORDERED ? TWORDS + 2 : NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
+        for (u32 k = tid; k < (ORDERED ? BWORDS : NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
         for (u32 k = tid; k < SS * NWAVE; k += DBLOCK) (&wst[0][0])[k] = 0u;
         __syncthreads();
         // sweep 1: stable rank of every element among the equal symbols of its wave's 1024 elements
@@ -252,86 +246,132 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
         }
         __syncthreads();
-        // counts -> positions: population of each symbol, exclusive scan over symbols, start of
-        // every (wave, symbol)
-        u32 tot = 0, pre = 0;
+        // counts -> positions: population of each symbol, the stream words its run touches,
+        // exclusive scans over symbols, start of every (wave, symbol)
+        u32 tot = 0, nW = 0, s0 = 0, preW = 0, preE = 0;
+        u64 fb = 0;
         if (tid < S) {
 #pragma unroll
             for (int wv = 0; wv < NWAVE; wv++) tot += wst[wv][tid];
+            fb = (u64)gb[tid] * wB;
+            s0 = (u32)(fb & 63u);
+            nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
         }
         if (tid < 320u) { // waves 0..4 hold the 258 symbols
-            u32 inc = tot;
+            u32 incW = nW, incE = tot;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
-                u32 v = __shfl_up(inc, o);
-                if ((int)lane >= o) inc += v;
+                u32 v = __shfl_up(incW, o);
+                u32 e = __shfl_up(incE, o);
+                if ((int)lane >= o) {
+                    incW += v;
+                    incE += e;
+                }
             }
-            pre = inc - tot;
-            if (lane == 63u) wtot[wave] = inc;
+            preW = incW - nW;
+            preE = incE - tot;
+            if (lane == 63u) {
+                wtot[wave] = incW;
+                etot[wave] = incE;
+            }
         }
         __syncthreads();
         if (tid < S) {
-            u32 base = pre;
-            for (u32 w2 = 0; w2 < wave; w2++) base += wtot[w2];
+            u32 ws = preW, es = preE;
+            for (u32 w2 = 0; w2 < wave; w2++) {
+                ws += wtot[w2];
+                es += etot[w2];
+            }
             gcnt[tid] = tot;
-            lbase[tid] = base;
+            wstart[tid] = ws;
+            if (tid == S - 1u) wstart[S] = ws + nW;
+            dbase[tid] = (fb >> 6) - (u64)ws;
+            tailp[tid] = (s0 + tot * wB) & 63u;
+            if (PERM) lbase[tid] = es;
             u32 cwv[NWAVE];
 #pragma unroll
             for (int wv = 0; wv < NWAVE; wv++) cwv[wv] = wst[wv][tid];
+            u32 bitpos = ws * 64u + s0;
 #pragma unroll
             for (int wv = 0; wv < NWAVE; wv++) {
-                wst[wv][tid] = base;
-                base += cwv[wv];
+                wst[wv][tid] = bitpos;
+                bitpos += cwv[wv] * wB;
+                if (PERM) {
+                    wel[wv][tid] = es;
+                    es += cwv[wv];
+                }
             }
         }
         __syncthreads();
-        // sweep 2: the tile's deltas, group by group, as a bit stream (all slots are zero again)
+        // sweep 2: the image of the tile's output words (all slots are zero again)
 #pragma unroll
         for (u32 r = 0; r < 16u; r++) {
             const u32 v = reg[r];
             if (v >> 31) {
-                const u32 sp = v & 511u, dv = (v >> 19) & 511u;
-                const u32 L = wst[wave][sp] + ((v >> 9) & 1023u);
+                const u32 sp = v & 511u, dv = (v >> 19) & 511u, within = (v >> 9) & 1023u;
                 if (dv) {
-                    const u32 bo = L * wB;
+                    const u32 bo = wst[wave][sp] + within * wB;
                     const u32 word = bo >> 6, sh = bo & 63u;
                     atomicOr(&bits[word], (unsigned long long)dv << sh);
                     if (sh + wB > 64u) atomicOr(&bits[word + 1u], (unsigned long long)dv >> (64u - sh));
                 }
-                if (PERM) si[L] = (u16)(wave * 1024u + r * 64u + lane);
+                if (PERM) si[wel[wave][sp] + within] = (u16)(wave * 1024u + r * 64u + lane);
             }
         }
         __syncthreads();
-        // copy each group's run to its place in the output stream: short runs one thread each,
-        // long runs one wave each
-        if (tid < S) {
-            const u32 c = gcnt[tid];
-            if (c) {
-                const u64 fb = (u64)gb[tid] * wB;
-                const u32 s0 = (u32)(fb & 63u), nbits = c * wB;
-                const u32 nW = (s0 + nbits + 63u) >> 6;
-                if (nW <= SHORT_RUN) {
-                    const int src0 = (int)(lbase[tid] * wB);
-                    for (u32 j = 0; j < nW; j++) emit_word(bits, out, j, s0, fb >> 6, nbits, src0);
-                    if (PERM)
-                        for (u32 i = 0; i < c; i++)
-                            gptr(d.perm)[gb[tid] + i] = (u32)(e0 + si[lbase[tid] + i]);
+        // one thread per output word
+        const u32 n_img = wstart[S];
+        for (u32 k = tid; k < n_img; k += DBLOCK) {
+            u32 g = 0;
+            for (u32 step = step0; step; step >>= 1)
+                if (wstart[g + step] <= k) g += step;
+            const bool first = k == wstart[g], last = k + 1u == wstart[g + 1u];
+            unsigned long long val = bits[k];
+            const bool shared = first && own[g] == 0u;
+            if (first && !shared) val |= carry[g];
+            GLOBAL_AS unsigned long long *dst = out + (dbase[g] + k);
+            if (last && tailp[g]) { // the stream word stays incomplete after this tile
+                if (shared) {
+                    if (val) __hip_atomic_fetch_or(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    nown[g] = 0u;
+                    ncarry[g] = 0ull;
+                } else {
+                    nown[g] = 1u;
+                    ncarry[g] = val;
+                }
+            } else {
+                if (shared) {
+                    if (val) __hip_atomic_fetch_or(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *dst = val;
+                }
+                if (last) {
+                    nown[g] = 1u;
+                    ncarry[g] = 0ull;
                 }
             }
         }
-        for (u32 g = wave; g < S; g += NWAVE) {
-            const u32 c = gcnt[g];
-            if (c == 0u) continue;
-            const u64 fb = (u64)gb[g] * wB;
-            const u32 s0 = (u32)(fb & 63u), nbits = c * wB;
-            const u32 nW = (s0 + nbits + 63u) >> 6;
-            if (nW <= SHORT_RUN) continue;
-            const int src0 = (int)(lbase[g] * wB);
-            for (u32 j = lane; j < nW; j += 64u) emit_word(bits, out, j, s0, fb >> 6, nbits, src0);
-            if (PERM)
+        if (PERM) {
+            for (u32 g = wave; g < S; g += NWAVE) {
+                const u32 c = gcnt[g];
                 for (u32 i = lane; i < c; i += 64u)
                     gptr(d.perm)[gb[g] + i] = (u32)(e0 + si[lbase[g] + i]);
+            }
         }
+    }
+    __syncthreads();
+    if (tid < S) { // the partial words that the chunk leaves behind
+        u32 pos = gb[tid];
+        unsigned long long cv = carry[tid];
+        u32 o = own[tid];
+        if (gcnt[tid]) {
+            pos += gcnt[tid];
+            cv = ncarry[tid];
+            o = nown[tid];
+        }
+        if (o && cv)
+            __hip_atomic_fetch_or(out + (((u64)pos * wB) >> 6), cv, __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -383,18 +423,25 @@ __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
     }
 }
 
-// clears the packed outputs that k_dscatter ORs into
-__global__ __launch_bounds__(256) void k_dzero(const DDesc *__restrict__ dd,
-                                               const u32 *__restrict__ chunk_tensor)
+// clears the stream words that k_dscatter ORs into: the first word of every (chunk, group) run,
+// which is also where the run before it ends, and the word where the stream ends
+__global__ __launch_bounds__(SS) void k_dzero(const DDesc *__restrict__ dd,
+                                              const u32 *__restrict__ chunk_tensor,
+                                              const u32 *__restrict__ chunk_tot)
 {
     const u64 chunk = blockIdx.x;
     const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
     if (d.prev_perm) return;
-    // this chunk's share of the output words (by position, not by content)
-    const u64 per = (d.out_words + d.n_chunks - 1) / d.n_chunks;
-    const u64 k0 = (chunk - d.chunk0) * per;
-    const u64 k1 = (k0 + per < d.out_words) ? k0 + per : d.out_words;
-    for (u64 k = k0 + threadIdx.x; k < k1; k += blockDim.x) gptr(d.out)[k] = 0ull;
+    const u32 g = threadIdx.x, S = d.Kp + 2u;
+    u64 pos;
+    if (g < S)
+        pos = gptr(d.group_off)[g] + chunk_tot[chunk * SS + g];
+    else if (g == S && chunk == d.chunk0)
+        pos = d.n;
+    else
+        return;
+    const u64 word = (pos * d.wB) >> 6;
+    if (word < d.out_words) gptr(d.out)[word] = 0ull;
 }
 
 // 1 if same-address LDS atomics with return are served in ascending lane order, for every pattern
@@ -444,7 +491,7 @@ hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
     PROF("k_dhist", s, k_dhist<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
     PROF("k_dgroups", s, k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot));
     if (any_scatter || any_perm)
-        PROF("k_dzero", s, k_dzero<<<(unsigned)n_chunks, 256, 0, s>>>(dd, chunk_tensor));
+        PROF("k_dzero", s, k_dzero<<<(unsigned)n_chunks, SS, 0, s>>>(dd, chunk_tensor, chunk_tot));
     if (any_scatter) {
         if (lds_ordered)
             PROF("k_dscatter", s, k_dscatter<false, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
