@@ -155,7 +155,9 @@ def main():
                                f"{n_total} values, Student-t(3)*0.015 with 0.1% channels x20, "
                                f"next step = prev + N(0,1e-4); grid bits 2..8 x prune {{0,.05,.1,.2,.4}} x "
                                f"protect {{0,1e-4,1e-3}} (105 configs), eps {eps}",
-                   "bytes_fp32": n_total * 4},
+                   "bytes_fp32": n_total * 4,
+                   "chosen_configs": {f"b{b}_p{p}_o{o}": sum(1 for c in cfgs if tuple(c) == (b, p, o))
+                                      for (b, p, o) in sorted(set(tuple(c) for c in cfgs))}},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

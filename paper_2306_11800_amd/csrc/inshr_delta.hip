@@ -49,6 +49,7 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
     const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
     const GLOBAL_AS unsigned long long *src = gptr(d.prev);
     for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
+    u32 zeros = 0u;
     for (u64 e0 = c0; e0 < c1; e0 += HTILE) {
         const u32 cnt = (c1 - e0 < (u64)HTILE) ? (u32)(c1 - e0) : (u32)HTILE;
         __syncthreads();
@@ -61,11 +62,17 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
         }
         if (tid < 2) P[2 * nw + tid] = 0u;
         __syncthreads();
-        for (u32 idx = tid; idx < cnt; idx += BLOCK) {
-            const u32 sym = lds_extract(P, idx, d.wp);
-            if (sym < S) atomicAdd(&hw[wave][sym], 1u);
+        // symbol 0 (pruned: the most frequent one when pruning is on) is counted from ballots,
+        // the others with LDS atomics
+        for (u32 base = 0; base < cnt; base += BLOCK) {
+            const u32 idx = base + tid;
+            const u32 sym = idx < cnt ? lds_extract(P, idx, d.wp) : S;
+            zeros += (u32)__popcll(__ballot(sym == 0u));
+            if (sym != 0u && sym < S) atomicAdd(&hw[wave][sym], 1u);
         }
     }
+    __syncthreads();
+    if ((tid & 63u) == 0u) hw[wave][0] = zeros;
     __syncthreads();
     for (u32 g = tid; g < SS; g += BLOCK) {
         u32 s = 0;
@@ -137,6 +144,91 @@ static_assert(TWORDS + 1 <= 3 * DBLOCK, "three words per thread cover a tile");
 // stream word that the stream position dictates, so LDS word k is stream word dbase[g] + k.  A run
 // of b bits touches at most b / 64 + 2 words.
 constexpr int BWORDS = TWORDS + 2 * SS + 2;
+constexpr int WST = NWAVE * SS;       // per-(wave, symbol) counters; the row stride is S + 1
+constexpr int CIDX = BWORDS / 8 + 2;  // one entry per 8 image words: the group of the first of them
+
+struct ScatterShared {
+    u32 P[DTILE * 9 / 32 + 8];
+    u32 C[DTILE * 9 / 32 + 8];
+    u32 wst[WST];                   // counts, then bit position in the image of (wave, symbol)
+    u32 wstart[SS + 8];             // first image word of each group's run; [S] = words in use
+    unsigned long long dbase[SS];   // image word k of group g is stream word dbase[g] + k
+    unsigned long long carry[SS], ncarry[SS]; // partial trailing word of the group
+    u32 own[SS], nown[SS];          // the group's current stream word belongs to this chunk alone
+    u32 tailp[SS];                  // this tile's run of the group ends inside a word
+    u32 gcnt[SS];                   // tile population per symbol
+    u32 gb[SS];                     // stream position of each group's next run (n < 2^32)
+    u32 wtot[8], etot[8];
+    unsigned long long hotkey;      // population << 9 | symbol, maximum over the tensor's groups
+    u16 cidx[CIDX];
+};
+
+// Sweep 1 of a tile: stable rank of every element among the equal symbols of its wave's 1024
+// elements.  Row r of a lane is element ebase + 64 r: its bit offset in the packed words moves
+// by 64 w per row, so the shift is a lane constant and the word address advances by 2 w.
+template <bool FULL, bool ORDERED>
+__device__ __forceinline__ void rank_rows(const u32 *P, const u32 *C, u32 *wrow,
+                                          unsigned long long *myslot, u32 ebase, u32 cnt, u32 S,
+                                          u32 Bm, u32 wp, u32 wc, u32 hot, u32 (&reg)[16])
+{
+    u32 hot_seen = 0u; // elements of the wave so far that hold the most frequent symbol
+    const u32 lane = threadIdx.x & 63u;
+    const u64 ltmask = (1ull << lane) - 1ull;
+    const unsigned long long lanebit = 1ull << lane;
+    const u32 offP = ebase * wp, offC = ebase * wc;
+    const u32 shP = offP & 31u, shC = offC & 31u;
+    const u32 mP = (1u << wp) - 1u, mC = (1u << wc) - 1u;
+    const u32 *pp = P + (offP >> 5), *pc = C + (offC >> 5);
+#pragma unroll
+    for (u32 rb = 0; rb < 16u; rb += 4u) {
+        u32 xp[4][2], xc[4][2];
+#pragma unroll
+        for (u32 q = 0; q < 4u; q++) { // the reads of four rows are in flight together
+            const u32 r = rb + q;
+            xp[q][0] = pp[r * 2u * wp];
+            xp[q][1] = pp[r * 2u * wp + 1u];
+            xc[q][0] = pc[r * 2u * wc];
+            xc[q][1] = pc[r * 2u * wc + 1u];
+        }
+#pragma unroll
+        for (u32 q = 0; q < 4u; q++) {
+            const u32 r = rb + q;
+            const bool valid = FULL || (ebase + r * 64u < cnt);
+            u32 sp = S, sc = 0u; // lanes past the end share the unused symbol S
+            if (valid) {
+                sp = __builtin_amdgcn_alignbit(xp[q][1], xp[q][0], shP) & mP;
+                sc = __builtin_amdgcn_alignbit(xc[q][1], xc[q][0], shC) & mC;
+                sp = sp < S - 1u ? sp : S - 1u; // clamps a malformed stream
+            }
+            u32 within; // elements of this wave with the same symbol and a lower index
+            if (ORDERED) {
+                // the most frequent symbol (the pruned one, typically a fifth of all elements) would
+                // serialise the atomic: its lanes rank themselves from the ballot instead
+                const bool is_hot = sp == hot;
+                const u64 hm = __ballot(is_hot);
+                const u32 hrank = __builtin_amdgcn_mbcnt_hi((u32)(hm >> 32),
+                                                            __builtin_amdgcn_mbcnt_lo((u32)hm, hot_seen));
+                hot_seen += (u32)__popcll(hm);
+                within = hrank;
+                if (!is_hot) within = atomicAdd(&wrow[sp], 1u);
+            } else {
+                atomicOr(&myslot[sp], lanebit);
+                const unsigned long long peers = myslot[sp];
+                const u32 rank = __popcll(peers & ltmask);
+                const u32 old = wrow[sp];
+                if (rank == 0u) {
+                    myslot[sp] = 0ull;
+                    wrow[sp] = old + (u32)__popcll(peers);
+                }
+                within = old + rank;
+            }
+            u32 dv = sp - sc;
+            if (sp < sc) dv += Bm;
+            reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
+        }
+    }
+    if (ORDERED && lane == 0u) wrow[hot] = hot_seen;
+}
 
 // ORDERED: same-address LDS atomics with return are served in ascending lane order on this device
 // (checked by k_lds_order_check before the library relies on it); one returning add then ranks an
@@ -151,24 +243,14 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                                                      const u32 *__restrict__ chunk_tensor,
                                                      const u32 *__restrict__ chunk_tot)
 {
-    __shared__ u32 P[DTILE * 9 / 32 + 8];
-    __shared__ u32 C[DTILE * 9 / 32 + 8];
+    __shared__ ScatterShared sh;
     // slot[wave][symbol]: lanes of the wave's current step that hold the symbol (sweep 1);
     // the same memory then holds the image of the tile's output words (sweep 2, output)
     __shared__ unsigned long long slot[ORDERED ? BWORDS : NWAVE * SS];
-    __shared__ u32 wst[NWAVE][SS];  // counts, then bit position in the image of (wave, symbol)
-    __shared__ u32 wel[PERM ? NWAVE : 1][SS]; // local regrouped index of (wave, symbol)
-    __shared__ u32 wstart[512];     // first image word of each group's run; [S] = words in use
-    __shared__ unsigned long long dbase[SS]; // image word k of group g is stream word dbase[g] + k
-    __shared__ unsigned long long carry[SS], ncarry[SS]; // partial trailing word of the group
-    __shared__ u32 own[SS], nown[SS]; // the group's current stream word belongs to this chunk alone
-    __shared__ u32 tailp[SS];      // this tile's run of the group ends inside a word
+    __shared__ u32 wel[PERM ? WST : 1];  // local regrouped index of (wave, symbol)
     __shared__ u32 lbase[PERM ? SS : 1]; // local regrouped index of each group's run
-    __shared__ u32 gcnt[SS];       // tile population per symbol
-    __shared__ u32 gb[SS];         // stream position of each group's next run (n < 2^32)
-    __shared__ u32 wtot[8], etot[8];
     __shared__ u16 si[PERM ? DTILE : 1]; // local indices in regrouped order
-    unsigned long long *bits = slot;
+    u32 *img = (u32 *)slot;
     static_assert(NWAVE * SS >= BWORDS, "output image fits the slot array");
 
     const u64 chunk = blockIdx.x;
@@ -177,83 +259,66 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     if (PERM != (d.perm != nullptr)) return;
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 S = d.Kp + 2u, Bm = d.B, wB = d.wB, wp = d.wp, wc = d.wc;
-    const u32 step0 = 1u << (31 - __clz(S - 1u)); // first stride of the search over wstart[0..S)
+    const u32 srow = S + 1u; // row stride of the (wave, symbol) tables
     const u64 n_tiles = (d.n + DTILE - 1) / DTILE;
     const u64 lt0 = (chunk - d.chunk0) * DCHUNK;
     const u64 lt1 = (lt0 + DCHUNK < n_tiles) ? lt0 + DCHUNK : n_tiles;
     GLOBAL_AS unsigned long long *out = gptr(d.out);
     if (tid < S) {
         const u32 g0 = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
-        gb[tid] = g0;
-        gcnt[tid] = 0u;
-        carry[tid] = 0ull;
-        own[tid] = ((((u64)g0 * wB) & 63u) == 0u) ? 1u : 0u;
+        sh.gb[tid] = g0;
+        sh.gcnt[tid] = 0u;
+        sh.carry[tid] = 0ull;
+        sh.own[tid] = ((((u64)g0 * wB) & 63u) == 0u) ? 1u : 0u;
     }
-    if (tid < 512u) wstart[tid] = 0xFFFFFFFFu;
-    const u64 ltmask = (1ull << lane) - 1ull;
-    const unsigned long long lanebit = 1ull << lane;
+    if (tid < SS + 8u) sh.wstart[tid] = 0xFFFFFFFFu;
+    if (tid == 0u) sh.hotkey = 0ull;
+    __syncthreads();
+    if (tid < S)
+        atomicMax(&sh.hotkey, ((gptr(d.group_off)[tid + 1u] - gptr(d.group_off)[tid]) << 9) | tid);
+    __syncthreads();
+    const u32 hot = __builtin_amdgcn_readfirstlane((u32)sh.hotkey & 511u);
+    u32 *wrow = sh.wst + wave * srow;
 
     auto tile_cnt = [&](u64 lt) -> u32 {
         const u64 rem = d.n - lt * (u64)DTILE;
         return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     };
+    TileWords nextP = fetch_words(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp);
+    TileWords nextC = fetch_words(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc);
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
         __syncthreads();
-        if (tid < S && gcnt[tid]) { // the previous tile's runs have been written
-            gb[tid] += gcnt[tid];
-            carry[tid] = ncarry[tid];
-            own[tid] = nown[tid];
+        if (tid < S && sh.gcnt[tid]) { // the previous tile's runs have been written
+            sh.gb[tid] += sh.gcnt[tid];
+            sh.carry[tid] = sh.ncarry[tid];
+            sh.own[tid] = sh.nown[tid];
         }
-        store_words(fetch_words(gptr(d.prev), e0, cnt, wp), cnt, wp, P);
-        store_words(fetch_words(gptr(d.cur), e0, cnt, wc), cnt, wc, C);
-        for (u32 k = tid; k < (ORDERED ? BWORDS : NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
-        for (u32 k = tid; k < SS * NWAVE; k += DBLOCK) (&wst[0][0])[k] = 0u;
+        store_words(nextP, cnt, wp, sh.P);
+        store_words(nextC, cnt, wc, sh.C);
+        {
+            const u32 nz = ORDERED ? ((cnt * wB) >> 6) + 2u * S + 2u : (u32)(NWAVE * SS);
+            for (u32 k = tid; k < nz; k += DBLOCK) slot[k] = 0ull;
+            for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u;
+        }
         __syncthreads();
-        // sweep 1: stable rank of every element among the equal symbols of its wave's 1024 elements
         u32 reg[16];
-        unsigned long long *myslot = slot + wave * SS;
         u32 ebase = wave * 1024u + lane;
-        asm volatile("" : "+v"(ebase)); // keeps the 32 per-step LDS addresses from being hoisted
-                                        // out of the tile loop and spilled
-#pragma unroll
-        for (u32 r = 0; r < 16u; r++) {
-            const u32 idx = ebase + r * 64u;
-            const bool valid = idx < cnt;
-            u32 sp = S, sc = 0u; // lanes past the end share the unused symbol S
-            if (valid) {
-                sp = lds_extract(P, idx, wp);
-                sc = lds_extract(C, idx, wc);
-                if (sp >= S) sp = S - 1u; // never for a well-formed stream
-            }
-            u32 within; // elements of this wave with the same symbol and a lower index
-            if (ORDERED) {
-                within = atomicAdd(&wst[wave][sp], 1u);
-            } else {
-                atomicOr(&myslot[sp], lanebit);
-                const unsigned long long peers = myslot[sp];
-                const u32 rank = __popcll(peers & ltmask);
-                const u32 old = wst[wave][sp];
-                if (rank == 0u) {
-                    myslot[sp] = 0ull;
-                    wst[wave][sp] = old + (u32)__popcll(peers);
-                }
-                within = old + rank;
-            }
-            u32 dv = sp + Bm - sc;
-            if (dv >= Bm) dv -= Bm;
-            reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
-        }
+        asm volatile("" : "+v"(ebase)); // keeps the per-row LDS addresses from being hoisted out of
+                                        // the tile loop and spilled
+        if (cnt == (u32)DTILE)
+            rank_rows<true, ORDERED>(sh.P, sh.C, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
+        else
+            rank_rows<false, ORDERED>(sh.P, sh.C, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
         __syncthreads();
         // counts -> positions: population of each symbol, the stream words its run touches,
         // exclusive scans over symbols, start of every (wave, symbol)
         u32 tot = 0, nW = 0, s0 = 0, preW = 0, preE = 0;
         u64 fb = 0;
         if (tid < S) {
-#pragma unroll
-            for (int wv = 0; wv < NWAVE; wv++) tot += wst[wv][tid];
-            fb = (u64)gb[tid] * wB;
+            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + tid];
+            fb = (u64)sh.gb[tid] * wB;
             s0 = (u32)(fb & 63u);
             nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
         }
@@ -262,7 +327,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 u32 v = __shfl_up(incW, o);
-                u32 e = __shfl_up(incE, o);
+                u32 e = PERM ? __shfl_up(incE, o) : 0u;
                 if ((int)lane >= o) {
                     incW += v;
                     incE += e;
@@ -271,73 +336,80 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             preW = incW - nW;
             preE = incE - tot;
             if (lane == 63u) {
-                wtot[wave] = incW;
-                etot[wave] = incE;
+                sh.wtot[wave] = incW;
+                sh.etot[wave] = incE;
             }
         }
         __syncthreads();
         if (tid < S) {
             u32 ws = preW, es = preE;
             for (u32 w2 = 0; w2 < wave; w2++) {
-                ws += wtot[w2];
-                es += etot[w2];
+                ws += sh.wtot[w2];
+                es += sh.etot[w2];
             }
-            gcnt[tid] = tot;
-            wstart[tid] = ws;
-            if (tid == S - 1u) wstart[S] = ws + nW;
-            dbase[tid] = (fb >> 6) - (u64)ws;
-            tailp[tid] = (s0 + tot * wB) & 63u;
+            sh.gcnt[tid] = tot;
+            sh.wstart[tid] = ws;
+            if (tid == S - 1u) sh.wstart[S] = ws + nW;
+            sh.dbase[tid] = (fb >> 6) - (u64)ws;
+            sh.tailp[tid] = (s0 + tot * wB) & 63u;
+            for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
             if (PERM) lbase[tid] = es;
-            u32 cwv[NWAVE];
-#pragma unroll
-            for (int wv = 0; wv < NWAVE; wv++) cwv[wv] = wst[wv][tid];
             u32 bitpos = ws * 64u + s0;
-#pragma unroll
             for (int wv = 0; wv < NWAVE; wv++) {
-                wst[wv][tid] = bitpos;
-                bitpos += cwv[wv] * wB;
+                const u32 c = sh.wst[wv * srow + tid];
+                sh.wst[wv * srow + tid] = bitpos;
+                bitpos += c * wB;
                 if (PERM) {
-                    wel[wv][tid] = es;
-                    es += cwv[wv];
+                    wel[wv * srow + tid] = es;
+                    es += c;
                 }
             }
         }
         __syncthreads();
         // sweep 2: the image of the tile's output words (all slots are zero again)
 #pragma unroll
-        for (u32 r = 0; r < 16u; r++) {
-            const u32 v = reg[r];
-            if (v >> 31) {
-                const u32 sp = v & 511u, dv = (v >> 19) & 511u, within = (v >> 9) & 1023u;
-                if (dv) {
-                    const u32 bo = wst[wave][sp] + within * wB;
-                    const u32 word = bo >> 6, sh = bo & 63u;
-                    atomicOr(&bits[word], (unsigned long long)dv << sh);
-                    if (sh + wB > 64u) atomicOr(&bits[word + 1u], (unsigned long long)dv >> (64u - sh));
+        for (u32 rb = 0; rb < 16u; rb += 8u) {
+            u32 start[8];
+#pragma unroll
+            for (u32 q = 0; q < 8u; q++) start[q] = wrow[reg[rb + q] & 511u];
+#pragma unroll
+            for (u32 q = 0; q < 8u; q++) {
+                const u32 r = rb + q;
+                const u32 v = reg[r];
+                const u32 dv = (v >> 19) & 511u, within = (v >> 9) & 1023u;
+                if ((v >> 31) && dv) {
+                    const u32 bo = start[q] + within * wB;
+                    const u32 word = bo >> 5, shf = bo & 31u;
+                    atomicOr(&img[word], dv << shf);
+                    if (shf + wB > 32u) atomicOr(&img[word + 1u], dv >> (32u - shf));
                 }
-                if (PERM) si[wel[wave][sp] + within] = (u16)(wave * 1024u + r * 64u + lane);
+                if (PERM && (v >> 31))
+                    si[wel[wave * srow + (v & 511u)] + within] = (u16)(wave * 1024u + r * 64u + lane);
             }
+        }
+        if (lt + 1 < lt1) { // the next tile's words travel while this tile's output is written
+            nextP = fetch_words(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp);
+            nextC = fetch_words(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc);
         }
         __syncthreads();
         // one thread per output word
-        const u32 n_img = wstart[S];
+        const u32 n_img = sh.wstart[S];
         for (u32 k = tid; k < n_img; k += DBLOCK) {
-            u32 g = 0;
-            for (u32 step = step0; step; step >>= 1)
-                if (wstart[g + step] <= k) g += step;
-            const bool first = k == wstart[g], last = k + 1u == wstart[g + 1u];
-            unsigned long long val = bits[k];
-            const bool shared = first && own[g] == 0u;
-            if (first && !shared) val |= carry[g];
-            GLOBAL_AS unsigned long long *dst = out + (dbase[g] + k);
-            if (last && tailp[g]) { // the stream word stays incomplete after this tile
+            u32 g = sh.cidx[k >> 3];
+            while (sh.wstart[g + 1u] <= k) g++;
+            const bool first = k == sh.wstart[g], last = k + 1u == sh.wstart[g + 1u];
+            unsigned long long val = slot[k];
+            const bool shared = first && sh.own[g] == 0u;
+            if (first && !shared) val |= sh.carry[g];
+            GLOBAL_AS unsigned long long *dst = out + (sh.dbase[g] + k);
+            if (last && sh.tailp[g]) { // the stream word stays incomplete after this tile
                 if (shared) {
                     if (val) __hip_atomic_fetch_or(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    nown[g] = 0u;
-                    ncarry[g] = 0ull;
+                    sh.nown[g] = 0u;
+                    sh.ncarry[g] = 0ull;
                 } else {
-                    nown[g] = 1u;
-                    ncarry[g] = val;
+                    sh.nown[g] = 1u;
+                    sh.ncarry[g] = val;
                 }
             } else {
                 if (shared) {
@@ -346,28 +418,28 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                     *dst = val;
                 }
                 if (last) {
-                    nown[g] = 1u;
-                    ncarry[g] = 0ull;
+                    sh.nown[g] = 1u;
+                    sh.ncarry[g] = 0ull;
                 }
             }
         }
         if (PERM) {
             for (u32 g = wave; g < S; g += NWAVE) {
-                const u32 c = gcnt[g];
+                const u32 c = sh.gcnt[g];
                 for (u32 i = lane; i < c; i += 64u)
-                    gptr(d.perm)[gb[g] + i] = (u32)(e0 + si[lbase[g] + i]);
+                    gptr(d.perm)[sh.gb[g] + i] = (u32)(e0 + si[lbase[g] + i]);
             }
         }
     }
     __syncthreads();
     if (tid < S) { // the partial words that the chunk leaves behind
-        u32 pos = gb[tid];
-        unsigned long long cv = carry[tid];
-        u32 o = own[tid];
-        if (gcnt[tid]) {
-            pos += gcnt[tid];
-            cv = ncarry[tid];
-            o = nown[tid];
+        u32 pos = sh.gb[tid];
+        unsigned long long cv = sh.carry[tid];
+        u32 o = sh.own[tid];
+        if (sh.gcnt[tid]) {
+            pos += sh.gcnt[tid];
+            cv = sh.ncarry[tid];
+            o = sh.nown[tid];
         }
         if (o && cv)
             __hip_atomic_fetch_or(out + (((u64)pos * wB) >> 6), cv, __ATOMIC_RELAXED,
