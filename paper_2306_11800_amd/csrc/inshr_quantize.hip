@@ -59,22 +59,92 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
     }
 }
 
+// The symbol is a step function of the key: the 255 bin boundaries and the four class edges
+// (first quantized negative key, first pruned key, first quantized positive key, first protected
+// positive key) cut the key axis into at most 260 slots, each with one symbol.  A table over the
+// 15-bit key prefix gives the number of breakpoints below the prefix; four comparisons finish the
+// search (prefixes with more than four breakpoints take a short loop).
+constexpr int QBP = 264;          // breakpoints, padded
+constexpr int PKW = 256 * 9;      // most packed words of a tile
+constexpr int SM_QUANT = L1_BINS * 2 + 2 * PKW * 8;
+
+struct QuantTables {
+    u32 bp[QBP + 8];   // sorted breakpoints, then 0xFFFFFFFF
+    u32 raw[QBP];      // boundaries of the configuration, then the class edges
+    u16 symtab[QBP];   // symbol of slot s = #{breakpoints <= key}
+    u32 wcnt[2][64];   // protected values per (quarter j, wave) of the tile, per buffer
+};
+
+template <bool FULL>
+__device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, const u16 *ctab,
+                                              const QuantTables &qt, u32 n_bp, u32 w,
+                                              unsigned long long *pk, u32 *wcnt, u32 &omask,
+                                              u32 (&pre)[4])
+{
+    const u32 tid = threadIdx.x, lane = tid & 63u;
+    omask = 0u;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        u32 e[4], key[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            key[c] = key_of_bits(canon_bits(__float_as_uint(v[4 * j + c])));
+            e[c] = ctab[key[c] >> L1_SHIFT];
+        }
+        unsigned long long piece = 0ull;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const u32 lo = e[c] & 511u;
+            u32 s = lo;
+            s += (qt.bp[lo] <= key[c]) ? 1u : 0u;
+            s += (qt.bp[lo + 1u] <= key[c]) ? 1u : 0u;
+            s += (qt.bp[lo + 2u] <= key[c]) ? 1u : 0u;
+            s += (qt.bp[lo + 3u] <= key[c]) ? 1u : 0u;
+            if (e[c] >> 15)
+                while (s < n_bp && qt.bp[s] <= key[c]) s++;
+            u32 sym = qt.symtab[s];
+            if (!FULL && !((mask >> (4 * j + c)) & 1u)) sym = 0u;
+            piece |= (unsigned long long)sym << (c * w);
+            omask |= (sym == 1u ? 1u : 0u) << (4 * j + c);
+        }
+        const u32 bitoff = 4u * (tid + 1024u * j) * w;
+        const u32 word = bitoff >> 6, shf = bitoff & 63u;
+        if (piece) {
+            atomicOr(&pk[word], piece << shf);
+            if (shf + 4u * w > 64u) atomicOr(&pk[word + 1u], piece >> (64u - shf));
+        }
+        // protected values of this wave's 256 elements: total, and those of lower lanes
+        const u32 cj = __popc((omask >> (4 * j)) & 0xFu);
+        u32 tot = 0u;
+        pre[j] = 0u;
+        if (__ballot(cj != 0u)) {
+            const u64 m0 = __ballot(cj & 1u), m1 = __ballot(cj & 2u), m2 = __ballot(cj & 4u);
+            pre[j] = __builtin_amdgcn_mbcnt_hi((u32)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((u32)m0, 0u)) +
+                     2u * __builtin_amdgcn_mbcnt_hi((u32)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((u32)m1, 0u)) +
+                     4u * __builtin_amdgcn_mbcnt_hi((u32)(m2 >> 32), __builtin_amdgcn_mbcnt_lo((u32)m2, 0u));
+            tot = (u32)__popcll(m0) + 2u * (u32)__popcll(m1) + 4u * (u32)__popcll(m2);
+        }
+        if (lane == 0u) wcnt[j * 16 + (tid >> 6)] = tot;
+    }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, int nT,
                                                  const u64 *__restrict__ wg_tile0,
                                                  const GridDesc *__restrict__ gd,
                                                  const QDesc *__restrict__ qd_by_tensor, Bufs B)
 {
-    __shared__ u32 bnd[256];
-    __shared__ u16 ctab[COARSE]; // per 12-bit key prefix: boundaries below it | boundaries up to its end << 8
-    __shared__ unsigned long long pk[256 * 9];
-    __shared__ u32 wtot[4][BLOCK / 64];
-    __shared__ u32 wbase[4][BLOCK / 64];
+    extern __shared__ u32 smem[];
+    u16 *ctab = reinterpret_cast<u16 *>(smem); // [L1_BINS]: breakpoints below the prefix | many << 15
+    unsigned long long *pk0 = reinterpret_cast<unsigned long long *>(smem + L1_BINS / 2); // [2][PKW]
+    __shared__ QuantTables qt;
 
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
+    for (u32 k = tid; k < 2u * PKW; k += BLOCK) pk0[k] = 0ull;
     int t = find_tensor(td, nT, tile_lo);
     u64 tile = tile_lo;
+    u32 buf = 0u;
     while (tile < tile_hi) {
         const TDesc d = td[t];
         const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
@@ -92,99 +162,106 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         const u32 o = gd->pair_o[pair];
         const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + o];
         const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
+        const u32 n_bnd = K - 1u, n_bp = n_bnd + 4u;
         __syncthreads();
-        if (tid < 256u) bnd[tid] = (tid + 1u < K) ? tk[((tid + 1u) << sh) - 1u] : 0xFFFFFFFFu;
-        __syncthreads();
-        for (u32 c = tid; c < (u32)COARSE; c += BLOCK) {
-            const u32 first = c << COARSE_SHIFT, last = first | ((1u << COARSE_SHIFT) - 1u);
-            u32 lo = 0u, hi = 0u; // lo = #{t < first}, hi = #{t <= last}
-            for (u32 step = K >> 1; step > 0u; step >>= 1) {
-                if (bnd[lo + step - 1u] < first) lo += step;
-                if (bnd[hi + step - 1u] <= last) hi += step;
-            }
-            ctab[c] = (u16)(lo | (hi << 8));
+        if (tid < n_bnd) qt.raw[tid] = tk[((tid + 1u) << sh) - 1u];
+        if (tid == 0u) {
+            qt.raw[n_bnd] = key_neg(tau_o);           // first quantized negative key
+            qt.raw[n_bnd + 1u] = key_neg(tau_p) + 1u; // first pruned key
+            qt.raw[n_bnd + 2u] = key_pos(tau_p);      // first quantized positive key
+            qt.raw[n_bnd + 3u] = key_pos(tau_o) + 1u; // first protected positive key (wraps to 0
+                                                      // when nothing is protected)
         }
         __syncthreads();
+        if (tid < n_bp) { // sort by counting the smaller ones
+            const u32 x = qt.raw[tid];
+            u32 r = 0u;
+            for (u32 i = 0; i < n_bp; i++) {
+                const u32 y = qt.raw[i];
+                r += (y < x || (y == x && i < tid)) ? 1u : 0u;
+            }
+            qt.bp[r] = x;
+        } else if (tid < (u32)QBP + 8u) {
+            qt.bp[tid] = 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        if (tid <= n_bp) { // symbol of each slot, from its smallest key
+            const u32 rep = tid ? qt.bp[tid - 1u] : 0u;
+            const u32 m = mag_of_key(rep);
+            u32 sym;
+            if (m < tau_p) {
+                sym = 0u;
+            } else if (m > tau_o) {
+                sym = 1u;
+            } else {
+                u32 lo = 0u, hi = n_bnd; // #{boundaries <= rep}
+                while (lo < hi) {
+                    const u32 mid = (lo + hi) >> 1;
+                    if (qt.raw[mid] <= rep)
+                        lo = mid + 1u;
+                    else
+                        hi = mid;
+                }
+                sym = 2u + lo;
+            }
+            qt.symtab[tid] = (u16)sym;
+        }
+        for (u32 c = tid; c < (u32)L1_BINS; c += BLOCK) { // breakpoints below each key prefix
+            const u32 first = c << L1_SHIFT;
+            u32 lo = 0u, hi = n_bp;
+            while (lo < hi) {
+                const u32 mid = (lo + hi) >> 1;
+                if (qt.bp[mid] < first)
+                    lo = mid + 1u;
+                else
+                    hi = mid;
+            }
+            ctab[c] = (u16)lo;
+        }
+        __syncthreads();
+        for (u32 c = tid; c < (u32)L1_BINS; c += BLOCK) {
+            const u32 lo = ctab[c] & 511u;
+            const u32 nx = (c + 1u < (u32)L1_BINS) ? (ctab[c + 1u] & 511u) : n_bp;
+            if (nx - lo > 4u) ctab[c] = (u16)(lo | 0x8000u);
+        }
+        __syncthreads();
+        GLOBAL_AS unsigned long long *packed = gptr(q.packed);
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
-            const u32 n_words = (cnt * w + 63u) >> 6;
-            for (u32 k = tid; k < 256u * w; k += BLOCK) pk[k] = 0ull;
             float v[16];
             const u32 mask = load_tile(d, e0, cnt, v);
-            const u32 n_out_tile = B.tile_out[tile * MAX_FRAC + o];
+            unsigned long long *pk = pk0 + buf * PKW;
+            u32 *wcnt = qt.wcnt[buf];
+            u32 omask, pre[4];
+            if (mask == 0xFFFFu)
+                classify_tile<true>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);
+            else
+                classify_tile<false>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);
             __syncthreads();
-            u32 omask = 0u;
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                unsigned long long piece = 0ull;
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    const int i = 4 * j + c;
-                    u32 s = 0u;
-                    if ((mask >> i) & 1u) {
-                        const u32 b = canon_bits(__float_as_uint(v[i]));
-                        const u32 m = b & 0x7fffffffu;
-                        if (m < tau_p) {
-                            s = 0u;
-                        } else if (m > tau_o) {
-                            s = 1u;
-                            omask |= 1u << i;
-                        } else {
-                            const u32 key = key_of_bits(b);
-                            const u32 e = ctab[key >> COARSE_SHIFT];
-                            u32 lo = e & 255u, hi = e >> 8;
-                            while (lo < hi) { // bin = #{t <= key}, known to lie in [lo, hi]
-                                const u32 mid = (lo + hi) >> 1;
-                                if (bnd[mid] <= key)
-                                    lo = mid + 1u;
-                                else
-                                    hi = mid;
-                            }
-                            s = 2u + lo;
-                        }
-                    }
-                    piece |= (unsigned long long)s << (c * w);
-                }
-                const u32 bitoff = 4u * (tid + 1024u * j) * w;
-                const u32 word = bitoff >> 6, shf = bitoff & 63u;
-                if (piece) {
-                    atomicOr(&pk[word], piece << shf);
-                    if (shf + 4u * w > 64u) atomicOr(&pk[word + 1u], piece >> (64u - shf));
-                }
+            // the tile's words leave, and the buffer is clean for the tile after the next
+            const u32 n_words = (cnt * w + 63u) >> 6;
+            GLOBAL_AS unsigned long long *dst = packed + (tile - d.tile0) * (u64)(256u * w);
+            for (u32 k = tid; k < 256u * w; k += BLOCK) {
+                const unsigned long long x = pk[k];
+                if (k < n_words) dst[k] = x;
+                pk[k] = 0ull;
             }
-            if (n_out_tile) {
-                // rank of each protected value in index order: (j, thread, c)
-                u32 incl[4], cj[4];
+            // protected values in ascending index: quarter j, wave, lane, c
+            const u32 wc = wcnt[lane];
+            u32 inc = wc;
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    cj[j] = __popc((omask >> (4 * j)) & 0xFu);
-                    u32 x = cj[j];
-#pragma unroll
-                    for (int ofs = 1; ofs < 64; ofs <<= 1) {
-                        u32 y = __shfl_up(x, ofs);
-                        if ((int)lane >= ofs) x += y;
-                    }
-                    incl[j] = x;
-                    if (lane == 63u) wtot[j][wave] = x;
-                }
-                __syncthreads();
-                if (tid < 64u) {
-                    const u32 j = tid >> 4, wv = tid & 15u;
-                    u32 x = wtot[j][wv], inc = x;
-#pragma unroll
-                    for (int ofs = 1; ofs < 64; ofs <<= 1) {
-                        u32 y = __shfl_up(inc, ofs);
-                        if ((int)tid >= ofs) inc += y;
-                    }
-                    wbase[j][wv] = inc - x;
-                }
-                __syncthreads();
+            for (int ofs = 1; ofs < 64; ofs <<= 1) {
+                const u32 y = __shfl_up(inc, ofs);
+                if ((int)lane >= ofs) inc += y;
+            }
+            if (__builtin_amdgcn_readlane(inc, 63) != 0u) {
+                const u32 excl = inc - wc;
                 const u64 obase = B.tile_off[tile];
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
-                    u32 r = wbase[j][wave] + incl[j] - cj[j];
+                    u32 r = __builtin_amdgcn_readlane(excl, j * 16 + wave) + pre[j];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         const int i = 4 * j + c;
@@ -199,10 +276,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                     }
                 }
             }
-            __syncthreads();
-            GLOBAL_AS unsigned long long *dst = gptr(q.packed) + (tile - d.tile0) * (u64)(256u * w);
-            for (u32 k = tid; k < n_words; k += BLOCK) dst[k] = pk[k];
-            __syncthreads();
+            buf ^= 1u;
         }
         t++;
     }
@@ -215,10 +289,12 @@ hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStrea
         hipError_t e = hipFuncSetAttribute((const void *)k_qprep,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (L2_BINS + 4) * 4);
         if (e) return e;
+        e = hipFuncSetAttribute((const void *)k_quant, hipFuncAttributeMaxDynamicSharedMemorySize, SM_QUANT);
+        if (e) return e;
         attr = true;
     }
     PROF("k_qprep", s, k_qprep<<<bt.nT, BLOCK, (L2_BINS + 4) * 4, s>>>(bt.td, bt.gd, qd, qi, bt.bufs));
-    PROF("k_quant", s, k_quant<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs));
+    PROF("k_quant", s, k_quant<<<bt.n_wg, BLOCK, SM_QUANT, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs));
     return hipGetLastError();
 }
 
