@@ -331,6 +331,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         bt.n_grp_total = (u32 *)(db + o_ngt);
         bt.n_units = (int)units;
         bt.n_bucket_blocks = c->n_cu * 2;
+        bt.lds_ordered = c->lds_ordered;
         bt.nT = (int)nT;
         bt.n_wg = n_wg;
         bt.n_pairs = g.n_pairs;
@@ -427,8 +428,9 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
         int v = atoi(e);
         if (v >= 1 && v <= 16) c->wg_per_cu = v;
     }
-    // the delta kernels have a fast path that needs same-address LDS atomics to be served in lane
-    // order; it is used only if this device passes the check (INSHR_DELTA_SLOTS=1 forces it off)
+    // the delta scatter and the group sort have a fast path that needs same-address LDS atomics to
+    // be served in lane order; it is used only if this device passes the check
+    // (INSHR_NO_LDS_ORDER=1, or its older name INSHR_DELTA_SLOTS=1, forces it off)
     {
         u32 *viol = nullptr;
         u32 h = 1;
@@ -440,8 +442,9 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
                 c->lds_ordered = (h == 0);
             (void)hipFree(viol);
         }
-        if (const char *e = getenv("INSHR_DELTA_SLOTS"))
-            if (atoi(e) != 0) c->lds_ordered = false;
+        for (const char *name : {"INSHR_NO_LDS_ORDER", "INSHR_DELTA_SLOTS"})
+            if (const char *e = getenv(name))
+                if (atoi(e) != 0) c->lds_ordered = false;
     }
     *out = c;
     return INSHR_OK;

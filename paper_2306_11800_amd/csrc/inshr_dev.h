@@ -167,69 +167,6 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
-// k-th smallest (0-based) of a[0..c) under the order of keys (by_mag == false) or of their
-// magnitudes (by_mag == true); one wavefront, all lanes return the value.  Radix select from the
-// highest bit that differs; lists of up to 1024 values are held in registers.
-template <class Ptr>
-__device__ inline u32 wave_select(Ptr a, u32 c, u32 k, bool by_mag)
-{
-    const u32 lane = threadIdx.x & 63u;
-    u32 r[16];
-    const bool cached = c <= 1024u;
-    u32 vo = 0u, va = 0xFFFFFFFFu;
-    if (cached) {
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-            u32 idx = lane + 64u * i;
-            u32 v = 0u;
-            if (idx < c) {
-                v = a[idx];
-                if (by_mag) v = mag_of_key(v);
-                vo |= v;
-                va &= v;
-            }
-            r[i] = v;
-        }
-    } else {
-        for (u32 i = lane; i < c; i += 64u) {
-            u32 v = a[i];
-            if (by_mag) v = mag_of_key(v);
-            vo |= v;
-            va &= v;
-        }
-    }
-    vo = wave_or(vo);
-    va = wave_and(va);
-    u32 diff = vo ^ va;
-    if (diff == 0u) return va;
-    int hb = 31 - __clz(diff);
-    u32 pref = va & ~((2u << hb) - 1u); // bits above hb are common to all
-    for (int b = hb; b >= 0; b--) {
-        const u32 himask = ~((2u << b) - 1u);
-        const u32 bit = 1u << b;
-        u32 cnt = 0u;
-        if (cached) {
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                u32 idx = lane + 64u * i;
-                cnt += (idx < c && ((r[i] ^ pref) & himask) == 0u && (r[i] & bit) == 0u) ? 1u : 0u;
-            }
-        } else {
-            for (u32 i = lane; i < c; i += 64u) {
-                u32 v = a[i];
-                if (by_mag) v = mag_of_key(v);
-                cnt += (((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
-            }
-        }
-        cnt = wave_sum(cnt);
-        if (k >= cnt) {
-            k -= cnt;
-            pref |= bit;
-        }
-    }
-    return pref;
-}
-
 // Exclusive scan of in[0..n) (n <= 32 * BLOCK) into out[0..n], out[n] = total; whole workgroup of
 // BLOCK threads; tmp is LDS scratch of BLOCK/64 + 1 words.  in/out may alias only if equal.
 __device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)

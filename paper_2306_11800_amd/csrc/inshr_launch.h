@@ -60,6 +60,7 @@ struct Batch {
     int n_wg;
     int n_units;
     int n_bucket_blocks;
+    bool lds_ordered;    // same-address LDS atomics return in lane order on this device
     u32 n_pairs, n_cfg;
     u64 n_tiles;
     Bufs bufs;

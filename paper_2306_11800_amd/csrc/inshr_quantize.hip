@@ -226,12 +226,21 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         }
         __syncthreads();
         GLOBAL_AS unsigned long long *packed = gptr(q.packed);
+        auto tile_cnt = [&](u64 tl) -> u32 {
+            const u64 rem = d.n - (tl - d.tile0) * (u64)TILE;
+            return rem < (u64)TILE ? (u32)rem : (u32)TILE;
+        };
+        float vn[16];
+        u32 maskn = load_tile(d, (tile - d.tile0) * (u64)TILE, tile_cnt(tile), vn);
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
-            const u64 rem = d.n - e0;
-            const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+            const u32 cnt = tile_cnt(tile);
             float v[16];
-            const u32 mask = load_tile(d, e0, cnt, v);
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = vn[i];
+            const u32 mask = maskn;
+            if (tile + 1 < stop) // the next tile travels while this one is classified
+                maskn = load_tile(d, e0 + TILE, tile_cnt(tile + 1), vn);
             unsigned long long *pk = pk0 + buf * PKW;
             u32 *wcnt = qt.wcnt[buf];
             u32 omask, pre[4];

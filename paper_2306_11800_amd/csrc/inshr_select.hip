@@ -734,70 +734,8 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 // exact boundaries: residual-rank element of the boundary's bin, searched in the bin's group
 // ------------------------------------------------------------------------------------------
-constexpr int BUCKET_CAP = 16384;  // keys of a group held in LDS
-constexpr int MATCH_CAP = 1024;    // keys of one bin a wave sets aside in LDS
-
-// k-th smallest of the keys in [klo, khi] among a[0..n) (LDS or global); one wavefront.
-// *found = number of keys in the range.  The keys of the range are set aside in the wave's LDS
-// scratch when they fit there (then a register-resident radix select finishes); otherwise every
-// round of the radix select rescans the list.
-template <class Ptr>
-__device__ inline u32 wave_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, LDS_AS u32 *scratch,
-                                        u32 *found)
-{
-    const u32 lane = threadIdx.x & 63u;
-    u32 total = 0u; // wave-uniform
-    u32 vo = 0u, va = 0xFFFFFFFFu;
-    for (u32 i0 = 0; i0 < n; i0 += 256u) {
-        u32 v[4];
-        bool in[4];
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const u32 i = i0 + lane + 64u * j;
-            v[j] = (i < n) ? a[i] : 0u;
-            in[j] = (i < n) && v[j] >= klo && v[j] <= khi;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const u64 m = __ballot(in[j]);
-            if (m == 0ull) continue;
-            if (in[j]) {
-                const u32 pos = total + __popcll(m & ((1ull << lane) - 1ull));
-                if (pos < (u32)MATCH_CAP) scratch[pos] = v[j];
-                vo |= v[j];
-                va &= v[j];
-            }
-            total += (u32)__popcll(m);
-        }
-    }
-    *found = total;
-    if (total == 0u) return 0u;
-    if (total <= (u32)MATCH_CAP) return wave_select((const LDS_AS u32 *)scratch, total, k, false);
-    vo = wave_or(vo);
-    va = wave_and(va);
-    const u32 diff = vo ^ va;
-    if (diff == 0u) return va;
-    const int hb = 31 - __clz(diff);
-    u32 pref = va & ~((2u << hb) - 1u);
-    for (int b = hb; b >= 0; b--) {
-        const u32 himask = ~((2u << b) - 1u), bit = 1u << b;
-        u32 cnt = 0u;
-        for (u32 i0 = 0; i0 < n; i0 += 256u) {
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const u32 i = i0 + lane + 64u * j;
-                const u32 v = (i < n) ? a[i] : 0u;
-                cnt += (i < n && v >= klo && v <= khi && ((v ^ pref) & himask) == 0u && (v & bit) == 0u) ? 1u : 0u;
-            }
-        }
-        cnt = wave_sum(cnt);
-        if (k >= cnt) {
-            k -= cnt;
-            pref |= bit;
-        }
-    }
-    return pref;
-}
+constexpr int BUCKET_CAP = 16384;  // keys of a group sorted in LDS
+constexpr int SORT_ROWS = BUCKET_CAP / BLOCK; // rows of 64 keys per wave and pass, at most
 
 // k-th smallest of the keys in [klo, khi] (khi - klo + 1 a power of two) among a[0..n), by the whole
 // workgroup: radix select, 8 bits per round, LDS histogram.  *found = keys in the range (in sh[2]).
@@ -863,20 +801,50 @@ __device__ inline u32 block_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, 
     return klo + P;
 }
 
+// Stable rank of a key's digit among the keys its wave has seen in this pass.  ORDERED: one
+// returning LDS add (same-address LDS atomics are served in ascending lane order, verified when the
+// context is created).  Otherwise lanes with equal digits find each other with eight ballots.
+template <bool ORDERED>
+__device__ __forceinline__ u32 digit_rank(u32 *wcnt, u32 digit, bool valid)
+{
+    if (ORDERED) {
+        u32 r = 0u;
+        if (valid) r = atomicAdd(&wcnt[digit], 1u);
+        return r;
+    }
+    const u32 lane = threadIdx.x & 63u;
+    u64 peers = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; b++) {
+        const bool bit = (digit >> b) & 1u;
+        const u64 m = __ballot(bit);
+        peers &= bit ? m : ~m;
+    }
+    const u32 rank = __popcll(peers & ((1ull << lane) - 1ull));
+    u32 old = 0u;
+    if (valid) old = wcnt[digit];
+    if (valid && rank == 0u) wcnt[digit] = old + (u32)__popcll(peers);
+    return old + rank;
+}
+
+// One group of active bins per step: its keys are sorted in LDS (least significant digit first,
+// 8 bits per pass, only the digits in which the keys differ), and every boundary of the group is
+// read at its rank: offset of its bin inside the group + residual rank inside the bin.
+template <bool ORDERED>
 __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT, u32 TG,
                                                   const u32 *__restrict__ grp_list,
                                                   const u32 *__restrict__ n_grp_total, Bufs B)
 {
     extern __shared__ u32 smem[];
-    u32 *keys = smem;                 // [BUCKET_CAP]
-    u32 *scratch = smem + BUCKET_CAP; // [16][MATCH_CAP]
-    __shared__ u32 tlist[TGT_STRIDE]; // targets of this group: small bins from the front, large
-                                      // bins from the back
-    __shared__ u32 s_nt, s_nl;
+    u32 *bufA = smem;                      // [BUCKET_CAP]
+    u32 *bufB = smem + BUCKET_CAP;         // [BUCKET_CAP]
+    u32 *wcount = smem + 2 * BUCKET_CAP;   // [16 waves][256 digits]
     __shared__ u32 hist[256];
     __shared__ u32 sh[3];
+    __shared__ u32 s_diff;
+    __shared__ u32 wsum[4];
 
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 total = *n_grp_total;
     for (u32 idx = blockIdx.x; idx < total; idx += gridDim.x) {
         const u32 packed = grp_list[idx];
@@ -886,68 +854,128 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
         const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
         const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
         __syncthreads();
-        if (tid == 0) {
-            s_nt = 0u;
-            s_nl = 0u;
-        }
+        if (tid == 0) s_diff = 0u;
         __syncthreads();
         if (gend <= goff) continue; // no keys in this window of the order
         const u32 n = gend - goff;
         const u32 *src = B.pool2 + td[t].pool_thr + goff;
-        const bool in_lds = n <= (u32)BUCKET_CAP;
-        if (in_lds)
-            for (u32 i = tid; i < n; i += BLOCK) keys[i] = src[i];
         const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
         const u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
+        const u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
+        const u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
+        const u32 *thi = B.tgt_khi + (size_t)t * TGT_STRIDE;
+        u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
         const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+        const u32 *binfo = B.binfo + (size_t)t * L2_BINS;
         const u32 zbin = st->zbin, nz = (u32)st->n_zero;
-        for (u32 i = tid; i < TG; i += BLOCK) {
-            const u32 bin = tb[i];
-            if (bin != RESOLVED && tg[i] == g) {
-                const u32 pop = h2[bin] - (bin == zbin ? nz : 0u);
-                if (pop <= (u32)MATCH_CAP)
-                    tlist[atomicAdd(&s_nt, 1u)] = i;
-                else
-                    tlist[TGT_STRIDE - 1u - atomicAdd(&s_nl, 1u)] = i;
+        if (n <= (u32)BUCKET_CAP) {
+            const u32 first = gptr(src)[0];
+            u32 diff = 0u;
+            for (u32 i = tid; i < n; i += BLOCK) {
+                const u32 k = gptr(src)[i];
+                bufA[i] = k;
+                diff |= k ^ first;
             }
-        }
-        __syncthreads();
-        const u32 nt = s_nt, nl = s_nl;
-        // boundaries in small bins: one wave each
-        LDS_AS u32 *wscratch = (LDS_AS u32 *)(scratch + wave * MATCH_CAP);
-        for (u32 k = wave; k < nt; k += BLOCK / 64) {
-            const u32 i = tlist[k];
-            const u32 bin = tb[i];
-            const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
-            const u32 klo = B.tgt_klo[(size_t)t * TGT_STRIDE + i], khi = B.tgt_khi[(size_t)t * TGT_STRIDE + i];
-            const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
-            u32 found = 0u;
-            // the zero key is never gathered: it is excluded from the range when the bin holds it
-            const u32 kl = (klo == ZERO_KEY) ? klo + 1u : klo;
-            const u32 key = in_lds ? wave_select_range((const LDS_AS u32 *)keys, n, kl, khi, res, wscratch, &found)
-                                   : wave_select_range((const GLOBAL_AS u32 *)src, n, kl, khi, res, wscratch, &found);
-            if (lane == 0u) {
-                if (found != expect || res >= found)
-                    atomicOr(&st->internal_err, 128u);
-                else
-                    B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
-            }
-        }
-        // boundaries in large bins: the whole workgroup, one after the other
-        for (u32 k = 0; k < nl; k++) {
+            diff = wave_or(diff);
+            if (lane == 0u && diff) atomicOr(&s_diff, diff);
             __syncthreads();
-            const u32 i = tlist[TGT_STRIDE - 1u - k];
-            const u32 bin = tb[i];
-            const u32 res = B.tgt_res[(size_t)t * TGT_STRIDE + i];
-            const u32 klo = B.tgt_klo[(size_t)t * TGT_STRIDE + i], khi = B.tgt_khi[(size_t)t * TGT_STRIDE + i];
-            const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
-            const u32 key = in_lds ? block_select_range((const LDS_AS u32 *)keys, n, klo, khi, res, klo == ZERO_KEY, hist, sh)
-                                   : block_select_range((const GLOBAL_AS u32 *)src, n, klo, khi, res, klo == ZERO_KEY, hist, sh);
-            if (tid == 0u) {
-                if (sh[2] != expect || res >= expect)
-                    atomicOr(&st->internal_err, 128u);
+            const u32 dbits = s_diff;
+            u32 *from = bufA, *to = bufB;
+            const u32 rows = (n + BLOCK - 1u) / BLOCK; // rows of 64 keys per wave
+            const u32 chunk = rows * 64u;
+            u32 *wcnt = wcount + wave * 256u;
+            for (u32 shift = 0; shift < 32u && (dbits >> shift) != 0u; shift += 8u) {
+                if (((dbits >> shift) & 255u) == 0u) continue; // this digit is the same in all keys
+                for (u32 i = tid; i < 16u * 256u; i += BLOCK) wcount[i] = 0u;
+                __syncthreads();
+                u32 kreg[SORT_ROWS], rreg[SORT_ROWS];
+#pragma unroll
+                for (u32 r = 0; r < (u32)SORT_ROWS; r++) {
+                    kreg[r] = 0u;
+                    rreg[r] = 0u;
+                    if (r < rows) {
+                        const u32 i = wave * chunk + r * 64u + lane;
+                        const bool valid = i < n;
+                        const u32 k = valid ? from[i] : 0u;
+                        kreg[r] = k;
+                        rreg[r] = digit_rank<ORDERED>(wcnt, (k >> shift) & 255u, valid);
+                    }
+                }
+                __syncthreads();
+                // start of every (digit, wave) run: digits in order, waves in order inside a digit
+                u32 tot = 0u, excl = 0u;
+                if (tid < 256u) {
+#pragma unroll
+                    for (int w = 0; w < 16; w++) tot += wcount[w * 256 + tid];
+                    u32 inc = tot;
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const u32 v = __shfl_up(inc, o);
+                        if ((int)lane >= o) inc += v;
+                    }
+                    excl = inc - tot;
+                    if (lane == 63u) wsum[wave] = inc;
+                }
+                __syncthreads();
+                if (tid < 256u) {
+                    u32 run = excl;
+                    for (u32 w = 0; w < wave; w++) run += wsum[w];
+#pragma unroll
+                    for (int w = 0; w < 16; w++) {
+                        const u32 c = wcount[w * 256 + tid];
+                        wcount[w * 256 + tid] = run;
+                        run += c;
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (u32 r = 0; r < (u32)SORT_ROWS; r++) {
+                    if (r < rows) {
+                        const u32 i = wave * chunk + r * 64u + lane;
+                        if (i < n) to[wcnt[(kreg[r] >> shift) & 255u] + rreg[r]] = kreg[r];
+                    }
+                }
+                __syncthreads();
+                u32 *x = from;
+                from = to;
+                to = x;
+            }
+            // every boundary of the group, at its rank
+            for (u32 i = tid; i < TG; i += BLOCK) {
+                const u32 bin = tb[i];
+                if (bin == RESOLVED || tg[i] != g) continue;
+                const u32 pop = h2[bin] - (bin == zbin ? nz : 0u);
+                const u32 res = tr[i];
+                const u32 pos = binfo[bin] - goff + res;
+                bool ok = res < pop && pos < n;
+                u32 key = 0u;
+                if (ok) {
+                    key = from[pos];
+                    ok = key >= tlo[i] && key <= thi[i];
+                }
+                if (ok)
+                    tk[i] = key;
                 else
-                    B.tgt_key[(size_t)t * TGT_STRIDE + i] = key;
+                    atomicOr(&st->internal_err, 128u);
+            }
+        } else {
+            // a group too large for LDS (one bin of very many keys): every boundary is selected
+            // from the group's keys in device memory by the whole workgroup
+            for (u32 i = 0; i < TG; i++) {
+                const u32 bin = tb[i];
+                if (bin == RESOLVED || tg[i] != g) continue;
+                __syncthreads();
+                const u32 res = tr[i];
+                const u32 klo = tlo[i], khi = thi[i];
+                const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
+                const u32 key = block_select_range((const GLOBAL_AS u32 *)src, n, klo, khi, res,
+                                                   klo == ZERO_KEY, hist, sh);
+                if (tid == 0u) {
+                    if (sh[2] != expect || res >= expect)
+                        atomicOr(&st->internal_err, 128u);
+                    else
+                        tk[i] = key;
+                }
             }
         }
     }
@@ -972,7 +1000,7 @@ constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
-constexpr int SM_BUCKET = (BUCKET_CAP + (BLOCK / 64) * MATCH_CAP) * 4;
+constexpr int SM_BUCKET = (2 * BUCKET_CAP + 16 * 256) * 4;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
@@ -984,7 +1012,8 @@ static hipError_t set_attrs()
     if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
-    if ((e = hipFuncSetAttribute((const void *)k_bucket, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_bucket<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_bucket<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
     g_attr_done = true;
     return hipSuccess;
 }
@@ -1003,7 +1032,10 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
     PROF("k_split", s, k_split<<<bt.n_units, BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     const u32 TG = bt.n_pairs * NB8;
-    PROF("k_bucket", s, k_bucket<<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
+    if (bt.lds_ordered)
+        PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
+    else
+        PROF("k_bucket_ballots", s, k_bucket<false><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
     return hipGetLastError();
 }
 

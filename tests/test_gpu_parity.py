@@ -2,6 +2,8 @@
 same seeded inputs.  Bit-exact on thresholds, boundaries, symbols, protected lists, permutations,
 delta streams, counts and chosen configurations; 1e-6 relative on centres and error sums (plus an
 absolute floor of 1e-12 * sumsq on error sums, the fp64 rounding of sumsq - sum_bins(...))."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -212,6 +214,36 @@ def test_errors(ctx):
     # still usable afterwards
     best, feas, _ = ctx.search([dev(x)], synth.grid_small(), 0.01)
     assert feas == [1]
+
+
+def test_heavy_duplicates_exceed_the_lds_sort(ctx):
+    """A few distinct values, each held by far more elements than one group sort takes in LDS:
+    the boundaries are then selected from device memory."""
+    rng = np.random.default_rng(11)
+    n = 150_000
+    vals = np.array([-0.5, 0.1, 0.1000001, 0.7, 0.0, 3.0], np.float32)
+    prev = rng.choice(vals, n)
+    cur = prev.copy()
+    flip = rng.random(n) < 0.02
+    cur[flip] = rng.choice(vals, int(flip.sum()))
+    mixed = np.concatenate([prev[:60_000], (0.01 * rng.standard_normal(60_000)).astype(np.float32)])
+    run_pipeline(ctx, [prev, mixed], [cur, mixed.copy()], synth.grid_small(), synth.EPS_DEFAULT)
+
+
+def test_without_lane_ordered_lds_atomics():
+    """The group sort and the delta scatter have a ballot-based path for devices whose LDS atomics
+    do not return in lane order; INSHR_NO_LDS_ORDER=1 selects it."""
+    from paper_2306_11800_amd import api
+    os.environ["INSHR_NO_LDS_ORDER"] = "1"
+    try:
+        c = api.Context(torch.device("cuda:0"))
+    finally:
+        del os.environ["INSHR_NO_LDS_ORDER"]
+    rng = np.random.default_rng(12)
+    prev, cur = synth.config0(seed=3, n=250_007)
+    few = rng.choice(np.array([-0.5, 0.1, 0.7, 0.0, 3.0], np.float32), 30_000)
+    run_pipeline(c, [prev, few], [cur, few.copy()], synth.grid_small(), synth.EPS_DEFAULT)
+    c.close()
 
 
 def test_deterministic_bytes(ctx):
