@@ -263,6 +263,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_h1 = cv.take((size_t)nT * L1_BINS * 4);
         const size_t o_h2 = cv.take((size_t)nT * L2_BINS * 4);
         const size_t o_ngt = cv.take(256);
+        const size_t o_gcn = cv.take((size_t)nT * 2 * MAX_EDGES * 4);
+        const size_t o_gsx = cv.take((size_t)nT * 2 * MAX_EDGES * 8);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
         const size_t o_us = cv.take((size_t)units * 8);
@@ -278,13 +280,16 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_ed = cv.take((size_t)nT * MAX_EDGES * 4);
         const size_t o_sl = cv.take((size_t)nT * (L2_BINS + 64) * 2);
         const size_t o_pe = cv.take((size_t)nT * MAX_PAIRS * 260 * 2);
-        const size_t o_mc = cv.take((size_t)units * MAX_EDGES * 4);
+        const size_t o_eb = cv.take((size_t)nT * MAX_EDGES * 4);
+        const size_t o_ei = cv.take((size_t)nT * MAX_EDGES * 2);
+        const size_t o_gel = cv.take((size_t)nT * MAX_GROUPS * 4);
+        const size_t o_geh = cv.take((size_t)nT * MAX_GROUPS * 4);
+        const size_t o_sgc = cv.take((size_t)nT * MAX_EDGES * 4);
         const size_t o_ms = cv.take((size_t)units * MAX_EDGES * 8);
         const size_t o_cb = cv.take((size_t)nT * n_cfg * CB_STRIDE * 4);
         const size_t o_sc = cv.take((size_t)nT * n_cfg * sizeof(Score));
         const size_t o_bt = cv.take((size_t)nT * n_cfg * CB_STRIDE * 8);
         const size_t o_uc = cv.take((size_t)units * 4);
-        const size_t o_abm = cv.take((size_t)nT * (L2_BINS / 32) * 4);
         const size_t o_bg = cv.take((size_t)nT * L2_BINS * 2);
         const size_t o_go = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_ge = cv.take((size_t)nT * MAX_GROUPS * 4);
@@ -352,12 +357,11 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.pool = (u32 *)(db + o_pool);
         B.pool2 = B.pool;
         B.unit_cand = (u32 *)(db + o_uc);
-        B.active_bits = (u32 *)(db + o_abm);
         B.bin_group = (u16 *)(db + o_bg);
         B.grp_off = (u32 *)(db + o_go);
         B.grp_end = (u32 *)(db + o_ge);
         B.grp_cur = (u32 *)(db + o_gc);
-        B.tgt_grp = (u32 *)(db + o_tgg);
+        B.tgt_rank = (u32 *)(db + o_tgg);
         B.tgt_klo = (u32 *)(db + o_tkl);
         B.tgt_khi = (u32 *)(db + o_tkh);
         B.tile_out = (u32 *)(db + o_to);
@@ -366,7 +370,13 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.edges = (u32 *)(db + o_ed);
         B.sl = (u16 *)(db + o_sl);
         B.pair_eidx = (u16 *)(db + o_pe);
-        B.mom_cnt = (u32 *)(db + o_mc);
+        B.edge_bin = (u32 *)(db + o_eb);
+        B.edge_item = (u16 *)(db + o_ei);
+        B.grp_elo = (u32 *)(db + o_gel);
+        B.grp_ehi = (u32 *)(db + o_geh);
+        B.seg_cnt = (u32 *)(db + o_sgc);
+        B.grp_cnt = (u32 *)(db + o_gcn);
+        B.grp_sx = (double *)(db + o_gsx);
         B.mom_sx = (double *)(db + o_ms);
         B.codebook = (float *)(db + o_cb);
         B.scores = (Score *)(db + o_sc);

@@ -38,6 +38,8 @@ constexpr int MAX_THR = 2 * MAX_FRAC;
 constexpr int MAX_PAIRS = 15;       // distinct (prune, protect) pairs in a grid
 constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits use a subset
 constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 = 3885 fits)
+constexpr int EPP = NB8 + 4;        // edges per pair: 255 boundaries + 4 class edges
+constexpr int EIDX_STRIDE = 260;    // per-pair stride of the edge positions
 constexpr int MAX_CFG = 256;
 constexpr int GROUP_SHIFT = 13;     // gathered keys per group of active bins: about 2^13
 constexpr int MAX_GROUPS = 4096;    // groups per tensor (the shift grows for huge tensors)
@@ -65,6 +67,19 @@ __host__ __device__ __forceinline__ bool key_is_neg(u32 k) { return (k & 0x80000
 // keys of +m and -m for a magnitude image m (m == 0 maps both to ZERO_KEY's neighbourhood)
 __host__ __device__ __forceinline__ u32 key_pos(u32 m) { return 0x80000000u + m; }
 __host__ __device__ __forceinline__ u32 key_neg(u32 m) { return 0x7fffffffu - m; }
+
+// The four class edges of a (prune threshold tp, protect threshold to) pair on the key axis:
+// 0 first quantized negative key, 1 first pruned key, 2 first quantized positive key,
+// 3 first protected positive key.
+__host__ __device__ __forceinline__ u32 class_edge_key(u32 which, u32 tp, u32 to)
+{
+    switch (which) {
+    case 0: return key_neg(to);
+    case 1: return key_neg(tp) + 1u;
+    case 2: return key_pos(tp);
+    default: return to >= 0x7fffffffu ? 0xFFFFFFFFu : key_pos(to) + 1u;
+    }
+}
 
 // second-level bin of a key: table entry = bucket mask << 20 | base << 5 | depth.  Bit 20 + s of
 // the entry says that first-level bin s of the 8 under this 12-bit key prefix holds a threshold.

@@ -24,22 +24,28 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *pool;      // gathered keys: per tensor a threshold region and an active-bin region, n each
     u32 *pool2;     // same layout; the threshold region is reused for the keys in bin-group order
     u32 *unit_cand; // [units] active-bin keys the unit gathered
-    u32 *active_bits; // [nT][1024] bitmap of active bins
     u16 *bin_group; // [nT][32768] group of each active bin
     u32 *grp_off;   // [nT][MAX_GROUPS] first / one-past-last position of each group in bin order
     u32 *grp_end;
     u32 *grp_cur;   // [nT][MAX_GROUPS] keys placed so far
-    u32 *tgt_grp;   // [nT][TGT_STRIDE] group, first and last key of each boundary's bin
-    u32 *tgt_klo;
+    u32 *tgt_rank;  // [nT][TGT_STRIDE] rank of each boundary among all keys of the tensor
+    u32 *tgt_klo;   // [nT][TGT_STRIDE] first and last key of each boundary's bin
     u32 *tgt_khi;
     u32 *tile_out;  // [tiles][MAX_FRAC] protected values per tile and protect fraction
     double *sq_part; // [units][SQ_STRIDE]
-    // scoring
-    u32 *edges;     // [nT][MAX_EDGES] merged, sorted, distinct edge keys
-    u16 *sl;        // [nT][32768 + 64] edges below each second-level bin
-    u16 *pair_eidx; // [nT][MAX_PAIRS][260] index of each pair's edges in the merged list
-    u32 *mom_cnt;   // [units][MAX_EDGES]
-    double *mom_sx; // [units][MAX_EDGES]
+    // scoring: all boundaries and class edges of all pairs in one list ordered by key ("edges");
+    // slot s holds the keys with exactly s edges at or below them
+    u32 *edges;     // [nT][MAX_EDGES] edge keys in that order
+    u32 *edge_bin;  // [nT][MAX_EDGES] second-level bin of each edge
+    u16 *edge_item; // [nT][MAX_EDGES] pair * 259 + (boundary j - 1, or 255 + class edge)
+    u16 *sl;        // [nT][32768 + 64] slot of every bin without an edge; 0xFFFF for the others
+    u16 *pair_eidx; // [nT][MAX_PAIRS][260] position of each pair's edges in the list
+    u32 *grp_elo;   // [nT][MAX_GROUPS] first / one-past-last edge of each group of active bins
+    u32 *grp_ehi;
+    u32 *seg_cnt;   // [nT][MAX_EDGES] keys per slot that lie in bins without an edge
+    u32 *grp_cnt;   // [nT][2][MAX_EDGES] keys per slot from the group of the slot's lower / upper edge
+    double *grp_sx; // [nT][2][MAX_EDGES] ... and their sums
+    double *mom_sx; // [units][MAX_EDGES] per slot: sum over the unit's keys in bins without an edge
     float *codebook; // [nT][n_cfg][CB_STRIDE]
     Score *scores;  // [nT][n_cfg]
     double *bin_term; // [nT][n_cfg][CB_STRIDE] per-bin 2cS - nc^2
@@ -106,6 +112,7 @@ void prof_end(hipStream_t s);
     } while (0)
 
 hipError_t launch_select(const Batch &bt, hipStream_t s);
+hipError_t launch_edges(const Batch &bt, hipStream_t s); // edge order, bins without edges (inside launch_select)
 hipError_t launch_score(const Batch &bt, hipStream_t s);
 hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStream_t s);
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,

@@ -1,58 +1,85 @@
-// Scoring of every grid configuration in one sweep (Sec. 5: the search evaluates a grid of
-// configurations; here all of them share one pass over the data).
+// Scoring of every grid configuration from one pass over the data (Sec. 5: the search evaluates a
+// grid of configurations; here all of them share the sweeps).
 //
-// All thresholds and boundaries of all (prune, protect) pairs are merged into one sorted list of
-// distinct "edges"; an element's slot in that list fixes its class and bin under every
-// configuration, because the boundaries for fewer bits are a subset of those for 8 bits
-// (floor(j*M/2^b) = floor(j*2^(8-b)*M/2^8)).  The sweep accumulates (count, sum x) per slot; a
-// small kernel turns slots into per-bin centres (Sec. 4.4, one centre update) and errors:
+// All boundaries and class edges of all (prune, protect) pairs form one list of "edges" ordered by
+// key; slot s holds the keys with exactly s edges at or below them, and a slot fixes class and bin
+// under every configuration, because the boundaries for fewer bits are a subset of those for
+// 8 bits (floor(j*M/2^b) = floor(j*2^(8-b)*M/2^8)).  The order of the list is known before any
+// boundary key is: a boundary is the key of a given rank, a class edge has a known number of keys
+// below it, and rank order is key order (a class edge goes before a boundary of equal rank).
+// Per slot the sweeps provide (count, sum x); a small kernel turns slots into per-bin centres
+// (Sec. 4.4, one centre update) and errors:
 //   sse = sum_all x^2 - sum_protected x^2 - sum_bins (2 c S - n c^2)        (c rounded to fp32)
 // (a pruned element's error x^2 is its own share of sum_all x^2).
 #include "inshr_launch.h"
 
 namespace inshr {
 
-constexpr int EPP = NB8 + 4; // edges per pair: 255 boundaries + 4 class edges
-constexpr int EIDX_STRIDE = 260;
-
 // ------------------------------------------------------------------------------------------
-// plan 3: merged edge list and its lookup accelerator
+// edge order; for every bin without an edge its slot, and the keys per slot in such bins
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_plan3(const GridDesc *__restrict__ gd, Bufs B)
+__global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
+                                                 const GridDesc *__restrict__ gd, Bufs B)
 {
     extern __shared__ u32 smem[];
-    u32 *srt = smem;              // [4096]
-    u32 *cnt = smem + MAX_EDGES;  // [32768 + 4]
-    __shared__ u32 tmp[BLOCK / 64 + 1];
+    u64 *srt = reinterpret_cast<u64 *>(smem); // [4096] sort word, see below
+    u32 *ebin = smem + 2 * MAX_EDGES;         // [4096] bin of each edge, in order
+    u32 *segc = ebin + MAX_EDGES;             // [4096] keys per slot in bins without an edge
 
     const int t = blockIdx.x;
     const u32 tid = threadIdx.x;
     TState *st = B.ts + t;
+    const u64 n = td[t].n, n_neg = st->n_neg;
     const u32 n_pairs = gd->n_pairs, n_p = gd->n_p;
-    const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
-    const u32 n_in = n_pairs * EPP;
+    const u32 n_e = n_pairs * EPP;
+    const u32 nb2 = st->nb2, zbin = st->zbin;
+    const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
+    const u32 *trank = B.tgt_rank + (size_t)t * TGT_STRIDE;
+    const u32 *tab = B.table2 + (size_t)t * COARSE;
+    const u32 *binfo = B.binfo + (size_t)t * L2_BINS;
+    const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+    const u16 *gtab = B.bin_group + (size_t)t * L2_BINS;
 
-    auto edge_key = [&](u32 idx) -> u32 {
-        const u32 q = idx / EPP, e = idx % EPP;
-        if (e < (u32)NB8) return tk[q * NB8 + e];
-        const u32 tp = st->thr_mag[gd->pair_p[q]], to = st->thr_mag[n_p + gd->pair_o[q]];
-        switch (e - NB8) {
-        case 0: return key_neg(to);           // first quantized negative key
-        case 1: return key_neg(tp) + 1u;      // first pruned key
-        case 2: return key_pos(tp);           // first quantized positive key
-        default: return key_pos(to) + 1u;     // first protected positive key
-        }
-    };
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) srt[i] = (i < n_in) ? edge_key(i) : 0xFFFFFFFFu;
+    // Sort word: (keys below the edge << 1 | is boundary) << 18 | order of the key among the class
+    // edges << 12 | item.  Class edges with the same number of keys below them have no key between
+    // them, but they may lie in different bins, so they are put in key order.
+    __shared__ u32 ckey[MAX_PAIRS * 4];
+    if (tid < n_pairs * 4u)
+        ckey[tid] = class_edge_key(tid & 3u, st->thr_mag[gd->pair_p[tid >> 2]],
+                                   st->thr_mag[n_p + gd->pair_o[tid >> 2]]);
     __syncthreads();
-    // bitonic sort of 4096 keys
-    for (u32 k = 2; k <= (u32)MAX_EDGES; k <<= 1) {
+    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
+        u64 v = ~0ull;
+        if (i < n_e) {
+            const u32 q = i / EPP, e = i % EPP;
+            u64 below, is_boundary, corder = 0ull;
+            if (e < (u32)NB8) {
+                below = trank[q * NB8 + e];
+                is_boundary = 1ull;
+            } else {
+                const u32 me = q * 4u + (e - NB8), key = ckey[me];
+                for (u32 j = 0; j < n_pairs * 4u; j++)
+                    corder += (ckey[j] < key || (ckey[j] == key && j < me)) ? 1ull : 0ull;
+                switch (e - NB8) {
+                case 0: below = st->pair_An[q]; break;                 // keys < first quantized negative
+                case 1: below = n_neg - st->pair_Pn[q]; break;         // keys < first pruned
+                case 2: below = n_neg + st->pair_Pp[q]; break;         // keys < first quantized positive
+                default: below = n - st->pair_Ap[q]; break;            // keys < first protected positive
+                }
+                is_boundary = 0ull;
+            }
+            v = (((below << 1) | is_boundary) << 18) | (corder << 12) | (u64)i;
+        }
+        srt[i] = v;
+    }
+    __syncthreads();
+    for (u32 k = 2; k <= (u32)MAX_EDGES; k <<= 1) { // bitonic sort
         for (u32 j = k >> 1; j > 0; j >>= 1) {
             for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
-                u32 l = i ^ j;
+                const u32 l = i ^ j;
                 if (l > i) {
-                    u32 a = srt[i], b = srt[l];
-                    bool up = (i & k) == 0;
+                    const u64 a = srt[i], b = srt[l];
+                    const bool up = (i & k) == 0;
                     if ((a > b) == up) {
                         srt[i] = b;
                         srt[l] = a;
@@ -62,122 +89,73 @@ __global__ __launch_bounds__(BLOCK) void k_plan3(const GridDesc *__restrict__ gd
             __syncthreads();
         }
     }
-    // distinct values, in order
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK)
-        cnt[i] = (srt[i] != 0xFFFFFFFFu && (i == 0 || srt[i] != srt[i - 1])) ? 1u : 0u;
-    __syncthreads();
     u32 *E = B.edges + (size_t)t * MAX_EDGES;
-    u32 *Ec = cnt + 2 * MAX_EDGES; // LDS copy of the distinct list
-    // the scan overwrites the flags with positions, so each thread keeps its own flags
-    u32 flags[MAX_EDGES / BLOCK];
-    for (int r = 0; r < MAX_EDGES / BLOCK; r++) flags[r] = cnt[tid + r * BLOCK];
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) Ec[i] = 0xFFFFFFFFu;
+    u32 *eb = B.edge_bin + (size_t)t * MAX_EDGES;
+    u16 *ei = B.edge_item + (size_t)t * MAX_EDGES;
+    u16 *pe = B.pair_eidx + (size_t)t * MAX_PAIRS * EIDX_STRIDE;
+    u32 *elo = B.grp_elo + (size_t)t * MAX_GROUPS;
+    u32 *ehi = B.grp_ehi + (size_t)t * MAX_GROUPS;
+    for (u32 pos = tid; pos < (u32)MAX_EDGES; pos += BLOCK) {
+        u32 bin = 0xFFFFFFFFu;
+        if (pos < n_e) {
+            const u32 item = (u32)(srt[pos] & 4095ull);
+            const u32 q = item / EPP, e = item % EPP;
+            u32 key = 0u; // a boundary's key is found later, from the gathered keys
+            if (e < (u32)NB8) {
+                bin = tb[q * NB8 + e];
+                if (bin == RESOLVED) {
+                    bin = zbin;
+                    key = ZERO_KEY;
+                }
+            } else {
+                key = class_edge_key(e - NB8, st->thr_mag[gd->pair_p[q]], st->thr_mag[n_p + gd->pair_o[q]]);
+                bin = l2_bin(key, tab[key >> COARSE_SHIFT]);
+            }
+            E[pos] = key;
+            eb[pos] = bin;
+            ei[pos] = (u16)item;
+            pe[q * EIDX_STRIDE + e] = (u16)pos;
+        }
+        ebin[pos] = bin;
+        segc[pos] = 0u;
+    }
+    for (u32 g = tid; g < (u32)MAX_GROUPS; g += BLOCK) {
+        elo[g] = 0xFFFFFFFFu;
+        ehi[g] = 0u;
+    }
     __syncthreads();
-    const u32 m = block_excl_scan(cnt, cnt, MAX_EDGES, tmp);
-    for (int r = 0; r < MAX_EDGES / BLOCK; r++) {
-        u32 i = tid + r * BLOCK;
-        if (flags[r]) {
-            E[cnt[i]] = srt[i];
-            Ec[cnt[i]] = srt[i];
+    for (u32 pos = tid; pos < n_e; pos += BLOCK) {
+        const u32 bin = ebin[pos];
+        if (pos + 1u < n_e && ebin[pos + 1u] < bin) atomicOr(&st->internal_err, 512u);
+        const u32 g = (bin < nb2) ? gtab[bin] : 0xFFFFu;
+        if (g >= (u32)MAX_GROUPS) {
+            atomicOr(&st->internal_err, 512u);
+        } else {
+            atomicMin(&elo[g], pos);
+            atomicMax(&ehi[g], pos + 1u);
         }
     }
-    if (tid == 0) st->n_edges = m;
-    __syncthreads();
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) srt[i] = Ec[i];
-    __syncthreads();
-    u16 *pe = B.pair_eidx + (size_t)t * MAX_PAIRS * EIDX_STRIDE;
-    for (u32 i = tid; i < n_in; i += BLOCK) {
-        const u32 key = edge_key(i);
-        u32 lo = 0, hi = m; // first index with srt[idx] >= key
+    u16 *sl = B.sl + (size_t)t * (L2_BINS + 64);
+    for (u32 b = tid; b < nb2; b += BLOCK) {
+        if (binfo[b] != INACTIVE) {
+            sl[b] = 0xFFFFu;
+            continue;
+        }
+        u32 lo = 0u, hi = n_e; // edges in lower bins
         while (lo < hi) {
-            u32 mid = (lo + hi) >> 1;
-            if (srt[mid] < key)
-                lo = mid + 1;
+            const u32 mid = (lo + hi) >> 1;
+            if (ebin[mid] < b)
+                lo = mid + 1u;
             else
                 hi = mid;
         }
-        pe[(i / EPP) * EIDX_STRIDE + (i % EPP)] = (u16)lo;
-    }
-    // edges below each second-level bin
-    const u32 nb2 = st->nb2;
-    const u32 *tab = B.table2 + (size_t)t * COARSE;
-    for (u32 i = tid; i <= nb2; i += BLOCK) cnt[i] = 0u;
-    __syncthreads();
-    for (u32 i = tid; i < m; i += BLOCK) {
-        u32 key = srt[i];
-        atomicAdd(&cnt[l2_bin(key, tab[key >> COARSE_SHIFT])], 1u);
+        sl[b] = (u16)lo;
+        if (h2[b]) atomicAdd(&segc[lo], h2[b]);
     }
     __syncthreads();
-    block_excl_scan(cnt, cnt, (int)nb2, tmp);
-    u16 *sl = B.sl + (size_t)t * (L2_BINS + 64);
-    for (u32 i = tid; i <= nb2; i += BLOCK) sl[i] = (u16)cnt[i];
-}
-
-// ------------------------------------------------------------------------------------------
-// sweep 4: per-slot count and sum
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_score(const TDesc *__restrict__ td, int nT,
-                                                 const u64 *__restrict__ wg_tile0,
-                                                 const u32 *__restrict__ wg_fu0, Bufs B)
-{
-    extern __shared__ u32 smem[];
-    double *sx = reinterpret_cast<double *>(smem);         // [4096]
-    u32 *cnt = smem + 2 * MAX_EDGES;                       // [4096]
-    u32 *E = cnt + MAX_EDGES;                              // [4096]
-    u32 *T = E + MAX_EDGES;                                // [4096]
-    u16 *SL = reinterpret_cast<u16 *>(T + COARSE);         // [32768 + 64]
-
-    const u32 tid = threadIdx.x;
-    const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
-    if (tile_lo >= tile_hi) return;
-    int t = find_tensor(td, nT, tile_lo);
-    const int t_first = t;
-    u64 tile = tile_lo;
-    while (tile < tile_hi) {
-        const TDesc d = td[t];
-        const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
-        const u64 t_end = d.tile0 + n_tiles_t;
-        const u64 stop = t_end < tile_hi ? t_end : tile_hi;
-        const TState *st = B.ts + t;
-        const u32 m = st->n_edges, nb2 = st->nb2;
-        for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
-            sx[i] = 0.0;
-            cnt[i] = 0u;
-            E[i] = (i < m) ? B.edges[(size_t)t * MAX_EDGES + i] : 0xFFFFFFFFu;
-            T[i] = B.table2[(size_t)t * COARSE + i];
-        }
-        const u16 *gsl = B.sl + (size_t)t * (L2_BINS + 64);
-        for (u32 i = tid; i <= nb2; i += BLOCK) SL[i] = gsl[i];
-        __syncthreads();
-        for (; tile < stop; tile++) {
-            const u64 e0 = (tile - d.tile0) * (u64)TILE;
-            const u64 rem = d.n - e0;
-            const u32 c = rem < (u64)TILE ? (u32)rem : (u32)TILE;
-            float v[16];
-            const u32 mask = load_tile(d, e0, c, v);
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                if (!((mask >> i) & 1u)) continue;
-                const u32 key = key_of_bits(canon_bits(__float_as_uint(v[i])));
-                const u32 b2 = l2_bin(key, T[key >> COARSE_SHIFT]);
-                u32 s = SL[b2];
-                const u32 hi = SL[b2 + 1];
-                while (s < hi && E[s] <= key) s++;
-                atomicAdd(&cnt[s], 1u);
-                atomicAdd(&sx[s], (double)v[i]);
-            }
-        }
-        __syncthreads();
-        const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
-        u32 *gc = B.mom_cnt + (size_t)fu * MAX_EDGES;
-        double *gs = B.mom_sx + (size_t)fu * MAX_EDGES;
-        for (u32 i = tid; i <= m; i += BLOCK) {
-            gc[i] = cnt[i];
-            gs[i] = sx[i];
-        }
-        __syncthreads();
-        t++;
-    }
+    u32 *sc = B.seg_cnt + (size_t)t * MAX_EDGES;
+    for (u32 i = tid; i <= n_e; i += BLOCK) sc[i] = segc[i];
+    if (tid == 0) st->n_edges = n_e;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -204,15 +182,19 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     const u32 u0 = t_fu_off[t], u1 = t_fu_off[t + 1];
     const u32 n_cfg = gd->n_cfg, n_p = gd->n_p, n_o = gd->n_o;
 
+    const u32 *segc = B.seg_cnt + (size_t)t * MAX_EDGES;
+    const u32 *gc = B.grp_cnt + (size_t)t * 2 * MAX_EDGES;
+    const double *gs = B.grp_sx + (size_t)t * 2 * MAX_EDGES;
     for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
         double s = 0.0;
         u64 c = 0;
         if (i <= m) {
-            for (u32 u = u0; u < u1; u++) {
-                const u32 fu = t_fu_ids[u];
-                c += B.mom_cnt[(size_t)fu * MAX_EDGES + i];
-                s += B.mom_sx[(size_t)fu * MAX_EDGES + i];
-            }
+            // keys of bins without an edge (per unit, in unit order), then the gathered keys from
+            // the group of the slot's lower edge and from the group of its upper edge
+            for (u32 u = u0; u < u1; u++) s += B.mom_sx[(size_t)t_fu_ids[u] * MAX_EDGES + i];
+            s += gs[i];
+            s += gs[MAX_EDGES + i];
+            c = (u64)segc[i] + gc[i] + gc[MAX_EDGES + i];
         }
         S[i] = s;
         C[i] = c;
@@ -306,24 +288,33 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     }
 }
 
-constexpr int SM_PLAN3 = (MAX_EDGES + L2_BINS + 4) * 4;
-constexpr int SM_SCORE = (2 * MAX_EDGES + 3 * MAX_EDGES) * 4 + (L2_BINS + 64) * 2;
+constexpr int SM_EDGES = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4;
 constexpr int SM_FINAL = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4;
 
 static bool g_attr_done = false;
+static hipError_t set_attrs()
+{
+    if (g_attr_done) return hipSuccess;
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void *)k_edges, hipFuncAttributeMaxDynamicSharedMemorySize, SM_EDGES))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_final, hipFuncAttributeMaxDynamicSharedMemorySize, SM_FINAL))) return e;
+    g_attr_done = true;
+    return hipSuccess;
+}
+
+hipError_t launch_edges(const Batch &bt, hipStream_t s)
+{
+    hipError_t e = set_attrs();
+    if (e) return e;
+    PROF("k_edges", s, k_edges<<<bt.nT, BLOCK, SM_EDGES, s>>>(bt.td, bt.gd, bt.bufs));
+    return hipGetLastError();
+}
+
 hipError_t launch_score(const Batch &bt, hipStream_t s)
 {
-    if (!g_attr_done) {
-        hipError_t e;
-        if ((e = hipFuncSetAttribute((const void *)k_plan3, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN3))) return e;
-        if ((e = hipFuncSetAttribute((const void *)k_score, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SCORE))) return e;
-        if ((e = hipFuncSetAttribute((const void *)k_final, hipFuncAttributeMaxDynamicSharedMemorySize, SM_FINAL))) return e;
-        g_attr_done = true;
-    }
-    const Bufs &B = bt.bufs;
-    PROF("k_plan3", s, k_plan3<<<bt.nT, BLOCK, SM_PLAN3, s>>>(bt.gd, B));
-    PROF("k_score", s, k_score<<<bt.n_wg, BLOCK, SM_SCORE, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
-    PROF("k_final", s, k_final<<<bt.nT, BLOCK, SM_FINAL, s>>>(bt.td, bt.gd, bt.t_fu_off, bt.t_fu_ids, B));
+    hipError_t e = set_attrs();
+    if (e) return e;
+    PROF("k_final", s, k_final<<<bt.nT, BLOCK, SM_FINAL, s>>>(bt.td, bt.gd, bt.t_fu_off, bt.t_fu_ids, bt.bufs));
     return hipGetLastError();
 }
 

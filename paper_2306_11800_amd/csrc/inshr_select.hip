@@ -458,11 +458,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
     u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
     u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
     u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
+    u32 *trank = B.tgt_rank + (size_t)t * TGT_STRIDE;
     for (u32 i = tid; i < TG; i += BLOCK) {
         const u32 q = i / NB8, j = i % NB8 + 1u;
         const u64 M = sM[q];
         const u64 k = (u64)j * M / 256ull;
         const u64 r = (k < sMn[q]) ? sAn[q] + k : sAn[q] + sPP[q] + k;
+        trank[i] = (u32)r;
         // first index in [0, nb2] with cum[idx] > r
         u32 lo = 0, hi = nb2;
         while (lo < hi) {
@@ -484,12 +486,20 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
             tb[i] = RESOLVED;
             tr[i] = 0u;
             tk[i] = ZERO_KEY;
+            binfo[bin] = 1u; // the bin holds an edge: its other keys are classified one by one
         } else {
             if (bin == zbin) res -= n_zero;
             tb[i] = bin;
             tr[i] = (u32)res;
             binfo[bin] = 1u;
         }
+    }
+    // the bins of the class edges (first quantized / pruned / protected key of either sign) are
+    // active too, so that every bin without an edge lies inside one slot
+    for (u32 i = tid; i < n_pairs * 4u; i += BLOCK) {
+        const u32 q = i >> 2;
+        const u32 key = class_edge_key(i & 3u, st->thr_mag[gd->pair_p[q]], st->thr_mag[n_p + gd->pair_o[q]]);
+        binfo[l2_bin(key, tab[key >> COARSE_SHIFT])] = 1u;
     }
     __syncthreads();
     // gathered population of every bin in bin order -> offset of the bin in that order
@@ -500,7 +510,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
     // groups: runs of active bins of about 2^gshift gathered keys; at most MAX_GROUPS per tensor
     u32 gshift = GROUP_SHIFT;
     while ((ctot >> gshift) >= (u32)MAX_GROUPS) gshift++;
-    const u32 n_groups = ctot ? ((ctot - 1u) >> gshift) + 1u : 0u;
+    const u32 n_groups = ctot ? ((ctot - 1u) >> gshift) + 1u : 1u; // edges exist even without keys
     u32 *goff = B.grp_off + d.tile0 * 0 + (size_t)t * MAX_GROUPS;
     u32 *gend = B.grp_end + (size_t)t * MAX_GROUPS;
     u32 *gcur = B.grp_cur + (size_t)t * MAX_GROUPS;
@@ -510,17 +520,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         gcur[g] = 0u;
     }
     __syncthreads();
-    u32 *abm = B.active_bits + (size_t)t * (L2_BINS / 32);
     u16 *gtab = B.bin_group + (size_t)t * L2_BINS;
-    for (u32 i = tid; i < (u32)L2_BINS / 32; i += BLOCK) abm[i] = 0u;
-    __syncthreads();
     for (u32 i = tid; i < nb2; i += BLOCK) {
         if (binfo[i]) {
             const u32 c = h2[i] - ((i == zbin) ? (u32)n_zero : 0u);
-            const u32 g = cur[i] >> gshift;
+            const u32 g = min(cur[i] >> gshift, n_groups - 1u); // an empty bin at the very end
             atomicMin(&goff[g], cur[i]);
             atomicMax(&gend[g], cur[i] + c);
-            atomicOr(&abm[i >> 5], 1u << (i & 31u));
             gtab[i] = (u16)g;
             binfo[i] = cur[i]; // offset of the bin's keys once they are in bin order
         } else {
@@ -529,14 +535,12 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         }
     }
     __syncthreads();
-    // per target: its group and the key range of its bin
-    u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
+    // per target: the key range of its bin
     u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
     u32 *thi = B.tgt_khi + (size_t)t * TGT_STRIDE;
     for (u32 i = tid; i < TG; i += BLOCK) {
         const u32 bin = tb[i];
         if (bin == RESOLVED) continue;
-        tg[i] = gtab[bin];
         // last 12-bit prefix whose first bin is <= bin
         u32 lo = 0, hi = COARSE - 1;
         while (lo < hi) {
@@ -559,15 +563,19 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
 }
 
 // ------------------------------------------------------------------------------------------
-// sweep 3: gather the elements of active bins; sums of squares; protected counts per tile
+// sweep 3: every key either lies in a bin without an edge, and then its slot is known from the bin
+// alone (its value is added to the slot's sum), or it is gathered for the exact boundaries.  Also:
+// sums of squares, protected counts per tile.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, int nT,
                                                   const u64 *__restrict__ wg_tile0,
                                                   const u32 *__restrict__ wg_fu0,
                                                   const GridDesc *__restrict__ gd, Bufs B)
 {
-    __shared__ u32 abm[L2_BINS / 32]; // active bins
-    __shared__ u32 T[COARSE];
+    extern __shared__ u32 smem[];
+    double *sx = reinterpret_cast<double *>(smem);             // [MAX_EDGES] sum per slot
+    u32 *T = smem + 2 * MAX_EDGES;                             // [COARSE]
+    u16 *SEG = reinterpret_cast<u16 *>(T + COARSE);            // [L2_BINS] slot of the bin, or 0xFFFF
     __shared__ u32 s_tau_o[MAX_FRAC];
     __shared__ u32 s_oc[MAX_FRAC];
     __shared__ u32 s_gathered;
@@ -586,8 +594,14 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         const u64 t_end = d.tile0 + n_tiles_t;
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
-        for (u32 i = tid; i < (u32)L2_BINS / 32; i += BLOCK) abm[i] = B.active_bits[(size_t)t * (L2_BINS / 32) + i];
+        const u32 n_slots = st->n_edges + 1u;
+        {
+            const u32 *gseg = reinterpret_cast<const u32 *>(B.sl + (size_t)t * (L2_BINS + 64));
+            u32 *seg32 = reinterpret_cast<u32 *>(SEG);
+            for (u32 i = tid; i < (u32)L2_BINS / 2; i += BLOCK) seg32[i] = gseg[i];
+        }
         for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+        for (u32 i = tid; i < n_slots; i += BLOCK) sx[i] = 0.0;
         if (tid < MAX_FRAC) {
             s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
             s_oc[tid] = 0u;
@@ -618,7 +632,9 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
                 const double xd = (double)v[i];
                 q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
                 const u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
-                const bool cand = valid && b != 0u && ((abm[bin >> 5] >> (bin & 31u)) & 1u);
+                const u32 slot = SEG[bin];
+                if (valid && slot != 0xFFFFu) atomicAdd(&sx[slot], xd);
+                const bool cand = valid && b != 0u && slot == 0xFFFFu;
                 const u64 cm = __ballot(cand);
                 if (cm) {
                     u32 base = 0u;
@@ -648,6 +664,8 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         // flush partial sums of this (workgroup, tensor) unit in a fixed order
         const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
         if (tid == 0) B.unit_cand[fu] = s_gathered;
+        double *gs = B.mom_sx + (size_t)fu * MAX_EDGES;
+        for (u32 i = tid; i < n_slots; i += BLOCK) gs[i] = sx[i];
         double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
 #pragma unroll
         for (int o = 0; o <= MAX_FRAC; o++) {
@@ -736,6 +754,7 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 constexpr int BUCKET_CAP = 16384;  // keys of a group sorted in LDS
 constexpr int SORT_ROWS = BUCKET_CAP / BLOCK; // rows of 64 keys per wave and pass, at most
+constexpr int EDGE_CAP = MAX_PAIRS * EPP + 11; // edges of a group (all of a tensor's at most) + 1, even
 
 // k-th smallest of the keys in [klo, khi] (khi - klo + 1 a power of two) among a[0..n), by the whole
 // workgroup: radix select, 8 bits per round, LDS histogram.  *found = keys in the range (in sh[2]).
@@ -828,17 +847,20 @@ __device__ __forceinline__ u32 digit_rank(u32 *wcnt, u32 digit, bool valid)
 }
 
 // One group of active bins per step: its keys are sorted in LDS (least significant digit first,
-// 8 bits per pass, only the digits in which the keys differ), and every boundary of the group is
-// read at its rank: offset of its bin inside the group + residual rank inside the bin.
+// 8 bits per pass, only the digits in which the keys differ).  Every boundary of the group is read
+// at its rank (offset of its bin inside the group + residual rank inside the bin); then all edges
+// of the group are known, and the group's keys are counted and summed per slot.  The slot below
+// the group's first edge is shared with the group before it: its figures go to the "upper" half
+// of the per-slot arrays, all others to the "lower" half, so that every entry has one writer.
 template <bool ORDERED>
-__global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT, u32 TG,
+__global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT,
                                                   const u32 *__restrict__ grp_list,
                                                   const u32 *__restrict__ n_grp_total, Bufs B)
 {
     extern __shared__ u32 smem[];
     u32 *bufA = smem;                      // [BUCKET_CAP]
     u32 *bufB = smem + BUCKET_CAP;         // [BUCKET_CAP]
-    u32 *wcount = smem + 2 * BUCKET_CAP;   // [16 waves][256 digits]
+    u32 *wcount = smem + 2 * BUCKET_CAP;   // [16 waves][256 digits]; later the group's edge keys
     __shared__ u32 hist[256];
     __shared__ u32 sh[3];
     __shared__ u32 s_diff;
@@ -851,24 +873,30 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
         const int t = (int)(packed >> 12);
         const u32 g = packed & 0xFFFu;
         TState *st = B.ts + t;
-        const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
-        const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
+        const u32 elo = B.grp_elo[(size_t)t * MAX_GROUPS + g];
+        const u32 ehi = B.grp_ehi[(size_t)t * MAX_GROUPS + g];
         __syncthreads();
         if (tid == 0) s_diff = 0u;
         __syncthreads();
-        if (gend <= goff) continue; // no keys in this window of the order
-        const u32 n = gend - goff;
+        if (elo >= ehi) continue; // no bin falls into this window of the order
+        const u32 n_e = ehi - elo;
+        const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
+        const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
+        const u32 n = gend > goff ? gend - goff : 0u;
         const u32 *src = B.pool2 + td[t].pool_thr + goff;
         const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
-        const u32 *tg = B.tgt_grp + (size_t)t * TGT_STRIDE;
         const u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
         const u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
         const u32 *thi = B.tgt_khi + (size_t)t * TGT_STRIDE;
         u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
         const u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
         const u32 *binfo = B.binfo + (size_t)t * L2_BINS;
+        const u16 *eitem = B.edge_item + (size_t)t * MAX_EDGES;
+        u32 *ekey = B.edges + (size_t)t * MAX_EDGES;
         const u32 zbin = st->zbin, nz = (u32)st->n_zero;
-        if (n <= (u32)BUCKET_CAP) {
+        const bool sorted = n <= (u32)BUCKET_CAP;
+        u32 *from = bufA, *to = bufB;
+        if (sorted && n) {
             const u32 first = gptr(src)[0];
             u32 diff = 0u;
             for (u32 i = tid; i < n; i += BLOCK) {
@@ -880,7 +908,6 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
             if (lane == 0u && diff) atomicOr(&s_diff, diff);
             __syncthreads();
             const u32 dbits = s_diff;
-            u32 *from = bufA, *to = bufB;
             const u32 rows = (n + BLOCK - 1u) / BLOCK; // rows of 64 keys per wave
             const u32 chunk = rows * 64u;
             u32 *wcnt = wcount + wave * 256u;
@@ -940,43 +967,146 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
                 from = to;
                 to = x;
             }
-            // every boundary of the group, at its rank
-            for (u32 i = tid; i < TG; i += BLOCK) {
-                const u32 bin = tb[i];
-                if (bin == RESOLVED || tg[i] != g) continue;
-                const u32 pop = h2[bin] - (bin == zbin ? nz : 0u);
-                const u32 res = tr[i];
-                const u32 pos = binfo[bin] - goff + res;
-                bool ok = res < pop && pos < n;
-                u32 key = 0u;
-                if (ok) {
-                    key = from[pos];
-                    ok = key >= tlo[i] && key <= thi[i];
+        }
+        // the buffer that does not hold the sorted keys, and the digit counters, are free now
+        u32 *ek = wcount;                                         // [n_e] edge keys
+        u32 *pp = to;                                             // [n_e + 1] keys below each edge
+        u32 *lcnt = to + EDGE_CAP;                                // [n_e + 1] keys per local slot
+        double *lsx = reinterpret_cast<double *>(to + 2 * EDGE_CAP); // [n_e + 1] their sums
+        __syncthreads();
+        for (u32 j = tid; j <= n_e; j += BLOCK) {
+            lcnt[j] = 0u;
+            lsx[j] = 0.0;
+        }
+        if (sorted) {
+            for (u32 j = tid; j < n_e; j += BLOCK) {
+                const u32 item = eitem[elo + j];
+                const u32 q = item / EPP, w = item % EPP;
+                u32 key = ekey[elo + j]; // class edges are known beforehand
+                if (w < (u32)NB8) {
+                    const u32 i = q * NB8 + w;
+                    const u32 bin = tb[i];
+                    if (bin == RESOLVED) {
+                        key = ZERO_KEY;
+                    } else {
+                        const u32 pop = h2[bin] - (bin == zbin ? nz : 0u);
+                        const u32 res = tr[i];
+                        const u32 pos = binfo[bin] - goff + res;
+                        bool ok = res < pop && pos < n;
+                        if (ok) {
+                            key = from[pos];
+                            ok = key >= tlo[i] && key <= thi[i];
+                        }
+                        if (ok)
+                            tk[i] = key;
+                        else
+                            atomicOr(&st->internal_err, 128u);
+                    }
+                    ekey[elo + j] = key;
                 }
-                if (ok)
-                    tk[i] = key;
-                else
-                    atomicOr(&st->internal_err, 128u);
+                ek[j] = key;
+                u32 lo = 0u, hi = n; // keys of the group below the edge
+                while (lo < hi) {
+                    const u32 mid = (lo + hi) >> 1;
+                    if (from[mid] < key)
+                        lo = mid + 1u;
+                    else
+                        hi = mid;
+                }
+                pp[j] = lo;
+            }
+            if (tid == 0u) pp[n_e] = n;
+            __syncthreads();
+            for (u32 j = tid; j <= n_e; j += BLOCK) {
+                const u32 below = j ? pp[j - 1u] : 0u;
+                if (pp[j] < below) atomicOr(&st->internal_err, 512u);
+                lcnt[j] = pp[j] - below;
+            }
+            // sums: every thread walks a run of consecutive sorted keys (odd length: no LDS bank
+            // is hit twice by a wave) and adds each slot's part once
+            const u32 per = ((n + BLOCK - 1u) / BLOCK) | 1u;
+            const u32 i0 = tid * per;
+            if (i0 < n) {
+                const u32 i1 = min(n, i0 + per);
+                u32 l = 0u, hi = n_e; // slot of key i0 = edges with pp <= i0
+                while (l < hi) {
+                    const u32 mid = (l + hi) >> 1;
+                    if (pp[mid] <= i0)
+                        l = mid + 1u;
+                    else
+                        hi = mid;
+                }
+                double acc = 0.0;
+                for (u32 i = i0; i < i1; i++) {
+                    while (l < n_e && pp[l] <= i) {
+                        if (acc != 0.0) atomicAdd(&lsx[l], acc);
+                        acc = 0.0;
+                        l++;
+                    }
+                    acc += (double)__uint_as_float(bits_of_key(from[i]));
+                }
+                if (acc != 0.0) atomicAdd(&lsx[l], acc);
             }
         } else {
             // a group too large for LDS (one bin of very many keys): every boundary is selected
-            // from the group's keys in device memory by the whole workgroup
-            for (u32 i = 0; i < TG; i++) {
-                const u32 bin = tb[i];
-                if (bin == RESOLVED || tg[i] != g) continue;
-                __syncthreads();
-                const u32 res = tr[i];
-                const u32 klo = tlo[i], khi = thi[i];
-                const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
-                const u32 key = block_select_range((const GLOBAL_AS u32 *)src, n, klo, khi, res,
-                                                   klo == ZERO_KEY, hist, sh);
-                if (tid == 0u) {
-                    if (sh[2] != expect || res >= expect)
-                        atomicOr(&st->internal_err, 128u);
-                    else
-                        tk[i] = key;
+            // from the group's keys in device memory by the whole workgroup, then the keys are
+            // classified one by one
+            for (u32 j = 0; j < n_e; j++) {
+                const u32 item = eitem[elo + j];
+                const u32 q = item / EPP, w = item % EPP;
+                u32 key = ekey[elo + j];
+                if (w < (u32)NB8) {
+                    const u32 i = q * NB8 + w;
+                    const u32 bin = tb[i];
+                    if (bin == RESOLVED) {
+                        key = ZERO_KEY;
+                    } else {
+                        __syncthreads();
+                        const u32 res = tr[i];
+                        const u32 klo = tlo[i], khi = thi[i];
+                        const u32 expect = h2[bin] - ((bin == zbin) ? nz : 0u);
+                        key = block_select_range((const GLOBAL_AS u32 *)src, n, klo, khi, res,
+                                                 klo == ZERO_KEY, hist, sh);
+                        if (tid == 0u) {
+                            if (sh[2] != expect || res >= expect)
+                                atomicOr(&st->internal_err, 128u);
+                            else
+                                tk[i] = key;
+                        }
+                    }
+                    if (tid == 0u) ekey[elo + j] = key;
                 }
+                if (tid == 0u) ek[j] = key;
             }
+            __syncthreads();
+            for (u32 i = tid; i < n; i += BLOCK) {
+                const u32 key = gptr(src)[i];
+                u32 l = 0u, hi = n_e; // edges at or below the key
+                while (l < hi) {
+                    const u32 mid = (l + hi) >> 1;
+                    if (ek[mid] <= key)
+                        l = mid + 1u;
+                    else
+                        hi = mid;
+                }
+                atomicAdd(&lcnt[l], 1u);
+                atomicAdd(&lsx[l], (double)__uint_as_float(bits_of_key(key)));
+            }
+        }
+        __syncthreads();
+        // exact zeros are counted, never gathered: they join the slot of the zero key
+        if (tid == 0u && nz && binfo[zbin] != INACTIVE && B.bin_group[(size_t)t * L2_BINS + zbin] == g) {
+            u32 l = 0u;
+            while (l < n_e && ek[l] <= ZERO_KEY) l++;
+            lcnt[l] += nz;
+        }
+        __syncthreads();
+        u32 *gc = B.grp_cnt + (size_t)t * 2 * MAX_EDGES;
+        double *gs = B.grp_sx + (size_t)t * 2 * MAX_EDGES;
+        for (u32 j = tid; j <= n_e; j += BLOCK) {
+            const u32 half = j ? 0u : (u32)MAX_EDGES; // slot elo: this group holds its upper edge
+            gc[half + elo + j] = lcnt[j];
+            gs[half + elo + j] = lsx[j];
         }
     }
 }
@@ -1001,6 +1131,8 @@ constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
 constexpr int SM_BUCKET = (2 * BUCKET_CAP + 16 * 256) * 4;
+constexpr int SM_GATHER = MAX_EDGES * 8 + COARSE * 4 + L2_BINS * 2;
+static_assert(16 * 256 >= EDGE_CAP && BUCKET_CAP >= 4 * EDGE_CAP, "edge scratch fits");
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
@@ -1011,6 +1143,7 @@ static hipError_t set_attrs()
     if ((e = hipFuncSetAttribute((const void *)k_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_gather, hipFuncAttributeMaxDynamicSharedMemorySize, SM_GATHER))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
@@ -1028,14 +1161,14 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
     PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
-    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
+    if ((e = launch_edges(bt, s))) return e;
+    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
     PROF("k_split", s, k_split<<<bt.n_units, BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
-    const u32 TG = bt.n_pairs * NB8;
     if (bt.lds_ordered)
-        PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
+        PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
     else
-        PROF("k_bucket_ballots", s, k_bucket<false><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, TG, bt.grp_list, bt.n_grp_total, B));
+        PROF("k_bucket_ballots", s, k_bucket<false><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
     return hipGetLastError();
 }
 
