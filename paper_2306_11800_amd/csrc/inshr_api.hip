@@ -226,12 +226,15 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             td[t].data = tensors[t].data;
             td[t].n = tensors[t].n;
             td[t].tile0 = tile;
+            // two gather regions per tensor, each of whole tiles: a wave's share of a region is
+            // 1024 keys per tile, whether or not the tensor's last tile is full
+            const u64 padded = (tensors[t].n + TILE - 1) / TILE * TILE;
             td[t].pool_thr = pool;
-            td[t].pool_cand = pool + tensors[t].n;
+            td[t].pool_cand = pool + padded;
             td[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
             td[t].pad = 0;
-            tile += (tensors[t].n + TILE - 1) / TILE;
-            pool += 2 * tensors[t].n;
+            tile += padded / TILE;
+            pool += 2 * padded;
         }
         for (int w = 0; w <= n_wg; w++) wg_tile0[w] = total_tiles * (u64)w / (u64)n_wg;
         u32 units = 0;
@@ -265,16 +268,17 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_ngt = cv.take(256);
         const size_t o_gcn = cv.take((size_t)nT * 2 * MAX_EDGES * 4);
         const size_t o_gsx = cv.take((size_t)nT * 2 * MAX_EDGES * 8);
+        const size_t o_to = cv.take((size_t)total_tiles * MAX_FRAC * 4);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
         const size_t o_us = cv.take((size_t)units * 8);
-        const size_t o_ut = cv.take((size_t)units * 4);
+        const size_t o_ut = cv.take((size_t)units * 16 * 4);
+        const size_t o_usb = cv.take((size_t)units * 4);
         const size_t o_bi = cv.take((size_t)nT * L2_BINS * 4);
         const size_t o_cur = cv.take((size_t)nT * CURSOR_STRIDE * 4);
         const size_t o_tb = cv.take((size_t)nT * TGT_STRIDE * 4);
         const size_t o_tr = cv.take((size_t)nT * TGT_STRIDE * 4);
         const size_t o_tk = cv.take((size_t)nT * TGT_STRIDE * 4);
-        const size_t o_to = cv.take((size_t)total_tiles * MAX_FRAC * 4);
         const size_t o_tf = cv.take((size_t)total_tiles * 4);
         const size_t o_sq = cv.take((size_t)units * SQ_STRIDE * 8);
         const size_t o_ed = cv.take((size_t)nT * MAX_EDGES * 4);
@@ -289,7 +293,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_cb = cv.take((size_t)nT * n_cfg * CB_STRIDE * 4);
         const size_t o_sc = cv.take((size_t)nT * n_cfg * sizeof(Score));
         const size_t o_bt = cv.take((size_t)nT * n_cfg * CB_STRIDE * 8);
-        const size_t o_uc = cv.take((size_t)units * 4);
+        const size_t o_uc = cv.take((size_t)units * 16 * 4);
         const size_t o_bg = cv.take((size_t)nT * L2_BINS * 2);
         const size_t o_go = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_ge = cv.take((size_t)nT * MAX_GROUPS * 4);
@@ -349,6 +353,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.table2 = (u32 *)(db + o_tab);
         B.unit_start = (u64 *)(db + o_us);
         B.unit_thr = (u32 *)(db + o_ut);
+        B.unit_sub = (u32 *)(db + o_usb);
         B.binfo = (u32 *)(db + o_bi);
         B.cursor2 = (u32 *)(db + o_cur);
         B.tgt_bin = (u32 *)(db + o_tb);

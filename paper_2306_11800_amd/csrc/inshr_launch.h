@@ -14,7 +14,8 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *hist1;     // [nT][32768]
     u32 *table2;    // [nT][4096]
     u64 *unit_start; // [units] first element of each (workgroup, tensor) unit inside its tensor
-    u32 *unit_thr;   // [units] threshold-bucket keys the unit gathered
+    u32 *unit_sub;   // [units] one wave's share of the unit's gather regions (1024 per tile)
+    u32 *unit_thr;   // [units][16] threshold-bucket keys each wave of the unit gathered
     u32 *hist2;     // [nT][32768]
     u32 *binfo;     // [nT][32768] offset of an active bin's elements in the gather pool, or INACTIVE
     u32 *cursor2;   // [nT][CURSOR_STRIDE]
@@ -23,7 +24,7 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *tgt_key;   // results: boundary keys
     u32 *pool;      // gathered keys: per tensor a threshold region and an active-bin region, n each
     u32 *pool2;     // same layout; the threshold region is reused for the keys in bin-group order
-    u32 *unit_cand; // [units] active-bin keys the unit gathered
+    u32 *unit_cand; // [units][16] active-bin keys each wave of the unit gathered
     u16 *bin_group; // [nT][32768] group of each active bin
     u32 *grp_off;   // [nT][MAX_GROUPS] first / one-past-last position of each group in bin order
     u32 *grp_end;

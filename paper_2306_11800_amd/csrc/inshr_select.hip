@@ -29,9 +29,9 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
     extern __shared__ u32 smem[];
     u32 *h = smem;                 // 32768 counters
     u32 *T = smem + L2_BINS;       // LEVEL 2: 4096 table entries
-    __shared__ u32 s_gathered; // LEVEL 2: keys this workgroup has gathered from the current tensor
+    __shared__ double s_red[BLOCK / 64];
 
-    const u32 tid = threadIdx.x, lane = tid & 63u;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     for (int i = tid; i < L2_BINS; i += BLOCK) h[i] = 0u;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
@@ -44,17 +44,21 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         const u64 t_end = d.tile0 + n_tiles_t;
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
+        const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
         // Elements of the thresholds' first-level magnitude bins are gathered into a region of the
-        // pool that belongs to this workgroup alone: it starts at the workgroup's first element of
-        // the tensor and cannot outgrow the workgroup's share, so no global counter is needed.
+        // pool that belongs to this wave alone: the workgroup's region starts at its first element
+        // of the tensor, and a wave's share of it is as large as the wave's share of the elements
+        // (1024 per tile), so no counter is shared.
         const u64 unit_start = (tile - d.tile0) * (u64)TILE;
-        u32 *gdst = B.pool + d.pool_thr + unit_start;
+        const u32 sub = (u32)(stop - tile) * (u32)(TILE / (BLOCK / 64));
+        GLOBAL_AS u32 *gdst = gptr(B.pool) + d.pool_thr + unit_start + (u64)wave * sub;
+        u32 gathered = 0u; // wave-uniform
         if (LEVEL == 2) {
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
-            if (tid == 0) s_gathered = 0u;
         }
         __syncthreads();
         u32 c_neg = 0u, c_zero = 0u, c_bad = 0u;
+        double q_tot = 0.0; // LEVEL 1: sum of squares
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
@@ -67,6 +71,8 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 const u32 b = canon_bits(__float_as_uint(v[i]));
                 const u32 key = key_of_bits(b);
                 if (LEVEL == 1) {
+                    const double xd = (double)v[i];
+                    q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
                     if (valid) {
                         c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
                         c_neg += (b >> 31);
@@ -79,13 +85,10 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                     // elements of a threshold's first-level magnitude bin are gathered
                     const bool cand = valid && in_threshold_bucket(key, entry) && b != 0u;
                     const u64 cm = __ballot(cand);
-                    if (cm) {
-                        u32 base = 0u;
-                        if (lane == (u32)__ffsll((unsigned long long)cm) - 1u)
-                            base = atomicAdd(&s_gathered, (u32)__popcll(cm));
-                        base = __shfl(base, __ffsll((unsigned long long)cm) - 1);
-                        if (cand) gdst[base + __popcll(cm & ((1ull << lane) - 1ull))] = key;
-                    }
+                    if (cand)
+                        gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32),
+                                                       __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key;
+                    gathered += (u32)__popcll(cm);
                 }
             }
         }
@@ -99,19 +102,29 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 h[i] = 0u;
             }
         }
-        if (LEVEL == 2 && tid == 0) {
-            const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
-            B.unit_start[fu] = unit_start;
-            B.unit_thr[fu] = s_gathered;
+        if (LEVEL == 2) {
+            if (lane == 0u) B.unit_thr[(size_t)fu * 16 + wave] = gathered;
+            if (tid == 0) {
+                B.unit_start[fu] = unit_start;
+                B.unit_sub[fu] = sub;
+            }
         }
         if (LEVEL == 1) {
             c_neg = wave_sum(c_neg);
             c_zero = wave_sum(c_zero);
             c_bad = wave_sum(c_bad);
-            if ((tid & 63u) == 0u) {
+            q_tot = wave_sum_f64(q_tot);
+            if (lane == 0u) {
                 if (c_neg) atomicAdd((unsigned long long *)&st->n_neg, (unsigned long long)c_neg);
                 if (c_zero) atomicAdd((unsigned long long *)&st->n_zero, (unsigned long long)c_zero);
                 if (c_bad) atomicOr(&st->nonfinite, 1u);
+                s_red[wave] = q_tot;
+            }
+            __syncthreads();
+            if (tid == 0) { // partial sum of squares of this (workgroup, tensor) unit, fixed order
+                double sum = 0.0;
+                for (int w = 0; w < BLOCK / 64; w++) sum += s_red[w];
+                B.sq_part[(size_t)fu * SQ_STRIDE] = sum;
             }
         }
         __syncthreads();
@@ -256,14 +269,15 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 constexpr int TSEL = 1024;
 
-// The gathered keys of a tensor lie in one fragment per (workgroup, tensor) unit, all buckets
-// mixed; a threshold looks at the keys whose magnitude falls in its own bucket.
+// The gathered keys of a tensor lie in 16 fragments (one per wave) per (workgroup, tensor) unit,
+// all buckets mixed; a threshold looks at the keys whose magnitude falls in its own bucket.
 struct Fragments {
     const u32 *pool;      // tensor's gather region
-    const u64 *start;     // per unit: first element of the fragment
-    const u32 *count;     // per unit: keys in the fragment
+    const u64 *start;     // per unit: first element of the unit's region
+    const u32 *sub;       // per unit: size of one wave's share of the region
+    const u32 *count;     // per unit and wave: keys in the fragment
     const u32 *ids;       // units of this tensor
-    u32 n_units;
+    u32 n_units;          // fragments = 16 * n_units
 };
 
 // k-th smallest magnitude among the gathered keys of magnitude bin mb (all share the bits above
@@ -278,10 +292,10 @@ __device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *h
         const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
         for (u32 i = tid; i < 512u; i += TSEL) hist[i] = 0u;
         __syncthreads();
-        for (u32 u = 0; u < f.n_units; u++) {
-            const u32 fu = f.ids[u];
-            const u32 *list = f.pool + f.start[fu];
-            const u32 c = f.count[fu];
+        for (u32 u = 0; u < 16u * f.n_units; u++) {
+            const u32 fu = f.ids[u >> 4];
+            const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
+            const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
             for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
                 u32 kk[4];
 #pragma unroll
@@ -349,6 +363,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
     Fragments f;
     f.pool = B.pool + td[t].pool_thr;
     f.start = B.unit_start;
+    f.sub = B.unit_sub;
     f.count = B.unit_thr;
     f.ids = t_fu_ids + t_fu_off[t];
     f.n_units = t_fu_off[t + 1] - t_fu_off[t];
@@ -365,10 +380,10 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
         if (tid == 0 && (u64)s_seen != expect) atomicOr(&st->internal_err, 4u);
     }
     u32 cn[4] = {0, 0, 0, 0};
-    for (u32 u = 0; u < f.n_units; u++) {
-        const u32 fu = f.ids[u];
-        const u32 *list = f.pool + f.start[fu];
-        const u32 c = f.count[fu];
+    for (u32 u = 0; u < 16u * f.n_units; u++) {
+        const u32 fu = f.ids[u >> 4];
+        const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
+        const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
         for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
             u32 kk[4];
 #pragma unroll
@@ -577,11 +592,9 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
     u32 *T = smem + 2 * MAX_EDGES;                             // [COARSE]
     u16 *SEG = reinterpret_cast<u16 *>(T + COARSE);            // [L2_BINS] slot of the bin, or 0xFFFF
     __shared__ u32 s_tau_o[MAX_FRAC];
-    __shared__ u32 s_oc[MAX_FRAC];
-    __shared__ u32 s_gathered;
     __shared__ double s_red[BLOCK / 64];
 
-    const u32 tid = threadIdx.x, lane = tid & 63u;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     const u32 n_p = gd->n_p, n_o = gd->n_o;
@@ -602,77 +615,72 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         }
         for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         for (u32 i = tid; i < n_slots; i += BLOCK) sx[i] = 0.0;
-        if (tid < MAX_FRAC) {
-            s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
-            s_oc[tid] = 0u;
-        }
-        if (tid == 0) s_gathered = 0u;
+        if (tid < MAX_FRAC) s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
         __syncthreads();
         u32 tau_o_min = 0x7fffffffu;
         for (u32 o = 0; o < n_o; o++) tau_o_min = min(tau_o_min, s_tau_o[o]);
-        // keys of active bins go to a region of the pool that belongs to this workgroup alone
-        // (it starts at the workgroup's first element of the tensor), in arrival order
+        // keys of active bins go, in arrival order, to a region of the pool that belongs to this
+        // wave alone (the workgroup's region starts at its first element of the tensor; a wave's
+        // share of it is as large as its share of the elements)
         const u64 unit_start = (tile - d.tile0) * (u64)TILE;
-        u32 *gdst = B.pool + d.pool_cand + unit_start;
-        double q_tot = 0.0;
+        const u32 sub = (u32)(stop - tile) * (u32)(TILE / (BLOCK / 64));
+        GLOBAL_AS u32 *gdst = gptr(B.pool) + d.pool_cand + unit_start + (u64)wave * sub;
+        u32 gathered = 0u; // wave-uniform
         double q_out[MAX_FRAC];
 #pragma unroll
         for (int o = 0; o < MAX_FRAC; o++) q_out[o] = 0.0;
-        for (; tile < stop; tile++) {
+        for (; tile < stop; tile++) { // no barrier inside: the waves drift apart freely
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
             float v[16];
             const u32 mask = load_tile(d, e0, cnt, v);
+            u32 oc[MAX_FRAC]; // protected values of this wave in this tile (wave-uniform)
+#pragma unroll
+            for (int o = 0; o < MAX_FRAC; o++) oc[o] = 0u;
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const bool valid = (mask >> i) & 1u;
                 const u32 b = canon_bits(__float_as_uint(v[i]));
                 const u32 key = key_of_bits(b);
-                const double xd = (double)v[i];
-                q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
                 const u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
                 const u32 slot = SEG[bin];
-                if (valid && slot != 0xFFFFu) atomicAdd(&sx[slot], xd);
+                if (valid && slot != 0xFFFFu) atomicAdd(&sx[slot], (double)v[i]);
                 const bool cand = valid && b != 0u && slot == 0xFFFFu;
                 const u64 cm = __ballot(cand);
-                if (cm) {
-                    u32 base = 0u;
-                    if (lane == (u32)__ffsll((unsigned long long)cm) - 1u)
-                        base = atomicAdd(&s_gathered, (u32)__popcll(cm));
-                    base = __shfl(base, __ffsll((unsigned long long)cm) - 1);
-                    if (cand) gdst[base + __popcll(cm & ((1ull << lane) - 1ull))] = key;
-                }
+                if (cand)
+                    gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32),
+                                                   __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key;
+                gathered += (u32)__popcll(cm);
                 const u32 m = b & 0x7fffffffu;
-                if (valid && m > tau_o_min) {
+                if (__ballot(valid && m > tau_o_min)) { // rare
+                    const double xd = (double)v[i];
 #pragma unroll
                     for (int o = 0; o < MAX_FRAC; o++) {
-                        if (o < (int)n_o && m > s_tau_o[o]) {
-                            q_out[o] = fma(xd, xd, q_out[o]);
-                            atomicAdd(&s_oc[o], 1u);
-                        }
+                        const bool out = o < (int)n_o && valid && m > s_tau_o[o];
+                        if (out) q_out[o] = fma(xd, xd, q_out[o]);
+                        oc[o] += (u32)__popcll(__ballot(out));
                     }
                 }
             }
-            __syncthreads();
-            if (tid < MAX_FRAC) {
-                B.tile_out[tile * MAX_FRAC + tid] = s_oc[tid];
-                s_oc[tid] = 0u;
+            if (lane == 0u) {
+#pragma unroll
+                for (int o = 0; o < MAX_FRAC; o++)
+                    if (oc[o]) atomicAdd(&B.tile_out[tile * MAX_FRAC + o], oc[o]); // cleared beforehand
             }
-            __syncthreads();
         }
+        __syncthreads();
         // flush partial sums of this (workgroup, tensor) unit in a fixed order
         const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
-        if (tid == 0) B.unit_cand[fu] = s_gathered;
+        if (lane == 0u) B.unit_cand[(size_t)fu * 16 + wave] = gathered;
         double *gs = B.mom_sx + (size_t)fu * MAX_EDGES;
         for (u32 i = tid; i < n_slots; i += BLOCK) gs[i] = sx[i];
         double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
 #pragma unroll
-        for (int o = 0; o <= MAX_FRAC; o++) {
+        for (int o = 1; o <= MAX_FRAC; o++) {
             if (o > (int)n_o) break;
-            double x = (o == 0) ? q_tot : q_out[o == 0 ? 0 : o - 1];
-            x = wave_sum_f64(x);
-            if ((tid & 63u) == 0u) s_red[tid >> 6] = x;
+            double x = wave_sum_f64(q_out[o - 1]);
+            if (lane == 0u) s_red[wave] = x;
             __syncthreads();
             if (tid == 0) {
                 double s = 0.0;
@@ -701,13 +709,16 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
 
     const u32 fu = blockIdx.x;
     const int t = (int)fu_tensor[fu];
-    const u32 tid = threadIdx.x;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const TDesc d = td[t];
     const TState *st = B.ts + t;
-    const u32 c = B.unit_cand[fu];
-    if (c == 0u) return;
+    // every wave splits the fragment that the same wave of the gathering sweep wrote
+    const u32 c = B.unit_cand[(size_t)fu * 16 + wave];
+    u32 cmax = 0u;
+    for (int w = 0; w < BLOCK / 64; w++) cmax = max(cmax, B.unit_cand[(size_t)fu * 16 + w]);
+    if (cmax == 0u) return;
     const u32 nb2 = st->nb2, G = st->n_groups;
-    const u32 *src = B.pool + d.pool_cand + B.unit_start[fu];
+    const u32 *src = B.pool + d.pool_cand + B.unit_start[fu] + (u64)wave * B.unit_sub[fu];
     u32 *dst = B.pool2 + d.pool_thr; // the tensor's second region, one key per slot in bin-group order
     const u32 *goff = B.grp_off + (size_t)t * MAX_GROUPS;
     u32 *gcur = B.grp_cur + (size_t)t * MAX_GROUPS;
@@ -715,16 +726,16 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
     for (u32 i = tid; i < nb2; i += BLOCK) gtab[i] = B.bin_group[(size_t)t * L2_BINS + i];
     for (u32 g = tid; g < G; g += BLOCK) gcount[g] = 0u;
     __syncthreads();
-    for (u32 base = 0; base < c; base += BLOCK * SPLIT_PER) {
+    for (u32 base = 0; base < cmax; base += 64u * SPLIT_PER) {
         u32 key[SPLIT_PER], gr[SPLIT_PER]; // group << 16 | rank inside (step, group)
 #pragma unroll
         for (int j = 0; j < SPLIT_PER; j++) {
-            const u32 i = base + tid + j * BLOCK;
+            const u32 i = base + lane + j * 64u;
             key[j] = (i < c) ? src[i] : 0u;
         }
 #pragma unroll
         for (int j = 0; j < SPLIT_PER; j++) {
-            const u32 i = base + tid + j * BLOCK;
+            const u32 i = base + lane + j * 64u;
             gr[j] = 0xFFFFFFFFu;
             if (i < c) {
                 const u32 g = gtab[l2_bin(key[j], T[key[j] >> COARSE_SHIFT])];
@@ -742,7 +753,7 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < SPLIT_PER; j++) {
-            const u32 i = base + tid + j * BLOCK;
+            const u32 i = base + lane + j * 64u;
             if (i < c && gr[j] != 0xFFFFFFFFu) dst[gbase[gr[j] >> 16] + (gr[j] & 0xFFFFu)] = key[j];
         }
         __syncthreads();
