@@ -244,7 +244,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             unsigned long long *pk = pk0 + buf * PKW;
             u32 *wcnt = qt.wcnt[buf];
             u32 omask, pre[4];
-            if (mask == 0xFFFFu)
+            if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
                 classify_tile<true>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);
             else
                 classify_tile<false>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);

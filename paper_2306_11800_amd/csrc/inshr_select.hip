@@ -21,6 +21,51 @@ namespace inshr {
 // ------------------------------------------------------------------------------------------
 // sweeps 1 and 2: histograms
 // ------------------------------------------------------------------------------------------
+// One tile of sweep 1: first-level histogram, sum of squares, sign / zero / non-finite counts.
+template <bool FULL>
+__device__ __forceinline__ void hist1_tile(const float (&v)[16], u32 mask, u32 *h, double &q_tot,
+                                           u32 &c_neg, u32 &c_zero, u32 &c_bad)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const bool valid = FULL || ((mask >> i) & 1u);
+        const u32 b = canon_bits(__float_as_uint(v[i]));
+        const u32 key = key_of_bits(b);
+        const double xd = (double)v[i];
+        q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
+        if (valid) {
+            c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
+            c_neg += (b >> 31);
+            c_zero += (b == 0u) ? 1u : 0u;
+            atomicAdd(&h[key >> L1_SHIFT], 1u);
+        }
+    }
+}
+
+// One tile of sweep 2: exact second-level histogram; the elements of a threshold's first-level
+// magnitude bin are appended to the wave's gather region.
+template <bool FULL>
+__device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *h, const u32 *T,
+                                           GLOBAL_AS u32 *gdst, u32 &gathered)
+{
+    u32 key[16], ent[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) { // all table reads are in flight together
+        key[i] = key_of_bits(canon_bits(__float_as_uint(v[i])));
+        ent[i] = T[key[i] >> COARSE_SHIFT];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const bool valid = FULL || ((mask >> i) & 1u);
+        if (valid) atomicAdd(&h[l2_bin(key[i], ent[i])], 1u);
+        const bool cand = valid && in_threshold_bucket(key[i], ent[i]) && key[i] != ZERO_KEY;
+        const u64 cm = __ballot(cand);
+        if (cand)
+            gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key[i];
+        gathered += (u32)__popcll(cm);
+    }
+}
+
 template <int LEVEL>
 __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, int nT,
                                                 const u64 *__restrict__ wg_tile0,
@@ -65,31 +110,16 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
             float v[16];
             const u32 mask = load_tile(d, e0, cnt, v);
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const bool valid = (mask >> i) & 1u;
-                const u32 b = canon_bits(__float_as_uint(v[i]));
-                const u32 key = key_of_bits(b);
-                if (LEVEL == 1) {
-                    const double xd = (double)v[i];
-                    q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
-                    if (valid) {
-                        c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
-                        c_neg += (b >> 31);
-                        c_zero += (b == 0u) ? 1u : 0u;
-                        atomicAdd(&h[key >> L1_SHIFT], 1u);
-                    }
-                } else {
-                    const u32 entry = T[key >> COARSE_SHIFT];
-                    if (valid) atomicAdd(&h[l2_bin(key, entry)], 1u);
-                    // elements of a threshold's first-level magnitude bin are gathered
-                    const bool cand = valid && in_threshold_bucket(key, entry) && b != 0u;
-                    const u64 cm = __ballot(cand);
-                    if (cand)
-                        gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32),
-                                                       __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key;
-                    gathered += (u32)__popcll(cm);
-                }
+            if (LEVEL == 1) {
+                if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
+                    hist1_tile<true>(v, mask, h, q_tot, c_neg, c_zero, c_bad);
+                else
+                    hist1_tile<false>(v, mask, h, q_tot, c_neg, c_zero, c_bad);
+            } else {
+                if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
+                    hist2_tile<true>(v, mask, h, T, gdst, gathered);
+                else
+                    hist2_tile<false>(v, mask, h, T, gdst, gathered);
             }
         }
         __syncthreads();
@@ -292,18 +322,18 @@ __device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *h
         const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
         for (u32 i = tid; i < 512u; i += TSEL) hist[i] = 0u;
         __syncthreads();
-        for (u32 u = 0; u < 16u * f.n_units; u++) {
+        for (u32 u = tid >> 6; u < 16u * f.n_units; u += TSEL / 64) { // one fragment per wave
             const u32 fu = f.ids[u >> 4];
             const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
             const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
-            for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
+            for (u32 i0 = tid & 63u; i0 < c; i0 += 256u) {
                 u32 kk[4];
 #pragma unroll
-                for (int j = 0; j < 4; j++) kk[j] = (i0 + j * TSEL < c) ? list[i0 + j * TSEL] : 0u;
+                for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
                     const u32 mag = mag_of_key(kk[j]);
-                    if (i0 + j * TSEL >= c || (mag >> L1_SHIFT) != mb) continue;
+                    if (i0 + j * 64u >= c || (mag >> L1_SHIFT) != mb) continue;
                     const u32 m = mag & 0x1FFFFu;
                     if (round == 0 || (m >> 8) == prefix)
                         atomicAdd(&hist[(m >> shift) & (nbin - 1u)], 1u);
@@ -380,19 +410,19 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
         if (tid == 0 && (u64)s_seen != expect) atomicOr(&st->internal_err, 4u);
     }
     u32 cn[4] = {0, 0, 0, 0};
-    for (u32 u = 0; u < 16u * f.n_units; u++) {
+    for (u32 u = tid >> 6; u < 16u * f.n_units; u += TSEL / 64) { // one fragment per wave
         const u32 fu = f.ids[u >> 4];
         const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
         const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
-        for (u32 i0 = tid; i0 < c; i0 += 4u * TSEL) {
+        for (u32 i0 = tid & 63u; i0 < c; i0 += 256u) {
             u32 kk[4];
 #pragma unroll
-            for (int j = 0; j < 4; j++) kk[j] = (i0 + j * TSEL < c) ? list[i0 + j * TSEL] : 0u;
+            for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 const u32 k = kk[j];
                 const u32 m = mag_of_key(k);
-                if (i0 + j * TSEL >= c || (m >> L1_SHIFT) != mb) continue;
+                if (i0 + j * 64u >= c || (m >> L1_SHIFT) != mb) continue;
                 const bool neg = key_is_neg(k);
                 cn[0] += (m < tau && neg) ? 1u : 0u;
                 cn[1] += (m < tau && !neg) ? 1u : 0u;
@@ -582,6 +612,50 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
 // alone (its value is added to the slot's sum), or it is gathered for the exact boundaries.  Also:
 // sums of squares, protected counts per tile.
 // ------------------------------------------------------------------------------------------
+template <bool FULL>
+__device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, const u32 *T, const u16 *SEG,
+                                            double *sx, GLOBAL_AS u32 *gdst, u32 &gathered,
+                                            u32 tau_o_min, const u32 *s_tau_o, u32 n_o,
+                                            double (&q_out)[MAX_FRAC], u32 (&oc)[MAX_FRAC])
+{
+    u32 key[16], slot[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        key[i] = key_of_bits(canon_bits(__float_as_uint(v[i])));
+        slot[i] = T[key[i] >> COARSE_SHIFT];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) slot[i] = SEG[l2_bin(key[i], slot[i])];
+    u32 mmax = 0u;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const bool valid = FULL || ((mask >> i) & 1u);
+        if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (double)v[i]);
+        const bool cand = valid && key[i] != ZERO_KEY && slot[i] == 0xFFFFu;
+        const u64 cm = __ballot(cand);
+        if (cand)
+            gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key[i];
+        gathered += (u32)__popcll(cm);
+        if (valid) mmax = max(mmax, mag_of_key(key[i]));
+    }
+    if (__ballot(mmax > tau_o_min)) { // rare: some value of the wave's 1024 is protected
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const bool valid = FULL || ((mask >> i) & 1u);
+            const u32 m = mag_of_key(key[i]);
+            if (__ballot(valid && m > tau_o_min)) {
+                const double xd = (double)v[i];
+#pragma unroll
+                for (int o = 0; o < MAX_FRAC; o++) {
+                    const bool out = o < (int)n_o && valid && m > s_tau_o[o];
+                    if (out) q_out[o] = fma(xd, xd, q_out[o]);
+                    oc[o] += (u32)__popcll(__ballot(out));
+                }
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, int nT,
                                                   const u64 *__restrict__ wg_tile0,
                                                   const u32 *__restrict__ wg_fu0,
@@ -638,31 +712,10 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
             u32 oc[MAX_FRAC]; // protected values of this wave in this tile (wave-uniform)
 #pragma unroll
             for (int o = 0; o < MAX_FRAC; o++) oc[o] = 0u;
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const bool valid = (mask >> i) & 1u;
-                const u32 b = canon_bits(__float_as_uint(v[i]));
-                const u32 key = key_of_bits(b);
-                const u32 bin = l2_bin(key, T[key >> COARSE_SHIFT]);
-                const u32 slot = SEG[bin];
-                if (valid && slot != 0xFFFFu) atomicAdd(&sx[slot], (double)v[i]);
-                const bool cand = valid && b != 0u && slot == 0xFFFFu;
-                const u64 cm = __ballot(cand);
-                if (cand)
-                    gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32),
-                                                   __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key;
-                gathered += (u32)__popcll(cm);
-                const u32 m = b & 0x7fffffffu;
-                if (__ballot(valid && m > tau_o_min)) { // rare
-                    const double xd = (double)v[i];
-#pragma unroll
-                    for (int o = 0; o < MAX_FRAC; o++) {
-                        const bool out = o < (int)n_o && valid && m > s_tau_o[o];
-                        if (out) q_out[o] = fma(xd, xd, q_out[o]);
-                        oc[o] += (u32)__popcll(__ballot(out));
-                    }
-                }
-            }
+            if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
+                gather_tile<true>(v, mask, T, SEG, sx, gdst, gathered, tau_o_min, s_tau_o, n_o, q_out, oc);
+            else
+                gather_tile<false>(v, mask, T, SEG, sx, gdst, gathered, tau_o_min, s_tau_o, n_o, q_out, oc);
             if (lane == 0u) {
 #pragma unroll
                 for (int o = 0; o < MAX_FRAC; o++)

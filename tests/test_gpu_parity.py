@@ -230,6 +230,18 @@ def test_heavy_duplicates_exceed_the_lds_sort(ctx):
     run_pipeline(ctx, [prev, mixed], [cur, mixed.copy()], synth.grid_small(), synth.EPS_DEFAULT)
 
 
+def test_protected_values_in_the_last_lanes_of_a_ragged_tile(ctx):
+    """The protected values sit at the very end of a tensor whose last tile misses one element, so
+    that the last lane of the last wave sees fewer valid elements than its neighbours."""
+    rng = np.random.default_rng(13)
+    n = 2 * 16384 - 1
+    prev = (0.01 * rng.standard_normal(n)).astype(np.float32)
+    prev[-40:] = ((10.0 + np.arange(40)) * np.where(np.arange(40) % 3 == 0, -1.0, 1.0)).astype(np.float32)
+    cur = prev.copy()
+    cur[:1000] += (1e-4 * rng.standard_normal(1000)).astype(np.float32)
+    run_pipeline(ctx, [prev], [cur], synth.grid_small(), synth.EPS_DEFAULT)
+
+
 def test_without_lane_ordered_lds_atomics():
     """The group sort and the delta scatter have a ballot-based path for devices whose LDS atomics
     do not return in lane order; INSHR_NO_LDS_ORDER=1 selects it."""
