@@ -339,7 +339,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         bt.grp_list = (u32 *)(db + o_gl);
         bt.n_grp_total = (u32 *)(db + o_ngt);
         bt.n_units = (int)units;
-        bt.n_bucket_blocks = c->n_cu * 2;
+        bt.n_bucket_blocks = c->n_cu * 4;
         bt.lds_ordered = c->lds_ordered;
         bt.nT = (int)nT;
         bt.n_wg = n_wg;

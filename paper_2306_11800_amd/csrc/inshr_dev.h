@@ -41,8 +41,8 @@ constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 =
 constexpr int EPP = NB8 + 4;        // edges per pair: 255 boundaries + 4 class edges
 constexpr int EIDX_STRIDE = 260;    // per-pair stride of the edge positions
 constexpr int MAX_CFG = 256;
-constexpr int GROUP_SHIFT = 13;     // gathered keys per group of active bins: about 2^13
-constexpr int MAX_GROUPS = 4096;    // groups per tensor (the shift grows for huge tensors)
+constexpr int GROUP_SHIFT = 12;     // gathered keys per group of active bins: about 2^12
+constexpr int MAX_GROUPS = 8192;    // groups per tensor (the shift grows for huge tensors)
 constexpr u32 INACTIVE = 0xFFFFFFFFu;
 constexpr u32 RESOLVED = 0xFFFFFFFEu;
 constexpr u32 ZERO_KEY = 0x80000000u;

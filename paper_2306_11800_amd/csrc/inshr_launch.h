@@ -61,7 +61,7 @@ struct Batch {
     const u32 *t_fu_off; // device [nT + 1] CSR of the units that touch each tensor ...
     const u32 *t_fu_ids; // device         ... in ascending workgroup order
     const u32 *fu_tensor; // device [units] tensor of each unit
-    u32 *grp_list;       // device [nT * MAX_GROUPS] (tensor << 12 | group) of every group
+    u32 *grp_list;       // device [nT * MAX_GROUPS] (tensor << 13 | group) of every group
     u32 *n_grp_total;    // device
     int nT;
     int n_wg;

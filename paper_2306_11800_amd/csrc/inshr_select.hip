@@ -816,12 +816,16 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 // exact boundaries: residual-rank element of the boundary's bin, searched in the bin's group
 // ------------------------------------------------------------------------------------------
-constexpr int BUCKET_CAP = 16384;  // keys of a group sorted in LDS
-constexpr int SORT_ROWS = BUCKET_CAP / BLOCK; // rows of 64 keys per wave and pass, at most
+constexpr int BB = 512;            // threads of a group-sort workgroup: two workgroups share a CU
+constexpr int BUCKET_CAP = 8192;   // keys of a group sorted in LDS
+constexpr int SORT_ROWS = BUCKET_CAP / BB; // keys per thread
 constexpr int EDGE_CAP = MAX_PAIRS * EPP + 11; // edges of a group (all of a tensor's at most) + 1, even
+constexpr int SLOT_WIN = 1024;     // slots summed per round (a group rarely has more than a few dozen)
+static_assert(2 * EDGE_CAP <= BUCKET_CAP && 2 * SLOT_WIN <= (BB / 64) * 256, "edge scratch fits");
 
 // k-th smallest of the keys in [klo, khi] (khi - klo + 1 a power of two) among a[0..n), by the whole
-// workgroup: radix select, 8 bits per round, LDS histogram.  *found = keys in the range (in sh[2]).
+// workgroup of BB threads: radix select, 8 bits per round, LDS histogram.  *found = keys in the
+// range (in sh[2]).
 template <class Ptr>
 __device__ inline u32 block_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, bool skip_zero,
                                          u32 *hist /*[256]*/, u32 *sh /*[3]*/)
@@ -832,15 +836,15 @@ __device__ inline u32 block_select_range(Ptr a, u32 n, u32 klo, u32 khi, u32 k, 
     bool first = true;
     while (R > 0) {
         const int w = R < 8 ? R : 8;
-        for (u32 i = tid; i < 256u; i += BLOCK) hist[i] = 0u;
+        for (u32 i = tid; i < 256u; i += BB) hist[i] = 0u;
         __syncthreads();
-        for (u32 i0 = 0; i0 < n; i0 += 4u * BLOCK) {
+        for (u32 i0 = 0; i0 < n; i0 += 4u * BB) {
             u32 v[4];
 #pragma unroll
-            for (int j = 0; j < 4; j++) v[j] = (i0 + tid + j * BLOCK < n) ? a[i0 + tid + j * BLOCK] : 0u;
+            for (int j = 0; j < 4; j++) v[j] = (i0 + tid + j * BB < n) ? a[i0 + tid + j * BB] : 0u;
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                if (i0 + tid + j * BLOCK >= n || v[j] < klo || v[j] > khi) continue;
+                if (i0 + tid + j * BB >= n || v[j] < klo || v[j] > khi) continue;
                 if (skip_zero && v[j] == ZERO_KEY) continue;
                 const u32 rel = v[j] - klo;
                 if (!first && (rel >> R) != P) continue;
@@ -910,43 +914,95 @@ __device__ __forceinline__ u32 digit_rank(u32 *wcnt, u32 digit, bool valid)
     return old + rank;
 }
 
+struct GroupHead { // one (tensor, group) of the work list
+    int t;
+    u32 g, elo, ehi, goff, n;
+};
+__device__ __forceinline__ GroupHead group_head(const Bufs &B, const u32 *grp_list, u32 idx)
+{
+    GroupHead h;
+    const u32 packed = grp_list[idx];
+    h.t = (int)(packed >> 13);
+    h.g = packed & 0x1FFFu;
+    h.elo = B.grp_elo[(size_t)h.t * MAX_GROUPS + h.g];
+    h.ehi = B.grp_ehi[(size_t)h.t * MAX_GROUPS + h.g];
+    h.goff = B.grp_off[(size_t)h.t * MAX_GROUPS + h.g];
+    const u32 gend = B.grp_end[(size_t)h.t * MAX_GROUPS + h.g];
+    h.n = (h.elo < h.ehi && gend > h.goff) ? gend - h.goff : 0u;
+    return h;
+}
+
 // One group of active bins per step: its keys are sorted in LDS (least significant digit first,
 // 8 bits per pass, only the digits in which the keys differ).  Every boundary of the group is read
 // at its rank (offset of its bin inside the group + residual rank inside the bin); then all edges
 // of the group are known, and the group's keys are counted and summed per slot.  The slot below
 // the group's first edge is shared with the group before it: its figures go to the "upper" half
 // of the per-slot arrays, all others to the "lower" half, so that every entry has one writer.
+// The keys of the next group travel from device memory while this one is worked on.
 template <bool ORDERED>
-__global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, int nT,
-                                                  const u32 *__restrict__ grp_list,
-                                                  const u32 *__restrict__ n_grp_total, Bufs B)
+__global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int nT,
+                                               const u32 *__restrict__ grp_list,
+                                               const u32 *__restrict__ n_grp_total, Bufs B)
 {
     extern __shared__ u32 smem[];
     u32 *bufA = smem;                      // [BUCKET_CAP]
     u32 *bufB = smem + BUCKET_CAP;         // [BUCKET_CAP]
-    u32 *wcount = smem + 2 * BUCKET_CAP;   // [16 waves][256 digits]; later the group's edge keys
+    u32 *wcount = smem + 2 * BUCKET_CAP;   // [8 waves][256 digits]; later the sums of a slot window
     __shared__ u32 hist[256];
     __shared__ u32 sh[3];
-    __shared__ u32 s_diff;
+    __shared__ u32 s_or, s_and, s_lz;
     __shared__ u32 wsum[4];
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 total = *n_grp_total;
+    u32 kpre[SORT_ROWS];
+    GroupHead nxt;
+    auto prefetch = [&](u32 idx2) {
+        nxt = group_head(B, grp_list, idx2);
+        if (nxt.n && nxt.n <= (u32)BUCKET_CAP) {
+            const GLOBAL_AS u32 *src2 = gptr(B.pool2) + td[nxt.t].pool_thr + nxt.goff;
+#pragma unroll
+            for (int r = 0; r < SORT_ROWS; r++) {
+                const u32 i = tid + r * BB;
+                kpre[r] = (i < nxt.n) ? src2[i] : 0u;
+            }
+        }
+    };
+    if (blockIdx.x < total) prefetch(blockIdx.x);
     for (u32 idx = blockIdx.x; idx < total; idx += gridDim.x) {
-        const u32 packed = grp_list[idx];
-        const int t = (int)(packed >> 12);
-        const u32 g = packed & 0xFFFu;
+        const GroupHead hd = nxt;
+        const int t = hd.t;
+        const u32 g = hd.g, elo = hd.elo, ehi = hd.ehi, goff = hd.goff, n = hd.n;
         TState *st = B.ts + t;
-        const u32 elo = B.grp_elo[(size_t)t * MAX_GROUPS + g];
-        const u32 ehi = B.grp_ehi[(size_t)t * MAX_GROUPS + g];
         __syncthreads();
-        if (tid == 0) s_diff = 0u;
+        if (tid == 0) {
+            s_or = 0u;
+            s_and = 0xFFFFFFFFu;
+            s_lz = 0xFFFFFFFFu;
+        }
         __syncthreads();
+        const bool sorted = n <= (u32)BUCKET_CAP;
+        if (sorted && n) { // keys that were fetched ahead -> LDS
+            u32 vo = 0u, va = 0xFFFFFFFFu;
+#pragma unroll
+            for (int r = 0; r < SORT_ROWS; r++) {
+                const u32 i = tid + r * BB;
+                if (i < n) {
+                    bufA[i] = kpre[r];
+                    vo |= kpre[r];
+                    va &= kpre[r];
+                }
+            }
+            vo = wave_or(vo);
+            va = wave_and(va);
+            if (lane == 0u) {
+                atomicOr(&s_or, vo);
+                atomicAnd(&s_and, va);
+            }
+        }
+        if (idx + gridDim.x < total) prefetch(idx + gridDim.x);
         if (elo >= ehi) continue; // no bin falls into this window of the order
         const u32 n_e = ehi - elo;
-        const u32 goff = B.grp_off[(size_t)t * MAX_GROUPS + g];
-        const u32 gend = B.grp_end[(size_t)t * MAX_GROUPS + g];
-        const u32 n = gend > goff ? gend - goff : 0u;
         const u32 *src = B.pool2 + td[t].pool_thr + goff;
         const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
         const u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
@@ -958,26 +1014,16 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
         const u16 *eitem = B.edge_item + (size_t)t * MAX_EDGES;
         u32 *ekey = B.edges + (size_t)t * MAX_EDGES;
         const u32 zbin = st->zbin, nz = (u32)st->n_zero;
-        const bool sorted = n <= (u32)BUCKET_CAP;
         u32 *from = bufA, *to = bufB;
         if (sorted && n) {
-            const u32 first = gptr(src)[0];
-            u32 diff = 0u;
-            for (u32 i = tid; i < n; i += BLOCK) {
-                const u32 k = gptr(src)[i];
-                bufA[i] = k;
-                diff |= k ^ first;
-            }
-            diff = wave_or(diff);
-            if (lane == 0u && diff) atomicOr(&s_diff, diff);
             __syncthreads();
-            const u32 dbits = s_diff;
-            const u32 rows = (n + BLOCK - 1u) / BLOCK; // rows of 64 keys per wave
+            const u32 dbits = s_or ^ s_and; // bits in which the keys differ
+            const u32 rows = (n + BB - 1u) / BB; // rows of 64 keys per wave
             const u32 chunk = rows * 64u;
             u32 *wcnt = wcount + wave * 256u;
             for (u32 shift = 0; shift < 32u && (dbits >> shift) != 0u; shift += 8u) {
                 if (((dbits >> shift) & 255u) == 0u) continue; // this digit is the same in all keys
-                for (u32 i = tid; i < 16u * 256u; i += BLOCK) wcount[i] = 0u;
+                for (u32 i = tid; i < (BB / 64) * 256u; i += BB) wcount[i] = 0u;
                 __syncthreads();
                 u32 kreg[SORT_ROWS], rreg[SORT_ROWS];
 #pragma unroll
@@ -997,7 +1043,7 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
                 u32 tot = 0u, excl = 0u;
                 if (tid < 256u) {
 #pragma unroll
-                    for (int w = 0; w < 16; w++) tot += wcount[w * 256 + tid];
+                    for (int w = 0; w < BB / 64; w++) tot += wcount[w * 256 + tid];
                     u32 inc = tot;
 #pragma unroll
                     for (int o = 1; o < 64; o <<= 1) {
@@ -1012,7 +1058,7 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
                     u32 run = excl;
                     for (u32 w = 0; w < wave; w++) run += wsum[w];
 #pragma unroll
-                    for (int w = 0; w < 16; w++) {
+                    for (int w = 0; w < BB / 64; w++) {
                         const u32 c = wcount[w * 256 + tid];
                         wcount[w * 256 + tid] = run;
                         run += c;
@@ -1033,17 +1079,13 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
             }
         }
         // the buffer that does not hold the sorted keys, and the digit counters, are free now
-        u32 *ek = wcount;                                         // [n_e] edge keys
-        u32 *pp = to;                                             // [n_e + 1] keys below each edge
-        u32 *lcnt = to + EDGE_CAP;                                // [n_e + 1] keys per local slot
-        double *lsx = reinterpret_cast<double *>(to + 2 * EDGE_CAP); // [n_e + 1] their sums
+        u32 *ek = to;                                   // [n_e] edge keys
+        u32 *pp = to + EDGE_CAP;                        // [n_e + 1] keys below each edge (sorted)
+        u32 *lcnt = from;                               // [n_e + 1] keys per slot (not sorted)
+        double *lsx = reinterpret_cast<double *>(wcount); // [SLOT_WIN] sums of the current window
         __syncthreads();
-        for (u32 j = tid; j <= n_e; j += BLOCK) {
-            lcnt[j] = 0u;
-            lsx[j] = 0.0;
-        }
         if (sorted) {
-            for (u32 j = tid; j < n_e; j += BLOCK) {
+            for (u32 j = tid; j < n_e; j += BB) {
                 const u32 item = eitem[elo + j];
                 const u32 q = item / EPP, w = item % EPP;
                 u32 key = ekey[elo + j]; // class edges are known beforehand
@@ -1080,41 +1122,10 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
                 pp[j] = lo;
             }
             if (tid == 0u) pp[n_e] = n;
-            __syncthreads();
-            for (u32 j = tid; j <= n_e; j += BLOCK) {
-                const u32 below = j ? pp[j - 1u] : 0u;
-                if (pp[j] < below) atomicOr(&st->internal_err, 512u);
-                lcnt[j] = pp[j] - below;
-            }
-            // sums: every thread walks a run of consecutive sorted keys (odd length: no LDS bank
-            // is hit twice by a wave) and adds each slot's part once
-            const u32 per = ((n + BLOCK - 1u) / BLOCK) | 1u;
-            const u32 i0 = tid * per;
-            if (i0 < n) {
-                const u32 i1 = min(n, i0 + per);
-                u32 l = 0u, hi = n_e; // slot of key i0 = edges with pp <= i0
-                while (l < hi) {
-                    const u32 mid = (l + hi) >> 1;
-                    if (pp[mid] <= i0)
-                        l = mid + 1u;
-                    else
-                        hi = mid;
-                }
-                double acc = 0.0;
-                for (u32 i = i0; i < i1; i++) {
-                    while (l < n_e && pp[l] <= i) {
-                        if (acc != 0.0) atomicAdd(&lsx[l], acc);
-                        acc = 0.0;
-                        l++;
-                    }
-                    acc += (double)__uint_as_float(bits_of_key(from[i]));
-                }
-                if (acc != 0.0) atomicAdd(&lsx[l], acc);
-            }
         } else {
             // a group too large for LDS (one bin of very many keys): every boundary is selected
-            // from the group's keys in device memory by the whole workgroup, then the keys are
-            // classified one by one
+            // from the group's keys in device memory by the whole workgroup
+            for (u32 j = tid; j <= n_e; j += BB) lcnt[j] = 0u;
             for (u32 j = 0; j < n_e; j++) {
                 const u32 item = eitem[elo + j];
                 const u32 q = item / EPP, w = item % EPP;
@@ -1142,35 +1153,75 @@ __global__ __launch_bounds__(BLOCK) void k_bucket(const TDesc *__restrict__ td, 
                 }
                 if (tid == 0u) ek[j] = key;
             }
-            __syncthreads();
-            for (u32 i = tid; i < n; i += BLOCK) {
-                const u32 key = gptr(src)[i];
-                u32 l = 0u, hi = n_e; // edges at or below the key
-                while (l < hi) {
-                    const u32 mid = (l + hi) >> 1;
-                    if (ek[mid] <= key)
-                        l = mid + 1u;
-                    else
-                        hi = mid;
-                }
-                atomicAdd(&lcnt[l], 1u);
-                atomicAdd(&lsx[l], (double)__uint_as_float(bits_of_key(key)));
-            }
         }
         __syncthreads();
         // exact zeros are counted, never gathered: they join the slot of the zero key
         if (tid == 0u && nz && binfo[zbin] != INACTIVE && B.bin_group[(size_t)t * L2_BINS + zbin] == g) {
             u32 l = 0u;
             while (l < n_e && ek[l] <= ZERO_KEY) l++;
-            lcnt[l] += nz;
+            s_lz = l;
         }
-        __syncthreads();
+        if (sorted)
+            for (u32 j = tid + 1u; j <= n_e; j += BB)
+                if (pp[j] < pp[j - 1u]) atomicOr(&st->internal_err, 512u);
         u32 *gc = B.grp_cnt + (size_t)t * 2 * MAX_EDGES;
         double *gs = B.grp_sx + (size_t)t * 2 * MAX_EDGES;
-        for (u32 j = tid; j <= n_e; j += BLOCK) {
-            const u32 half = j ? 0u : (u32)MAX_EDGES; // slot elo: this group holds its upper edge
-            gc[half + elo + j] = lcnt[j];
-            gs[half + elo + j] = lsx[j];
+        // counts and sums per slot, a window of slots at a time
+        for (u32 w0 = 0; w0 <= n_e; w0 += SLOT_WIN) {
+            for (u32 j = tid; j < (u32)SLOT_WIN; j += BB) lsx[j] = 0.0;
+            __syncthreads();
+            if (sorted) {
+                // every thread walks a run of consecutive sorted keys (odd length: no LDS bank is
+                // hit twice by a wave) and adds each slot's part once
+                const u32 per = ((n + BB - 1u) / BB) | 1u;
+                const u32 i0 = tid * per;
+                if (i0 < n) {
+                    const u32 i1 = min(n, i0 + per);
+                    u32 l = 0u, hi = n_e; // slot of key i0 = edges with pp <= i0
+                    while (l < hi) {
+                        const u32 mid = (l + hi) >> 1;
+                        if (pp[mid] <= i0)
+                            l = mid + 1u;
+                        else
+                            hi = mid;
+                    }
+                    double acc = 0.0;
+                    for (u32 i = i0; i < i1; i++) {
+                        while (l < n_e && pp[l] <= i) {
+                            if (acc != 0.0 && l - w0 < (u32)SLOT_WIN) atomicAdd(&lsx[l - w0], acc);
+                            acc = 0.0;
+                            l++;
+                        }
+                        acc += (double)__uint_as_float(bits_of_key(from[i]));
+                    }
+                    if (acc != 0.0 && l - w0 < (u32)SLOT_WIN) atomicAdd(&lsx[l - w0], acc);
+                }
+            } else {
+                for (u32 i = tid; i < n; i += BB) {
+                    const u32 key = gptr(src)[i];
+                    u32 l = 0u, hi = n_e; // edges at or below the key
+                    while (l < hi) {
+                        const u32 mid = (l + hi) >> 1;
+                        if (ek[mid] <= key)
+                            l = mid + 1u;
+                        else
+                            hi = mid;
+                    }
+                    if (l - w0 < (u32)SLOT_WIN) {
+                        atomicAdd(&lcnt[l], 1u);
+                        atomicAdd(&lsx[l - w0], (double)__uint_as_float(bits_of_key(key)));
+                    }
+                }
+            }
+            __syncthreads();
+            for (u32 j = w0 + tid; j <= n_e && j < w0 + (u32)SLOT_WIN; j += BB) {
+                u32 c = sorted ? pp[j] - (j ? pp[j - 1u] : 0u) : lcnt[j];
+                if (j == s_lz) c += nz;
+                const u32 half = j ? 0u : (u32)MAX_EDGES; // slot elo: this group holds its upper edge
+                gc[half + elo + j] = c;
+                gs[half + elo + j] = lsx[j - w0];
+            }
+            __syncthreads();
         }
     }
 }
@@ -1183,7 +1234,7 @@ __global__ void k_group_list(int nT, Bufs B, u32 *grp_list, u32 *n_grp_total)
     const u32 G = B.ts[t].n_groups;
     if (G == 0u) return;
     const u32 at = atomicAdd(n_grp_total, G);
-    for (u32 g = 0; g < G; g++) grp_list[at + g] = ((u32)t << 12) | g;
+    for (u32 g = 0; g < G; g++) grp_list[at + g] = ((u32)t << 13) | g;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1194,9 +1245,8 @@ constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
-constexpr int SM_BUCKET = (2 * BUCKET_CAP + 16 * 256) * 4;
+constexpr int SM_BUCKET = (2 * BUCKET_CAP + (BB / 64) * 256) * 4;
 constexpr int SM_GATHER = MAX_EDGES * 8 + COARSE * 4 + L2_BINS * 2;
-static_assert(16 * 256 >= EDGE_CAP && BUCKET_CAP >= 4 * EDGE_CAP, "edge scratch fits");
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
@@ -1230,9 +1280,9 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
     PROF("k_split", s, k_split<<<bt.n_units, BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     if (bt.lds_ordered)
-        PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
+        PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BB, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
     else
-        PROF("k_bucket_ballots", s, k_bucket<false><<<bt.n_bucket_blocks, BLOCK, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
+        PROF("k_bucket_ballots", s, k_bucket<false><<<bt.n_bucket_blocks, BB, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
     return hipGetLastError();
 }
 
