@@ -100,22 +100,38 @@ class InshrError(RuntimeError):
         self.code = code
 
 
-@dataclass
 class Quantized:
-    """Device-side result of quantizing one tensor."""
-    n: int
-    bits: int
-    sym_bits: int
-    packed: torch.Tensor        # int64 words (bit pattern of u64)
-    codebook: torch.Tensor      # float32 [K]
-    boundaries: torch.Tensor    # float32 [K-1]
-    outlier_idx: torch.Tensor   # int32 (bit pattern of u32) [n_outlier]
-    outlier_val: torch.Tensor   # float32 [n_outlier]
-    n_pruned: int
-    n_outlier: int
-    n_kept: int
-    tau_prune: float
-    tau_outlier: float
+    """Device-side result of quantizing one tensor.  The tensors are views of buffers allocated at
+    the capacity inshr_quantize_bound gives; the views are made when they are asked for."""
+    __slots__ = ("n", "bits", "sym_bits", "n_pruned", "n_outlier", "n_kept", "tau_prune",
+                 "tau_outlier", "_bufs", "_ptrs")
+
+    def __init__(self, n, bits, bufs):
+        self.n, self.bits, self.sym_bits = n, bits, bits + 1
+        self.n_pruned = self.n_outlier = self.n_kept = 0
+        self.tau_prune = self.tau_outlier = 0.0
+        self._bufs = bufs                                   # packed, codebook, boundaries, idx, val
+        self._ptrs = tuple(b.data_ptr() for b in bufs)
+
+    @property
+    def packed(self) -> torch.Tensor:        # int64 words (bit pattern of u64)
+        return self._bufs[0][:(self.n * self.sym_bits + 63) // 64]
+
+    @property
+    def codebook(self) -> torch.Tensor:      # float32 [K]
+        return self._bufs[1][:1 << self.bits]
+
+    @property
+    def boundaries(self) -> torch.Tensor:    # float32 [K-1]
+        return self._bufs[2][:(1 << self.bits) - 1]
+
+    @property
+    def outlier_idx(self) -> torch.Tensor:   # int32 (bit pattern of u32) [n_outlier]
+        return self._bufs[3][:self.n_outlier]
+
+    @property
+    def outlier_val(self) -> torch.Tensor:   # float32 [n_outlier]
+        return self._bufs[4][:self.n_outlier]
 
 
 @dataclass
@@ -156,6 +172,7 @@ class Context:
         if rc:
             raise InshrError(rc, self.lib.inshr_strerror(rc).decode())
         self.h = h
+        self._bounds = {}
 
     def close(self):
         if getattr(self, "h", None):
@@ -210,43 +227,42 @@ class Context:
         ta = _tensor_array(tensors)
         ca = _config_array(cfgs)
         qa = (CQuantized * nT)()
-        bufs = []
+        res: List[Quantized] = []
         for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
-            words, cap = C.c_uint64(), C.c_uint64()
-            self._check(self.lib.inshr_quantize_bound(t.numel(), C.byref(ca[i]), C.byref(words), C.byref(cap)))
-            K = 1 << int(cfg[0])
+            n = t.numel()
+            words, cap = self._bound(n, ca[i], cfg)
             if out is not None:
-                packed, cb, bd, oi, ov = out[i]._bufs
-                if packed.numel() < words.value or oi.numel() < cap.value:
+                q = out[i]
+                if q.n != n or q._bufs[0].numel() < words or q._bufs[3].numel() < cap:
                     raise ValueError("pre-allocated buffers are too small")
+                q.bits, q.sym_bits = int(cfg[0]), int(cfg[0]) + 1
             else:
-                packed = torch.empty(words.value, dtype=torch.int64, device=t.device)
-                cb = torch.empty(256, dtype=torch.float32, device=t.device)
-                bd = torch.empty(255, dtype=torch.float32, device=t.device)
-                oi = torch.empty(max(cap.value, 1), dtype=torch.int32, device=t.device)
-                ov = torch.empty(max(cap.value, 1), dtype=torch.float32, device=t.device)
-            qa[i].packed = packed.data_ptr()
-            qa[i].packed_words = packed.numel()
-            qa[i].codebook = cb.data_ptr()
-            qa[i].boundaries = bd.data_ptr()
-            qa[i].outlier_idx = oi.data_ptr()
-            qa[i].outlier_val = ov.data_ptr()
-            qa[i].outlier_cap = cap.value
-            bufs.append((packed, cb, bd, oi, ov, K))
-        self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, INSHR_REUSE_SEARCH if reuse_search else 0))
-        res = []
-        for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
-            packed, cb, bd, oi, ov, K = bufs[i]
-            no = int(qa[i].n_outlier)
-            w = int(qa[i].sym_bits)
-            q = Quantized(n=t.numel(), bits=int(cfg[0]), sym_bits=w,
-                          packed=packed[:(t.numel() * w + 63) // 64], codebook=cb[:K],
-                          boundaries=bd[:K - 1], outlier_idx=oi[:no], outlier_val=ov[:no],
-                          n_pruned=int(qa[i].n_pruned), n_outlier=no, n_kept=int(qa[i].n_kept),
-                          tau_prune=float(qa[i].tau_prune), tau_outlier=float(qa[i].tau_outlier))
-            q._bufs = (packed, cb, bd, oi, ov)
+                q = Quantized(n, int(cfg[0]), (
+                    torch.empty(words, dtype=torch.int64, device=t.device),
+                    torch.empty(256, dtype=torch.float32, device=t.device),
+                    torch.empty(255, dtype=torch.float32, device=t.device),
+                    torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
+                    torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)))
+            e = qa[i]
+            e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
+            e.packed_words = q._bufs[0].numel()
+            e.outlier_cap = cap
             res.append(q)
+        self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, INSHR_REUSE_SEARCH if reuse_search else 0))
+        for q, e in zip(res, qa):
+            q.sym_bits = e.sym_bits
+            q.n_pruned, q.n_outlier, q.n_kept = e.n_pruned, e.n_outlier, e.n_kept
+            q.tau_prune, q.tau_outlier = e.tau_prune, e.tau_outlier
         return res
+
+    def _bound(self, n, ccfg, cfg):
+        key = (n, int(cfg[0]), int(cfg[1]), int(cfg[2]))
+        hit = self._bounds.get(key)
+        if hit is None:
+            words, cap = C.c_uint64(), C.c_uint64()
+            self._check(self.lib.inshr_quantize_bound(n, C.byref(ccfg), C.byref(words), C.byref(cap)))
+            hit = self._bounds[key] = (words.value, cap.value)
+        return hit
 
     # -- inshr_delta ----------------------------------------------------------------------
     def delta(self, prev: Sequence[Quantized], cur: Sequence[Quantized], want_perm: bool = False,
@@ -261,20 +277,23 @@ class Context:
         pp = (C.c_void_p * nT)() if prev_perm is not None else None
         res: List[Delta] = []
         for i, (p, c) in enumerate(zip(prev, cur)):
-            pa[i] = CCodes(p.packed.data_ptr(), p.sym_bits, p.bits, p.n)
-            ca[i] = CCodes(c.packed.data_ptr(), c.sym_bits, c.bits, c.n)
-            words = C.c_uint64()
-            rc = self.lib.inshr_delta_bound(C.byref(pa[i]), C.byref(ca[i]), C.byref(words))
-            self._check(rc)
+            pa[i] = CCodes(p._ptrs[0], p.sym_bits, p.bits, p.n)
+            ca[i] = CCodes(c._ptrs[0], c.sym_bits, c.bits, c.n)
+            key = (p.n, p.sym_bits, p.bits, c.n, c.sym_bits, c.bits)
+            need = self._bounds.get(key)
+            if need is None:
+                words = C.c_uint64()
+                self._check(self.lib.inshr_delta_bound(C.byref(pa[i]), C.byref(ca[i]), C.byref(words)))
+                need = self._bounds[key] = words.value
             if out is not None:
                 d = out[i]
             else:
-                dev = p.packed.device
+                dev = p._bufs[0].device
                 d = Delta(n=p.n, delta_bits=max(p.bits, c.bits) + 1,
-                          packed=torch.empty(words.value, dtype=torch.int64, device=dev),
+                          packed=torch.empty(need, dtype=torch.int64, device=dev),
                           group_off=torch.empty((1 << p.bits) + 3, dtype=torch.int64, device=dev),
                           perm=torch.empty(p.n, dtype=torch.int32, device=dev) if want_perm else None)
-            if d.packed.numel() < words.value:
+            if d.packed.numel() < need:
                 raise ValueError("pre-allocated delta buffer is too small")
             oa[i].packed = d.packed.data_ptr()
             oa[i].packed_words = d.packed.numel()
