@@ -53,8 +53,11 @@ constexpr u32 ZERO_KEY = 0x80000000u;
 __host__ __device__ __forceinline__ u32 canon_bits(u32 b) { return b == 0x80000000u ? 0u : b; }
 __host__ __device__ __forceinline__ u32 key_of_bits(u32 b)
 {
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return b ^ ((u32)((int)b >> 31) | 0x80000000u); // negative: all bits flip; else the sign bit is set
 }
+// key of a value; -0.0 becomes +0.0 first (x + 0.0f is +0.0 for either zero, x otherwise;
+// denormals are kept: the library is built without flush-to-zero)
+__device__ __forceinline__ u32 key_of_float(float x) { return key_of_bits(__float_as_uint(x + 0.0f)); }
 __host__ __device__ __forceinline__ u32 mag_of_key(u32 k)
 {
     return (k & 0x80000000u) ? (k & 0x7fffffffu) : (~k & 0x7fffffffu);
@@ -81,16 +84,22 @@ __host__ __device__ __forceinline__ u32 class_edge_key(u32 which, u32 tp, u32 to
     }
 }
 
-// second-level bin of a key: table entry = bucket mask << 20 | base << 5 | depth.  Bit 20 + s of
+// second-level bin of a key: table entry = bucket mask << 24 | base << 5 | depth.  Bit 31 - s of
 // the entry says that first-level bin s of the 8 under this 12-bit key prefix holds a threshold.
 __host__ __device__ __forceinline__ u32 l2_bin(u32 key, u32 entry)
 {
-    u32 d = entry & 31u;
+#if defined(__HIP_DEVICE_COMPILE__)
+    // bit-field extract takes offset and width from the low five bits of its operands
+    return ((entry >> 5) & 0x7fffu) + __builtin_amdgcn_ubfe(key, (u32)COARSE_SHIFT - entry, entry);
+#else
+    const u32 d = entry & 31u;
     return ((entry >> 5) & 0x7fffu) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
+#endif
 }
+__host__ __device__ __forceinline__ u32 bucket_flag(u32 l1_bin) { return 0x80000000u >> (l1_bin & 7u); }
 __host__ __device__ __forceinline__ bool in_threshold_bucket(u32 key, u32 entry)
 {
-    return (entry >> (20u + ((key >> L1_SHIFT) & 7u))) & 1u;
+    return (int)(entry << ((key >> L1_SHIFT) & 7u)) < 0;
 }
 
 // ------------------------------------------------------------------------------------------

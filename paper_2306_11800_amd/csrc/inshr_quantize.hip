@@ -88,7 +88,7 @@ __device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, co
         u32 e[4], key[4];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-            key[c] = key_of_bits(canon_bits(__float_as_uint(v[4 * j + c])));
+            key[c] = key_of_float(v[4 * j + c]);
             e[c] = ctab[key[c] >> L1_SHIFT];
         }
         unsigned long long piece = 0ull;

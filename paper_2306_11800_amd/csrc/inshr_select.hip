@@ -21,24 +21,20 @@ namespace inshr {
 // ------------------------------------------------------------------------------------------
 // sweeps 1 and 2: histograms
 // ------------------------------------------------------------------------------------------
-// One tile of sweep 1: first-level histogram, sum of squares, sign / zero / non-finite counts.
+// One tile of sweep 1: first-level histogram, sum of squares, exact zeros (the numbers of negative
+// and of non-finite values follow from the histogram).
 template <bool FULL>
 __device__ __forceinline__ void hist1_tile(const float (&v)[16], u32 mask, u32 *h, double &q_tot,
-                                           u32 &c_neg, u32 &c_zero, u32 &c_bad)
+                                           u32 &c_zero)
 {
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         const bool valid = FULL || ((mask >> i) & 1u);
-        const u32 b = canon_bits(__float_as_uint(v[i]));
-        const u32 key = key_of_bits(b);
+        const u32 key = key_of_float(v[i]);
         const double xd = (double)v[i];
         q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
-        if (valid) {
-            c_bad += ((b & 0x7f800000u) == 0x7f800000u) ? 1u : 0u;
-            c_neg += (b >> 31);
-            c_zero += (b == 0u) ? 1u : 0u;
-            atomicAdd(&h[key >> L1_SHIFT], 1u);
-        }
+        c_zero += (u32)__popcll(__ballot(valid && key == ZERO_KEY)); // wave-uniform
+        if (valid) atomicAdd(&h[key >> L1_SHIFT], 1u);
     }
 }
 
@@ -51,7 +47,7 @@ __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *
     u32 key[16], ent[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) { // all table reads are in flight together
-        key[i] = key_of_bits(canon_bits(__float_as_uint(v[i])));
+        key[i] = key_of_float(v[i]);
         ent[i] = T[key[i] >> COARSE_SHIFT];
     }
 #pragma unroll
@@ -102,7 +98,7 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         }
         __syncthreads();
-        u32 c_neg = 0u, c_zero = 0u, c_bad = 0u;
+        u32 c_zero = 0u;    // LEVEL 1: exact zeros seen by this wave
         double q_tot = 0.0; // LEVEL 1: sum of squares
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
@@ -112,9 +108,9 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             const u32 mask = load_tile(d, e0, cnt, v);
             if (LEVEL == 1) {
                 if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
-                    hist1_tile<true>(v, mask, h, q_tot, c_neg, c_zero, c_bad);
+                    hist1_tile<true>(v, mask, h, q_tot, c_zero);
                 else
-                    hist1_tile<false>(v, mask, h, q_tot, c_neg, c_zero, c_bad);
+                    hist1_tile<false>(v, mask, h, q_tot, c_zero);
             } else {
                 if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
                     hist2_tile<true>(v, mask, h, T, gdst, gathered);
@@ -140,14 +136,9 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             }
         }
         if (LEVEL == 1) {
-            c_neg = wave_sum(c_neg);
-            c_zero = wave_sum(c_zero);
-            c_bad = wave_sum(c_bad);
             q_tot = wave_sum_f64(q_tot);
             if (lane == 0u) {
-                if (c_neg) atomicAdd((unsigned long long *)&st->n_neg, (unsigned long long)c_neg);
                 if (c_zero) atomicAdd((unsigned long long *)&st->n_zero, (unsigned long long)c_zero);
-                if (c_bad) atomicOr(&st->nonfinite, 1u);
                 s_red[wave] = q_tot;
             }
             __syncthreads();
@@ -200,8 +191,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     }
     __syncthreads();
     u32 total = block_excl_scan(A, A, L1_MAGBINS, tmp);
-    block_excl_scan(Bn, Bn, L1_MAGBINS, tmp);
-    if (tid == 0 && (u64)total != n) atomicOr(&st->internal_err, 1u);
+    const u32 total_neg = block_excl_scan(Bn, Bn, L1_MAGBINS, tmp);
+    if (tid == 0) {
+        if ((u64)total != n) atomicOr(&st->internal_err, 1u);
+        st->n_neg = total_neg;
+        // magnitude bins from 0x7f800000 >> 17 on hold Inf and NaN only
+        if (total - A[0x7f800000u >> L1_SHIFT] != 0u) st->nonfinite = 1u;
+    }
 
     const u32 n_p = gd->n_p, n_o = gd->n_o, n_thr = n_p + n_o;
     if (tid < n_thr) {
@@ -277,13 +273,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     u32 *tab = B.table2 + (size_t)t * COARSE;
     for (int c = tid; c < COARSE; c += BLOCK) {
         u32 d = nc[c] ? depth_for(nc[c], lo) : 0u;
-        // bits 20..27: which of the 8 first-level bins under this key prefix hold a threshold
+        // top byte: which of the 8 first-level bins under this key prefix hold a threshold
         // (magnitude bin j is first-level key bin 16384 + j for positive, 16383 - j for negative)
         u32 flag = 0u;
         for (u32 q = 0; q < n_thr; q++) {
             const u32 kp = (u32)L1_MAGBINS + s_j[q], kn = (u32)L1_MAGBINS - 1u - s_j[q];
-            if ((kp >> 3) == (u32)c) flag |= 1u << (20u + (kp & 7u));
-            if ((kn >> 3) == (u32)c) flag |= 1u << (20u + (kn & 7u));
+            if ((kp >> 3) == (u32)c) flag |= bucket_flag(kp);
+            if ((kn >> 3) == (u32)c) flag |= bucket_flag(kn);
         }
         tab[c] = flag | (Bn[c] << 5) | d;
     }
@@ -621,7 +617,7 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
     u32 key[16], slot[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) {
-        key[i] = key_of_bits(canon_bits(__float_as_uint(v[i])));
+        key[i] = key_of_float(v[i]);
         slot[i] = T[key[i] >> COARSE_SHIFT];
     }
 #pragma unroll
