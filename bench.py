@@ -50,6 +50,12 @@ def cpu_baseline(sample, grid, eps, threads):
     return 2 * n * 4 / dt / 1e9, dt
 
 
+# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# bench on the full workload, scaled by the counters' readings for a plain 1 GiB device copy
+# (profiles/bench_llama7b_hbm_traffic.md); counters cannot be read from inside the process.
+MEASURED_TRAFFIC_BYTES = {"k_dscatter": 65.8e9, "k_quant": 34.6e9, "k_gather": 30.0e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,7 +135,8 @@ def main():
     dom_bytes = kernel_bytes.get(dom, 4.0) * n_total
     achieved = dom_bytes / (per_launch[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if args.layers == 32 else None,
                 "avg_launch_ms": round(per_launch[dom], 4),
                 "path_floor_bytes_per_elem": round(a_bytes / n_total, 3),
                 "path_achieved": round(path_gbs, 1), "path_frac": round(path_gbs / HBM_PEAK_GBS, 4),
