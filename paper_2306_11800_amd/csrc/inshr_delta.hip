@@ -5,13 +5,11 @@
 //   k_dhist     per chunk (64 tiles of 12288 elements): population of every previous symbol
 //   k_dgroups   per tensor: group offsets and the start of every chunk inside every group
 //   k_dscatter  one workgroup of 12 waves per chunk walks its tiles in order.  Per tile each wave
-//               owns 1024 consecutive elements, 64 consecutive elements per step.  Equal symbols of
-//               a step find each other by OR-ing their lane bit into the symbol's LDS slot, which
-//               gives the stable rank inside the step; per-(wave, symbol) counters carry it across
-//               steps and waves.  The tile's deltas are laid out group by group as a bit stream in
-//               LDS, and each group's run is copied to its place in the packed output with a funnel
-//               shift (whole words stored, the words shared with neighbouring runs OR-ed into the
-//               zeroed output).
+//               owns 1024 consecutive elements, 64 consecutive elements per step; a returning LDS
+//               add per element (or lane bits OR-ed into the symbol's LDS slot) gives the stable
+//               rank.  The tile's deltas are OR-ed into an LDS image of the output words of every
+//               group's run, and one thread per word stores it (first / last word of a chunk's run
+//               are OR-ed into words that k_dzero cleared).
 #include "inshr_launch.h"
 
 namespace inshr {
@@ -34,42 +32,68 @@ __device__ __forceinline__ u32 lds_extract(const u32 *W, u32 idx, u32 w)
     return (u32)(two >> sh) & ((1u << w) - 1u);
 }
 
+// Symbols of one chunk counted by width W: every lane takes runs of 64 consecutive symbols (W whole
+// words), extracts them from registers with compile-time shifts and counts them in its wave's LDS
+// histogram; symbol 0 (pruned: the most frequent one when pruning is on) is counted from ballots.
+template <int W>
+__device__ __forceinline__ void count_symbols(const DDesc &d, u64 c0, u64 c1, u32 S, u32 *hrow,
+                                              u32 &zeros)
+{
+    const u32 tid = threadIdx.x;
+    const GLOBAL_AS unsigned long long *src = gptr(d.prev);
+    const u64 total_words = (d.n * W + 63u) >> 6;
+    const u32 n_runs = (u32)((c1 - c0 + 63u) >> 6);
+    for (u32 u = tid; u < n_runs; u += BLOCK) {
+        const u64 e = c0 + 64ull * u;
+        const u32 nvalid = (c1 - e < 64ull) ? (u32)(c1 - e) : 64u;
+        const u64 w0 = (e >> 6) * W; // e is a multiple of 64
+        u32 x[2 * W + 1];
+#pragma unroll
+        for (int k = 0; k < W; k++) {
+            const unsigned long long v = (w0 + k < total_words) ? src[w0 + k] : 0ull;
+            x[2 * k] = (u32)v;
+            x[2 * k + 1] = (u32)(v >> 32);
+        }
+        x[2 * W] = 0u;
+        const bool whole = __ballot(nvalid < 64u) == 0ull; // the same for every active lane
+#pragma unroll
+        for (int i = 0; i < 64; i++) {
+            constexpr u32 mask = (1u << W) - 1u;
+            const int p = i * W, dw = p >> 5, sh = p & 31;
+            u32 sym = (sh + W <= 32) ? (x[dw] >> sh) & mask
+                                     : __builtin_amdgcn_alignbit(x[dw + 1], x[dw], sh) & mask;
+            const bool valid = whole || (u32)i < nvalid;
+            zeros += (u32)__popcll(__ballot(valid && sym == 0u));
+            sym = sym < S ? sym : S; // a malformed stream counts into the unused entry S
+            if (valid && sym != 0u) atomicAdd(&hrow[sym], 1u);
+        }
+    }
+}
+
 // population of every previous symbol in one chunk
 __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
                                                  const u32 *__restrict__ chunk_tensor,
                                                  u32 *__restrict__ chunk_tot)
 {
-    __shared__ u32 P[HTILE * 9 / 32 + 4];
     __shared__ u32 hw[BLOCK / 64][SS];
     const u64 chunk = blockIdx.x;
     const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
-    const u32 tid = threadIdx.x, wave = tid >> 6;
+    const u32 tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 S = d.Kp + 2u;
     const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
     const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
-    const GLOBAL_AS unsigned long long *src = gptr(d.prev);
     for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
     u32 zeros = 0u;
-    for (u64 e0 = c0; e0 < c1; e0 += HTILE) {
-        const u32 cnt = (c1 - e0 < (u64)HTILE) ? (u32)(c1 - e0) : (u32)HTILE;
-        __syncthreads();
-        const u64 w0 = e0 * d.wp / 64u; // exact: e0 is a multiple of 64
-        const u32 nw = (cnt * d.wp + 63u) >> 6;
-        for (u32 k = tid; k < nw; k += BLOCK) {
-            unsigned long long x = src[w0 + k];
-            P[2 * k] = (u32)x;
-            P[2 * k + 1] = (u32)(x >> 32);
-        }
-        if (tid < 2) P[2 * nw + tid] = 0u;
-        __syncthreads();
-        // symbol 0 (pruned: the most frequent one when pruning is on) is counted from ballots,
-        // the others with LDS atomics
-        for (u32 base = 0; base < cnt; base += BLOCK) {
-            const u32 idx = base + tid;
-            const u32 sym = idx < cnt ? lds_extract(P, idx, d.wp) : S;
-            zeros += (u32)__popcll(__ballot(sym == 0u));
-            if (sym != 0u && sym < S) atomicAdd(&hw[wave][sym], 1u);
-        }
+    __syncthreads();
+    switch (d.wp) {
+    case 2: count_symbols<2>(d, c0, c1, S, hw[wave], zeros); break;
+    case 3: count_symbols<3>(d, c0, c1, S, hw[wave], zeros); break;
+    case 4: count_symbols<4>(d, c0, c1, S, hw[wave], zeros); break;
+    case 5: count_symbols<5>(d, c0, c1, S, hw[wave], zeros); break;
+    case 6: count_symbols<6>(d, c0, c1, S, hw[wave], zeros); break;
+    case 7: count_symbols<7>(d, c0, c1, S, hw[wave], zeros); break;
+    case 8: count_symbols<8>(d, c0, c1, S, hw[wave], zeros); break;
+    default: count_symbols<9>(d, c0, c1, S, hw[wave], zeros); break;
     }
     __syncthreads();
     if ((tid & 63u) == 0u) hw[wave][0] = zeros;
