@@ -133,36 +133,38 @@ __global__ __launch_bounds__(SS) void k_dgroups(const DDesc *__restrict__ dd,
     }
 }
 
-// words of one tile's packed symbols held in registers (prefetch of the next tile)
-struct TileWords {
-    unsigned long long w[3];
-};
-__device__ __forceinline__ TileWords fetch_words(const GLOBAL_AS unsigned long long *src, u64 e0,
-                                                 u32 cnt, u32 w)
+// The packed words of one tile's symbols go from device memory straight into LDS (no registers in
+// between, nothing waits here): every lane moves 16 bytes per instruction when the source is
+// 16-byte aligned, 4 bytes otherwise; a wave's lanes write consecutive LDS addresses.  The words are
+// complete after `s_waitcnt vmcnt(0)` and a barrier.
+__device__ __forceinline__ void lds_fetch(const GLOBAL_AS unsigned long long *src, u64 e0, u32 cnt,
+                                          u32 w, u32 *dst, u32 wave)
 {
-    TileWords t;
-    const u64 w0 = e0 * w / 64u; // exact: e0 is a multiple of 64
-    const u32 nw = (cnt * w + 63u) >> 6;
+    u32 lane = threadIdx.x & 63u;
+    asm volatile("" : "+v"(lane)); // the addresses below are cheap: recomputing them in every tile
+                                   // beats keeping them in (spilled) registers across the loop
+    const GLOBAL_AS u32 *g = (const GLOBAL_AS u32 *)(src + e0 * w / 64u); // exact: e0 % 64 == 0
+    LDS_AS u32 *l = (LDS_AS u32 *)dst;
+    const u32 nd = 2u * ((cnt * w + 63u) >> 6); // dwords of the tile, all inside the packed array
+    // at most DTILE * 9 / 32 = 3456 dwords: two rounds of 16-byte pieces, or five of single dwords
+    u32 done = 0u;
+    if ((((u64)g) & 15u) == 0u) {
+        const u32 n16 = nd >> 2;
 #pragma unroll
-    for (int k = 0; k < 3; k++) {
-        const u32 i = threadIdx.x + k * DBLOCK;
-        t.w[k] = (i < nw) ? src[w0 + i] : 0ull;
-    }
-    return t;
-}
-__device__ __forceinline__ void store_words(const TileWords &t, u32 cnt, u32 w, u32 *dst)
-{
-    const u32 nw = (cnt * w + 63u) >> 6; // <= TWORDS < 3 * DBLOCK
-#pragma unroll
-    for (int k = 0; k < 3; k++) {
-        const u32 i = threadIdx.x + k * DBLOCK;
-        if (i <= nw) { // one zero word of padding after the last
-            dst[2 * i] = (u32)t.w[k];
-            dst[2 * i + 1] = (u32)(t.w[k] >> 32);
+        for (u32 it = 0; it < 2u; it++) {
+            const u32 c0 = (it * NWAVE + wave) * 64u;
+            if (c0 + lane < n16)
+                __builtin_amdgcn_global_load_lds(g + (c0 + lane) * 4u, l + c0 * 4u, 16, 0, 0);
         }
+        done = n16 << 2;
+    }
+#pragma unroll
+    for (u32 it = 0; it < 5u; it++) {
+        const u32 c0 = done + (it * NWAVE + wave) * 64u;
+        if (c0 + lane < nd) __builtin_amdgcn_global_load_lds(g + (c0 + lane), l + c0, 4, 0, 0);
     }
 }
-static_assert(TWORDS + 1 <= 3 * DBLOCK, "three words per thread cover a tile");
+static_assert(2 * NWAVE * 64 * 4 >= DTILE * 9 / 32 && 5 * NWAVE * 64 >= DTILE * 9 / 32, "rounds cover a tile");
 
 // Words of the LDS image of one tile's output: every group's run starts at the bit of its first
 // stream word that the stream position dictates, so LDS word k is stream word dbase[g] + k.  A run
@@ -172,8 +174,6 @@ constexpr int WST = NWAVE * SS;       // per-(wave, symbol) counters; the row st
 constexpr int CIDX = BWORDS / 8 + 2;  // one entry per 8 image words: the group of the first of them
 
 struct ScatterShared {
-    u32 P[DTILE * 9 / 32 + 8];
-    u32 C[DTILE * 9 / 32 + 8];
     u32 wst[WST];                   // counts, then bit position in the image of (wave, symbol)
     u32 wstart[SS + 8];             // first image word of each group's run; [S] = words in use
     unsigned long long dbase[SS];   // image word k of group g is stream word dbase[g] + k
@@ -268,6 +268,10 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                                                      const u32 *__restrict__ chunk_tot)
 {
     __shared__ ScatterShared sh;
+    // packed symbols of the current tile (variables of their own: the loads that fill them are
+    // asynchronous, and only reads of these two arrays have to wait for them)
+    __shared__ __attribute__((aligned(16))) u32 Pw[DTILE * 9 / 32 + 8];
+    __shared__ __attribute__((aligned(16))) u32 Cw[DTILE * 9 / 32 + 8];
     // slot[wave][symbol]: lanes of the wave's current step that hold the symbol (sweep 1);
     // the same memory then holds the image of the tile's output words (sweep 2, output)
     __shared__ unsigned long long slot[ORDERED ? BWORDS : NWAVE * SS];
@@ -297,6 +301,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     }
     if (tid < SS + 8u) sh.wstart[tid] = 0xFFFFFFFFu;
     if (tid == 0u) sh.hotkey = 0ull;
+    for (u32 k = tid; k < (u32)WST; k += DBLOCK) sh.wst[k] = 0u;
     __syncthreads();
     if (tid < S)
         atomicMax(&sh.hotkey, ((gptr(d.group_off)[tid + 1u] - gptr(d.group_off)[tid]) << 9) | tid);
@@ -308,41 +313,46 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u64 rem = d.n - lt * (u64)DTILE;
         return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     };
-    TileWords nextP = fetch_words(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp);
-    TileWords nextC = fetch_words(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc);
+    lds_fetch(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
+    lds_fetch(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc, Cw, wave);
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
-        __syncthreads();
-        if (tid < S && sh.gcnt[tid]) { // the previous tile's runs have been written
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the tile's words
+        __syncthreads(); // all shares are in LDS; the previous tile's output is written
+        if (tid < S && sh.gcnt[tid]) {
             sh.gb[tid] += sh.gcnt[tid];
             sh.carry[tid] = sh.ncarry[tid];
             sh.own[tid] = sh.nown[tid];
         }
-        store_words(nextP, cnt, wp, sh.P);
-        store_words(nextC, cnt, wc, sh.C);
         {
             const u32 nz = ORDERED ? ((cnt * wB) >> 6) + 2u * S + 2u : (u32)(NWAVE * SS);
             for (u32 k = tid; k < nz; k += DBLOCK) slot[k] = 0ull;
-            for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u;
         }
-        __syncthreads();
+        if (!ORDERED) __syncthreads(); // sweep 1 uses the slots
         u32 reg[16];
         u32 ebase = wave * 1024u + lane;
         asm volatile("" : "+v"(ebase)); // keeps the per-row LDS addresses from being hoisted out of
                                         // the tile loop and spilled
         if (cnt == (u32)DTILE)
-            rank_rows<true, ORDERED>(sh.P, sh.C, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
+            rank_rows<true, ORDERED>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
         else
-            rank_rows<false, ORDERED>(sh.P, sh.C, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
+            rank_rows<false, ORDERED>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
         __syncthreads();
+        if (lt + 1 < lt1) { // the symbols are in registers: the next tile's words start travelling
+            lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
+            lds_fetch(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave);
+        }
         // counts -> positions: population of each symbol, the stream words its run touches,
         // exclusive scans over symbols, start of every (wave, symbol)
         u32 tot = 0, nW = 0, s0 = 0, preW = 0, preE = 0;
         u64 fb = 0;
+        u32 sy = tid; // this thread's symbol
+        asm volatile("" : "+v"(sy)); // its table addresses are recomputed per tile, not kept (and
+                                     // spilled: a reload would wait for the words in flight)
         if (tid < S) {
-            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + tid];
-            fb = (u64)sh.gb[tid] * wB;
+            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
+            fb = (u64)sh.gb[sy] * wB;
             s0 = (u32)(fb & 63u);
             nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
         }
@@ -371,20 +381,20 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                 ws += sh.wtot[w2];
                 es += sh.etot[w2];
             }
-            sh.gcnt[tid] = tot;
-            sh.wstart[tid] = ws;
+            sh.gcnt[sy] = tot;
+            sh.wstart[sy] = ws;
             if (tid == S - 1u) sh.wstart[S] = ws + nW;
-            sh.dbase[tid] = (fb >> 6) - (u64)ws;
-            sh.tailp[tid] = (s0 + tot * wB) & 63u;
+            sh.dbase[sy] = (fb >> 6) - (u64)ws;
+            sh.tailp[sy] = (s0 + tot * wB) & 63u;
             for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
-            if (PERM) lbase[tid] = es;
+            if (PERM) lbase[sy] = es;
             u32 bitpos = ws * 64u + s0;
             for (int wv = 0; wv < NWAVE; wv++) {
-                const u32 c = sh.wst[wv * srow + tid];
-                sh.wst[wv * srow + tid] = bitpos;
+                const u32 c = sh.wst[wv * srow + sy];
+                sh.wst[wv * srow + sy] = bitpos;
                 bitpos += c * wB;
                 if (PERM) {
-                    wel[wv * srow + tid] = es;
+                    wel[wv * srow + sy] = es;
                     es += c;
                 }
             }
@@ -410,10 +420,6 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                 if (PERM && (v >> 31))
                     si[wel[wave * srow + (v & 511u)] + within] = (u16)(wave * 1024u + r * 64u + lane);
             }
-        }
-        if (lt + 1 < lt1) { // the next tile's words travel while this tile's output is written
-            nextP = fetch_words(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp);
-            nextC = fetch_words(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc);
         }
         __syncthreads();
         // one thread per output word
@@ -447,6 +453,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                 }
             }
         }
+        for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u; // for the next tile's counts
         if (PERM) {
             for (u32 g = wave; g < S; g += NWAVE) {
                 const u32 c = sh.gcnt[g];

@@ -193,6 +193,31 @@ def test_delta_unequal_bits_and_given_permutation(ctx):
     assert not d[0].packed.any()
 
 
+def test_delta_of_codes_at_8_byte_aligned_addresses(ctx):
+    """The packed symbols may sit at any 8-byte aligned address (the fast copy into LDS wants 16)."""
+    from paper_2306_11800_amd import api
+    prev, cur = synth.config0(seed=21, n=100_003)
+    cfg = (6, 100000, 1000)
+    ts = [dev(prev), dev(cur)]
+    q = ctx.quantize(ts, [cfg, cfg])
+    shifted = []
+    for x in q:
+        words = x.packed.numel()
+        big = torch.empty(words + 3, dtype=torch.int64, device="cuda:0")
+        view = big[1:1 + words]
+        assert view.data_ptr() % 16 == 8
+        view.copy_(x.packed)
+        y = api.Quantized(x.n, x.bits, (view,) + tuple(x._bufs[1:]))
+        shifted.append(y)
+    d = ctx.delta([shifted[0]], [shifted[1]], want_perm=True)
+    ctx.sync()
+    rp, rc = ref.quantize(prev, cfg), ref.quantize(cur, cfg)
+    check_delta(d[0], rp, cfg[0], rc, cfg[0], True)
+    d = ctx.delta([shifted[0]], [shifted[1]], want_perm=False)
+    ctx.sync()
+    check_delta(d[0], rp, cfg[0], rc, cfg[0], False)
+
+
 def test_errors(ctx):
     from paper_2306_11800_amd import api
     x = np.ones(1000, np.float32)
