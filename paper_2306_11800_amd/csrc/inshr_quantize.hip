@@ -61,12 +61,13 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
 
 // The symbol is a step function of the key: the 255 bin boundaries and the four class edges
 // (first quantized negative key, first pruned key, first quantized positive key, first protected
-// positive key) cut the key axis into at most 260 slots, each with one symbol.  A table over the
-// 15-bit key prefix gives the number of breakpoints below the prefix; four comparisons finish the
-// search (prefixes with more than four breakpoints take a short loop).
+// positive key) cut the key axis into at most 260 slots, each with one symbol.  The search's
+// equal-population bins (32768 of them) are far finer than the slots, so a table gives the symbol
+// of every bin that holds no breakpoint; in the few bins that do, the key is compared with the
+// breakpoints from the bin's first one on.
 constexpr int QBP = 264;          // breakpoints, padded
 constexpr int PKW = 256 * 9;      // most packed words of a tile
-constexpr int SM_QUANT = L1_BINS * 2 + 2 * PKW * 8;
+constexpr int SM_QUANT = COARSE * 4 + L2_BINS * 2 + 2 * PKW * 8;
 
 struct QuantTables {
     u32 bp[QBP + 8];   // sorted breakpoints, then 0xFFFFFFFF
@@ -76,8 +77,8 @@ struct QuantTables {
 };
 
 template <bool FULL>
-__device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, const u16 *ctab,
-                                              const QuantTables &qt, u32 n_bp, u32 w,
+__device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, const u32 *T,
+                                              const u16 *symt, const QuantTables &qt, u32 n_bp, u32 w,
                                               unsigned long long *pk, u32 *wcnt, u32 &omask,
                                               u32 (&pre)[4])
 {
@@ -89,24 +90,27 @@ __device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, co
 #pragma unroll
         for (int c = 0; c < 4; c++) {
             key[c] = key_of_float(v[4 * j + c]);
-            e[c] = ctab[key[c] >> L1_SHIFT];
+            e[c] = T[key[c] >> COARSE_SHIFT];
         }
-        unsigned long long piece = 0ull;
+#pragma unroll
+        for (int c = 0; c < 4; c++) e[c] = symt[l2_bin(key[c], e[c])];
+        u32 lo32 = 0u, s3 = 0u;
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-            const u32 lo = e[c] & 511u;
-            u32 s = lo;
-            s += (qt.bp[lo] <= key[c]) ? 1u : 0u;
-            s += (qt.bp[lo + 1u] <= key[c]) ? 1u : 0u;
-            s += (qt.bp[lo + 2u] <= key[c]) ? 1u : 0u;
-            s += (qt.bp[lo + 3u] <= key[c]) ? 1u : 0u;
-            if (e[c] >> 15)
+            u32 sym = e[c];
+            if (sym & 0x8000u) { // the bin holds breakpoints: count those at or below the key
+                u32 s = sym & 0x7fffu;
                 while (s < n_bp && qt.bp[s] <= key[c]) s++;
-            u32 sym = qt.symtab[s];
+                sym = qt.symtab[s];
+            }
             if (!FULL && !((mask >> (4 * j + c)) & 1u)) sym = 0u;
-            piece |= (unsigned long long)sym << (c * w);
+            if (c < 3)
+                lo32 |= sym << (c * w);
+            else
+                s3 = sym;
             omask |= (sym == 1u ? 1u : 0u) << (4 * j + c);
         }
+        const unsigned long long piece = (unsigned long long)lo32 | ((unsigned long long)s3 << (3u * w));
         const u32 bitoff = 4u * (tid + 1024u * j) * w;
         const u32 word = bitoff >> 6, shf = bitoff & 63u;
         if (piece) {
@@ -134,8 +138,9 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                                                  const QDesc *__restrict__ qd_by_tensor, Bufs B)
 {
     extern __shared__ u32 smem[];
-    u16 *ctab = reinterpret_cast<u16 *>(smem); // [L1_BINS]: breakpoints below the prefix | many << 15
-    unsigned long long *pk0 = reinterpret_cast<unsigned long long *>(smem + L1_BINS / 2); // [2][PKW]
+    u32 *T = smem;                                                // [COARSE] key prefix -> bins
+    u16 *symt = reinterpret_cast<u16 *>(smem + COARSE);           // [L2_BINS] symbol, or 0x8000 | first breakpoint
+    unsigned long long *pk0 = reinterpret_cast<unsigned long long *>(smem + COARSE + L2_BINS / 2); // [2][PKW]
     __shared__ QuantTables qt;
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -161,17 +166,13 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         const u32 w = bits + 1u, sh = 8u - bits;
         const u32 o = gd->pair_o[pair];
         const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + o];
+        const u32 nb2 = st->nb2;
         const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
         const u32 n_bnd = K - 1u, n_bp = n_bnd + 4u;
         __syncthreads();
+        for (u32 i = tid; i < (u32)COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         if (tid < n_bnd) qt.raw[tid] = tk[((tid + 1u) << sh) - 1u];
-        if (tid == 0u) {
-            qt.raw[n_bnd] = key_neg(tau_o);           // first quantized negative key
-            qt.raw[n_bnd + 1u] = key_neg(tau_p) + 1u; // first pruned key
-            qt.raw[n_bnd + 2u] = key_pos(tau_p);      // first quantized positive key
-            qt.raw[n_bnd + 3u] = key_pos(tau_o) + 1u; // first protected positive key (wraps to 0
-                                                      // when nothing is protected)
-        }
+        if (tid < 4u) qt.raw[n_bnd + tid] = class_edge_key(tid, tau_p, tau_o);
         __syncthreads();
         if (tid < n_bp) { // sort by counting the smaller ones
             const u32 x = qt.raw[tid];
@@ -206,23 +207,25 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             }
             qt.symtab[tid] = (u16)sym;
         }
-        for (u32 c = tid; c < (u32)L1_BINS; c += BLOCK) { // breakpoints below each key prefix
-            const u32 first = c << L1_SHIFT;
-            u32 lo = 0u, hi = n_bp;
-            while (lo < hi) {
-                const u32 mid = (lo + hi) >> 1;
-                if (qt.bp[mid] < first)
-                    lo = mid + 1u;
-                else
-                    hi = mid;
-            }
-            ctab[c] = (u16)lo;
-        }
         __syncthreads();
-        for (u32 c = tid; c < (u32)L1_BINS; c += BLOCK) {
-            const u32 lo = ctab[c] & 511u;
-            const u32 nx = (c + 1u < (u32)L1_BINS) ? (ctab[c + 1u] & 511u) : n_bp;
-            if (nx - lo > 4u) ctab[c] = (u16)(lo | 0x8000u);
+        for (u32 b = tid; b < nb2; b += BLOCK) { // symbol of every bin, or its first breakpoint
+            u32 lo = 0u, hi = COARSE - 1u; // key prefix of the bin: last one that starts at or below it
+            while (lo < hi) {
+                const u32 mid = (lo + hi + 1u) >> 1;
+                if (((T[mid] >> 5) & 0x7fffu) <= b)
+                    lo = mid;
+                else
+                    hi = mid - 1u;
+            }
+            const u32 e = T[lo], dd = e & 31u, sub = b - ((e >> 5) & 0x7fffu);
+            const u32 first = (lo << COARSE_SHIFT) | (sub << (COARSE_SHIFT - dd));
+            const u32 last = first + ((1u << (COARSE_SHIFT - dd)) - 1u);
+            u32 below = 0u, upto = 0u; // breakpoints < first, breakpoints <= last
+            for (u32 step = 256u; step > 0u; step >>= 1) {
+                if (below + step <= n_bp && qt.bp[below + step - 1u] < first) below += step;
+                if (upto + step <= n_bp && qt.bp[upto + step - 1u] <= last) upto += step;
+            }
+            symt[b] = (below == upto) ? qt.symtab[below] : (u16)(0x8000u | below);
         }
         __syncthreads();
         GLOBAL_AS unsigned long long *packed = gptr(q.packed);
@@ -235,6 +238,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u32 cnt = tile_cnt(tile);
+            const u32 obase = B.tile_off[tile]; // asked for early: it is needed after the barrier
             float v[16];
 #pragma unroll
             for (int i = 0; i < 16; i++) v[i] = vn[i];
@@ -245,9 +249,9 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             u32 *wcnt = qt.wcnt[buf];
             u32 omask, pre[4];
             if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
-                classify_tile<true>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);
+                classify_tile<true>(v, mask, T, symt, qt, n_bp, w, pk, wcnt, omask, pre);
             else
-                classify_tile<false>(v, mask, ctab, qt, n_bp, w, pk, wcnt, omask, pre);
+                classify_tile<false>(v, mask, T, symt, qt, n_bp, w, pk, wcnt, omask, pre);
             __syncthreads();
             // the tile's words leave, and the buffer is clean for the tile after the next
             const u32 n_words = (cnt * w + 63u) >> 6;
@@ -267,7 +271,6 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             }
             if (__builtin_amdgcn_readlane(inc, 63) != 0u) {
                 const u32 excl = inc - wc;
-                const u64 obase = B.tile_off[tile];
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
                     u32 r = __builtin_amdgcn_readlane(excl, j * 16 + wave) + pre[j];
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                     for (int c = 0; c < 4; c++) {
                         const int i = 4 * j + c;
                         if ((omask >> i) & 1u) {
-                            const u64 pos = obase + r;
+                            const u64 pos = (u64)obase + r;
                             if (pos < q.out_cap) {
                                 gptr(q.out_idx)[pos] = (u32)(e0 + 4u * (tid + 1024u * j) + c);
                                 gptr(q.out_val)[pos] = v[i];
