@@ -172,4 +172,20 @@ __device__ __forceinline__ u32 load_tile(const TDesc &d, u64 e0, u32 cnt, float 
     return mask;
 }
 
+// A whole tile at a 16-byte aligned address, asked for without any branch: the values may stay in
+// flight until their first use (a tile fetched ahead).
+__device__ __forceinline__ void load_tile_ahead(const TDesc &d, u64 e0, float (&v)[16])
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const GLOBAL_AS f4 *p4 = (const GLOBAL_AS f4 *)(gptr(d.data) + e0);
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const f4 q = p4[threadIdx.x + 1024u * j];
+        v[4 * j + 0] = q.x;
+        v[4 * j + 1] = q.y;
+        v[4 * j + 2] = q.z;
+        v[4 * j + 3] = q.w;
+    }
+}
+
 } // namespace inshr

@@ -233,30 +233,25 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             const u64 rem = d.n - (tl - d.tile0) * (u64)TILE;
             return rem < (u64)TILE ? (u32)rem : (u32)TILE;
         };
+        // Software pipeline of one tile: (1) the tile's values, asked for during the tile before,
+        // arrive; (2) the words and protected values of the tile before leave (their stores drain
+        // while this tile is classified, and no load ever waits behind a store); (3) the next tile
+        // is asked for; (4) this tile is classified into the other LDS buffer; barrier.
         float vn[16];
-        u32 maskn = load_tile(d, (tile - d.tile0) * (u64)TILE, tile_cnt(tile), vn);
-        for (; tile < stop; tile++) {
-            const u64 e0 = (tile - d.tile0) * (u64)TILE;
-            const u32 cnt = tile_cnt(tile);
-            const u32 obase = B.tile_off[tile]; // asked for early: it is needed after the barrier
-            float v[16];
-#pragma unroll
-            for (int i = 0; i < 16; i++) v[i] = vn[i];
-            const u32 mask = maskn;
-            if (tile + 1 < stop) // the next tile travels while this one is classified
-                maskn = load_tile(d, e0 + TILE, tile_cnt(tile + 1), vn);
-            unsigned long long *pk = pk0 + buf * PKW;
-            u32 *wcnt = qt.wcnt[buf];
-            u32 omask, pre[4];
-            if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
-                classify_tile<true>(v, mask, T, symt, qt, n_bp, w, pk, wcnt, omask, pre);
-            else
-                classify_tile<false>(v, mask, T, symt, qt, n_bp, w, pk, wcnt, omask, pre);
-            __syncthreads();
+        bool ahead = false; // vn holds the tile about to be worked on (uniform)
+        float vp[16];           // values of the tile before (its protected ones are still to be written)
+        u32 omask_p = 0u, pre_p[4] = {0u, 0u, 0u, 0u}, obase_p = 0u;
+        bool have_prev = false; // uniform
+        auto write_out = [&](u64 tl, u32 bf) { // phase 2 of tile tl, classified into buffer bf
+            const u64 e0 = (tl - d.tile0) * (u64)TILE;
+            const u32 cnt = tile_cnt(tl);
+            const u32 w_ = w;
+            unsigned long long *pk = pk0 + bf * PKW;
+            const u32 *wcnt = qt.wcnt[bf];
             // the tile's words leave, and the buffer is clean for the tile after the next
-            const u32 n_words = (cnt * w + 63u) >> 6;
-            GLOBAL_AS unsigned long long *dst = packed + (tile - d.tile0) * (u64)(256u * w);
-            for (u32 k = tid; k < 256u * w; k += BLOCK) {
+            const u32 n_words = (cnt * w_ + 63u) >> 6;
+            GLOBAL_AS unsigned long long *dst = packed + (tl - d.tile0) * (u64)(256u * w_);
+            for (u32 k = tid; k < 256u * w_; k += BLOCK) {
                 const unsigned long long x = pk[k];
                 if (k < n_words) dst[k] = x;
                 pk[k] = 0ull;
@@ -271,25 +266,61 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             }
             if (__builtin_amdgcn_readlane(inc, 63) != 0u) {
                 const u32 excl = inc - wc;
+                const u64 obase = obase_p;
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
-                    u32 r = __builtin_amdgcn_readlane(excl, j * 16 + wave) + pre[j];
+                    u32 r = __builtin_amdgcn_readlane(excl, j * 16 + wave) + pre_p[j];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         const int i = 4 * j + c;
-                        if ((omask >> i) & 1u) {
-                            const u64 pos = (u64)obase + r;
+                        if ((omask_p >> i) & 1u) {
+                            const u64 pos = obase + r;
                             if (pos < q.out_cap) {
                                 gptr(q.out_idx)[pos] = (u32)(e0 + 4u * (tid + 1024u * j) + c);
-                                gptr(q.out_val)[pos] = v[i];
+                                gptr(q.out_val)[pos] = vp[i];
                             }
                             r++;
                         }
                     }
                 }
             }
+        };
+        for (; tile < stop; tile++) {
+            const u64 e0 = (tile - d.tile0) * (u64)TILE;
+            const u32 cnt = tile_cnt(tile);
+            float v[16];
+            u32 mask = 0xFFFFu;
+            if (ahead) {
+#pragma unroll
+                for (int i = 0; i < 16; i++) v[i] = vn[i];
+            } else {
+                mask = load_tile(d, e0, cnt, v);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; i++)
+                asm volatile("" : "+v"(v[i])); // the values are taken here, before any store below
+            // offset of this tile's protected values in the list (needed one tile later)
+            const u32 obase = __builtin_amdgcn_readfirstlane(B.tile_off[tile]);
+            if (have_prev) write_out(tile - 1, buf ^ 1u);
+            // a whole, aligned next tile is asked for now and used one iteration later
+            ahead = tile + 1 < stop && d.aligned16 && tile_cnt(tile + 1) == (u32)TILE;
+            if (ahead) load_tile_ahead(d, e0 + TILE, vn);
+            u32 omask, pre[4];
+            if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
+                classify_tile<true>(v, mask, T, symt, qt, n_bp, w, pk0 + buf * PKW, qt.wcnt[buf], omask, pre);
+            else
+                classify_tile<false>(v, mask, T, symt, qt, n_bp, w, pk0 + buf * PKW, qt.wcnt[buf], omask, pre);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) vp[i] = v[i];
+            omask_p = omask;
+            obase_p = obase;
+#pragma unroll
+            for (int j = 0; j < 4; j++) pre_p[j] = pre[j];
+            have_prev = true;
             buf ^= 1u;
         }
+        if (have_prev) write_out(stop - 1, buf ^ 1u);
         t++;
     }
 }
