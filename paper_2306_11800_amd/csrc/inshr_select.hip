@@ -746,6 +746,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
 // gathered keys -> groups of consecutive active bins (one workgroup per (workgroup, tensor) unit)
 // ------------------------------------------------------------------------------------------
 constexpr int SPLIT_PER = 8; // keys per thread per step
+constexpr int SPLIT_PARTS = 4; // workgroups that share one unit (they take its steps in turn)
 
 __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
                                                  const u32 *__restrict__ fu_tensor, Bufs B)
@@ -775,7 +776,7 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
     for (u32 i = tid; i < nb2; i += BLOCK) gtab[i] = B.bin_group[(size_t)t * L2_BINS + i];
     for (u32 g = tid; g < G; g += BLOCK) gcount[g] = 0u;
     __syncthreads();
-    for (u32 base = 0; base < cmax; base += 64u * SPLIT_PER) {
+    for (u32 base = blockIdx.y * 64u * SPLIT_PER; base < cmax; base += SPLIT_PARTS * 64u * SPLIT_PER) {
         u32 key[SPLIT_PER], gr[SPLIT_PER]; // group << 16 | rank inside (step, group)
 #pragma unroll
         for (int j = 0; j < SPLIT_PER; j++) {
@@ -1274,7 +1275,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     if ((e = launch_edges(bt, s))) return e;
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
-    PROF("k_split", s, k_split<<<bt.n_units, BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
+    PROF("k_split", s, k_split<<<dim3(bt.n_units, SPLIT_PARTS), BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     if (bt.lds_ordered)
         PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BB, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
     else
