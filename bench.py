@@ -62,6 +62,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the 7B shape (32 = full)")
+    ap.add_argument("--config", type=int, default=4, choices=[0, 1, 2, 3, 4],
+                    help="benchmark configuration: 4 (default) is the metric's workload; 0-3 are the "
+                         "smaller ones (config0 tensor, ResNet-50 / BERT-base / GPT-2-medium shapes "
+                         "with Adam state), reported for reference")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,9 +79,27 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    grid = synth.grid_full()
+    grid = synth.grid_full() if args.config >= 2 else synth.grid_small()
     eps = synth.EPS_DEFAULT
-    names, prev, cur = synth.llama7b_device_checkpoint(dev, seed=4000, n_layers=args.layers)
+    if args.config == 4:
+        names, prev, cur = synth.llama7b_device_checkpoint(dev, seed=4000, n_layers=args.layers)
+        what = (f"Llama-7B-shaped fp32 checkpoint, {args.layers} layers, Student-t(3)*0.015 with 0.1% "
+                f"channels x20, next step = prev + N(0,1e-4)")
+    else:  # host generators, uploaded once
+        if args.config == 0:
+            p0, c0 = synth.config0(seed=0)
+            items, what = [("config0", p0, c0)], "one tensor 0.9 N(0,0.02) + 0.1 Laplace(0,0.08), next = prev + N(0,1e-4)"
+        elif args.config == 1:
+            items, what = list(synth.resnet50_checkpoint()), "ResNet-50-shaped weights + Adam m, v, one Adam step"
+        elif args.config == 2:
+            items, what = list(synth.bert_base_checkpoint()), "BERT-base-shaped weights + Adam m, v, sparse embedding update"
+        else:
+            items = [(n, st[0], st[1]) for n, st in synth.gpt2_medium_steps(n_steps=2)]
+            what = "GPT-2-medium-shaped weights + Adam m, v, steps 0 -> 1"
+        names = [n for n, _, _ in items]
+        prev = [torch.from_numpy(a).to(dev) for _, a, _ in items]
+        cur = [torch.from_numpy(b).to(dev) for _, _, b in items]
+        del items
     n_total = sum(t.numel() for t in cur)
     ctx = api.Context(dev)
 
@@ -136,7 +158,7 @@ def main():
     achieved = dom_bytes / (per_launch[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if args.layers == 32 else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if (args.layers == 32 and args.config == 4) else None,
                 "avg_launch_ms": round(per_launch[dom], 4),
                 "path_floor_bytes_per_elem": round(a_bytes / n_total, 3),
                 "path_achieved": round(path_gbs, 1), "path_frac": round(path_gbs / HBM_PEAK_GBS, 4),
@@ -158,10 +180,11 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"Llama-7B-shaped fp32 checkpoint, {args.layers} layers, {len(cur)} tensors, "
-                               f"{n_total} values, Student-t(3)*0.015 with 0.1% channels x20, "
-                               f"next step = prev + N(0,1e-4); grid bits 2..8 x prune {{0,.05,.1,.2,.4}} x "
-                               f"protect {{0,1e-4,1e-3}} (105 configs), eps {eps}",
+        "config": {"workload": f"{what}; {len(cur)} tensors, {n_total} values; grid of {len(grid)} "
+                               f"configurations (" + ("bits 2..8 x prune {0,.05,.1,.2,.4} x protect {0,1e-4,1e-3}"
+                                                      if len(grid) == 105 else
+                                                      "bits {2,3,4,8} x prune {0,.1,.3} x protect {0,.001}")
+                               + f"), eps {eps}",
                    "bytes_fp32": n_total * 4,
                    "chosen_configs": {f"b{b}_p{p}_o{o}": sum(1 for c in cfgs if tuple(c) == (b, p, o))
                                       for (b, p, o) in sorted(set(tuple(c) for c in cfgs))}},

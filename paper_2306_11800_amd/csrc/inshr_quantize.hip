@@ -100,7 +100,14 @@ __device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, co
             u32 sym = e[c];
             if (sym & 0x8000u) { // the bin holds breakpoints: count those at or below the key
                 u32 s = sym & 0x7fffu;
-                while (s < n_bp && qt.bp[s] <= key[c]) s++;
+                if (qt.bp[s] <= key[c]) { // (the bin's first breakpoint exists: s < n_bp)
+                    s++;
+                    if (qt.bp[s] <= key[c]) { // many equal values put many breakpoints into one bin
+                        s++;
+                        for (u32 step = 256u; step > 0u; step >>= 1)
+                            if (s + step <= n_bp && qt.bp[s + step - 1u] <= key[c]) s += step;
+                    }
+                }
                 sym = qt.symtab[s];
             }
             if (!FULL && !((mask >> (4 * j + c)) & 1u)) sym = 0u;

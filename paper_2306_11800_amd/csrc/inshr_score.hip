@@ -185,19 +185,61 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     const u32 *segc = B.seg_cnt + (size_t)t * MAX_EDGES;
     const u32 *gc = B.grp_cnt + (size_t)t * 2 * MAX_EDGES;
     const double *gs = B.grp_sx + (size_t)t * 2 * MAX_EDGES;
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
-        double s = 0.0;
-        u64 c = 0;
-        if (i <= m) {
-            // keys of bins without an edge (per unit, in unit order), then the gathered keys from
-            // the group of the slot's lower edge and from the group of its upper edge
-            for (u32 u = u0; u < u1; u++) s += B.mom_sx[(size_t)t_fu_ids[u] * MAX_EDGES + i];
-            s += gs[i];
-            s += gs[MAX_EDGES + i];
-            c = (u64)segc[i] + gc[i] + gc[MAX_EDGES + i];
+    // Per slot: count and sum.  They are kept as inclusive prefixes over the slots (a bin is a run
+    // of consecutive slots, so its count and sum are two differences): every thread owns four
+    // consecutive slots, the running totals of the threads before it come from a scan.
+    __shared__ double w_s[BLOCK / 64];
+    __shared__ u64 w_c[BLOCK / 64];
+    {
+        double ps[4];
+        u64 pc[4];
+        double run_s = 0.0;
+        u64 run_c = 0;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const u32 i = 4u * tid + r;
+            double sv = 0.0;
+            u64 c = 0;
+            if (i <= m) {
+                // keys of bins without an edge (per unit, in unit order), then the gathered keys
+                // from the group of the slot's lower edge and from the group of its upper edge
+                for (u32 u = u0; u < u1; u++) sv += B.mom_sx[(size_t)t_fu_ids[u] * MAX_EDGES + i];
+                sv += gs[i];
+                sv += gs[MAX_EDGES + i];
+                c = (u64)segc[i] + gc[i] + gc[MAX_EDGES + i];
+            }
+            run_s += sv;
+            run_c += c;
+            ps[r] = run_s;
+            pc[r] = run_c;
         }
-        S[i] = s;
-        C[i] = c;
+        double inc_s = run_s;
+        u64 inc_c = run_c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double a = __shfl_up(inc_s, o);
+            const u64 b = __shfl_up(inc_c, o);
+            if ((int)(tid & 63u) >= o) {
+                inc_s += a;
+                inc_c += b;
+            }
+        }
+        if ((tid & 63u) == 63u) {
+            w_s[tid >> 6] = inc_s;
+            w_c[tid >> 6] = inc_c;
+        }
+        __syncthreads();
+        double base_s = inc_s - run_s;
+        u64 base_c = inc_c - run_c;
+        for (u32 w = 0; w < (tid >> 6); w++) {
+            base_s += w_s[w];
+            base_c += w_c[w];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            S[4u * tid + r] = base_s + ps[r];
+            C[4u * tid + r] = base_c + pc[r];
+        }
     }
     if (tid <= n_o) {
         double s = 0.0;
@@ -228,12 +270,13 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         const u32 i_lo = (k == 0) ? e[NB8 + 0] : e[(k << sh) - 1u];
         const u32 i_hi = (k == K - 1u) ? e[NB8 + 3] : e[((k + 1u) << sh) - 1u];
         const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
-        u64 nk = 0;
-        double sk = 0.0;
-        for (u32 s = i_lo + 1u; s <= i_hi; s++) {
-            if (s > g_lo && s <= g_hi) continue;
-            nk += C[s];
-            sk += S[s];
+        // slots i_lo+1 .. i_hi without those of the pruned gap (g_lo, g_hi]
+        u64 nk = C[i_hi] - C[i_lo];
+        double sk = S[i_hi] - S[i_lo];
+        const u32 a = max(i_lo, g_lo), b = min(i_hi, g_hi);
+        if (a < b) {
+            nk -= C[b] - C[a];
+            sk -= S[b] - S[a];
         }
         float c;
         if (nk)
@@ -246,6 +289,8 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     }
     __syncthreads();
     Score *sc = B.scores + (size_t)t * n_cfg;
+    __shared__ double s_sse[MAX_CFG];
+    __shared__ u64 s_cost[MAX_CFG];
     for (u32 g = tid; g < n_cfg; g += BLOCK) {
         const u32 bits = gd->cfg_bits[g], K = 1u << bits, q = gd->cfg_pair[g];
         double acc = 0.0;
@@ -260,27 +305,29 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         r.n_kept = st->pair_M[q];
         r.cost_bits = r.n_kept * (u64)bits + 32ull * r.n_outlier + 32ull * (u64)K;
         sc[g] = r;
+        s_sse[g] = sse;
+        s_cost[g] = r.cost_bits;
         if (r.n_pruned + r.n_outlier + r.n_kept != n) atomicOr(&st->internal_err, 256u);
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0) { // Sec. 5: cheapest feasible configuration, else the most accurate one
         bool have_f = false, have_a = false;
         u32 best_f = 0, best_a = 0;
         u64 best_cost = 0;
         double best_sse = 0.0;
-        const double eps = gd->eps;
+        const double eps = gd->eps, sumsq = s_sumsq;
         for (u32 g = 0; g < n_cfg; g++) {
-            const Score r = sc[g];
-            const double rel = (r.sumsq > 0.0) ? r.sse / r.sumsq : 0.0;
-            if (rel <= eps && (!have_f || r.cost_bits < best_cost)) {
+            const double sse = s_sse[g];
+            const double rel = (sumsq > 0.0) ? sse / sumsq : 0.0;
+            if (rel <= eps && (!have_f || s_cost[g] < best_cost)) {
                 have_f = true;
                 best_f = g;
-                best_cost = r.cost_bits;
+                best_cost = s_cost[g];
             }
-            if (!have_a || r.sse < best_sse) {
+            if (!have_a || sse < best_sse) {
                 have_a = true;
                 best_a = g;
-                best_sse = r.sse;
+                best_sse = sse;
             }
         }
         st->best = have_f ? best_f : best_a;
