@@ -315,11 +315,12 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     };
     lds_fetch(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
     lds_fetch(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc, Cw, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the first tile's words
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the tile's words
-        __syncthreads(); // all shares are in LDS; the previous tile's output is written
+        __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
+                         // before its output phase); the previous tile's output phase is over
         if (tid < S && sh.gcnt[tid]) {
             sh.gb[tid] += sh.gcnt[tid];
             sh.carry[tid] = sh.ncarry[tid];
@@ -421,6 +422,9 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                     si[wel[wave * srow + (v & 511u)] + within] = (u16)(wave * 1024u + r * 64u + lane);
             }
         }
+        // The next tile's words were asked for a while ago: waiting for them here is free, while at
+        // the top of the loop it would also wait for the stores of the output phase below.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         // one thread per output word
         const u32 n_img = sh.wstart[S];
