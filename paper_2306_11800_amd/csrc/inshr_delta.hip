@@ -173,19 +173,35 @@ constexpr int BWORDS = TWORDS + 2 * SS + 2;
 constexpr int WST = NWAVE * SS;       // per-(wave, symbol) counters; the row stride is S + 1
 constexpr int CIDX = BWORDS / 8 + 2;  // one entry per 8 image words: the group of the first of them
 
+constexpr int LINE = 4; // stream words (32 bytes) per output line
+
 struct ScatterShared {
     u32 wst[WST];                   // counts, then bit position in the image of (wave, symbol)
     u32 wstart[SS + 8];             // first image word of each group's run; [S] = words in use
-    unsigned long long dbase[SS];   // image word k of group g is stream word dbase[g] + k
-    unsigned long long carry[SS], ncarry[SS]; // partial trailing word of the group
-    u32 own[SS], nown[SS];          // the group's current stream word belongs to this chunk alone
-    u32 tailp[SS];                  // this tile's run of the group ends inside a word
+    unsigned long long lw[SS][LINE]; // per group: the words of its current, incomplete output line
+    u32 fo[SS];                     // first stream word that this chunk's run of the group owns
+                                    // alone; bit 31: the word before it is shared with the run before
     u32 gcnt[SS];                   // tile population per symbol
-    u32 gb[SS];                     // stream position of each group's next run (n < 2^32)
+    u32 gb[SS];                     // stream position of each group's run of this tile (n < 2^32)
     u32 wtot[8], etot[8];
     unsigned long long hotkey;      // population << 9 | symbol, maximum over the tensor's groups
     u16 cidx[CIDX];
 };
+
+// Where a group's run of `cnt` symbols that starts at stream position `pos` lies in the stream.
+struct RunWords {
+    u32 Wf, We; // word of its first bit; first word that is still incomplete after it
+    u32 tail;   // bits of word We that are filled
+};
+__device__ __forceinline__ RunWords run_words(u32 pos, u32 cnt, u32 wB)
+{
+    RunWords r;
+    const u64 fb = (u64)pos * wB, fe = fb + (u64)cnt * wB;
+    r.Wf = (u32)(fb >> 6);
+    r.We = (u32)(fe >> 6);
+    r.tail = (u32)(fe & 63u);
+    return r;
+}
 
 // Sweep 1 of a tile: stable rank of every element among the equal symbols of its wave's 1024
 // elements.  Row r of a lane is element ebase + 64 r: its bit offset in the packed words moves
@@ -254,14 +270,39 @@ __device__ __forceinline__ void rank_rows(const u32 *P, const u32 *C, u32 *wrow,
     if (ORDERED && lane == 0u) wrow[hot] = hot_seen;
 }
 
+// After a tile's output phase: the words of each group's open line that came from this tile's image
+// (the complete ones of a line that is the chunk's own, and the partial last word) move into the
+// group's line buffer.  One thread per (group, word of the line); nothing else touches the buffers
+// or the image meanwhile.
+__device__ __forceinline__ void commit_lines(ScatterShared &sh, const unsigned long long *image, u32 S,
+                                             u32 wB, u32 tid)
+{
+    for (u32 i = tid; i < S * LINE; i += DBLOCK) {
+        const u32 g = i / LINE, j = i % LINE;
+        const u32 c = sh.gcnt[g];
+        if (c == 0u) continue;
+        const RunWords r = run_words(sh.gb[g], c, wB);
+        const u32 Wt = (r.We / LINE) * LINE + j; // word j of the line that is open after the tile
+        if (Wt > r.We || Wt < r.Wf) continue;    // not written yet / buffered by an earlier tile
+        unsigned long long v = 0ull;
+        if (Wt < r.We || r.tail) {
+            v = image[sh.wstart[g] + (Wt - r.Wf)];
+            if (Wt == r.Wf) v |= sh.lw[g][j]; // bits of earlier tiles in the run's first word
+        }
+        sh.lw[g][j] = v;
+    }
+}
+
 // ORDERED: same-address LDS atomics with return are served in ascending lane order on this device
 // (checked by k_lds_order_check before the library relies on it); one returning add then ranks an
 // element.  Otherwise equal symbols of a step find each other through the slot array.
 //
-// Stream words that lie wholly inside one chunk's part of one group are written with plain stores:
-// the trailing partial word of a group's run is carried in LDS to the next tile of the chunk.  Only
-// the words at the two ends of a (chunk, group) run are shared with other workgroups; those are
-// OR-ed into words that k_dzero cleared.
+// Output: a group's run of one tile is a few dozen bytes, and 258 groups interleave, so storing it
+// as it comes would reach memory as partial lines.  Each group therefore keeps the words of its
+// current 64-byte line in LDS until the line is complete; complete lines are stored whole.  Only the
+// ends of a (chunk, group) run are different: its first partial line is stored word by word, its
+// first word, when shared with the run before, and its last partial word are OR-ed into words that
+// k_dzero cleared.
 template <bool PERM, bool ORDERED>
 __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict__ dd,
                                                      const u32 *__restrict__ chunk_tensor,
@@ -296,9 +337,10 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u32 g0 = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
         sh.gb[tid] = g0;
         sh.gcnt[tid] = 0u;
-        sh.carry[tid] = 0ull;
-        sh.own[tid] = ((((u64)g0 * wB) & 63u) == 0u) ? 1u : 0u;
+        const u64 sb = (u64)g0 * wB;
+        sh.fo[tid] = (u32)((sb + 63u) >> 6) | ((sb & 63u) ? 0x80000000u : 0u);
     }
+    for (u32 k = tid; k < S * LINE; k += DBLOCK) (&sh.lw[0][0])[k] = 0ull;
     if (tid < SS + 8u) sh.wstart[tid] = 0xFFFFFFFFu;
     if (tid == 0u) sh.hotkey = 0ull;
     for (u32 k = tid; k < (u32)WST; k += DBLOCK) sh.wst[k] = 0u;
@@ -321,16 +363,12 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u32 cnt = tile_cnt(lt);
         __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
                          // before its output phase); the previous tile's output phase is over
-        if (tid < S && sh.gcnt[tid]) {
-            sh.gb[tid] += sh.gcnt[tid];
-            sh.carry[tid] = sh.ncarry[tid];
-            sh.own[tid] = sh.nown[tid];
+        commit_lines(sh, slot, S, wB, tid); // the previous tile's trailing words -> line buffers
+        if (!ORDERED) { // sweep 1 uses the slots
+            __syncthreads();
+            for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
+            __syncthreads();
         }
-        {
-            const u32 nz = ORDERED ? ((cnt * wB) >> 6) + 2u * S + 2u : (u32)(NWAVE * SS);
-            for (u32 k = tid; k < nz; k += DBLOCK) slot[k] = 0ull;
-        }
-        if (!ORDERED) __syncthreads(); // sweep 1 uses the slots
         u32 reg[16];
         u32 ebase = wave * 1024u + lane;
         asm volatile("" : "+v"(ebase)); // keeps the per-row LDS addresses from being hoisted out of
@@ -344,6 +382,13 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
             lds_fetch(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave);
         }
+        if (ORDERED) { // the image of the previous tile has been taken over; clear it for sweep 2
+            const u32 nz = ((cnt * wB) >> 6) + 2u * S + 2u;
+            u32 k0 = tid;
+            asm volatile("" : "+v"(k0)); // (address recomputed here, not reloaded from a spill slot:
+                                         // a reload would wait for the words in flight)
+            for (u32 k = k0; k < nz; k += DBLOCK) slot[k] = 0ull;
+        }
         // counts -> positions: population of each symbol, the stream words its run touches,
         // exclusive scans over symbols, start of every (wave, symbol)
         u32 tot = 0, nW = 0, s0 = 0, preW = 0, preE = 0;
@@ -353,7 +398,9 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                                      // spilled: a reload would wait for the words in flight)
         if (tid < S) {
             for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
-            fb = (u64)sh.gb[sy] * wB;
+            const u32 pos = sh.gb[sy] + sh.gcnt[sy]; // after the previous tile's run
+            sh.gb[sy] = pos;
+            fb = (u64)pos * wB;
             s0 = (u32)(fb & 63u);
             nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
         }
@@ -385,8 +432,6 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             sh.gcnt[sy] = tot;
             sh.wstart[sy] = ws;
             if (tid == S - 1u) sh.wstart[S] = ws + nW;
-            sh.dbase[sy] = (fb >> 6) - (u64)ws;
-            sh.tailp[sy] = (s0 + tot * wB) & 63u;
             for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
             if (PERM) lbase[sy] = es;
             u32 bitpos = ws * 64u + s0;
@@ -426,36 +471,35 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         // the top of the loop it would also wait for the stores of the output phase below.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        // one thread per output word
+        // one thread per image word: complete words leave now, unless their line is still open
         const u32 n_img = sh.wstart[S];
         for (u32 k = tid; k < n_img; k += DBLOCK) {
             u32 g = sh.cidx[k >> 3];
             while (sh.wstart[g + 1u] <= k) g++;
-            const bool first = k == sh.wstart[g], last = k + 1u == sh.wstart[g + 1u];
+            const RunWords r = run_words(sh.gb[g], sh.gcnt[g], wB);
+            const u32 j = k - sh.wstart[g], Wg = r.Wf + j;
+            if (Wg >= r.We) continue; // the run's last, partial word: taken over at the next tile
             unsigned long long val = slot[k];
-            const bool shared = first && sh.own[g] == 0u;
-            if (first && !shared) val |= sh.carry[g];
-            GLOBAL_AS unsigned long long *dst = out + (sh.dbase[g] + k);
-            if (last && sh.tailp[g]) { // the stream word stays incomplete after this tile
-                if (shared) {
-                    if (val) __hip_atomic_fetch_or(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    sh.nown[g] = 0u;
-                    sh.ncarry[g] = 0ull;
-                } else {
-                    sh.nown[g] = 1u;
-                    sh.ncarry[g] = val;
-                }
+            if (j == 0u) val |= sh.lw[g][r.Wf & (LINE - 1u)]; // bits of earlier tiles in this word
+            const u32 fo = sh.fo[g], own = fo & 0x7fffffffu;
+            const u32 L = Wg / LINE;
+            if ((fo >> 31) && Wg + 1u == own) { // shared with the run before this chunk's
+                if (val) __hip_atomic_fetch_or(out + Wg, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else if (L * LINE >= own && L == r.We / LINE) {
+                // a line of this chunk's own that is not complete yet: it waits in LDS
             } else {
-                if (shared) {
-                    if (val) __hip_atomic_fetch_or(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } else {
-                    *dst = val;
-                }
-                if (last) {
-                    sh.nown[g] = 1u;
-                    sh.ncarry[g] = 0ull;
-                }
+                out[Wg] = val;
             }
+        }
+        // one thread per buffered word: the words of a line that this tile has completed
+        for (u32 i = tid; i < S * LINE; i += DBLOCK) {
+            const u32 g = i / LINE, j = i % LINE;
+            const u32 c = sh.gcnt[g];
+            if (c == 0u) continue;
+            const RunWords r = run_words(sh.gb[g], c, wB);
+            const u32 Lf = r.Wf / LINE;
+            if (Lf * LINE >= (sh.fo[g] & 0x7fffffffu) && Lf < r.We / LINE && j < (r.Wf & (LINE - 1u)))
+                out[Lf * LINE + j] = sh.lw[g][j];
         }
         for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u; // for the next tile's counts
         if (PERM) {
@@ -467,18 +511,16 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         }
     }
     __syncthreads();
-    if (tid < S) { // the partial words that the chunk leaves behind
-        u32 pos = sh.gb[tid];
-        unsigned long long cv = sh.carry[tid];
-        u32 o = sh.own[tid];
-        if (sh.gcnt[tid]) {
-            pos += sh.gcnt[tid];
-            cv = sh.ncarry[tid];
-            o = sh.nown[tid];
-        }
-        if (o && cv)
-            __hip_atomic_fetch_or(out + (((u64)pos * wB) >> 6), cv, __ATOMIC_RELAXED,
-                                  __HIP_MEMORY_SCOPE_AGENT);
+    commit_lines(sh, slot, S, wB, tid);
+    __syncthreads();
+    if (tid < S) { // what the chunk leaves behind: the words of an open line, the last partial word
+        const RunWords r = run_words(sh.gb[tid] + sh.gcnt[tid], 0u, wB);
+        const u32 Le = r.We / LINE, wl = r.We & (LINE - 1u);
+        if (Le * LINE >= (sh.fo[tid] & 0x7fffffffu))
+            for (u32 j = 0; j < wl; j++) out[Le * LINE + j] = sh.lw[tid][j];
+        const unsigned long long part = sh.lw[tid][wl];
+        if (r.tail && part)
+            __hip_atomic_fetch_or(out + r.We, part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
