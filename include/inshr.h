@@ -14,6 +14,7 @@
  *                   bit-packed symbols + codebook + protected-value list.
  *   inshr_delta     Delta Encoder (Sec. 6): cyclic difference of symbols against the previous
  *                   checkpoint, regrouped by the previous checkpoint's symbol (Algorithm 5).
+ * and their inverses for the restore side: inshr_reconstruct (Algorithm 6) and inshr_dequantize.
  *
  * Conventions
  *   - Every function returns 0 on success or a negative INSHR_E_* code; nothing aborts or throws.
@@ -146,6 +147,41 @@ int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t 
  * recomputed. */
 int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *prev_perm,
                 const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors);
+
+/* ---- restore side ------------------------------------------------------------------------- */
+
+typedef struct {
+    const uint64_t *packed;      /* device symbol stream, (bits + 1)-bit symbols                  */
+    const float *codebook;       /* device, 1 << bits bin centres                                 */
+    const uint32_t *outlier_idx; /* device, n_outlier ascending indices (may be NULL if 0)        */
+    const float *outlier_val;    /* device, their original values                                 */
+    uint64_t n_outlier;
+    uint64_t n;
+    uint8_t bits;
+} inshr_dequant_in;
+
+/* Inverse of the Quantizer (Sec. 4): out[t][i] = +0.0 for symbol 0, the protected value for symbol
+ * 1 and codebook[s - 2] for symbol s >= 2.  out: host array of n_tensors device pointers, each to n
+ * floats (4-byte aligned).  Returns after the work has completed.  INSHR_E_ARG: a symbol above
+ * K + 1; INSHR_E_SHAPE: the elements with symbol 1 are not exactly the listed indices (or these are
+ * not ascending). */
+int inshr_dequantize(inshr_ctx *ctx, const inshr_dequant_in *in, float *const *out,
+                     uint32_t n_tensors);
+
+typedef struct {
+    uint64_t *packed;      /* device, receives the symbols of the current checkpoint              */
+    uint64_t packed_words; /* >= ceil(n * (bits + 1) / 64)                                         */
+    uint8_t bits;          /* bits of the current checkpoint's configuration                       */
+} inshr_codes_out;
+
+/* Inverse of the Delta Encoder (Sec. 6, Algorithm 6): element i, whose previous symbol is g, takes
+ * the next delta e of group g in the stream and becomes (g - e) mod B.  delta[t] is what
+ * inshr_delta wrote for the same prev codes: packed, packed_words and delta_bits are read; group_off
+ * (may be NULL) is compared with the offsets that prev implies; perm is not used.  Returns after the
+ * work has completed.  INSHR_E_SHAPE: group offsets disagree with prev; INSHR_E_ARG: a delta >= B or
+ * a result above K_cur + 1 (the stream does not belong to these codes). */
+int inshr_reconstruct(inshr_ctx *ctx, const inshr_codes *prev, const inshr_delta_out *delta,
+                      inshr_codes_out *cur, uint32_t n_tensors);
 
 /* Per-kernel timing for benchmarks (not part of the method): when enabled, every kernel launch of
  * this process is bracketed by HIP events on its stream.  inshr_profile(ctx, 1) clears the totals

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
-           "inshr_delta_bound", "inshr_delta", "inshr_profile", "inshr_profile_read"]
+           "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
+           "inshr_profile", "inshr_profile_read"]
 
 INSHR_REUSE_SEARCH = 1
 
@@ -58,6 +59,16 @@ class CDeltaOut(C.Structure):
                 ("perm", C.c_void_p), ("delta_bits", C.c_uint32)]
 
 
+class CDequantIn(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("codebook", C.c_void_p), ("outlier_idx", C.c_void_p),
+                ("outlier_val", C.c_void_p), ("n_outlier", C.c_uint64), ("n", C.c_uint64),
+                ("bits", C.c_uint8)]
+
+
+class CCodesOut(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("bits", C.c_uint8)]
+
+
 _lib = None
 
 
@@ -87,6 +98,10 @@ def load_library() -> C.CDLL:
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
+    lib.inshr_dequantize.argtypes = [C.c_void_p, C.POINTER(CDequantIn), C.POINTER(C.c_void_p),
+                                     C.c_uint32]
+    lib.inshr_reconstruct.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CDeltaOut),
+                                      C.POINTER(CCodesOut), C.c_uint32]
     lib.inshr_profile.argtypes = [C.c_void_p, C.c_int]
     lib.inshr_profile_read.argtypes = [C.c_void_p, C.POINTER(CKernelTime), C.c_uint32,
                                        C.POINTER(C.c_uint32)]
@@ -305,4 +320,47 @@ class Context:
         self._check(self.lib.inshr_delta(self.h, pa, pp, ca, oa, nT))
         for i in range(nT):
             res[i].delta_bits = int(oa[i].delta_bits)
+        return res
+
+    # -- inshr_dequantize -----------------------------------------------------------------
+    def dequantize(self, qs: Sequence[Quantized],
+                   out: Optional[Sequence[torch.Tensor]] = None) -> List[torch.Tensor]:
+        """fp32 tensors decoded from the quantized form; returns after the work has completed."""
+        nT = len(qs)
+        ia = (CDequantIn * nT)()
+        oa = (C.c_void_p * nT)()
+        res = []
+        for i, q in enumerate(qs):
+            ia[i] = CDequantIn(q._ptrs[0], q._ptrs[1], q._ptrs[3], q._ptrs[4], q.n_outlier, q.n, q.bits)
+            x = out[i] if out is not None else torch.empty(q.n, dtype=torch.float32,
+                                                           device=q._bufs[0].device)
+            if x.dtype != torch.float32 or x.numel() != q.n or not x.is_contiguous():
+                raise ValueError("output must be a contiguous float32 tensor of n elements")
+            oa[i] = x.data_ptr()
+            res.append(x)
+        self._check(self.lib.inshr_dequantize(self.h, ia, oa, nT))
+        return res
+
+    # -- inshr_reconstruct ----------------------------------------------------------------
+    def reconstruct(self, prev: Sequence[Quantized], deltas: Sequence[Delta],
+                    bits_cur: Sequence[int]) -> List[torch.Tensor]:
+        """Packed symbols (int64 words) of the current checkpoint from the previous codes and the
+        delta streams; returns after the work has completed."""
+        nT = len(prev)
+        pa = (CCodes * nT)()
+        da = (CDeltaOut * nT)()
+        ca = (CCodesOut * nT)()
+        res = []
+        for i, (p, d) in enumerate(zip(prev, deltas)):
+            pa[i] = CCodes(p._ptrs[0], p.sym_bits, p.bits, p.n)
+            da[i].packed = d.packed.data_ptr()
+            da[i].packed_words = d.packed.numel()
+            da[i].group_off = d.group_off.data_ptr() if d.group_off is not None else None
+            da[i].perm = None
+            da[i].delta_bits = d.delta_bits
+            words = (p.n * (int(bits_cur[i]) + 1) + 63) // 64
+            w = torch.empty(words, dtype=torch.int64, device=p._bufs[0].device)
+            ca[i] = CCodesOut(w.data_ptr(), words, int(bits_cur[i]))
+            res.append(w)
+        self._check(self.lib.inshr_reconstruct(self.h, pa, da, ca, nT))
         return res

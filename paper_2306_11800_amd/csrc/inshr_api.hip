@@ -757,4 +757,135 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
     return INSHR_OK;
 }
 
+int inshr_dequantize(inshr_ctx *c, const inshr_dequant_in *in, float *const *out, uint32_t n_tensors)
+{
+    if (!c || !in || !out || n_tensors == 0 || n_tensors > 65535u) return INSHR_E_ARG;
+    std::vector<RDesc> rd(n_tensors);
+    u64 tile = 0, max_out = 0;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        const inshr_dequant_in &q = in[t];
+        if (q.bits < 1 || q.bits > 8) return INSHR_E_CONFIG;
+        if (q.n == 0 || q.n >= (1ull << 32) || !q.packed || !q.codebook || !out[t]) return INSHR_E_ARG;
+        if (q.n_outlier && (!q.outlier_idx || !q.outlier_val)) return INSHR_E_ARG;
+        if (q.n_outlier > q.n) return INSHR_E_SHAPE;
+        RDesc &d = rd[t];
+        memset(&d, 0, sizeof(d));
+        d.packed = (const unsigned long long *)q.packed;
+        d.codebook = q.codebook;
+        d.out_idx = q.outlier_idx;
+        d.out_val = q.outlier_val;
+        d.dst = out[t];
+        d.n = q.n;
+        d.n_outlier = q.n_outlier;
+        d.tile0 = tile;
+        d.w = q.bits + 1u;
+        d.K = 1u << q.bits;
+        tile += (q.n + TILE - 1) / TILE;
+        max_out = std::max<u64>(max_out, q.n_outlier);
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    Carver cv;
+    const size_t o_rd = cv.take(sizeof(RDesc) * n_tensors);
+    const size_t o_fl = cv.take(sizeof(u32) * (n_tensors + 1)); // flags, then symbol-1 counts
+    const size_t up_bytes = cv.off;
+    int rc = ensure_dev(c, c->aux_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, up_bytes);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_down, sizeof(u32));
+    if (rc) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
+    char *hb = (char *)c->h_up.p, *db = (char *)c->aux_mem.p;
+    memset(hb, 0, up_bytes);
+    memcpy(hb + o_rd, rd.data(), sizeof(RDesc) * n_tensors);
+    HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
+    u32 *flags = (u32 *)(db + o_fl);
+    HIPCHK(c, launch_dequantize((const RDesc *)(db + o_rd), (int)n_tensors, tile, max_out, flags,
+                                flags + 1, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, flags, sizeof(u32), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const u32 f = *(const u32 *)c->h_down.p;
+    if (f & RF_SYMBOL) return INSHR_E_ARG;
+    if (f & RF_LIST) return INSHR_E_SHAPE;
+    return INSHR_OK;
+}
+
+int inshr_reconstruct(inshr_ctx *c, const inshr_codes *prev, const inshr_delta_out *delta,
+                      inshr_codes_out *cur, uint32_t n_tensors)
+{
+    if (!c || !prev || !delta || !cur || n_tensors == 0) return INSHR_E_ARG;
+    std::vector<DDesc> dd(n_tensors);
+    std::vector<XDesc> xd(n_tensors);
+    std::vector<u32> chunk_tensor;
+    u64 dtile = 0, chunk = 0;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        const uint64_t n = prev[t].n;
+        if (prev[t].bits < 1 || prev[t].bits > 8 || cur[t].bits < 1 || cur[t].bits > 8) return INSHR_E_CONFIG;
+        if (prev[t].sym_bits != prev[t].bits + 1u) return INSHR_E_CONFIG;
+        if (n == 0 || n >= (1ull << 32) || !prev[t].packed || !delta[t].packed || !cur[t].packed) return INSHR_E_ARG;
+        const uint32_t wB = (uint32_t)std::max(prev[t].bits, cur[t].bits) + 1u;
+        if (delta[t].delta_bits != wB) return INSHR_E_CONFIG;
+        if (delta[t].packed_words < (n * wB + 63) / 64) return INSHR_E_CAPACITY;
+        const uint32_t wc = cur[t].bits + 1u;
+        if (cur[t].packed_words < (n * wc + 63) / 64) return INSHR_E_CAPACITY;
+        DDesc &d = dd[t];
+        memset(&d, 0, sizeof(d));
+        d.prev = (const unsigned long long *)prev[t].packed;
+        d.out = (unsigned long long *)delta[t].packed; // read only on this side
+        d.n = n;
+        d.out_words = (n * wB + 63) / 64;
+        d.wp = prev[t].sym_bits;
+        d.wc = wc;
+        d.Kp = 1u << prev[t].bits;
+        const uint32_t Kc = 1u << cur[t].bits;
+        d.B = std::max(d.Kp, Kc) + 2u;
+        d.wB = wB;
+        d.dtile0 = dtile;
+        d.chunk0 = chunk;
+        const u64 nt = (n + DELTA_TILE - 1) / DELTA_TILE;
+        d.n_chunks = (nt + DELTA_CHUNK - 1) / DELTA_CHUNK;
+        for (u64 k = 0; k < d.n_chunks; k++) chunk_tensor.push_back(t);
+        dtile += nt;
+        chunk += d.n_chunks;
+        XDesc &x = xd[t];
+        memset(&x, 0, sizeof(x));
+        x.cur_out = (unsigned long long *)cur[t].packed;
+        x.group_off_in = delta[t].group_off;
+        x.Sc = Kc + 2u;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    Carver cv;
+    const size_t o_dd = cv.take(sizeof(DDesc) * n_tensors);
+    const size_t o_xd = cv.take(sizeof(XDesc) * n_tensors);
+    const size_t o_ct = cv.take(sizeof(u32) * chunk_tensor.size());
+    const size_t o_fl = cv.take(sizeof(u32));
+    const size_t up_bytes = cv.off;
+    const size_t o_go = cv.take(sizeof(u64) * (DELTA_SS + 8) * n_tensors); // group offsets from prev
+    const size_t o_ck = cv.take((size_t)chunk * DELTA_SS * 4);
+    int rc = ensure_dev(c, c->aux_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, up_bytes);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_down, sizeof(u32));
+    if (rc) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    char *hb = (char *)c->h_up.p, *db = (char *)c->aux_mem.p;
+    for (uint32_t t = 0; t < n_tensors; t++) dd[t].group_off = (u64 *)(db + o_go) + (size_t)t * (DELTA_SS + 8);
+    memset(hb, 0, up_bytes);
+    memcpy(hb + o_dd, dd.data(), sizeof(DDesc) * n_tensors);
+    memcpy(hb + o_xd, xd.data(), sizeof(XDesc) * n_tensors);
+    memcpy(hb + o_ct, chunk_tensor.data(), sizeof(u32) * chunk_tensor.size());
+    HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
+    u32 *flags = (u32 *)(db + o_fl);
+    HIPCHK(c, launch_reconstruct((const DDesc *)(db + o_dd), (const XDesc *)(db + o_xd),
+                                 (int)n_tensors, chunk, (const u32 *)(db + o_ct),
+                                 (u32 *)(db + o_ck), flags, c->lds_ordered, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, flags, sizeof(u32), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const u32 f = *(const u32 *)c->h_down.p;
+    if (f & RF_GROUPS) return INSHR_E_SHAPE;
+    if (f & RF_DELTA) return INSHR_E_ARG;
+    return INSHR_OK;
+}
+
 } // extern "C"

@@ -593,6 +593,134 @@ __global__ __launch_bounds__(SS) void k_dzero(const DDesc *__restrict__ dd,
     if (word < d.out_words) gptr(d.out)[word] = 0ull;
 }
 
+// Restore side (Algorithm 6): s_cur[i] = (s_prev[i] - e[r]) mod B, where r is the position of element
+// i in the stable order of s_prev.  Same chunk and tile walk as k_dscatter: sweep 1 ranks the
+// elements of a tile, sweep 2 reads every element's delta at its stream position and ORs the
+// current symbol into an LDS image of the tile's packed words, which is stored whole.
+template <bool ORDERED>
+__global__ __launch_bounds__(DBLOCK) void k_drestore(const DDesc *__restrict__ dd,
+                                                     const XDesc *__restrict__ xd,
+                                                     const u32 *__restrict__ chunk_tensor,
+                                                     const u32 *__restrict__ chunk_tot,
+                                                     u32 *__restrict__ flags)
+{
+    __shared__ u32 wst[WST];
+    __shared__ u32 gb[SS]; // stream position of each group's next element
+    __shared__ unsigned long long hotkey;
+    __shared__ u32 Pw[DTILE * 9 / 32 + 8];
+    __shared__ u32 Ci[DTILE * 9 / 32 + 8]; // image of the tile's current symbols
+    __shared__ unsigned long long slot[ORDERED ? 1 : NWAVE * SS];
+    const u64 chunk = blockIdx.x;
+    const u32 t = __builtin_amdgcn_readfirstlane(chunk_tensor[chunk]);
+    const DDesc d = dd[t];
+    const XDesc x = xd[t];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const u32 S = d.Kp + 2u, Bm = d.B, wB = d.wB, wp = d.wp, wc = d.wc;
+    const u32 srow = S + 1u;
+    const u64 n_tiles = (d.n + DTILE - 1) / DTILE;
+    const u64 lt0 = (chunk - d.chunk0) * DCHUNK;
+    const u64 lt1 = (lt0 + DCHUNK < n_tiles) ? lt0 + DCHUNK : n_tiles;
+    if (tid < S) gb[tid] = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
+    if (tid == 0u) hotkey = 0ull;
+    __syncthreads();
+    if (tid < S) atomicMax(&hotkey, ((gptr(d.group_off)[tid + 1u] - gptr(d.group_off)[tid]) << 9) | tid);
+    __syncthreads();
+    const u32 hot = __builtin_amdgcn_readfirstlane((u32)hotkey & 511u);
+    u32 *wrow = wst + wave * srow;
+    const GLOBAL_AS u32 *stream = (const GLOBAL_AS u32 *)gptr(d.out);
+    const u32 mB = (1u << wB) - 1u;
+    u32 bad = 0u;
+    for (u64 lt = lt0; lt < lt1; lt++) {
+        const u64 e0 = lt * (u64)DTILE;
+        const u64 rem = d.n - e0;
+        const u32 cnt = rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
+        __syncthreads(); // the previous tile's image has been stored
+        const u32 ndp = 2u * ((cnt * wp + 63u) >> 6), ndc = 2u * ((cnt * wc + 63u) >> 6);
+        const GLOBAL_AS u32 *src = (const GLOBAL_AS u32 *)(gptr(d.prev) + e0 * wp / 64u);
+        for (u32 k = tid; k < ndp; k += DBLOCK) Pw[k] = src[k];
+        for (u32 k = tid; k < ndc + 2u; k += DBLOCK) Ci[k] = 0u;
+        for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) wst[k] = 0u;
+        if (!ORDERED)
+            for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
+        __syncthreads();
+        u32 reg[16];
+        const u32 ebase = wave * 1024u + lane;
+        if (cnt == (u32)DTILE)
+            rank_rows<true, ORDERED>(Pw, Pw, wrow, slot + (ORDERED ? 0 : wave * SS), ebase, cnt, S, Bm, wp, wp, hot, reg);
+        else
+            rank_rows<false, ORDERED>(Pw, Pw, wrow, slot + (ORDERED ? 0 : wave * SS), ebase, cnt, S, Bm, wp, wp, hot, reg);
+        __syncthreads();
+        if (tid < S) { // counts -> stream position of the first element of every (wave, symbol)
+            u32 run = gb[tid];
+            for (int wv = 0; wv < NWAVE; wv++) {
+                const u32 c = wst[wv * srow + tid];
+                wst[wv * srow + tid] = run;
+                run += c;
+            }
+            gb[tid] = run;
+        }
+        __syncthreads();
+#pragma unroll
+        for (u32 r = 0; r < 16u; r++) {
+            const u32 v = reg[r];
+            if (!(v >> 31)) continue;
+            const u32 sp = v & 511u, within = (v >> 9) & 1023u;
+            const u64 pos = (u64)wrow[sp] + within;
+            if (pos >= d.n) { // more elements in this group than the offsets allow: never read past
+                bad = 1u;     // the stream
+                continue;
+            }
+            const u64 bit = pos * wB;
+            const u64 wd = bit >> 5;
+            const u32 sh = (u32)bit & 31u;
+            const u32 lo = stream[wd];
+            const u32 hi = (sh + wB > 32u) ? stream[wd + 1u] : 0u;
+            const u32 e = __builtin_amdgcn_alignbit(hi, lo, sh) & mB;
+            u32 sc = sp >= e ? sp - e : sp + Bm - e;
+            if (e >= Bm || sc >= x.Sc) {
+                bad = 1u;
+                sc = 0u;
+            }
+            const u32 bo = (ebase + 64u * r) * wc;
+            const u32 word = bo >> 5, shf = bo & 31u;
+            if (sc) {
+                atomicOr(&Ci[word], sc << shf);
+                if (shf + wc > 32u) atomicOr(&Ci[word + 1u], sc >> (32u - shf));
+            }
+        }
+        __syncthreads();
+        GLOBAL_AS u32 *dst = (GLOBAL_AS u32 *)(gptr(x.cur_out) + e0 * wc / 64u);
+        for (u32 k = tid; k < ndc; k += DBLOCK) dst[k] = Ci[k];
+    }
+    if (__ballot(bad != 0u) && lane == 0u) atomicOr(flags, RF_DELTA);
+}
+
+// group offsets that came with the stream against those of the previous symbols
+__global__ __launch_bounds__(SS) void k_dcheck_groups(const DDesc *__restrict__ dd,
+                                                      const XDesc *__restrict__ xd,
+                                                      u32 *__restrict__ flags)
+{
+    const DDesc d = dd[blockIdx.x];
+    const XDesc x = xd[blockIdx.x];
+    const u32 g = threadIdx.x;
+    if (x.group_off_in && g <= d.Kp + 2u && gptr(x.group_off_in)[g] != gptr(d.group_off)[g])
+        atomicOr(flags, RF_GROUPS);
+}
+
+hipError_t launch_reconstruct(const DDesc *dd, const XDesc *xd, int nT, u64 n_chunks,
+                              const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool lds_ordered,
+                              hipStream_t s)
+{
+    PROF("k_dhist", s, k_dhist<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+    PROF("k_dgroups", s, k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot));
+    PROF("k_dcheck_groups", s, k_dcheck_groups<<<nT, SS, 0, s>>>(dd, xd, flags));
+    if (lds_ordered)
+        PROF("k_drestore", s, k_drestore<true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, xd, chunk_tensor, chunk_tot, flags));
+    else
+        PROF("k_drestore_slots", s, k_drestore<false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, xd, chunk_tensor, chunk_tot, flags));
+    return hipGetLastError();
+}
+
 // 1 if same-address LDS atomics with return are served in ascending lane order, for every pattern
 // tried: all lanes on one address, few addresses, many addresses, with inactive lanes
 __global__ __launch_bounds__(256) void k_lds_order_check(u32 *__restrict__ violations)

@@ -98,6 +98,25 @@ struct DDesc { // one tensor of a delta call
     u64 dtile0, chunk0, n_chunks;
     u32 wp, wc, Kp, B, wB, pad;
 };
+struct RDesc { // one tensor of a dequantize call
+    const unsigned long long *packed;
+    const float *codebook;
+    const u32 *out_idx;
+    const float *out_val;
+    float *dst;
+    u64 n, n_outlier, tile0;
+    u32 w, K;
+};
+struct XDesc { // one tensor of a reconstruct call: the delta descriptor plus what is checked
+    unsigned long long *cur_out; // receives the current symbols
+    const u64 *group_off_in;     // group offsets that came with the stream, or NULL
+    u32 Sc, pad;                 // symbols of the current checkpoint
+};
+// bits of the flag word the restore kernels raise
+constexpr u32 RF_SYMBOL = 1u;  // a symbol outside 0 .. K + 1
+constexpr u32 RF_LIST = 2u;    // protected list and symbol stream disagree
+constexpr u32 RF_GROUPS = 4u;  // group offsets do not match the previous symbols
+constexpr u32 RF_DELTA = 8u;   // a delta outside 0 .. B - 1, or a result outside 0 .. K_cur + 1
 constexpr int DELTA_TILE = 12288;
 constexpr int DELTA_CHUNK = 64;
 constexpr int DELTA_SS = 264;
@@ -120,6 +139,11 @@ hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
                         const u32 *chunk_tensor, u32 *chunk_tot, bool any_scatter, bool any_perm,
                         bool any_gather, bool lds_ordered, hipStream_t s);
 hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
+hipError_t launch_dequantize(const RDesc *rd, int nT, u64 n_tiles, u64 max_outlier, u32 *flags,
+                             u32 *ones, hipStream_t s);
+hipError_t launch_reconstruct(const DDesc *dd, const XDesc *xd, int nT, u64 n_chunks,
+                              const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool lds_ordered,
+                              hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
 // tile iteration shared by the streaming kernels
