@@ -67,6 +67,9 @@ def main():
                          "smaller ones (config0 tensor, ResNet-50 / BERT-base / GPT-2-medium shapes "
                          "with Adam state), reported for reference")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--restore", action="store_true",
+                    help="also time the restore side (reconstruct + dequantize of the checkpoint) after "
+                         "the timed steps and report it as an extra object; needs 4 more bytes per value")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -164,6 +167,27 @@ def main():
                 "path_achieved": round(path_gbs, 1), "path_frac": round(path_gbs / HBM_PEAK_GBS, 4),
                 "kernel_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in sorted(prof.items())}}
 
+    restore = None
+    if args.restore:
+        bits_cur = [c[0] for c in cfgs]
+        xs = [torch.empty_like(t) for t in cur]
+        for it in range(3):
+            if it == 1:
+                torch.cuda.synchronize()
+                ctx.profile(True)
+                t0 = time.perf_counter()
+            rec = ctx.reconstruct(q_prev, d_out, bits_cur)
+            ctx.dequantize(q_cur, out=xs)
+        torch.cuda.synchronize()
+        rdt = (time.perf_counter() - t0) / 2
+        rprof = ctx.profile_read()
+        ctx.profile(False)
+        same = all(torch.equal(r, q.packed) for r, q in zip(rec, q_cur))
+        restore = {"ms": round(rdt * 1e3, 3), "GB/s_of_fp32_restored": round(n_total * 4 / rdt / 1e9, 1),
+                   "reconstructed_equals_current_codes": same,
+                   "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(rprof.items())}}
+        del xs, rec
+
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
@@ -191,6 +215,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if restore is not None:
+        out["restore"] = restore
     print(json.dumps(out))
 
 

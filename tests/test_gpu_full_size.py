@@ -2,8 +2,8 @@
 configuration the bench uses, checked on every element against definitions written with torch's
 library routines on the device (sort, bucketize, stable sort, bincount) — the CPU oracle would need
 minutes for this size.  Thresholds, boundaries, every symbol, the protected list, the delta stream,
-the regrouping permutation and the group offsets are compared bit for bit; centres and the error sum
-of the chosen configuration to 1e-6."""
+the regrouping permutation, the group offsets, the reconstructed symbols and the decoded values are
+compared bit for bit; centres and the error sum of the chosen configuration to 1e-6."""
 import numpy as np
 import pytest
 import torch
@@ -131,3 +131,12 @@ def test_largest_tensor_every_element(ctx):
     out2 = ctx.delta([qs[0]], [qs[1]], want_perm=False)[0]
     ctx.sync()
     assert torch.equal(out2.packed, out.packed)
+    # restore side: the current symbols come back from the previous symbols and the stream, and
+    # decoding them gives 0 / the protected value / the centre of the bin for every element
+    rec = ctx.reconstruct([qs[0]], [out2], [cfg[0]])[0]
+    assert torch.equal(rec, qs[1].packed)
+    xh = ctx.dequantize([qs[1]])[0]
+    sym = refs[1]["sym"].to(torch.int64)
+    want = torch.where(sym >= 2, qs[1].codebook[(sym - 2).clamp(min=0)], torch.zeros((), device=dev))
+    want[refs[1]["prot"]] = cur[refs[1]["prot"]]
+    assert torch.equal(xh.view(torch.int32), want.view(torch.int32))
