@@ -181,8 +181,10 @@ struct ScatterShared {
     unsigned long long lw[SS][LINE]; // per group: the words of its current, incomplete output line
     u32 fo[SS];                     // first stream word that this chunk's run of the group owns
                                     // alone; bit 31: the word before it is shared with the run before
-    u32 gcnt[SS];                   // tile population per symbol
-    u32 gb[SS];                     // stream position of each group's run of this tile (n < 2^32)
+    u32 gb[SS];                     // stream position after each group's runs so far (n < 2^32)
+    u32 gWf[SS], gWe[SS];           // the group's run of the current tile: stream word of its first
+                                    // bit; first word that is still incomplete after it
+    u32 gtl[SS];                    // bits of word gWe that are filled; bit 31: the run is not empty
     u32 wtot[8], etot[8];
     unsigned long long hotkey;      // population << 9 | symbol, maximum over the tensor's groups
     u16 cidx[CIDX];
@@ -206,10 +208,12 @@ __device__ __forceinline__ RunWords run_words(u32 pos, u32 cnt, u32 wB)
 // Sweep 1 of a tile: stable rank of every element among the equal symbols of its wave's 1024
 // elements.  Row r of a lane is element ebase + 64 r: its bit offset in the packed words moves
 // by 64 w per row, so the shift is a lane constant and the word address advances by 2 w.
-template <bool FULL, bool ORDERED>
+// reg[r] = symbol | rank << 9 | delta << 19 | valid << 31, or with BITPOS (needs wB): symbol |
+// (rank * wB) << 9 | delta << 23, where an element past the end has delta 0.
+template <bool FULL, bool ORDERED, bool BITPOS = false>
 __device__ __forceinline__ void rank_rows(const u32 *P, const u32 *C, u32 *wrow,
                                           unsigned long long *myslot, u32 ebase, u32 cnt, u32 S,
-                                          u32 Bm, u32 wp, u32 wc, u32 hot, u32 (&reg)[16])
+                                          u32 Bm, u32 wp, u32 wc, u32 hot, u32 (&reg)[16], u32 wB = 0u)
 {
     u32 hot_seen = 0u; // elements of the wave so far that hold the most frequent symbol
     const u32 lane = threadIdx.x & 63u;
@@ -264,30 +268,39 @@ __device__ __forceinline__ void rank_rows(const u32 *P, const u32 *C, u32 *wrow,
             }
             u32 dv = sp - sc;
             if (sp < sc) dv += Bm;
-            reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
+            if (BITPOS)
+                reg[r] = (__umul24(within, wB << 9) + sp) | ((valid ? dv : 0u) << 23);
+            else
+                reg[r] = sp | (within << 9) | (dv << 19) | ((valid ? 1u : 0u) << 31);
         }
     }
     if (ORDERED && lane == 0u) wrow[hot] = hot_seen;
 }
 
-// After a tile's output phase: the words of each group's open line that came from this tile's image
-// (the complete ones of a line that is the chunk's own, and the partial last word) move into the
-// group's line buffer.  One thread per (group, word of the line); nothing else touches the buffers
-// or the image meanwhile.
-__device__ __forceinline__ void commit_lines(ScatterShared &sh, const unsigned long long *image, u32 S,
-                                             u32 wB, u32 tid)
+// After a tile's output phase, one thread per group: the words of the line that the tile completed
+// and that earlier tiles had buffered are stored; then the words of the group's open line that came
+// from this tile's image (the complete ones of a line that is the chunk's own, and the partial last
+// word) move into the group's line buffer.  Nothing else touches the buffers or the image meanwhile.
+__device__ __forceinline__ void flush_and_commit(ScatterShared &sh, const unsigned long long *image,
+                                                 GLOBAL_AS unsigned long long *out, u32 g)
 {
-    for (u32 i = tid; i < S * LINE; i += DBLOCK) {
-        const u32 g = i / LINE, j = i % LINE;
-        const u32 c = sh.gcnt[g];
-        if (c == 0u) continue;
-        const RunWords r = run_words(sh.gb[g], c, wB);
-        const u32 Wt = (r.We / LINE) * LINE + j; // word j of the line that is open after the tile
-        if (Wt > r.We || Wt < r.Wf) continue;    // not written yet / buffered by an earlier tile
+    asm volatile("" : "+v"(g)); // the group's addresses are recomputed here, not kept across the tile
+                                // loop in spilled registers (a reload would wait for the stores)
+    const u32 meta = sh.gtl[g];
+    if (!(meta >> 31)) return; // the group had no element in the tile
+    const u32 Wf = sh.gWf[g], We = sh.gWe[g], tail = meta & 63u;
+    const u32 own = sh.fo[g] & 0x7fffffffu, ws = sh.wstart[g];
+    const u32 Lf = Wf / LINE, Le = We / LINE;
+    if (Lf * LINE >= own && Lf < Le)
+        for (u32 j = 0; j < (Wf & (LINE - 1u)); j++) out[Lf * LINE + j] = sh.lw[g][j];
+#pragma unroll
+    for (u32 j = 0; j < (u32)LINE; j++) {
+        const u32 Wt = Le * LINE + j;         // word j of the line that is open after the tile
+        if (Wt > We || Wt < Wf) continue;     // not written yet / buffered by an earlier tile
         unsigned long long v = 0ull;
-        if (Wt < r.We || r.tail) {
-            v = image[sh.wstart[g] + (Wt - r.Wf)];
-            if (Wt == r.Wf) v |= sh.lw[g][j]; // bits of earlier tiles in the run's first word
+        if (Wt < We || tail) {
+            v = image[ws + (Wt - Wf)];
+            if (Wt == Wf) v |= sh.lw[g][j];   // bits of earlier tiles in the run's first word
         }
         sh.lw[g][j] = v;
     }
@@ -317,7 +330,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     // the same memory then holds the image of the tile's output words (sweep 2, output)
     __shared__ unsigned long long slot[ORDERED ? BWORDS : NWAVE * SS];
     __shared__ u32 wel[PERM ? WST : 1];  // local regrouped index of (wave, symbol)
-    __shared__ u32 lbase[PERM ? SS : 1]; // local regrouped index of each group's run
+    __shared__ u32 lbase[PERM ? SS : 1]; // local regrouped index of each group's run; [S] = elements
     __shared__ u16 si[PERM ? DTILE : 1]; // local indices in regrouped order
     u32 *img = (u32 *)slot;
     static_assert(NWAVE * SS >= BWORDS, "output image fits the slot array");
@@ -336,7 +349,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     if (tid < S) {
         const u32 g0 = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
         sh.gb[tid] = g0;
-        sh.gcnt[tid] = 0u;
+        sh.gtl[tid] = 0u;
         const u64 sb = (u64)g0 * wB;
         sh.fo[tid] = (u32)((sb + 63u) >> 6) | ((sb & 63u) ? 0x80000000u : 0u);
     }
@@ -363,7 +376,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u32 cnt = tile_cnt(lt);
         __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
                          // before its output phase); the previous tile's output phase is over
-        commit_lines(sh, slot, S, wB, tid); // the previous tile's trailing words -> line buffers
+        if (tid < S) flush_and_commit(sh, slot, out, tid); // the previous tile's lines
         if (!ORDERED) { // sweep 1 uses the slots
             __syncthreads();
             for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
@@ -374,9 +387,9 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         asm volatile("" : "+v"(ebase)); // keeps the per-row LDS addresses from being hoisted out of
                                         // the tile loop and spilled
         if (cnt == (u32)DTILE)
-            rank_rows<true, ORDERED>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
+            rank_rows<true, ORDERED, !PERM>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg, wB);
         else
-            rank_rows<false, ORDERED>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg);
+            rank_rows<false, ORDERED, !PERM>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg, wB);
         __syncthreads();
         if (lt + 1 < lt1) { // the symbols are in registers: the next tile's words start travelling
             lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
@@ -398,8 +411,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                                      // spilled: a reload would wait for the words in flight)
         if (tid < S) {
             for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
-            const u32 pos = sh.gb[sy] + sh.gcnt[sy]; // after the previous tile's run
-            sh.gb[sy] = pos;
+            const u32 pos = sh.gb[sy]; // after the previous tile's run
             fb = (u64)pos * wB;
             s0 = (u32)(fb & 63u);
             nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
@@ -429,9 +441,16 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
                 ws += sh.wtot[w2];
                 es += sh.etot[w2];
             }
-            sh.gcnt[sy] = tot;
+            const u64 fe = fb + (u64)tot * wB;
+            sh.gb[sy] += tot;
+            sh.gWf[sy] = (u32)(fb >> 6);
+            sh.gWe[sy] = (u32)(fe >> 6);
+            sh.gtl[sy] = (u32)(fe & 63u) | (tot ? 0x80000000u : 0u);
             sh.wstart[sy] = ws;
-            if (tid == S - 1u) sh.wstart[S] = ws + nW;
+            if (tid == S - 1u) {
+                sh.wstart[S] = ws + nW;
+                if (PERM) lbase[S] = es + tot;
+            }
             for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
             if (PERM) lbase[sy] = es;
             u32 bitpos = ws * 64u + s0;
@@ -456,9 +475,10 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             for (u32 q = 0; q < 8u; q++) {
                 const u32 r = rb + q;
                 const u32 v = reg[r];
-                const u32 dv = (v >> 19) & 511u, within = (v >> 9) & 1023u;
-                if ((v >> 31) && dv) {
-                    const u32 bo = start[q] + within * wB;
+                const u32 dv = PERM ? (v >> 19) & 511u : v >> 23;
+                const u32 within = (v >> 9) & 1023u; // (PERM)
+                if ((!PERM || (v >> 31)) && dv) {
+                    const u32 bo = start[q] + (PERM ? within * wB : (v >> 9) & 0x3FFFu);
                     const u32 word = bo >> 5, shf = bo & 31u;
                     atomicOr(&img[word], dv << shf);
                     if (shf + wB > 32u) atomicOr(&img[word + 1u], dv >> (32u - shf));
@@ -476,45 +496,35 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         for (u32 k = tid; k < n_img; k += DBLOCK) {
             u32 g = sh.cidx[k >> 3];
             while (sh.wstart[g + 1u] <= k) g++;
-            const RunWords r = run_words(sh.gb[g], sh.gcnt[g], wB);
-            const u32 j = k - sh.wstart[g], Wg = r.Wf + j;
-            if (Wg >= r.We) continue; // the run's last, partial word: taken over at the next tile
+            const u32 Wf = sh.gWf[g], We = sh.gWe[g];
+            const u32 j = k - sh.wstart[g], Wg = Wf + j;
+            if (Wg >= We) continue; // the run's last, partial word: taken over at the next tile
             unsigned long long val = slot[k];
-            if (j == 0u) val |= sh.lw[g][r.Wf & (LINE - 1u)]; // bits of earlier tiles in this word
+            if (j == 0u) val |= sh.lw[g][Wf & (LINE - 1u)]; // bits of earlier tiles in this word
             const u32 fo = sh.fo[g], own = fo & 0x7fffffffu;
             const u32 L = Wg / LINE;
             if ((fo >> 31) && Wg + 1u == own) { // shared with the run before this chunk's
                 if (val) __hip_atomic_fetch_or(out + Wg, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else if (L * LINE >= own && L == r.We / LINE) {
+            } else if (L * LINE >= own && L == We / LINE) {
                 // a line of this chunk's own that is not complete yet: it waits in LDS
             } else {
                 out[Wg] = val;
             }
         }
-        // one thread per buffered word: the words of a line that this tile has completed
-        for (u32 i = tid; i < S * LINE; i += DBLOCK) {
-            const u32 g = i / LINE, j = i % LINE;
-            const u32 c = sh.gcnt[g];
-            if (c == 0u) continue;
-            const RunWords r = run_words(sh.gb[g], c, wB);
-            const u32 Lf = r.Wf / LINE;
-            if (Lf * LINE >= (sh.fo[g] & 0x7fffffffu) && Lf < r.We / LINE && j < (r.Wf & (LINE - 1u)))
-                out[Lf * LINE + j] = sh.lw[g][j];
-        }
         for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u; // for the next tile's counts
         if (PERM) {
             for (u32 g = wave; g < S; g += NWAVE) {
-                const u32 c = sh.gcnt[g];
+                const u32 c = lbase[g + 1u] - lbase[g];
+                const u32 p0 = sh.gb[g] - c;
                 for (u32 i = lane; i < c; i += 64u)
-                    gptr(d.perm)[sh.gb[g] + i] = (u32)(e0 + si[lbase[g] + i]);
+                    gptr(d.perm)[p0 + i] = (u32)(e0 + si[lbase[g] + i]);
             }
         }
     }
     __syncthreads();
-    commit_lines(sh, slot, S, wB, tid);
-    __syncthreads();
     if (tid < S) { // what the chunk leaves behind: the words of an open line, the last partial word
-        const RunWords r = run_words(sh.gb[tid] + sh.gcnt[tid], 0u, wB);
+        flush_and_commit(sh, slot, out, tid);
+        const RunWords r = run_words(sh.gb[tid], 0u, wB);
         const u32 Le = r.We / LINE, wl = r.We & (LINE - 1u);
         if (Le * LINE >= (sh.fo[tid] & 0x7fffffffu))
             for (u32 j = 0; j < wl; j++) out[Le * LINE + j] = sh.lw[tid][j];
