@@ -55,7 +55,8 @@ __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *
         const bool valid = FULL || ((mask >> i) & 1u);
         if (valid) atomicAdd(&h[l2_bin(key[i], ent[i])], 1u);
         const bool cand = valid && in_threshold_bucket(key[i], ent[i]) && key[i] != ZERO_KEY;
-        const u64 cm = __ballot(cand);
+        u64 cm = __ballot(in_threshold_bucket(key[i], ent[i])) & __ballot(key[i] != ZERO_KEY);
+        if (!FULL) cm &= __ballot(valid);
         if (cand)
             gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key[i];
         gathered += (u32)__popcll(cm);
@@ -615,26 +616,31 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
                                             double (&q_out)[MAX_FRAC], u32 (&oc)[MAX_FRAC])
 {
     u32 key[16], slot[16];
+    float amax = 0.0f; // largest magnitude of the lane's values (entries past the end are 0.0)
 #pragma unroll
     for (int i = 0; i < 16; i++) {
-        key[i] = key_of_float(v[i]);
+        const float xc = v[i] + 0.0f; // -0.0 becomes +0.0
+        key[i] = key_of_bits(__float_as_uint(xc));
         slot[i] = T[key[i] >> COARSE_SHIFT];
+        amax = fmaxf(amax, fabsf(xc));
     }
 #pragma unroll
     for (int i = 0; i < 16; i++) slot[i] = SEG[l2_bin(key[i], slot[i])];
-    u32 mmax = 0u;
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         const bool valid = FULL || ((mask >> i) & 1u);
-        if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (double)v[i]);
         const bool cand = valid && key[i] != ZERO_KEY && slot[i] == 0xFFFFu;
-        const u64 cm = __ballot(cand);
+        // (a ballot of each comparison, taken next to it and combined as scalars: the ballot of a
+        // combined or an earlier condition would be rebuilt from a vector register)
+        u64 cm = __ballot(key[i] != ZERO_KEY) & __ballot(slot[i] == 0xFFFFu);
+        if (!FULL) cm &= __ballot(valid);
+        if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (double)v[i]);
         if (cand)
             gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key[i];
         gathered += (u32)__popcll(cm);
-        if (valid) mmax = max(mmax, mag_of_key(key[i]));
     }
-    if (__ballot(mmax > tau_o_min)) { // rare: some value of the wave's 1024 is protected
+    // the bits of a non-negative float order like its magnitude image
+    if (__ballot(__float_as_uint(amax) > tau_o_min)) { // rare: some value of the wave's 1024 is protected
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             const bool valid = FULL || ((mask >> i) & 1u);
@@ -652,17 +658,24 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
     }
 }
 
+
+constexpr int SM_GATHER = MAX_EDGES * 8 + COARSE * 4 + L2_BINS * 2 + (BLOCK / 64) * 8 + MAX_FRAC * 4;
+
 __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, int nT,
                                                   const u64 *__restrict__ wg_tile0,
                                                   const u32 *__restrict__ wg_fu0,
                                                   const GridDesc *__restrict__ gd, Bufs B)
 {
-    extern __shared__ u32 smem[];
+    // one static array (the only one, so it starts at LDS address 0): table offsets then fold into
+    // the LDS instructions, which the base of a dynamic array does not allow
+    __shared__ __attribute__((aligned(16))) u32 smem[SM_GATHER / 4];
     double *sx = reinterpret_cast<double *>(smem);             // [MAX_EDGES] sum per slot
     u32 *T = smem + 2 * MAX_EDGES;                             // [COARSE]
     u16 *SEG = reinterpret_cast<u16 *>(T + COARSE);            // [L2_BINS] slot of the bin, or 0xFFFF
-    __shared__ u32 s_tau_o[MAX_FRAC];
-    __shared__ double s_red[BLOCK / 64];
+    // (no static LDS arrays: the tables then start at LDS address 0 and their offsets fold into
+    // the instructions)
+    double *s_red = reinterpret_cast<double *>(SEG + L2_BINS); // [BLOCK / 64]
+    u32 *s_tau_o = reinterpret_cast<u32 *>(s_red + BLOCK / 64); // [MAX_FRAC]
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
@@ -1243,7 +1256,6 @@ constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
 constexpr int SM_BUCKET = (2 * BUCKET_CAP + (BB / 64) * 256) * 4;
-constexpr int SM_GATHER = MAX_EDGES * 8 + COARSE * 4 + L2_BINS * 2;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
@@ -1254,7 +1266,6 @@ static hipError_t set_attrs()
     if ((e = hipFuncSetAttribute((const void *)k_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
-    if ((e = hipFuncSetAttribute((const void *)k_gather, hipFuncAttributeMaxDynamicSharedMemorySize, SM_GATHER))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
@@ -1273,7 +1284,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     if ((e = launch_edges(bt, s))) return e;
-    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, SM_GATHER, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
+    PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
     PROF("k_split", s, k_split<<<dim3(bt.n_units, SPLIT_PARTS), BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     if (bt.lds_ordered)
