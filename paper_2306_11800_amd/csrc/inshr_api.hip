@@ -780,7 +780,7 @@ int inshr_dequantize(inshr_ctx *c, const inshr_dequant_in *in, float *const *out
         d.tile0 = tile;
         d.w = q.bits + 1u;
         d.K = 1u << q.bits;
-        tile += (q.n + TILE - 1) / TILE;
+        tile += (q.n + DEQUANT_TILE - 1) / DEQUANT_TILE;
         max_out = std::max<u64>(max_out, q.n_outlier);
     }
     HIPCHK(c, hipSetDevice(c->device));
@@ -801,7 +801,7 @@ int inshr_dequantize(inshr_ctx *c, const inshr_dequant_in *in, float *const *out
     HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
     u32 *flags = (u32 *)(db + o_fl);
     HIPCHK(c, launch_dequantize((const RDesc *)(db + o_rd), (int)n_tensors, tile, max_out, flags,
-                                flags + 1, c->stream));
+                                flags + 1, c->n_cu, c->stream));
     HIPCHK(c, hipMemcpyAsync(c->h_down.p, flags, sizeof(u32), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     const u32 f = *(const u32 *)c->h_down.p;

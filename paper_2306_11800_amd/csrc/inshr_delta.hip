@@ -604,22 +604,35 @@ __global__ __launch_bounds__(SS) void k_dzero(const DDesc *__restrict__ dd,
 }
 
 // Restore side (Algorithm 6): s_cur[i] = (s_prev[i] - e[r]) mod B, where r is the position of element
-// i in the stable order of s_prev.  Same chunk and tile walk as k_dscatter: sweep 1 ranks the
-// elements of a tile, sweep 2 reads every element's delta at its stream position and ORs the
-// current symbol into an LDS image of the tile's packed words, which is stored whole.
+// i in the stable order of s_prev.  Same chunk and tile walk as k_dscatter, with the data flowing the
+// other way: sweep 1 ranks the elements of a tile; the stream words of every group's run of the tile
+// are copied into an LDS image (one thread per word, consecutive words of a run by consecutive
+// threads); sweep 2 takes every element's delta from the image and ORs the current symbol into an
+// LDS image of the tile's packed words, which is stored whole.
+struct RestoreShared {
+    u32 wst[WST];       // counts, then bit position in the stream image of (wave, symbol)
+    u32 wstart[SS + 8]; // first image word of each group's run; [S] = words in use
+    u32 gWf[SS];        // stream word of the first bit of each group's run of this tile
+    u32 gb[SS];         // stream position after each group's runs so far
+    u32 wtot[8];
+    unsigned long long hotkey;
+    u16 cidx[CIDX];
+};
+
 template <bool ORDERED>
-__global__ __launch_bounds__(DBLOCK) void k_drestore(const DDesc *__restrict__ dd,
-                                                     const XDesc *__restrict__ xd,
-                                                     const u32 *__restrict__ chunk_tensor,
-                                                     const u32 *__restrict__ chunk_tot,
-                                                     u32 *__restrict__ flags)
+__global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict__ dd,
+                                                        const XDesc *__restrict__ xd,
+                                                        const u32 *__restrict__ chunk_tensor,
+                                                        const u32 *__restrict__ chunk_tot,
+                                                        u32 *__restrict__ flags)
 {
-    __shared__ u32 wst[WST];
-    __shared__ u32 gb[SS]; // stream position of each group's next element
-    __shared__ unsigned long long hotkey;
-    __shared__ u32 Pw[DTILE * 9 / 32 + 8];
+    __shared__ RestoreShared sh;
+    __shared__ __attribute__((aligned(16))) u32 Pw[DTILE * 9 / 32 + 8];
     __shared__ u32 Ci[DTILE * 9 / 32 + 8]; // image of the tile's current symbols
-    __shared__ unsigned long long slot[ORDERED ? 1 : NWAVE * SS];
+    // slots of sweep 1 (ballot ranking only); then the image of the tile's stream words
+    __shared__ unsigned long long slot[NWAVE * SS];
+    static_assert(NWAVE * SS >= BWORDS, "stream image fits the slot array");
+    const u32 *img = (const u32 *)slot;
     const u64 chunk = blockIdx.x;
     const u32 t = __builtin_amdgcn_readfirstlane(chunk_tensor[chunk]);
     const DDesc d = dd[t];
@@ -630,44 +643,96 @@ __global__ __launch_bounds__(DBLOCK) void k_drestore(const DDesc *__restrict__ d
     const u64 n_tiles = (d.n + DTILE - 1) / DTILE;
     const u64 lt0 = (chunk - d.chunk0) * DCHUNK;
     const u64 lt1 = (lt0 + DCHUNK < n_tiles) ? lt0 + DCHUNK : n_tiles;
-    if (tid < S) gb[tid] = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
-    if (tid == 0u) hotkey = 0ull;
+    if (tid < S) sh.gb[tid] = (u32)gptr(d.group_off)[tid] + chunk_tot[chunk * SS + tid];
+    if (tid < SS + 8u) sh.wstart[tid] = 0xFFFFFFFFu;
+    if (tid == 0u) sh.hotkey = 0ull;
+    for (u32 k = tid; k < (u32)WST; k += DBLOCK) sh.wst[k] = 0u;
     __syncthreads();
-    if (tid < S) atomicMax(&hotkey, ((gptr(d.group_off)[tid + 1u] - gptr(d.group_off)[tid]) << 9) | tid);
+    if (tid < S)
+        atomicMax(&sh.hotkey, ((gptr(d.group_off)[tid + 1u] - gptr(d.group_off)[tid]) << 9) | tid);
     __syncthreads();
-    const u32 hot = __builtin_amdgcn_readfirstlane((u32)hotkey & 511u);
-    u32 *wrow = wst + wave * srow;
-    const GLOBAL_AS u32 *stream = (const GLOBAL_AS u32 *)gptr(d.out);
+    const u32 hot = __builtin_amdgcn_readfirstlane((u32)sh.hotkey & 511u);
+    u32 *wrow = sh.wst + wave * srow;
+    const GLOBAL_AS unsigned long long *stream = gptr(d.out);
     const u32 mB = (1u << wB) - 1u;
     u32 bad = 0u;
+    auto tile_cnt = [&](u64 lt) -> u32 {
+        const u64 rem = d.n - lt * (u64)DTILE;
+        return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
+    };
+    lds_fetch(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
-        const u64 rem = d.n - e0;
-        const u32 cnt = rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
-        __syncthreads(); // the previous tile's image has been stored
-        const u32 ndp = 2u * ((cnt * wp + 63u) >> 6), ndc = 2u * ((cnt * wc + 63u) >> 6);
-        const GLOBAL_AS u32 *src = (const GLOBAL_AS u32 *)(gptr(d.prev) + e0 * wp / 64u);
-        for (u32 k = tid; k < ndp; k += DBLOCK) Pw[k] = src[k];
-        for (u32 k = tid; k < ndc + 2u; k += DBLOCK) Ci[k] = 0u;
-        for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) wst[k] = 0u;
-        if (!ORDERED)
+        const u32 cnt = tile_cnt(lt);
+        __syncthreads(); // the tile's previous symbols are in LDS; the previous tile has been stored
+        if (!ORDERED) {
             for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
-        __syncthreads();
+            __syncthreads();
+        }
         u32 reg[16];
-        const u32 ebase = wave * 1024u + lane;
+        u32 ebase = wave * 1024u + lane;
+        asm volatile("" : "+v"(ebase)); // (the per-row LDS addresses are not kept across tiles)
         if (cnt == (u32)DTILE)
-            rank_rows<true, ORDERED>(Pw, Pw, wrow, slot + (ORDERED ? 0 : wave * SS), ebase, cnt, S, Bm, wp, wp, hot, reg);
+            rank_rows<true, ORDERED>(Pw, Pw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wp, hot, reg);
         else
-            rank_rows<false, ORDERED>(Pw, Pw, wrow, slot + (ORDERED ? 0 : wave * SS), ebase, cnt, S, Bm, wp, wp, hot, reg);
+            rank_rows<false, ORDERED>(Pw, Pw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wp, hot, reg);
         __syncthreads();
-        if (tid < S) { // counts -> stream position of the first element of every (wave, symbol)
-            u32 run = gb[tid];
-            for (int wv = 0; wv < NWAVE; wv++) {
-                const u32 c = wst[wv * srow + tid];
-                wst[wv * srow + tid] = run;
-                run += c;
+        if (lt + 1 < lt1) lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
+        {
+            const u32 ndc = 2u * ((cnt * wc + 63u) >> 6) + 2u;
+            u32 k0 = tid;
+            asm volatile("" : "+v"(k0));
+            for (u32 k = k0; k < ndc; k += DBLOCK) Ci[k] = 0u;
+        }
+        // counts -> positions, as in the scatter: the stream words each group's run touches,
+        // exclusive scan over symbols, bit position of every (wave, symbol) in the image
+        u32 tot = 0, nW = 0, s0 = 0, preW = 0;
+        u64 fb = 0;
+        u32 sy = tid;
+        asm volatile("" : "+v"(sy));
+        if (tid < S) {
+            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
+            fb = (u64)sh.gb[sy] * wB;
+            s0 = (u32)(fb & 63u);
+            nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
+        }
+        if (tid < 320u) {
+            u32 incW = nW;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                u32 v = __shfl_up(incW, o);
+                if ((int)lane >= o) incW += v;
             }
-            gb[tid] = run;
+            preW = incW - nW;
+            if (lane == 63u) sh.wtot[wave] = incW;
+        }
+        __syncthreads();
+        if (tid < S) {
+            u32 ws = preW;
+            for (u32 w2 = 0; w2 < wave; w2++) ws += sh.wtot[w2];
+            sh.gb[sy] += tot;
+            sh.gWf[sy] = (u32)(fb >> 6);
+            sh.wstart[sy] = ws;
+            if (tid == S - 1u) sh.wstart[S] = ws + nW;
+            for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
+            u32 bitpos = ws * 64u + s0;
+            for (int wv = 0; wv < NWAVE; wv++) {
+                const u32 c = sh.wst[wv * srow + sy];
+                sh.wst[wv * srow + sy] = bitpos;
+                bitpos += c * wB;
+            }
+        }
+        __syncthreads();
+        { // the stream words of the tile: image word k is stream word gWf[g] + k - wstart[g]
+            const u32 n_img = sh.wstart[S];
+            for (u32 k = tid; k < n_img; k += DBLOCK) {
+                u32 g = sh.cidx[k >> 3];
+                while (sh.wstart[g + 1u] <= k) g++;
+                const u64 W = (u64)sh.gWf[g] + (k - sh.wstart[g]);
+                slot[k] = W < d.out_words ? stream[W] : 0ull;
+            }
+            if (tid < 2u) slot[n_img + tid] = 0ull; // sweep 2 reads one dword past a run's last bit
         }
         __syncthreads();
 #pragma unroll
@@ -675,32 +740,28 @@ __global__ __launch_bounds__(DBLOCK) void k_drestore(const DDesc *__restrict__ d
             const u32 v = reg[r];
             if (!(v >> 31)) continue;
             const u32 sp = v & 511u, within = (v >> 9) & 1023u;
-            const u64 pos = (u64)wrow[sp] + within;
-            if (pos >= d.n) { // more elements in this group than the offsets allow: never read past
-                bad = 1u;     // the stream
-                continue;
-            }
-            const u64 bit = pos * wB;
-            const u64 wd = bit >> 5;
-            const u32 sh = (u32)bit & 31u;
-            const u32 lo = stream[wd];
-            const u32 hi = (sh + wB > 32u) ? stream[wd + 1u] : 0u;
-            const u32 e = __builtin_amdgcn_alignbit(hi, lo, sh) & mB;
+            const u32 bo = wrow[sp] + within * wB;
+            const u32 e = __builtin_amdgcn_alignbit(img[(bo >> 5) + 1u], img[bo >> 5], bo & 31u) & mB;
             u32 sc = sp >= e ? sp - e : sp + Bm - e;
             if (e >= Bm || sc >= x.Sc) {
                 bad = 1u;
                 sc = 0u;
             }
-            const u32 bo = (ebase + 64u * r) * wc;
-            const u32 word = bo >> 5, shf = bo & 31u;
+            const u32 co = (ebase + 64u * r) * wc;
+            const u32 word = co >> 5, shf = co & 31u;
             if (sc) {
                 atomicOr(&Ci[word], sc << shf);
                 if (shf + wc > 32u) atomicOr(&Ci[word + 1u], sc >> (32u - shf));
             }
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the next tile's words
         __syncthreads();
-        GLOBAL_AS u32 *dst = (GLOBAL_AS u32 *)(gptr(x.cur_out) + e0 * wc / 64u);
-        for (u32 k = tid; k < ndc; k += DBLOCK) dst[k] = Ci[k];
+        {
+            const u32 ndc = 2u * ((cnt * wc + 63u) >> 6);
+            GLOBAL_AS u32 *dst = (GLOBAL_AS u32 *)(gptr(x.cur_out) + e0 * wc / 64u);
+            for (u32 k = tid; k < ndc; k += DBLOCK) dst[k] = Ci[k];
+            for (u32 k = tid; k < NWAVE * srow; k += DBLOCK) sh.wst[k] = 0u; // for the next tile's counts
+        }
     }
     if (__ballot(bad != 0u) && lane == 0u) atomicOr(flags, RF_DELTA);
 }

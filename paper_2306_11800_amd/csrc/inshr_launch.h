@@ -107,6 +107,7 @@ struct RDesc { // one tensor of a dequantize call
     u64 n, n_outlier, tile0;
     u32 w, K;
 };
+constexpr int DEQUANT_TILE = 16384; // elements per workgroup of the decoding kernel (RDesc::tile0 counts these)
 struct XDesc { // one tensor of a reconstruct call: the delta descriptor plus what is checked
     unsigned long long *cur_out; // receives the current symbols
     const u64 *group_off_in;     // group offsets that came with the stream, or NULL
@@ -140,7 +141,7 @@ hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
                         bool any_gather, bool lds_ordered, hipStream_t s);
 hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
 hipError_t launch_dequantize(const RDesc *rd, int nT, u64 n_tiles, u64 max_outlier, u32 *flags,
-                             u32 *ones, hipStream_t s);
+                             u32 *ones, int n_cu, hipStream_t s);
 hipError_t launch_reconstruct(const DDesc *dd, const XDesc *xd, int nT, u64 n_chunks,
                               const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool lds_ordered,
                               hipStream_t s);
