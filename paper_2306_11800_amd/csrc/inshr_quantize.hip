@@ -67,13 +67,19 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
 // breakpoints from the bin's first one on.
 constexpr int QBP = 264;          // breakpoints, padded
 constexpr int PKW = 256 * 9;      // most packed words of a tile
-constexpr int SM_QUANT = COARSE * 4 + L2_BINS * 2 + 2 * PKW * 8;
 
 struct QuantTables {
     u32 bp[QBP + 8];   // sorted breakpoints, then 0xFFFFFFFF
     u32 raw[QBP];      // boundaries of the configuration, then the class edges
     u16 symtab[QBP];   // symbol of slot s = #{breakpoints <= key}
     u32 wcnt[2][64];   // protected values per (quarter j, wave) of the tile, per buffer
+};
+
+struct QuantShared {
+    u32 T[COARSE];                     // key prefix -> bins
+    u16 symt[L2_BINS];                 // symbol, or 0x8000 | first breakpoint of the bin
+    unsigned long long pk[2 * PKW];    // two bit buffers of packed symbols
+    QuantTables qt;
 };
 
 template <bool FULL>
@@ -144,11 +150,13 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                                                  const GridDesc *__restrict__ gd,
                                                  const QDesc *__restrict__ qd_by_tensor, Bufs B)
 {
-    extern __shared__ u32 smem[];
-    u32 *T = smem;                                                // [COARSE] key prefix -> bins
-    u16 *symt = reinterpret_cast<u16 *>(smem + COARSE);           // [L2_BINS] symbol, or 0x8000 | first breakpoint
-    unsigned long long *pk0 = reinterpret_cast<unsigned long long *>(smem + COARSE + L2_BINS / 2); // [2][PKW]
-    __shared__ QuantTables qt;
+    // one static LDS object (it starts at LDS address 0): table offsets then fold into the LDS
+    // instructions, which the base of a dynamic array does not allow
+    __shared__ QuantShared qs;
+    u32 *T = qs.T;
+    u16 *symt = qs.symt;
+    unsigned long long *pk0 = qs.pk;
+    QuantTables &qt = qs.qt;
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
@@ -339,12 +347,10 @@ hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStrea
         hipError_t e = hipFuncSetAttribute((const void *)k_qprep,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (L2_BINS + 4) * 4);
         if (e) return e;
-        e = hipFuncSetAttribute((const void *)k_quant, hipFuncAttributeMaxDynamicSharedMemorySize, SM_QUANT);
-        if (e) return e;
         attr = true;
     }
     PROF("k_qprep", s, k_qprep<<<bt.nT, BLOCK, (L2_BINS + 4) * 4, s>>>(bt.td, bt.gd, qd, qi, bt.bufs));
-    PROF("k_quant", s, k_quant<<<bt.n_wg, BLOCK, SM_QUANT, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs));
+    PROF("k_quant", s, k_quant<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, qd, bt.bufs));
     return hipGetLastError();
 }
 

@@ -68,10 +68,11 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                                                 const u64 *__restrict__ wg_tile0,
                                                 const u32 *__restrict__ wg_fu0, Bufs B)
 {
-    extern __shared__ u32 smem[];
+    // one static array (it starts at LDS address 0, so offsets fold into the LDS instructions)
+    __shared__ __attribute__((aligned(16))) u32 smem[L2_BINS + (LEVEL == 2 ? COARSE : 0) + 2 * (BLOCK / 64)];
     u32 *h = smem;                 // 32768 counters
     u32 *T = smem + L2_BINS;       // LEVEL 2: 4096 table entries
-    __shared__ double s_red[BLOCK / 64];
+    double *s_red = reinterpret_cast<double *>(smem + L2_BINS + (LEVEL == 2 ? COARSE : 0));
 
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     for (int i = tid; i < L2_BINS; i += BLOCK) h[i] = 0u;
@@ -1250,8 +1251,6 @@ __global__ void k_group_list(int nT, Bufs B, u32 *grp_list, u32 *n_grp_total)
 // ------------------------------------------------------------------------------------------
 // launch wrappers
 // ------------------------------------------------------------------------------------------
-constexpr int SM_HIST1 = L2_BINS * 4;
-constexpr int SM_HIST2 = (L2_BINS + COARSE) * 4;
 constexpr int SM_PLAN1 = (2 * (L1_MAGBINS + 4) + COARSE + 4) * 4;
 constexpr int SM_PLAN2 = (L2_BINS + 4) * 4;
 constexpr int SM_SPLIT = (COARSE + 2 * MAX_GROUPS) * 4 + L2_BINS * 2;
@@ -1262,8 +1261,6 @@ static hipError_t set_attrs()
 {
     if (g_attr_done) return hipSuccess;
     hipError_t e;
-    if ((e = hipFuncSetAttribute((const void *)k_hist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST1))) return e;
-    if ((e = hipFuncSetAttribute((const void *)k_hist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_HIST2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
@@ -1278,9 +1275,9 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     hipError_t e = set_attrs();
     if (e) return e;
     const Bufs &B = bt.bufs;
-    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, SM_HIST1, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
+    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
     PROF("k_plan1", s, k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
-    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, SM_HIST2, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
+    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
     PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     if ((e = launch_edges(bt, s))) return e;
