@@ -309,16 +309,20 @@ struct Fragments {
 };
 
 // k-th smallest magnitude among the gathered keys of magnitude bin mb (all share the bits above
-// bit 16).  Two counting rounds over 9 and 8 bits with an LDS histogram.  Returns the low 17 bits;
-// *seen = number of keys of the bin that were found.
-__device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *hist /*[512]*/,
-                                       u32 *sh, u32 *seen)
+// bit 16), and the numbers of the bin's keys below and above it by sign.  Two counting rounds over
+// 9 and 8 bits with LDS histograms kept per sign, so that no third pass has to count the classes:
+// keys below = bins below the chosen one in round 1 + digits below the chosen one in round 2.
+// Returns the low 17 bits; cn = {#(m < tau, negative), #(m < tau, positive), #(m > tau, negative),
+// #(m > tau, positive)}; *seen = number of keys of the bin that were found.
+__device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *hist /*[2][512]*/,
+                                       u32 *sh /*[8]*/, u32 *seen, u32 (&cn)[4])
 {
     const u32 tid = threadIdx.x;
     u32 prefix = 0u; // chosen bits so far (of the low 17)
+    cn[0] = cn[1] = cn[2] = cn[3] = 0u;
     for (int round = 0; round < 2; round++) {
         const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
-        for (u32 i = tid; i < 512u; i += TSEL) hist[i] = 0u;
+        for (u32 i = tid; i < 1024u; i += TSEL) hist[i] = 0u;
         __syncthreads();
         for (u32 u = tid >> 6; u < 16u * f.n_units; u += TSEL / 64) { // one fragment per wave
             const u32 fu = f.ids[u >> 4];
@@ -334,40 +338,55 @@ __device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *h
                     if (i0 + j * 64u >= c || (mag >> L1_SHIFT) != mb) continue;
                     const u32 m = mag & 0x1FFFFu;
                     if (round == 0 || (m >> 8) == prefix)
-                        atomicAdd(&hist[(m >> shift) & (nbin - 1u)], 1u);
+                        atomicAdd(&hist[(key_is_neg(kk[j]) ? 0u : 512u) + ((m >> shift) & (nbin - 1u))], 1u);
                 }
             }
         }
         __syncthreads();
         if (tid < 64u) { // 8 bins per lane
-            u32 loc[8], s = 0;
+            u32 ln[8], lp[8], sn = 0, sp = 0;
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                loc[j] = hist[tid * 8u + j];
-                s += loc[j];
+                ln[j] = hist[tid * 8u + j];
+                lp[j] = hist[512u + tid * 8u + j];
+                sn += ln[j];
+                sp += lp[j];
             }
-            u32 inc = s;
+            u32 incn = sn, incp = sp;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
-                u32 v = __shfl_up(inc, o);
-                if ((int)tid >= o) inc += v;
+                const u32 vn = __shfl_up(incn, o), vp = __shfl_up(incp, o);
+                if ((int)tid >= o) {
+                    incn += vn;
+                    incp += vp;
+                }
             }
-            u32 run = inc - s;
-            if (round == 0 && tid == 63u) *seen = inc;
-            if (k >= run && k < inc) {
+            const u32 totn = __shfl(incn, 63), totp = __shfl(incp, 63);
+            u32 bn = incn - sn, bp = incp - sp; // keys in the bins before this lane's
+            if (round == 0 && tid == 63u) *seen = incn + incp;
+            if (k >= bn + bp && k < incn + incp) {
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
-                    if (k >= run && k < run + loc[j]) {
+                    if (k >= bn + bp && k < bn + bp + ln[j] + lp[j]) {
                         sh[0] = tid * 8u + j;
-                        sh[1] = k - run;
+                        sh[1] = k - (bn + bp);
+                        sh[2] = bn;                    // below the chosen bin, by sign
+                        sh[3] = bp;
+                        sh[4] = totn - bn - ln[j];     // above it
+                        sh[5] = totp - bp - lp[j];
                     }
-                    run += loc[j];
+                    bn += ln[j];
+                    bp += lp[j];
                 }
             }
         }
         __syncthreads();
         prefix = (round == 0) ? sh[0] : ((prefix << 8) | sh[0]);
         k = sh[1];
+        cn[0] += sh[2];
+        cn[1] += sh[3];
+        cn[2] += sh[4];
+        cn[3] += sh[5];
         __syncthreads();
     }
     return prefix;
@@ -377,10 +396,9 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
                                                      const u32 *__restrict__ t_fu_off,
                                                      const u32 *__restrict__ t_fu_ids, Bufs B)
 {
-    __shared__ u32 hist[512];
-    __shared__ u32 sh[2];
+    __shared__ u32 hist[1024];
+    __shared__ u32 sh[8];
     __shared__ u32 s_seen;
-    __shared__ u32 red[4][TSEL / 64];
     const int t = blockIdx.x / MAX_THR;
     const u32 q = blockIdx.x % MAX_THR;
     TState *st = B.ts + t;
@@ -399,54 +417,23 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
     const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
     const u64 res = st->thr_res[q];
     u32 tau = 0u;
+    // keys of the bucket below / above the threshold, by sign (the zeros were not gathered)
+    u32 cn[4] = {0u, 0u, st->bucket_cnt_neg[bq], (u32)(st->bucket_cnt_pos[bq] - zeros)};
     if (res >= zeros) {
         if (res - zeros >= expect) {
             if (tid == 0) atomicOr(&st->internal_err, 8u);
             return;
         }
-        tau = (mb << L1_SHIFT) | block_select_mag(f, mb, (u32)(res - zeros), hist, sh, &s_seen);
+        tau = (mb << L1_SHIFT) | block_select_mag(f, mb, (u32)(res - zeros), hist, sh, &s_seen, cn);
         if (tid == 0 && (u64)s_seen != expect) atomicOr(&st->internal_err, 4u);
     }
-    u32 cn[4] = {0, 0, 0, 0};
-    for (u32 u = tid >> 6; u < 16u * f.n_units; u += TSEL / 64) { // one fragment per wave
-        const u32 fu = f.ids[u >> 4];
-        const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
-        const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
-        for (u32 i0 = tid & 63u; i0 < c; i0 += 256u) {
-            u32 kk[4];
-#pragma unroll
-            for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const u32 k = kk[j];
-                const u32 m = mag_of_key(k);
-                if (i0 + j * 64u >= c || (m >> L1_SHIFT) != mb) continue;
-                const bool neg = key_is_neg(k);
-                cn[0] += (m < tau && neg) ? 1u : 0u;
-                cn[1] += (m < tau && !neg) ? 1u : 0u;
-                cn[2] += (m > tau && neg) ? 1u : 0u;
-                cn[3] += (m > tau && !neg) ? 1u : 0u;
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        u32 x = wave_sum(cn[j]);
-        if ((tid & 63u) == 0u) red[j][tid >> 6] = x;
-    }
-    __syncthreads();
     if (tid == 0) {
-        u32 s4[4];
-        for (int j = 0; j < 4; j++) {
-            s4[j] = 0;
-            for (int w = 0; w < TSEL / 64; w++) s4[j] += red[j][w];
-        }
         const u64 n = td[t].n, n_neg = st->n_neg, n_pos = n - n_neg;
         st->thr_mag[q] = tau;
-        st->thr_lt_neg[q] = st->bucket_below_neg[bq] + s4[0];
-        st->thr_lt_pos[q] = st->bucket_below_pos[bq] + s4[1] + ((mb == 0u && tau > 0u) ? zeros : 0ull);
-        st->thr_gt_neg[q] = n_neg - st->bucket_below_neg[bq] - st->bucket_cnt_neg[bq] + s4[2];
-        st->thr_gt_pos[q] = n_pos - st->bucket_below_pos[bq] - st->bucket_cnt_pos[bq] + s4[3];
+        st->thr_lt_neg[q] = st->bucket_below_neg[bq] + cn[0];
+        st->thr_lt_pos[q] = st->bucket_below_pos[bq] + cn[1] + ((mb == 0u && tau > 0u) ? zeros : 0ull);
+        st->thr_gt_neg[q] = n_neg - st->bucket_below_neg[bq] - st->bucket_cnt_neg[bq] + cn[2];
+        st->thr_gt_pos[q] = n_pos - st->bucket_below_pos[bq] - st->bucket_cnt_pos[bq] + cn[3];
     }
 }
 
