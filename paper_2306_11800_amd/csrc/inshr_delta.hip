@@ -33,11 +33,25 @@ __device__ __forceinline__ u32 lds_extract(const u32 *W, u32 idx, u32 w)
 }
 
 // Symbols of one chunk counted by width W: every lane takes runs of 64 consecutive symbols (W whole
-// words), extracts them from registers with compile-time shifts and counts them in its wave's LDS
-// histogram; symbol 0 (pruned: the most frequent one when pruning is on) is counted from ballots.
+// words), extracts them from registers with compile-time shifts and counts the non-zero ones in its
+// wave's LDS histogram.  Symbol 0 (pruned: the most frequent one when pruning is on) is not counted:
+// its population is what the others leave of the chunk.
+template <int W, bool WHOLE>
+__device__ __forceinline__ void count_run(const u32 (&x)[2 * W + 1], u32 nvalid, u32 S, u32 *hrow)
+{
+#pragma unroll
+    for (int i = 0; i < 64; i++) {
+        constexpr u32 mask = (1u << W) - 1u;
+        const int p = i * W, dw = p >> 5, sh = p & 31;
+        u32 sym = (sh + W <= 32) ? (x[dw] >> sh) & mask
+                                 : __builtin_amdgcn_alignbit(x[dw + 1], x[dw], sh) & mask;
+        sym = sym < S ? sym : S; // a malformed stream counts into the unused entry S
+        if (sym != 0u && (WHOLE || (u32)i < nvalid)) atomicAdd(&hrow[sym], 1u);
+    }
+}
+
 template <int W>
-__device__ __forceinline__ void count_symbols(const DDesc &d, u64 c0, u64 c1, u32 S, u32 *hrow,
-                                              u32 &zeros)
+__device__ __forceinline__ void count_symbols(const DDesc &d, u64 c0, u64 c1, u32 S, u32 *hrow)
 {
     const u32 tid = threadIdx.x;
     const GLOBAL_AS unsigned long long *src = gptr(d.prev);
@@ -55,18 +69,10 @@ __device__ __forceinline__ void count_symbols(const DDesc &d, u64 c0, u64 c1, u3
             x[2 * k + 1] = (u32)(v >> 32);
         }
         x[2 * W] = 0u;
-        const bool whole = __ballot(nvalid < 64u) == 0ull; // the same for every active lane
-#pragma unroll
-        for (int i = 0; i < 64; i++) {
-            constexpr u32 mask = (1u << W) - 1u;
-            const int p = i * W, dw = p >> 5, sh = p & 31;
-            u32 sym = (sh + W <= 32) ? (x[dw] >> sh) & mask
-                                     : __builtin_amdgcn_alignbit(x[dw + 1], x[dw], sh) & mask;
-            const bool valid = whole || (u32)i < nvalid;
-            zeros += (u32)__popcll(__ballot(valid && sym == 0u));
-            sym = sym < S ? sym : S; // a malformed stream counts into the unused entry S
-            if (valid && sym != 0u) atomicAdd(&hrow[sym], 1u);
-        }
+        if (__ballot(nvalid < 64u) == 0ull) // the same for every active lane
+            count_run<W, true>(x, nvalid, S, hrow);
+        else
+            count_run<W, false>(x, nvalid, S, hrow);
     }
 }
 
@@ -76,6 +82,7 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
                                                  u32 *__restrict__ chunk_tot)
 {
     __shared__ u32 hw[BLOCK / 64][SS];
+    __shared__ u32 s_nonzero;
     const u64 chunk = blockIdx.x;
     const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
     const u32 tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -83,27 +90,27 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
     const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
     const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
     for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
-    u32 zeros = 0u;
+    if (tid == 0u) s_nonzero = 0u;
     __syncthreads();
     switch (d.wp) {
-    case 2: count_symbols<2>(d, c0, c1, S, hw[wave], zeros); break;
-    case 3: count_symbols<3>(d, c0, c1, S, hw[wave], zeros); break;
-    case 4: count_symbols<4>(d, c0, c1, S, hw[wave], zeros); break;
-    case 5: count_symbols<5>(d, c0, c1, S, hw[wave], zeros); break;
-    case 6: count_symbols<6>(d, c0, c1, S, hw[wave], zeros); break;
-    case 7: count_symbols<7>(d, c0, c1, S, hw[wave], zeros); break;
-    case 8: count_symbols<8>(d, c0, c1, S, hw[wave], zeros); break;
-    default: count_symbols<9>(d, c0, c1, S, hw[wave], zeros); break;
+    case 2: count_symbols<2>(d, c0, c1, S, hw[wave]); break;
+    case 3: count_symbols<3>(d, c0, c1, S, hw[wave]); break;
+    case 4: count_symbols<4>(d, c0, c1, S, hw[wave]); break;
+    case 5: count_symbols<5>(d, c0, c1, S, hw[wave]); break;
+    case 6: count_symbols<6>(d, c0, c1, S, hw[wave]); break;
+    case 7: count_symbols<7>(d, c0, c1, S, hw[wave]); break;
+    case 8: count_symbols<8>(d, c0, c1, S, hw[wave]); break;
+    default: count_symbols<9>(d, c0, c1, S, hw[wave]); break;
     }
     __syncthreads();
-    if ((tid & 63u) == 0u) hw[wave][0] = zeros;
-    __syncthreads();
-    for (u32 g = tid; g < SS; g += BLOCK) {
-        u32 s = 0;
-        if (g < S)
-            for (int wv = 0; wv < BLOCK / 64; wv++) s += hw[wv][g];
-        chunk_tot[chunk * SS + g] = s;
+    u32 mine = 0u; // population of symbol tid (symbols above S - 1 are in entry S)
+    if (tid >= 1u && tid <= S) {
+        for (int wv = 0; wv < BLOCK / 64; wv++) mine += hw[wv][tid];
+        if (mine) atomicAdd(&s_nonzero, mine);
     }
+    __syncthreads();
+    if (tid == 0u) mine = (u32)(c1 - c0) - s_nonzero;
+    if (tid < SS) chunk_tot[chunk * SS + tid] = tid < S ? mine : 0u;
 }
 
 // per tensor: group offsets; chunk_tot becomes the start of each chunk inside its group
