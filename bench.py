@@ -105,6 +105,7 @@ def main():
         del items
     n_total = sum(t.numel() for t in cur)
     ctx = api.Context(dev)
+    cur = ctx.batch(cur)  # the binding marshals the tensor list once, not in every step
 
     # previous checkpoint's codes (set-up, untimed)
     best_p, _, _ = ctx.search(prev, grid, eps, want_scores=False)

@@ -117,16 +117,34 @@ class InshrError(RuntimeError):
 
 class Quantized:
     """Device-side result of quantizing one tensor.  The tensors are views of buffers allocated at
-    the capacity inshr_quantize_bound gives; the views are made when they are asked for."""
-    __slots__ = ("n", "bits", "sym_bits", "n_pruned", "n_outlier", "n_kept", "tau_prune",
-                 "tau_outlier", "_bufs", "_ptrs")
+    the capacity inshr_quantize_bound gives; the views are made when they are asked for.  Counts,
+    thresholds and the symbol width are read from the C struct that inshr_quantize filled."""
+    __slots__ = ("n", "_bufs", "_ptrs", "_c", "_keep")
 
-    def __init__(self, n, bits, bufs):
-        self.n, self.bits, self.sym_bits = n, bits, bits + 1
-        self.n_pruned = self.n_outlier = self.n_kept = 0
-        self.tau_prune = self.tau_outlier = 0.0
+    def __init__(self, n, bits, bufs, c_entry=None, keep=None):
+        if c_entry is None:
+            c_entry = CQuantized()
+        self.n = n
         self._bufs = bufs                                   # packed, codebook, boundaries, idx, val
         self._ptrs = tuple(b.data_ptr() for b in bufs)
+        self._c = c_entry                                   # element of the CQuantized array
+        self._keep = keep                                   # the array itself
+        c_entry.sym_bits = bits + 1
+
+    sym_bits = property(lambda self: self._c.sym_bits)
+    bits = property(lambda self: self._c.sym_bits - 1)
+    n_pruned = property(lambda self: self._c.n_pruned)
+    n_kept = property(lambda self: self._c.n_kept)
+    tau_prune = property(lambda self: self._c.tau_prune)
+    tau_outlier = property(lambda self: self._c.tau_outlier)
+
+    @property
+    def n_outlier(self):
+        return self._c.n_outlier
+
+    @n_outlier.setter
+    def n_outlier(self, v):                  # (tests hand a wrong list length to the decoder)
+        self._c.n_outlier = v
 
     @property
     def packed(self) -> torch.Tensor:        # int64 words (bit pattern of u64)
@@ -149,6 +167,22 @@ class Quantized:
         return self._bufs[4][:self.n_outlier]
 
 
+class TensorBatch(list):
+    """A list of tensors with its marshalled C array, for callers that pass the same tensors again
+    and again (Context.batch).  The list must not be changed afterwards."""
+    __slots__ = ("_ta",)
+
+
+class QuantizedBatch(list):
+    """The list inshr_quantize's binding returns; it keeps the C array of its entries so that a
+    call with out=<this list> writes the same buffers again without marshalling them again."""
+    __slots__ = ("_qa", "_sizes")
+
+
+class DeltaBatch(list):
+    __slots__ = ("_pa", "_ca", "_oa", "_prev", "_cur")
+
+
 @dataclass
 class Delta:
     n: int
@@ -159,6 +193,8 @@ class Delta:
 
 
 def _tensor_array(tensors: Sequence[torch.Tensor]):
+    if isinstance(tensors, TensorBatch):
+        return tensors._ta
     arr = (CTensor * len(tensors))()
     for i, t in enumerate(tensors):
         if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
@@ -220,6 +256,12 @@ class Context:
         return {arr[i].name.decode(): (arr[i].total_ms, int(arr[i].launches))
                 for i in range(min(n.value, 64))}
 
+    def batch(self, tensors: Sequence[torch.Tensor]) -> TensorBatch:
+        """The same tensors as a list that carries its C array (see TensorBatch)."""
+        b = TensorBatch(tensors)
+        b._ta = _tensor_array(list(tensors))
+        return b
+
     # -- inshr_search ---------------------------------------------------------------------
     def search(self, tensors: Sequence[torch.Tensor], grid, eps: float, want_scores: bool = True):
         """Returns (best[list of int], feasible[list of int], scores or None) where scores is a
@@ -236,38 +278,43 @@ class Context:
     # -- inshr_quantize -------------------------------------------------------------------
     def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False,
                  out: Optional[List[Quantized]] = None) -> List[Quantized]:
-        """`out` may carry the Quantized objects of an earlier call on tensors of the same sizes;
-        their device buffers (allocated at full capacity) are then written again."""
+        """`out` may carry the list an earlier call returned for tensors of the same sizes; its
+        device buffers are then written again.  When that call sized them for the largest
+        configuration (8 bits and the largest protect fraction in use), nothing is marshalled
+        again."""
         nT = len(tensors)
         ta = _tensor_array(tensors)
         ca = _config_array(cfgs)
+        flags = INSHR_REUSE_SEARCH if reuse_search else 0
+        if isinstance(out, QuantizedBatch) and out._sizes == tuple(t.numel() for t in tensors):
+            # the C side checks every buffer against what the configuration needs
+            self._check(self.lib.inshr_quantize(self.h, ta, ca, out._qa, nT, flags))
+            return out
         qa = (CQuantized * nT)()
-        res: List[Quantized] = []
+        res = QuantizedBatch()
         for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
             n = t.numel()
             words, cap = self._bound(n, ca[i], cfg)
+            e = qa[i]
             if out is not None:
                 q = out[i]
                 if q.n != n or q._bufs[0].numel() < words or q._bufs[3].numel() < cap:
                     raise ValueError("pre-allocated buffers are too small")
-                q.bits, q.sym_bits = int(cfg[0]), int(cfg[0]) + 1
+                q = Quantized(n, int(cfg[0]), q._bufs, e, qa)
             else:
                 q = Quantized(n, int(cfg[0]), (
                     torch.empty(words, dtype=torch.int64, device=t.device),
                     torch.empty(256, dtype=torch.float32, device=t.device),
                     torch.empty(255, dtype=torch.float32, device=t.device),
                     torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
-                    torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)))
-            e = qa[i]
+                    torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa)
             e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
             e.packed_words = q._bufs[0].numel()
-            e.outlier_cap = cap
+            e.outlier_cap = q._bufs[3].numel()
             res.append(q)
-        self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, INSHR_REUSE_SEARCH if reuse_search else 0))
-        for q, e in zip(res, qa):
-            q.sym_bits = e.sym_bits
-            q.n_pruned, q.n_outlier, q.n_kept = e.n_pruned, e.n_outlier, e.n_kept
-            q.tau_prune, q.tau_outlier = e.tau_prune, e.tau_outlier
+        res._qa = qa
+        res._sizes = tuple(q.n for q in res)
+        self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, flags))
         return res
 
     def _bound(self, n, ccfg, cfg):
@@ -284,13 +331,25 @@ class Context:
               prev_perm: Optional[Sequence[Optional[torch.Tensor]]] = None,
               out: Optional[List[Delta]] = None) -> List[Delta]:
         """Enqueues the delta of every (prev[i], cur[i]); call sync() before reading on the host.
-        `out` may carry pre-allocated Delta buffers of a previous call with the same shapes."""
+        `out` may carry the list a previous call returned for the same shapes; with the same prev
+        and cur lists as in that call only the symbol widths are marshalled again."""
         nT = len(prev)
+        if (isinstance(out, DeltaBatch) and out._prev is prev and out._cur is cur and prev_perm is None
+                and not want_perm):
+            pa, ca, oa = out._pa, out._ca, out._oa
+            for i in range(nT):
+                a, b = prev[i]._c.sym_bits, cur[i]._c.sym_bits
+                pa[i].sym_bits, pa[i].bits = a, a - 1
+                ca[i].sym_bits, ca[i].bits = b, b - 1
+            self._check(self.lib.inshr_delta(self.h, pa, None, ca, oa, nT))
+            for i in range(nT):
+                out[i].delta_bits = int(oa[i].delta_bits)
+            return out
         pa = (CCodes * nT)()
         ca = (CCodes * nT)()
         oa = (CDeltaOut * nT)()
         pp = (C.c_void_p * nT)() if prev_perm is not None else None
-        res: List[Delta] = []
+        res = DeltaBatch()
         for i, (p, c) in enumerate(zip(prev, cur)):
             pa[i] = CCodes(p._ptrs[0], p.sym_bits, p.bits, p.n)
             ca[i] = CCodes(c._ptrs[0], c.sym_bits, c.bits, c.n)
@@ -320,6 +379,7 @@ class Context:
         self._check(self.lib.inshr_delta(self.h, pa, pp, ca, oa, nT))
         for i in range(nT):
             res[i].delta_bits = int(oa[i].delta_bits)
+        res._pa, res._ca, res._oa, res._prev, res._cur = pa, ca, oa, prev, cur
         return res
 
     # -- inshr_dequantize -----------------------------------------------------------------

@@ -293,3 +293,37 @@ def test_deterministic_bytes(ctx):
         outs.append((q.packed.clone(), q.boundaries.clone(), q.outlier_idx.clone()))
     for a, b in zip(outs[0], outs[1]):
         assert torch.equal(a, b)
+
+
+def test_reused_batches_give_the_same_bytes(ctx):
+    """Lists that carry their marshalled C arrays (Context.batch, out= of quantize and delta) against
+    plain lists, over steps whose configurations differ."""
+    rng = np.random.default_rng(41)
+    xs = [(0.02 * rng.standard_t(4, n)).astype(np.float32) for n in (70_001, 16384, 300_000)]
+    ys = [(x + rng.normal(0, 2e-4, x.size)).astype(np.float32) for x in xs]
+    tp, tc = [dev(x) for x in xs], [dev(y) for y in ys]
+    qp = ctx.quantize(tp, [(8, 0, 1000)] * 3)
+    cb = ctx.batch(tc)
+    q_re = ctx.quantize(cb, [(8, 0, 1000)] * 3)      # sizes the buffers
+    d_re = ctx.delta(qp, q_re)
+    ctx.sync()
+    for cfgs in ([(4, 100000, 1000), (8, 0, 0), (2, 300000, 100)], [(8, 200000, 1000)] * 3,
+                 [(3, 0, 0), (5, 50000, 1000), (8, 0, 1000)]):
+        q_re2 = ctx.quantize(cb, cfgs, out=q_re)
+        assert q_re2 is q_re
+        d_re2 = ctx.delta(qp, q_re, out=d_re)
+        assert d_re2 is d_re
+        ctx.sync()
+        q_pl = ctx.quantize(tc, cfgs)
+        d_pl = ctx.delta(qp, q_pl)
+        ctx.sync()
+        for a, b, da, db in zip(q_re, q_pl, d_re, d_pl):
+            assert (a.bits, a.sym_bits, a.n_pruned, a.n_outlier, a.n_kept) == \
+                (b.bits, b.sym_bits, b.n_pruned, b.n_outlier, b.n_kept)
+            assert (a.tau_prune, a.tau_outlier) == (b.tau_prune, b.tau_outlier)
+            assert torch.equal(a.packed, b.packed) and torch.equal(a.codebook, b.codebook)
+            assert torch.equal(a.outlier_idx, b.outlier_idx) and torch.equal(a.outlier_val, b.outlier_val)
+            assert da.delta_bits == db.delta_bits
+            words = (da.n * da.delta_bits + 63) // 64
+            assert torch.equal(da.packed[:words], db.packed[:words])
+            assert torch.equal(da.group_off, db.group_off)
