@@ -53,7 +53,7 @@ def cpu_baseline(sample, grid, eps, threads):
 # HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # bench on the full workload, scaled by the counters' readings for a plain 1 GiB device copy
 # (profiles/bench_llama7b_hbm_traffic.md); counters cannot be read from inside the process.
-MEASURED_TRAFFIC_BYTES = {"k_dscatter": 26.2e9, "k_quant": 34.6e9, "k_gather": 30.0e9}
+MEASURED_TRAFFIC_BYTES = {"k_dscatter": 26.5e9, "k_quant": 34.65e9, "k_gather": 29.95e9}
 
 
 def main():
