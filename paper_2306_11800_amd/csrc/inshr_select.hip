@@ -251,6 +251,13 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     __syncthreads();
 
     // second-level table: smallest target population whose bin total fits
+    // (exact zeros are counted, never gathered or sorted: they do not ask for bins)
+    if (tid == 0) {
+        const u32 zc = ZERO_KEY >> COARSE_SHIFT;
+        const u64 nz = st->n_zero;
+        nc[zc] = (u64)nc[zc] > nz ? (u32)(nc[zc] - nz) : 1u;
+    }
+    __syncthreads();
     u64 lo = 1, hi = n;
     while (lo < hi) {
         u64 mid = lo + ((hi - lo) >> 1);
@@ -1155,8 +1162,14 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
         __syncthreads();
         // exact zeros are counted, never gathered: they join the slot of the zero key
         if (tid == 0u && nz && binfo[zbin] != INACTIVE && B.bin_group[(size_t)t * L2_BINS + zbin] == g) {
-            u32 l = 0u;
-            while (l < n_e && ek[l] <= ZERO_KEY) l++;
+            u32 l = 0u, hi = n_e; // edges at or below the zero key (the edges are in key order)
+            while (l < hi) {
+                const u32 mid = (l + hi) >> 1;
+                if (ek[mid] <= ZERO_KEY)
+                    l = mid + 1u;
+                else
+                    hi = mid;
+            }
             s_lz = l;
         }
         if (sorted)
@@ -1185,10 +1198,20 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                     }
                     double acc = 0.0;
                     for (u32 i = i0; i < i1; i++) {
-                        while (l < n_e && pp[l] <= i) {
+                        if (l < n_e && pp[l] <= i) { // key i lies above edge l: slot l is complete
                             if (acc != 0.0 && l - w0 < (u32)SLOT_WIN) atomicAdd(&lsx[l - w0], acc);
                             acc = 0.0;
                             l++;
+                            if (l < n_e && pp[l] <= i) { // more edges at the same place (thousands,
+                                u32 b = n_e;             // when most boundaries are the zero key)
+                                while (l < b) {
+                                    const u32 mid = (l + b) >> 1;
+                                    if (pp[mid] <= i)
+                                        l = mid + 1u;
+                                    else
+                                        b = mid;
+                                }
+                            }
                         }
                         acc += (double)__uint_as_float(bits_of_key(from[i]));
                     }
