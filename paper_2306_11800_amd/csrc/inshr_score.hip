@@ -195,15 +195,26 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         u64 pc[4];
         double run_s = 0.0;
         u64 run_c = 0;
+        // keys of bins without an edge: per unit, in unit order (a thread's four slots are 32
+        // consecutive bytes of a unit's row; entries past the last slot are never used)
+        double su[4] = {0.0, 0.0, 0.0, 0.0};
+        if (4u * tid <= m) {
+#pragma unroll 4
+            for (u32 u = u0; u < u1; u++) {
+                const double *row = B.mom_sx + (size_t)t_fu_ids[u] * MAX_EDGES + 4u * tid;
+#pragma unroll
+                for (int r = 0; r < 4; r++) su[r] += row[r];
+            }
+        }
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             const u32 i = 4u * tid + r;
             double sv = 0.0;
             u64 c = 0;
             if (i <= m) {
-                // keys of bins without an edge (per unit, in unit order), then the gathered keys
-                // from the group of the slot's lower edge and from the group of its upper edge
-                for (u32 u = u0; u < u1; u++) sv += B.mom_sx[(size_t)t_fu_ids[u] * MAX_EDGES + i];
+                // then the gathered keys from the group of the slot's lower edge and from the
+                // group of its upper edge
+                sv = su[r];
                 sv += gs[i];
                 sv += gs[MAX_EDGES + i];
                 c = (u64)segc[i] + gc[i] + gc[MAX_EDGES + i];
