@@ -1,19 +1,24 @@
 // Exact thresholds and bin boundaries (Sec. 4.2-4.4) by two counting sweeps and one gathering
 // sweep over the tensors; every launch covers all tensors of a batch.
 //
-//   sweep 1  k_hist<1>     LDS histogram of key >> 17 (32768 bins), zero / negative counts,
-//                          NaN / Inf detection
+//   sweep 1  k_hist<1>     LDS histogram of key >> 17 (32768 bins), sum of squares, exact zeros
+//                          (negative and non-finite counts follow from the histogram)
 //   k_plan1                per tensor: first-level magnitude bin ("bucket") of every prune /
 //                          protect threshold rank; a key -> bin table whose bins hold about
 //                          n / 32768 elements each
 //   sweep 2  k_hist<2>     LDS histogram over the table's bins; elements of threshold buckets are
-//                          gathered
+//                          gathered into wave-private regions
 //   k_thr_select           exact thresholds and class counts from the gathered buckets
 //   k_plan2                exact rank of every boundary of every (prune, protect) pair -> its bin;
-//                          only those bins are "active"
-//   sweep 3  k_gather      elements of active bins are gathered bin by bin; sums of squares;
-//                          protected-value counts per tile
-//   k_bnd_select           exact boundary = residual-rank element of its bin
+//                          only those bins (and the bins of the class edges) are "active";
+//                          groups of consecutive active bins
+//   (k_edges, in the scoring file: order of all boundaries and class edges, slot of every bin
+//   without an edge)
+//   sweep 3  k_gather      keys of bins without an edge add to their slot's sum; keys of active
+//                          bins are gathered; protected counts per tile and their squares
+//   k_split                gathered keys -> groups of consecutive active bins
+//   k_bucket               one group per step: sort in LDS, every boundary read at its rank, counts
+//                          and sums per slot
 #include "inshr_launch.h"
 
 namespace inshr {
