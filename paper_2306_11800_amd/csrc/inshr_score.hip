@@ -169,8 +169,9 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
                                                  const u32 *__restrict__ t_fu_ids, Bufs B)
 {
     extern __shared__ u32 smem[];
-    double *S = reinterpret_cast<double *>(smem);              // [4096]
-    u64 *C = reinterpret_cast<u64 *>(smem + 2 * MAX_EDGES);    // [4096]
+    double *V = reinterpret_cast<double *>(smem);              // [4096] sum of each slot
+    u64 *C = reinterpret_cast<u64 *>(smem + 2 * MAX_EDGES);    // [4096] keys in slots 0..s
+    double *S8 = reinterpret_cast<double *>(smem + 4 * MAX_EDGES); // [MAX_PAIRS][256] sums of 8-bit bins
     __shared__ double s_qout[MAX_FRAC];
     __shared__ double s_sumsq;
 
@@ -185,15 +186,14 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     const u32 *segc = B.seg_cnt + (size_t)t * MAX_EDGES;
     const u32 *gc = B.grp_cnt + (size_t)t * 2 * MAX_EDGES;
     const double *gs = B.grp_sx + (size_t)t * 2 * MAX_EDGES;
-    // Per slot: count and sum.  They are kept as inclusive prefixes over the slots (a bin is a run
-    // of consecutive slots, so its count and sum are two differences): every thread owns four
-    // consecutive slots, the running totals of the threads before it come from a scan.
-    __shared__ double w_s[BLOCK / 64];
+    // Per slot: count and sum.  The counts are kept as inclusive prefixes over the slots (a bin is
+    // a run of consecutive slots, so its count is a difference): every thread owns four consecutive
+    // slots, the running totals of the threads before it come from a scan.  The sums are kept per
+    // slot and added bin by bin: a difference of prefix sums would lose a bin of small values next
+    // to large ones (fp64 carries 16 digits, fp32 values span 83).
     __shared__ u64 w_c[BLOCK / 64];
     {
-        double ps[4];
         u64 pc[4];
-        double run_s = 0.0;
         u64 run_c = 0;
         // keys of bins without an edge: per unit, in unit order (a thread's four slots are 32
         // consecutive bytes of a unit's row; entries past the last slot are never used)
@@ -219,38 +219,22 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
                 sv += gs[MAX_EDGES + i];
                 c = (u64)segc[i] + gc[i] + gc[MAX_EDGES + i];
             }
-            run_s += sv;
+            V[i] = sv;
             run_c += c;
-            ps[r] = run_s;
             pc[r] = run_c;
         }
-        double inc_s = run_s;
         u64 inc_c = run_c;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
-            const double a = __shfl_up(inc_s, o);
             const u64 b = __shfl_up(inc_c, o);
-            if ((int)(tid & 63u) >= o) {
-                inc_s += a;
-                inc_c += b;
-            }
+            if ((int)(tid & 63u) >= o) inc_c += b;
         }
-        if ((tid & 63u) == 63u) {
-            w_s[tid >> 6] = inc_s;
-            w_c[tid >> 6] = inc_c;
-        }
+        if ((tid & 63u) == 63u) w_c[tid >> 6] = inc_c;
         __syncthreads();
-        double base_s = inc_s - run_s;
         u64 base_c = inc_c - run_c;
-        for (u32 w = 0; w < (tid >> 6); w++) {
-            base_s += w_s[w];
-            base_c += w_c[w];
-        }
+        for (u32 w = 0; w < (tid >> 6); w++) base_c += w_c[w];
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            S[4u * tid + r] = base_s + ps[r];
-            C[4u * tid + r] = base_c + pc[r];
-        }
+        for (int r = 0; r < 4; r++) C[4u * tid + r] = base_c + pc[r];
     }
     if (tid <= n_o) {
         double s = 0.0;
@@ -266,6 +250,20 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     __syncthreads();
 
     const u16 *pe = B.pair_eidx + (size_t)t * MAX_PAIRS * EIDX_STRIDE;
+    // sums of the 8-bit bins of every pair, slot by slot; the bins for fewer bits are unions of them
+    for (u32 w = tid; w < gd->n_pairs * 256u; w += BLOCK) {
+        const u32 q = w >> 8, k = w & 255u;
+        const u16 *e = pe + q * EIDX_STRIDE;
+        // bin k covers slots idx(lo)+1 .. idx(hi) without those of the pruned gap (g_lo, g_hi]
+        const u32 i_lo = (k == 0) ? e[NB8 + 0] : e[k - 1u];
+        const u32 i_hi = (k == 255u) ? e[NB8 + 3] : e[k];
+        const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
+        double sk = 0.0;
+        for (u32 i = i_lo + 1u; i <= i_hi; i++)
+            if (i <= g_lo || i > g_hi) sk += V[i];
+        S8[w] = sk;
+    }
+    __syncthreads();
     const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
     float *cb = B.codebook + (size_t)t * n_cfg * CB_STRIDE;
     double *bt = B.bin_term + (size_t)t * n_cfg * CB_STRIDE;
@@ -283,12 +281,10 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
         // slots i_lo+1 .. i_hi without those of the pruned gap (g_lo, g_hi]
         u64 nk = C[i_hi] - C[i_lo];
-        double sk = S[i_hi] - S[i_lo];
         const u32 a = max(i_lo, g_lo), b = min(i_hi, g_hi);
-        if (a < b) {
-            nk -= C[b] - C[a];
-            sk -= S[b] - S[a];
-        }
+        if (a < b) nk -= C[b] - C[a];
+        double sk = 0.0;
+        for (u32 j = 0; j < (1u << sh); j++) sk += S8[q * 256u + (k << sh) + j];
         float c;
         if (nk)
             c = (float)(sk / (double)nk);
@@ -347,7 +343,7 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
 }
 
 constexpr int SM_EDGES = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4;
-constexpr int SM_FINAL = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4;
+constexpr int SM_FINAL = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4 + MAX_PAIRS * 256 * 8;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()
