@@ -259,8 +259,8 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         const u32 i_hi = (k == 255u) ? e[NB8 + 3] : e[k];
         const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
         double sk = 0.0;
-        for (u32 i = i_lo + 1u; i <= i_hi; i++)
-            if (i <= g_lo || i > g_hi) sk += V[i];
+        for (u32 i = i_lo + 1u; i <= min(i_hi, g_lo); i++) sk += V[i];
+        for (u32 i = max(i_lo, g_hi) + 1u; i <= i_hi; i++) sk += V[i];
         S8[w] = sk;
     }
     __syncthreads();
