@@ -142,10 +142,12 @@ __global__ __launch_bounds__(SS) void k_dgroups(const DDesc *__restrict__ dd,
 
 // The packed words of one tile's symbols go from device memory straight into LDS (no registers in
 // between, nothing waits here): every lane moves 16 bytes per instruction when the source is
-// 16-byte aligned, 4 bytes otherwise; a wave's lanes write consecutive LDS addresses.  The words are
-// complete after `s_waitcnt vmcnt(0)` and a barrier.
+// 16-byte aligned, 4 bytes otherwise; a wave's lanes write consecutive LDS addresses.  NW waves
+// share the work, the calling wave being number widx of them.  The words are complete after
+// `s_waitcnt vmcnt(0)` and a barrier.
+template <int NW>
 __device__ __forceinline__ void lds_fetch(const GLOBAL_AS unsigned long long *src, u64 e0, u32 cnt,
-                                          u32 w, u32 *dst, u32 wave)
+                                          u32 w, u32 *dst, u32 widx)
 {
     u32 lane = threadIdx.x & 63u;
     asm volatile("" : "+v"(lane)); // the addresses below are cheap: recomputing them in every tile
@@ -153,25 +155,28 @@ __device__ __forceinline__ void lds_fetch(const GLOBAL_AS unsigned long long *sr
     const GLOBAL_AS u32 *g = (const GLOBAL_AS u32 *)(src + e0 * w / 64u); // exact: e0 % 64 == 0
     LDS_AS u32 *l = (LDS_AS u32 *)dst;
     const u32 nd = 2u * ((cnt * w + 63u) >> 6); // dwords of the tile, all inside the packed array
-    // at most DTILE * 9 / 32 = 3456 dwords: two rounds of 16-byte pieces, or five of single dwords
+    constexpr u32 MAXD = DTILE * 9 / 32;        // at most 3456 dwords
+    constexpr u32 R16 = (MAXD / 4 + NW * 64 - 1) / (NW * 64), R4 = (MAXD + NW * 64 - 1) / (NW * 64);
     u32 done = 0u;
     if ((((u64)g) & 15u) == 0u) {
         const u32 n16 = nd >> 2;
 #pragma unroll
-        for (u32 it = 0; it < 2u; it++) {
-            const u32 c0 = (it * NWAVE + wave) * 64u;
+        for (u32 it = 0; it < R16; it++) {
+            const u32 c0 = (it * NW + widx) * 64u;
             if (c0 + lane < n16)
                 __builtin_amdgcn_global_load_lds(g + (c0 + lane) * 4u, l + c0 * 4u, 16, 0, 0);
         }
         done = n16 << 2;
     }
+    if (done < nd) { // (the same for the whole workgroup: nothing is left after the 16-byte pieces
+                     // of a whole tile)
 #pragma unroll
-    for (u32 it = 0; it < 5u; it++) {
-        const u32 c0 = done + (it * NWAVE + wave) * 64u;
-        if (c0 + lane < nd) __builtin_amdgcn_global_load_lds(g + (c0 + lane), l + c0, 4, 0, 0);
+        for (u32 it = 0; it < R4; it++) {
+            const u32 c0 = done + (it * NW + widx) * 64u;
+            if (c0 + lane < nd) __builtin_amdgcn_global_load_lds(g + (c0 + lane), l + c0, 4, 0, 0);
+        }
     }
 }
-static_assert(2 * NWAVE * 64 * 4 >= DTILE * 9 / 32 && 5 * NWAVE * 64 >= DTILE * 9 / 32, "rounds cover a tile");
 
 // Words of the LDS image of one tile's output: every group's run starts at the bit of its first
 // stream word that the stream position dictates, so LDS word k is stream word dbase[g] + k.  A run
@@ -375,15 +380,17 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u64 rem = d.n - lt * (u64)DTILE;
         return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     };
-    lds_fetch(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
-    lds_fetch(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc, Cw, wave);
+    lds_fetch<NWAVE>(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
+    lds_fetch<NWAVE>(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc, Cw, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the first tile's words
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
         __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
                          // before its output phase); the previous tile's output phase is over
-        if (tid < S) flush_and_commit(sh, slot, out, tid); // the previous tile's lines
+        // the previous tile's lines: by the last five waves (the first five have the scans below)
+        if (tid >= (u32)DBLOCK - 320u && tid - ((u32)DBLOCK - 320u) < S)
+            flush_and_commit(sh, slot, out, tid - ((u32)DBLOCK - 320u));
         if (!ORDERED) { // sweep 1 uses the slots
             __syncthreads();
             for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
@@ -398,9 +405,11 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         else
             rank_rows<false, ORDERED, !PERM>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg, wB);
         __syncthreads();
-        if (lt + 1 < lt1) { // the symbols are in registers: the next tile's words start travelling
-            lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
-            lds_fetch(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave);
+        // the symbols are in registers: the next tile's words start travelling, asked for by the
+        // waves that have no scan to do
+        if (lt + 1 < lt1 && wave >= 5u) {
+            lds_fetch<NWAVE - 5>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave - 5u);
+            lds_fetch<NWAVE - 5>(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave - 5u);
         }
         if (ORDERED) { // the image of the previous tile has been taken over; clear it for sweep 2
             const u32 nz = ((cnt * wB) >> 6) + 2u * S + 2u;
@@ -413,27 +422,19 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         // exclusive scans over symbols, start of every (wave, symbol)
         u32 tot = 0, nW = 0, s0 = 0, preW = 0, preE = 0;
         u64 fb = 0;
-        u32 sy = tid; // this thread's symbol
+        u32 sy = tid;  // this thread's symbol
         asm volatile("" : "+v"(sy)); // its table addresses are recomputed per tile, not kept (and
                                      // spilled: a reload would wait for the words in flight)
-        if (tid < S) {
-            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
-            const u32 pos = sh.gb[sy]; // after the previous tile's run
-            fb = (u64)pos * wB;
-            s0 = (u32)(fb & 63u);
-            nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
-        }
         if (tid < 320u) { // waves 0..4 hold the 258 symbols
-            u32 incW = nW, incE = tot;
+            if (tid < S) {
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                u32 v = __shfl_up(incW, o);
-                u32 e = PERM ? __shfl_up(incE, o) : 0u;
-                if ((int)lane >= o) {
-                    incW += v;
-                    incE += e;
-                }
+                for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
+                const u32 pos = sh.gb[sy]; // after the previous tile's run
+                fb = (u64)pos * wB;
+                s0 = (u32)(fb & 63u);
+                nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
             }
+            const u32 incW = wave_incl_scan(nW), incE = PERM ? wave_incl_scan(tot) : 0u;
             preW = incW - nW;
             preE = incE - tot;
             if (lane == 63u) {
@@ -461,13 +462,20 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
             if (PERM) lbase[sy] = es;
             u32 bitpos = ws * 64u + s0;
-            for (int wv = 0; wv < NWAVE; wv++) {
-                const u32 c = sh.wst[wv * srow + sy];
-                sh.wst[wv * srow + sy] = bitpos;
-                bitpos += c * wB;
-                if (PERM) {
-                    wel[wv * srow + sy] = es;
-                    es += c;
+            static_assert(NWAVE % 4 == 0, "the waves are taken four at a time");
+#pragma unroll
+            for (int w0 = 0; w0 < NWAVE; w0 += 4) { // four counts are read together, then replaced
+                u32 c4[4];
+#pragma unroll
+                for (int j = 0; j < 4; j++) c4[j] = sh.wst[(w0 + j) * srow + sy];
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    sh.wst[(w0 + j) * srow + sy] = bitpos;
+                    bitpos += c4[j] * wB;
+                    if (PERM) {
+                        wel[(w0 + j) * srow + sy] = es;
+                        es += c4[j];
+                    }
                 }
             }
         }
@@ -667,7 +675,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
         const u64 rem = d.n - lt * (u64)DTILE;
         return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     };
-    lds_fetch(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
+    lds_fetch<NWAVE>(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
@@ -685,7 +693,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
         else
             rank_rows<false, ORDERED>(Pw, Pw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wp, hot, reg);
         __syncthreads();
-        if (lt + 1 < lt1) lds_fetch(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
+        if (lt + 1 < lt1) lds_fetch<NWAVE>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
         {
             const u32 ndc = 2u * ((cnt * wc + 63u) >> 6) + 2u;
             u32 k0 = tid;
