@@ -289,33 +289,31 @@ __device__ __forceinline__ void rank_rows(const u32 *P, const u32 *C, u32 *wrow,
     if (ORDERED && lane == 0u) wrow[hot] = hot_seen;
 }
 
-// After a tile's output phase, one thread per group: the words of the line that the tile completed
-// and that earlier tiles had buffered are stored; then the words of the group's open line that came
-// from this tile's image (the complete ones of a line that is the chunk's own, and the partial last
-// word) move into the group's line buffer.  Nothing else touches the buffers or the image meanwhile.
+// After a tile's output phase, one thread per (group, word j of a line): word j of the line that
+// the tile completed, if earlier tiles had buffered it, is stored; then word j of the group's open
+// line, if it came from this tile's image (a complete word of a line that is the chunk's own, or the
+// partial last word), moves into the group's line buffer.  A thread touches no other thread's
+// buffer word, and nothing else touches the buffers or the image meanwhile.
 __device__ __forceinline__ void flush_and_commit(ScatterShared &sh, const unsigned long long *image,
-                                                 GLOBAL_AS unsigned long long *out, u32 g)
+                                                 GLOBAL_AS unsigned long long *out, u32 item)
 {
-    asm volatile("" : "+v"(g)); // the group's addresses are recomputed here, not kept across the tile
-                                // loop in spilled registers (a reload would wait for the stores)
+    asm volatile("" : "+v"(item)); // the item's addresses are recomputed here, not kept across the
+                                   // tile loop in spilled registers (a reload would wait for stores)
+    const u32 g = item / LINE, j = item % LINE;
     const u32 meta = sh.gtl[g];
     if (!(meta >> 31)) return; // the group had no element in the tile
     const u32 Wf = sh.gWf[g], We = sh.gWe[g], tail = meta & 63u;
-    const u32 own = sh.fo[g] & 0x7fffffffu, ws = sh.wstart[g];
+    const u32 own = sh.fo[g] & 0x7fffffffu;
     const u32 Lf = Wf / LINE, Le = We / LINE;
-    if (Lf * LINE >= own && Lf < Le)
-        for (u32 j = 0; j < (Wf & (LINE - 1u)); j++) out[Lf * LINE + j] = sh.lw[g][j];
-#pragma unroll
-    for (u32 j = 0; j < (u32)LINE; j++) {
-        const u32 Wt = Le * LINE + j;         // word j of the line that is open after the tile
-        if (Wt > We || Wt < Wf) continue;     // not written yet / buffered by an earlier tile
-        unsigned long long v = 0ull;
-        if (Wt < We || tail) {
-            v = image[ws + (Wt - Wf)];
-            if (Wt == Wf) v |= sh.lw[g][j];   // bits of earlier tiles in the run's first word
-        }
-        sh.lw[g][j] = v;
+    if (Lf * LINE >= own && Lf < Le && j < (Wf & (LINE - 1u))) out[Lf * LINE + j] = sh.lw[g][j];
+    const u32 Wt = Le * LINE + j;      // word j of the line that is open after the tile
+    if (Wt > We || Wt < Wf) return;    // not written yet / buffered by an earlier tile
+    unsigned long long v = 0ull;
+    if (Wt < We || tail) {
+        v = image[sh.wstart[g] + (Wt - Wf)];
+        if (Wt == Wf) v |= sh.lw[g][j]; // bits of earlier tiles in the run's first word
     }
+    sh.lw[g][j] = v;
 }
 
 // ORDERED: same-address LDS atomics with return are served in ascending lane order on this device
@@ -388,9 +386,10 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u32 cnt = tile_cnt(lt);
         __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
                          // before its output phase); the previous tile's output phase is over
-        // the previous tile's lines: by the last five waves (the first five have the scans below)
-        if (tid >= (u32)DBLOCK - 320u && tid - ((u32)DBLOCK - 320u) < S)
-            flush_and_commit(sh, slot, out, tid - ((u32)DBLOCK - 320u));
+        // the previous tile's lines (the second round falls to the last waves: the first five have
+        // the scans below)
+        if (tid < S * LINE) flush_and_commit(sh, slot, out, tid);
+        if (tid >= (u32)DBLOCK - 320u && tid + 320u < S * LINE) flush_and_commit(sh, slot, out, tid + 320u);
         if (!ORDERED) { // sweep 1 uses the slots
             __syncthreads();
             for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
@@ -405,12 +404,6 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         else
             rank_rows<false, ORDERED, !PERM>(Pw, Cw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wc, hot, reg, wB);
         __syncthreads();
-        // the symbols are in registers: the next tile's words start travelling, asked for by the
-        // waves that have no scan to do
-        if (lt + 1 < lt1 && wave >= 5u) {
-            lds_fetch<NWAVE - 5>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave - 5u);
-            lds_fetch<NWAVE - 5>(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave - 5u);
-        }
         if (ORDERED) { // the image of the previous tile has been taken over; clear it for sweep 2
             const u32 nz = ((cnt * wB) >> 6) + 2u * S + 2u;
             u32 k0 = tid;
@@ -443,11 +436,19 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
             }
         }
         __syncthreads();
+        // the symbols are in registers: the next tile's words start travelling, asked for by the
+        // waves that have no scan to do
+        if (lt + 1 < lt1 && wave >= 5u) {
+            lds_fetch<NWAVE - 5>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave - 5u);
+            lds_fetch<NWAVE - 5>(gptr(d.cur), e0 + DTILE, tile_cnt(lt + 1), wc, Cw, wave - 5u);
+        }
         if (tid < S) {
             u32 ws = preW, es = preE;
-            for (u32 w2 = 0; w2 < wave; w2++) {
-                ws += sh.wtot[w2];
-                es += sh.etot[w2];
+#pragma unroll
+            for (u32 w2 = 0; w2 < 4u; w2++) { // (all read together, the needed ones added)
+                const u32 a = sh.wtot[w2], b = PERM ? sh.etot[w2] : 0u;
+                ws += w2 < wave ? a : 0u;
+                es += w2 < wave ? b : 0u;
             }
             const u64 fe = fb + (u64)tot * wB;
             sh.gb[sy] += tot;
@@ -537,8 +538,9 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         }
     }
     __syncthreads();
+    for (u32 i = tid; i < S * LINE; i += DBLOCK) flush_and_commit(sh, slot, out, i);
+    __syncthreads();
     if (tid < S) { // what the chunk leaves behind: the words of an open line, the last partial word
-        flush_and_commit(sh, slot, out, tid);
         const RunWords r = run_words(sh.gb[tid], 0u, wB);
         const u32 Le = r.We / LINE, wl = r.We & (LINE - 1u);
         if (Le * LINE >= (sh.fo[tid] & 0x7fffffffu))
