@@ -386,10 +386,9 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         const u32 cnt = tile_cnt(lt);
         __syncthreads(); // all shares of the tile's words are in LDS (every wave waited for its own
                          // before its output phase); the previous tile's output phase is over
-        // the previous tile's lines (the second round falls to the last waves: the first five have
-        // the scans below)
+        // the previous tile's lines
         if (tid < S * LINE) flush_and_commit(sh, slot, out, tid);
-        if (tid >= (u32)DBLOCK - 320u && tid + 320u < S * LINE) flush_and_commit(sh, slot, out, tid + 320u);
+        if (tid + (u32)DBLOCK < S * LINE) flush_and_commit(sh, slot, out, tid + (u32)DBLOCK);
         if (!ORDERED) { // sweep 1 uses the slots
             __syncthreads();
             for (u32 k = tid; k < (u32)(NWAVE * SS); k += DBLOCK) slot[k] = 0ull;
