@@ -96,6 +96,23 @@ __host__ __device__ __forceinline__ u32 l2_bin(u32 key, u32 entry)
     return ((entry >> 5) & 0x7fffu) + ((key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u));
 #endif
 }
+// The same table entry for kernels that index 16-bit tables by the bin: base << 6 | depth, so that
+// entry >> 5 is the byte offset of the first bin and no mask is needed.
+__host__ __device__ __forceinline__ u32 entry_for_u16(u32 entry)
+{
+    return (((entry >> 5) & 0x7fffu) << 6) | (entry & 31u);
+}
+__device__ __forceinline__ u32 lookup_u16(const u16 *table, u32 key, u32 entry16)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // bit-field extract takes offset and width from the low five bits of its operands
+    const u32 sub = __builtin_amdgcn_ubfe(key, (u32)COARSE_SHIFT - entry16, entry16);
+#else
+    const u32 d = entry16 & 31u;
+    const u32 sub = (key >> (COARSE_SHIFT - d)) & ((1u << d) - 1u);
+#endif
+    return *reinterpret_cast<const u16 *>(reinterpret_cast<const char *>(table) + (entry16 >> 5) + sub * 2u);
+}
 __host__ __device__ __forceinline__ u32 bucket_flag(u32 l1_bin) { return 0x80000000u >> (l1_bin & 7u); }
 __host__ __device__ __forceinline__ bool in_threshold_bucket(u32 key, u32 entry)
 {

@@ -99,7 +99,7 @@ __device__ __forceinline__ void classify_tile(const float (&v)[16], u32 mask, co
             e[c] = T[key[c] >> COARSE_SHIFT];
         }
 #pragma unroll
-        for (int c = 0; c < 4; c++) e[c] = symt[l2_bin(key[c], e[c])];
+        for (int c = 0; c < 4; c++) e[c] = lookup_u16(symt, key[c], e[c]);
         u32 lo32 = 0u, s3 = 0u;
 #pragma unroll
         for (int c = 0; c < 4; c++) {
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
         const u32 n_bnd = K - 1u, n_bp = n_bnd + 4u;
         __syncthreads();
-        for (u32 i = tid; i < (u32)COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+        for (u32 i = tid; i < (u32)COARSE; i += BLOCK) T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);
         if (tid < n_bnd) qt.raw[tid] = tk[((tid + 1u) << sh) - 1u];
         if (tid < 4u) qt.raw[n_bnd + tid] = class_edge_key(tid, tau_p, tau_o);
         __syncthreads();
@@ -227,12 +227,12 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             u32 lo = 0u, hi = COARSE - 1u; // key prefix of the bin: last one that starts at or below it
             while (lo < hi) {
                 const u32 mid = (lo + hi + 1u) >> 1;
-                if (((T[mid] >> 5) & 0x7fffu) <= b)
+                if ((T[mid] >> 6) <= b)
                     lo = mid;
                 else
                     hi = mid - 1u;
             }
-            const u32 e = T[lo], dd = e & 31u, sub = b - ((e >> 5) & 0x7fffu);
+            const u32 e = T[lo], dd = e & 31u, sub = b - (e >> 6);
             const u32 first = (lo << COARSE_SHIFT) | (sub << (COARSE_SHIFT - dd));
             const u32 last = first + ((1u << (COARSE_SHIFT - dd)) - 1u);
             u32 below = 0u, upto = 0u; // breakpoints < first, breakpoints <= last

@@ -625,7 +625,7 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
         amax = fmaxf(amax, fabsf(xc));
     }
 #pragma unroll
-    for (int i = 0; i < 16; i++) slot[i] = SEG[l2_bin(key[i], slot[i])];
+    for (int i = 0; i < 16; i++) slot[i] = lookup_u16(SEG, key[i], slot[i]);
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         const bool valid = FULL || ((mask >> i) & 1u);
@@ -635,8 +635,8 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
         u64 cm = __ballot(key[i] != ZERO_KEY) & __ballot(slot[i] == 0xFFFFu);
         if (!FULL) cm &= __ballot(valid);
         if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (double)v[i]);
-        if (cand)
-            gdst[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, gathered))] = key[i];
+        if (cand) // (the wave's cursor is a scalar: it goes into the address, not into the rank)
+            (gdst + gathered)[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, 0u))] = key[i];
         gathered += (u32)__popcll(cm);
     }
     // the bits of a non-negative float order like its magnitude image
@@ -696,7 +696,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
             u32 *seg32 = reinterpret_cast<u32 *>(SEG);
             for (u32 i = tid; i < (u32)L2_BINS / 2; i += BLOCK) seg32[i] = gseg[i];
         }
-        for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
+        for (int i = tid; i < COARSE; i += BLOCK) T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);
         for (u32 i = tid; i < n_slots; i += BLOCK) sx[i] = 0.0;
         if (tid < MAX_FRAC) s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
         __syncthreads();
