@@ -1252,15 +1252,18 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
     }
 }
 
-// list of all (tensor, group) pairs of the batch
-__global__ void k_group_list(int nT, Bufs B, u32 *grp_list, u32 *n_grp_total)
+// list of all (tensor, group) pairs of the batch (one workgroup per tensor; the order of the list
+// is the order in which the group sort takes them and does not matter)
+__global__ __launch_bounds__(256) void k_group_list(int nT, Bufs B, u32 *grp_list, u32 *n_grp_total)
 {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= nT) return;
+    __shared__ u32 s_at;
+    const int t = blockIdx.x;
     const u32 G = B.ts[t].n_groups;
     if (G == 0u) return;
-    const u32 at = atomicAdd(n_grp_total, G);
-    for (u32 g = 0; g < G; g++) grp_list[at + g] = ((u32)t << 13) | g;
+    if (threadIdx.x == 0) s_at = atomicAdd(n_grp_total, G);
+    __syncthreads();
+    const u32 at = s_at;
+    for (u32 g = threadIdx.x; g < G; g += 256u) grp_list[at + g] = ((u32)t << 13) | g;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1297,7 +1300,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     if ((e = launch_edges(bt, s))) return e;
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
-    PROF("k_group_list", s, k_group_list<<<(bt.nT + 255) / 256, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
+    PROF("k_group_list", s, k_group_list<<<bt.nT, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));
     PROF("k_split", s, k_split<<<dim3(bt.n_units, SPLIT_PARTS), BLOCK, SM_SPLIT, s>>>(bt.td, bt.fu_tensor, B));
     if (bt.lds_ordered)
         PROF("k_bucket", s, k_bucket<true><<<bt.n_bucket_blocks, BB, SM_BUCKET, s>>>(bt.td, bt.nT, bt.grp_list, bt.n_grp_total, B));
