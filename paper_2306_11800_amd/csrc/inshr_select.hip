@@ -1051,27 +1051,25 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                 __syncthreads();
                 // start of every (digit, wave) run: digits in order, waves in order inside a digit
                 u32 tot = 0u, excl = 0u;
+                u32 cw[BB / 64]; // this digit's count in every wave
                 if (tid < 256u) {
 #pragma unroll
-                    for (int w = 0; w < BB / 64; w++) tot += wcount[w * 256 + tid];
-                    u32 inc = tot;
+                    for (int w = 0; w < BB / 64; w++) cw[w] = wcount[w * 256 + tid];
 #pragma unroll
-                    for (int o = 1; o < 64; o <<= 1) {
-                        const u32 v = __shfl_up(inc, o);
-                        if ((int)lane >= o) inc += v;
-                    }
+                    for (int w = 0; w < BB / 64; w++) tot += cw[w];
+                    const u32 inc = wave_incl_scan(tot);
                     excl = inc - tot;
                     if (lane == 63u) wsum[wave] = inc;
                 }
                 __syncthreads();
                 if (tid < 256u) {
                     u32 run = excl;
-                    for (u32 w = 0; w < wave; w++) run += wsum[w];
+#pragma unroll
+                    for (u32 w = 0; w < 3u; w++) run += w < wave ? wsum[w] : 0u; // (waves 0..3 scan)
 #pragma unroll
                     for (int w = 0; w < BB / 64; w++) {
-                        const u32 c = wcount[w * 256 + tid];
                         wcount[w * 256 + tid] = run;
-                        run += c;
+                        run += cw[w];
                     }
                 }
                 __syncthreads();
