@@ -183,6 +183,34 @@ typedef struct {
 int inshr_reconstruct(inshr_ctx *ctx, const inshr_codes *prev, const inshr_delta_out *delta,
                       inshr_codes_out *cur, uint32_t n_tensors);
 
+/* ---- entropy stage of the delta (host memory only, outside the timed path) ------------------- */
+
+typedef struct {
+    uint64_t n_tokens;      /* run-length tokens of all groups                                    */
+    uint64_t table_bytes;   /* group headers and code tables                                      */
+    uint64_t payload_bytes; /* Huffman-coded tokens                                               */
+} inshr_entropy_stats;
+
+/* Sec. 6, "Encoding Delta": every group of the delta stream is run-length encoded (a run of r equal
+ * values v becomes the token -v, followed by +r when r > 1) and Huffman coded with a code of its
+ * own.  Input, all host memory: either `packed` (the stream inshr_delta wrote, copied to the host:
+ * delta_bits-bit fields) or `values` (one uint16 per delta value), the other NULL; group_off with
+ * n_groups + 1 entries (group g = values [group_off[g], group_off[g+1]); group_off[0] = 0,
+ * group_off[n_groups] = n).  One group spanning everything encodes a stream without regrouping.
+ * out (host, out_cap bytes) receives the container; *out_bytes its size.  With out == NULL or
+ * out_cap too small the call returns INSHR_E_CAPACITY and *out_bytes is the size needed.
+ * stats may be NULL. */
+int inshr_entropy_encode(const uint64_t *packed, const uint16_t *values, uint64_t n,
+                         uint32_t delta_bits, const uint64_t *group_off, uint32_t n_groups,
+                         uint8_t *out, uint64_t out_cap, uint64_t *out_bytes,
+                         inshr_entropy_stats *stats);
+
+/* Inverse: the container back into `packed` (ceil(n * delta_bits / 64) words) or `values` (n
+ * entries), the other NULL, and group_off (n_groups + 1 entries, may be NULL).  n, delta_bits and
+ * n_groups must be those of the encoder.  INSHR_E_SHAPE: the container is malformed. */
+int inshr_entropy_decode(const uint8_t *in, uint64_t in_bytes, uint64_t n, uint32_t delta_bits,
+                         uint32_t n_groups, uint64_t *packed, uint16_t *values, uint64_t *group_off);
+
 /* Per-kernel timing for benchmarks (not part of the method): when enabled, every kernel launch of
  * this process is bracketed by HIP events on its stream.  inshr_profile(ctx, 1) clears the totals
  * and starts recording, inshr_profile(ctx, 0) stops.  inshr_profile_read synchronises the stream

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
            "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
+           "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
 
 INSHR_REUSE_SEARCH = 1
@@ -65,6 +66,10 @@ class CDequantIn(C.Structure):
                 ("bits", C.c_uint8)]
 
 
+class CEntropyStats(C.Structure):
+    _fields_ = [("n_tokens", C.c_uint64), ("table_bytes", C.c_uint64), ("payload_bytes", C.c_uint64)]
+
+
 class CCodesOut(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("bits", C.c_uint8)]
 
@@ -102,6 +107,11 @@ def load_library() -> C.CDLL:
                                      C.c_uint32]
     lib.inshr_reconstruct.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CDeltaOut),
                                       C.POINTER(CCodesOut), C.c_uint32]
+    lib.inshr_entropy_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
+                                         C.c_uint32, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64),
+                                         C.POINTER(CEntropyStats)]
+    lib.inshr_entropy_decode.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
     lib.inshr_profile.argtypes = [C.c_void_p, C.c_int]
     lib.inshr_profile_read.argtypes = [C.c_void_p, C.POINTER(CKernelTime), C.c_uint32,
                                        C.POINTER(C.c_uint32)]
@@ -424,3 +434,48 @@ class Context:
             res.append(w)
         self._check(self.lib.inshr_reconstruct(self.h, pa, da, ca, nT))
         return res
+
+
+# -- entropy stage of the delta: host memory, no device involved ------------------------------------
+def _host_ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def entropy_encode(group_off, delta_bits: int, packed=None, values=None):
+    """Container bytes (numpy uint8) and (n_tokens, table_bytes, payload_bytes) for a delta stream in
+    host memory: `packed` (numpy uint64 words as inshr_delta wrote them) or `values` (numpy uint16)."""
+    import numpy as np
+    lib = load_library()
+    group_off = np.ascontiguousarray(group_off, dtype=np.uint64)
+    n, n_groups = int(group_off[-1]), group_off.size - 1
+    if packed is not None:
+        packed = np.ascontiguousarray(packed, dtype=np.uint64)
+    if values is not None:
+        values = np.ascontiguousarray(values, dtype=np.uint16)
+    stats, size = CEntropyStats(), C.c_uint64()
+    out = np.empty(max(64, n // 4), dtype=np.uint8)
+    for _ in range(2):
+        rc = lib.inshr_entropy_encode(_host_ptr(packed), _host_ptr(values), n, delta_bits,
+                                      _host_ptr(group_off), n_groups, _host_ptr(out), out.size,
+                                      C.byref(size), C.byref(stats))
+        if rc != -4:
+            break
+        out = np.empty(size.value, dtype=np.uint8)
+    if rc:
+        raise InshrError(rc, lib.inshr_strerror(rc).decode())
+    return out[:size.value], (stats.n_tokens, stats.table_bytes, stats.payload_bytes)
+
+
+def entropy_decode(data, n: int, delta_bits: int, n_groups: int, as_values: bool = False):
+    """(stream, group_off): the stream as packed uint64 words, or as uint16 values."""
+    import numpy as np
+    lib = load_library()
+    data = np.ascontiguousarray(data, dtype=np.uint8)
+    goff = np.empty(n_groups + 1, dtype=np.uint64)
+    packed = None if as_values else np.empty((n * delta_bits + 63) // 64, dtype=np.uint64)
+    values = np.empty(n, dtype=np.uint16) if as_values else None
+    rc = lib.inshr_entropy_decode(_host_ptr(data), data.size, n, delta_bits, n_groups,
+                                  _host_ptr(packed), _host_ptr(values), _host_ptr(goff))
+    if rc:
+        raise InshrError(rc, lib.inshr_strerror(rc).decode())
+    return (values if as_values else packed), goff
