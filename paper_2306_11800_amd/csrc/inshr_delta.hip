@@ -694,7 +694,6 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
         else
             rank_rows<false, ORDERED>(Pw, Pw, wrow, slot + wave * SS, ebase, cnt, S, Bm, wp, wp, hot, reg);
         __syncthreads();
-        if (lt + 1 < lt1) lds_fetch<NWAVE>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave);
         {
             const u32 ndc = 2u * ((cnt * wc + 63u) >> 6) + 2u;
             u32 k0 = tid;
@@ -707,36 +706,42 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
         u64 fb = 0;
         u32 sy = tid;
         asm volatile("" : "+v"(sy));
-        if (tid < S) {
-            for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
-            fb = (u64)sh.gb[sy] * wB;
-            s0 = (u32)(fb & 63u);
-            nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
-        }
-        if (tid < 320u) {
-            u32 incW = nW;
+        if (tid < 320u) { // waves 0..4 hold the 258 symbols
+            if (tid < S) {
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                u32 v = __shfl_up(incW, o);
-                if ((int)lane >= o) incW += v;
+                for (int wv = 0; wv < NWAVE; wv++) tot += sh.wst[wv * srow + sy];
+                fb = (u64)sh.gb[sy] * wB;
+                s0 = (u32)(fb & 63u);
+                nW = tot ? (s0 + tot * wB + 63u) >> 6 : 0u;
             }
+            const u32 incW = wave_incl_scan(nW);
             preW = incW - nW;
             if (lane == 63u) sh.wtot[wave] = incW;
         }
         __syncthreads();
+        // the next tile's previous symbols start travelling, asked for by the waves without a scan
+        if (lt + 1 < lt1 && wave >= 5u)
+            lds_fetch<NWAVE - 5>(gptr(d.prev), e0 + DTILE, tile_cnt(lt + 1), wp, Pw, wave - 5u);
         if (tid < S) {
             u32 ws = preW;
-            for (u32 w2 = 0; w2 < wave; w2++) ws += sh.wtot[w2];
+#pragma unroll
+            for (u32 w2 = 0; w2 < 4u; w2++) ws += w2 < wave ? sh.wtot[w2] : 0u;
             sh.gb[sy] += tot;
             sh.gWf[sy] = (u32)(fb >> 6);
             sh.wstart[sy] = ws;
             if (tid == S - 1u) sh.wstart[S] = ws + nW;
             for (u32 k = (ws + 7u) & ~7u; k < ws + nW; k += 8u) sh.cidx[k >> 3] = (u16)tid;
             u32 bitpos = ws * 64u + s0;
-            for (int wv = 0; wv < NWAVE; wv++) {
-                const u32 c = sh.wst[wv * srow + sy];
-                sh.wst[wv * srow + sy] = bitpos;
-                bitpos += c * wB;
+#pragma unroll
+            for (int w0 = 0; w0 < NWAVE; w0 += 4) { // four counts are read together, then replaced
+                u32 c4[4];
+#pragma unroll
+                for (int j = 0; j < 4; j++) c4[j] = sh.wst[(w0 + j) * srow + sy];
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    sh.wst[(w0 + j) * srow + sy] = bitpos;
+                    bitpos += c4[j] * wB;
+                }
             }
         }
         __syncthreads();
