@@ -14,7 +14,9 @@
  *                   bit-packed symbols + codebook + protected-value list.
  *   inshr_delta     Delta Encoder (Sec. 6): cyclic difference of symbols against the previous
  *                   checkpoint, regrouped by the previous checkpoint's symbol (Algorithm 5).
- * and their inverses for the restore side: inshr_reconstruct (Algorithm 6) and inshr_dequantize.
+ * and their inverses for the restore side: inshr_reconstruct (Algorithm 6) and inshr_dequantize;
+ * inshr_quantize_sketch is the Quantizer with the paper's own bins (log-space sketch, Algorithm 1,
+ * and weighted K-Means on its buckets, Algorithms 2 and 3).
  *
  * Conventions
  *   - Every function returns 0 on success or a negative INSHR_E_* code; nothing aborts or throws.
@@ -182,6 +184,39 @@ typedef struct {
  * a result above K_cur + 1 (the stream does not belong to these codes). */
 int inshr_reconstruct(inshr_ctx *ctx, const inshr_codes *prev, const inshr_delta_out *delta,
                       inshr_codes_out *cur, uint32_t n_tensors);
+
+/* ---- the paper's own boundary rule: sketch + weighted K-Means --------------------------------- */
+
+typedef struct {
+    double alpha;           /* relative error bound of the sketch, 0.01 <= alpha <= 0.5 (Sec. 4.3)  */
+    double sigma;           /* weight of the frequency term of the sample weights, 0..1 (Sec. 4.4)  */
+    uint32_t max_iter;      /* most Lloyd rounds after the K-Means++ start                          */
+    const double *uniforms; /* host [n_tensors * 256]: the random numbers in [0, 1) of the draws;   */
+                            /* draw r of tensors[t] uses uniforms[t * 256 + r]                      */
+} inshr_sketch_params;
+
+typedef struct {
+    uint32_t n_buckets; /* non-empty sketch buckets of the quantized values */
+    uint32_t rounds;    /* Lloyd rounds that changed the centres            */
+} inshr_sketch_info;
+
+/* inshr_quantize with the bins of Sec. 4.3-4.4 instead of equal-frequency bins: the values that
+ * are neither pruned nor protected (same exact thresholds as inshr_quantize) are counted per sketch
+ * bucket (sign, ceil(log_gamma |x|)), gamma = (1 + alpha) / (1 - alpha) (Algorithm 1, no bucket
+ * merging; exact zeros form a bucket of their own); a bucket stands for 2 gamma^i / (gamma + 1);
+ * the buckets are clustered into K = 2^bits clusters by K-Means with sample weights
+ * sigma * C / max C + (1 - sigma) * |X| / max |X| (Algorithm 2), started by weighted K-Means++
+ * (Algorithm 3: squared distances; a draw with number u takes the first bucket whose running sum
+ * of probabilities exceeds u times their total; when all remaining distances are zero the last
+ * centre is repeated) and iterated until the memberships repeat or max_iter rounds are done.  The
+ * codebook is the centres in fp32, ascending; a value takes the upper of two neighbouring centres
+ * when it lies strictly above their midpoint.  out[i].boundaries receives the smallest fp32 number
+ * above each midpoint.  All arithmetic of the clustering is fp64.  info (host, n_tensors entries)
+ * may be NULL.  Everything else as inshr_quantize without INSHR_REUSE_SEARCH; the state of an
+ * earlier inshr_search on the context is replaced. */
+int inshr_quantize_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
+                          const inshr_sketch_params *params, inshr_quantized *out,
+                          inshr_sketch_info *info, uint32_t n_tensors);
 
 /* ---- entropy stage of the delta (host memory only, outside the timed path) ------------------- */
 

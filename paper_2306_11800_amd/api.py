@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_quantize_sketch",
            "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
@@ -44,6 +45,15 @@ class CQuantized(C.Structure):
                 ("outlier_cap", C.c_uint64), ("n_pruned", C.c_uint64), ("n_outlier", C.c_uint64),
                 ("n_kept", C.c_uint64), ("sym_bits", C.c_uint32), ("tau_prune", C.c_float),
                 ("tau_outlier", C.c_float)]
+
+
+class CSketchParams(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("sigma", C.c_double), ("max_iter", C.c_uint32),
+                ("uniforms", C.c_void_p)]
+
+
+class CSketchInfo(C.Structure):
+    _fields_ = [("n_buckets", C.c_uint32), ("rounds", C.c_uint32)]
 
 
 class CCodes(C.Structure):
@@ -100,6 +110,9 @@ def load_library() -> C.CDLL:
                                          C.POINTER(C.c_uint64)]
     lib.inshr_quantize.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
                                    C.POINTER(CQuantized), C.c_uint32, C.c_uint32]
+    lib.inshr_quantize_sketch.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
+                                          C.POINTER(CSketchParams), C.POINTER(CQuantized),
+                                          C.POINTER(CSketchInfo), C.c_uint32]
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
@@ -326,6 +339,41 @@ class Context:
         res._sizes = tuple(q.n for q in res)
         self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, flags))
         return res
+
+    # -- inshr_quantize_sketch -------------------------------------------------------------
+    def quantize_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, alpha: float = 0.01,
+                        sigma: float = 0.2, max_iter: int = 100):
+        """uniforms: numpy float64 array [len(tensors), 256] of numbers in [0, 1).  Returns
+        (list of Quantized, list of (n_buckets, rounds))."""
+        import numpy as np
+        nT = len(tensors)
+        ta = _tensor_array(tensors)
+        ca = _config_array(cfgs)
+        u = np.ascontiguousarray(uniforms, dtype=np.float64)
+        if u.shape != (nT, 256):
+            raise ValueError("uniforms must have shape [len(tensors), 256]")
+        qa = (CQuantized * nT)()
+        res = QuantizedBatch()
+        for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
+            n = t.numel()
+            words, cap = self._bound(n, ca[i], cfg)
+            e = qa[i]
+            q = Quantized(n, int(cfg[0]), (
+                torch.empty(words, dtype=torch.int64, device=t.device),
+                torch.empty(256, dtype=torch.float32, device=t.device),
+                torch.empty(255, dtype=torch.float32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa)
+            e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
+            e.packed_words = q._bufs[0].numel()
+            e.outlier_cap = q._bufs[3].numel()
+            res.append(q)
+        res._qa = qa
+        res._sizes = tuple(q.n for q in res)
+        par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
+        info = (CSketchInfo * nT)()
+        self._check(self.lib.inshr_quantize_sketch(self.h, ta, ca, C.byref(par), qa, info, nT))
+        return res, [(int(i.n_buckets), int(i.rounds)) for i in info]
 
     def _bound(self, n, ccfg, cfg):
         key = (n, int(cfg[0]), int(cfg[1]), int(cfg[2]))

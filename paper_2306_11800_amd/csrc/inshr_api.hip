@@ -2,8 +2,10 @@
 // kernel sequencing.  No arithmetic of the method runs here.
 #include "../../include/inshr.h"
 #include "inshr_launch.h"
+#include "inshr_sketch.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <string>
@@ -36,6 +38,7 @@ struct inshr_ctx {
 
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
     DevBuf aux_mem;    // quantize descriptors, delta scratch
+    DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
     HostBuf h_up;      // staging for descriptor uploads
     HostBuf h_down;    // staging for result downloads
 
@@ -472,6 +475,7 @@ void inshr_destroy(inshr_ctx *c)
     (void)hipStreamSynchronize(c->stream);
     if (c->search_mem.p) (void)hipFree(c->search_mem.p);
     if (c->aux_mem.p) (void)hipFree(c->aux_mem.p);
+    if (c->sketch_mem.p) (void)hipFree(c->sketch_mem.p);
     if (c->h_up.p) (void)hipHostFree(c->h_up.p);
     if (c->h_down.p) (void)hipHostFree(c->h_down.p);
     delete c;
@@ -565,8 +569,11 @@ int inshr_quantize_bound(uint64_t n, const inshr_config *cfg, uint64_t *packed_w
 }
 
 static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quantized *out,
-                               const uint32_t *which, uint32_t n_sel)
+                               const uint32_t *which, uint32_t n_sel, const u32 *alt_key = nullptr,
+                               const float *alt_cb = nullptr)
 {
+    // alt_key / alt_cb: device arrays with 256 entries per tensor of the batch that replace the
+    // search's boundaries and centres
     // which[k] = position in the search batch of the k-th tensor to quantize (cfg / out indexed by k)
     const uint32_t nT = (uint32_t)c->batch.nT;
     std::vector<QDesc> qd(nT);
@@ -591,6 +598,8 @@ static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quan
         qd[t].out_cap = out[k].outlier_cap;
         qd[t].cfg = gi;
         qd[t].tslot = t;
+        qd[t].alt_key = alt_key ? alt_key + (size_t)t * 256 : nullptr;
+        qd[t].alt_cb = alt_cb ? alt_cb + (size_t)t * 256 : nullptr;
     }
     Carver cv;
     const size_t o_qd = cv.take(sizeof(QDesc) * nT);
@@ -673,6 +682,171 @@ int inshr_quantize(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config
         }
         rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), (uint32_t)sub.size());
         for (size_t k = 0; k < sub.size(); k++) out[idx[k]] = subout[k];
+        if (rc) return rc;
+    }
+    return INSHR_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// sketch + weighted K-Means boundaries
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct SketchTables {
+    std::vector<u32> cell, tops;
+    std::vector<double> rep;
+};
+
+// Tables of the bucket law ceil(log_gamma |x|): tops[b] = magnitude image of the largest fp32
+// number <= gamma^(i_lo + b) (extended precision; a value x lies in the first bucket whose top
+// reaches it), rep[b] = the bucket's value, cell[c] = first bucket and its top for the magnitudes
+// c << 17 .. (c << 17) + 2^17 - 1.
+int build_sketch_tables(double alpha, SketchTables &T)
+{
+    if (!(alpha >= 0.01 && alpha <= 0.5)) return INSHR_E_CONFIG;
+    const double gamma = (1.0 + alpha) / (1.0 - alpha);
+    const long double lg = logl((long double)gamma);
+    const int i_lo = (int)floorl(-149.0L * logl(2.0L) / lg) - 2;
+    const int i_hi = (int)ceill(128.0L * logl(2.0L) / lg) + 1;
+    const int n_idx = i_hi - i_lo + 1;
+    if (n_idx > SK_MAX_IDX) return INSHR_E_CONFIG;
+    T.tops.resize(n_idx);
+    T.rep.resize(n_idx);
+    for (int b = 0; b < n_idx; b++) {
+        const int i = i_lo + b;
+        const long double v = powl((long double)gamma, (long double)i);
+        float f;
+        if (v >= (long double)3.402823466e+38F) {
+            f = 3.402823466e+38F;
+        } else {
+            f = (float)v;
+            if ((long double)f > v) f = nextafterf(f, -1.0f); // round down (v > 0)
+        }
+        u32 bits;
+        memcpy(&bits, &f, 4);
+        T.tops[b] = bits;
+        T.rep[b] = 2.0 * pow(gamma, (double)i) / (gamma + 1.0);
+    }
+    T.cell.assign(SK_CELLS, ((u32)(n_idx - 1) << 17) | 0x1FFFFu);
+    for (u32 c = 64; c < (0x7f800000u >> 17); c++) { // normal numbers
+        const u32 first = c << 17, last = first | 0x1FFFFu;
+        const u32 b0 = (u32)(std::lower_bound(T.tops.begin(), T.tops.end(), first) - T.tops.begin());
+        if (b0 + 1u >= (u32)n_idx || T.tops[b0 + 1u] < last) return INSHR_E_CONFIG; // more than two buckets
+        const u32 split = T.tops[b0] <= last ? (T.tops[b0] & 0x1FFFFu) : 0x1FFFFu;
+        T.cell[c] = (b0 << 17) | split;
+    }
+    return INSHR_OK;
+}
+
+} // namespace
+
+int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config *cfg,
+                          const inshr_sketch_params *params, inshr_quantized *out,
+                          inshr_sketch_info *info, uint32_t n_tensors)
+{
+    if (!c || !tensors || !cfg || !params || !out || n_tensors == 0 || !params->uniforms) return INSHR_E_ARG;
+    if (!(params->sigma >= 0.0 && params->sigma <= 1.0)) return INSHR_E_CONFIG;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        int rc = check_config(cfg[t]);
+        if (rc) return rc;
+        for (int r = 0; r < (1 << cfg[t].bits); r++) {
+            const double u = params->uniforms[(size_t)t * 256 + r];
+            if (!(u >= 0.0 && u < 1.0)) return INSHR_E_ARG;
+        }
+    }
+    SketchTables T;
+    int rc = build_sketch_tables(params->alpha, T);
+    if (rc) return rc;
+    HIPCHK(c, hipSetDevice(c->device));
+    // one single-configuration search per distinct configuration gives thresholds and counts
+    std::vector<char> done(n_tensors, 0);
+    for (uint32_t t0 = 0; t0 < n_tensors; t0++) {
+        if (done[t0]) continue;
+        std::vector<inshr_tensor> sub;
+        std::vector<inshr_config> subcfg;
+        std::vector<uint32_t> idx;
+        for (uint32_t t = t0; t < n_tensors; t++) {
+            if (!done[t] && cfg[t].bits == cfg[t0].bits && cfg[t].prune_ppm == cfg[t0].prune_ppm &&
+                cfg[t].outlier_ppm == cfg[t0].outlier_ppm) {
+                done[t] = 1;
+                sub.push_back(tensors[t]);
+                subcfg.push_back(cfg[t]);
+                idx.push_back(t);
+            }
+        }
+        const uint32_t nS = (uint32_t)sub.size();
+        rc = run_search(c, sub.data(), nS, &cfg[t0], 1, 0.0);
+        if (rc) return rc;
+        const size_t n_idx = T.tops.size();
+        Carver cv;
+        const size_t o_cell = cv.take(sizeof(u32) * SK_CELLS);
+        const size_t o_tops = cv.take(sizeof(u32) * n_idx);
+        const size_t o_rep = cv.take(sizeof(double) * n_idx);
+        const size_t o_uni = cv.take(sizeof(double) * 256 * nS);
+        const size_t o_sd = cv.take(sizeof(SketchDesc) * nS);
+        const size_t upload = cv.off; // everything up to here comes from the host
+        const size_t o_info = cv.take(sizeof(SketchInfo) * nS);
+        const size_t o_key = cv.take(sizeof(u32) * 256 * nS);
+        const size_t o_cb = cv.take(sizeof(float) * 256 * nS);
+        const size_t o_hist = cv.take(sizeof(u32) * SK_HIST * nS);
+        const size_t o_xq = cv.take(sizeof(double) * SK_HIST * nS);
+        const size_t o_w = cv.take(sizeof(double) * SK_HIST * nS);
+        const size_t o_d = cv.take(sizeof(double) * SK_HIST * nS);
+        rc = ensure_dev(c, c->sketch_mem, cv.off);
+        if (rc) return rc;
+        rc = ensure_host(c, c->h_up, upload);
+        if (rc) return rc;
+        rc = ensure_host(c, c->h_down, sizeof(SketchInfo) * nS);
+        if (rc) return rc;
+        char *hb = (char *)c->h_up.p, *db = (char *)c->sketch_mem.p;
+        HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
+        memcpy(hb + o_cell, T.cell.data(), sizeof(u32) * SK_CELLS);
+        memcpy(hb + o_tops, T.tops.data(), sizeof(u32) * n_idx);
+        memcpy(hb + o_rep, T.rep.data(), sizeof(double) * n_idx);
+        for (uint32_t k = 0; k < nS; k++) {
+            memcpy(hb + o_uni + sizeof(double) * 256 * k, params->uniforms + (size_t)idx[k] * 256,
+                   sizeof(double) * 256);
+            SketchDesc sd;
+            sd.active = 1u;
+            sd.cfg = 0u; // the one configuration of the search just made
+            memcpy(hb + o_sd + sizeof(SketchDesc) * k, &sd, sizeof(sd));
+        }
+        HIPCHK(c, hipMemcpyAsync(db, hb, upload, hipMemcpyHostToDevice, c->stream));
+        HIPCHK(c, hipMemsetAsync(db + o_hist, 0, sizeof(u32) * SK_HIST * nS, c->stream));
+        SketchParams P;
+        P.sigma = params->sigma;
+        P.max_iter = params->max_iter;
+        P.n_idx = (u32)n_idx;
+        P.cell = (const u32 *)(db + o_cell);
+        P.tops = (const u32 *)(db + o_tops);
+        P.rep = (const double *)(db + o_rep);
+        P.uniforms = (const double *)(db + o_uni);
+        P.hist = (u32 *)(db + o_hist);
+        P.xq = (double *)(db + o_xq);
+        P.w = (double *)(db + o_w);
+        P.d = (double *)(db + o_d);
+        P.alt_key = (u32 *)(db + o_key);
+        P.alt_cb = (float *)(db + o_cb);
+        P.info = (SketchInfo *)(db + o_info);
+        HIPCHK(c, launch_sketch(c->batch, (const SketchDesc *)(db + o_sd), P, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_info, sizeof(SketchInfo) * nS, hipMemcpyDeviceToHost,
+                                 c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        if (info) {
+            const SketchInfo *si = (const SketchInfo *)c->h_down.p;
+            for (uint32_t k = 0; k < nS; k++) {
+                info[idx[k]].n_buckets = si[k].n_buckets;
+                info[idx[k]].rounds = si[k].rounds;
+            }
+        }
+        std::vector<inshr_quantized> subout(nS);
+        std::vector<uint32_t> which(nS);
+        for (uint32_t k = 0; k < nS; k++) {
+            subout[k] = out[idx[k]];
+            which[k] = k;
+        }
+        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), nS, P.alt_key, P.alt_cb);
+        for (uint32_t k = 0; k < nS; k++) out[idx[k]] = subout[k];
         if (rc) return rc;
     }
     return INSHR_OK;

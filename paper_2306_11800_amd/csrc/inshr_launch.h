@@ -82,6 +82,9 @@ struct QDesc { // one tensor of a quantize call (indexed like the batch)
     u64 out_cap;
     u32 cfg;   // index into the grid of the search state
     u32 tslot;
+    const u32 *alt_key; // NULL, or 256 boundary keys that replace the search's (boundary j of K at
+                        // (j << (8 - bits)) - 1) ...
+    const float *alt_cb; // ... and the K centres that go with them
 };
 struct QInfo {
     u64 n_pruned, n_outlier, n_kept;

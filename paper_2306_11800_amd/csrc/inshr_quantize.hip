@@ -38,12 +38,12 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
         carry += tot;
         __syncthreads();
     }
-    const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
+    const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
     const u32 sh = 8u - bits;
     if (q.boundaries)
         for (u32 j = 1 + tid; j < K; j += BLOCK)
             gptr(q.boundaries)[j - 1] = __uint_as_float(bits_of_key(tk[(j << sh) - 1u]));
-    const float *cb = B.codebook + ((size_t)t * gd->n_cfg + g) * CB_STRIDE;
+    const float *cb = q.alt_cb ? q.alt_cb : B.codebook + ((size_t)t * gd->n_cfg + g) * CB_STRIDE;
     for (u32 k = tid; k < K; k += BLOCK) gptr(q.codebook)[k] = cb[k];
     if (tid == 0) {
         QInfo r;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
         const u32 o = gd->pair_o[pair];
         const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + o];
         const u32 nb2 = st->nb2;
-        const u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
+        const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
         const u32 n_bnd = K - 1u, n_bp = n_bnd + 4u;
         __syncthreads();
         for (u32 i = tid; i < (u32)COARSE; i += BLOCK) T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);

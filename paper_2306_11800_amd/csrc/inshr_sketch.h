@@ -1,0 +1,37 @@
+// Descriptors of the sketch-based boundary rule (kernels in inshr_sketch.hip, tables and
+// sequencing in inshr_api.hip).
+#pragma once
+#include "inshr_launch.h"
+
+namespace inshr {
+
+constexpr int SK_CELLS = 16384;            // magnitude >> 17: sign-free exponent and 6 mantissa bits
+constexpr int SK_MAX_IDX = 9728;           // most bucket indices per sign (alpha = 0.01 needs 9604)
+constexpr int SK_HIST = 2 * SK_MAX_IDX + 1; // negative buckets descending, zero, positive ascending
+
+struct SketchDesc { // one tensor of the batch
+    u32 active;     // part of the call
+    u32 cfg;        // its configuration in the grid of the search state (thresholds, bits)
+};
+struct SketchInfo {
+    u32 n_buckets;  // non-empty buckets
+    u32 rounds;     // Lloyd rounds that changed the centres
+};
+struct SketchParams {
+    double sigma;
+    u32 max_iter;
+    u32 n_idx;             // bucket b stands for index i_lo + b
+    const u32 *cell;       // [SK_CELLS] first bucket of the cell << 17 | low 17 bits of that bucket's largest magnitude
+    const u32 *tops;       // [n_idx] magnitude image of the largest fp32 number <= gamma^(i_lo + b)
+    const double *rep;     // [n_idx] 2 gamma^(i_lo + b) / (gamma + 1)
+    const double *uniforms; // [nT][256] the random numbers of the draws
+    u32 *hist;             // [nT][SK_HIST], zero on entry
+    double *xq, *w, *d;    // [nT][SK_HIST] bucket values, weights, squared distances
+    u32 *alt_key;          // [nT][256] boundary keys where the quantizer looks for them
+    float *alt_cb;         // [nT][256] codebook
+    SketchInfo *info;      // [nT]
+};
+
+hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s);
+
+} // namespace inshr

@@ -1,0 +1,353 @@
+// Boundaries from the log-space sketch and weighted K-Means on its buckets (Sec. 4.3 / Algorithm 1,
+// Sec. 4.4 / Algorithms 2 and 3), as an alternative to the equal-population bins of the search: the
+// values between the two thresholds are counted per bucket (sign, ceil(log_gamma |x|)), the
+// buckets are clustered with sample weights sigma * frequency + (1 - sigma) * magnitude (both
+// divided by their largest entry), and the cluster centres become the codebook; the quantizer then
+// runs with the midpoints of neighbouring centres as boundaries.
+//
+//   k_sketch_hist    one more sweep over the tensors (4 bytes per element, like the search's
+//                    sweeps): a table in LDS maps the magnitude's top 14 bits to the first bucket
+//                    that its 2^17 magnitudes touch and the largest magnitude of that bucket (a
+//                    range of 2^(1/64) never touches more than two buckets for alpha >= 0.01), so
+//                    the bucket is one LDS read, a compare and an add; the counts go to an LDS
+//                    histogram in value order (negative buckets descending, zero, positive
+//                    ascending).  Denormals, whose ranges are wider, search the bucket list.
+//   k_sketch_kmeans  one workgroup per tensor: compacts the non-empty buckets, draws the K
+//                    starting centres (running sums by a block scan, the draw itself by the one
+//                    thread whose share holds it), then Lloyd rounds on the sorted list — a
+//                    cluster is a contiguous run of buckets, found by bisection on the midpoints
+//                    and summed in index order by one thread — until the runs repeat.
+//                    All arithmetic is fp64 without contraction (products and sums rounded
+//                    separately).
+#include "inshr_sketch.h"
+
+namespace inshr {
+
+__device__ __forceinline__ u32 sketch_slot(u32 key, u32 mag, const u32 *cell, const SketchParams &P)
+{
+    if (mag == 0u) return (u32)SK_MAX_IDX;
+    u32 b;
+    if (mag < 0x00800000u) { // denormal: first bucket whose largest magnitude reaches mag
+        u32 lo = 0u, hi = P.n_idx - 1u;
+        while (lo < hi) {
+            const u32 mid = (lo + hi) >> 1;
+            if (P.tops[mid] >= mag)
+                hi = mid;
+            else
+                lo = mid + 1u;
+        }
+        b = lo;
+    } else {
+        const u32 e = cell[mag >> 17];
+        b = (e >> 17) + ((mag & 0x1FFFFu) > (e & 0x1FFFFu) ? 1u : 0u);
+    }
+    return key_is_neg(key) ? (u32)SK_MAX_IDX - 1u - b : (u32)SK_MAX_IDX + 1u + b;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__ td, int nT,
+                                                       const u64 *__restrict__ wg_tile0,
+                                                       const GridDesc *__restrict__ gd,
+                                                       const SketchDesc *__restrict__ sd,
+                                                       SketchParams P, Bufs B)
+{
+    __shared__ u32 smem[SK_CELLS + SK_HIST];
+    u32 *cell = smem;
+    u32 *h = smem + SK_CELLS;
+    const u32 tid = threadIdx.x;
+    const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
+    if (tile_lo >= tile_hi) return;
+    for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = P.cell[i];
+    for (int i = tid; i < SK_HIST; i += BLOCK) h[i] = 0u;
+    int t = find_tensor(td, nT, tile_lo);
+    u64 tile = tile_lo;
+    while (tile < tile_hi) {
+        const TDesc d = td[t];
+        const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
+        const u64 t_end = d.tile0 + n_tiles_t;
+        const u64 stop = t_end < tile_hi ? t_end : tile_hi;
+        const SketchDesc s = sd[t];
+        if (!s.active) {
+            tile = stop;
+            t++;
+            continue;
+        }
+        const TState *st = B.ts + t;
+        const u32 pair = gd->cfg_pair[s.cfg];
+        const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + gd->pair_o[pair]];
+        __syncthreads();
+        for (; tile < stop; tile++) {
+            const u64 e0 = (tile - d.tile0) * (u64)TILE;
+            const u64 rem = d.n - e0;
+            const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+            float v[16];
+            const u32 mask = load_tile(d, e0, cnt, v);
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const u32 key = key_of_float(v[i]);
+                const u32 mag = mag_of_key(key);
+                const bool take = ((mask >> i) & 1u) && mag >= tau_p && mag <= tau_o;
+                if (take) atomicAdd(&h[sketch_slot(key, mag, cell, P)], 1u);
+            }
+        }
+        __syncthreads();
+        u32 *gh = P.hist + (size_t)t * SK_HIST;
+        for (int i = tid; i < SK_HIST; i += BLOCK) {
+            const u32 c = h[i];
+            if (c) {
+                atomicAdd(&gh[i], c);
+                h[i] = 0u;
+            }
+        }
+        t++;
+    }
+}
+
+// value of the bucket at position slot of the histogram
+__device__ __forceinline__ double slot_value(u32 slot, const SketchParams &P)
+{
+    if (slot == (u32)SK_MAX_IDX) return 0.0;
+    if (slot > (u32)SK_MAX_IDX) return P.rep[slot - (u32)SK_MAX_IDX - 1u];
+    return -P.rep[(u32)SK_MAX_IDX - 1u - slot];
+}
+
+// Scan of one double per thread over the workgroup: returns this thread's inclusive value,
+// *excl = the sum of the threads before it, *total = the sum of all.  red: LDS scratch of
+// BLOCK / 64 + 1 doubles.
+__device__ inline double block_scan_f64(double s, double *red, double *excl, double *total)
+{
+    const u32 tid = threadIdx.x, lane = tid & 63u;
+    double inc = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double y = __shfl_up(inc, o);
+        if ((int)lane >= o) inc = __dadd_rn(inc, y);
+    }
+    const double before = __shfl_up(inc, 1); // inclusive value of the lane below
+    __syncthreads();
+    if (lane == 63u) red[tid >> 6] = inc;
+    __syncthreads();
+    if (tid == 0) {
+        double run = 0.0;
+        for (int w = 0; w < BLOCK / 64; w++) {
+            const double y = red[w];
+            red[w] = run;
+            run = __dadd_rn(run, y);
+        }
+        red[BLOCK / 64] = run;
+    }
+    __syncthreads();
+    *total = red[BLOCK / 64];
+    *excl = lane ? __dadd_rn(red[tid >> 6], before) : red[tid >> 6];
+    return __dadd_rn(red[tid >> 6], inc);
+}
+
+__global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restrict__ gd,
+                                                         const SketchDesc *__restrict__ sd,
+                                                         SketchParams P)
+{
+    __shared__ u32 s_u32[BLOCK / 64 + 2];
+    __shared__ double s_red[BLOCK / 64 + 2];
+    __shared__ double cen[256], craw[256];
+    __shared__ u32 seg[257], seg_prev[257];
+    __shared__ u32 s_pick, s_last, s_changed, s_chosen;
+    const int t = blockIdx.x;
+    const SketchDesc s = sd[t];
+    if (!s.active) return;
+    const u32 tid = threadIdx.x, lane = tid & 63u;
+    const u32 K = 1u << gd->cfg_bits[s.cfg];
+    const u32 *h = P.hist + (size_t)t * SK_HIST;
+    double *xq = P.xq + (size_t)t * SK_HIST;
+    double *w = P.w + (size_t)t * SK_HIST;
+    double *dist = P.d + (size_t)t * SK_HIST;
+
+    // ---- the non-empty buckets in value order (Algorithm 1: unique with counts) ----
+    constexpr u32 PER = (SK_HIST + BLOCK - 1) / BLOCK;
+    u32 mine = 0u, cmax = 0u;
+    for (u32 i = 0; i < PER; i++) {
+        const u32 slot = tid * PER + i;
+        const u32 c = slot < (u32)SK_HIST ? h[slot] : 0u;
+        mine += c ? 1u : 0u;
+        cmax = c > cmax ? c : cmax;
+    }
+    u32 inc = wave_incl_scan(mine);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const u32 y = __shfl_xor(cmax, o);
+        cmax = y > cmax ? y : cmax;
+    }
+    if (lane == 63u) s_u32[tid >> 6] = inc;
+    if (lane == 0u) seg_prev[tid >> 6] = cmax; // (scratch until the Lloyd rounds)
+    __syncthreads();
+    u32 base = 0u, m = 0u, maxc = 0u;
+    for (u32 wv = 0; wv < BLOCK / 64; wv++) {
+        const u32 y = s_u32[wv];
+        if (wv < (tid >> 6)) base += y;
+        m += y;
+        maxc = seg_prev[wv] > maxc ? seg_prev[wv] : maxc;
+    }
+    u32 pos = base + inc - mine;
+    for (u32 i = 0; i < PER; i++) {
+        const u32 slot = tid * PER + i;
+        const u32 c = slot < (u32)SK_HIST ? h[slot] : 0u;
+        if (c) {
+            xq[pos] = slot_value(slot, P);
+            w[pos] = (double)c; // the count, replaced by the weight below
+            pos++;
+        }
+    }
+    __syncthreads();
+    if (m == 0u) { // (cannot happen: at least one value lies between the thresholds)
+        if (tid == 0) {
+            P.info[t].n_buckets = 0u;
+            P.info[t].rounds = 0u;
+        }
+        return;
+    }
+    // ---- sample weights (Algorithm 2): sigma * C / max C + (1 - sigma) * |X| / max |X| ----
+    const double x_first = fabs(xq[0]), x_last = fabs(xq[m - 1u]);
+    const double mx = x_first > x_last ? x_first : x_last;
+    const double one_minus = __dsub_rn(1.0, P.sigma);
+    __syncthreads();
+    for (u32 i = tid; i < m; i += BLOCK) {
+        const double c_hat = __ddiv_rn(w[i], (double)maxc);
+        const double x_hat = mx > 0.0 ? __ddiv_rn(fabs(xq[i]), mx) : 0.0;
+        w[i] = __dadd_rn(__dmul_rn(P.sigma, c_hat), __dmul_rn(one_minus, x_hat));
+    }
+    __syncthreads();
+
+    // ---- weighted K-Means++ draws (Algorithm 3) ----
+    const u32 per = (m + BLOCK - 1u) / BLOCK;
+    const u32 lo = tid * per < m ? tid * per : m, hi = lo + per < m ? lo + per : m;
+    const double *uni = P.uniforms + (size_t)t * 256;
+    for (u32 r = 0; r < K; r++) {
+        double sum = 0.0;
+        for (u32 i = lo; i < hi; i++) sum = __dadd_rn(sum, r ? __dmul_rn(dist[i], w[i]) : w[i]);
+        if (tid == 0) {
+            s_pick = 0xFFFFFFFFu;
+            s_last = 0u;
+        }
+        double total, excl;
+        const double incl = block_scan_f64(sum, s_red, &excl, &total);
+        const double target = __dmul_rn(uni[r], total);
+        if (r > 0u && !(total > 0.0)) { // every bucket is a centre already: repeat the last one
+            if (tid == 0) craw[r] = craw[r - 1u];
+            __syncthreads();
+            continue;
+        }
+        if (incl > target) atomicMin(&s_pick, tid);
+        for (u32 i = lo; i < hi; i++)
+            if ((r ? __dmul_rn(dist[i], w[i]) : w[i]) > 0.0) atomicMax(&s_last, i);
+        __syncthreads();
+        if (tid == (s_pick == 0xFFFFFFFFu ? 0u : s_pick)) {
+            u32 j = s_last; // (when no running sum exceeds the target: the last bucket that could be drawn)
+            if (s_pick != 0xFFFFFFFFu) {
+                double run = excl; // the running sum at the start of this thread's share
+                u32 last_pos = lo;
+                bool found = false;
+                for (u32 i = lo; i < hi; i++) {
+                    const double p = r ? __dmul_rn(dist[i], w[i]) : w[i];
+                    if (p > 0.0) last_pos = i;
+                    run = __dadd_rn(run, p);
+                    if (run > target) {
+                        j = i;
+                        found = true;
+                        break;
+                    }
+                }
+                if (!found) j = last_pos;
+            }
+            s_chosen = j;
+            craw[r] = xq[j];
+        }
+        __syncthreads();
+        const double cj = xq[s_chosen];
+        for (u32 i = lo; i < hi; i++) {
+            const double df = __dsub_rn(xq[i], cj);
+            const double d2 = __dmul_rn(df, df);
+            dist[i] = (r == 0u || d2 < dist[i]) ? d2 : dist[i];
+        }
+        __syncthreads();
+    }
+    // ---- sort the centres ----
+    if (tid < K) {
+        const double x = craw[tid];
+        u32 rank = 0u;
+        for (u32 i = 0; i < K; i++) {
+            const double y = craw[i];
+            rank += (y < x || (y == x && i < tid)) ? 1u : 0u;
+        }
+        cen[rank] = x;
+    }
+    __syncthreads();
+    // ---- weighted Lloyd rounds: cluster j = buckets (mid[j-1], mid[j]] ----
+    u32 rounds = 0u;
+    for (u32 it = 0; it < P.max_iter; it++) {
+        if (tid == 0) s_changed = (it == 0u) ? 1u : 0u;
+        __syncthreads();
+        if (tid <= K) {
+            u32 first = 0u;
+            if (tid == K) {
+                first = m;
+            } else if (tid > 0u) {
+                const double mid = __dmul_rn(__dadd_rn(cen[tid - 1u], cen[tid]), 0.5);
+                u32 a = 0u, b = m; // first bucket above the midpoint
+                while (a < b) {
+                    const u32 c = (a + b) >> 1;
+                    if (xq[c] > mid)
+                        b = c;
+                    else
+                        a = c + 1u;
+                }
+                first = a;
+            }
+            seg[tid] = first;
+            if (it > 0u && seg_prev[tid] != first) s_changed = 1u;
+        }
+        __syncthreads();
+        if (!s_changed) break;
+        if (tid < K) {
+            double sw = 0.0, swx = 0.0;
+            for (u32 i = seg[tid]; i < seg[tid + 1u]; i++) {
+                sw = __dadd_rn(sw, w[i]);
+                swx = __dadd_rn(swx, __dmul_rn(w[i], xq[i]));
+            }
+            if (sw > 0.0) cen[tid] = __ddiv_rn(swx, sw);
+        }
+        if (tid <= K) seg_prev[tid] = seg[tid];
+        rounds++;
+        __syncthreads();
+    }
+    __syncthreads();
+    // ---- codebook and boundaries ----
+    const u32 sh = 8u - gd->cfg_bits[s.cfg];
+    u32 *ak = P.alt_key + (size_t)t * 256;
+    float *acb = P.alt_cb + (size_t)t * 256;
+    if (tid < 256u) ak[tid] = 0u;
+    __syncthreads();
+    if (tid < K) {
+        acb[tid] = __double2float_rn(cen[tid]);
+        if (tid + 1u < K) {
+            const double a = (double)__double2float_rn(cen[tid]), b = (double)__double2float_rn(cen[tid + 1u]);
+            const double mid = __dmul_rn(__dadd_rn(a, b), 0.5);
+            // a value goes to the upper centre when it lies strictly above the midpoint: the
+            // boundary is the smallest fp32 number above it
+            ak[((tid + 1u) << sh) - 1u] = key_of_float(__double2float_rd(mid)) + 1u;
+        }
+    } else if (tid < 256u) {
+        acb[tid] = 0.0f;
+    }
+    if (tid == 0) {
+        P.info[t].n_buckets = m;
+        P.info[t].rounds = rounds;
+    }
+}
+
+hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s)
+{
+    PROF("k_sketch_hist", s,
+         k_sketch_hist<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, sd, P, bt.bufs));
+    PROF("k_sketch_kmeans", s, k_sketch_kmeans<<<bt.nT, BLOCK, 0, s>>>(bt.gd, sd, P));
+    return hipGetLastError();
+}
+
+} // namespace inshr

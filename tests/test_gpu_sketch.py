@@ -1,0 +1,115 @@
+"""GPU parity of the sketch-based boundary rule (inshr_quantize_sketch through the C ABI) against
+oracle/sketch_kmeans.py on the same seeded inputs and the same uniform numbers.  Bit-exact:
+classes, bucket counts, Lloyd rounds, boundaries, symbols, protected lists.  Centres: the clustering
+is fp64 with the oracle's operation order except for the running sums of a draw (block scan against
+a sequential sum), so the codebook is compared at 1e-6 relative and found equal in practice."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from oracle import sketch_kmeans as sk
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2306_11800_amd import api
+    c = api.Context(torch.device("cuda:0"))
+    yield c
+    c.close()
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+
+
+def families(rng, n):
+    t3 = (rng.standard_t(3, n) * 0.015).astype(np.float32)
+    zeros = t3.copy()
+    zeros[rng.uniform(size=n) < 0.3] = 0.0
+    zeros[rng.uniform(size=n) < 0.05] = -0.0
+    positive = np.abs(t3) + np.float32(1e-3)
+    wide = (np.exp(rng.uniform(-60, 60, n)) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    denormal = (rng.standard_normal(n) * 1e-40).astype(np.float32)
+    denormal[::3] = t3[::3]
+    lattice = (rng.integers(-5, 6, n) * 0.25).astype(np.float32)
+    return dict(t3=t3, zeros=zeros, positive=positive, wide=wide, denormal=denormal, lattice=lattice)
+
+
+def check(ctx, xs, cfgs, alpha, sigma, max_iter, seed):
+    rng = np.random.default_rng(seed)
+    uni = rng.uniform(size=(len(xs), 256))
+    qs, info = ctx.quantize_sketch([dev(x) for x in xs], cfgs, uni, alpha=alpha, sigma=sigma,
+                                   max_iter=max_iter)
+    for i, (x, cfg) in enumerate(zip(xs, cfgs)):
+        print("sketch case", seed, i, x.size, cfg, alpha, sigma, flush=True)
+        bits = cfg[0]
+        K = 1 << bits
+        base = ref.quantize(x, cfg)  # classes and thresholds of the exact-threshold oracle
+        r = sk.quantize_values(x, base["sym"], K, alpha, sigma, uni[i], max_iter)
+        q = qs[i]
+        assert (q.n_pruned, q.n_outlier, q.n_kept) == (base["n_pruned"], base["n_outlier"], base["n_kept"])
+        assert info[i] == (r["n_buckets"], r["rounds"]), (info[i], r["n_buckets"], r["rounds"])
+        cb = q.codebook.cpu().numpy()[:K]
+        np.testing.assert_allclose(cb, r["codebook"], rtol=1e-6, atol=0)
+        assert np.array_equal(q.boundaries.cpu().numpy()[:K - 1].view(np.uint32), r["boundaries"].view(np.uint32))
+        got = ref.unpack(q.packed.cpu().numpy().view(np.uint64), x.size, bits + 1)
+        bad = np.nonzero(got != r["sym"])[0]
+        assert bad.size == 0, (bad[:10], got[bad[:10]], r["sym"][bad[:10]])
+        assert np.array_equal(q.outlier_idx.cpu().numpy().view(np.uint32), base["outlier_idx"])
+        assert np.array_equal(q.outlier_val.cpu().numpy().view(np.uint32), base["outlier_val"].view(np.uint32))
+
+
+def test_families_and_configurations(ctx):
+    rng = np.random.default_rng(11)
+    cfgs_all = [(2, 0, 0), (4, 100000, 1000), (8, 300000, 100), (3, 50000, 0), (8, 0, 1000)]
+    for n in (1, 7, 1000, 16384 + 5, 70001):
+        fam = families(rng, n)
+        xs = list(fam.values())
+        cfgs = [cfgs_all[(j + n) % len(cfgs_all)] for j in range(len(xs))]
+        check(ctx, xs, cfgs, 0.01, 0.2, 100, 1000 + n)
+
+
+def test_parameters(ctx):
+    rng = np.random.default_rng(12)
+    x = (rng.standard_t(3, 50000) * 0.015).astype(np.float32)
+    for alpha, sigma, max_iter in ((0.01, 1.0, 100), (0.05, 0.0, 100), (0.5, 0.4, 100), (0.02, 0.2, 1),
+                                   (0.02, 0.2, 0), (0.01, 0.1, 300)):
+        check(ctx, [x, -np.abs(x)], [(5, 100000, 1000), (6, 0, 0)], alpha, sigma, max_iter, 7)
+
+
+def test_more_clusters_than_buckets(ctx):
+    x = np.array([0.5, 0.5, -0.25, 0.0, 1.0, 1.0, 1.0, 0.5], np.float32)
+    check(ctx, [x, np.full(300, 3.0, np.float32)], [(4, 0, 0), (8, 0, 0)], 0.01, 0.2, 50, 3)
+
+
+def test_argument_errors(ctx):
+    from paper_2306_11800_amd import api
+    x = dev(np.ones(100, np.float32))
+    uni = np.full((1, 256), 0.5)
+    for kw in (dict(alpha=0.001), dict(alpha=0.7), dict(sigma=1.5), dict(sigma=-0.1)):
+        with pytest.raises(api.InshrError) as e:
+            ctx.quantize_sketch([x], [(4, 0, 0)], uni, **kw)
+        assert e.value.code == -2
+    with pytest.raises(api.InshrError) as e:
+        ctx.quantize_sketch([x], [(4, 0, 0)], np.full((1, 256), 1.0))
+    assert e.value.code == -1
+
+
+def test_restore_round_trip(ctx):
+    rng = np.random.default_rng(13)
+    x = (rng.standard_t(3, 40000) * 0.015).astype(np.float32)
+    uni = rng.uniform(size=(1, 256))
+    qs, _ = ctx.quantize_sketch([dev(x)], [(4, 100000, 1000)], uni)
+    y = ctx.dequantize(qs)[0].cpu().numpy()
+    q = qs[0]
+    sym = ref.unpack(q.packed.cpu().numpy().view(np.uint64), x.size, 5)
+    cb = q.codebook.cpu().numpy()
+    want = np.where(sym == 0, np.float32(0), np.where(sym == 1, x, cb[np.maximum(sym.astype(np.int64) - 2, 0)]))
+    assert np.array_equal(y.view(np.uint32), want.astype(np.float32).view(np.uint32))
+    # every quantized value decodes to the nearest centre
+    m = sym >= 2
+    d = np.abs(x[m].astype(np.float64)[:, None] - cb[:16].astype(np.float64)[None, :])
+    assert np.all(np.abs(y[m].astype(np.float64) - x[m]) <= d.min(axis=1) * (1 + 1e-12))
