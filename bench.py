@@ -70,6 +70,10 @@ def main():
     ap.add_argument("--restore", action="store_true",
                     help="also time the restore side (reconstruct + dequantize of the checkpoint) after "
                          "the timed steps and report it as an extra object; needs 4 more bytes per value")
+    ap.add_argument("--sketch", action="store_true",
+                    help="also time the quantizer with the sketch + weighted K-Means bins on the chosen "
+                         "configurations after the timed steps, and compare its squared error with the "
+                         "equal-frequency bins (extra object; needs 4 more bytes per value)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -189,6 +193,53 @@ def main():
                    "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(rprof.items())}}
         del xs, rec
 
+    sketch = None
+    if args.sketch:
+        uni = np.random.default_rng(12345).uniform(size=(len(cur), 256))
+        # stand-alone (one single-configuration search per distinct configuration inside), then on
+        # top of the grid search of the step
+        for it in range(2):
+            if it == 1:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            q_sk, sk_info = ctx.quantize_sketch(cur, cfgs, uni, alpha=0.01, sigma=0.2, max_iter=100)
+        torch.cuda.synchronize()
+        sdt_alone = time.perf_counter() - t0
+        ctx.search(cur, grid, eps, want_scores=False)
+        for it in range(3):
+            if it == 1:
+                torch.cuda.synchronize()
+                ctx.profile(True)
+                t0 = time.perf_counter()
+            q_sk, sk_info = ctx.quantize_sketch(cur, cfgs, uni, alpha=0.01, sigma=0.2, max_iter=100,
+                                                reuse_search=True)
+        torch.cuda.synchronize()
+        sdt = (time.perf_counter() - t0) / 2
+        sprof = ctx.profile_read()
+        ctx.profile(False)
+        q_eq = ctx.quantize(cur, cfgs, reuse_search=False)
+        err_sk = err_eq = sumsq = 0.0
+        buf = torch.empty(max(t.numel() for t in cur), dtype=torch.float32, device=dev)
+        for t, a, b in zip(cur, q_sk, q_eq):
+            y = buf[:t.numel()]
+            ctx.dequantize([a], out=[y])
+            err_sk += float(((t.reshape(-1).double() - y.double()) ** 2).sum())
+            ctx.dequantize([b], out=[y])
+            err_eq += float(((t.reshape(-1).double() - y.double()) ** 2).sum())
+            sumsq += float((t.double() ** 2).sum())
+        hist_ms = sprof["k_sketch_hist"][0] / 2
+        sketch = {"ms_after_a_search": round(sdt * 1e3, 3), "ms_stand_alone": round(sdt_alone * 1e3, 3),
+                  "alpha": 0.01, "sigma": 0.2, "max_iter": 100,
+                  "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(sprof.items())},
+                  "k_sketch_hist_GB/s": round(n_total * 4 / (hist_ms * 1e-3) / 1e9, 1),
+                  "buckets_mean": round(sum(i[0] for i in sk_info) / len(sk_info), 1),
+                  "buckets_max": max(i[0] for i in sk_info),
+                  "rounds_mean": round(sum(i[1] for i in sk_info) / len(sk_info), 1),
+                  "rounds_max": max(i[1] for i in sk_info),
+                  "rel_sq_error_sketch_bins": err_sk / sumsq,
+                  "rel_sq_error_equal_frequency_bins": err_eq / sumsq}
+        del q_sk, q_eq, buf
+
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
@@ -218,6 +269,8 @@ def main():
     }
     if restore is not None:
         out["restore"] = restore
+    if sketch is not None:
+        out["sketch"] = sketch
     print(json.dumps(out))
 
 

@@ -212,11 +212,12 @@ typedef struct {
  * codebook is the centres in fp32, ascending; a value takes the upper of two neighbouring centres
  * when it lies strictly above their midpoint.  out[i].boundaries receives the smallest fp32 number
  * above each midpoint.  All arithmetic of the clustering is fp64.  info (host, n_tensors entries)
- * may be NULL.  Everything else as inshr_quantize without INSHR_REUSE_SEARCH; the state of an
- * earlier inshr_search on the context is replaced. */
+ * may be NULL.  flags and everything else as inshr_quantize: with INSHR_REUSE_SEARCH the thresholds
+ * come from the last inshr_search on the context, otherwise one single-configuration search per
+ * distinct configuration replaces that state. */
 int inshr_quantize_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
                           const inshr_sketch_params *params, inshr_quantized *out,
-                          inshr_sketch_info *info, uint32_t n_tensors);
+                          inshr_sketch_info *info, uint32_t n_tensors, uint32_t flags);
 
 /* ---- entropy stage of the delta (host memory only, outside the timed path) ------------------- */
 

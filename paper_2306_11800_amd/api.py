@@ -112,7 +112,7 @@ def load_library() -> C.CDLL:
                                    C.POINTER(CQuantized), C.c_uint32, C.c_uint32]
     lib.inshr_quantize_sketch.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
                                           C.POINTER(CSketchParams), C.POINTER(CQuantized),
-                                          C.POINTER(CSketchInfo), C.c_uint32]
+                                          C.POINTER(CSketchInfo), C.c_uint32, C.c_uint32]
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
@@ -342,7 +342,7 @@ class Context:
 
     # -- inshr_quantize_sketch -------------------------------------------------------------
     def quantize_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, alpha: float = 0.01,
-                        sigma: float = 0.2, max_iter: int = 100):
+                        sigma: float = 0.2, max_iter: int = 100, reuse_search: bool = False):
         """uniforms: numpy float64 array [len(tensors), 256] of numbers in [0, 1).  Returns
         (list of Quantized, list of (n_buckets, rounds))."""
         import numpy as np
@@ -372,7 +372,8 @@ class Context:
         res._sizes = tuple(q.n for q in res)
         par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
         info = (CSketchInfo * nT)()
-        self._check(self.lib.inshr_quantize_sketch(self.h, ta, ca, C.byref(par), qa, info, nT))
+        self._check(self.lib.inshr_quantize_sketch(self.h, ta, ca, C.byref(par), qa, info, nT,
+                                                   INSHR_REUSE_SEARCH if reuse_search else 0))
         return res, [(int(i.n_buckets), int(i.rounds)) for i in info]
 
     def _bound(self, n, ccfg, cfg):

@@ -727,14 +727,102 @@ int build_sketch_tables(double alpha, SketchTables &T)
         T.tops[b] = bits;
         T.rep[b] = 2.0 * pow(gamma, (double)i) / (gamma + 1.0);
     }
-    T.cell.assign(SK_CELLS, ((u32)(n_idx - 1) << 17) | 0x1FFFFu);
+    T.cell.assign(SK_CELLS, (u32)(n_idx - 1) << 17);
     for (u32 c = 64; c < (0x7f800000u >> 17); c++) { // normal numbers
         const u32 first = c << 17, last = first | 0x1FFFFu;
         const u32 b0 = (u32)(std::lower_bound(T.tops.begin(), T.tops.end(), first) - T.tops.begin());
         if (b0 + 1u >= (u32)n_idx || T.tops[b0 + 1u] < last) return INSHR_E_CONFIG; // more than two buckets
         const u32 split = T.tops[b0] <= last ? (T.tops[b0] & 0x1FFFFu) : 0x1FFFFu;
-        T.cell[c] = (b0 << 17) | split;
+        T.cell[c] = (b0 << 17) | (0x1FFFFu - split); // adding the low magnitude bits carries above the split
     }
+    return INSHR_OK;
+}
+
+} // namespace
+
+namespace {
+
+// Sketch and clustering for tensors which[k] of the searched batch with configurations cfg[k] (all
+// in the search's grid); src[k] = the tensor's position in the caller's arrays (uniforms, info).
+// Leaves 256 boundary keys and centres per tensor of the batch in *alt_key / *alt_cb (device).
+int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *which, const uint32_t *src,
+                      uint32_t n_sel, const inshr_sketch_params *params, const SketchTables &T,
+                      inshr_sketch_info *info, const u32 **alt_key, const float **alt_cb)
+{
+    const uint32_t nT = (uint32_t)c->batch.nT;
+    std::vector<SketchDesc> sd(nT);
+    for (auto &d : sd) d.active = d.cfg = 0u;
+    for (uint32_t k = 0; k < n_sel; k++) {
+        uint32_t gi = 0;
+        for (gi = 0; gi < c->grid.n_cfg; gi++)
+            if (c->grid_cfgs[gi].bits == cfg[k].bits && c->grid_cfgs[gi].prune_ppm == cfg[k].prune_ppm &&
+                c->grid_cfgs[gi].outlier_ppm == cfg[k].outlier_ppm)
+                break;
+        if (gi == c->grid.n_cfg) return INSHR_E_SHAPE;
+        sd[which[k]].active = 1u;
+        sd[which[k]].cfg = gi;
+    }
+    const size_t n_idx = T.tops.size();
+    Carver cv;
+    const size_t o_cell = cv.take(sizeof(u32) * SK_CELLS);
+    const size_t o_tops = cv.take(sizeof(u32) * n_idx);
+    const size_t o_rep = cv.take(sizeof(double) * n_idx);
+    const size_t o_uni = cv.take(sizeof(double) * 256 * nT);
+    const size_t o_sd = cv.take(sizeof(SketchDesc) * nT);
+    const size_t upload = cv.off; // everything up to here comes from the host
+    const size_t o_info = cv.take(sizeof(SketchInfo) * nT);
+    const size_t o_key = cv.take(sizeof(u32) * 256 * nT);
+    const size_t o_cb = cv.take(sizeof(float) * 256 * nT);
+    const size_t o_hist = cv.take(sizeof(u32) * SK_HIST * nT);
+    const size_t o_xq = cv.take(sizeof(double) * SK_HIST * nT);
+    const size_t o_w = cv.take(sizeof(double) * SK_HIST * nT);
+    const size_t o_d = cv.take(sizeof(double) * SK_HIST * nT);
+    int rc = ensure_dev(c, c->sketch_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, upload);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_down, sizeof(SketchInfo) * nT);
+    if (rc) return rc;
+    char *hb = (char *)c->h_up.p, *db = (char *)c->sketch_mem.p;
+    HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
+    memcpy(hb + o_cell, T.cell.data(), sizeof(u32) * SK_CELLS);
+    memcpy(hb + o_tops, T.tops.data(), sizeof(u32) * n_idx);
+    memcpy(hb + o_rep, T.rep.data(), sizeof(double) * n_idx);
+    memset(hb + o_uni, 0, sizeof(double) * 256 * nT);
+    for (uint32_t k = 0; k < n_sel; k++)
+        memcpy(hb + o_uni + sizeof(double) * 256 * which[k], params->uniforms + (size_t)src[k] * 256,
+               sizeof(double) * 256);
+    memcpy(hb + o_sd, sd.data(), sizeof(SketchDesc) * nT);
+    HIPCHK(c, hipMemcpyAsync(db, hb, upload, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemsetAsync(db + o_hist, 0, sizeof(u32) * SK_HIST * nT, c->stream));
+    SketchParams P;
+    P.sigma = params->sigma;
+    P.max_iter = params->max_iter;
+    P.n_idx = (u32)n_idx;
+    P.cell = (const u32 *)(db + o_cell);
+    P.tops = (const u32 *)(db + o_tops);
+    P.rep = (const double *)(db + o_rep);
+    P.uniforms = (const double *)(db + o_uni);
+    P.hist = (u32 *)(db + o_hist);
+    P.xq = (double *)(db + o_xq);
+    P.w = (double *)(db + o_w);
+    P.d = (double *)(db + o_d);
+    P.alt_key = (u32 *)(db + o_key);
+    P.alt_cb = (float *)(db + o_cb);
+    P.info = (SketchInfo *)(db + o_info);
+    HIPCHK(c, launch_sketch(c->batch, (const SketchDesc *)(db + o_sd), P, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_info, sizeof(SketchInfo) * nT, hipMemcpyDeviceToHost,
+                             c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (info) {
+        const SketchInfo *si = (const SketchInfo *)c->h_down.p;
+        for (uint32_t k = 0; k < n_sel; k++) {
+            info[src[k]].n_buckets = si[which[k]].n_buckets;
+            info[src[k]].rounds = si[which[k]].rounds;
+        }
+    }
+    *alt_key = P.alt_key;
+    *alt_cb = P.alt_cb;
     return INSHR_OK;
 }
 
@@ -742,7 +830,7 @@ int build_sketch_tables(double alpha, SketchTables &T)
 
 int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config *cfg,
                           const inshr_sketch_params *params, inshr_quantized *out,
-                          inshr_sketch_info *info, uint32_t n_tensors)
+                          inshr_sketch_info *info, uint32_t n_tensors, uint32_t flags)
 {
     if (!c || !tensors || !cfg || !params || !out || n_tensors == 0 || !params->uniforms) return INSHR_E_ARG;
     if (!(params->sigma >= 0.0 && params->sigma <= 1.0)) return INSHR_E_CONFIG;
@@ -758,7 +846,20 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
     int rc = build_sketch_tables(params->alpha, T);
     if (rc) return rc;
     HIPCHK(c, hipSetDevice(c->device));
-    // one single-configuration search per distinct configuration gives thresholds and counts
+    const u32 *alt_key = nullptr;
+    const float *alt_cb = nullptr;
+    if (flags & INSHR_REUSE_SEARCH) {
+        if (!c->have_search || c->tensors.size() != n_tensors) return INSHR_E_SHAPE;
+        std::vector<uint32_t> which(n_tensors);
+        for (uint32_t t = 0; t < n_tensors; t++) {
+            if (c->tensors[t].data != tensors[t].data || c->tensors[t].n != tensors[t].n) return INSHR_E_SHAPE;
+            which[t] = t;
+        }
+        rc = sketch_with_state(c, cfg, which.data(), which.data(), n_tensors, params, T, info, &alt_key, &alt_cb);
+        if (rc) return rc;
+        return quantize_with_state(c, cfg, out, which.data(), n_tensors, alt_key, alt_cb);
+    }
+    // stand-alone: one single-configuration search per distinct configuration gives the thresholds
     std::vector<char> done(n_tensors, 0);
     for (uint32_t t0 = 0; t0 < n_tensors; t0++) {
         if (done[t0]) continue;
@@ -777,75 +878,15 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
         const uint32_t nS = (uint32_t)sub.size();
         rc = run_search(c, sub.data(), nS, &cfg[t0], 1, 0.0);
         if (rc) return rc;
-        const size_t n_idx = T.tops.size();
-        Carver cv;
-        const size_t o_cell = cv.take(sizeof(u32) * SK_CELLS);
-        const size_t o_tops = cv.take(sizeof(u32) * n_idx);
-        const size_t o_rep = cv.take(sizeof(double) * n_idx);
-        const size_t o_uni = cv.take(sizeof(double) * 256 * nS);
-        const size_t o_sd = cv.take(sizeof(SketchDesc) * nS);
-        const size_t upload = cv.off; // everything up to here comes from the host
-        const size_t o_info = cv.take(sizeof(SketchInfo) * nS);
-        const size_t o_key = cv.take(sizeof(u32) * 256 * nS);
-        const size_t o_cb = cv.take(sizeof(float) * 256 * nS);
-        const size_t o_hist = cv.take(sizeof(u32) * SK_HIST * nS);
-        const size_t o_xq = cv.take(sizeof(double) * SK_HIST * nS);
-        const size_t o_w = cv.take(sizeof(double) * SK_HIST * nS);
-        const size_t o_d = cv.take(sizeof(double) * SK_HIST * nS);
-        rc = ensure_dev(c, c->sketch_mem, cv.off);
-        if (rc) return rc;
-        rc = ensure_host(c, c->h_up, upload);
-        if (rc) return rc;
-        rc = ensure_host(c, c->h_down, sizeof(SketchInfo) * nS);
-        if (rc) return rc;
-        char *hb = (char *)c->h_up.p, *db = (char *)c->sketch_mem.p;
-        HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
-        memcpy(hb + o_cell, T.cell.data(), sizeof(u32) * SK_CELLS);
-        memcpy(hb + o_tops, T.tops.data(), sizeof(u32) * n_idx);
-        memcpy(hb + o_rep, T.rep.data(), sizeof(double) * n_idx);
-        for (uint32_t k = 0; k < nS; k++) {
-            memcpy(hb + o_uni + sizeof(double) * 256 * k, params->uniforms + (size_t)idx[k] * 256,
-                   sizeof(double) * 256);
-            SketchDesc sd;
-            sd.active = 1u;
-            sd.cfg = 0u; // the one configuration of the search just made
-            memcpy(hb + o_sd + sizeof(SketchDesc) * k, &sd, sizeof(sd));
-        }
-        HIPCHK(c, hipMemcpyAsync(db, hb, upload, hipMemcpyHostToDevice, c->stream));
-        HIPCHK(c, hipMemsetAsync(db + o_hist, 0, sizeof(u32) * SK_HIST * nS, c->stream));
-        SketchParams P;
-        P.sigma = params->sigma;
-        P.max_iter = params->max_iter;
-        P.n_idx = (u32)n_idx;
-        P.cell = (const u32 *)(db + o_cell);
-        P.tops = (const u32 *)(db + o_tops);
-        P.rep = (const double *)(db + o_rep);
-        P.uniforms = (const double *)(db + o_uni);
-        P.hist = (u32 *)(db + o_hist);
-        P.xq = (double *)(db + o_xq);
-        P.w = (double *)(db + o_w);
-        P.d = (double *)(db + o_d);
-        P.alt_key = (u32 *)(db + o_key);
-        P.alt_cb = (float *)(db + o_cb);
-        P.info = (SketchInfo *)(db + o_info);
-        HIPCHK(c, launch_sketch(c->batch, (const SketchDesc *)(db + o_sd), P, c->stream));
-        HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_info, sizeof(SketchInfo) * nS, hipMemcpyDeviceToHost,
-                                 c->stream));
-        HIPCHK(c, hipStreamSynchronize(c->stream));
-        if (info) {
-            const SketchInfo *si = (const SketchInfo *)c->h_down.p;
-            for (uint32_t k = 0; k < nS; k++) {
-                info[idx[k]].n_buckets = si[k].n_buckets;
-                info[idx[k]].rounds = si[k].rounds;
-            }
-        }
         std::vector<inshr_quantized> subout(nS);
         std::vector<uint32_t> which(nS);
         for (uint32_t k = 0; k < nS; k++) {
             subout[k] = out[idx[k]];
             which[k] = k;
         }
-        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), nS, P.alt_key, P.alt_cb);
+        rc = sketch_with_state(c, subcfg.data(), which.data(), idx.data(), nS, params, T, info, &alt_key, &alt_cb);
+        if (rc) return rc;
+        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), nS, alt_key, alt_cb);
         for (uint32_t k = 0; k < nS; k++) out[idx[k]] = subout[k];
         if (rc) return rc;
     }

@@ -7,7 +7,8 @@ namespace inshr {
 
 constexpr int SK_CELLS = 16384;            // magnitude >> 17: sign-free exponent and 6 mantissa bits
 constexpr int SK_MAX_IDX = 9728;           // most bucket indices per sign (alpha = 0.01 needs 9604)
-constexpr int SK_HIST = 2 * SK_MAX_IDX + 1; // negative buckets descending, zero, positive ascending
+constexpr int SK_HIST = 2 * SK_MAX_IDX + 1; // positive buckets, negative buckets, zeros
+constexpr int SK_LDS = 4096;               // longest bucket list that the clustering keeps in LDS
 
 struct SketchDesc { // one tensor of the batch
     u32 active;     // part of the call
@@ -21,7 +22,7 @@ struct SketchParams {
     double sigma;
     u32 max_iter;
     u32 n_idx;             // bucket b stands for index i_lo + b
-    const u32 *cell;       // [SK_CELLS] first bucket of the cell << 17 | low 17 bits of that bucket's largest magnitude
+    const u32 *cell;       // [SK_CELLS] first bucket of the cell << 17 | 2^17 - 1 - low bits of that bucket's largest magnitude
     const u32 *tops;       // [n_idx] magnitude image of the largest fp32 number <= gamma^(i_lo + b)
     const double *rep;     // [n_idx] 2 gamma^(i_lo + b) / (gamma + 1)
     const double *uniforms; // [nT][256] the random numbers of the draws

@@ -9,9 +9,9 @@
 //                    sweeps): a table in LDS maps the magnitude's top 14 bits to the first bucket
 //                    that its 2^17 magnitudes touch and the largest magnitude of that bucket (a
 //                    range of 2^(1/64) never touches more than two buckets for alpha >= 0.01), so
-//                    the bucket is one LDS read, a compare and an add; the counts go to an LDS
-//                    histogram in value order (negative buckets descending, zero, positive
-//                    ascending).  Denormals, whose ranges are wider, search the bucket list.
+//                    the bucket is one LDS read, an add and a shift; the counts go to an LDS
+//                    histogram (positive buckets, negative buckets, zeros).  Zeros and denormals,
+//                    whose ranges are wider, are set aside and search the bucket list.
 //   k_sketch_kmeans  one workgroup per tensor: compacts the non-empty buckets, draws the K
 //                    starting centres (running sums by a block scan, the draw itself by the one
 //                    thread whose share holds it), then Lloyd rounds on the sorted list — a
@@ -23,25 +23,47 @@
 
 namespace inshr {
 
-__device__ __forceinline__ u32 sketch_slot(u32 key, u32 mag, const u32 *cell, const SketchParams &P)
+// Histogram layout: positive bucket b at b, negative bucket b at SK_MAX_IDX + b, zeros at
+// 2 * SK_MAX_IDX.  Bucket of a denormal or zero magnitude (rare): search of the bucket list.
+__device__ __noinline__ u32 sketch_slot_small(u32 bits, const SketchParams &P)
 {
-    if (mag == 0u) return (u32)SK_MAX_IDX;
-    u32 b;
-    if (mag < 0x00800000u) { // denormal: first bucket whose largest magnitude reaches mag
-        u32 lo = 0u, hi = P.n_idx - 1u;
-        while (lo < hi) {
-            const u32 mid = (lo + hi) >> 1;
-            if (P.tops[mid] >= mag)
-                hi = mid;
-            else
-                lo = mid + 1u;
-        }
-        b = lo;
-    } else {
-        const u32 e = cell[mag >> 17];
-        b = (e >> 17) + ((mag & 0x1FFFFu) > (e & 0x1FFFFu) ? 1u : 0u);
+    const u32 mag = bits & 0x7fffffffu;
+    if (mag == 0u) return 2u * (u32)SK_MAX_IDX;
+    u32 lo = 0u, hi = P.n_idx - 1u;
+    while (lo < hi) { // first bucket whose largest magnitude reaches mag
+        const u32 mid = (lo + hi) >> 1;
+        if (P.tops[mid] >= mag)
+            hi = mid;
+        else
+            lo = mid + 1u;
     }
-    return key_is_neg(key) ? (u32)SK_MAX_IDX - 1u - b : (u32)SK_MAX_IDX + 1u + b;
+    return lo + (bits >> 31) * (u32)SK_MAX_IDX;
+}
+
+template <bool FULL>
+__device__ __forceinline__ void sketch_tile(const float (&v)[16], u32 mask, u32 tau_p, u32 tau_o,
+                                            const u32 *cell, u32 *h, const SketchParams &P)
+{
+    u32 small = 0u; // elements between the thresholds whose magnitude is zero or denormal
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const u32 bits = __float_as_uint(v[i]);
+        const u32 mag = bits & 0x7fffffffu;
+        bool take = mag >= tau_p && mag <= tau_o;
+        if (!FULL) take = take && ((mask >> i) & 1u);
+        if (take && mag < 0x00800000u) small |= 1u << i;
+        if (take && mag >= 0x00800000u) {
+            // entry = first bucket of the cell << 17 | (2^17 - 1 - low bits of that bucket's largest
+            // magnitude): the sum carries into the bucket field when the magnitude lies above it
+            const u32 b = (cell[mag >> 17] + (mag & 0x1FFFFu)) >> 17;
+            atomicAdd(&h[b + (bits >> 31) * (u32)SK_MAX_IDX], 1u);
+        }
+    }
+    if (__ballot(small != 0u)) {
+#pragma unroll 1
+        for (int i = 0; i < 16; i++)
+            if ((small >> i) & 1u) atomicAdd(&h[sketch_slot_small(__float_as_uint(v[i]), P)], 1u);
+    }
 }
 
 __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__ td, int nT,
@@ -50,6 +72,7 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
                                                        const SketchDesc *__restrict__ sd,
                                                        SketchParams P, Bufs B)
 {
+    // one static array (it starts at LDS address 0, so offsets fold into the LDS instructions)
     __shared__ u32 smem[SK_CELLS + SK_HIST];
     u32 *cell = smem;
     u32 *h = smem + SK_CELLS;
@@ -81,13 +104,10 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
             float v[16];
             const u32 mask = load_tile(d, e0, cnt, v);
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const u32 key = key_of_float(v[i]);
-                const u32 mag = mag_of_key(key);
-                const bool take = ((mask >> i) & 1u) && mag >= tau_p && mag <= tau_o;
-                if (take) atomicAdd(&h[sketch_slot(key, mag, cell, P)], 1u);
-            }
+            if (cnt == (u32)TILE)
+                sketch_tile<true>(v, mask, tau_p, tau_o, cell, h, P);
+            else
+                sketch_tile<false>(v, mask, tau_p, tau_o, cell, h, P);
         }
         __syncthreads();
         u32 *gh = P.hist + (size_t)t * SK_HIST;
@@ -102,12 +122,19 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
     }
 }
 
+// histogram slot of position v in value order: negative buckets descending, zeros, positive ascending
+__device__ __forceinline__ u32 slot_in_value_order(u32 v)
+{
+    if (v < (u32)SK_MAX_IDX) return 2u * (u32)SK_MAX_IDX - 1u - v;
+    if (v == (u32)SK_MAX_IDX) return 2u * (u32)SK_MAX_IDX;
+    return v - (u32)SK_MAX_IDX - 1u;
+}
 // value of the bucket at position slot of the histogram
 __device__ __forceinline__ double slot_value(u32 slot, const SketchParams &P)
 {
-    if (slot == (u32)SK_MAX_IDX) return 0.0;
-    if (slot > (u32)SK_MAX_IDX) return P.rep[slot - (u32)SK_MAX_IDX - 1u];
-    return -P.rep[(u32)SK_MAX_IDX - 1u - slot];
+    if (slot == 2u * (u32)SK_MAX_IDX) return 0.0;
+    if (slot < (u32)SK_MAX_IDX) return P.rep[slot];
+    return -P.rep[slot - (u32)SK_MAX_IDX];
 }
 
 // Scan of one double per thread over the workgroup: returns this thread's inclusive value,
@@ -156,16 +183,16 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
     const u32 tid = threadIdx.x, lane = tid & 63u;
     const u32 K = 1u << gd->cfg_bits[s.cfg];
     const u32 *h = P.hist + (size_t)t * SK_HIST;
-    double *xq = P.xq + (size_t)t * SK_HIST;
-    double *w = P.w + (size_t)t * SK_HIST;
-    double *dist = P.d + (size_t)t * SK_HIST;
+    // bucket values, weights and squared distances: in LDS when the list is short enough (a few
+    // hundred to a few thousand buckets is the rule), else in the tensor's scratch rows
+    __shared__ double l_x[SK_LDS], l_w[SK_LDS], l_d[SK_LDS];
 
     // ---- the non-empty buckets in value order (Algorithm 1: unique with counts) ----
     constexpr u32 PER = (SK_HIST + BLOCK - 1) / BLOCK;
     u32 mine = 0u, cmax = 0u;
     for (u32 i = 0; i < PER; i++) {
-        const u32 slot = tid * PER + i;
-        const u32 c = slot < (u32)SK_HIST ? h[slot] : 0u;
+        const u32 v = tid * PER + i;
+        const u32 c = v < (u32)SK_HIST ? h[slot_in_value_order(v)] : 0u;
         mine += c ? 1u : 0u;
         cmax = c > cmax ? c : cmax;
     }
@@ -185,10 +212,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
         m += y;
         maxc = seg_prev[wv] > maxc ? seg_prev[wv] : maxc;
     }
+    const bool fits = m <= (u32)SK_LDS;
+    double *xq = fits ? l_x : P.xq + (size_t)t * SK_HIST;
+    double *w = fits ? l_w : P.w + (size_t)t * SK_HIST;
+    double *dist = fits ? l_d : P.d + (size_t)t * SK_HIST;
     u32 pos = base + inc - mine;
     for (u32 i = 0; i < PER; i++) {
-        const u32 slot = tid * PER + i;
-        const u32 c = slot < (u32)SK_HIST ? h[slot] : 0u;
+        const u32 v = tid * PER + i;
+        const u32 slot = slot_in_value_order(v < (u32)SK_HIST ? v : 0u);
+        const u32 c = v < (u32)SK_HIST ? h[slot] : 0u;
         if (c) {
             xq[pos] = slot_value(slot, P);
             w[pos] = (double)c; // the count, replaced by the weight below

@@ -85,6 +85,29 @@ def test_more_clusters_than_buckets(ctx):
     check(ctx, [x, np.full(300, 3.0, np.float32)], [(4, 0, 0), (8, 0, 0)], 0.01, 0.2, 50, 3)
 
 
+def test_on_top_of_a_grid_search(ctx):
+    rng = np.random.default_rng(14)
+    xs = [(rng.standard_t(3, n) * 0.015).astype(np.float32) for n in (30000, 5, 16384, 50001)]
+    grid = [(b, p, o) for b in (3, 6, 8) for p in (0, 200000) for o in (0, 1000)]
+    cfgs = [grid[3], grid[0], grid[11], grid[6]]
+    uni = rng.uniform(size=(len(xs), 256))
+    dx = [dev(x) for x in xs]
+    alone, info_a = ctx.quantize_sketch(dx, cfgs, uni)
+    ctx.search(dx, grid, 0.01, want_scores=False)
+    reuse, info_r = ctx.quantize_sketch(dx, cfgs, uni, reuse_search=True)
+    assert info_a == info_r
+    for a, r in zip(alone, reuse):
+        assert torch.equal(a.packed, r.packed)
+        assert torch.equal(a.codebook[:1 << a.bits], r.codebook[:1 << a.bits])
+        assert torch.equal(a.boundaries[:(1 << a.bits) - 1], r.boundaries[:(1 << a.bits) - 1])
+        assert torch.equal(a.outlier_idx, r.outlier_idx) and torch.equal(a.outlier_val, r.outlier_val)
+    # without a matching search the call is refused
+    from paper_2306_11800_amd import api
+    with pytest.raises(api.InshrError) as e:
+        ctx.quantize_sketch(dx[:2], cfgs[:2], uni[:2], reuse_search=True)
+    assert e.value.code == -5
+
+
 def test_argument_errors(ctx):
     from paper_2306_11800_amd import api
     x = dev(np.ones(100, np.float32))
