@@ -137,46 +137,15 @@ __device__ __forceinline__ double slot_value(u32 slot, const SketchParams &P)
     return -P.rep[slot - (u32)SK_MAX_IDX];
 }
 
-// Scan of one double per thread over the workgroup: returns this thread's inclusive value,
-// *excl = the sum of the threads before it, *total = the sum of all.  red: LDS scratch of
-// BLOCK / 64 + 1 doubles.
-__device__ inline double block_scan_f64(double s, double *red, double *excl, double *total)
-{
-    const u32 tid = threadIdx.x, lane = tid & 63u;
-    double inc = s;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const double y = __shfl_up(inc, o);
-        if ((int)lane >= o) inc = __dadd_rn(inc, y);
-    }
-    const double before = __shfl_up(inc, 1); // inclusive value of the lane below
-    __syncthreads();
-    if (lane == 63u) red[tid >> 6] = inc;
-    __syncthreads();
-    if (tid == 0) {
-        double run = 0.0;
-        for (int w = 0; w < BLOCK / 64; w++) {
-            const double y = red[w];
-            red[w] = run;
-            run = __dadd_rn(run, y);
-        }
-        red[BLOCK / 64] = run;
-    }
-    __syncthreads();
-    *total = red[BLOCK / 64];
-    *excl = lane ? __dadd_rn(red[tid >> 6], before) : red[tid >> 6];
-    return __dadd_rn(red[tid >> 6], inc);
-}
-
 __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restrict__ gd,
                                                          const SketchDesc *__restrict__ sd,
                                                          SketchParams P)
 {
     __shared__ u32 s_u32[BLOCK / 64 + 2];
-    __shared__ double s_red[BLOCK / 64 + 2];
+    __shared__ double s_red[2 * (BLOCK / 64)];
     __shared__ double cen[256], craw[256];
     __shared__ u32 seg[257], seg_prev[257];
-    __shared__ u32 s_pick, s_last, s_changed, s_chosen;
+    __shared__ u32 s_pick[2], s_last[2], s_changed, s_chosen;
     const int t = blockIdx.x;
     const SketchDesc s = sd[t];
     if (!s.active) return;
@@ -250,56 +219,94 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
     // ---- weighted K-Means++ draws (Algorithm 3) ----
     const u32 per = (m + BLOCK - 1u) / BLOCK;
     const u32 lo = tid * per < m ? tid * per : m, hi = lo + per < m ? lo + per : m;
-    const double *uni = P.uniforms + (size_t)t * 256;
+    double *uni = cen; // the draws' random numbers (the sorted centres take this array afterwards)
+    if (tid < 256u) uni[tid] = P.uniforms[(size_t)t * 256 + tid];
+    if (tid < 2u) {
+        s_pick[tid] = 0xFFFFFFFFu;
+        s_last[tid] = 0u;
+    }
+    __syncthreads();
+    // Per draw: (1) every thread sums the probabilities of its share, a wave scan gives the running
+    // sums inside the wave, the wave totals go to LDS; (2) every thread adds the totals of the
+    // waves before its own (in wave order) and the first thread whose running sum exceeds the
+    // target announces itself; (3) that thread walks its share.  With at most one bucket per
+    // thread (the rule) step 3 is empty.  The LDS cells alternate between two copies from draw to
+    // draw, so that a draw never waits for the cells of the one before to be read.
     for (u32 r = 0; r < K; r++) {
+        const u32 cp = r & 1u;
         double sum = 0.0;
-        for (u32 i = lo; i < hi; i++) sum = __dadd_rn(sum, r ? __dmul_rn(dist[i], w[i]) : w[i]);
-        if (tid == 0) {
-            s_pick = 0xFFFFFFFFu;
-            s_last = 0u;
+        u32 last_pos = 0u; // last bucket of the share that could be drawn, + 1
+        for (u32 i = lo; i < hi; i++) {
+            const double p = r ? __dmul_rn(dist[i], w[i]) : w[i];
+            sum = __dadd_rn(sum, p);
+            if (p > 0.0) last_pos = i + 1u;
         }
-        double total, excl;
-        const double incl = block_scan_f64(sum, s_red, &excl, &total);
-        const double target = __dmul_rn(uni[r], total);
+        double inc = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double y = __shfl_up(inc, o);
+            if ((int)lane >= o) inc = __dadd_rn(inc, y);
+        }
+        const double before = __shfl_up(inc, 1); // inclusive value of the lane below
+        if (lane == 63u) s_red[cp * (BLOCK / 64) + (tid >> 6)] = inc;
+        __syncthreads();
+        double wbase = 0.0, total = 0.0;
+        for (u32 wv = 0; wv < BLOCK / 64; wv++) {
+            if (wv == (tid >> 6)) wbase = total;
+            total = __dadd_rn(total, s_red[cp * (BLOCK / 64) + wv]);
+        }
         if (r > 0u && !(total > 0.0)) { // every bucket is a centre already: repeat the last one
             if (tid == 0) craw[r] = craw[r - 1u];
-            __syncthreads();
-            continue;
+            continue; // (nothing of this draw's cells is used again before two more barriers)
         }
-        if (incl > target) atomicMin(&s_pick, tid);
-        for (u32 i = lo; i < hi; i++)
-            if ((r ? __dmul_rn(dist[i], w[i]) : w[i]) > 0.0) atomicMax(&s_last, i);
+        const double target = __dmul_rn(uni[r], total);
+        const double excl = lane ? __dadd_rn(wbase, before) : wbase;
+        const double incl = __dadd_rn(wbase, inc);
+        // one atomic per wave: its first lane above the target, its last lane with a drawable bucket
+        const u64 above = __ballot(incl > target), drawable = __ballot(last_pos != 0u);
+        if (above && lane == (u32)__builtin_ctzll(above)) atomicMin(&s_pick[cp], tid);
+        if (drawable && lane == 63u - (u32)__builtin_clzll(drawable)) atomicMax(&s_last[cp], last_pos);
         __syncthreads();
-        if (tid == (s_pick == 0xFFFFFFFFu ? 0u : s_pick)) {
-            u32 j = s_last; // (when no running sum exceeds the target: the last bucket that could be drawn)
-            if (s_pick != 0xFFFFFFFFu) {
-                double run = excl; // the running sum at the start of this thread's share
-                u32 last_pos = lo;
-                bool found = false;
-                for (u32 i = lo; i < hi; i++) {
-                    const double p = r ? __dmul_rn(dist[i], w[i]) : w[i];
-                    if (p > 0.0) last_pos = i;
-                    run = __dadd_rn(run, p);
-                    if (run > target) {
-                        j = i;
-                        found = true;
-                        break;
+        const u32 pick = s_pick[cp];
+        u32 j;
+        if (per == 1u) {
+            // no running sum exceeds the target (rounding): the last bucket that could be drawn
+            j = pick != 0xFFFFFFFFu ? pick : (s_last[cp] ? s_last[cp] - 1u : 0u);
+            if (tid == 0) {
+                craw[r] = xq[j];
+                s_pick[cp ^ 1u] = 0xFFFFFFFFu;
+                s_last[cp ^ 1u] = 0u;
+            }
+        } else {
+            if (tid == (pick == 0xFFFFFFFFu ? 0u : pick)) {
+                u32 jj = s_last[cp] ? s_last[cp] - 1u : 0u;
+                if (pick != 0xFFFFFFFFu) {
+                    double run = excl; // the running sum at the start of this thread's share
+                    jj = last_pos ? last_pos - 1u : lo;
+                    for (u32 i = lo; i < hi; i++) {
+                        run = __dadd_rn(run, r ? __dmul_rn(dist[i], w[i]) : w[i]);
+                        if (run > target) {
+                            jj = i;
+                            break;
+                        }
                     }
                 }
-                if (!found) j = last_pos;
+                s_chosen = jj;
+                craw[r] = xq[jj];
+                s_pick[cp ^ 1u] = 0xFFFFFFFFu;
+                s_last[cp ^ 1u] = 0u;
             }
-            s_chosen = j;
-            craw[r] = xq[j];
+            __syncthreads();
+            j = s_chosen;
         }
-        __syncthreads();
-        const double cj = xq[s_chosen];
+        const double cj = xq[j];
         for (u32 i = lo; i < hi; i++) {
             const double df = __dsub_rn(xq[i], cj);
             const double d2 = __dmul_rn(df, df);
             dist[i] = (r == 0u || d2 < dist[i]) ? d2 : dist[i];
         }
-        __syncthreads();
     }
+    __syncthreads();
     // ---- sort the centres ----
     if (tid < K) {
         const double x = craw[tid];
