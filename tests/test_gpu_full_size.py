@@ -140,3 +140,64 @@ def test_largest_tensor_every_element(ctx):
     want = torch.where(sym >= 2, qs[1].codebook[(sym - 2).clamp(min=0)], torch.zeros((), device=dev))
     want[refs[1]["prot"]] = cur[refs[1]["prot"]]
     assert torch.equal(xh.view(torch.int32), want.view(torch.int32))
+
+
+def test_largest_tensor_sketch_bins(ctx):
+    """The sketch quantizer on the same shape, in the launch configuration bench.py --sketch uses
+    (on top of a grid search): the bucket counts are recomputed with torch.bucketize over the exact
+    bucket tops (integer arithmetic, oracle/sketch_kmeans.py), the clustering of those few hundred
+    buckets is the CPU oracle's, and every symbol is compared with torch.bucketize over the
+    resulting boundaries."""
+    from oracle import sketch_kmeans as sk
+
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(78)
+    x = torch.empty(N, dtype=torch.float32, device=dev)
+    step = 1 << 26
+    for s in range(0, N, step):
+        e = min(N, s + step)
+        z = torch.randn(4, e - s, dtype=torch.float32, device=dev, generator=g)
+        x[s:e] = 0.015 * z[0] / torch.sqrt((z[1] * z[1] + z[2] * z[2] + z[3] * z[3]) / 3.0)
+        del z
+    x[x == 0] = 1e-6
+    grid = synth.grid_full()
+    cfg = (8, 200000, 1000)
+    alpha, sigma, max_iter = 0.01, 0.2, 100
+    uni = np.random.default_rng(5).uniform(size=(1, 256))
+    ctx.search([x], grid, synth.EPS_DEFAULT, want_scores=False)
+    (q,), (info,) = ctx.quantize_sketch([x], [cfg], uni, alpha=alpha, sigma=sigma, max_iter=max_iter,
+                                        reuse_search=True)
+    # classes from order statistics of |x|
+    A = torch.sort(x.abs()).values
+    tau_p, tau_o = A[N * cfg[1] // 1_000_000], A[N - 1 - N * cfg[2] // 1_000_000]
+    del A
+    mag = x.abs()
+    pruned, prot = mag < tau_p, mag > tau_o
+    kept = ~(pruned | prot)
+    assert q.tau_prune == float(tau_p) and q.tau_outlier == float(tau_o)
+    # Algorithm 1 with library routines: bucket = first one whose top reaches |x|
+    i_lo, tops = sk._bucket_tops(alpha)
+    b = torch.bucketize(mag[kept], torch.from_numpy(tops).to(dev), right=False).to(torch.int64)
+    neg = x[kept] < 0
+    n_b = tops.size
+    counts = torch.bincount(torch.where(neg, n_b - 1 - b, n_b + b), minlength=2 * n_b).cpu().numpy()
+    nz = np.nonzero(counts)[0]
+    sign = np.where(nz < n_b, -1, 1)
+    idx = np.where(nz < n_b, n_b - 1 - nz, nz - n_b) + i_lo
+    xq = sk.bucket_value(sign, idx, alpha)
+    assert np.all(np.diff(xq) > 0)
+    w = sk.sample_weights(xq, counts[nz], sigma)
+    init = sk.weighted_kmeanspp(xq, w, 256, uni[0])
+    centres, rounds = sk.weighted_lloyd(xq, w, xq[init], max_iter)
+    assert info == (nz.size, rounds)
+    cb = centres.astype(np.float32)
+    np.testing.assert_allclose(q.codebook.cpu().numpy(), cb, rtol=1e-6, atol=0)
+    bnd = np.array([sk.boundary_above(m) for m in sk.midpoints(cb.astype(np.float64))], np.float32)
+    assert np.array_equal(q.boundaries.cpu().numpy().view(np.uint32), bnd.view(np.uint32))
+    sym = (2 + torch.bucketize(x, torch.from_numpy(bnd).to(dev), right=True)).to(torch.int16)
+    sym[pruned] = 0
+    sym[prot] = 1
+    got = unpack(q.packed, N, 9)
+    assert torch.equal(got, sym), int((got != sym).sum())
+    assert torch.equal(q.outlier_idx, torch.nonzero(prot).flatten().to(torch.int32))
