@@ -241,3 +241,38 @@ def test_quantize_values_assigns_nearest_centre():
     # more weight on magnitude (small sigma) spreads the centres further out than frequency alone
     r_freq = sk.quantize_values(x, cls, 16, 0.01, 1.0, rng.uniform(size=16), 100)
     assert r["rounds"] >= 1 and r_freq["rounds"] >= 1
+
+
+def test_bound_is_tight_and_buckets_per_decade():
+    # gamma = (1 + alpha) / (1 - alpha): the worst relative error of a dense sample reaches alpha
+    # (a finer or coarser sketch would not), and a decade holds ln 10 / ln gamma buckets
+    x = np.exp(np.linspace(math.log(1e-3), math.log(1e3), 400001)).astype(np.float32)
+    for alpha in (0.01, 0.05):
+        s, i, c = sk.sketch_histogram(x, alpha)
+        v = sk.bucket_value(s, i, alpha)
+        idx = sk.bucket_index(x, alpha)
+        rep = v[np.searchsorted(i, idx)]
+        rel = np.abs(rep - x.astype(np.float64)) / x.astype(np.float64)
+        assert 0.99 * alpha < rel.max() <= alpha * (1 + 1e-12)
+        per_decade = math.log(10.0) / math.log((1 + alpha) / (1 - alpha))
+        assert abs(v.size - 6 * per_decade) <= 2
+
+
+def test_conventions_at_exact_ties():
+    # random_choice: u * total equal to a running sum goes to the next index (running sum must exceed it)
+    assert sk.weighted_kmeanspp([1.0, 2.0, 3.0], [1.0, 1.0, 2.0], 1, [0.25]) == [1]
+    assert sk.weighted_kmeanspp([1.0, 2.0, 3.0], [1.0, 1.0, 2.0], 1, [0.2499999]) == [0]
+    assert sk.weighted_kmeanspp([1.0, 2.0, 3.0], [1.0, 1.0, 2.0], 1, [0.5]) == [2]
+    # a point on the midpoint stays with the lower centre; the boundary is the next fp32 number
+    assert list(sk.assign([2.0, np.nextafter(2.0, 3.0)], [1.0, 3.0])) == [0, 1]
+    assert sk.boundary_above(2.0) == np.nextafter(np.float32(2.0), np.float32(3.0))
+    assert sk.boundary_above(2.0 + 1e-12) == np.nextafter(np.float32(2.0), np.float32(3.0))
+    assert sk.boundary_above(2.0 - 1e-12) == np.float32(2.0)
+    assert sk.boundary_above(0.0) == np.nextafter(np.float32(0), np.float32(1))
+    assert sk.boundary_above(-1e-60) == np.float32(0.0)
+    # a cluster without members keeps its centre
+    c, rounds = sk.weighted_lloyd([1.0, 2.0, 3.0], [1.0, 1.0, 1.0], [1.5, 2.5, 100.0], 10)
+    assert list(c) == [1.5, 3.0, 100.0]  # {1, 2} (2 is on the midpoint), {3}, {}
+    # ... and so does one whose members have no weight
+    c, _ = sk.weighted_lloyd([0.0, 1.0, 2.0], [0.0, 1.0, 1.0], [0.25, 1.5], 10)
+    assert c[0] == 0.25
