@@ -61,7 +61,13 @@ typedef struct inshr_ctx inshr_ctx; /* opaque: one device, one stream, scratch m
 /* device: HIP device ordinal.  hip_stream: a hipStream_t or NULL for the default stream.
  * scratch_bytes: largest single device allocation the context may make for its scratch (0 = no
  * limit).  A search over tensors of N elements in total needs about 8*N bytes plus about 1.5 MB per
- * tensor; a call that needs more than the limit returns INSHR_E_CAPACITY. */
+ * tensor; a call that needs more than the limit returns INSHR_E_CAPACITY.
+ * Environment read here (test and tuning switches; results never depend on them):
+ * INSHR_SAMPLE_MIN_N (default 4194304): tensors with at least this many elements read one tile in
+ * eight in the first sweep of a search and predict where the thresholds fall (a wrong prediction
+ * repeats the exact sweeps for that tensor); INSHR_SAMPLE_FORCE_MISS=1 treats every prediction as
+ * wrong; INSHR_SAMPLE_DEBUG=1 prints how many tensors were sampled and repeated;
+ * INSHR_NO_LDS_ORDER=1 selects the ballot-ranked paths of the group sort and the delta scatter. */
 int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch_bytes);
 void inshr_destroy(inshr_ctx *ctx);
 const char *inshr_strerror(int code);

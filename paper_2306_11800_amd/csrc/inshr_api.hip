@@ -34,6 +34,10 @@ struct inshr_ctx {
     int n_cu = 256;
     int wg_per_cu = 2;
     bool lds_ordered = false; // same-address LDS atomics return in lane order (checked at creation)
+    // tensors of at least this many elements get a sampled first sweep (INSHR_SAMPLE_MIN_N; 0 = never)
+    uint64_t sample_min_n = 4ull << 20;
+    bool sample_force_miss = false; // INSHR_SAMPLE_FORCE_MISS=1 (tests): always take the exact sweeps again
+    std::vector<char> batch_sampled;
     std::string last_err;
 
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
@@ -225,6 +229,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
     std::vector<std::vector<u32>> t_units(nT);
     {
         u64 tile = 0, pool = 0;
+        bool any_sampled = false;
         for (uint32_t t = 0; t < nT; t++) {
             td[t].data = tensors[t].data;
             td[t].n = tensors[t].n;
@@ -235,7 +240,11 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             td[t].pool_thr = pool;
             td[t].pool_cand = pool + padded;
             td[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
-            td[t].pad = 0;
+            td[t].sampled = (c->sample_min_n && tensors[t].n >= c->sample_min_n && tensors[t].n < (1ull << 31))
+                                ? 1u : 0u;
+            any_sampled = any_sampled || td[t].sampled;
+            c->batch_sampled.resize(nT);
+            c->batch_sampled[t] = (char)td[t].sampled;
             tile += padded / TILE;
             pool += 2 * padded;
         }
@@ -344,6 +353,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         bt.n_units = (int)units;
         bt.n_bucket_blocks = c->n_cu * 4;
         bt.lds_ordered = c->lds_ordered;
+        bt.any_sampled = any_sampled;
+        bt.force_miss = c->sample_force_miss;
         bt.nT = (int)nT;
         bt.n_wg = n_wg;
         bt.n_pairs = g.n_pairs;
@@ -408,6 +419,15 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
     for (uint32_t t = 0; t < nT; t++) {
         if (hts[t].nonfinite) return INSHR_E_NONFINITE;
     }
+    if (getenv("INSHR_SAMPLE_DEBUG")) { // how many sampled first sweeps had to be repeated exactly
+        uint32_t n_sampled = 0, n_redo = 0;
+        for (uint32_t t = 0; t < nT; t++) {
+            n_sampled += c->batch_sampled.size() > t && c->batch_sampled[t] ? 1u : 0u;
+            n_redo += hts[t].redo ? 1u : 0u;
+        }
+        fprintf(stderr, "inshr_search: %u tensors, %u with a sampled first sweep, %u of them repeated\n",
+                nT, n_sampled, n_redo);
+    }
     for (uint32_t t = 0; t < nT; t++) {
         if (hts[t].internal_err) {
             c->last_err = "kernel self-check failed on tensor " + std::to_string(t) + ", code " +
@@ -464,6 +484,8 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
             if (const char *e = getenv(name))
                 if (atoi(e) != 0) c->lds_ordered = false;
     }
+    if (const char *e = getenv("INSHR_SAMPLE_MIN_N")) c->sample_min_n = strtoull(e, nullptr, 10);
+    if (const char *e = getenv("INSHR_SAMPLE_FORCE_MISS")) c->sample_force_miss = atoi(e) != 0;
     *out = c;
     return INSHR_OK;
 }

@@ -129,8 +129,10 @@ struct TDesc {           // one tensor of a batch
     u64 pool_thr;        // this tensor's region of the gather pool for threshold buckets (u32 units)
     u64 pool_cand;       // ... and for the elements of active bins
     u32 aligned16;       // data pointer is 16-byte aligned (float4 loads allowed)
-    u32 pad;
+    u32 sampled;         // sweep 1 reads one tile in SAMPLE_RATE (large tensors): its histogram only
+                         // shapes the second-level table and predicts where the thresholds lie
 };
+constexpr int SAMPLE_RATE = 8;
 
 struct GridDesc {        // the configuration grid, decomposed
     u32 n_cfg, n_pairs, n_p, n_o;
@@ -148,6 +150,11 @@ struct TState {
     // thresholds: index t < n_p is the prune threshold of p_ppm[t], t >= n_p the protect
     // threshold of o_ppm[t - n_p]
     u32 n_thr;
+    u32 redo;                          // a sampled sweep 1 mispredicted a threshold: the tensor takes
+                                       // the exact sweeps again
+    u32 thr_jlo[MAX_THR], thr_jhi[MAX_THR]; // first-level magnitude bins gathered for each threshold
+    u32 mag_min, mag_max;              // smallest / largest magnitude image (sampled first sweep only:
+                                       // the thresholds of rank 0 and n - 1 are these)
     u32 thr_bucket[MAX_THR];
     u64 thr_res[MAX_THR];              // rank inside the bucket, magnitude order, zeros first
     u32 thr_mag[MAX_THR];              // result: magnitude image of the threshold

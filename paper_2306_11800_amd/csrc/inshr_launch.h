@@ -68,6 +68,8 @@ struct Batch {
     int n_units;
     int n_bucket_blocks;
     bool lds_ordered;    // same-address LDS atomics return in lane order on this device
+    bool any_sampled;    // some tensor's sweep 1 is sampled
+    bool force_miss;     // (tests) every sampled tensor is sent through the exact sweeps again
     u32 n_pairs, n_cfg;
     u64 n_tiles;
     Bufs bufs;

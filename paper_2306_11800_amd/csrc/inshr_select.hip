@@ -2,13 +2,25 @@
 // sweep over the tensors; every launch covers all tensors of a batch.
 //
 //   sweep 1  k_hist<1>     LDS histogram of key >> 17 (32768 bins), sum of squares, exact zeros
-//                          (negative and non-finite counts follow from the histogram)
+//                          (negative and non-finite counts follow from the histogram).  Tensors of
+//                          4 Mi elements or more read only one tile in eight here ("sampled").
 //   k_plan1                per tensor: first-level magnitude bin ("bucket") of every prune /
 //                          protect threshold rank; a key -> bin table whose bins hold about
-//                          n / 32768 elements each
+//                          n / 32768 elements each.  From a sampled histogram the bucket is only
+//                          predicted: a window of bins around it is gathered (8 standard deviations
+//                          of the rank estimate wide), and the table gives the key prefixes of the
+//                          window at least 8 bins, so that sweep 2 resolves first-level bins there.
 //   sweep 2  k_hist<2>     LDS histogram over the table's bins; elements of threshold buckets are
-//                          gathered into wave-private regions
-//   k_thr_select           exact thresholds and class counts from the gathered buckets
+//                          gathered into wave-private regions.  For sampled tensors also what
+//                          sweep 1 gives otherwise (sum of squares, zeros) and the smallest and
+//                          largest magnitude (the thresholds of rank 0 and n - 1 cannot be
+//                          predicted from a sample).
+//   k_plan1b               sampled tensors: exact size checks and the exact bucket of every
+//                          threshold from the second histogram; a bucket outside its window marks
+//                          the tensor, and k_hist<1>, k_plan1, k_hist<2> run once more for the
+//                          marked tensors alone, unsampled (the results never depend on sampling).
+//   k_thr_select           exact thresholds and class counts from the gathered buckets, all
+//                          thresholds of a tensor in two passes over its gathered keys
 //   k_plan2                exact rank of every boundary of every (prune, protect) pair -> its bin;
 //                          only those bins (and the bins of the class edges) are "active";
 //                          groups of consecutive active bins
@@ -45,15 +57,28 @@ __device__ __forceinline__ void hist1_tile(const float (&v)[16], u32 mask, u32 *
 
 // One tile of sweep 2: exact second-level histogram; the elements of a threshold's first-level
 // magnitude bin are appended to the wave's gather region.
-template <bool FULL>
+// STATS: also the sum of squares and the exact zeros (tensors whose sweep 1 was sampled).
+template <bool FULL, bool STATS>
 __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *h, const u32 *T,
-                                           GLOBAL_AS u32 *gdst, u32 &gathered)
+                                           GLOBAL_AS u32 *gdst, u32 &gathered, double &q_tot,
+                                           u32 &c_zero, u32 &mn, u32 &mx)
 {
     u32 key[16], ent[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) { // all table reads are in flight together
         key[i] = key_of_float(v[i]);
         ent[i] = T[key[i] >> COARSE_SHIFT];
+        if (STATS) {
+            const double xd = (double)v[i];
+            q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
+            const bool valid = FULL || ((mask >> i) & 1u);
+            c_zero += (u32)__popcll(__ballot(valid && key[i] == ZERO_KEY)); // wave-uniform
+            const u32 mag = __float_as_uint(v[i]) & 0x7fffffffu;
+            if (FULL || valid) {
+                mn = mag < mn ? mag : mn;
+                mx = mag > mx ? mag : mx;
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < 16; i++) {
@@ -68,7 +93,9 @@ __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *
     }
 }
 
-template <int LEVEL>
+// REDO: the pass over the tensors whose sampled sweep 1 mispredicted a threshold (TState::redo);
+// they are treated as not sampled, all other tensors are skipped.
+template <int LEVEL, bool REDO>
 __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, int nT,
                                                 const u64 *__restrict__ wg_tile0,
                                                 const u32 *__restrict__ wg_fu0, Bufs B)
@@ -93,6 +120,12 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
         const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
+        if (REDO && !st->redo) { // (the same for the whole workgroup)
+            tile = stop;
+            t++;
+            continue;
+        }
+        const bool sampled = !REDO && d.sampled != 0u;
         // Elements of the thresholds' first-level magnitude bins are gathered into a region of the
         // pool that belongs to this wave alone: the workgroup's region starts at its first element
         // of the tensor, and a wave's share of it is as large as the wave's share of the elements
@@ -105,9 +138,12 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         }
         __syncthreads();
-        u32 c_zero = 0u;    // LEVEL 1: exact zeros seen by this wave
-        double q_tot = 0.0; // LEVEL 1: sum of squares
+        u32 c_zero = 0u;    // exact zeros seen by this wave (LEVEL 1; LEVEL 2 of a sampled tensor)
+        u32 mn = 0xFFFFFFFFu, mx = 0u; // smallest / largest magnitude seen (LEVEL 2 of a sampled tensor)
+        double q_tot = 0.0; // sum of squares (the same)
         for (; tile < stop; tile++) {
+            // a sampled sweep 1 takes one tile in SAMPLE_RATE
+            if (LEVEL == 1 && sampled && (tile - d.tile0) % (u64)SAMPLE_RATE != 0u) continue;
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
@@ -119,10 +155,17 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 else
                     hist1_tile<false>(v, mask, h, q_tot, c_zero);
             } else {
-                if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
-                    hist2_tile<true>(v, mask, h, T, gdst, gathered);
-                else
-                    hist2_tile<false>(v, mask, h, T, gdst, gathered);
+                if (sampled) {
+                    if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
+                        hist2_tile<true, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                    else
+                        hist2_tile<false, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                } else {
+                    if (cnt == (u32)TILE)
+                        hist2_tile<true, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                    else
+                        hist2_tile<false, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                }
             }
         }
         __syncthreads();
@@ -142,7 +185,22 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 B.unit_sub[fu] = sub;
             }
         }
-        if (LEVEL == 1) {
+        // sum of squares and zeros: from sweep 1, or from sweep 2 when sweep 1 was sampled (the
+        // sampled sweep's own zeros, scaled, are an estimate that shapes the table; k_plan1 clears it)
+        if (LEVEL == 1 || sampled) {
+            if (LEVEL == 1 && sampled) c_zero *= (u32)SAMPLE_RATE;
+            if (LEVEL == 2) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const u32 a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
+                    mn = a < mn ? a : mn;
+                    mx = b > mx ? b : mx;
+                }
+                if (lane == 0u) {
+                    atomicMin(&st->mag_min, mn);
+                    atomicMax(&st->mag_max, mx);
+                }
+            }
             q_tot = wave_sum_f64(q_tot);
             if (lane == 0u) {
                 if (c_zero) atomicAdd((unsigned long long *)&st->n_zero, (unsigned long long)c_zero);
@@ -170,6 +228,69 @@ __device__ __forceinline__ u32 depth_for(u32 nc, u64 target)
     return d;
 }
 
+// rank of threshold q: the floor(n * ppm / 1e6) smallest magnitudes are pruned, as many of the
+// largest are protected
+__device__ __forceinline__ u64 threshold_rank(const GridDesc *gd, u32 q, u64 n)
+{
+    if (q < gd->n_p) return n * (u64)gd->p_ppm[q] / 1000000ull;
+    return n - 1ull - n * (u64)gd->o_ppm[q - gd->n_p] / 1000000ull;
+}
+
+// which of the 8 first-level bins under key prefix c are gathered for some threshold
+__device__ __forceinline__ u32 cell_flags(u32 c, const u32 *jlo, const u32 *jhi, u32 n_thr)
+{
+    u32 flag = 0u;
+    for (u32 q = 0; q < n_thr; q++) {
+        // magnitude bin j is first-level key bin 16384 + j for positive, 16383 - j for negative
+        const u32 p0 = (u32)L1_MAGBINS + jlo[q], p1 = (u32)L1_MAGBINS + jhi[q];
+        const u32 n0 = (u32)L1_MAGBINS - 1u - jhi[q], n1 = (u32)L1_MAGBINS - 1u - jlo[q];
+        for (u32 i = 0; i < 8u; i++) {
+            const u32 k = 8u * c + i;
+            if ((k >= p0 && k <= p1) || (k >= n0 && k <= n1)) flag |= bucket_flag(k);
+        }
+    }
+    return flag;
+}
+
+constexpr u32 NO_BUCKET = 0xFFFFFFFFu;
+
+// The buckets of a tensor from the exact figures of its thresholds (one thread): thresholds that
+// fall into the same first-level magnitude bin share a bucket.
+__device__ inline void make_buckets(TState *st, u32 n_thr, const u32 *s_j, const u64 *s_res,
+                                    const u64 *s_bn, const u64 *s_bp, const u32 *s_cn, const u32 *s_cp)
+{
+    u32 nb = 0;
+    u64 off = 0;
+    st->n_thr = n_thr;
+    for (u32 q = 0; q < n_thr; q++) {
+        const u32 j = s_j[q];
+        if (j == NO_BUCKET) { // rank 0 or n - 1 of a sampled tensor: the extreme magnitude itself
+            st->thr_bucket[q] = NO_BUCKET;
+            st->thr_res[q] = s_res[q]; // 0: the smallest magnitude, 1: the largest
+            continue;
+        }
+        u32 found = nb;
+        for (u32 k = 0; k < nb; k++)
+            if (st->bucket_magbin[k] == j) found = k;
+        if (found == nb) {
+            st->bucket_magbin[nb] = j;
+            st->bucket_below_neg[nb] = s_bn[q];
+            st->bucket_below_pos[nb] = s_bp[q];
+            st->bucket_cnt_neg[nb] = s_cn[q];
+            st->bucket_cnt_pos[nb] = s_cp[q];
+            st->bucket_off[nb] = off;
+            st->bucket_cursor[nb] = 0u;
+            off += (u64)s_cn[q] + s_cp[q];
+            nb++;
+        }
+        st->thr_bucket[q] = found;
+        st->thr_res[q] = s_res[q];
+    }
+    st->n_buckets = nb;
+}
+
+// REDO: only the tensors whose sampled sweep 1 mispredicted (their histogram is exact now).
+template <bool REDO>
 __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
                                                  const GridDesc *__restrict__ gd, Bufs B)
 {
@@ -178,28 +299,31 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     u32 *Bn = smem + (L1_MAGBINS + 4); // [16385] negative counts -> exclusive prefix
     u32 *nc = Bn + (L1_MAGBINS + 4);  // [4097] per coarse prefix
     __shared__ u32 tmp[BLOCK / 64 + 1];
-    __shared__ u32 s_j[MAX_THR];
-    __shared__ u64 s_res[MAX_THR];
+    __shared__ u32 s_j[MAX_THR], s_jlo[MAX_THR], s_jhi[MAX_THR], s_cn[MAX_THR], s_cp[MAX_THR];
+    __shared__ u64 s_res[MAX_THR], s_bn[MAX_THR], s_bp[MAX_THR];
 
     const int t = blockIdx.x;
     const u32 tid = threadIdx.x;
     const u64 n = td[t].n;
     TState *st = B.ts + t;
+    if (REDO && !st->redo) return;
+    const bool sampled = !REDO && td[t].sampled != 0u;
+    const u32 scale = sampled ? (u32)SAMPLE_RATE : 1u; // a sampled histogram stands for the whole
     const u32 *h1 = B.hist1 + (size_t)t * L1_BINS;
     for (int j = tid; j < L1_MAGBINS; j += BLOCK) {
-        u32 cn = h1[L1_MAGBINS - 1 - j], cp = h1[L1_MAGBINS + j];
+        u32 cn = h1[L1_MAGBINS - 1 - j] * scale, cp = h1[L1_MAGBINS + j] * scale;
         A[j] = cn + cp;
         Bn[j] = cn;
     }
     for (int c = tid; c < COARSE; c += BLOCK) {
         u32 s = 0;
         for (int i = 0; i < 8; i++) s += h1[8 * c + i];
-        nc[c] = s;
+        nc[c] = s * scale;
     }
     __syncthreads();
     u32 total = block_excl_scan(A, A, L1_MAGBINS, tmp);
     const u32 total_neg = block_excl_scan(Bn, Bn, L1_MAGBINS, tmp);
-    if (tid == 0) {
+    if (tid == 0 && !sampled) { // (a sampled tensor gets these from the exact second histogram)
         if ((u64)total != n) atomicOr(&st->internal_err, 1u);
         st->n_neg = total_neg;
         // magnitude bins from 0x7f800000 >> 17 on hold Inf and NaN only
@@ -208,66 +332,88 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
 
     const u32 n_p = gd->n_p, n_o = gd->n_o, n_thr = n_p + n_o;
     if (tid < n_thr) {
-        u64 R;
-        if (tid < n_p)
-            R = n * (u64)gd->p_ppm[tid] / 1000000ull;
-        else
-            R = n - 1ull - n * (u64)gd->o_ppm[tid - n_p] / 1000000ull;
-        // first i in [0, 16384] with A[i] > R
-        int lo = 0, hi = L1_MAGBINS;
-        while (lo < hi) {
-            int mid = (lo + hi) >> 1;
-            if ((u64)A[mid] > R)
-                hi = mid;
-            else
-                lo = mid + 1;
+        const u64 R = threshold_rank(gd, tid, n);
+        // bin of a rank: last j in [0, 16384) with A[j] <= rank
+        auto bin_of = [&](u64 rank) -> u32 {
+            int lo = 0, hi = L1_MAGBINS;
+            while (lo < hi) {
+                int mid = (lo + hi) >> 1;
+                if ((u64)A[mid] > rank)
+                    hi = mid;
+                else
+                    lo = mid + 1;
+            }
+            return (u32)(lo > 0 ? lo - 1 : 0);
+        };
+        if (!sampled) {
+            const u32 j = bin_of(R);
+            s_j[tid] = s_jlo[tid] = s_jhi[tid] = j;
+            s_res[tid] = R - (u64)A[j];
+            s_bn[tid] = Bn[j];
+            s_bp[tid] = A[j] - Bn[j];
+            s_cn[tid] = h1[L1_MAGBINS - 1 - j];
+            s_cp[tid] = h1[L1_MAGBINS + j];
+        } else {
+            // The rank's bin is only predicted: all bins that may hold it are gathered.  The
+            // estimate of a cumulative count c from one tile in SAMPLE_RATE has a standard
+            // deviation of about sqrt(SAMPLE_RATE * c) for independent elements; tiles are not
+            // independent draws, so the margin is generous, and a miss is caught afterwards.
+            // (ranks 0 and n - 1 are not predicted: the second sweep takes the smallest and the
+            // largest magnitude directly, and nothing is gathered for them)
+            const u64 tail = R < n - R ? R + 1ull : n - R;
+            const u64 margin = (u64)(8.0 * sqrt((double)SAMPLE_RATE * (double)tail)) + 8ull * SAMPLE_RATE;
+            const u64 r_lo = R > margin ? R - margin : 0ull;
+            const u64 r_hi = R + margin < n ? R + margin : n - 1ull;
+            const u64 last = total ? (u64)total - 1ull : 0ull; // (the scaled total is not n)
+            s_jlo[tid] = bin_of(r_lo < last ? r_lo : last);
+            u32 jh = bin_of(r_hi < last ? r_hi : last);
+            if (r_hi >= last && jh + 1u < (u32)L1_MAGBINS) jh++; // the sample may have missed the top
+            s_jhi[tid] = jh;
+            s_j[tid] = 0u;
+            if (R == 0ull || R == n - 1ull) { // an empty window
+                s_jlo[tid] = 1u;
+                s_jhi[tid] = 0u;
+            }
         }
-        int j = lo - 1;
-        s_j[tid] = (u32)j;
-        s_res[tid] = R - (u64)A[j];
+        st->thr_jlo[tid] = s_jlo[tid];
+        st->thr_jhi[tid] = s_jhi[tid];
     }
     __syncthreads();
     if (tid == 0) {
-        u32 nb = 0;
-        u64 off = 0;
+        if (!sampled) make_buckets(st, n_thr, s_j, s_res, s_bn, s_bp, s_cn, s_cp);
         st->n_thr = n_thr;
-        for (u32 q = 0; q < n_thr; q++) {
-            u32 j = s_j[q];
-            u32 found = nb;
-            for (u32 k = 0; k < nb; k++)
-                if (st->bucket_magbin[k] == j) found = k;
-            if (found == nb) {
-                st->bucket_magbin[nb] = j;
-                st->bucket_below_neg[nb] = Bn[j];
-                st->bucket_below_pos[nb] = A[j] - Bn[j];
-                u32 cn = h1[L1_MAGBINS - 1 - j], cp = h1[L1_MAGBINS + j];
-                st->bucket_cnt_neg[nb] = cn;
-                st->bucket_cnt_pos[nb] = cp;
-                st->bucket_off[nb] = off;
-                st->bucket_cursor[nb] = 0u;
-                off += (u64)cn + cp;
-                nb++;
-            }
-            st->thr_bucket[q] = found;
-            st->thr_res[q] = s_res[q];
-        }
-        st->n_buckets = nb;
     }
     __syncthreads();
 
     // second-level table: smallest target population whose bin total fits
-    // (exact zeros are counted, never gathered or sorted: they do not ask for bins)
+    // (exact zeros are counted, never gathered or sorted: they do not ask for bins; a prefix with
+    // gathered first-level bins gets at least 8 bins, so that the second histogram resolves them)
     if (tid == 0) {
         const u32 zc = ZERO_KEY >> COARSE_SHIFT;
         const u64 nz = st->n_zero;
         nc[zc] = (u64)nc[zc] > nz ? (u32)(nc[zc] - nz) : 1u;
+        if (sampled) {
+            st->n_zero = 0ull; // (an estimate: the second sweep counts the zeros exactly)
+            st->mag_min = 0xFFFFFFFFu;
+            st->mag_max = 0u;
+        }
     }
     __syncthreads();
+    // gathered first-level bins of this thread's key prefixes (prefix c = tid + BLOCK * k)
+    u32 my_flags[COARSE / BLOCK];
+#pragma unroll
+    for (int k = 0; k < COARSE / BLOCK; k++) my_flags[k] = cell_flags(tid + (u32)BLOCK * k, s_jlo, s_jhi, n_thr);
+    auto depth_of = [&](int c, u64 target, int k) -> u32 {
+        u32 d = nc[c] ? depth_for(nc[c], target) : 0u;
+        if (sampled && d < 3u && my_flags[k]) d = 3u;
+        return d;
+    };
     u64 lo = 1, hi = n;
     while (lo < hi) {
         u64 mid = lo + ((hi - lo) >> 1);
         u32 s = 0;
-        for (int c = tid; c < COARSE; c += BLOCK) s += nc[c] ? (1u << depth_for(nc[c], mid)) : 1u;
+#pragma unroll
+        for (int k = 0; k < COARSE / BLOCK; k++) s += 1u << depth_of(tid + BLOCK * k, mid, k);
         s = wave_sum(s);
         __syncthreads();
         if ((tid & 63u) == 0u) tmp[tid >> 6] = s;
@@ -281,21 +427,17 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     }
     __syncthreads();
     u32 *cnt = A; // reuse: bins per coarse prefix
-    for (int c = tid; c < COARSE; c += BLOCK) cnt[c] = nc[c] ? (1u << depth_for(nc[c], lo)) : 1u;
+#pragma unroll
+    for (int k = 0; k < COARSE / BLOCK; k++) cnt[tid + BLOCK * k] = 1u << depth_of(tid + BLOCK * k, lo, k);
     __syncthreads();
     u32 nb2 = block_excl_scan(cnt, Bn, COARSE, tmp); // Bn[c] = base
     u32 *tab = B.table2 + (size_t)t * COARSE;
-    for (int c = tid; c < COARSE; c += BLOCK) {
-        u32 d = nc[c] ? depth_for(nc[c], lo) : 0u;
-        // top byte: which of the 8 first-level bins under this key prefix hold a threshold
-        // (magnitude bin j is first-level key bin 16384 + j for positive, 16383 - j for negative)
-        u32 flag = 0u;
-        for (u32 q = 0; q < n_thr; q++) {
-            const u32 kp = (u32)L1_MAGBINS + s_j[q], kn = (u32)L1_MAGBINS - 1u - s_j[q];
-            if ((kp >> 3) == (u32)c) flag |= bucket_flag(kp);
-            if ((kn >> 3) == (u32)c) flag |= bucket_flag(kn);
-        }
-        tab[c] = flag | (Bn[c] << 5) | d;
+#pragma unroll
+    for (int k = 0; k < COARSE / BLOCK; k++) {
+        const int c = tid + BLOCK * k;
+        const u32 d = depth_of(c, lo, k);
+        // top byte: which of the 8 first-level bins under this key prefix are gathered
+        tab[c] = my_flags[k] | (Bn[c] << 5) | d;
     }
     if (tid == 0) {
         st->nb2 = nb2;
@@ -304,88 +446,240 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     }
 }
 
+// After the second histogram of a tensor whose sweep 1 was sampled: the exact figures that sweep 1
+// gives otherwise (size, negative count, non-finite values) and, for every threshold, the
+// first-level magnitude bin that holds its rank, with the exact counts below and inside it by sign.
+// The bins resolve only where the table has at least 8 bins under a key prefix, which k_plan1
+// arranged for the bins it had gathered; a rank outside them sends the tensor through the exact
+// sweeps again (TState::redo).
+__global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
+                                                  const GridDesc *__restrict__ gd, Bufs B, u32 force_miss)
+{
+    __shared__ u32 cc[COARSE];             // exact count under every key prefix
+    __shared__ u32 Am[COARSE / 2 + 1];     // per magnitude prefix, both signs -> exclusive prefix
+    __shared__ u32 Nm[COARSE / 2 + 1];     // negative ones -> exclusive prefix
+    __shared__ u32 tmp[BLOCK / 64 + 1];
+    __shared__ u32 s_j[MAX_THR], s_cn[MAX_THR], s_cp[MAX_THR], s_miss;
+    __shared__ u64 s_res[MAX_THR], s_bn[MAX_THR], s_bp[MAX_THR];
+    const int t = blockIdx.x;
+    const u32 tid = threadIdx.x;
+    if (!td[t].sampled) return;
+    const u64 n = td[t].n;
+    TState *st = B.ts + t;
+    const u32 *tab = B.table2 + (size_t)t * COARSE;
+    u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
+    constexpr int HALF = COARSE / 2;
+    if (tid == 0) s_miss = force_miss;
+    for (int c = tid; c < COARSE; c += BLOCK) {
+        const u32 e = tab[c], base = (e >> 5) & 0x7fffu, nb = 1u << (e & 31u);
+        u32 s = 0;
+        for (u32 i = 0; i < nb; i++) s += h2[base + i];
+        cc[c] = s;
+    }
+    __syncthreads();
+    for (int m = tid; m < HALF; m += BLOCK) {
+        Am[m] = cc[HALF + m] + cc[HALF - 1 - m];
+        Nm[m] = cc[HALF - 1 - m];
+    }
+    __syncthreads();
+    const u32 total = block_excl_scan(Am, Am, HALF, tmp);
+    const u32 total_neg = block_excl_scan(Nm, Nm, HALF, tmp);
+    if (tid == 0) {
+        if ((u64)total != n) atomicOr(&st->internal_err, 1u);
+        st->n_neg = total_neg;
+        if (total - Am[0x7f800000u >> COARSE_SHIFT] != 0u) st->nonfinite = 1u;
+    }
+    const u32 n_thr = gd->n_p + gd->n_o;
+    if (tid < n_thr && (threshold_rank(gd, tid, n) == 0ull || threshold_rank(gd, tid, n) == n - 1ull)) {
+        s_j[tid] = NO_BUCKET; // the smallest / largest magnitude, taken by the second sweep
+        s_res[tid] = threshold_rank(gd, tid, n) == 0ull ? 0ull : 1ull;
+    } else if (tid < n_thr) {
+        const u64 R = threshold_rank(gd, tid, n);
+        int lo = 0, hi = HALF; // last magnitude prefix m with Am[m] <= R
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if ((u64)Am[mid] > R)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const u32 m = (u32)(lo > 0 ? lo - 1 : 0);
+        const u32 ep = tab[HALF + m], en = tab[HALF - 1 - m];
+        const u32 dp = ep & 31u, dn = en & 31u;
+        bool ok = (dp >= 3u || cc[HALF + m] == 0u) && (dn >= 3u || cc[HALF - 1 - m] == 0u);
+        if (ok) {
+            u64 cum = Am[m], cum_neg = Nm[m];
+            u32 found = 8u, fcn = 0u, fcp = 0u;
+            for (u32 i = 0; i < 8u; i++) { // the 8 first-level magnitude bins of the prefix, ascending
+                u32 cp = 0u, cn = 0u;
+                if (dp >= 3u) {
+                    const u32 per = 1u << (dp - 3u), b0 = ((ep >> 5) & 0x7fffu) + i * per;
+                    for (u32 k = 0; k < per; k++) cp += h2[b0 + k];
+                }
+                if (dn >= 3u) { // negative keys ascend as the magnitude descends
+                    const u32 per = 1u << (dn - 3u), b0 = ((en >> 5) & 0x7fffu) + (7u - i) * per;
+                    for (u32 k = 0; k < per; k++) cn += h2[b0 + k];
+                }
+                if (R < cum + cp + cn) {
+                    found = i;
+                    fcn = cn;
+                    fcp = cp;
+                    break;
+                }
+                cum += (u64)cp + cn;
+                cum_neg += cn;
+            }
+            const u32 j = m * 8u + found;
+            ok = found < 8u && j >= st->thr_jlo[tid] && j <= st->thr_jhi[tid];
+            if (ok) {
+                s_j[tid] = j;
+                s_res[tid] = R - cum;
+                s_bn[tid] = cum_neg;
+                s_bp[tid] = cum - cum_neg;
+                s_cn[tid] = fcn;
+                s_cp[tid] = fcp;
+            }
+        }
+        if (!ok) s_miss = 1u;
+    }
+    __syncthreads();
+    if (s_miss) { // the exact sweeps start from cleared histograms and zero count
+        u32 *h1 = B.hist1 + (size_t)t * L1_BINS;
+        for (int i = tid; i < L2_BINS; i += BLOCK) {
+            h1[i] = 0u;
+            h2[i] = 0u;
+        }
+        if (tid == 0) {
+            st->redo = 1u;
+            st->n_zero = 0ull;
+            st->nonfinite = 0u;
+        }
+        return;
+    }
+    if (tid == 0) make_buckets(st, n_thr, s_j, s_res, s_bn, s_bp, s_cn, s_cp);
+}
+
 // ------------------------------------------------------------------------------------------
-// exact thresholds from the gathered buckets (one workgroup per threshold)
+// exact thresholds from the gathered buckets (one workgroup per tensor, all thresholds together)
 // ------------------------------------------------------------------------------------------
 constexpr int TSEL = 1024;
 
 // The gathered keys of a tensor lie in 16 fragments (one per wave) per (workgroup, tensor) unit,
-// all buckets mixed; a threshold looks at the keys whose magnitude falls in its own bucket.
-struct Fragments {
-    const u32 *pool;      // tensor's gather region
-    const u64 *start;     // per unit: first element of the unit's region
-    const u32 *sub;       // per unit: size of one wave's share of the region
-    const u32 *count;     // per unit and wave: keys in the fragment
-    const u32 *ids;       // units of this tensor
-    u32 n_units;          // fragments = 16 * n_units
-};
-
-// k-th smallest magnitude among the gathered keys of magnitude bin mb (all share the bits above
-// bit 16), and the numbers of the bin's keys below and above it by sign.  Two counting rounds over
-// 9 and 8 bits with LDS histograms kept per sign, so that no third pass has to count the classes:
-// keys below = bins below the chosen one in round 1 + digits below the chosen one in round 2.
-// Returns the low 17 bits; cn = {#(m < tau, negative), #(m < tau, positive), #(m > tau, negative),
-// #(m > tau, positive)}; *seen = number of keys of the bin that were found.
-__device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *hist /*[2][512]*/,
-                                       u32 *sh /*[8]*/, u32 *seen, u32 (&cn)[4])
+// all buckets mixed.  Every threshold wants the k-th smallest magnitude among the keys of its
+// bucket (one first-level magnitude bin: all keys share the bits above bit 16) and the numbers of
+// the bucket's keys below and above it by sign.  Two passes over the fragments with LDS histograms
+// kept per sign: 9 bits per bucket in the first, the remaining 8 bits per threshold (inside the
+// bin its first pass chose) in the second; the counts of the classes fall out of the histograms:
+// keys below = bins below the chosen one in pass 1 + digits below the chosen one in pass 2.  A byte
+// table over the magnitude bins names the bucket of a key, so a key costs one table read and one
+// or two LDS atomics however many thresholds the grid has.
+__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td,
+                                                     const u32 *__restrict__ t_fu_off,
+                                                     const u32 *__restrict__ t_fu_ids, Bufs B)
 {
-    const u32 tid = threadIdx.x;
-    u32 prefix = 0u; // chosen bits so far (of the low 17)
-    cn[0] = cn[1] = cn[2] = cn[3] = 0u;
+    __shared__ u32 hist[MAX_THR * 1024];      // [bucket or threshold][sign][512]
+    __shared__ unsigned char which[L1_MAGBINS]; // bucket of a magnitude bin + 1, or 0
+    __shared__ u32 s_k[MAX_THR], s_prefix[MAX_THR], s_want[MAX_THR], s_cn[MAX_THR][4], s_seen[MAX_THR];
+    __shared__ u32 s_members[MAX_THR][MAX_THR], s_nmem[MAX_THR]; // thresholds of each bucket
+    const int t = blockIdx.x;
+    TState *st = B.ts + t;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 n_thr = st->n_thr, nb = st->n_buckets;
+    const u32 *pool = B.pool + td[t].pool_thr;
+    const u32 *ids = t_fu_ids + t_fu_off[t];
+    const u32 n_units = t_fu_off[t + 1] - t_fu_off[t];
+
+    for (u32 i = tid; i < (u32)L1_MAGBINS / 4u; i += TSEL) reinterpret_cast<u32 *>(which)[i] = 0u;
+    if (tid < (u32)MAX_THR) s_nmem[tid] = 0u;
+    __syncthreads();
+    if (tid < nb) which[st->bucket_magbin[tid]] = (unsigned char)(tid + 1u);
+    if (tid == 0) {
+        for (u32 q = 0; q < n_thr; q++) { // which thresholds take part, and their ranks
+            s_want[q] = 0xFFFFFFFFu;
+            s_prefix[q] = 0u;
+            s_cn[q][0] = s_cn[q][1] = s_cn[q][2] = s_cn[q][3] = 0u;
+            const u32 bq = st->thr_bucket[q];
+            if (bq == NO_BUCKET) continue; // rank 0 or n - 1 of a tensor whose first sweep was sampled
+            const u32 mb = st->bucket_magbin[bq];
+            const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
+            const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
+            const u64 res = st->thr_res[q];
+            if (res < zeros) continue; // the threshold is 0
+            if (res - zeros >= expect) {
+                atomicOr(&st->internal_err, 8u);
+                continue;
+            }
+            s_k[q] = (u32)(res - zeros);
+            s_want[q] = mb << 9; // (completed by the chosen 9-bit prefix after the first pass)
+            s_members[bq][s_nmem[bq]++] = q;
+        }
+    }
+    __syncthreads();
+
     for (int round = 0; round < 2; round++) {
-        const u32 shift = round == 0 ? 8u : 0u, nbin = round == 0 ? 512u : 256u;
-        for (u32 i = tid; i < 1024u; i += TSEL) hist[i] = 0u;
+        const u32 n_slots = (round == 0 ? nb : n_thr) * 1024u;
+        for (u32 i = tid; i < n_slots; i += TSEL) hist[i] = 0u;
         __syncthreads();
-        for (u32 u = tid >> 6; u < 16u * f.n_units; u += TSEL / 64) { // one fragment per wave
-            const u32 fu = f.ids[u >> 4];
-            const u32 *list = f.pool + f.start[fu] + (u64)(u & 15u) * f.sub[fu];
-            const u32 c = f.count[(size_t)fu * 16 + (u & 15u)];
-            for (u32 i0 = tid & 63u; i0 < c; i0 += 256u) {
+        for (u32 u = wave; u < 16u * n_units; u += TSEL / 64) { // one fragment per wave
+            const u32 fu = ids[u >> 4];
+            const u32 *list = pool + B.unit_start[fu] + (u64)(u & 15u) * B.unit_sub[fu];
+            const u32 c = B.unit_thr[(size_t)fu * 16 + (u & 15u)];
+            for (u32 i0 = lane; i0 < c; i0 += 256u) {
                 u32 kk[4];
 #pragma unroll
                 for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
+                    if (i0 + j * 64u >= c) continue;
                     const u32 mag = mag_of_key(kk[j]);
-                    if (i0 + j * 64u >= c || (mag >> L1_SHIFT) != mb) continue;
-                    const u32 m = mag & 0x1FFFFu;
-                    if (round == 0 || (m >> 8) == prefix)
-                        atomicAdd(&hist[(key_is_neg(kk[j]) ? 0u : 512u) + ((m >> shift) & (nbin - 1u))], 1u);
+                    const u32 bk = which[mag >> L1_SHIFT];
+                    if (bk == 0u) continue; // (gathered for a window of bins, not in a bucket)
+                    const u32 sgn = key_is_neg(kk[j]) ? 0u : 512u;
+                    if (round == 0) {
+                        atomicAdd(&hist[(bk - 1u) * 1024u + sgn + ((mag >> 8) & 511u)], 1u);
+                    } else {
+                        const u32 nm = s_nmem[bk - 1u];
+                        for (u32 e = 0; e < nm; e++) {
+                            const u32 q = s_members[bk - 1u][e];
+                            if ((mag >> 8) == s_want[q]) atomicAdd(&hist[q * 1024u + sgn + (mag & 255u)], 1u);
+                        }
+                    }
                 }
             }
         }
         __syncthreads();
-        if (tid < 64u) { // 8 bins per lane
-            u32 ln[8], lp[8], sn = 0, sp = 0;
+        if (wave < n_thr && s_want[wave] != 0xFFFFFFFFu) { // wave q scans the histogram of threshold q
+            const u32 q = wave;
+            const u32 *hq = hist + (round == 0 ? st->thr_bucket[q] : q) * 1024u;
+            const u32 k = s_k[q];
+            u32 ln[8], lp[8], sn = 0, sp = 0; // 8 bins per lane
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                ln[j] = hist[tid * 8u + j];
-                lp[j] = hist[512u + tid * 8u + j];
+                ln[j] = hq[lane * 8u + j];
+                lp[j] = hq[512u + lane * 8u + j];
                 sn += ln[j];
                 sp += lp[j];
             }
-            u32 incn = sn, incp = sp;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const u32 vn = __shfl_up(incn, o), vp = __shfl_up(incp, o);
-                if ((int)tid >= o) {
-                    incn += vn;
-                    incp += vp;
-                }
-            }
-            const u32 totn = __shfl(incn, 63), totp = __shfl(incp, 63);
+            const u32 incn = wave_incl_scan(sn), incp = wave_incl_scan(sp);
+            const u32 totn = __builtin_amdgcn_readlane(incn, 63), totp = __builtin_amdgcn_readlane(incp, 63);
             u32 bn = incn - sn, bp = incp - sp; // keys in the bins before this lane's
-            if (round == 0 && tid == 63u) *seen = incn + incp;
+            if (round == 0 && lane == 63u) s_seen[q] = incn + incp;
             if (k >= bn + bp && k < incn + incp) {
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
                     if (k >= bn + bp && k < bn + bp + ln[j] + lp[j]) {
-                        sh[0] = tid * 8u + j;
-                        sh[1] = k - (bn + bp);
-                        sh[2] = bn;                    // below the chosen bin, by sign
-                        sh[3] = bp;
-                        sh[4] = totn - bn - ln[j];     // above it
-                        sh[5] = totp - bp - lp[j];
+                        const u32 digit = lane * 8u + j;
+                        s_k[q] = k - (bn + bp);
+                        s_cn[q][0] += bn;                   // below the chosen bin, by sign
+                        s_cn[q][1] += bp;
+                        s_cn[q][2] += totn - bn - ln[j];    // above it
+                        s_cn[q][3] += totp - bp - lp[j];
+                        if (round == 0) {
+                            s_prefix[q] = digit;
+                            s_want[q] |= digit;
+                        } else {
+                            s_prefix[q] = (s_prefix[q] << 8) | digit;
+                        }
                     }
                     bn += ln[j];
                     bp += lp[j];
@@ -393,53 +687,30 @@ __device__ inline u32 block_select_mag(const Fragments &f, u32 mb, u32 k, u32 *h
             }
         }
         __syncthreads();
-        prefix = (round == 0) ? sh[0] : ((prefix << 8) | sh[0]);
-        k = sh[1];
-        cn[0] += sh[2];
-        cn[1] += sh[3];
-        cn[2] += sh[4];
-        cn[3] += sh[5];
-        __syncthreads();
     }
-    return prefix;
-}
 
-__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td,
-                                                     const u32 *__restrict__ t_fu_off,
-                                                     const u32 *__restrict__ t_fu_ids, Bufs B)
-{
-    __shared__ u32 hist[1024];
-    __shared__ u32 sh[8];
-    __shared__ u32 s_seen;
-    const int t = blockIdx.x / MAX_THR;
-    const u32 q = blockIdx.x % MAX_THR;
-    TState *st = B.ts + t;
-    if (q >= st->n_thr) return;
-    const u32 tid = threadIdx.x;
-    const u32 bq = st->thr_bucket[q];
-    const u32 mb = st->bucket_magbin[bq];
-    Fragments f;
-    f.pool = B.pool + td[t].pool_thr;
-    f.start = B.unit_start;
-    f.sub = B.unit_sub;
-    f.count = B.unit_thr;
-    f.ids = t_fu_ids + t_fu_off[t];
-    f.n_units = t_fu_off[t + 1] - t_fu_off[t];
-    const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
-    const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
-    const u64 res = st->thr_res[q];
-    u32 tau = 0u;
-    // keys of the bucket below / above the threshold, by sign (the zeros were not gathered)
-    u32 cn[4] = {0u, 0u, st->bucket_cnt_neg[bq], (u32)(st->bucket_cnt_pos[bq] - zeros)};
-    if (res >= zeros) {
-        if (res - zeros >= expect) {
-            if (tid == 0) atomicOr(&st->internal_err, 8u);
+    if (tid < n_thr) {
+        const u32 q = tid;
+        const u32 bq = st->thr_bucket[q];
+        if (bq == NO_BUCKET) {
+            st->thr_mag[q] = st->thr_res[q] == 0ull ? st->mag_min : st->mag_max;
+            st->thr_lt_neg[q] = st->thr_lt_pos[q] = 0ull; // (used for a prune threshold: nothing below the minimum)
+            st->thr_gt_neg[q] = st->thr_gt_pos[q] = 0ull; // (used for a protect threshold: nothing above the maximum)
             return;
         }
-        tau = (mb << L1_SHIFT) | block_select_mag(f, mb, (u32)(res - zeros), hist, sh, &s_seen, cn);
-        if (tid == 0 && (u64)s_seen != expect) atomicOr(&st->internal_err, 4u);
-    }
-    if (tid == 0) {
+        const u32 mb = st->bucket_magbin[bq];
+        const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
+        u32 tau = 0u;
+        // keys of the bucket below / above the threshold, by sign (the zeros were not gathered)
+        u32 cn[4] = {0u, 0u, st->bucket_cnt_neg[bq], (u32)(st->bucket_cnt_pos[bq] - zeros)};
+        if (s_want[q] != 0xFFFFFFFFu) {
+            tau = (mb << L1_SHIFT) | s_prefix[q];
+            for (int i = 0; i < 4; i++) cn[i] = s_cn[q][i];
+            const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
+            if ((u64)s_seen[q] != expect) atomicOr(&st->internal_err, 4u);
+        } else if (st->thr_res[q] >= zeros) {
+            return; // (rank beyond the bucket: the error bit is set)
+        }
         const u64 n = td[t].n, n_neg = st->n_neg, n_pos = n - n_neg;
         st->thr_mag[q] = tau;
         st->thr_lt_neg[q] = st->bucket_below_neg[bq] + cn[0];
@@ -1277,7 +1548,8 @@ static hipError_t set_attrs()
 {
     if (g_attr_done) return hipSuccess;
     hipError_t e;
-    if ((e = hipFuncSetAttribute((const void *)k_plan1, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_plan1<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_plan1<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
@@ -1291,10 +1563,18 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     hipError_t e = set_attrs();
     if (e) return e;
     const Bufs &B = bt.bufs;
-    PROF("k_hist1", s, k_hist<1><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
-    PROF("k_plan1", s, k_plan1<<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
-    PROF("k_hist2", s, k_hist<2><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B));
-    PROF("k_thr_select", s, k_thr_select<<<bt.nT * MAX_THR, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
+    PROF("k_hist1", s, (k_hist<1, false><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
+    PROF("k_plan1", s, k_plan1<false><<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
+    PROF("k_hist2", s, (k_hist<2, false><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
+    if (bt.any_sampled) {
+        // tensors whose sweep 1 was sampled: exact figures from the second histogram; those whose
+        // thresholds were mispredicted take the exact sweeps (the kernels skip all other tensors)
+        PROF("k_plan1b", s, k_plan1b<<<bt.nT, BLOCK, 0, s>>>(bt.td, bt.gd, B, bt.force_miss ? 1u : 0u));
+        PROF("k_hist1_redo", s, (k_hist<1, true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
+        PROF("k_plan1_redo", s, k_plan1<true><<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
+        PROF("k_hist2_redo", s, (k_hist<2, true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
+    }
+    PROF("k_thr_select", s, k_thr_select<<<bt.nT, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     if ((e = launch_edges(bt, s))) return e;
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));

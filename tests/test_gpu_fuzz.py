@@ -71,3 +71,32 @@ def test_chunk_boundaries_of_the_delta(ctx):
     prevs = [family(rng, k % 3, n) for k, n in enumerate(sizes)]
     curs = [step(rng, x, k) for k, x in enumerate(prevs)]
     run_pipeline(ctx, prevs, curs, synth.grid_small(), synth.EPS_DEFAULT, want_perm=False)
+
+
+@pytest.mark.parametrize("mode", ["sampled", "sampled_all_missed"])
+def test_sampled_first_sweep(mode):
+    """Large tensors read one tile in eight in the first sweep and predict where the thresholds
+    fall; INSHR_SAMPLE_MIN_N=1 does that for every tensor, INSHR_SAMPLE_FORCE_MISS=1 treats every
+    prediction as wrong (both exact sweeps are then repeated).  The last tensor's sampled tiles are
+    a hundred times larger than the others, so its predictions are wrong by themselves.  Results
+    must not depend on any of this."""
+    import os
+    from paper_2306_11800_amd import api
+    env = {"INSHR_SAMPLE_MIN_N": "1"}
+    if mode == "sampled_all_missed":
+        env["INSHR_SAMPLE_FORCE_MISS"] = "1"
+    os.environ.update(env)
+    try:
+        c = api.Context(torch.device("cuda:0"))
+    finally:
+        for k in env:
+            del os.environ[k]
+    rng = np.random.default_rng(105)
+    sizes = [5, 16_384, 40_000, 131_072, 200_003, 300_001, 16_384 * 24 + 77]
+    prevs = [family(rng, k, n) for k, n in zip([0, 5, 3, 6, 8, 9, 0], sizes)]
+    biased = prevs[-1].reshape(-1)
+    for tile in range(0, biased.size // 16_384, 8):
+        biased[tile * 16_384:(tile + 1) * 16_384] *= 100.0
+    curs = [step(rng, x, k) for k, x in enumerate(prevs)]
+    run_pipeline(c, prevs, curs, synth.grid_full(), synth.EPS_DEFAULT, want_perm=False)
+    c.close()
