@@ -63,7 +63,7 @@ typedef struct inshr_ctx inshr_ctx; /* opaque: one device, one stream, scratch m
  * limit).  A search over tensors of N elements in total needs about 8*N bytes plus about 1.5 MB per
  * tensor; a call that needs more than the limit returns INSHR_E_CAPACITY.
  * Environment read here (test and tuning switches; results never depend on them):
- * INSHR_SAMPLE_MIN_N (default 4194304): tensors with at least this many elements read one tile in
+ * INSHR_SAMPLE_MIN_N (default 16777216): tensors with at least this many elements read one tile in
  * eight in the first sweep of a search and predict where the thresholds fall (a wrong prediction
  * repeats the exact sweeps for that tensor); INSHR_SAMPLE_FORCE_MISS=1 treats every prediction as
  * wrong; INSHR_SAMPLE_DEBUG=1 prints how many tensors were sampled and repeated;

@@ -35,7 +35,7 @@ struct inshr_ctx {
     int wg_per_cu = 2;
     bool lds_ordered = false; // same-address LDS atomics return in lane order (checked at creation)
     // tensors of at least this many elements get a sampled first sweep (INSHR_SAMPLE_MIN_N; 0 = never)
-    uint64_t sample_min_n = 4ull << 20;
+    uint64_t sample_min_n = 16ull << 20;
     bool sample_force_miss = false; // INSHR_SAMPLE_FORCE_MISS=1 (tests): always take the exact sweeps again
     std::vector<char> batch_sampled;
     std::string last_err;
@@ -424,6 +424,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         for (uint32_t t = 0; t < nT; t++) {
             n_sampled += c->batch_sampled.size() > t && c->batch_sampled[t] ? 1u : 0u;
             n_redo += hts[t].redo ? 1u : 0u;
+            if (hts[t].redo)
+                fprintf(stderr, "inshr_search: tensor %u (n = %llu) repeated, thresholds missed: 0x%x\n", t,
+                        (unsigned long long)tensors[t].n, hts[t].redo >> 1);
         }
         fprintf(stderr, "inshr_search: %u tensors, %u with a sampled first sweep, %u of them repeated\n",
                 nT, n_sampled, n_redo);

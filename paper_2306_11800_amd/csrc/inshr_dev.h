@@ -153,6 +153,14 @@ struct TState {
     u32 redo;                          // a sampled sweep 1 mispredicted a threshold: the tensor takes
                                        // the exact sweeps again
     u32 thr_jlo[MAX_THR], thr_jhi[MAX_THR]; // first-level magnitude bins gathered for each threshold
+    // exact selection inside the buckets (k_thr_setup / k_thr_count / k_thr_pick)
+    u32 sel_k[MAX_THR];                // rank still to resolve inside the chosen bins
+    u32 sel_want[MAX_THR];             // magnitude >> 8 of the keys that still take part, or ~0: none
+    u32 sel_prefix[MAX_THR];           // chosen bits of the low 17
+    u32 sel_cn[MAX_THR][4];            // keys of the bucket below (neg, pos) / above (neg, pos) so far
+    u32 sel_seen[MAX_THR];             // keys of the bucket that were found
+    u32 sel_nmem[MAX_THR];             // thresholds that share bucket b ...
+    unsigned char sel_members[MAX_THR][MAX_THR]; // ... and which
     u32 mag_min, mag_max;              // smallest / largest magnitude image (sampled first sweep only:
                                        // the thresholds of rank 0 and n - 1 are these)
     u32 thr_bucket[MAX_THR];

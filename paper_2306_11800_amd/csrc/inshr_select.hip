@@ -3,7 +3,7 @@
 //
 //   sweep 1  k_hist<1>     LDS histogram of key >> 17 (32768 bins), sum of squares, exact zeros
 //                          (negative and non-finite counts follow from the histogram).  Tensors of
-//                          4 Mi elements or more read only one tile in eight here ("sampled").
+//                          16 Mi elements or more read only one tile in eight here ("sampled").
 //   k_plan1                per tensor: first-level magnitude bin ("bucket") of every prune /
 //                          protect threshold rank; a key -> bin table whose bins hold about
 //                          n / 32768 elements each.  From a sampled histogram the bucket is only
@@ -19,8 +19,8 @@
 //                          threshold from the second histogram; a bucket outside its window marks
 //                          the tensor, and k_hist<1>, k_plan1, k_hist<2> run once more for the
 //                          marked tensors alone, unsampled (the results never depend on sampling).
-//   k_thr_select           exact thresholds and class counts from the gathered buckets, all
-//                          thresholds of a tensor in two passes over its gathered keys
+//   k_thr_setup/count/pick exact thresholds and class counts from the gathered buckets: all
+//                          thresholds of a tensor in two counting passes over its gathered keys
 //   k_plan2                exact rank of every boundary of every (prune, protect) pair -> its bin;
 //                          only those bins (and the bins of the class edges) are "active";
 //                          groups of consecutive active bins
@@ -362,9 +362,14 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
             // largest magnitude directly, and nothing is gathered for them)
             const u64 tail = R < n - R ? R + 1ull : n - R;
             const u64 margin = (u64)(8.0 * sqrt((double)SAMPLE_RATE * (double)tail)) + 8ull * SAMPLE_RATE;
-            const u64 r_lo = R > margin ? R - margin : 0ull;
-            const u64 r_hi = R + margin < n ? R + margin : n - 1ull;
-            const u64 last = total ? (u64)total - 1ull : 0ull; // (the scaled total is not n)
+            // The scaled total is not n.  A rank of the upper half is counted from the top of the
+            // scaled histogram, so that an error in the estimate of a large population below it
+            // (exact zeros that come in whole rows, say) does not shift it.
+            const u64 last = total ? (u64)total - 1ull : 0ull;
+            const bool from_top = R > n - 1ull - R;
+            const u64 Rs = !from_top ? R : (last > n - 1ull - R ? last - (n - 1ull - R) : 0ull);
+            const u64 r_lo = Rs > margin ? Rs - margin : 0ull;
+            const u64 r_hi = Rs + margin;
             s_jlo[tid] = bin_of(r_lo < last ? r_lo : last);
             u32 jh = bin_of(r_hi < last ? r_hi : last);
             if (r_hi >= last && jh + 1u < (u32)L1_MAGBINS) jh++; // the sample may have missed the top
@@ -455,7 +460,6 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
 __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
                                                   const GridDesc *__restrict__ gd, Bufs B, u32 force_miss)
 {
-    __shared__ u32 cc[COARSE];             // exact count under every key prefix
     __shared__ u32 Am[COARSE / 2 + 1];     // per magnitude prefix, both signs -> exclusive prefix
     __shared__ u32 Nm[COARSE / 2 + 1];     // negative ones -> exclusive prefix
     __shared__ u32 tmp[BLOCK / 64 + 1];
@@ -470,16 +474,15 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
     u32 *h2 = B.hist2 + (size_t)t * L2_BINS;
     constexpr int HALF = COARSE / 2;
     if (tid == 0) s_miss = force_miss;
-    for (int c = tid; c < COARSE; c += BLOCK) {
+    extern __shared__ u32 pre2[]; // [L2_BINS + 1] exclusive prefix of the second histogram
+    block_excl_scan(h2, pre2, L2_BINS, tmp);
+    auto cc = [&](u32 c) -> u32 { // exact count under key prefix c
         const u32 e = tab[c], base = (e >> 5) & 0x7fffu, nb = 1u << (e & 31u);
-        u32 s = 0;
-        for (u32 i = 0; i < nb; i++) s += h2[base + i];
-        cc[c] = s;
-    }
-    __syncthreads();
+        return pre2[base + nb] - pre2[base];
+    };
     for (int m = tid; m < HALF; m += BLOCK) {
-        Am[m] = cc[HALF + m] + cc[HALF - 1 - m];
-        Nm[m] = cc[HALF - 1 - m];
+        Am[m] = cc(HALF + m) + cc(HALF - 1 - m);
+        Nm[m] = cc(HALF - 1 - m);
     }
     __syncthreads();
     const u32 total = block_excl_scan(Am, Am, HALF, tmp);
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
         const u32 m = (u32)(lo > 0 ? lo - 1 : 0);
         const u32 ep = tab[HALF + m], en = tab[HALF - 1 - m];
         const u32 dp = ep & 31u, dn = en & 31u;
-        bool ok = (dp >= 3u || cc[HALF + m] == 0u) && (dn >= 3u || cc[HALF - 1 - m] == 0u);
+        bool ok = (dp >= 3u || cc(HALF + m) == 0u) && (dn >= 3u || cc(HALF - 1 - m) == 0u);
         if (ok) {
             u64 cum = Am[m], cum_neg = Nm[m];
             u32 found = 8u, fcn = 0u, fcp = 0u;
@@ -514,11 +517,11 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
                 u32 cp = 0u, cn = 0u;
                 if (dp >= 3u) {
                     const u32 per = 1u << (dp - 3u), b0 = ((ep >> 5) & 0x7fffu) + i * per;
-                    for (u32 k = 0; k < per; k++) cp += h2[b0 + k];
+                    cp = pre2[b0 + per] - pre2[b0];
                 }
                 if (dn >= 3u) { // negative keys ascend as the magnitude descends
                     const u32 per = 1u << (dn - 3u), b0 = ((en >> 5) & 0x7fffu) + (7u - i) * per;
-                    for (u32 k = 0; k < per; k++) cn += h2[b0 + k];
+                    cn = pre2[b0 + per] - pre2[b0];
                 }
                 if (R < cum + cp + cn) {
                     found = i;
@@ -540,7 +543,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
                 s_cp[tid] = fcp;
             }
         }
-        if (!ok) s_miss = 1u;
+        if (!ok) atomicOr(&s_miss, 2u << tid); // (bit 0: forced)
     }
     __syncthreads();
     if (s_miss) { // the exact sweeps start from cleared histograms and zero count
@@ -550,7 +553,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
             h2[i] = 0u;
         }
         if (tid == 0) {
-            st->redo = 1u;
+            st->redo = s_miss; // which thresholds missed (bit q + 1), for diagnosis
             st->n_zero = 0ull;
             st->nonfinite = 0u;
         }
@@ -560,135 +563,162 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
 }
 
 // ------------------------------------------------------------------------------------------
-// exact thresholds from the gathered buckets (one workgroup per tensor, all thresholds together)
+// exact thresholds from the gathered buckets
 // ------------------------------------------------------------------------------------------
 constexpr int TSEL = 1024;
+constexpr int SEL_HIST = MAX_THR * 1024; // words of a tensor's selection histograms ([slot][sign][512])
 
 // The gathered keys of a tensor lie in 16 fragments (one per wave) per (workgroup, tensor) unit,
 // all buckets mixed.  Every threshold wants the k-th smallest magnitude among the keys of its
 // bucket (one first-level magnitude bin: all keys share the bits above bit 16) and the numbers of
-// the bucket's keys below and above it by sign.  Two passes over the fragments with LDS histograms
-// kept per sign: 9 bits per bucket in the first, the remaining 8 bits per threshold (inside the
-// bin its first pass chose) in the second; the counts of the classes fall out of the histograms:
-// keys below = bins below the chosen one in pass 1 + digits below the chosen one in pass 2.  A byte
-// table over the magnitude bins names the bucket of a key, so a key costs one table read and one
-// or two LDS atomics however many thresholds the grid has.
-__global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ td,
-                                                     const u32 *__restrict__ t_fu_off,
-                                                     const u32 *__restrict__ t_fu_ids, Bufs B)
+// the bucket's keys below and above it by sign.  Two counting passes over the fragments, one
+// workgroup per unit, all thresholds of the tensor together: 9 bits per bucket in the first, the
+// remaining 8 bits per threshold (inside the bin its first pass chose) in the second.  A byte table
+// over the magnitude bins names the bucket of a key, so a key costs one table read and one or two
+// LDS atomics however many thresholds the grid has; the unit's counts are added to the tensor's
+// histograms in global memory (the first half of its first-level histogram, which is no longer
+// needed).  After each pass one workgroup per tensor picks the bins (wave q scans threshold q); the
+// histograms are kept per sign, so the counts of the classes fall out of them: keys below = bins
+// below the chosen one in pass 1 + digits below the chosen one in pass 2.
+__global__ __launch_bounds__(TSEL) void k_thr_setup(Bufs B)
 {
-    __shared__ u32 hist[MAX_THR * 1024];      // [bucket or threshold][sign][512]
+    const int t = blockIdx.x;
+    TState *st = B.ts + t;
+    u32 *gh = B.hist1 + (size_t)t * L1_BINS;
+    for (u32 i = threadIdx.x; i < (u32)SEL_HIST; i += TSEL) gh[i] = 0u;
+    if (threadIdx.x != 0) return;
+    const u32 n_thr = st->n_thr;
+    for (u32 b = 0; b < (u32)MAX_THR; b++) st->sel_nmem[b] = 0u;
+    for (u32 q = 0; q < n_thr; q++) { // which thresholds take part, and their ranks
+        st->sel_want[q] = 0xFFFFFFFFu;
+        st->sel_prefix[q] = 0u;
+        st->sel_seen[q] = 0u;
+        st->sel_cn[q][0] = st->sel_cn[q][1] = st->sel_cn[q][2] = st->sel_cn[q][3] = 0u;
+        const u32 bq = st->thr_bucket[q];
+        if (bq == NO_BUCKET) continue; // rank 0 or n - 1 of a tensor whose first sweep was sampled
+        const u32 mb = st->bucket_magbin[bq];
+        const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
+        const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
+        const u64 res = st->thr_res[q];
+        if (res < zeros) continue; // the threshold is 0
+        if (res - zeros >= expect) {
+            atomicOr(&st->internal_err, 8u);
+            continue;
+        }
+        st->sel_k[q] = (u32)(res - zeros);
+        st->sel_want[q] = mb << 9; // (completed by the chosen 9-bit prefix after the first pass)
+        st->sel_members[bq][st->sel_nmem[bq]++] = (unsigned char)q;
+    }
+}
+
+template <int ROUND>
+__global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td,
+                                                    const u32 *__restrict__ fu_tensor, Bufs B)
+{
+    __shared__ u32 hist[SEL_HIST];
     __shared__ unsigned char which[L1_MAGBINS]; // bucket of a magnitude bin + 1, or 0
-    __shared__ u32 s_k[MAX_THR], s_prefix[MAX_THR], s_want[MAX_THR], s_cn[MAX_THR][4], s_seen[MAX_THR];
-    __shared__ u32 s_members[MAX_THR][MAX_THR], s_nmem[MAX_THR]; // thresholds of each bucket
+    __shared__ u32 s_want[MAX_THR], s_nmem[MAX_THR];
+    __shared__ unsigned char s_members[MAX_THR][MAX_THR];
+    const u32 fu = blockIdx.x;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 c = B.unit_thr[(size_t)fu * 16 + wave]; // keys in this wave's fragment
+    if (__syncthreads_or(c != 0u) == 0) return;
+    const int t = (int)fu_tensor[fu];
+    const TState *st = B.ts + t;
+    const u32 n_thr = st->n_thr, nb = st->n_buckets;
+    const u32 n_slots = (ROUND == 0 ? nb : n_thr) * 1024u;
+    for (u32 i = tid; i < (u32)L1_MAGBINS / 4u; i += TSEL) reinterpret_cast<u32 *>(which)[i] = 0u;
+    for (u32 i = tid; i < n_slots; i += TSEL) hist[i] = 0u;
+    if (tid < (u32)MAX_THR) {
+        s_want[tid] = tid < n_thr ? st->sel_want[tid] : 0xFFFFFFFFu;
+        s_nmem[tid] = st->sel_nmem[tid];
+        for (u32 e = 0; e < (u32)MAX_THR; e++) s_members[tid][e] = st->sel_members[tid][e];
+    }
+    __syncthreads();
+    if (tid < nb) which[st->bucket_magbin[tid]] = (unsigned char)(tid + 1u);
+    __syncthreads();
+    const u32 *list = B.pool + td[t].pool_thr + B.unit_start[fu] + (u64)wave * B.unit_sub[fu];
+    for (u32 i0 = lane; i0 < c; i0 += 256u) {
+        u32 kk[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (i0 + j * 64u >= c) continue;
+            const u32 mag = mag_of_key(kk[j]);
+            const u32 bk = which[mag >> L1_SHIFT];
+            if (bk == 0u) continue; // (gathered for a window of bins, not in a bucket)
+            const u32 sgn = key_is_neg(kk[j]) ? 0u : 512u;
+            if (ROUND == 0) {
+                atomicAdd(&hist[(bk - 1u) * 1024u + sgn + ((mag >> 8) & 511u)], 1u);
+            } else {
+                const u32 nm = s_nmem[bk - 1u];
+                for (u32 e = 0; e < nm; e++) {
+                    const u32 q = s_members[bk - 1u][e];
+                    if ((mag >> 8) == s_want[q]) atomicAdd(&hist[q * 1024u + sgn + (mag & 255u)], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    u32 *gh = B.hist1 + (size_t)t * L1_BINS;
+    for (u32 i = tid; i < n_slots; i += TSEL) {
+        const u32 v = hist[i];
+        if (v) atomicAdd(&gh[i], v);
+    }
+}
+
+template <int ROUND>
+__global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td, Bufs B)
+{
     const int t = blockIdx.x;
     TState *st = B.ts + t;
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u32 n_thr = st->n_thr, nb = st->n_buckets;
-    const u32 *pool = B.pool + td[t].pool_thr;
-    const u32 *ids = t_fu_ids + t_fu_off[t];
-    const u32 n_units = t_fu_off[t + 1] - t_fu_off[t];
-
-    for (u32 i = tid; i < (u32)L1_MAGBINS / 4u; i += TSEL) reinterpret_cast<u32 *>(which)[i] = 0u;
-    if (tid < (u32)MAX_THR) s_nmem[tid] = 0u;
-    __syncthreads();
-    if (tid < nb) which[st->bucket_magbin[tid]] = (unsigned char)(tid + 1u);
-    if (tid == 0) {
-        for (u32 q = 0; q < n_thr; q++) { // which thresholds take part, and their ranks
-            s_want[q] = 0xFFFFFFFFu;
-            s_prefix[q] = 0u;
-            s_cn[q][0] = s_cn[q][1] = s_cn[q][2] = s_cn[q][3] = 0u;
-            const u32 bq = st->thr_bucket[q];
-            if (bq == NO_BUCKET) continue; // rank 0 or n - 1 of a tensor whose first sweep was sampled
-            const u32 mb = st->bucket_magbin[bq];
-            const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
-            const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
-            const u64 res = st->thr_res[q];
-            if (res < zeros) continue; // the threshold is 0
-            if (res - zeros >= expect) {
-                atomicOr(&st->internal_err, 8u);
-                continue;
-            }
-            s_k[q] = (u32)(res - zeros);
-            s_want[q] = mb << 9; // (completed by the chosen 9-bit prefix after the first pass)
-            s_members[bq][s_nmem[bq]++] = q;
-        }
-    }
-    __syncthreads();
-
-    for (int round = 0; round < 2; round++) {
-        const u32 n_slots = (round == 0 ? nb : n_thr) * 1024u;
-        for (u32 i = tid; i < n_slots; i += TSEL) hist[i] = 0u;
-        __syncthreads();
-        for (u32 u = wave; u < 16u * n_units; u += TSEL / 64) { // one fragment per wave
-            const u32 fu = ids[u >> 4];
-            const u32 *list = pool + B.unit_start[fu] + (u64)(u & 15u) * B.unit_sub[fu];
-            const u32 c = B.unit_thr[(size_t)fu * 16 + (u & 15u)];
-            for (u32 i0 = lane; i0 < c; i0 += 256u) {
-                u32 kk[4];
+    const u32 n_thr = st->n_thr;
+    u32 *gh = B.hist1 + (size_t)t * L1_BINS;
+    if (wave < n_thr && st->sel_want[wave] != 0xFFFFFFFFu) { // wave q scans the histogram of threshold q
+        const u32 q = wave;
+        const u32 *hq = gh + (ROUND == 0 ? st->thr_bucket[q] : q) * 1024u;
+        const u32 k = st->sel_k[q];
+        u32 ln[8], lp[8], sn = 0, sp = 0; // 8 bins per lane
 #pragma unroll
-                for (int j = 0; j < 4; j++) kk[j] = (i0 + j * 64u < c) ? list[i0 + j * 64u] : 0u;
-#pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    if (i0 + j * 64u >= c) continue;
-                    const u32 mag = mag_of_key(kk[j]);
-                    const u32 bk = which[mag >> L1_SHIFT];
-                    if (bk == 0u) continue; // (gathered for a window of bins, not in a bucket)
-                    const u32 sgn = key_is_neg(kk[j]) ? 0u : 512u;
-                    if (round == 0) {
-                        atomicAdd(&hist[(bk - 1u) * 1024u + sgn + ((mag >> 8) & 511u)], 1u);
-                    } else {
-                        const u32 nm = s_nmem[bk - 1u];
-                        for (u32 e = 0; e < nm; e++) {
-                            const u32 q = s_members[bk - 1u][e];
-                            if ((mag >> 8) == s_want[q]) atomicAdd(&hist[q * 1024u + sgn + (mag & 255u)], 1u);
-                        }
-                    }
-                }
-            }
+        for (int j = 0; j < 8; j++) {
+            ln[j] = hq[lane * 8u + j];
+            lp[j] = hq[512u + lane * 8u + j];
+            sn += ln[j];
+            sp += lp[j];
         }
-        __syncthreads();
-        if (wave < n_thr && s_want[wave] != 0xFFFFFFFFu) { // wave q scans the histogram of threshold q
-            const u32 q = wave;
-            const u32 *hq = hist + (round == 0 ? st->thr_bucket[q] : q) * 1024u;
-            const u32 k = s_k[q];
-            u32 ln[8], lp[8], sn = 0, sp = 0; // 8 bins per lane
+        const u32 incn = wave_incl_scan(sn), incp = wave_incl_scan(sp);
+        const u32 totn = __builtin_amdgcn_readlane(incn, 63), totp = __builtin_amdgcn_readlane(incp, 63);
+        u32 bn = incn - sn, bp = incp - sp; // keys in the bins before this lane's
+        if (ROUND == 0 && lane == 63u) st->sel_seen[q] = incn + incp;
+        if (k >= bn + bp && k < incn + incp) {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                ln[j] = hq[lane * 8u + j];
-                lp[j] = hq[512u + lane * 8u + j];
-                sn += ln[j];
-                sp += lp[j];
-            }
-            const u32 incn = wave_incl_scan(sn), incp = wave_incl_scan(sp);
-            const u32 totn = __builtin_amdgcn_readlane(incn, 63), totp = __builtin_amdgcn_readlane(incp, 63);
-            u32 bn = incn - sn, bp = incp - sp; // keys in the bins before this lane's
-            if (round == 0 && lane == 63u) s_seen[q] = incn + incp;
-            if (k >= bn + bp && k < incn + incp) {
-#pragma unroll
-                for (int j = 0; j < 8; j++) {
-                    if (k >= bn + bp && k < bn + bp + ln[j] + lp[j]) {
-                        const u32 digit = lane * 8u + j;
-                        s_k[q] = k - (bn + bp);
-                        s_cn[q][0] += bn;                   // below the chosen bin, by sign
-                        s_cn[q][1] += bp;
-                        s_cn[q][2] += totn - bn - ln[j];    // above it
-                        s_cn[q][3] += totp - bp - lp[j];
-                        if (round == 0) {
-                            s_prefix[q] = digit;
-                            s_want[q] |= digit;
-                        } else {
-                            s_prefix[q] = (s_prefix[q] << 8) | digit;
-                        }
+                if (k >= bn + bp && k < bn + bp + ln[j] + lp[j]) {
+                    const u32 digit = lane * 8u + j;
+                    st->sel_k[q] = k - (bn + bp);
+                    st->sel_cn[q][0] += bn;                   // below the chosen bin, by sign
+                    st->sel_cn[q][1] += bp;
+                    st->sel_cn[q][2] += totn - bn - ln[j];    // above it
+                    st->sel_cn[q][3] += totp - bp - lp[j];
+                    if (ROUND == 0) {
+                        st->sel_prefix[q] = digit;
+                        st->sel_want[q] |= digit;
+                    } else {
+                        st->sel_prefix[q] = (st->sel_prefix[q] << 8) | digit;
                     }
-                    bn += ln[j];
-                    bp += lp[j];
                 }
+                bn += ln[j];
+                bp += lp[j];
             }
         }
-        __syncthreads();
     }
-
+    __syncthreads();
+    if (ROUND == 0) { // the second pass starts from cleared histograms
+        for (u32 i = tid; i < (u32)SEL_HIST; i += TSEL) gh[i] = 0u;
+        return;
+    }
     if (tid < n_thr) {
         const u32 q = tid;
         const u32 bq = st->thr_bucket[q];
@@ -703,11 +733,11 @@ __global__ __launch_bounds__(TSEL) void k_thr_select(const TDesc *__restrict__ t
         u32 tau = 0u;
         // keys of the bucket below / above the threshold, by sign (the zeros were not gathered)
         u32 cn[4] = {0u, 0u, st->bucket_cnt_neg[bq], (u32)(st->bucket_cnt_pos[bq] - zeros)};
-        if (s_want[q] != 0xFFFFFFFFu) {
-            tau = (mb << L1_SHIFT) | s_prefix[q];
-            for (int i = 0; i < 4; i++) cn[i] = s_cn[q][i];
+        if (st->sel_want[q] != 0xFFFFFFFFu) {
+            tau = (mb << L1_SHIFT) | st->sel_prefix[q];
+            for (int i = 0; i < 4; i++) cn[i] = st->sel_cn[q][i];
             const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
-            if ((u64)s_seen[q] != expect) atomicOr(&st->internal_err, 4u);
+            if ((u64)st->sel_seen[q] != expect) atomicOr(&st->internal_err, 4u);
         } else if (st->thr_res[q] >= zeros) {
             return; // (rank beyond the bucket: the error bit is set)
         }
@@ -1551,6 +1581,7 @@ static hipError_t set_attrs()
     if ((e = hipFuncSetAttribute((const void *)k_plan1<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan1<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN1))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_plan2, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
+    if ((e = hipFuncSetAttribute((const void *)k_plan1b, hipFuncAttributeMaxDynamicSharedMemorySize, SM_PLAN2))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_split, hipFuncAttributeMaxDynamicSharedMemorySize, SM_SPLIT))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<true>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
     if ((e = hipFuncSetAttribute((const void *)k_bucket<false>, hipFuncAttributeMaxDynamicSharedMemorySize, SM_BUCKET))) return e;
@@ -1569,12 +1600,16 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     if (bt.any_sampled) {
         // tensors whose sweep 1 was sampled: exact figures from the second histogram; those whose
         // thresholds were mispredicted take the exact sweeps (the kernels skip all other tensors)
-        PROF("k_plan1b", s, k_plan1b<<<bt.nT, BLOCK, 0, s>>>(bt.td, bt.gd, B, bt.force_miss ? 1u : 0u));
+        PROF("k_plan1b", s, k_plan1b<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B, bt.force_miss ? 1u : 0u));
         PROF("k_hist1_redo", s, (k_hist<1, true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
         PROF("k_plan1_redo", s, k_plan1<true><<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
         PROF("k_hist2_redo", s, (k_hist<2, true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
     }
-    PROF("k_thr_select", s, k_thr_select<<<bt.nT, TSEL, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, B));
+    PROF("k_thr_setup", s, k_thr_setup<<<bt.nT, TSEL, 0, s>>>(B));
+    PROF("k_thr_count", s, k_thr_count<0><<<bt.n_units, TSEL, 0, s>>>(bt.td, bt.fu_tensor, B));
+    PROF("k_thr_pick", s, k_thr_pick<0><<<bt.nT, TSEL, 0, s>>>(bt.td, B));
+    PROF("k_thr_count", s, k_thr_count<1><<<bt.n_units, TSEL, 0, s>>>(bt.td, bt.fu_tensor, B));
+    PROF("k_thr_pick", s, k_thr_pick<1><<<bt.nT, TSEL, 0, s>>>(bt.td, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
     if ((e = launch_edges(bt, s))) return e;
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
