@@ -201,3 +201,29 @@ def test_largest_tensor_sketch_bins(ctx):
     got = unpack(q.packed, N, 9)
     assert torch.equal(got, sym), int((got != sym).sum())
     assert torch.equal(q.outlier_idx, torch.nonzero(prot).flatten().to(torch.int32))
+
+
+def test_tile_structured_tensor_under_the_sampled_sweep(ctx):
+    """24 Mi values whose scale changes from tile to tile by up to six decades: the first sweep of
+    the search samples one tile in eight for a tensor of this size, its predictions of the threshold
+    buckets are wrong here, and the exact sweeps are repeated for the tensor.  Thresholds,
+    boundaries and every symbol are compared with the torch definitions."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(79)
+    n = 24 << 20
+    x = torch.randn(n, dtype=torch.float32, device=dev, generator=g)
+    scale = torch.pow(10.0, torch.rand(n // 16384, device=dev, generator=g) * 6.0 - 3.0)
+    x = (x.view(-1, 16384) * scale[:, None]).reshape(-1).contiguous()
+    x[x == 0] = 1e-6
+    grid = synth.grid_full()
+    for cfg in ((8, 200000, 1000), (5, 0, 0)):
+        r = torch_quantize(x, cfg)
+        ctx.search([x], grid, synth.EPS_DEFAULT, want_scores=False)
+        q = ctx.quantize([x], [cfg], reuse_search=True)[0]
+        assert q.tau_prune == float(r["tau_p"]) and q.tau_outlier == float(r["tau_o"])
+        K = 1 << cfg[0]
+        assert torch.equal(q.boundaries[:K - 1].view(torch.int32), r["t"].view(torch.int32))
+        got = unpack(q.packed, n, cfg[0] + 1)
+        assert torch.equal(got, r["sym"]), int((got != r["sym"]).sum())
+        assert (q.n_kept, q.n_outlier) == (r["M"], int(r["prot"].sum()))
