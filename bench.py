@@ -227,6 +227,23 @@ def main():
             ctx.dequantize([b], out=[y])
             err_eq += float(((t.reshape(-1).double() - y.double()) ** 2).sum())
             sumsq += float((t.double() ** 2).sum())
+        # fewer bits with the same prune / protect fractions: how many tensors still meet eps, and
+        # the error of the whole checkpoint (Sec. 4.4: non-uniform bins need fewer of them)
+        sq_t = [float((t.double() ** 2).sum()) for t in cur]
+        fewer = {}
+        ctx.search(cur, grid, eps, want_scores=False)
+        for drop in (1, 2, 3, 4):
+            c2 = [(max(2, c[0] - drop), c[1], c[2]) for c in cfgs]
+            q2, _ = ctx.quantize_sketch(cur, c2, uni, alpha=0.01, sigma=0.2, max_iter=100, reuse_search=True)
+            ok, tot = 0, 0.0
+            for t, a, sq in zip(cur, q2, sq_t):
+                y = buf[:t.numel()]
+                ctx.dequantize([a], out=[y])
+                e = float(((t.reshape(-1).double() - y.double()) ** 2).sum())
+                tot += e
+                ok += 1 if e <= eps * sq else 0
+            fewer[f"bits-{drop}"] = {"tensors_within_eps": ok, "rel_sq_error": tot / sumsq}
+            del q2
         hist_ms = sprof["k_sketch_hist"][0] / 2
         sketch = {"ms_after_a_search": round(sdt * 1e3, 3), "ms_stand_alone": round(sdt_alone * 1e3, 3),
                   "alpha": 0.01, "sigma": 0.2, "max_iter": 100,
@@ -237,7 +254,8 @@ def main():
                   "rounds_mean": round(sum(i[1] for i in sk_info) / len(sk_info), 1),
                   "rounds_max": max(i[1] for i in sk_info),
                   "rel_sq_error_sketch_bins": err_sk / sumsq,
-                  "rel_sq_error_equal_frequency_bins": err_eq / sumsq}
+                  "rel_sq_error_equal_frequency_bins": err_eq / sumsq,
+                  "sketch_bins_with_fewer_bits": fewer}
         del q_sk, q_eq, buf
 
     cpu = None
