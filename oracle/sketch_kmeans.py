@@ -232,3 +232,30 @@ def quantize_values(x, sym_class, k, alpha, sigma, uniforms, max_iter):
     bnd = np.array([boundary_above(m) for m in midpoints(codebook.astype(np.float64))], dtype=np.float32)
     return dict(sym=sym, codebook=codebook, boundaries=bnd, rounds=r["rounds"], n_buckets=r["n_buckets"],
                 centres=r["centres"])
+
+
+def search_bits(x, sym_class, alpha, sigma, uniforms, max_iter, eps, bits_range=(2, 3, 4, 5, 6, 7, 8)):
+    """Sec. 5 restricted to the number of bins, with the bins of Algorithm 2: for every bit width b
+    the quantized values are clustered into 2^b clusters (draw r of every width uses uniforms[r], so
+    the start of a narrower width is a prefix of the start of a wider one), the squared error of the
+    tensor is sum_pruned x^2 + sum_quantized (x - its centre)^2 (fp64, protected values are exact),
+    and the fewest bits whose error is at most eps * sum x^2 are chosen; when no width qualifies, the
+    widest (feasible = False).  Returns dict(best_bits, feasible, sse per width, sumsq, runs)."""
+    x = np.asarray(x, np.float32).ravel()
+    xd = x.astype(np.float64)
+    sym_class = np.asarray(sym_class)
+    sumsq = float(np.sum(xd * xd))
+    pruned = float(np.sum(xd[sym_class == 0] ** 2))
+    q = sym_class >= 2
+    sse, runs = {}, {}
+    for b in bits_range:
+        r = quantize_values(x, sym_class, 1 << b, alpha, sigma, uniforms, max_iter)
+        cb = r["codebook"].astype(np.float64)
+        sse[b] = pruned + float(np.sum((xd[q] - cb[r["sym"][q].astype(np.int64) - 2]) ** 2))
+        runs[b] = r
+    best, feasible = max(bits_range), False
+    for b in sorted(bits_range):
+        if sse[b] <= eps * sumsq:
+            best, feasible = b, True
+            break
+    return dict(best_bits=best, feasible=feasible, sse=sse, sumsq=sumsq, runs=runs)

@@ -276,3 +276,34 @@ def test_conventions_at_exact_ties():
     # ... and so does one whose members have no weight
     c, _ = sk.weighted_lloyd([0.0, 1.0, 2.0], [0.0, 1.0, 1.0], [0.25, 1.5], 10)
     assert c[0] == 0.25
+
+
+def test_search_over_bits():
+    rng = np.random.default_rng(10)
+    x = (rng.standard_t(3, 6000) * 0.015).astype(np.float32)
+    mag = np.abs(x)
+    lo, hi = np.quantile(mag, 0.2), np.quantile(mag, 0.999)
+    cls = np.where(mag < lo, 0, np.where(mag > hi, 1, 2))
+    uni = rng.uniform(size=256)
+    # the start of a narrower width is a prefix of the start of a wider one
+    s, i, c = sk.sketch_histogram(x[cls == 2], 0.01)
+    xq = sk.bucket_value(s, i, 0.01)
+    w = sk.sample_weights(xq, c, 0.2)
+    assert sk.weighted_kmeanspp(xq, w, 8, uni) == sk.weighted_kmeanspp(xq, w, 64, uni)[:8]
+    r = sk.search_bits(x, cls, 0.01, 0.2, uni, 100, 0.01)
+    # the error of a width is the squared distance to the decoded tensor (protected values exact)
+    for b in (2, 5, 8):
+        run = r["runs"][b]
+        dec = np.where(cls == 0, 0.0, np.where(cls == 1, x.astype(np.float64),
+                                               run["codebook"].astype(np.float64)[np.maximum(run["sym"].astype(np.int64) - 2, 0)]))
+        assert math.isclose(r["sse"][b], float(np.sum((x.astype(np.float64) - dec) ** 2)), rel_tol=1e-12)
+    assert math.isclose(r["sumsq"], float(np.sum(x.astype(np.float64) ** 2)), rel_tol=1e-15)
+    # the choice: the fewest bits within the bound; a bound below the pruned part is never met
+    ok = [b for b in range(2, 9) if r["sse"][b] <= 0.01 * r["sumsq"]]
+    assert r["feasible"] == bool(ok) and r["best_bits"] == (min(ok) if ok else 8)
+    tight = sk.search_bits(x, cls, 0.01, 0.2, uni, 100, 1e-9)
+    assert tight["feasible"] is False and tight["best_bits"] == 8
+    loose = sk.search_bits(x, cls, 0.01, 0.2, uni, 100, 0.9)
+    assert loose["feasible"] is True and loose["best_bits"] == 2
+    # more bins never hurt much here: 8 bits are far better than 2
+    assert r["sse"][8] < 0.05 * r["sse"][2]
