@@ -225,6 +225,27 @@ int inshr_quantize_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const ins
                           const inshr_sketch_params *params, inshr_quantized *out,
                           inshr_sketch_info *info, uint32_t n_tensors, uint32_t flags);
 
+typedef struct {
+    double sse[7];      /* squared error of the tensor with 2, 3, ..., 8 bits (fp64)          */
+    double sumsq;       /* sum_all x^2                                                        */
+    uint32_t rounds[7]; /* Lloyd rounds of each width                                         */
+    uint32_t best_bits; /* the fewest bits with sse <= eps * sumsq; 8 when there are none ... */
+    uint32_t feasible;  /* ... and then 0                                                     */
+} inshr_sketch_choice;
+
+/* The search of Sec. 5 restricted to the number of bins, with the bins of inshr_quantize_sketch:
+ * for tensors[i] and the prune / protect fractions of cfg[i] (cfg[i].bits is ignored) the sketch
+ * is clustered into 2^b clusters for b = 2 .. 8 (draw r of every width uses uniforms[t * 256 + r],
+ * so the start of a narrower width is a prefix of the start of a wider one), every width is scored
+ * exactly (sse = sum_pruned x^2 + sum_quantized (x - its centre)^2 over the tensor, one more sweep),
+ * the fewest bits within eps are chosen and the tensor is quantized with them into out[i] (sized
+ * for 8 bits).  choice: host, n_tensors entries.  With INSHR_REUSE_SEARCH the grid of the last
+ * inshr_search must hold the tensor's fractions with every width from 2 to 8 bits. */
+int inshr_search_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
+                        const inshr_sketch_params *params, double eps, inshr_quantized *out,
+                        inshr_sketch_choice *choice, inshr_sketch_info *info, uint32_t n_tensors,
+                        uint32_t flags);
+
 /* ---- entropy stage of the delta (host memory only, outside the timed path) ------------------- */
 
 typedef struct {

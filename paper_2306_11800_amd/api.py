@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
-           "inshr_quantize_sketch",
+           "inshr_quantize_sketch", "inshr_search_sketch",
            "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
@@ -54,6 +54,11 @@ class CSketchParams(C.Structure):
 
 class CSketchInfo(C.Structure):
     _fields_ = [("n_buckets", C.c_uint32), ("rounds", C.c_uint32)]
+
+
+class CSketchChoice(C.Structure):
+    _fields_ = [("sse", C.c_double * 7), ("sumsq", C.c_double), ("rounds", C.c_uint32 * 7),
+                ("best_bits", C.c_uint32), ("feasible", C.c_uint32)]
 
 
 class CCodes(C.Structure):
@@ -113,6 +118,10 @@ def load_library() -> C.CDLL:
     lib.inshr_quantize_sketch.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
                                           C.POINTER(CSketchParams), C.POINTER(CQuantized),
                                           C.POINTER(CSketchInfo), C.c_uint32, C.c_uint32]
+    lib.inshr_search_sketch.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig),
+                                        C.POINTER(CSketchParams), C.c_double, C.POINTER(CQuantized),
+                                        C.POINTER(CSketchChoice), C.POINTER(CSketchInfo), C.c_uint32,
+                                        C.c_uint32]
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
@@ -375,6 +384,48 @@ class Context:
         self._check(self.lib.inshr_quantize_sketch(self.h, ta, ca, C.byref(par), qa, info, nT,
                                                    INSHR_REUSE_SEARCH if reuse_search else 0))
         return res, [(int(i.n_buckets), int(i.rounds)) for i in info]
+
+    # -- inshr_search_sketch ---------------------------------------------------------------
+    def search_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, eps: float,
+                      alpha: float = 0.01, sigma: float = 0.2, max_iter: int = 100,
+                      reuse_search: bool = False):
+        """cfgs: (ignored bits, prune_ppm, outlier_ppm) per tensor.  Returns (list of Quantized with
+        the chosen bits, list of dict(best_bits, feasible, sse[7], sumsq, rounds[7]), list of
+        (n_buckets, rounds of the widest set))."""
+        import numpy as np
+        nT = len(tensors)
+        ta = _tensor_array(tensors)
+        wide = [(8, int(c[1]), int(c[2])) for c in cfgs]
+        ca = _config_array(wide)
+        u = np.ascontiguousarray(uniforms, dtype=np.float64)
+        if u.shape != (nT, 256):
+            raise ValueError("uniforms must have shape [len(tensors), 256]")
+        qa = (CQuantized * nT)()
+        res = QuantizedBatch()
+        for i, (t, cfg) in enumerate(zip(tensors, wide)):
+            n = t.numel()
+            words, cap = self._bound(n, ca[i], cfg)
+            e = qa[i]
+            q = Quantized(n, 8, (
+                torch.empty(words, dtype=torch.int64, device=t.device),
+                torch.empty(256, dtype=torch.float32, device=t.device),
+                torch.empty(255, dtype=torch.float32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa)
+            e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
+            e.packed_words = q._bufs[0].numel()
+            e.outlier_cap = q._bufs[3].numel()
+            res.append(q)
+        res._qa = qa
+        res._sizes = tuple(q.n for q in res)
+        par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
+        info = (CSketchInfo * nT)()
+        choice = (CSketchChoice * nT)()
+        self._check(self.lib.inshr_search_sketch(self.h, ta, ca, C.byref(par), float(eps), qa, choice, info,
+                                                 nT, INSHR_REUSE_SEARCH if reuse_search else 0))
+        choices = [dict(best_bits=int(c.best_bits), feasible=bool(c.feasible), sse=list(c.sse),
+                        sumsq=float(c.sumsq), rounds=list(c.rounds)) for c in choice]
+        return res, choices, [(int(i.n_buckets), int(i.rounds)) for i in info]
 
     def _bound(self, n, ccfg, cfg):
         key = (n, int(cfg[0]), int(cfg[1]), int(cfg[2]))

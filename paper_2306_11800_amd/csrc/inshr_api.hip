@@ -772,8 +772,11 @@ namespace {
 // Leaves 256 boundary keys and centres per tensor of the batch in *alt_key / *alt_cb (device).
 int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *which, const uint32_t *src,
                       uint32_t n_sel, const inshr_sketch_params *params, const SketchTables &T,
-                      inshr_sketch_info *info, const u32 **alt_key, const float **alt_cb)
+                      inshr_sketch_info *info, const u32 **alt_key, const float **alt_cb,
+                      bool multi = false, double eps = 0.0, inshr_sketch_choice *choice = nullptr)
 {
+    // multi: centres for 2 .. 8 bits, their exact errors and the choice (cfg[k].bits must be 8 then:
+    // it names the grid entry that carries the tensor's prune / protect fractions)
     const uint32_t nT = (uint32_t)c->batch.nT;
     std::vector<SketchDesc> sd(nT);
     for (auto &d : sd) d.active = d.cfg = 0u;
@@ -796,17 +799,28 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
     const size_t o_sd = cv.take(sizeof(SketchDesc) * nT);
     const size_t upload = cv.off; // everything up to here comes from the host
     const size_t o_info = cv.take(sizeof(SketchInfo) * nT);
-    const size_t o_key = cv.take(sizeof(u32) * 256 * nT);
-    const size_t o_cb = cv.take(sizeof(float) * 256 * nT);
     const size_t o_hist = cv.take(sizeof(u32) * SK_HIST * nT);
     const size_t o_xq = cv.take(sizeof(double) * SK_HIST * nT);
     const size_t o_w = cv.take(sizeof(double) * SK_HIST * nT);
     const size_t o_d = cv.take(sizeof(double) * SK_HIST * nT);
+    const size_t n_sets = multi ? SK_SETS : 1;
+    const size_t o_key = cv.take(sizeof(u32) * 256 * n_sets * nT);
+    const size_t o_cb = cv.take(sizeof(float) * 256 * n_sets * nT);
+    const size_t o_sr = cv.take(sizeof(u32) * SK_SETS * nT);
+    const size_t o_ch = cv.take(sizeof(SketchChoice) * nT);
+    const size_t o_fk = cv.take(sizeof(u32) * 256 * nT);
+    const size_t o_fc = cv.take(sizeof(float) * 256 * nT);
+    const size_t o_se = cv.take(sizeof(u32) * SK_SLOTS * nT);
+    const size_t o_slot = cv.off; // slot moments, cleared before the scoring sweep
+    const size_t o_sc = cv.take(sizeof(u32) * SK_SLOTS * nT);
+    const size_t o_sx = cv.take(sizeof(double) * SK_SLOTS * nT);
+    const size_t o_sxx = cv.take(sizeof(double) * SK_SLOTS * nT);
+    const size_t slot_end = cv.off;
     int rc = ensure_dev(c, c->sketch_mem, cv.off);
     if (rc) return rc;
     rc = ensure_host(c, c->h_up, upload);
     if (rc) return rc;
-    rc = ensure_host(c, c->h_down, sizeof(SketchInfo) * nT);
+    rc = ensure_host(c, c->h_down, (sizeof(SketchInfo) + sizeof(SketchChoice)) * nT);
     if (rc) return rc;
     char *hb = (char *)c->h_up.p, *db = (char *)c->sketch_mem.p;
     HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
@@ -835,7 +849,21 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
     P.alt_key = (u32 *)(db + o_key);
     P.alt_cb = (float *)(db + o_cb);
     P.info = (SketchInfo *)(db + o_info);
+    P.multi = multi ? 1u : 0u;
+    P.eps = eps;
+    P.set_rounds = (u32 *)(db + o_sr);
+    P.slot_cnt = (u32 *)(db + o_sc);
+    P.slot_sx = (double *)(db + o_sx);
+    P.slot_sxx = (double *)(db + o_sxx);
+    P.slot_edge = (u32 *)(db + o_se);
+    P.choice = (SketchChoice *)(db + o_ch);
+    P.final_key = (u32 *)(db + o_fk);
+    P.final_cb = (float *)(db + o_fc);
+    if (multi) HIPCHK(c, hipMemsetAsync(db + o_slot, 0, slot_end - o_slot, c->stream));
     HIPCHK(c, launch_sketch(c->batch, (const SketchDesc *)(db + o_sd), P, c->stream));
+    if (multi)
+        HIPCHK(c, hipMemcpyAsync((char *)c->h_down.p + sizeof(SketchInfo) * nT, db + o_ch,
+                                 sizeof(SketchChoice) * nT, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_info, sizeof(SketchInfo) * nT, hipMemcpyDeviceToHost,
                              c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -846,8 +874,22 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
             info[src[k]].rounds = si[which[k]].rounds;
         }
     }
-    *alt_key = P.alt_key;
-    *alt_cb = P.alt_cb;
+    if (multi && choice) {
+        const SketchChoice *sc = (const SketchChoice *)((const char *)c->h_down.p + sizeof(SketchInfo) * nT);
+        for (uint32_t k = 0; k < n_sel; k++) {
+            const SketchChoice &r = sc[which[k]];
+            inshr_sketch_choice &o = choice[src[k]];
+            for (int b = 0; b < SK_SETS; b++) {
+                o.sse[b] = r.sse[b];
+                o.rounds[b] = r.rounds[b];
+            }
+            o.sumsq = r.sumsq;
+            o.best_bits = r.best_bits;
+            o.feasible = r.feasible;
+        }
+    }
+    *alt_key = multi ? P.final_key : P.alt_key;
+    *alt_cb = multi ? P.final_cb : P.alt_cb;
     return INSHR_OK;
 }
 
@@ -912,6 +954,87 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
         rc = sketch_with_state(c, subcfg.data(), which.data(), idx.data(), nS, params, T, info, &alt_key, &alt_cb);
         if (rc) return rc;
         rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), nS, alt_key, alt_cb);
+        for (uint32_t k = 0; k < nS; k++) out[idx[k]] = subout[k];
+        if (rc) return rc;
+    }
+    return INSHR_OK;
+}
+
+int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config *cfg,
+                        const inshr_sketch_params *params, double eps, inshr_quantized *out,
+                        inshr_sketch_choice *choice, inshr_sketch_info *info, uint32_t n_tensors,
+                        uint32_t flags)
+{
+    if (!c || !tensors || !cfg || !params || !out || !choice || n_tensors == 0 || !params->uniforms)
+        return INSHR_E_ARG;
+    if (!(params->sigma >= 0.0 && params->sigma <= 1.0) || !(eps >= 0.0)) return INSHR_E_CONFIG;
+    std::vector<inshr_config> wide(n_tensors); // the tensor's fractions with 8 bits
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        wide[t] = cfg[t];
+        wide[t].bits = 8;
+        int rc = check_config(wide[t]);
+        if (rc) return rc;
+        for (int r = 0; r < 256; r++) {
+            const double u = params->uniforms[(size_t)t * 256 + r];
+            if (!(u >= 0.0 && u < 1.0)) return INSHR_E_ARG;
+        }
+    }
+    SketchTables T;
+    int rc = build_sketch_tables(params->alpha, T);
+    if (rc) return rc;
+    HIPCHK(c, hipSetDevice(c->device));
+    const u32 *alt_key = nullptr;
+    const float *alt_cb = nullptr;
+    auto finish = [&](const inshr_config *sub_wide, inshr_quantized *sub_out, const uint32_t *which,
+                      const uint32_t *src, uint32_t n) -> int {
+        int r = sketch_with_state(c, sub_wide, which, src, n, params, T, info, &alt_key, &alt_cb, true, eps, choice);
+        if (r) return r;
+        std::vector<inshr_config> chosen(n);
+        for (uint32_t k = 0; k < n; k++) {
+            chosen[k] = sub_wide[k];
+            chosen[k].bits = (uint8_t)choice[src[k]].best_bits;
+        }
+        return quantize_with_state(c, chosen.data(), sub_out, which, n, alt_key, alt_cb);
+    };
+    if (flags & INSHR_REUSE_SEARCH) {
+        if (!c->have_search || c->tensors.size() != n_tensors) return INSHR_E_SHAPE;
+        std::vector<uint32_t> which(n_tensors);
+        for (uint32_t t = 0; t < n_tensors; t++) {
+            if (c->tensors[t].data != tensors[t].data || c->tensors[t].n != tensors[t].n) return INSHR_E_SHAPE;
+            which[t] = t;
+        }
+        return finish(wide.data(), out, which.data(), which.data(), n_tensors);
+    }
+    // stand-alone: one search over 2 .. 8 bits per distinct pair of fractions gives the thresholds
+    std::vector<char> done(n_tensors, 0);
+    for (uint32_t t0 = 0; t0 < n_tensors; t0++) {
+        if (done[t0]) continue;
+        std::vector<inshr_tensor> sub;
+        std::vector<inshr_config> subcfg;
+        std::vector<uint32_t> idx;
+        for (uint32_t t = t0; t < n_tensors; t++) {
+            if (!done[t] && cfg[t].prune_ppm == cfg[t0].prune_ppm && cfg[t].outlier_ppm == cfg[t0].outlier_ppm) {
+                done[t] = 1;
+                sub.push_back(tensors[t]);
+                subcfg.push_back(wide[t]);
+                idx.push_back(t);
+            }
+        }
+        const uint32_t nS = (uint32_t)sub.size();
+        inshr_config grid7[SK_SETS];
+        for (int b = 0; b < SK_SETS; b++) {
+            grid7[b] = wide[t0];
+            grid7[b].bits = (uint8_t)(2 + b);
+        }
+        rc = run_search(c, sub.data(), nS, grid7, SK_SETS, eps);
+        if (rc) return rc;
+        std::vector<inshr_quantized> subout(nS);
+        std::vector<uint32_t> which(nS);
+        for (uint32_t k = 0; k < nS; k++) {
+            subout[k] = out[idx[k]];
+            which[k] = k;
+        }
+        rc = finish(subcfg.data(), subout.data(), which.data(), idx.data(), nS);
         for (uint32_t k = 0; k < nS; k++) out[idx[k]] = subout[k];
         if (rc) return rc;
     }

@@ -9,6 +9,9 @@ constexpr int SK_CELLS = 16384;            // magnitude >> 17: sign-free exponen
 constexpr int SK_MAX_IDX = 9728;           // most bucket indices per sign (alpha = 0.01 needs 9604)
 constexpr int SK_HIST = 2 * SK_MAX_IDX + 1; // positive buckets, negative buckets, zeros
 constexpr int SK_LDS = 4096;               // longest bucket list that the clustering keeps in LDS
+constexpr int SK_SETS = 7;                 // sets of centres of a search over the bits: 2 .. 8 bits
+constexpr int SK_EDGES = 501;              // boundaries of all sets: sum of 2^b - 1
+constexpr int SK_SLOTS = 512;              // stride of the per-slot arrays (SK_EDGES + 1 slots)
 
 struct SketchDesc { // one tensor of the batch
     u32 active;     // part of the call
@@ -17,6 +20,12 @@ struct SketchDesc { // one tensor of the batch
 struct SketchInfo {
     u32 n_buckets;  // non-empty buckets
     u32 rounds;     // Lloyd rounds that changed the centres
+};
+struct SketchChoice { // result of the search over the bits, per tensor
+    double sse[SK_SETS];   // squared error with 2 .. 8 bits
+    double sumsq;
+    u32 rounds[SK_SETS];
+    u32 best_bits, feasible;
 };
 struct SketchParams {
     double sigma;
@@ -31,6 +40,16 @@ struct SketchParams {
     u32 *alt_key;          // [nT][256] boundary keys where the quantizer looks for them
     float *alt_cb;         // [nT][256] codebook
     SketchInfo *info;      // [nT]
+    // search over the bits (multi != 0): alt_key / alt_cb hold SK_SETS rows of 256 per tensor
+    u32 multi;
+    double eps;            // bound on sse / sumsq
+    u32 *set_rounds;       // [nT][SK_SETS]
+    u32 *slot_cnt;         // [nT][SK_SLOTS] values per slot between all boundaries, zero on entry
+    double *slot_sx, *slot_sxx; // [nT][SK_SLOTS] their sums and sums of squares, zero on entry
+    u32 *slot_edge;        // [nT][SK_SLOTS] the sorted boundaries
+    SketchChoice *choice;  // [nT]
+    u32 *final_key;        // [nT][256] the chosen set, where the quantizer looks for it
+    float *final_cb;       // [nT][256]
 };
 
 hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s);

@@ -150,7 +150,10 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
     const SketchDesc s = sd[t];
     if (!s.active) return;
     const u32 tid = threadIdx.x, lane = tid & 63u;
-    const u32 K = 1u << gd->cfg_bits[s.cfg];
+    // one set of centres for the configuration's bits, or (P.multi) one for each of 2 .. 8 bits: the
+    // draws of a narrower set are the first draws of the widest
+    const u32 K = P.multi ? 256u : 1u << gd->cfg_bits[s.cfg];
+    const u32 n_sets = P.multi ? (u32)SK_SETS : 1u;
     const u32 *h = P.hist + (size_t)t * SK_HIST;
     // bucket values, weights and squared distances: in LDS when the list is short enough (a few
     // hundred to a few thousand buckets is the rule), else in the tensor's scratch rows
@@ -307,73 +310,80 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
         }
     }
     __syncthreads();
-    // ---- sort the centres ----
-    if (tid < K) {
-        const double x = craw[tid];
-        u32 rank = 0u;
-        for (u32 i = 0; i < K; i++) {
-            const double y = craw[i];
-            rank += (y < x || (y == x && i < tid)) ? 1u : 0u;
-        }
-        cen[rank] = x;
-    }
-    __syncthreads();
-    // ---- weighted Lloyd rounds: cluster j = buckets (mid[j-1], mid[j]] ----
     u32 rounds = 0u;
-    for (u32 it = 0; it < P.max_iter; it++) {
-        if (tid == 0) s_changed = (it == 0u) ? 1u : 0u;
+    for (u32 set = 0; set < n_sets; set++) {
+        const u32 bits = P.multi ? 2u + set : gd->cfg_bits[s.cfg];
+        const u32 Kb = 1u << bits;
+        // ---- sort the centres ----
         __syncthreads();
-        if (tid <= K) {
-            u32 first = 0u;
-            if (tid == K) {
-                first = m;
-            } else if (tid > 0u) {
-                const double mid = __dmul_rn(__dadd_rn(cen[tid - 1u], cen[tid]), 0.5);
-                u32 a = 0u, b = m; // first bucket above the midpoint
-                while (a < b) {
-                    const u32 c = (a + b) >> 1;
-                    if (xq[c] > mid)
-                        b = c;
-                    else
-                        a = c + 1u;
+        if (tid < Kb) {
+            const double x = craw[tid];
+            u32 rank = 0u;
+            for (u32 i = 0; i < Kb; i++) {
+                const double y = craw[i];
+                rank += (y < x || (y == x && i < tid)) ? 1u : 0u;
+            }
+            cen[rank] = x;
+        }
+        __syncthreads();
+        // ---- weighted Lloyd rounds: cluster j = buckets (mid[j-1], mid[j]] ----
+        rounds = 0u;
+        for (u32 it = 0; it < P.max_iter; it++) {
+            if (tid == 0) s_changed = (it == 0u) ? 1u : 0u;
+            __syncthreads();
+            if (tid <= Kb) {
+                u32 first = 0u;
+                if (tid == Kb) {
+                    first = m;
+                } else if (tid > 0u) {
+                    const double mid = __dmul_rn(__dadd_rn(cen[tid - 1u], cen[tid]), 0.5);
+                    u32 a = 0u, b = m; // first bucket above the midpoint
+                    while (a < b) {
+                        const u32 c = (a + b) >> 1;
+                        if (xq[c] > mid)
+                            b = c;
+                        else
+                            a = c + 1u;
+                    }
+                    first = a;
                 }
-                first = a;
+                seg[tid] = first;
+                if (it > 0u && seg_prev[tid] != first) s_changed = 1u;
             }
-            seg[tid] = first;
-            if (it > 0u && seg_prev[tid] != first) s_changed = 1u;
+            __syncthreads();
+            if (!s_changed) break;
+            if (tid < Kb) {
+                double sw = 0.0, swx = 0.0;
+                for (u32 i = seg[tid]; i < seg[tid + 1u]; i++) {
+                    sw = __dadd_rn(sw, w[i]);
+                    swx = __dadd_rn(swx, __dmul_rn(w[i], xq[i]));
+                }
+                if (sw > 0.0) cen[tid] = __ddiv_rn(swx, sw);
+            }
+            if (tid <= Kb) seg_prev[tid] = seg[tid];
+            rounds++;
+            __syncthreads();
         }
         __syncthreads();
-        if (!s_changed) break;
-        if (tid < K) {
-            double sw = 0.0, swx = 0.0;
-            for (u32 i = seg[tid]; i < seg[tid + 1u]; i++) {
-                sw = __dadd_rn(sw, w[i]);
-                swx = __dadd_rn(swx, __dmul_rn(w[i], xq[i]));
-            }
-            if (sw > 0.0) cen[tid] = __ddiv_rn(swx, sw);
-        }
-        if (tid <= K) seg_prev[tid] = seg[tid];
-        rounds++;
+        // ---- codebook and boundaries ----
+        const u32 sh = 8u - bits;
+        u32 *ak = P.alt_key + ((size_t)t * n_sets + set) * 256;
+        float *acb = P.alt_cb + ((size_t)t * n_sets + set) * 256;
+        if (tid < 256u) ak[tid] = 0u;
         __syncthreads();
-    }
-    __syncthreads();
-    // ---- codebook and boundaries ----
-    const u32 sh = 8u - gd->cfg_bits[s.cfg];
-    u32 *ak = P.alt_key + (size_t)t * 256;
-    float *acb = P.alt_cb + (size_t)t * 256;
-    if (tid < 256u) ak[tid] = 0u;
-    __syncthreads();
-    if (tid < K) {
-        acb[tid] = __double2float_rn(cen[tid]);
-        if (tid + 1u < K) {
-            const double a = (double)__double2float_rn(cen[tid]), b = (double)__double2float_rn(cen[tid + 1u]);
-            const double mid = __dmul_rn(__dadd_rn(a, b), 0.5);
-            // a value goes to the upper centre when it lies strictly above the midpoint: the
-            // boundary is the smallest fp32 number above it
-            ak[((tid + 1u) << sh) - 1u] = key_of_float(__double2float_rd(mid)) + 1u;
+        if (tid < Kb) {
+            acb[tid] = __double2float_rn(cen[tid]);
+            if (tid + 1u < Kb) {
+                const double a = (double)__double2float_rn(cen[tid]), b = (double)__double2float_rn(cen[tid + 1u]);
+                const double mid = __dmul_rn(__dadd_rn(a, b), 0.5);
+                // a value goes to the upper centre when it lies strictly above the midpoint: the
+                // boundary is the smallest fp32 number above it
+                ak[((tid + 1u) << sh) - 1u] = key_of_float(__double2float_rd(mid)) + 1u;
+            }
+        } else if (tid < 256u) {
+            acb[tid] = 0.0f;
         }
-    } else if (tid < 256u) {
-        acb[tid] = 0.0f;
+        if (tid == 0 && P.multi) P.set_rounds[(size_t)t * SK_SETS + set] = rounds;
     }
     if (tid == 0) {
         P.info[t].n_buckets = m;
@@ -381,11 +391,181 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// exact error of every set of centres (Sec. 5 restricted to the number of bins)
+// ------------------------------------------------------------------------------------------
+// All boundaries of a tensor's SK_SETS sets, sorted, cut the key axis into at most SK_EDGES + 1
+// slots; a slot lies inside one cluster of every set, so count, sum and sum of squares per slot
+// give the error of every set: sum over slots of sxx - 2 c sx + n c^2 with c the slot's centre.
+__device__ __forceinline__ u32 n_boundaries_before(u32 set) { return (4u << set) - 4u - set; } // sum of 2^b - 1, b = 2 .. set + 1
+
+__global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict__ td, int nT,
+                                                        const u64 *__restrict__ wg_tile0,
+                                                        const GridDesc *__restrict__ gd,
+                                                        const SketchDesc *__restrict__ sd,
+                                                        SketchParams P, Bufs B)
+{
+    __shared__ u32 raw[SK_EDGES], edge[SK_EDGES + 1];
+    __shared__ u32 cnt[SK_EDGES + 1];
+    __shared__ double sx[SK_EDGES + 1], sxx[SK_EDGES + 1];
+    const u32 tid = threadIdx.x;
+    const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
+    if (tile_lo >= tile_hi) return;
+    int t = find_tensor(td, nT, tile_lo);
+    u64 tile = tile_lo;
+    while (tile < tile_hi) {
+        const TDesc d = td[t];
+        const u64 n_tiles_t = (d.n + TILE - 1) / TILE;
+        const u64 t_end = d.tile0 + n_tiles_t;
+        const u64 stop = t_end < tile_hi ? t_end : tile_hi;
+        const SketchDesc s = sd[t];
+        if (!s.active) {
+            tile = stop;
+            t++;
+            continue;
+        }
+        const TState *st = B.ts + t;
+        const u32 pair = gd->cfg_pair[s.cfg];
+        const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + gd->pair_o[pair]];
+        __syncthreads();
+        if (tid < (u32)SK_EDGES) { // boundary j of set b sits at ((j + 1) << (8 - bits)) - 1 of its row
+            u32 set = 0u;
+            while (set + 1u < (u32)SK_SETS && tid >= n_boundaries_before(set + 1u)) set++;
+            const u32 j = tid - n_boundaries_before(set), bits = 2u + set;
+            raw[tid] = P.alt_key[((size_t)t * SK_SETS + set) * 256 + (((j + 1u) << (8u - bits)) - 1u)];
+        }
+        for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
+            cnt[i] = 0u;
+            sx[i] = 0.0;
+            sxx[i] = 0.0;
+        }
+        __syncthreads();
+        if (tid < (u32)SK_EDGES) { // sort by counting the smaller ones
+            const u32 x = raw[tid];
+            u32 r = 0u;
+            for (u32 i = 0; i < (u32)SK_EDGES; i++) {
+                const u32 y = raw[i];
+                r += (y < x || (y == x && i < tid)) ? 1u : 0u;
+            }
+            edge[r] = x;
+        }
+        if (tid == 0) edge[SK_EDGES] = 0xFFFFFFFFu;
+        __syncthreads();
+        for (; tile < stop; tile++) {
+            const u64 e0 = (tile - d.tile0) * (u64)TILE;
+            const u64 rem = d.n - e0;
+            const u32 c = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+            float v[16];
+            const u32 mask = load_tile(d, e0, c, v);
+#pragma unroll 4
+            for (int i = 0; i < 16; i++) {
+                const u32 key = key_of_float(v[i]);
+                const u32 mag = mag_of_key(key);
+                if (!((mask >> i) & 1u) || mag < tau_p || mag > tau_o) continue;
+                u32 slot = 0u; // edges at or below the key
+#pragma unroll
+                for (u32 step = 256u; step > 0u; step >>= 1)
+                    if (slot + step <= (u32)SK_EDGES && edge[slot + step - 1u] <= key) slot += step;
+                const double x = (double)v[i];
+                atomicAdd(&cnt[slot], 1u);
+                atomicAdd(&sx[slot], x);
+                atomicAdd(&sxx[slot], x * x);
+            }
+        }
+        __syncthreads();
+        // this unit's part of the tensor's slot moments
+        u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
+        double *gx = P.slot_sx + (size_t)t * SK_SLOTS, *gxx = P.slot_sxx + (size_t)t * SK_SLOTS;
+        for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
+            if (cnt[i]) {
+                atomicAdd(&gc[i], cnt[i]);
+                atomicAdd(&gx[i], sx[i]);
+                atomicAdd(&gxx[i], sxx[i]);
+            }
+        }
+        if (tid < (u32)SK_EDGES) P.slot_edge[(size_t)t * SK_SLOTS + tid] = edge[tid]; // (the same from every unit)
+        t++;
+    }
+}
+
+// per tensor: error of every set, the fewest bits within eps, and that set's keys and centres
+// where the quantizer looks for them
+__global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__ td,
+                                                       const GridDesc *__restrict__ gd,
+                                                       const SketchDesc *__restrict__ sd,
+                                                       SketchParams P, Bufs B)
+{
+    __shared__ double s_sse[SK_SETS];
+    __shared__ u32 s_best;
+    const int t = blockIdx.x;
+    const SketchDesc s = sd[t];
+    if (!s.active) return;
+    const u32 tid = threadIdx.x;
+    const TState *st = B.ts + t;
+    const u32 pair = gd->cfg_pair[s.cfg];
+    // sum of squares of the pruned values = all - protected - quantized (the last from the slots)
+    const double not_protected = st->sumsq - st->thr_sumsq[gd->n_p + gd->pair_o[pair]];
+    const u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
+    const double *gx = P.slot_sx + (size_t)t * SK_SLOTS, *gxx = P.slot_sxx + (size_t)t * SK_SLOTS;
+    const u32 *edge = P.slot_edge + (size_t)t * SK_SLOTS;
+    if (tid < (u32)SK_SETS) {
+        const u32 set = tid, bits = 2u + set, Kb = 1u << bits, sh = 8u - bits;
+        const u32 *ak = P.alt_key + ((size_t)t * SK_SETS + set) * 256;
+        const float *acb = P.alt_cb + ((size_t)t * SK_SETS + set) * 256;
+        double sse = 0.0, quantized = 0.0;
+        u32 cluster = 0u; // of the current slot: boundaries of this set at or below the slot's keys
+        for (u32 slot = 0; slot <= (u32)SK_EDGES; slot++) {
+            if (slot > 0u) { // the slot starts at edge[slot - 1]
+                const u32 first = edge[slot - 1u];
+                while (cluster + 1u < Kb && ak[((cluster + 1u) << sh) - 1u] <= first) cluster++;
+            }
+            const u32 n = gc[slot];
+            if (n) {
+                const double c = (double)acb[cluster];
+                sse += gxx[slot] - 2.0 * c * gx[slot] + (double)n * c * c;
+                quantized += gxx[slot];
+            }
+        }
+        const double pruned = not_protected - quantized;
+        s_sse[set] = (pruned > 0.0 ? pruned : 0.0) + (sse > 0.0 ? sse : 0.0);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const double bound = P.eps * st->sumsq;
+        u32 best = SK_SETS - 1u, feasible = 0u;
+        for (u32 set = 0; set < (u32)SK_SETS; set++)
+            if (s_sse[set] <= bound) {
+                best = set;
+                feasible = 1u;
+                break;
+            }
+        s_best = best;
+        SketchChoice r;
+        for (u32 set = 0; set < (u32)SK_SETS; set++) {
+            r.sse[set] = s_sse[set];
+            r.rounds[set] = P.set_rounds[(size_t)t * SK_SETS + set];
+        }
+        r.sumsq = st->sumsq;
+        r.best_bits = 2u + best;
+        r.feasible = feasible;
+        P.choice[t] = r;
+    }
+    __syncthreads();
+    const u32 best = s_best;
+    P.final_key[(size_t)t * 256 + tid] = P.alt_key[((size_t)t * SK_SETS + best) * 256 + tid];
+    P.final_cb[(size_t)t * 256 + tid] = P.alt_cb[((size_t)t * SK_SETS + best) * 256 + tid];
+}
+
 hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s)
 {
     PROF("k_sketch_hist", s,
          k_sketch_hist<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, sd, P, bt.bufs));
     PROF("k_sketch_kmeans", s, k_sketch_kmeans<<<bt.nT, BLOCK, 0, s>>>(bt.gd, sd, P));
+    if (P.multi) {
+        PROF("k_sketch_score", s,
+             k_sketch_score<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, sd, P, bt.bufs));
+        PROF("k_sketch_choose", s, k_sketch_choose<<<bt.nT, 256, 0, s>>>(bt.td, bt.gd, sd, P, bt.bufs));
+    }
     return hipGetLastError();
 }
 

@@ -108,6 +108,54 @@ def test_on_top_of_a_grid_search(ctx):
     assert e.value.code == -5
 
 
+def check_search(ctx, xs, cfgs, eps, alpha, sigma, max_iter, seed, reuse_grid=None):
+    rng = np.random.default_rng(seed)
+    uni = rng.uniform(size=(len(xs), 256))
+    dx = [dev(x) for x in xs]
+    if reuse_grid is not None:
+        ctx.search(dx, reuse_grid, eps, want_scores=False)
+    qs, choices, info = ctx.search_sketch(dx, cfgs, uni, eps, alpha=alpha, sigma=sigma, max_iter=max_iter,
+                                          reuse_search=reuse_grid is not None)
+    for i, (x, cfg) in enumerate(zip(xs, cfgs)):
+        print("sketch search case", seed, i, x.size, cfg, eps, flush=True)
+        base = ref.quantize(x, (8, cfg[1], cfg[2]))
+        r = sk.search_bits(x, base["sym"], alpha, sigma, uni[i], max_iter, eps)
+        ch = choices[i]
+        assert abs(ch["sumsq"] - r["sumsq"]) <= 1e-6 * r["sumsq"]
+        border = False
+        for b in range(2, 9):
+            want = r["sse"][b]
+            assert abs(ch["sse"][b - 2] - want) <= 1e-6 * want + 1e-12 * r["sumsq"], (b, ch["sse"][b - 2], want)
+            assert ch["rounds"][b - 2] == r["runs"][b]["rounds"]
+            if r["sumsq"] > 0 and abs(want / r["sumsq"] - eps) <= 4e-6 * eps:
+                border = True
+        if border:
+            continue
+        assert (ch["best_bits"], ch["feasible"]) == (r["best_bits"], r["feasible"])
+        bits = r["best_bits"]
+        run = r["runs"][bits]
+        q = qs[i]
+        assert q.bits == bits and info[i][0] == run["n_buckets"]
+        np.testing.assert_allclose(q.codebook.cpu().numpy(), run["codebook"], rtol=1e-6, atol=0)
+        assert np.array_equal(q.boundaries.cpu().numpy().view(np.uint32), run["boundaries"].view(np.uint32))
+        got = ref.unpack(q.packed.cpu().numpy().view(np.uint64), x.size, bits + 1)
+        assert np.array_equal(got, run["sym"])
+        assert np.array_equal(q.outlier_idx.cpu().numpy().view(np.uint32), base["outlier_idx"])
+
+
+def test_search_over_bits(ctx):
+    rng = np.random.default_rng(15)
+    fam = families(rng, 50001)
+    xs = [fam["t3"], fam["zeros"], fam["positive"], fam["lattice"], fam["t3"][:7], fam["wide"][:3000]]
+    cfgs = [(0, 100000, 1000), (0, 0, 0), (0, 300000, 100), (0, 0, 1000), (0, 0, 0), (0, 50000, 0)]
+    for eps in (1e-2, 1e-4, 0.5):
+        check_search(ctx, xs, cfgs, eps, 0.01, 0.2, 100, 21)
+    # on top of a grid search that holds every width of the fractions in use
+    grid = [(b, p, o) for b in range(2, 9) for (p, o) in ((100000, 1000), (0, 0))]
+    check_search(ctx, [fam["t3"], fam["zeros"]], [(0, 100000, 1000), (0, 0, 0)], 1e-3, 0.02, 0.4, 50, 22,
+                 reuse_grid=grid)
+
+
 def test_argument_errors(ctx):
     from paper_2306_11800_amd import api
     x = dev(np.ones(100, np.float32))
