@@ -244,6 +244,31 @@ def main():
                 ok += 1 if e <= eps * sq else 0
             fewer[f"bits-{drop}"] = {"tensors_within_eps": ok, "rel_sq_error": tot / sumsq}
             del q2
+        # the search over the bit width with the sketch bins, on top of the grid search of the step
+        ctx.search(cur, grid, eps, want_scores=False)
+        for it in range(3):
+            if it == 1:
+                torch.cuda.synchronize()
+                ctx.profile(True)
+                t0 = time.perf_counter()
+            q_ss, choices, _ = ctx.search_sketch(cur, cfgs, uni, eps, alpha=0.01, sigma=0.2, max_iter=100,
+                                                 reuse_search=True)
+        torch.cuda.synchronize()
+        ssdt = (time.perf_counter() - t0) / 2
+        ssprof = ctx.profile_read()
+        ctx.profile(False)
+        bits_hist = {}
+        for ch in choices:
+            bits_hist[ch["best_bits"]] = bits_hist.get(ch["best_bits"], 0) + 1
+        search_bits = {"ms_after_a_search": round(ssdt * 1e3, 3),
+                       "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(ssprof.items())},
+                       "k_sketch_score_GB/s": round(n_total * 4 / (ssprof["k_sketch_score"][0] / 2 * 1e-3) / 1e9, 1),
+                       "chosen_bits": {str(b): bits_hist[b] for b in sorted(bits_hist)},
+                       "infeasible": sum(1 for ch in choices if not ch["feasible"]),
+                       "symbol_bits_per_value": round(sum(t.numel() * (ch["best_bits"] + 1) for t, ch in zip(cur, choices)) / n_total, 3),
+                       "symbol_bits_per_value_equal_frequency": round(sum(t.numel() * (c[0] + 1) for t, c in zip(cur, cfgs)) / n_total, 3),
+                       "rel_sq_error": sum(ch["sse"][ch["best_bits"] - 2] for ch in choices) / sum(ch["sumsq"] for ch in choices)}
+        del q_ss
         hist_ms = sprof["k_sketch_hist"][0] / 2
         sketch = {"ms_after_a_search": round(sdt * 1e3, 3), "ms_stand_alone": round(sdt_alone * 1e3, 3),
                   "alpha": 0.01, "sigma": 0.2, "max_iter": 100,
@@ -255,7 +280,8 @@ def main():
                   "rounds_max": max(i[1] for i in sk_info),
                   "rel_sq_error_sketch_bins": err_sk / sumsq,
                   "rel_sq_error_equal_frequency_bins": err_eq / sumsq,
-                  "sketch_bins_with_fewer_bits": fewer}
+                  "sketch_bins_with_fewer_bits": fewer,
+                  "search_over_bits": search_bits}
         del q_sk, q_eq, buf
 
     cpu = None

@@ -814,7 +814,6 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
     const size_t o_slot = cv.off; // slot moments, cleared before the scoring sweep
     const size_t o_sc = cv.take(sizeof(u32) * SK_SLOTS * nT);
     const size_t o_sx = cv.take(sizeof(double) * SK_SLOTS * nT);
-    const size_t o_sxx = cv.take(sizeof(double) * SK_SLOTS * nT);
     const size_t slot_end = cv.off;
     int rc = ensure_dev(c, c->sketch_mem, cv.off);
     if (rc) return rc;
@@ -854,7 +853,6 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
     P.set_rounds = (u32 *)(db + o_sr);
     P.slot_cnt = (u32 *)(db + o_sc);
     P.slot_sx = (double *)(db + o_sx);
-    P.slot_sxx = (double *)(db + o_sxx);
     P.slot_edge = (u32 *)(db + o_se);
     P.choice = (SketchChoice *)(db + o_ch);
     P.final_key = (u32 *)(db + o_fk);

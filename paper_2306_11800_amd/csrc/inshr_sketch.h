@@ -45,7 +45,7 @@ struct SketchParams {
     double eps;            // bound on sse / sumsq
     u32 *set_rounds;       // [nT][SK_SETS]
     u32 *slot_cnt;         // [nT][SK_SLOTS] values per slot between all boundaries, zero on entry
-    double *slot_sx, *slot_sxx; // [nT][SK_SLOTS] their sums and sums of squares, zero on entry
+    double *slot_sx;       // [nT][SK_SLOTS] their sums, zero on entry
     u32 *slot_edge;        // [nT][SK_SLOTS] the sorted boundaries
     SketchChoice *choice;  // [nT]
     u32 *final_key;        // [nT][256] the chosen set, where the quantizer looks for it

@@ -395,9 +395,19 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
 // exact error of every set of centres (Sec. 5 restricted to the number of bins)
 // ------------------------------------------------------------------------------------------
 // All boundaries of a tensor's SK_SETS sets, sorted, cut the key axis into at most SK_EDGES + 1
-// slots; a slot lies inside one cluster of every set, so count, sum and sum of squares per slot
-// give the error of every set: sum over slots of sxx - 2 c sx + n c^2 with c the slot's centre.
+// slots; a slot lies inside one cluster of every set, so count and sum per slot give the error of
+// every set: (sum_all - sum_protected) x^2 - sum over slots of (2 c sx - n c^2), c the slot's centre.
 __device__ __forceinline__ u32 n_boundaries_before(u32 set) { return (4u << set) - 4u - set; } // sum of 2^b - 1, b = 2 .. set + 1
+
+// first key (integer image) of the histogram position slot: positive bucket b holds the magnitudes
+// (top[b-1], top[b]], negative bucket b their mirror images, whose keys ascend towards -top[b-1] - 1
+__device__ __forceinline__ u32 first_key_of_slot(u32 slot, const SketchParams &P)
+{
+    if (slot == 2u * (u32)SK_MAX_IDX) return ZERO_KEY;
+    if (slot < (u32)SK_MAX_IDX) return slot < P.n_idx ? key_pos((slot ? P.tops[slot - 1u] : 0u) + 1u) : 0xFFFFFFFFu;
+    const u32 b = slot - (u32)SK_MAX_IDX;
+    return b < P.n_idx ? key_neg(P.tops[b]) : 0u;
+}
 
 __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict__ td, int nT,
                                                         const u64 *__restrict__ wg_tile0,
@@ -405,12 +415,18 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
                                                         const SketchDesc *__restrict__ sd,
                                                         SketchParams P, Bufs B)
 {
+    // The slot of a key = the boundaries at or below it.  The sketch bucket of the key (one table
+    // read, as in k_sketch_hist) gives the boundaries below the bucket's first key; the few
+    // boundaries inside the bucket are compared one by one.
+    __shared__ u32 cell[SK_CELLS];
+    __shared__ u16 base[SK_HIST + 1];
     __shared__ u32 raw[SK_EDGES], edge[SK_EDGES + 1];
     __shared__ u32 cnt[SK_EDGES + 1];
-    __shared__ double sx[SK_EDGES + 1], sxx[SK_EDGES + 1];
+    __shared__ double sx[SK_EDGES + 1];
     const u32 tid = threadIdx.x;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
+    for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = P.cell[i];
     int t = find_tensor(td, nT, tile_lo);
     u64 tile = tile_lo;
     while (tile < tile_hi) {
@@ -437,7 +453,6 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
         for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
             cnt[i] = 0u;
             sx[i] = 0.0;
-            sxx[i] = 0.0;
         }
         __syncthreads();
         if (tid < (u32)SK_EDGES) { // sort by counting the smaller ones
@@ -451,6 +466,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
         }
         if (tid == 0) edge[SK_EDGES] = 0xFFFFFFFFu;
         __syncthreads();
+        for (u32 i = tid; i < (u32)SK_HIST; i += BLOCK) { // boundaries below the first key of every bucket
+            const u32 fk = first_key_of_slot(i, P);
+            u32 lo = 0u;
+#pragma unroll
+            for (u32 step = 256u; step > 0u; step >>= 1)
+                if (lo + step <= (u32)SK_EDGES && edge[lo + step - 1u] < fk) lo += step;
+            base[i] = (u16)lo;
+        }
+        __syncthreads();
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
             const u64 rem = d.n - e0;
@@ -459,28 +483,29 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
             const u32 mask = load_tile(d, e0, c, v);
 #pragma unroll 4
             for (int i = 0; i < 16; i++) {
-                const u32 key = key_of_float(v[i]);
-                const u32 mag = mag_of_key(key);
+                const u32 bits = __float_as_uint(v[i]);
+                const u32 mag = bits & 0x7fffffffu;
                 if (!((mask >> i) & 1u) || mag < tau_p || mag > tau_o) continue;
-                u32 slot = 0u; // edges at or below the key
-#pragma unroll
-                for (u32 step = 256u; step > 0u; step >>= 1)
-                    if (slot + step <= (u32)SK_EDGES && edge[slot + step - 1u] <= key) slot += step;
-                const double x = (double)v[i];
+                u32 hs; // position in the sketch histogram
+                if (mag >= 0x00800000u)
+                    hs = ((cell[mag >> 17] + (mag & 0x1FFFFu)) >> 17) + (bits >> 31) * (u32)SK_MAX_IDX;
+                else
+                    hs = sketch_slot_small(bits, P);
+                const u32 key = key_of_float(v[i]);
+                u32 slot = base[hs];
+                while (edge[slot] <= key) slot++; // (the list ends with 0xFFFFFFFF, above every finite key)
                 atomicAdd(&cnt[slot], 1u);
-                atomicAdd(&sx[slot], x);
-                atomicAdd(&sxx[slot], x * x);
+                atomicAdd(&sx[slot], (double)v[i]);
             }
         }
         __syncthreads();
         // this unit's part of the tensor's slot moments
         u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
-        double *gx = P.slot_sx + (size_t)t * SK_SLOTS, *gxx = P.slot_sxx + (size_t)t * SK_SLOTS;
+        double *gx = P.slot_sx + (size_t)t * SK_SLOTS;
         for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
             if (cnt[i]) {
                 atomicAdd(&gc[i], cnt[i]);
                 atomicAdd(&gx[i], sx[i]);
-                atomicAdd(&gxx[i], sxx[i]);
             }
         }
         if (tid < (u32)SK_EDGES) P.slot_edge[(size_t)t * SK_SLOTS + tid] = edge[tid]; // (the same from every unit)
@@ -503,16 +528,16 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
     const u32 tid = threadIdx.x;
     const TState *st = B.ts + t;
     const u32 pair = gd->cfg_pair[s.cfg];
-    // sum of squares of the pruned values = all - protected - quantized (the last from the slots)
+    // sum_pruned x^2 + sum_quantized (x - c)^2 = (sum_all - sum_protected) x^2 - sum_quantized (2 c x - c^2)
     const double not_protected = st->sumsq - st->thr_sumsq[gd->n_p + gd->pair_o[pair]];
     const u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
-    const double *gx = P.slot_sx + (size_t)t * SK_SLOTS, *gxx = P.slot_sxx + (size_t)t * SK_SLOTS;
+    const double *gx = P.slot_sx + (size_t)t * SK_SLOTS;
     const u32 *edge = P.slot_edge + (size_t)t * SK_SLOTS;
     if (tid < (u32)SK_SETS) {
         const u32 set = tid, bits = 2u + set, Kb = 1u << bits, sh = 8u - bits;
         const u32 *ak = P.alt_key + ((size_t)t * SK_SETS + set) * 256;
         const float *acb = P.alt_cb + ((size_t)t * SK_SETS + set) * 256;
-        double sse = 0.0, quantized = 0.0;
+        double gain = 0.0;
         u32 cluster = 0u; // of the current slot: boundaries of this set at or below the slot's keys
         for (u32 slot = 0; slot <= (u32)SK_EDGES; slot++) {
             if (slot > 0u) { // the slot starts at edge[slot - 1]
@@ -522,12 +547,11 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
             const u32 n = gc[slot];
             if (n) {
                 const double c = (double)acb[cluster];
-                sse += gxx[slot] - 2.0 * c * gx[slot] + (double)n * c * c;
-                quantized += gxx[slot];
+                gain += 2.0 * c * gx[slot] - (double)n * c * c;
             }
         }
-        const double pruned = not_protected - quantized;
-        s_sse[set] = (pruned > 0.0 ? pruned : 0.0) + (sse > 0.0 ? sse : 0.0);
+        const double sse = not_protected - gain;
+        s_sse[set] = sse > 0.0 ? sse : 0.0;
     }
     __syncthreads();
     if (tid == 0) {
