@@ -227,3 +227,47 @@ def test_tile_structured_tensor_under_the_sampled_sweep(ctx):
         got = unpack(q.packed, n, cfg[0] + 1)
         assert torch.equal(got, r["sym"]), int((got != r["sym"]).sum())
         assert (q.n_kept, q.n_outlier) == (r["M"], int(r["prot"].sum()))
+
+
+def test_largest_tensor_search_over_bits_with_sketch_bins(ctx):
+    """inshr_search_sketch on the 131 M-value shape on top of a grid search (the configuration
+    bench.py --sketch times): the reported error of the chosen width equals the squared distance
+    between the tensor and its decoded form computed with torch, the choice obeys the rule (fewest
+    bits within the bound), and every symbol is the nearest centre of the returned codebook."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(80)
+    x = torch.empty(N, dtype=torch.float32, device=dev)
+    step = 1 << 26
+    for s in range(0, N, step):
+        e = min(N, s + step)
+        z = torch.randn(4, e - s, dtype=torch.float32, device=dev, generator=g)
+        x[s:e] = 0.015 * z[0] / torch.sqrt((z[1] * z[1] + z[2] * z[2] + z[3] * z[3]) / 3.0)
+        del z
+    x[x == 0] = 1e-6
+    grid = synth.grid_full()
+    eps = synth.EPS_DEFAULT
+    uni = np.random.default_rng(6).uniform(size=(1, 256))
+    ctx.search([x], grid, eps, want_scores=False)
+    (q,), (ch,), _ = ctx.search_sketch([x], [(0, 200000, 1000)], uni, eps, reuse_search=True)
+    bits = ch["best_bits"]
+    assert q.bits == bits and 2 <= bits <= 8
+    sumsq = float((x.double() ** 2).sum())
+    assert abs(ch["sumsq"] - sumsq) <= 1e-9 * sumsq
+    y = ctx.dequantize([q])[0]
+    sse = float(((x.double() - y.double()) ** 2).sum())
+    got_sse = ch["sse"][bits - 2]
+    assert abs(got_sse - sse) <= 1e-6 * sse + 1e-12 * sumsq, (got_sse, sse)
+    assert ch["feasible"] and got_sse <= eps * sumsq
+    assert bits == 2 or ch["sse"][bits - 3] > eps * sumsq
+    K = 1 << bits
+    cb = q.codebook.double()
+    assert bool((cb[1:] >= cb[:-1]).all())
+    mids = (cb[:-1] + cb[1:]) / 2
+    sym = unpack(q.packed, N, bits + 1)
+    kept = sym >= 2
+    want = 2 + torch.bucketize(x[kept].double(), mids, right=False)  # strictly above the midpoint -> upper centre
+    assert torch.equal(sym[kept].to(torch.int64), want)
+    A = torch.sort(x.abs()).values
+    tau_p, tau_o = A[N * 200000 // 1_000_000], A[N - 1 - N * 1000 // 1_000_000]
+    assert torch.equal(sym == 0, x.abs() < tau_p) and torch.equal(sym == 1, x.abs() > tau_o)
