@@ -12,6 +12,7 @@ constexpr int SK_LDS = 4096;               // longest bucket list that the clust
 constexpr int SK_SETS = 7;                 // sets of centres of a search over the bits: 2 .. 8 bits
 constexpr int SK_EDGES = 501;              // boundaries of all sets: sum of 2^b - 1
 constexpr int SK_SLOTS = 512;              // stride of the per-slot arrays (SK_EDGES + 1 slots)
+constexpr int SK_COPIES = 4;               // LDS copies of the slot moments in the scoring sweep (power of two)
 
 struct SketchDesc { // one tensor of the batch
     u32 active;     // part of the call

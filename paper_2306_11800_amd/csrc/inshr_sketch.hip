@@ -430,9 +430,11 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
     __shared__ u32 cell[SK_CELLS];
     __shared__ u16 base[SK_HIST + 1];
     __shared__ u32 raw[SK_EDGES], edge[SK_EDGES + 1];
-    __shared__ u32 cnt[SK_EDGES + 1];
-    __shared__ double sx[SK_EDGES + 1];
-    const u32 tid = threadIdx.x;
+    // (four copies of the slot moments, one per lane modulo 4: the slots are few and the lanes of a
+    // wave that hit the same address are served one after the other)
+    __shared__ u32 cnt[SK_COPIES * SK_SLOTS];
+    __shared__ double sx[SK_COPIES * SK_SLOTS];
+    const u32 tid = threadIdx.x, copy = (tid & (u32)(SK_COPIES - 1)) * (u32)SK_SLOTS;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = P.cell[i];
@@ -459,7 +461,7 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
             const u32 j = tid - n_boundaries_before(set), bits = 2u + set;
             raw[tid] = P.alt_key[((size_t)t * SK_SETS + set) * 256 + (((j + 1u) << (8u - bits)) - 1u)];
         }
-        for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
+        for (u32 i = tid; i < (u32)(SK_COPIES * SK_SLOTS); i += BLOCK) {
             cnt[i] = 0u;
             sx[i] = 0.0;
         }
@@ -503,8 +505,8 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
                 const u32 key = key_of_float(v[i]);
                 u32 slot = base[hs];
                 while (edge[slot] <= key) slot++; // (the list ends with 0xFFFFFFFF, above every finite key)
-                atomicAdd(&cnt[slot], 1u);
-                atomicAdd(&sx[slot], (double)v[i]);
+                atomicAdd(&cnt[copy + slot], 1u);
+                atomicAdd(&sx[copy + slot], (double)v[i]);
             }
         }
         __syncthreads();
@@ -512,9 +514,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
         u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
         double *gx = P.slot_sx + (size_t)t * SK_SLOTS;
         for (u32 i = tid; i <= (u32)SK_EDGES; i += BLOCK) {
-            if (cnt[i]) {
-                atomicAdd(&gc[i], cnt[i]);
-                atomicAdd(&gx[i], sx[i]);
+            u32 n = 0u;
+            double sum = 0.0;
+            for (u32 k = 0; k < (u32)SK_COPIES; k++) {
+                n += cnt[k * SK_SLOTS + i];
+                sum += sx[k * SK_SLOTS + i];
+            }
+            if (n) {
+                atomicAdd(&gc[i], n);
+                atomicAdd(&gx[i], sum);
             }
         }
         if (tid < (u32)SK_EDGES) P.slot_edge[(size_t)t * SK_SLOTS + tid] = edge[tid]; // (the same from every unit)
