@@ -2,7 +2,11 @@
 host, with and without the regrouping by the previous symbol (Sec. 6; the shape of the paper's delta
 ablation).  Synthetic GPT-2-medium-shaped weights with Adam state, five steps.
 
-    python -m paper_2306_11800_amd.ratio_report [--scale 0.25] [--threads 16]
+    python -m paper_2306_11800_amd.ratio_report [--scale 0.25] [--threads 16] [--bins sketch]
+
+--bins sketch keeps the prune / protect fractions the grid search chose and takes the bins from the
+sketch + weighted K-Means rule with the fewest bits that meet eps (inshr_search_sketch; the same
+uniform numbers at every step).
 
 Prints one JSON line per step and a summary line.  Bytes of a step = entropy-coded delta streams +
 codebooks + protected values (index and value, 8 bytes each) + group offsets.
@@ -37,6 +41,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks the first dimension of every tensor")
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--bins", choices=["equal", "sketch"], default="equal")
     args = ap.parse_args()
     dev = torch.device("cuda:0")
     ctx = api.Context(dev)
@@ -48,10 +53,15 @@ def main():
     for t in range(args.steps):
         ts = [torch.from_numpy(st[t]).to(dev) for _, st in items]
         best, _, _ = ctx.search(ts, grid, eps, want_scores=False)
-        q_cur = ctx.quantize(ts, [grid[b] for b in best], reuse_search=True)
+        if args.bins == "sketch":
+            uni = np.random.default_rng(0).uniform(size=(len(ts), 256))
+            q_cur, choices, _ = ctx.search_sketch(ts, [grid[b] for b in best], uni, eps, reuse_search=True)
+        else:
+            q_cur = ctx.quantize(ts, [grid[b] for b in best], reuse_search=True)
         side = sum(4 * (1 << q.bits) + 8 * q.n_outlier for q in q_cur)  # codebooks, protected values
         quantized = sum((q.n * q.sym_bits + 7) // 8 for q in q_cur) + side
-        line = dict(step=t, fp32_bytes=4 * n_total, quantized_bytes=quantized)
+        line = dict(step=t, fp32_bytes=4 * n_total, quantized_bytes=quantized,
+                    mean_symbol_bits=round(sum(q.n * q.sym_bits for q in q_cur) / n_total, 3))
         if q_prev is not None:
             ds = ctx.delta(q_prev, q_cur, want_perm=True)
             ctx.sync()
