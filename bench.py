@@ -269,6 +269,30 @@ def main():
                        "symbol_bits_per_value_equal_frequency": round(sum(t.numel() * (c[0] + 1) for t, c in zip(cur, cfgs)) / n_total, 3),
                        "rel_sq_error": sum(ch["sse"][ch["best_bits"] - 2] for ch in choices) / sum(ch["sumsq"] for ch in choices)}
         del q_ss
+        # a whole step with the sketch bins and fixed fractions (those most tensors got): thresholds
+        # only from the search kernels, sketch, clustering, scoring, quantize, then the delta
+        common = max(set((c[1], c[2]) for c in cfgs), key=lambda pq: sum(1 for c in cfgs if (c[1], c[2]) == pq))
+        fixed = [(0, common[0], common[1])] * len(cur)
+        q_alt = d_alt = None
+        for it in range(3):
+            if it == 1:
+                torch.cuda.synchronize()
+                ctx.profile(True)
+                t0 = time.perf_counter()
+            q_alt, alt_choices, _ = ctx.search_sketch(cur, fixed, uni, eps, alpha=0.01, sigma=0.2, max_iter=100,
+                                                      out=q_alt)
+            d_alt = ctx.delta(q_prev, q_alt, out=d_alt)
+            ctx.sync()
+        torch.cuda.synchronize()
+        adt = (time.perf_counter() - t0) / 2
+        aprof = ctx.profile_read()
+        ctx.profile(False)
+        search_bits["whole_step_with_fixed_fractions"] = {
+            "prune_ppm": common[0], "outlier_ppm": common[1], "ms": round(adt * 1e3, 3),
+            "GB/s": round(n_total * 4 / adt / 1e9, 1),
+            "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(aprof.items()) if v[0] / 2 >= 0.05},
+            "symbol_bits_per_value": round(sum(t.numel() * (ch["best_bits"] + 1) for t, ch in zip(cur, alt_choices)) / n_total, 3)}
+        del q_alt, d_alt
         hist_ms = sprof["k_sketch_hist"][0] / 2
         sketch = {"ms_after_a_search": round(sdt * 1e3, 3), "ms_stand_alone": round(sdt_alone * 1e3, 3),
                   "alpha": 0.01, "sigma": 0.2, "max_iter": 100,

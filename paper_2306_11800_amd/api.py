@@ -388,10 +388,11 @@ class Context:
     # -- inshr_search_sketch ---------------------------------------------------------------
     def search_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, eps: float,
                       alpha: float = 0.01, sigma: float = 0.2, max_iter: int = 100,
-                      reuse_search: bool = False):
+                      reuse_search: bool = False, out: Optional[List[Quantized]] = None):
         """cfgs: (ignored bits, prune_ppm, outlier_ppm) per tensor.  Returns (list of Quantized with
         the chosen bits, list of dict(best_bits, feasible, sse[7], sumsq, rounds[7]), list of
-        (n_buckets, rounds of the widest set))."""
+        (n_buckets, rounds of the widest set)).  `out` may carry the list an earlier call returned
+        for tensors of the same sizes and protect fractions; its buffers are then written again."""
         import numpy as np
         nT = len(tensors)
         ta = _tensor_array(tensors)
@@ -400,9 +401,12 @@ class Context:
         u = np.ascontiguousarray(uniforms, dtype=np.float64)
         if u.shape != (nT, 256):
             raise ValueError("uniforms must have shape [len(tensors), 256]")
-        qa = (CQuantized * nT)()
-        res = QuantizedBatch()
+        reuse_out = isinstance(out, QuantizedBatch) and out._sizes == tuple(t.numel() for t in tensors)
+        qa = out._qa if reuse_out else (CQuantized * nT)()
+        res = out if reuse_out else QuantizedBatch()
         for i, (t, cfg) in enumerate(zip(tensors, wide)):
+            if reuse_out:
+                break  # the C side checks every buffer against what the configuration needs
             n = t.numel()
             words, cap = self._bound(n, ca[i], cfg)
             e = qa[i]
@@ -416,8 +420,9 @@ class Context:
             e.packed_words = q._bufs[0].numel()
             e.outlier_cap = q._bufs[3].numel()
             res.append(q)
-        res._qa = qa
-        res._sizes = tuple(q.n for q in res)
+        if not reuse_out:
+            res._qa = qa
+            res._sizes = tuple(q.n for q in res)
         par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
         info = (CSketchInfo * nT)()
         choice = (CSketchChoice * nT)()

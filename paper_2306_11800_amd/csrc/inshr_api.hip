@@ -43,6 +43,9 @@ struct inshr_ctx {
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
     DevBuf aux_mem;    // quantize descriptors, delta scratch
     DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
+    double sketch_alpha = 0.0;                 // the bucket tables last built, and for which alpha
+    std::vector<u32> sketch_cell, sketch_tops;
+    std::vector<double> sketch_rep;
     HostBuf h_up;      // staging for descriptor uploads
     HostBuf h_down;    // staging for result downloads
 
@@ -203,8 +206,11 @@ int build_grid(const inshr_config *grid, uint32_t n_cfg, double eps, GridDesc &g
     return INSHR_OK;
 }
 
+// light: thresholds, class counts and the second-level table only (for the sketch quantizer, which
+// brings its own bins and takes the protected counts per tile in its own sweep); the state is then
+// not offered to INSHR_REUSE_SEARCH.
 int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const inshr_config *grid,
-               uint32_t n_cfg, double eps)
+               uint32_t n_cfg, double eps, bool light = false)
 {
     c->have_search = false;
     if (!tensors || !grid || nT == 0) return INSHR_E_ARG;
@@ -403,8 +409,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         c->ts_off = o_ts;
         c->scores_off = o_sc;
     }
+    c->batch.light = light;
     HIPCHK(c, launch_select(c->batch, c->stream));
-    HIPCHK(c, launch_score(c->batch, c->stream));
+    if (!light) HIPCHK(c, launch_score(c->batch, c->stream));
 
     // results: per-tensor state and scores
     const size_t ts_bytes = sizeof(TState) * nT, sc_bytes = sizeof(Score) * (size_t)nT * n_cfg;
@@ -441,7 +448,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
     c->grid = g;
     c->grid_cfgs.assign(grid, grid + n_cfg);
     c->tensors.assign(tensors, tensors + nT);
-    c->have_search = true;
+    c->have_search = !light;
     return INSHR_OK;
 }
 
@@ -726,9 +733,15 @@ struct SketchTables {
 // number <= gamma^(i_lo + b) (extended precision; a value x lies in the first bucket whose top
 // reaches it), rep[b] = the bucket's value, cell[c] = first bucket and its top for the magnitudes
 // c << 17 .. (c << 17) + 2^17 - 1.
-int build_sketch_tables(double alpha, SketchTables &T)
+int build_sketch_tables(inshr_ctx *ctx, double alpha, SketchTables &T)
 {
     if (!(alpha >= 0.01 && alpha <= 0.5)) return INSHR_E_CONFIG;
+    if (ctx->sketch_alpha == alpha) { // the tables of the call before
+        T.cell = ctx->sketch_cell;
+        T.tops = ctx->sketch_tops;
+        T.rep = ctx->sketch_rep;
+        return INSHR_OK;
+    }
     const double gamma = (1.0 + alpha) / (1.0 - alpha);
     const long double lg = logl((long double)gamma);
     const int i_lo = (int)floorl(-149.0L * logl(2.0L) / lg) - 2;
@@ -760,6 +773,10 @@ int build_sketch_tables(double alpha, SketchTables &T)
         const u32 split = T.tops[b0] <= last ? (T.tops[b0] & 0x1FFFFu) : 0x1FFFFu;
         T.cell[c] = (b0 << 17) | (0x1FFFFu - split); // adding the low magnitude bits carries above the split
     }
+    ctx->sketch_cell = T.cell;
+    ctx->sketch_tops = T.tops;
+    ctx->sketch_rep = T.rep;
+    ctx->sketch_alpha = alpha;
     return INSHR_OK;
 }
 
@@ -849,6 +866,7 @@ int sketch_with_state(inshr_ctx *c, const inshr_config *cfg, const uint32_t *whi
     P.alt_cb = (float *)(db + o_cb);
     P.info = (SketchInfo *)(db + o_info);
     P.multi = multi ? 1u : 0u;
+    P.light = c->batch.light ? 1u : 0u;
     P.eps = eps;
     P.set_rounds = (u32 *)(db + o_sr);
     P.slot_cnt = (u32 *)(db + o_sc);
@@ -908,7 +926,7 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
         }
     }
     SketchTables T;
-    int rc = build_sketch_tables(params->alpha, T);
+    int rc = build_sketch_tables(c, params->alpha, T);
     if (rc) return rc;
     HIPCHK(c, hipSetDevice(c->device));
     const u32 *alt_key = nullptr;
@@ -941,7 +959,7 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
             }
         }
         const uint32_t nS = (uint32_t)sub.size();
-        rc = run_search(c, sub.data(), nS, &cfg[t0], 1, 0.0);
+        rc = run_search(c, sub.data(), nS, &cfg[t0], 1, 0.0, true);
         if (rc) return rc;
         std::vector<inshr_quantized> subout(nS);
         std::vector<uint32_t> which(nS);
@@ -978,7 +996,7 @@ int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_c
         }
     }
     SketchTables T;
-    int rc = build_sketch_tables(params->alpha, T);
+    int rc = build_sketch_tables(c, params->alpha, T);
     if (rc) return rc;
     HIPCHK(c, hipSetDevice(c->device));
     const u32 *alt_key = nullptr;
@@ -1024,7 +1042,7 @@ int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_c
             grid7[b] = wide[t0];
             grid7[b].bits = (uint8_t)(2 + b);
         }
-        rc = run_search(c, sub.data(), nS, grid7, SK_SETS, eps);
+        rc = run_search(c, sub.data(), nS, grid7, SK_SETS, eps, true);
         if (rc) return rc;
         std::vector<inshr_quantized> subout(nS);
         std::vector<uint32_t> which(nS);

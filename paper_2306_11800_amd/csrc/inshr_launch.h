@@ -68,6 +68,8 @@ struct Batch {
     int n_units;
     int n_bucket_blocks;
     bool lds_ordered;    // same-address LDS atomics return in lane order on this device
+    bool light;          // thresholds and class counts only: no boundaries, no scores (the sketch
+                         // quantizer brings its own bins)
     bool any_sampled;    // some tensor's sweep 1 is sampled
     bool force_miss;     // (tests) every sampled tensor is sent through the exact sweeps again
     u32 n_pairs, n_cfg;

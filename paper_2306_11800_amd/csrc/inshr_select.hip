@@ -1611,6 +1611,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     PROF("k_thr_count", s, k_thr_count<1><<<bt.n_units, TSEL, 0, s>>>(bt.td, bt.fu_tensor, B));
     PROF("k_thr_pick", s, k_thr_pick<1><<<bt.nT, TSEL, 0, s>>>(bt.td, B));
     PROF("k_plan2", s, k_plan2<<<bt.nT, BLOCK, SM_PLAN2, s>>>(bt.td, bt.gd, B));
+    if (bt.light) return hipGetLastError();
     if ((e = launch_edges(bt, s))) return e;
     PROF("k_gather", s, k_gather<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, bt.gd, B));
     PROF("k_group_list", s, k_group_list<<<bt.nT, 256, 0, s>>>(bt.nT, B, bt.grp_list, bt.n_grp_total));

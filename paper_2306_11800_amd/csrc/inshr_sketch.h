@@ -43,6 +43,8 @@ struct SketchParams {
     SketchInfo *info;      // [nT]
     // search over the bits (multi != 0): alt_key / alt_cb hold SK_SETS rows of 256 per tensor
     u32 multi;
+    u32 light;             // the search state is a light one: this sweep also takes the protected counts
+                           // per tile and their sum of squares, and the choice sums the squares itself
     double eps;            // bound on sse / sumsq
     u32 *set_rounds;       // [nT][SK_SETS]
     u32 *slot_cnt;         // [nT][SK_SLOTS] values per slot between all boundaries, zero on entry

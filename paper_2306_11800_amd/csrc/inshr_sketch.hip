@@ -49,9 +49,11 @@ __device__ __noinline__ u32 sketch_slot_small(u32 bits, const SketchParams &P)
     return lo + (bits >> 31) * (u32)SK_MAX_IDX;
 }
 
-template <bool FULL>
+// LIGHT: also the protected values of the tile (wave-uniform count) and their squares.
+template <bool FULL, bool LIGHT>
 __device__ __forceinline__ void sketch_tile(const float (&v)[16], u32 mask, u32 tau_p, u32 tau_o,
-                                            const u32 *cell, u32 *h, const SketchParams &P)
+                                            const u32 *cell, u32 *h, const SketchParams &P, u32 &n_prot,
+                                            double &q_prot)
 {
     u32 small = 0u; // elements between the thresholds whose magnitude is zero or denormal
 #pragma unroll
@@ -60,6 +62,14 @@ __device__ __forceinline__ void sketch_tile(const float (&v)[16], u32 mask, u32 
         const u32 mag = bits & 0x7fffffffu;
         bool take = mag >= tau_p && mag <= tau_o;
         if (!FULL) take = take && ((mask >> i) & 1u);
+        if (LIGHT) {
+            const bool prot = mag > tau_o && (FULL || ((mask >> i) & 1u));
+            const u64 pm = __ballot(prot);
+            if (pm) {
+                n_prot += (u32)__popcll(pm);
+                if (prot) q_prot = fma((double)v[i], (double)v[i], q_prot);
+            }
+        }
         if (take && mag < 0x00800000u) small |= 1u << i;
         if (take && mag >= 0x00800000u) {
             // entry = first bucket of the cell << 17 | (2^17 - 1 - low bits of that bucket's largest
@@ -75,8 +85,10 @@ __device__ __forceinline__ void sketch_tile(const float (&v)[16], u32 mask, u32 
     }
 }
 
+template <bool LIGHT>
 __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__ td, int nT,
                                                        const u64 *__restrict__ wg_tile0,
+                                                       const u32 *__restrict__ wg_fu0,
                                                        const GridDesc *__restrict__ gd,
                                                        const SketchDesc *__restrict__ sd,
                                                        SketchParams P, Bufs B)
@@ -85,12 +97,14 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
     __shared__ u32 smem[SK_CELLS + SK_HIST];
     u32 *cell = smem;
     u32 *h = smem + SK_CELLS;
-    const u32 tid = threadIdx.x;
+    __shared__ double s_q[BLOCK / 64];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
     for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = P.cell[i];
     for (int i = tid; i < SK_HIST; i += BLOCK) h[i] = 0u;
     int t = find_tensor(td, nT, tile_lo);
+    const int t_first = t;
     u64 tile = tile_lo;
     while (tile < tile_hi) {
         const TDesc d = td[t];
@@ -105,7 +119,9 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
         }
         const TState *st = B.ts + t;
         const u32 pair = gd->cfg_pair[s.cfg];
-        const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + gd->pair_o[pair]];
+        const u32 o = gd->pair_o[pair];
+        const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + o];
+        double q_prot = 0.0; // squares of this thread's protected values
         __syncthreads();
         for (; tile < stop; tile++) {
             const u64 e0 = (tile - d.tile0) * (u64)TILE;
@@ -113,12 +129,23 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_hist(const TDesc *__restrict__
             const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
             float v[16];
             const u32 mask = load_tile(d, e0, cnt, v);
+            u32 n_prot = 0u; // protected values of this wave in the tile (wave-uniform)
             if (cnt == (u32)TILE)
-                sketch_tile<true>(v, mask, tau_p, tau_o, cell, h, P);
+                sketch_tile<true, LIGHT>(v, mask, tau_p, tau_o, cell, h, P, n_prot, q_prot);
             else
-                sketch_tile<false>(v, mask, tau_p, tau_o, cell, h, P);
+                sketch_tile<false, LIGHT>(v, mask, tau_p, tau_o, cell, h, P, n_prot, q_prot);
+            if (LIGHT && lane == 0u && n_prot) atomicAdd(&B.tile_out[tile * MAX_FRAC + o], n_prot);
+        }
+        if (LIGHT) { // this unit's sum of squares of the protected values, in a fixed order
+            q_prot = wave_sum_f64(q_prot);
+            if (lane == 0u) s_q[wave] = q_prot;
         }
         __syncthreads();
+        if (LIGHT && tid == 0) {
+            double sum = 0.0;
+            for (int w = 0; w < BLOCK / 64; w++) sum += s_q[w];
+            B.sq_part[(size_t)(wg_fu0[blockIdx.x] + (u32)(t - t_first)) * SQ_STRIDE + 1u + o] = sum;
+        }
         u32 *gh = P.hist + (size_t)t * SK_HIST;
         for (int i = tid; i < SK_HIST; i += BLOCK) {
             const u32 c = h[i];
@@ -533,6 +560,8 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
 // per tensor: error of every set, the fewest bits within eps, and that set's keys and centres
 // where the quantizer looks for them
 __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__ td,
+                                                       const u32 *__restrict__ t_fu_off,
+                                                       const u32 *__restrict__ t_fu_ids,
                                                        const GridDesc *__restrict__ gd,
                                                        const SketchDesc *__restrict__ sd,
                                                        SketchParams P, Bufs B)
@@ -546,7 +575,16 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
     const TState *st = B.ts + t;
     const u32 pair = gd->cfg_pair[s.cfg];
     // sum_pruned x^2 + sum_quantized (x - c)^2 = (sum_all - sum_protected) x^2 - sum_quantized (2 c x - c^2)
-    const double not_protected = st->sumsq - st->thr_sumsq[gd->n_p + gd->pair_o[pair]];
+    double sumsq = st->sumsq, protsq = st->thr_sumsq[gd->n_p + gd->pair_o[pair]];
+    if (P.light) { // no scoring kernel has added the units' parts up
+        sumsq = 0.0;
+        protsq = 0.0;
+        for (u32 u = t_fu_off[t]; u < t_fu_off[t + 1]; u++) {
+            sumsq += B.sq_part[(size_t)t_fu_ids[u] * SQ_STRIDE];
+            protsq += B.sq_part[(size_t)t_fu_ids[u] * SQ_STRIDE + 1u + gd->pair_o[pair]];
+        }
+    }
+    const double not_protected = sumsq - protsq;
     const u32 *gc = P.slot_cnt + (size_t)t * SK_SLOTS;
     const double *gx = P.slot_sx + (size_t)t * SK_SLOTS;
     const u32 *edge = P.slot_edge + (size_t)t * SK_SLOTS;
@@ -572,7 +610,7 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
     }
     __syncthreads();
     if (tid == 0) {
-        const double bound = P.eps * st->sumsq;
+        const double bound = P.eps * sumsq;
         u32 best = SK_SETS - 1u, feasible = 0u;
         for (u32 set = 0; set < (u32)SK_SETS; set++)
             if (s_sse[set] <= bound) {
@@ -586,7 +624,7 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
             r.sse[set] = s_sse[set];
             r.rounds[set] = P.set_rounds[(size_t)t * SK_SETS + set];
         }
-        r.sumsq = st->sumsq;
+        r.sumsq = sumsq;
         r.best_bits = 2u + best;
         r.feasible = feasible;
         P.choice[t] = r;
@@ -599,13 +637,18 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
 
 hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s)
 {
-    PROF("k_sketch_hist", s,
-         k_sketch_hist<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, sd, P, bt.bufs));
+    if (P.light)
+        PROF("k_sketch_hist", s, k_sketch_hist<true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0,
+                                                                              bt.gd, sd, P, bt.bufs));
+    else
+        PROF("k_sketch_hist", s, k_sketch_hist<false><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0,
+                                                                               bt.gd, sd, P, bt.bufs));
     PROF("k_sketch_kmeans", s, k_sketch_kmeans<<<bt.nT, BLOCK, 0, s>>>(bt.gd, sd, P));
     if (P.multi) {
         PROF("k_sketch_score", s,
              k_sketch_score<<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.gd, sd, P, bt.bufs));
-        PROF("k_sketch_choose", s, k_sketch_choose<<<bt.nT, 256, 0, s>>>(bt.td, bt.gd, sd, P, bt.bufs));
+        PROF("k_sketch_choose", s,
+             k_sketch_choose<<<bt.nT, 256, 0, s>>>(bt.td, bt.t_fu_off, bt.t_fu_ids, bt.gd, sd, P, bt.bufs));
     }
     return hipGetLastError();
 }
