@@ -156,6 +156,20 @@ def test_search_over_bits(ctx):
                  reuse_grid=grid)
 
 
+def test_stand_alone_state_is_not_offered_for_reuse(ctx):
+    """Stand-alone sketch calls search for thresholds and counts only; an equal-frequency quantize
+    that asks for the state of the last search must then be refused."""
+    from paper_2306_11800_amd import api
+    rng = np.random.default_rng(16)
+    x = dev((rng.standard_t(3, 30000) * 0.015).astype(np.float32))
+    ctx.quantize_sketch([x], [(4, 100000, 1000)], rng.uniform(size=(1, 256)))
+    with pytest.raises(api.InshrError) as e:
+        ctx.quantize([x], [(4, 100000, 1000)], reuse_search=True)
+    assert e.value.code == -5
+    q = ctx.quantize([x], [(4, 100000, 1000)])[0]  # stand-alone works as ever
+    assert q.n_kept > 0
+
+
 def test_argument_errors(ctx):
     from paper_2306_11800_amd import api
     x = dev(np.ones(100, np.float32))
