@@ -16,7 +16,8 @@
  *                   checkpoint, regrouped by the previous checkpoint's symbol (Algorithm 5).
  * and their inverses for the restore side: inshr_reconstruct (Algorithm 6) and inshr_dequantize;
  * inshr_quantize_sketch is the Quantizer with the paper's own bins (log-space sketch, Algorithm 1,
- * and weighted K-Means on its buckets, Algorithms 2 and 3).
+ * and weighted K-Means on its buckets, Algorithms 2 and 3), inshr_search_sketch the search for the
+ * fewest such bins that keep the error within eps (Sec. 5, over the number of bins).
  *
  * Conventions
  *   - Every function returns 0 on success or a negative INSHR_E_* code; nothing aborts or throws.
