@@ -99,4 +99,11 @@ def test_sampled_first_sweep(mode):
         biased[tile * 16_384:(tile + 1) * 16_384] *= 100.0
     curs = [step(rng, x, k) for k, x in enumerate(prevs)]
     run_pipeline(c, prevs, curs, synth.grid_full(), synth.EPS_DEFAULT, want_perm=False)
+    # a NaN / an Inf in a tile that the sampled sweep does not read is still found
+    for bad in (np.nan, np.inf, -np.inf):
+        x = prevs[3].copy()
+        x[3 * 16_384 + 5] = bad
+        with pytest.raises(api.InshrError) as e:
+            c.search([torch.from_numpy(x).to("cuda:0")], synth.grid_small(), synth.EPS_DEFAULT)
+        assert e.value.code == -3
     c.close()
