@@ -435,36 +435,29 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
 // every set: (sum_all - sum_protected) x^2 - sum over slots of (2 c sx - n c^2), c the slot's centre.
 __device__ __forceinline__ u32 n_boundaries_before(u32 set) { return (4u << set) - 4u - set; } // sum of 2^b - 1, b = 2 .. set + 1
 
-// first key (integer image) of the histogram position slot: positive bucket b holds the magnitudes
-// (top[b-1], top[b]], negative bucket b their mirror images, whose keys ascend towards -top[b-1] - 1
-__device__ __forceinline__ u32 first_key_of_slot(u32 slot, const SketchParams &P)
-{
-    if (slot == 2u * (u32)SK_MAX_IDX) return ZERO_KEY;
-    if (slot < (u32)SK_MAX_IDX) return slot < P.n_idx ? key_pos((slot ? P.tops[slot - 1u] : 0u) + 1u) : 0xFFFFFFFFu;
-    const u32 b = slot - (u32)SK_MAX_IDX;
-    return b < P.n_idx ? key_neg(P.tops[b]) : 0u;
-}
-
 __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict__ td, int nT,
                                                         const u64 *__restrict__ wg_tile0,
                                                         const GridDesc *__restrict__ gd,
                                                         const SketchDesc *__restrict__ sd,
                                                         SketchParams P, Bufs B)
 {
-    // The slot of a key = the boundaries at or below it.  The sketch bucket of the key (one table
-    // read, as in k_sketch_hist) gives the boundaries below the bucket's first key; the few
-    // boundaries inside the bucket are compared one by one.
-    __shared__ u32 cell[SK_CELLS];
-    __shared__ u16 base[SK_HIST + 1];
-    __shared__ u32 raw[SK_EDGES], edge[SK_EDGES + 1];
-    // (four copies of the slot moments, one per lane modulo 4: the slots are few and the lanes of a
-    // wave that hit the same address are served one after the other)
-    __shared__ u32 cnt[SK_COPIES * SK_SLOTS];
-    __shared__ double sx[SK_COPIES * SK_SLOTS];
+    // The slot of a key = the boundaries at or below it.  The search's equal-population bins (up to
+    // 32768 per tensor, found through the key-prefix table) are far finer than the 502 slots: a table
+    // gives the slot of every bin that holds no boundary, and for the few bins that do, the first
+    // boundary to compare the key with.
+    struct ScoreShared {
+        u32 T[COARSE];                        // key prefix -> bins
+        u16 stab[L2_BINS];                    // slot, or 0x8000 | boundaries below the bin
+        u32 raw[SK_EDGES], edge[SK_EDGES + 1];
+        // (four copies of the slot moments, one per lane modulo 4: the slots are few and the lanes
+        // of a wave that hit the same address are served one after the other)
+        u32 cnt[SK_COPIES * SK_SLOTS];
+        double sx[SK_COPIES * SK_SLOTS];
+    };
+    __shared__ ScoreShared sh;
     const u32 tid = threadIdx.x, copy = (tid & (u32)(SK_COPIES - 1)) * (u32)SK_SLOTS;
     const u64 tile_lo = wg_tile0[blockIdx.x], tile_hi = wg_tile0[blockIdx.x + 1];
     if (tile_lo >= tile_hi) return;
-    for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = P.cell[i];
     int t = find_tensor(td, nT, tile_lo);
     u64 tile = tile_lo;
     while (tile < tile_hi) {
@@ -481,36 +474,50 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
         const TState *st = B.ts + t;
         const u32 pair = gd->cfg_pair[s.cfg];
         const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + gd->pair_o[pair]];
+        const u32 nb2 = st->nb2;
         __syncthreads();
+        for (u32 i = tid; i < (u32)COARSE; i += BLOCK) sh.T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);
         if (tid < (u32)SK_EDGES) { // boundary j of set b sits at ((j + 1) << (8 - bits)) - 1 of its row
             u32 set = 0u;
             while (set + 1u < (u32)SK_SETS && tid >= n_boundaries_before(set + 1u)) set++;
             const u32 j = tid - n_boundaries_before(set), bits = 2u + set;
-            raw[tid] = P.alt_key[((size_t)t * SK_SETS + set) * 256 + (((j + 1u) << (8u - bits)) - 1u)];
+            sh.raw[tid] = P.alt_key[((size_t)t * SK_SETS + set) * 256 + (((j + 1u) << (8u - bits)) - 1u)];
         }
         for (u32 i = tid; i < (u32)(SK_COPIES * SK_SLOTS); i += BLOCK) {
-            cnt[i] = 0u;
-            sx[i] = 0.0;
+            sh.cnt[i] = 0u;
+            sh.sx[i] = 0.0;
         }
         __syncthreads();
         if (tid < (u32)SK_EDGES) { // sort by counting the smaller ones
-            const u32 x = raw[tid];
+            const u32 x = sh.raw[tid];
             u32 r = 0u;
             for (u32 i = 0; i < (u32)SK_EDGES; i++) {
-                const u32 y = raw[i];
+                const u32 y = sh.raw[i];
                 r += (y < x || (y == x && i < tid)) ? 1u : 0u;
             }
-            edge[r] = x;
+            sh.edge[r] = x;
         }
-        if (tid == 0) edge[SK_EDGES] = 0xFFFFFFFFu;
+        if (tid == 0) sh.edge[SK_EDGES] = 0xFFFFFFFFu;
         __syncthreads();
-        for (u32 i = tid; i < (u32)SK_HIST; i += BLOCK) { // boundaries below the first key of every bucket
-            const u32 fk = first_key_of_slot(i, P);
-            u32 lo = 0u;
+        for (u32 b = tid; b < nb2; b += BLOCK) { // slot of every bin, or its first boundary
+            u32 lo = 0u, hi = COARSE - 1u; // key prefix of the bin: last one that starts at or below it
+            while (lo < hi) {
+                const u32 mid = (lo + hi + 1u) >> 1;
+                if ((sh.T[mid] >> 6) <= b)
+                    lo = mid;
+                else
+                    hi = mid - 1u;
+            }
+            const u32 e = sh.T[lo], dd = e & 31u, sub = b - (e >> 6);
+            const u32 first = (lo << COARSE_SHIFT) | (sub << (COARSE_SHIFT - dd));
+            const u32 last = first + ((1u << (COARSE_SHIFT - dd)) - 1u);
+            u32 below = 0u, upto = 0u; // boundaries < first, boundaries <= last
 #pragma unroll
-            for (u32 step = 256u; step > 0u; step >>= 1)
-                if (lo + step <= (u32)SK_EDGES && edge[lo + step - 1u] < fk) lo += step;
-            base[i] = (u16)lo;
+            for (u32 step = 256u; step > 0u; step >>= 1) {
+                if (below + step <= (u32)SK_EDGES && sh.edge[below + step - 1u] < first) below += step;
+                if (upto + step <= (u32)SK_EDGES && sh.edge[upto + step - 1u] <= last) upto += step;
+            }
+            sh.stab[b] = (u16)((below == upto) ? below : (0x8000u | below));
         }
         __syncthreads();
         for (; tile < stop; tile++) {
@@ -521,19 +528,16 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
             const u32 mask = load_tile(d, e0, c, v);
 #pragma unroll 4
             for (int i = 0; i < 16; i++) {
-                const u32 bits = __float_as_uint(v[i]);
-                const u32 mag = bits & 0x7fffffffu;
-                if (!((mask >> i) & 1u) || mag < tau_p || mag > tau_o) continue;
-                u32 hs; // position in the sketch histogram
-                if (mag >= 0x00800000u)
-                    hs = ((cell[mag >> 17] + (mag & 0x1FFFFu)) >> 17) + (bits >> 31) * (u32)SK_MAX_IDX;
-                else
-                    hs = sketch_slot_small(bits, P);
                 const u32 key = key_of_float(v[i]);
-                u32 slot = base[hs];
-                while (edge[slot] <= key) slot++; // (the list ends with 0xFFFFFFFF, above every finite key)
-                atomicAdd(&cnt[copy + slot], 1u);
-                atomicAdd(&sx[copy + slot], (double)v[i]);
+                const u32 mag = mag_of_key(key);
+                if (!((mask >> i) & 1u) || mag < tau_p || mag > tau_o) continue;
+                u32 slot = lookup_u16(sh.stab, key, sh.T[key >> COARSE_SHIFT]);
+                if (slot & 0x8000u) {
+                    slot &= 0x7fffu;
+                    while (sh.edge[slot] <= key) slot++; // (the list ends with 0xFFFFFFFF, above every finite key)
+                }
+                atomicAdd(&sh.cnt[copy + slot], 1u);
+                atomicAdd(&sh.sx[copy + slot], (double)v[i]);
             }
         }
         __syncthreads();
@@ -544,15 +548,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_score(const TDesc *__restrict_
             u32 n = 0u;
             double sum = 0.0;
             for (u32 k = 0; k < (u32)SK_COPIES; k++) {
-                n += cnt[k * SK_SLOTS + i];
-                sum += sx[k * SK_SLOTS + i];
+                n += sh.cnt[k * SK_SLOTS + i];
+                sum += sh.sx[k * SK_SLOTS + i];
             }
             if (n) {
                 atomicAdd(&gc[i], n);
                 atomicAdd(&gx[i], sum);
             }
         }
-        if (tid < (u32)SK_EDGES) P.slot_edge[(size_t)t * SK_SLOTS + tid] = edge[tid]; // (the same from every unit)
+        if (tid < (u32)SK_EDGES) P.slot_edge[(size_t)t * SK_SLOTS + tid] = sh.edge[tid]; // (the same from every unit)
         t++;
     }
 }
