@@ -22,10 +22,11 @@
 //                    number of bins) the draws are made once for 256 clusters and the rounds run
 //                    for 4, 8, ..., 256 clusters from the first 4, 8, ... draws.
 //   k_sketch_score   the search's sweep: all boundaries of the seven sets, sorted, cut the key axis
-//                    into at most 502 slots; a key's sketch bucket (the same table read) gives the
-//                    boundaries below the bucket's first key, the few inside the bucket are
-//                    compared one by one; count and sum per slot in LDS, added to the tensor's
-//                    arrays in global memory.
+//                    into at most 502 slots; the slot of a key comes from the equal-population
+//                    bins of the threshold search (a table gives the slot of every bin without a
+//                    boundary; in the few bins with one the key is compared with the boundaries
+//                    from the bin's first one on); count and sum per slot in LDS, added to the
+//                    tensor's arrays in global memory.
 //   k_sketch_choose  per tensor: the error of every set from the slot moments, the fewest bits
 //                    within the bound, and that set's keys and centres for the quantizer.
 #include "inshr_sketch.h"
