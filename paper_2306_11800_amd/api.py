@@ -351,9 +351,12 @@ class Context:
 
     # -- inshr_quantize_sketch -------------------------------------------------------------
     def quantize_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, alpha: float = 0.01,
-                        sigma: float = 0.2, max_iter: int = 100, reuse_search: bool = False):
+                        sigma: float = 0.2, max_iter: int = 100, reuse_search: bool = False,
+                        out: Optional[List[Quantized]] = None):
         """uniforms: numpy float64 array [len(tensors), 256] of numbers in [0, 1).  Returns
-        (list of Quantized, list of (n_buckets, rounds))."""
+        (list of Quantized, list of (n_buckets, rounds)).  `out` may carry the list an earlier call
+        returned for tensors of the same sizes; its buffers are then written again (the C side
+        checks them against what the configurations need)."""
         import numpy as np
         nT = len(tensors)
         ta = _tensor_array(tensors)
@@ -361,9 +364,12 @@ class Context:
         u = np.ascontiguousarray(uniforms, dtype=np.float64)
         if u.shape != (nT, 256):
             raise ValueError("uniforms must have shape [len(tensors), 256]")
-        qa = (CQuantized * nT)()
-        res = QuantizedBatch()
+        reuse_out = isinstance(out, QuantizedBatch) and out._sizes == tuple(t.numel() for t in tensors)
+        qa = out._qa if reuse_out else (CQuantized * nT)()
+        res = out if reuse_out else QuantizedBatch()
         for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
+            if reuse_out:
+                break
             n = t.numel()
             words, cap = self._bound(n, ca[i], cfg)
             e = qa[i]
@@ -377,8 +383,9 @@ class Context:
             e.packed_words = q._bufs[0].numel()
             e.outlier_cap = q._bufs[3].numel()
             res.append(q)
-        res._qa = qa
-        res._sizes = tuple(q.n for q in res)
+        if not reuse_out:
+            res._qa = qa
+            res._sizes = tuple(q.n for q in res)
         par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
         info = (CSketchInfo * nT)()
         self._check(self.lib.inshr_quantize_sketch(self.h, ta, ca, C.byref(par), qa, info, nT,
