@@ -273,6 +273,8 @@ def main():
         # only from the search kernels, sketch, clustering, scoring, quantize, then the delta
         common = max(set((c[1], c[2]) for c in cfgs), key=lambda pq: sum(1 for c in cfgs if (c[1], c[2]) == pq))
         fixed = [(0, common[0], common[1])] * len(cur)
+        # (the previous checkpoint's codes come from the same kind of step, as in a chain)
+        q_prev_alt, _, _ = ctx.search_sketch(prev, fixed, uni, eps, alpha=0.01, sigma=0.2, max_iter=100)
         q_alt = d_alt = None
         for it in range(3):
             if it == 1:
@@ -281,7 +283,7 @@ def main():
                 t0 = time.perf_counter()
             q_alt, alt_choices, _ = ctx.search_sketch(cur, fixed, uni, eps, alpha=0.01, sigma=0.2, max_iter=100,
                                                       out=q_alt)
-            d_alt = ctx.delta(q_prev, q_alt, out=d_alt)
+            d_alt = ctx.delta(q_prev_alt, q_alt, out=d_alt)
             ctx.sync()
         torch.cuda.synchronize()
         adt = (time.perf_counter() - t0) / 2
@@ -292,7 +294,7 @@ def main():
             "GB/s": round(n_total * 4 / adt / 1e9, 1),
             "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(aprof.items()) if v[0] / 2 >= 0.05},
             "symbol_bits_per_value": round(sum(t.numel() * (ch["best_bits"] + 1) for t, ch in zip(cur, alt_choices)) / n_total, 3)}
-        del q_alt, d_alt
+        del q_alt, d_alt, q_prev_alt
         hist_ms = sprof["k_sketch_hist"][0] / 2
         sketch = {"ms_after_a_search": round(sdt * 1e3, 3), "ms_stand_alone": round(sdt_alone * 1e3, 3),
                   "alpha": 0.01, "sigma": 0.2, "max_iter": 100,

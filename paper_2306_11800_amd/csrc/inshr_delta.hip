@@ -36,9 +36,13 @@ __device__ __forceinline__ u32 lds_extract(const u32 *W, u32 idx, u32 w)
 // words), extracts them from registers with compile-time shifts and counts the non-zero ones in its
 // wave's LDS histogram.  Symbol 0 (pruned: the most frequent one when pruning is on) is not counted:
 // its population is what the others leave of the chunk.
+// Narrow symbols (few clusters, unequal populations: the bins of the sketch quantizer) make many
+// lanes of a wave hit the same counter at once; their lanes are spread over DH_COPIES rows.
+constexpr int DH_COPIES = 4;
 template <int W, bool WHOLE>
 __device__ __forceinline__ void count_run(const u32 (&x)[2 * W + 1], u32 nvalid, u32 S, u32 *hrow)
 {
+    if (W <= 7) hrow += (threadIdx.x & (u32)(DH_COPIES - 1)) * (u32)SS;
 #pragma unroll
     for (int i = 0; i < 64; i++) {
         constexpr u32 mask = (1u << W) - 1u;
@@ -81,7 +85,7 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
                                                  const u32 *__restrict__ chunk_tensor,
                                                  u32 *__restrict__ chunk_tot)
 {
-    __shared__ u32 hw[BLOCK / 64][SS];
+    __shared__ u32 hw[BLOCK / 64][DH_COPIES * SS];
     __shared__ u32 s_nonzero;
     const u64 chunk = blockIdx.x;
     const DDesc d = dd[__builtin_amdgcn_readfirstlane(chunk_tensor[chunk])];
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
     const u32 S = d.Kp + 2u;
     const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
     const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
-    for (u32 k = tid; k < (BLOCK / 64) * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
+    for (u32 k = tid; k < (BLOCK / 64) * DH_COPIES * SS; k += BLOCK) (&hw[0][0])[k] = 0u;
     if (tid == 0u) s_nonzero = 0u;
     __syncthreads();
     switch (d.wp) {
@@ -105,7 +109,8 @@ __global__ __launch_bounds__(BLOCK) void k_dhist(const DDesc *__restrict__ dd,
     __syncthreads();
     u32 mine = 0u; // population of symbol tid (symbols above S - 1 are in entry S)
     if (tid >= 1u && tid <= S) {
-        for (int wv = 0; wv < BLOCK / 64; wv++) mine += hw[wv][tid];
+        for (int wv = 0; wv < BLOCK / 64; wv++)
+            for (int cp = 0; cp < DH_COPIES; cp++) mine += hw[wv][cp * SS + tid];
         if (mine) atomicAdd(&s_nonzero, mine);
     }
     __syncthreads();
