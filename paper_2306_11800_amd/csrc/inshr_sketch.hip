@@ -31,7 +31,17 @@
 //                    within the bound, and that set's keys and centres for the quantizer.
 #include "inshr_sketch.h"
 
+// The clustering follows its definition operation by operation: no product may be fused into the
+// sum that takes it.  The __dmul_rn / __dadd_rn of the HIP headers are plain operators compiled with
+// the headers' own contraction setting, so the operations are written here, with contraction off.
+#pragma clang fp contract(off)
+
 namespace inshr {
+
+__device__ __forceinline__ double mul_rn(double a, double b) { return a * b; }
+__device__ __forceinline__ double add_rn(double a, double b) { return a + b; }
+__device__ __forceinline__ double sub_rn(double a, double b) { return a - b; }
+__device__ __forceinline__ double div_rn(double a, double b) { return a / b; }
 
 // Histogram layout: positive bucket b at b, negative bucket b at SK_MAX_IDX + b, zeros at
 // 2 * SK_MAX_IDX.  Bucket of a denormal or zero magnitude (rare): search of the bucket list.
@@ -247,12 +257,12 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
     // ---- sample weights (Algorithm 2): sigma * C / max C + (1 - sigma) * |X| / max |X| ----
     const double x_first = fabs(xq[0]), x_last = fabs(xq[m - 1u]);
     const double mx = x_first > x_last ? x_first : x_last;
-    const double one_minus = __dsub_rn(1.0, P.sigma);
+    const double one_minus = sub_rn(1.0, P.sigma);
     __syncthreads();
     for (u32 i = tid; i < m; i += BLOCK) {
-        const double c_hat = __ddiv_rn(w[i], (double)maxc);
-        const double x_hat = mx > 0.0 ? __ddiv_rn(fabs(xq[i]), mx) : 0.0;
-        w[i] = __dadd_rn(__dmul_rn(P.sigma, c_hat), __dmul_rn(one_minus, x_hat));
+        const double c_hat = div_rn(w[i], (double)maxc);
+        const double x_hat = mx > 0.0 ? div_rn(fabs(xq[i]), mx) : 0.0;
+        w[i] = add_rn(mul_rn(P.sigma, c_hat), mul_rn(one_minus, x_hat));
     }
     __syncthreads();
 
@@ -277,15 +287,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
         double sum = 0.0;
         u32 last_pos = 0u; // last bucket of the share that could be drawn, + 1
         for (u32 i = lo; i < hi; i++) {
-            const double p = r ? __dmul_rn(dist[i], w[i]) : w[i];
-            sum = __dadd_rn(sum, p);
+            const double p = r ? mul_rn(dist[i], w[i]) : w[i];
+            sum = add_rn(sum, p);
             if (p > 0.0) last_pos = i + 1u;
         }
         double inc = sum;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const double y = __shfl_up(inc, o);
-            if ((int)lane >= o) inc = __dadd_rn(inc, y);
+            if ((int)lane >= o) inc = add_rn(inc, y);
         }
         const double before = __shfl_up(inc, 1); // inclusive value of the lane below
         if (lane == 63u) s_red[cp * (BLOCK / 64) + (tid >> 6)] = inc;
@@ -293,15 +303,15 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
         double wbase = 0.0, total = 0.0;
         for (u32 wv = 0; wv < BLOCK / 64; wv++) {
             if (wv == (tid >> 6)) wbase = total;
-            total = __dadd_rn(total, s_red[cp * (BLOCK / 64) + wv]);
+            total = add_rn(total, s_red[cp * (BLOCK / 64) + wv]);
         }
         if (r > 0u && !(total > 0.0)) { // every bucket is a centre already: repeat the last one
             if (tid == 0) craw[r] = craw[r - 1u];
             continue; // (nothing of this draw's cells is used again before two more barriers)
         }
-        const double target = __dmul_rn(uni[r], total);
-        const double excl = lane ? __dadd_rn(wbase, before) : wbase;
-        const double incl = __dadd_rn(wbase, inc);
+        const double target = mul_rn(uni[r], total);
+        const double excl = lane ? add_rn(wbase, before) : wbase;
+        const double incl = add_rn(wbase, inc);
         // one atomic per wave: its first lane above the target, its last lane with a drawable bucket
         const u64 above = __ballot(incl > target), drawable = __ballot(last_pos != 0u);
         if (above && lane == (u32)__builtin_ctzll(above)) atomicMin(&s_pick[cp], tid);
@@ -324,7 +334,7 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
                     double run = excl; // the running sum at the start of this thread's share
                     jj = last_pos ? last_pos - 1u : lo;
                     for (u32 i = lo; i < hi; i++) {
-                        run = __dadd_rn(run, r ? __dmul_rn(dist[i], w[i]) : w[i]);
+                        run = add_rn(run, r ? mul_rn(dist[i], w[i]) : w[i]);
                         if (run > target) {
                             jj = i;
                             break;
@@ -341,8 +351,8 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
         }
         const double cj = xq[j];
         for (u32 i = lo; i < hi; i++) {
-            const double df = __dsub_rn(xq[i], cj);
-            const double d2 = __dmul_rn(df, df);
+            const double df = sub_rn(xq[i], cj);
+            const double d2 = mul_rn(df, df);
             dist[i] = (r == 0u || d2 < dist[i]) ? d2 : dist[i];
         }
     }
@@ -373,7 +383,7 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
                 if (tid == Kb) {
                     first = m;
                 } else if (tid > 0u) {
-                    const double mid = __dmul_rn(__dadd_rn(cen[tid - 1u], cen[tid]), 0.5);
+                    const double mid = mul_rn(add_rn(cen[tid - 1u], cen[tid]), 0.5);
                     u32 a = 0u, b = m; // first bucket above the midpoint
                     while (a < b) {
                         const u32 c = (a + b) >> 1;
@@ -392,10 +402,10 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
             if (tid < Kb) {
                 double sw = 0.0, swx = 0.0;
                 for (u32 i = seg[tid]; i < seg[tid + 1u]; i++) {
-                    sw = __dadd_rn(sw, w[i]);
-                    swx = __dadd_rn(swx, __dmul_rn(w[i], xq[i]));
+                    sw = add_rn(sw, w[i]);
+                    swx = add_rn(swx, mul_rn(w[i], xq[i]));
                 }
-                if (sw > 0.0) cen[tid] = __ddiv_rn(swx, sw);
+                if (sw > 0.0) cen[tid] = div_rn(swx, sw);
             }
             if (tid <= Kb) seg_prev[tid] = seg[tid];
             rounds++;
@@ -412,7 +422,7 @@ __global__ __launch_bounds__(BLOCK) void k_sketch_kmeans(const GridDesc *__restr
             acb[tid] = __double2float_rn(cen[tid]);
             if (tid + 1u < Kb) {
                 const double a = (double)__double2float_rn(cen[tid]), b = (double)__double2float_rn(cen[tid + 1u]);
-                const double mid = __dmul_rn(__dadd_rn(a, b), 0.5);
+                const double mid = mul_rn(add_rn(a, b), 0.5);
                 // a value goes to the upper centre when it lies strictly above the midpoint: the
                 // boundary is the smallest fp32 number above it
                 ak[((tid + 1u) << sh) - 1u] = key_of_float(__double2float_rd(mid)) + 1u;

@@ -80,6 +80,16 @@ def test_parameters(ctx):
         check(ctx, [x, -np.abs(x)], [(5, 100000, 1000), (6, 0, 0)], alpha, sigma, max_iter, 7)
 
 
+def test_sums_are_not_contracted(ctx):
+    """Eleven symmetric buckets, four clusters, magnitude-only weights: after the first Lloyd round
+    the two inner centres are exact mirror images only if every product is rounded before it is
+    added (a fused multiply-add moves one of them by two ulps, the midpoint leaves zero, the zero
+    bucket changes sides and a second round is counted)."""
+    rng = np.random.default_rng(17)
+    x = (rng.integers(-5, 6, 5000) * 0.25).astype(np.float32)
+    check(ctx, [x], [(2, 0, 0)], 0.01, 0.0, 3, 5132)
+
+
 def test_more_clusters_than_buckets(ctx):
     x = np.array([0.5, 0.5, -0.25, 0.0, 1.0, 1.0, 1.0, 0.5], np.float32)
     check(ctx, [x, np.full(300, 3.0, np.float32)], [(4, 0, 0), (8, 0, 0)], 0.01, 0.2, 50, 3)
