@@ -226,6 +226,13 @@ int inshr_quantize_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const ins
                           const inshr_sketch_params *params, inshr_quantized *out,
                           inshr_sketch_info *info, uint32_t n_tensors, uint32_t flags);
 
+/* Host only (no GPU work): the bucket law the sketch calls use for alpha.  Bucket index i_lo + b
+ * (b = 0 .. n_buckets - 1) holds the magnitudes above tops[b - 1] up to tops[b], the largest fp32
+ * number not above gamma^(i_lo + b), and stands for values[b] = 2 gamma^(i_lo + b) / (gamma + 1).
+ * tops / values: host arrays of cap entries, or NULL (then only i_lo and n_buckets are returned). */
+int inshr_sketch_buckets(double alpha, int32_t *i_lo, uint32_t *n_buckets, float *tops, double *values,
+                         uint32_t cap);
+
 typedef struct {
     double sse[7];      /* squared error of the tensor with 2, 3, ..., 8 bits (fp64)          */
     double sumsq;       /* sum_all x^2                                                        */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
-           "inshr_quantize_sketch", "inshr_search_sketch",
+           "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
@@ -122,6 +122,8 @@ def load_library() -> C.CDLL:
                                         C.POINTER(CSketchParams), C.c_double, C.POINTER(CQuantized),
                                         C.POINTER(CSketchChoice), C.POINTER(CSketchInfo), C.c_uint32,
                                         C.c_uint32]
+    lib.inshr_sketch_buckets.argtypes = [C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_uint32), C.c_void_p,
+                                         C.c_void_p, C.c_uint32]
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
@@ -549,6 +551,23 @@ class Context:
 
 
 # -- entropy stage of the delta: host memory, no device involved ------------------------------------
+def sketch_buckets(alpha: float):
+    """(i_lo, tops float32 array, values float64 array) of the bucket law for alpha (host only)."""
+    import numpy as np
+    lib = load_library()
+    i_lo, n = C.c_int32(), C.c_uint32()
+    rc = lib.inshr_sketch_buckets(float(alpha), C.byref(i_lo), C.byref(n), None, None, 0)
+    if rc:
+        raise InshrError(rc, lib.inshr_strerror(rc).decode())
+    tops = np.empty(n.value, np.float32)
+    values = np.empty(n.value, np.float64)
+    rc = lib.inshr_sketch_buckets(float(alpha), C.byref(i_lo), C.byref(n), tops.ctypes.data, values.ctypes.data,
+                                  n.value)
+    if rc:
+        raise InshrError(rc, lib.inshr_strerror(rc).decode())
+    return int(i_lo.value), tops, values
+
+
 def _host_ptr(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 

@@ -44,6 +44,7 @@ struct inshr_ctx {
     DevBuf aux_mem;    // quantize descriptors, delta scratch
     DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
     double sketch_alpha = 0.0;                 // the bucket tables last built, and for which alpha
+    int sketch_i_lo = 0;
     std::vector<u32> sketch_cell, sketch_tops;
     std::vector<double> sketch_rep;
     HostBuf h_up;      // staging for descriptor uploads
@@ -727,6 +728,7 @@ namespace {
 struct SketchTables {
     std::vector<u32> cell, tops;
     std::vector<double> rep;
+    int i_lo = 0; // tops[b] belongs to bucket index i_lo + b
 };
 
 // Tables of the bucket law ceil(log_gamma |x|): tops[b] = magnitude image of the largest fp32
@@ -736,7 +738,8 @@ struct SketchTables {
 int build_sketch_tables(inshr_ctx *ctx, double alpha, SketchTables &T)
 {
     if (!(alpha >= 0.01 && alpha <= 0.5)) return INSHR_E_CONFIG;
-    if (ctx->sketch_alpha == alpha) { // the tables of the call before
+    if (ctx && ctx->sketch_alpha == alpha) { // the tables of the call before
+        T.i_lo = ctx->sketch_i_lo;
         T.cell = ctx->sketch_cell;
         T.tops = ctx->sketch_tops;
         T.rep = ctx->sketch_rep;
@@ -748,6 +751,7 @@ int build_sketch_tables(inshr_ctx *ctx, double alpha, SketchTables &T)
     const int i_hi = (int)ceill(128.0L * logl(2.0L) / lg) + 1;
     const int n_idx = i_hi - i_lo + 1;
     if (n_idx > SK_MAX_IDX) return INSHR_E_CONFIG;
+    T.i_lo = i_lo;
     T.tops.resize(n_idx);
     T.rep.resize(n_idx);
     for (int b = 0; b < n_idx; b++) {
@@ -773,10 +777,13 @@ int build_sketch_tables(inshr_ctx *ctx, double alpha, SketchTables &T)
         const u32 split = T.tops[b0] <= last ? (T.tops[b0] & 0x1FFFFu) : 0x1FFFFu;
         T.cell[c] = (b0 << 17) | (0x1FFFFu - split); // adding the low magnitude bits carries above the split
     }
-    ctx->sketch_cell = T.cell;
-    ctx->sketch_tops = T.tops;
-    ctx->sketch_rep = T.rep;
-    ctx->sketch_alpha = alpha;
+    if (ctx) {
+        ctx->sketch_cell = T.cell;
+        ctx->sketch_tops = T.tops;
+        ctx->sketch_rep = T.rep;
+        ctx->sketch_i_lo = i_lo;
+        ctx->sketch_alpha = alpha;
+    }
     return INSHR_OK;
 }
 
@@ -1053,6 +1060,23 @@ int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_c
         rc = finish(subcfg.data(), subout.data(), which.data(), idx.data(), nS);
         for (uint32_t k = 0; k < nS; k++) out[idx[k]] = subout[k];
         if (rc) return rc;
+    }
+    return INSHR_OK;
+}
+
+int inshr_sketch_buckets(double alpha, int32_t *i_lo, uint32_t *n_buckets, float *tops, double *values,
+                         uint32_t cap)
+{
+    if (!i_lo || !n_buckets) return INSHR_E_ARG;
+    SketchTables T;
+    int rc = build_sketch_tables(nullptr, alpha, T);
+    if (rc) return rc;
+    *i_lo = T.i_lo;
+    *n_buckets = (uint32_t)T.tops.size();
+    if (cap < T.tops.size() && (tops || values)) return INSHR_E_CAPACITY;
+    for (size_t b = 0; b < T.tops.size(); b++) {
+        if (tops) memcpy(&tops[b], &T.tops[b], 4);
+        if (values) values[b] = T.rep[b];
     }
     return INSHR_OK;
 }

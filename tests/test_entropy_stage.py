@@ -117,3 +117,4 @@ def test_malformed_input_is_refused():
         a.entropy_decode(bad, 100, 3, 2)
     with pytest.raises(a.InshrError):
         a.entropy_encode(np.array([0, 60, 50, 100], np.uint64), 3, values=v)
+
