@@ -12,9 +12,11 @@
 //                          window at least 8 bins, so that sweep 2 resolves first-level bins there.
 //   sweep 2  k_hist<2>     LDS histogram over the table's bins; elements of threshold buckets are
 //                          gathered into wave-private regions.  For sampled tensors also what
-//                          sweep 1 gives otherwise (sum of squares, zeros) and the smallest and
-//                          largest magnitude (the thresholds of rank 0 and n - 1 cannot be
-//                          predicted from a sample).
+//                          sweep 1 gives otherwise (sum of squares, zeros).  The thresholds of rank
+//                          0 and n - 1 (the smallest and the largest magnitude) cannot be predicted
+//                          to a bin from a sample, but the sample's extreme bins bound them: all
+//                          bins beyond those are gathered (a handful of keys) and the select takes
+//                          the extremes of the gathered keys.
 //   k_plan1b               sampled tensors: exact size checks and the exact bucket of every
 //                          threshold from the second histogram; a bucket outside its window marks
 //                          the tensor, and k_hist<1>, k_plan1, k_hist<2> run once more for the
@@ -61,7 +63,7 @@ __device__ __forceinline__ void hist1_tile(const float (&v)[16], u32 mask, u32 *
 template <bool FULL, bool STATS>
 __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *h, const u32 *T,
                                            GLOBAL_AS u32 *gdst, u32 &gathered, double &q_tot,
-                                           u32 &c_zero, u32 &mn, u32 &mx)
+                                           u32 &c_zero)
 {
     u32 key[16], ent[16];
 #pragma unroll
@@ -73,11 +75,6 @@ __device__ __forceinline__ void hist2_tile(const float (&v)[16], u32 mask, u32 *
             q_tot = fma(xd, xd, q_tot); // invalid entries are 0.0
             const bool valid = FULL || ((mask >> i) & 1u);
             c_zero += (u32)__popcll(__ballot(valid && key[i] == ZERO_KEY)); // wave-uniform
-            const u32 mag = __float_as_uint(v[i]) & 0x7fffffffu;
-            if (FULL || valid) {
-                mn = mag < mn ? mag : mn;
-                mx = mag > mx ? mag : mx;
-            }
         }
     }
 #pragma unroll
@@ -139,7 +136,6 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         }
         __syncthreads();
         u32 c_zero = 0u;    // exact zeros seen by this wave (LEVEL 1; LEVEL 2 of a sampled tensor)
-        u32 mn = 0xFFFFFFFFu, mx = 0u; // smallest / largest magnitude seen (LEVEL 2 of a sampled tensor)
         double q_tot = 0.0; // sum of squares (the same)
         for (; tile < stop; tile++) {
             // a sampled sweep 1 takes one tile in SAMPLE_RATE
@@ -157,14 +153,14 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             } else {
                 if (sampled) {
                     if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
-                        hist2_tile<true, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                        hist2_tile<true, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero);
                     else
-                        hist2_tile<false, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                        hist2_tile<false, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero);
                 } else {
                     if (cnt == (u32)TILE)
-                        hist2_tile<true, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                        hist2_tile<true, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero);
                     else
-                        hist2_tile<false, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero, mn, mx);
+                        hist2_tile<false, false>(v, mask, h, T, gdst, gathered, q_tot, c_zero);
                 }
             }
         }
@@ -189,18 +185,6 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         // sampled sweep's own zeros, scaled, are an estimate that shapes the table; k_plan1 clears it)
         if (LEVEL == 1 || sampled) {
             if (LEVEL == 1 && sampled) c_zero *= (u32)SAMPLE_RATE;
-            if (LEVEL == 2) {
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const u32 a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
-                    mn = a < mn ? a : mn;
-                    mx = b > mx ? b : mx;
-                }
-                if (lane == 0u) {
-                    atomicMin(&st->mag_min, mn);
-                    atomicMax(&st->mag_max, mx);
-                }
-            }
             q_tot = wave_sum_f64(q_tot);
             if (lane == 0u) {
                 if (c_zero) atomicAdd((unsigned long long *)&st->n_zero, (unsigned long long)c_zero);
@@ -237,10 +221,12 @@ __device__ __forceinline__ u64 threshold_rank(const GridDesc *gd, u32 q, u64 n)
 }
 
 // which of the 8 first-level bins under key prefix c are gathered for some threshold
-__device__ __forceinline__ u32 cell_flags(u32 c, const u32 *jlo, const u32 *jhi, u32 n_thr)
+// (thresholds whose bit is set in skip are left out)
+__device__ __forceinline__ u32 cell_flags(u32 c, const u32 *jlo, const u32 *jhi, u32 n_thr, u32 skip = 0u)
 {
     u32 flag = 0u;
     for (u32 q = 0; q < n_thr; q++) {
+        if ((skip >> q) & 1u) continue;
         // magnitude bin j is first-level key bin 16384 + j for positive, 16383 - j for negative
         const u32 p0 = (u32)L1_MAGBINS + jlo[q], p1 = (u32)L1_MAGBINS + jhi[q];
         const u32 n0 = (u32)L1_MAGBINS - 1u - jhi[q], n1 = (u32)L1_MAGBINS - 1u - jlo[q];
@@ -358,8 +344,6 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
             // estimate of a cumulative count c from one tile in SAMPLE_RATE has a standard
             // deviation of about sqrt(SAMPLE_RATE * c) for independent elements; tiles are not
             // independent draws, so the margin is generous, and a miss is caught afterwards.
-            // (ranks 0 and n - 1 are not predicted: the second sweep takes the smallest and the
-            // largest magnitude directly, and nothing is gathered for them)
             const u64 tail = R < n - R ? R + 1ull : n - R;
             const u64 margin = (u64)(8.0 * sqrt((double)SAMPLE_RATE * (double)tail)) + 8ull * SAMPLE_RATE;
             // The scaled total is not n.  A rank of the upper half is counted from the top of the
@@ -375,9 +359,16 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
             if (r_hi >= last && jh + 1u < (u32)L1_MAGBINS) jh++; // the sample may have missed the top
             s_jhi[tid] = jh;
             s_j[tid] = 0u;
-            if (R == 0ull || R == n - 1ull) { // an empty window
-                s_jlo[tid] = 1u;
-                s_jhi[tid] = 0u;
+            // Ranks 0 and n - 1 are the smallest and the largest magnitude themselves.  The sample's
+            // extreme bins bound them: every bin up to the sample's lowest occupied one (from its
+            // highest occupied one on) is gathered — a handful of keys — and the threshold select
+            // takes the smallest (largest) magnitude of all gathered keys.
+            if (R == 0ull) {
+                s_jlo[tid] = 0u;
+                s_jhi[tid] = bin_of(0ull);
+            } else if (R == n - 1ull) {
+                s_jlo[tid] = bin_of(last);
+                s_jhi[tid] = (u32)L1_MAGBINS - 1u;
             }
         }
         st->thr_jlo[tid] = s_jlo[tid];
@@ -405,12 +396,23 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     }
     __syncthreads();
     // gathered first-level bins of this thread's key prefixes (prefix c = tid + BLOCK * k)
-    u32 my_flags[COARSE / BLOCK];
+    // (the windows of the ranks 0 and n - 1 of a sampled tensor are gathered, but nothing has to be
+    // resolved inside them: they ask for no bins)
+    u32 extreme = 0u;
+    if (sampled)
+        for (u32 q = 0; q < n_thr; q++) {
+            const u64 R = threshold_rank(gd, q, n);
+            if (R == 0ull || R == n - 1ull) extreme |= 1u << q;
+        }
+    u32 my_flags[COARSE / BLOCK], my_force[COARSE / BLOCK];
 #pragma unroll
-    for (int k = 0; k < COARSE / BLOCK; k++) my_flags[k] = cell_flags(tid + (u32)BLOCK * k, s_jlo, s_jhi, n_thr);
+    for (int k = 0; k < COARSE / BLOCK; k++) {
+        my_flags[k] = cell_flags(tid + (u32)BLOCK * k, s_jlo, s_jhi, n_thr);
+        my_force[k] = extreme ? cell_flags(tid + (u32)BLOCK * k, s_jlo, s_jhi, n_thr, extreme) : my_flags[k];
+    }
     auto depth_of = [&](int c, u64 target, int k) -> u32 {
         u32 d = nc[c] ? depth_for(nc[c], target) : 0u;
-        if (sampled && d < 3u && my_flags[k]) d = 3u;
+        if (sampled && d < 3u && my_force[k]) d = 3u;
         return d;
     };
     u64 lo = 1, hi = n;
@@ -638,6 +640,10 @@ __global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td
     if (tid < nb) which[st->bucket_magbin[tid]] = (unsigned char)(tid + 1u);
     __syncthreads();
     const u32 *list = B.pool + td[t].pool_thr + B.unit_start[fu] + (u64)wave * B.unit_sub[fu];
+    // smallest / largest magnitude among the gathered keys (first pass): for a tensor whose first
+    // sweep was sampled the windows of the ranks 0 and n - 1 were gathered, so these are the
+    // tensor's own extremes (exact zeros are never gathered: TState::n_zero tells of them)
+    u32 mn = 0xFFFFFFFFu, mx = 0u;
     for (u32 i0 = lane; i0 < c; i0 += 256u) {
         u32 kk[4];
 #pragma unroll
@@ -646,6 +652,10 @@ __global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td
         for (int j = 0; j < 4; j++) {
             if (i0 + j * 64u >= c) continue;
             const u32 mag = mag_of_key(kk[j]);
+            if (ROUND == 0) {
+                mn = mag < mn ? mag : mn;
+                mx = mag > mx ? mag : mx;
+            }
             const u32 bk = which[mag >> L1_SHIFT];
             if (bk == 0u) continue; // (gathered for a window of bins, not in a bucket)
             const u32 sgn = key_is_neg(kk[j]) ? 0u : 512u;
@@ -658,6 +668,18 @@ __global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td
                     if ((mag >> 8) == s_want[q]) atomicAdd(&hist[q * 1024u + sgn + (mag & 255u)], 1u);
                 }
             }
+        }
+    }
+    if (ROUND == 0 && td[t].sampled) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const u32 a = __shfl_xor(mn, o), b = __shfl_xor(mx, o);
+            mn = a < mn ? a : mn;
+            mx = b > mx ? b : mx;
+        }
+        if (lane == 0u && mx) {
+            atomicMin(&B.ts[t].mag_min, mn);
+            atomicMax(&B.ts[t].mag_max, mx);
         }
     }
     __syncthreads();
@@ -723,7 +745,10 @@ __global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td,
         const u32 q = tid;
         const u32 bq = st->thr_bucket[q];
         if (bq == NO_BUCKET) {
-            st->thr_mag[q] = st->thr_res[q] == 0ull ? st->mag_min : st->mag_max;
+            // (the smallest magnitude is 0 when the tensor holds exact zeros; a tensor of zeros
+            // only has gathered nothing, and both extremes are 0)
+            const u32 lowest = (st->n_zero || st->mag_min == 0xFFFFFFFFu) ? 0u : st->mag_min;
+            st->thr_mag[q] = st->thr_res[q] == 0ull ? lowest : st->mag_max;
             st->thr_lt_neg[q] = st->thr_lt_pos[q] = 0ull; // (used for a prune threshold: nothing below the minimum)
             st->thr_gt_neg[q] = st->thr_gt_pos[q] = 0ull; // (used for a protect threshold: nothing above the maximum)
             return;
