@@ -234,7 +234,8 @@ def main():
         ctx.search(cur, grid, eps, want_scores=False)
         for drop in (1, 2, 3, 4):
             c2 = [(max(2, c[0] - drop), c[1], c[2]) for c in cfgs]
-            q2, _ = ctx.quantize_sketch(cur, c2, uni, alpha=0.01, sigma=0.2, max_iter=100, reuse_search=True)
+            q2, _ = ctx.quantize_sketch(cur, c2, uni, alpha=0.01, sigma=0.2, max_iter=100,
+                                        reuse_search=len(grid) == 105)
             ok, tot = 0, 0.0
             for t, a, sq in zip(cur, q2, sq_t):
                 y = buf[:t.numel()]
@@ -251,8 +252,9 @@ def main():
                 torch.cuda.synchronize()
                 ctx.profile(True)
                 t0 = time.perf_counter()
+            # (on top of the grid search when its grid holds every width of the fractions in use)
             q_ss, choices, _ = ctx.search_sketch(cur, cfgs, uni, eps, alpha=0.01, sigma=0.2, max_iter=100,
-                                                 reuse_search=True)
+                                                 reuse_search=len(grid) == 105)
         torch.cuda.synchronize()
         ssdt = (time.perf_counter() - t0) / 2
         ssprof = ctx.profile_read()
