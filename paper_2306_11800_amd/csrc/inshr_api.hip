@@ -218,12 +218,11 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
     GridDesc g;
     int rc = build_grid(grid, n_cfg, eps, g);
     if (rc) return rc;
-    uint64_t total_tiles = 0, total_n = 0;
+    uint64_t total_tiles = 0;
     for (uint32_t t = 0; t < nT; t++) {
         if (!tensors[t].data || tensors[t].n == 0 || tensors[t].n >= (1ull << 32)) return INSHR_E_ARG;
         if ((uintptr_t)tensors[t].data & 3u) return INSHR_E_ARG;
         total_tiles += (tensors[t].n + TILE - 1) / TILE;
-        total_n += tensors[t].n;
     }
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->stream)); // staging buffers may be in flight (inshr_delta)
