@@ -247,7 +247,8 @@ typedef struct {
  * so the start of a narrower width is a prefix of the start of a wider one), every width is scored
  * exactly (sse = sum_pruned x^2 + sum_quantized (x - its centre)^2 over the tensor, one more sweep),
  * the fewest bits within eps are chosen and the tensor is quantized with them into out[i] (sized
- * for 8 bits).  choice: host, n_tensors entries.  With INSHR_REUSE_SEARCH the grid of the last
+ * for 8 bits).  choice: host, n_tensors entries.  info: host, n_tensors entries or NULL (n_buckets,
+ * and the Lloyd rounds of the 8-bit set).  With INSHR_REUSE_SEARCH the grid of the last
  * inshr_search must hold the tensor's fractions with every width from 2 to 8 bits. */
 int inshr_search_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
                         const inshr_sketch_params *params, double eps, inshr_quantized *out,
