@@ -271,3 +271,29 @@ def test_largest_tensor_search_over_bits_with_sketch_bins(ctx):
     A = torch.sort(x.abs()).values
     tau_p, tau_o = A[N * 200000 // 1_000_000], A[N - 1 - N * 1000 // 1_000_000]
     assert torch.equal(sym == 0, x.abs() < tau_p) and torch.equal(sym == 1, x.abs() > tau_o)
+
+
+@pytest.mark.parametrize("n", [4096 * 4096, 11008 * 4096, 4096 * 4096 + 12345])
+def test_other_bench_shapes(ctx, n):
+    """The other 2-D weight shapes of the bench (and a ragged size): at 16 Mi values and more the
+    first sweep of the search is sampled.  Thresholds, boundaries and every symbol against the
+    torch definitions for three configurations."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(81)
+    z = torch.randn(4, n, dtype=torch.float32, device=dev, generator=g)
+    x = 0.015 * z[0] / torch.sqrt((z[1] * z[1] + z[2] * z[2] + z[3] * z[3]) / 3.0)
+    del z
+    x[x == 0] = 1e-6
+    if n % 4096 == 0:
+        hot = torch.randperm(4096, device=dev, generator=g)[:4]
+        x.view(-1, 4096)[:, hot] *= 20.0
+    ctx.search([x], synth.grid_full(), synth.EPS_DEFAULT, want_scores=False)
+    for cfg in ((8, 200000, 1000), (7, 0, 0), (4, 400000, 100)):
+        r = torch_quantize(x, cfg)
+        q = ctx.quantize([x], [cfg], reuse_search=True)[0]
+        K = 1 << cfg[0]
+        assert q.tau_prune == float(r["tau_p"]) and q.tau_outlier == float(r["tau_o"])
+        assert torch.equal(q.boundaries[:K - 1].view(torch.int32), r["t"].view(torch.int32))
+        got = unpack(q.packed, n, cfg[0] + 1)
+        assert torch.equal(got, r["sym"]), int((got != r["sym"]).sum())
