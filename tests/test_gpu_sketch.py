@@ -180,6 +180,18 @@ def test_stand_alone_state_is_not_offered_for_reuse(ctx):
     assert q.n_kept > 0
 
 
+def test_degenerate_tensors(ctx):
+    """All zeros, a constant, one value, zeros with one other value, the ends of the fp32 range; an
+    error bound of zero."""
+    xs = [np.zeros(5000, np.float32), np.full(20000, -0.37, np.float32), np.array([1e-30], np.float32),
+          np.concatenate([np.zeros(100, np.float32), np.full(50, 2.5, np.float32)]),
+          np.array([3.0e38, -3.0e38, 1.0, 0.0], np.float32)]
+    fractions = [(0, 0, 0), (0, 100000, 1000), (0, 0, 0), (0, 300000, 0), (0, 0, 0)]
+    for eps in (1e-2, 0.0):
+        check_search(ctx, xs, fractions, eps, 0.01, 0.2, 100, 77)
+    check(ctx, xs, [(3, 0, 0), (8, 100000, 1000), (2, 0, 0), (5, 300000, 0), (4, 0, 0)], 0.01, 0.2, 100, 78)
+
+
 def test_argument_errors(ctx):
     from paper_2306_11800_amd import api
     x = dev(np.ones(100, np.float32))
