@@ -12,7 +12,7 @@ def build(force: bool = False) -> str:
             and os.path.getmtime(LIB) >= max(os.path.getmtime(SRC),
                                              os.path.getmtime(os.path.join(HERE, "inshr_ref.h")))):
         return LIB
-    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", SRC, "-o", LIB]
+    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", SRC, "-o", LIB, "-lm"]
     subprocess.check_call(cmd)
     return LIB
 

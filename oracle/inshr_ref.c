@@ -22,6 +22,7 @@
  */
 #include "inshr_ref.h"
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -49,9 +50,31 @@ static int cmp_u32(const void *a, const void *b)
     return (x > y) - (x < y);
 }
 
+/* number of bins of a configuration: the count itself when given (Sec. 5, search space), else 2^bits */
+static uint32_t bins_of(const inshr_ref_config *c) { return c->bins ? c->bins : (1u << c->bits); }
+
+uint32_t inshr_ref_symbol_bits(uint32_t K)
+{
+    uint32_t w = 1;
+    while ((1u << w) < K + 2u) w++; /* K bins + the pruned and the protected level (Sec. 6) */
+    return w;
+}
+
+/* payload of the quantized values: an ideal fixed-length code spends log2 K bits on each; log2 K is
+ * taken in units of 2^-16 (exact for powers of two) and the product rounded up */
+static uint64_t code_bits(uint64_t n_kept, uint32_t K)
+{
+    const uint64_t l16 = (uint64_t)floor(log2((double)K) * 65536.0 + 0.5);
+    return (n_kept * l16 + 65535ull) >> 16;
+}
+
 static int check_config(const inshr_ref_config *c)
 {
-    if (c->bits < 1 || c->bits > 8) return INSHR_REF_E_CONFIG;
+    if (c->bins) {
+        if (c->bins < 2 || c->bins > 256) return INSHR_REF_E_CONFIG;
+    } else if (c->bits < 1 || c->bits > 8) {
+        return INSHR_REF_E_CONFIG;
+    }
     if ((uint64_t)c->prune_ppm + (uint64_t)c->outlier_ppm >= 1000000ull) return INSHR_REF_E_CONFIG;
     return INSHR_REF_OK;
 }
@@ -104,7 +127,7 @@ static int quantize_one(const float *x, uint64_t n, const sorted_images *si,
                         const inshr_ref_config *cfg, uint16_t *sym, float *boundaries,
                         float *codebook, uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info)
 {
-    const uint32_t K = 1u << cfg->bits;
+    const uint32_t K = bins_of(cfg);
     const uint64_t n_p = n * (uint64_t)cfg->prune_ppm / 1000000ull;
     const uint64_t n_o = n * (uint64_t)cfg->outlier_ppm / 1000000ull;
 
@@ -196,13 +219,28 @@ static int quantize_one(const float *x, uint64_t n, const sorted_images *si,
         info->n_pruned = n_pruned;
         info->n_outlier = n_outlier;
         info->n_kept = n_kept;
-        info->sym_bits = cfg->bits + 1u;
+        info->sym_bits = inshr_ref_symbol_bits(K);
         info->tau_prune_bits = tau_p;
         info->tau_outlier_bits = tau_o;
         info->sse = sse;
         info->sumsq = sumsq;
     }
     return INSHR_REF_OK;
+}
+
+float inshr_ref_bf16_round(float x)
+{
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    /* round to nearest, ties to the even upper half; finite inputs only (a carry out of the largest
+     * finite exponent gives infinity, as the format defines) */
+    const uint32_t upper = b >> 16, lower = b & 0xFFFFu;
+    uint32_t r = upper;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) r = upper + 1u;
+    r <<= 16;
+    float f;
+    memcpy(&f, &r, 4);
+    return f;
 }
 
 int inshr_ref_quantize(const float *x, uint64_t n, const inshr_ref_config *cfg, uint16_t *sym,
@@ -250,8 +288,8 @@ int inshr_ref_search(const float *x, uint64_t n, const inshr_ref_config *grid, u
         sc.n_pruned = qi.n_pruned;
         sc.n_outlier = qi.n_outlier;
         sc.n_kept = qi.n_kept;
-        sc.cost_bits = qi.n_kept * (uint64_t)grid[g].bits + 32ull * qi.n_outlier +
-                       32ull * (1ull << grid[g].bits);
+        sc.cost_bits = code_bits(qi.n_kept, bins_of(&grid[g])) + 32ull * qi.n_outlier +
+                       32ull * (uint64_t)bins_of(&grid[g]);
         if (scores) scores[g] = sc;
 
         double rel = (sc.sumsq > 0.0) ? sc.sse / sc.sumsq : 0.0;
@@ -279,8 +317,15 @@ int inshr_ref_dequantize(const uint16_t *sym, uint64_t n, uint32_t bits, const f
                          const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,
                          float *xhat)
 {
-    if (!sym || !codebook || !xhat || bits < 1 || bits > 8) return INSHR_REF_E_ARG;
-    const uint32_t K = 1u << bits;
+    if (bits < 1 || bits > 8) return INSHR_REF_E_ARG;
+    return inshr_ref_dequantize_k(sym, n, 1u << bits, codebook, out_idx, out_val, n_outlier, xhat);
+}
+
+int inshr_ref_dequantize_k(const uint16_t *sym, uint64_t n, uint32_t K, const float *codebook,
+                           const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,
+                           float *xhat)
+{
+    if (!sym || !codebook || !xhat || K < 2 || K > 256) return INSHR_REF_E_ARG;
     uint64_t q = 0;
     for (uint64_t i = 0; i < n; i++) {
         uint16_t s = sym[i];
@@ -301,10 +346,18 @@ int inshr_ref_delta(const uint16_t *s_prev, uint32_t bits_prev, const uint16_t *
                     uint32_t bits_cur, uint64_t n, uint16_t *delta, uint32_t *perm,
                     uint64_t *group_off, uint16_t *stream)
 {
-    if (!s_prev || !s_cur || !group_off || n == 0 || n >= (1ull << 32)) return INSHR_REF_E_ARG;
     if (bits_prev < 1 || bits_prev > 8 || bits_cur < 1 || bits_cur > 8) return INSHR_REF_E_CONFIG;
-    const uint32_t Sp = (1u << bits_prev) + 2u; /* levels of the previous checkpoint */
-    const uint32_t Sc = (1u << bits_cur) + 2u;
+    return inshr_ref_delta_k(s_prev, 1u << bits_prev, s_cur, 1u << bits_cur, n, delta, perm, group_off, stream);
+}
+
+int inshr_ref_delta_k(const uint16_t *s_prev, uint32_t K_prev, const uint16_t *s_cur, uint32_t K_cur,
+                      uint64_t n, uint16_t *delta, uint32_t *perm, uint64_t *group_off,
+                      uint16_t *stream)
+{
+    if (!s_prev || !s_cur || !group_off || n == 0 || n >= (1ull << 32)) return INSHR_REF_E_ARG;
+    if (K_prev < 2 || K_prev > 256 || K_cur < 2 || K_cur > 256) return INSHR_REF_E_CONFIG;
+    const uint32_t Sp = K_prev + 2u; /* levels of the previous checkpoint */
+    const uint32_t Sc = K_cur + 2u;
     const uint32_t B = (Sp > Sc) ? Sp : Sc;     /* cyclic range */
     for (uint64_t i = 0; i < n; i++)
         if (s_prev[i] >= Sp || s_cur[i] >= Sc) return INSHR_REF_E_ARG;
@@ -334,10 +387,17 @@ int inshr_ref_reconstruct(const uint16_t *s_prev, uint32_t bits_prev, uint32_t b
                           uint64_t n, const uint64_t *group_off, const uint16_t *stream,
                           uint16_t *s_cur)
 {
-    if (!s_prev || !group_off || !stream || !s_cur) return INSHR_REF_E_ARG;
     if (bits_prev < 1 || bits_prev > 8 || bits_cur < 1 || bits_cur > 8) return INSHR_REF_E_CONFIG;
-    const uint32_t Sp = (1u << bits_prev) + 2u;
-    const uint32_t Sc = (1u << bits_cur) + 2u;
+    return inshr_ref_reconstruct_k(s_prev, 1u << bits_prev, 1u << bits_cur, n, group_off, stream, s_cur);
+}
+
+int inshr_ref_reconstruct_k(const uint16_t *s_prev, uint32_t K_prev, uint32_t K_cur, uint64_t n,
+                            const uint64_t *group_off, const uint16_t *stream, uint16_t *s_cur)
+{
+    if (!s_prev || !group_off || !stream || !s_cur) return INSHR_REF_E_ARG;
+    if (K_prev < 2 || K_prev > 256 || K_cur < 2 || K_cur > 256) return INSHR_REF_E_CONFIG;
+    const uint32_t Sp = K_prev + 2u;
+    const uint32_t Sc = K_cur + 2u;
     const uint32_t B = (Sp > Sc) ? Sp : Sc;
     uint64_t *cursor = (uint64_t *)malloc(Sp * sizeof(uint64_t));
     if (!cursor) return INSHR_REF_E_ARG;

@@ -33,7 +33,9 @@ enum {
 };
 
 typedef struct {
-    uint8_t bits;         /* K = 1 << bits bins, 1..8 */
+    uint8_t bits;         /* K = 1 << bits bins, 1..8, when bins == 0 */
+    uint16_t bins;        /* 0, or the number of bins K itself, 2..256: the search space of Sec. 5
+                             lists bin counts (4, 6, 8, 12, 16, 32), not bit widths */
     uint32_t prune_ppm;   /* pruning fraction x 1e6   */
     uint32_t outlier_ppm; /* protection fraction x 1e6 */
 } inshr_ref_config;
@@ -42,12 +44,13 @@ typedef struct {
     double sse;   /* sum over pruned of x^2 + sum over quantized of (x - centre)^2 */
     double sumsq; /* sum over all of x^2 */
     uint64_t n_pruned, n_outlier, n_kept;
-    uint64_t cost_bits; /* n_kept*bits + 32*n_outlier + 32*K */
+    uint64_t cost_bits; /* ceil(n_kept * log2 K) + 32*n_outlier + 32*K, with log2 K in units of 2^-16
+                           (n_kept * bits for K = 2^bits) */
 } inshr_ref_score;
 
 typedef struct {
     uint64_t n_pruned, n_outlier, n_kept;
-    uint32_t sym_bits;          /* bits + 1 */
+    uint32_t sym_bits;          /* ceil(log2(K + 2)); bits + 1 for K = 2^bits */
     uint32_t tau_prune_bits;    /* magnitude image (bits & 0x7fffffff) of the prune threshold   */
     uint32_t tau_outlier_bits;  /* magnitude image of the protection threshold                 */
     double sse, sumsq;
@@ -63,6 +66,10 @@ typedef struct {
 int inshr_ref_quantize(const float *x, uint64_t n, const inshr_ref_config *cfg, uint16_t *sym,
                        float *boundaries, float *codebook, uint32_t *out_idx, float *out_val,
                        inshr_ref_qinfo *info);
+
+/* Sec. 4.2 keeps the protected values in bfloat16: the value rounded to nearest even on the upper
+ * 16 bits of its fp32 image (returned as a float whose lower 16 bits are zero). */
+float inshr_ref_bf16_round(float x);
 
 /* Score every configuration of a grid independently and choose (Sec. 5): among configurations
  * with sse/sumsq <= eps the least cost_bits, ties to the lowest grid index; if none, the least
@@ -90,6 +97,18 @@ int inshr_ref_delta(const uint16_t *s_prev, uint32_t bits_prev, const uint16_t *
 int inshr_ref_reconstruct(const uint16_t *s_prev, uint32_t bits_prev, uint32_t bits_cur,
                           uint64_t n, const uint64_t *group_off, const uint16_t *stream,
                           uint16_t *s_cur);
+
+/* The same three with the numbers of bins K (2..256) given directly instead of as 2^bits. */
+int inshr_ref_dequantize_k(const uint16_t *sym, uint64_t n, uint32_t K, const float *codebook,
+                           const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,
+                           float *xhat);
+int inshr_ref_delta_k(const uint16_t *s_prev, uint32_t K_prev, const uint16_t *s_cur, uint32_t K_cur,
+                      uint64_t n, uint16_t *delta, uint32_t *perm, uint64_t *group_off,
+                      uint16_t *stream);
+int inshr_ref_reconstruct_k(const uint16_t *s_prev, uint32_t K_prev, uint32_t K_cur, uint64_t n,
+                            const uint64_t *group_off, const uint16_t *stream, uint16_t *s_cur);
+/* Width of a symbol stream with K bins: the smallest w with 2^w >= K + 2. */
+uint32_t inshr_ref_symbol_bits(uint32_t K);
 
 /* Little-endian bit stream: value i occupies bits [i*w, (i+1)*w) of the u64 word array,
  * tail zero-padded.  words must hold ceil(n*w/64) entries. */

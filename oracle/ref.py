@@ -12,7 +12,24 @@ from . import build as _build
 
 
 class Config(C.Structure):
-    _fields_ = [("bits", C.c_uint8), ("prune_ppm", C.c_uint32), ("outlier_ppm", C.c_uint32)]
+    _fields_ = [("bits", C.c_uint8), ("bins", C.c_uint16), ("prune_ppm", C.c_uint32),
+                ("outlier_ppm", C.c_uint32)]
+
+
+def _config(cfg):
+    """cfg = (bits, prune_ppm, outlier_ppm) or (bits, prune_ppm, outlier_ppm, bins): with bins > 0
+    the number of bins is that count, otherwise 2^bits."""
+    b, p, o = cfg[:3]
+    k = int(cfg[3]) if len(cfg) > 3 else 0
+    return Config(int(b), k, int(p), int(o))
+
+
+def bins_of(cfg):
+    return int(cfg[3]) if len(cfg) > 3 and cfg[3] else 1 << int(cfg[0])
+
+
+def symbol_bits(K):
+    return int(lib().inshr_ref_symbol_bits(C.c_uint32(K)))
 
 
 class Score(C.Structure):
@@ -42,8 +59,8 @@ def _p(a, t):
 
 def _grid(grid):
     arr = (Config * len(grid))()
-    for i, (b, p, o) in enumerate(grid):
-        arr[i] = Config(int(b), int(p), int(o))
+    for i, cfg in enumerate(grid):
+        arr[i] = _config(cfg)
     return arr
 
 
@@ -54,11 +71,11 @@ class RefError(RuntimeError):
 
 
 def quantize(x, cfg):
-    """cfg = (bits, prune_ppm, outlier_ppm). Returns dict of numpy arrays and scalars."""
+    """cfg = (bits, prune_ppm, outlier_ppm[, bins]). Returns dict of numpy arrays and scalars."""
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     n = x.size
-    bits, p, o = cfg
-    K = 1 << bits
+    o = cfg[2]
+    K = bins_of(cfg)
     cap = max(1, n * int(o) // 1000000)
     sym = np.empty(n, np.uint16)
     bnd = np.empty(max(K - 1, 1), np.float32)
@@ -66,7 +83,7 @@ def quantize(x, cfg):
     oi = np.empty(cap, np.uint32)
     ov = np.empty(cap, np.float32)
     info = QInfo()
-    c = Config(int(bits), int(p), int(o))
+    c = _config(cfg)
     rc = lib().inshr_ref_quantize(_p(x, C.c_float), C.c_uint64(n), C.byref(c), _p(sym, C.c_uint16),
                                   _p(bnd, C.c_float), _p(cb, C.c_float), _p(oi, C.c_uint32),
                                   _p(ov, C.c_float), C.byref(info))
@@ -75,9 +92,18 @@ def quantize(x, cfg):
     no = int(info.n_outlier)
     return dict(sym=sym, boundaries=bnd[:K - 1], codebook=cb, outlier_idx=oi[:no].copy(),
                 outlier_val=ov[:no].copy(), n_pruned=int(info.n_pruned), n_outlier=no,
-                n_kept=int(info.n_kept), sym_bits=int(info.sym_bits),
+                n_kept=int(info.n_kept), sym_bits=int(info.sym_bits), K=K,
                 tau_prune_bits=int(info.tau_prune_bits), tau_outlier_bits=int(info.tau_outlier_bits),
                 sse=float(info.sse), sumsq=float(info.sumsq))
+
+
+def bf16_round(x):
+    """Protected values as Sec. 4.2 stores them: rounded to bfloat16 (returned as float32)."""
+    x = np.ascontiguousarray(x, np.float32)
+    f = lib().inshr_ref_bf16_round
+    f.restype = C.c_float
+    f.argtypes = [C.c_float]
+    return np.array([f(float(v)) for v in x.ravel()], np.float32).reshape(x.shape)
 
 
 def search(x, grid, eps):
@@ -96,21 +122,26 @@ def search(x, grid, eps):
     return int(best.value), int(feas.value), scores
 
 
-def dequantize(sym, bits, codebook, outlier_idx, outlier_val):
+def dequantize(sym, bits, codebook, outlier_idx, outlier_val, K=None):
+    """K: the number of bins when it is not 2^bits."""
     sym = np.ascontiguousarray(sym, np.uint16)
     cb = np.ascontiguousarray(codebook, np.float32)
     oi = np.ascontiguousarray(outlier_idx, np.uint32)
     ov = np.ascontiguousarray(outlier_val, np.float32)
     out = np.empty(sym.size, np.float32)
-    rc = lib().inshr_ref_dequantize(_p(sym, C.c_uint16), C.c_uint64(sym.size), C.c_uint32(bits),
-                                    _p(cb, C.c_float), _p(oi, C.c_uint32), _p(ov, C.c_float),
-                                    C.c_uint64(oi.size), _p(out, C.c_float))
+    rc = lib().inshr_ref_dequantize_k(_p(sym, C.c_uint16), C.c_uint64(sym.size),
+                                      C.c_uint32(K if K else 1 << bits),
+                                      _p(cb, C.c_float), _p(oi, C.c_uint32), _p(ov, C.c_float),
+                                      C.c_uint64(oi.size), _p(out, C.c_float))
     if rc:
         raise RefError(rc)
     return out
 
 
-def delta(s_prev, bits_prev, s_cur, bits_cur):
+def delta(s_prev, bits_prev, s_cur, bits_cur, K_prev=None, K_cur=None):
+    """K_prev / K_cur: the numbers of bins when they are not 2^bits."""
+    K_prev = K_prev if K_prev else 1 << bits_prev
+    K_cur = K_cur if K_cur else 1 << bits_cur
     s_prev = np.ascontiguousarray(s_prev, np.uint16)
     s_cur = np.ascontiguousarray(s_cur, np.uint16)
     n = s_prev.size
@@ -118,26 +149,29 @@ def delta(s_prev, bits_prev, s_cur, bits_cur):
         raise RefError(-5)
     d = np.empty(n, np.uint16)
     perm = np.empty(n, np.uint32)
-    goff = np.empty((1 << bits_prev) + 3, np.uint64)
+    goff = np.empty(K_prev + 3, np.uint64)
     stream = np.empty(n, np.uint16)
-    rc = lib().inshr_ref_delta(_p(s_prev, C.c_uint16), C.c_uint32(bits_prev), _p(s_cur, C.c_uint16),
-                               C.c_uint32(bits_cur), C.c_uint64(n), _p(d, C.c_uint16),
-                               _p(perm, C.c_uint32), _p(goff, C.c_uint64), _p(stream, C.c_uint16))
+    rc = lib().inshr_ref_delta_k(_p(s_prev, C.c_uint16), C.c_uint32(K_prev), _p(s_cur, C.c_uint16),
+                                 C.c_uint32(K_cur), C.c_uint64(n), _p(d, C.c_uint16),
+                                 _p(perm, C.c_uint32), _p(goff, C.c_uint64), _p(stream, C.c_uint16))
     if rc:
         raise RefError(rc)
+    # the deltas lie in [0, B) with B = max(K_prev, K_cur) + 2 levels: same width as a symbol of the wider side
     return dict(delta=d, perm=perm, group_off=goff, stream=stream,
-                delta_bits=max(bits_prev, bits_cur) + 1)
+                delta_bits=symbol_bits(max(K_prev, K_cur)))
 
 
-def reconstruct(s_prev, bits_prev, bits_cur, group_off, stream):
+def reconstruct(s_prev, bits_prev, bits_cur, group_off, stream, K_prev=None, K_cur=None):
+    K_prev = K_prev if K_prev else 1 << bits_prev
+    K_cur = K_cur if K_cur else 1 << bits_cur
     s_prev = np.ascontiguousarray(s_prev, np.uint16)
     goff = np.ascontiguousarray(group_off, np.uint64)
     stream = np.ascontiguousarray(stream, np.uint16)
     out = np.empty(s_prev.size, np.uint16)
-    rc = lib().inshr_ref_reconstruct(_p(s_prev, C.c_uint16), C.c_uint32(bits_prev),
-                                     C.c_uint32(bits_cur), C.c_uint64(s_prev.size),
-                                     _p(goff, C.c_uint64), _p(stream, C.c_uint16),
-                                     _p(out, C.c_uint16))
+    rc = lib().inshr_ref_reconstruct_k(_p(s_prev, C.c_uint16), C.c_uint32(K_prev),
+                                       C.c_uint32(K_cur), C.c_uint64(s_prev.size),
+                                       _p(goff, C.c_uint64), _p(stream, C.c_uint16),
+                                       _p(out, C.c_uint16))
     if rc:
         raise RefError(rc)
     return out

@@ -25,6 +25,14 @@ def make_grid(bits: Sequence[int], prune: Sequence[float], outlier: Sequence[flo
             for b in bits for p in prune for o in outlier]
 
 
+def grid_paper(prune=(0.0, 0.1, 0.2, 0.3, 0.4, 0.5), protect=(0.0005, 0.005, 0.01),
+               bins=(4, 6, 8, 12, 16, 32)):
+    """The search space of the paper's Sec. 5 (magnitude metric): numbers of bins x pruning fractions x
+    protection fractions, as (0, prune_ppm, protect_ppm, bins).  All of it has 18 (prune, protect)
+    pairs; one call of the library takes 15."""
+    return [(0, int(round(p * 1e6)), int(round(o * 1e6)), int(k)) for k in bins for p in prune for o in protect]
+
+
 def grid_small():
     """24 configurations: bits {2,3,4,8} x prune {0,.1,.3} x protect {0,.001}."""
     return make_grid([2, 3, 4, 8], [0.0, 0.1, 0.3], [0.0, 0.001])

@@ -23,11 +23,12 @@ def f32(v):
     return float(np.float32(v))
 
 
-def brute_quantize(x, bits, p_ppm, o_ppm):
-    """Independent pure-Python statement of the definitions (sorted(), linear scans)."""
+def brute_quantize(x, bits, p_ppm, o_ppm, bins=0):
+    """Independent pure-Python statement of the definitions (sorted(), linear scans).  bins > 0:
+    that many bins (the search space of Sec. 5 lists counts); else 2^bits."""
     xs = [f32(v) + 0.0 for v in x]  # +0.0 turns -0.0 into +0.0
     n = len(xs)
-    K = 2 ** bits
+    K = bins if bins else 2 ** bits
     n_p = n * p_ppm // 10 ** 6
     n_o = n * o_ppm // 10 ** 6
     mags = sorted(abs(v) for v in xs)
@@ -65,8 +66,15 @@ def brute_quantize(x, bits, p_ppm, o_ppm):
             sse += (v - cb[s - 2]) ** 2
     n_out = sum(1 for s in sym if s == 1)
     n_kept = sum(1 for s in sym if s >= 2)
+    # payload: log2 K bits per quantized value in units of 2^-16, rounded up (n_kept * bits for 2^bits)
+    from fractions import Fraction
+    import math
+    l16 = int(Fraction(math.log2(K)) * 65536 + Fraction(1, 2))
+    code = -((-n_kept * l16) // 65536)
+    if not bins:
+        assert code == n_kept * bits
     return dict(sym=sym, t=t, cb=cb, sse=sse, sumsq=sumsq, n_pruned=sym.count(0), n_outlier=n_out,
-                n_kept=n_kept, cost=n_kept * bits + 32 * n_out + 32 * K, tau_p=tau_p, tau_o=tau_o)
+                n_kept=n_kept, cost=code + 32 * n_out + 32 * K, tau_p=tau_p, tau_o=tau_o)
 
 
 def brute_search(x, grid, eps):
@@ -81,6 +89,9 @@ def brute_search(x, grid, eps):
 
 
 TINY_GRID = synth.make_grid([1, 2, 3, 8], [0.0, 0.1, 0.3, 0.5], [0.0, 0.001, 0.05, 0.2])
+# bin counts that are not powers of two (Sec. 5: 4, 6, 8, 12, 16, 32 bins), mixed with powers of two
+COUNT_GRID = [(b, p, o, k) for (b, p, o) in synth.make_grid([0], [0.0, 0.3], [0.0, 0.05])
+              for k in (3, 6, 12, 5, 255)] + synth.make_grid([2, 3], [0.0, 0.3], [0.0, 0.05])
 
 
 def tiny_cases():
@@ -129,6 +140,76 @@ def test_brute_force_tiny(name):
             assert s["cost_bits"] == r["cost"]
             assert s["n_kept"] == r["n_kept"]
             assert s["sse"] == pytest.approx(r["sse"], rel=1e-12, abs=0.0)
+
+
+@pytest.mark.parametrize("name", list(tiny_cases().keys()))
+def test_brute_force_tiny_bin_counts(name):
+    """The same with numbers of bins that are not powers of two."""
+    x = tiny_cases()[name]
+    for cfg in COUNT_GRID:
+        b = brute_quantize(x, *cfg)
+        q = ref.quantize(x, cfg)
+        K = cfg[3] if len(cfg) > 3 else 1 << cfg[0]
+        assert q["K"] == K and len(q["codebook"]) == K and len(q["boundaries"]) == K - 1
+        assert 2 ** q["sym_bits"] >= K + 2 > 2 ** (q["sym_bits"] - 1)
+        assert q["sym"].tolist() == b["sym"], (name, cfg)
+        assert [f32(v) for v in q["boundaries"]] == b["t"], (name, cfg)
+        assert [f32(v) for v in q["codebook"]] == b["cb"], (name, cfg)
+        assert (q["n_pruned"], q["n_outlier"], q["n_kept"]) == (b["n_pruned"], b["n_outlier"], b["n_kept"])
+        assert q["sse"] == pytest.approx(b["sse"], rel=1e-12, abs=0.0)
+    for eps in (-1.0, 1e-3, 1e-2, 0.3):
+        best, feas, scores = ref.search(x, COUNT_GRID, eps)
+        bb, bf, rows = brute_search(x, COUNT_GRID, eps)
+        assert (best, feas) == (bb, bf), (name, eps)
+        for s, r in zip(scores, rows):
+            assert s["cost_bits"] == r["cost"] and s["n_kept"] == r["n_kept"]
+            assert s["sse"] == pytest.approx(r["sse"], rel=1e-12, abs=0.0)
+
+
+@pytest.mark.parametrize("K", [3, 6, 12, 100])
+def test_equal_frequency_binning_with_a_bin_count_matches_numpy(K):
+    x, _ = synth.config0(seed=4, n=30_011)
+    q = ref.quantize(x, (0, 0, 0, K))
+    srt = np.sort(x)
+    t = srt[(np.arange(1, K, dtype=np.int64) * x.size) // K]
+    assert np.array_equal(q["boundaries"].view(np.uint32), t.view(np.uint32))
+    codes = np.searchsorted(t, x, side="right")
+    assert np.array_equal(q["sym"], (codes + 2).astype(np.uint16))
+    cnt = np.bincount(codes, minlength=K)
+    assert cnt.max() - cnt.min() <= 1  # distinct values: equal-frequency up to rounding of j*M/K
+    sums = np.bincount(codes, weights=x.astype(np.float64), minlength=K)
+    np.testing.assert_allclose(q["codebook"], (sums / cnt).astype(np.float32), rtol=1e-7)
+
+
+def test_six_bins_nest_in_twelve_and_cost_lies_between_powers_of_two():
+    """floor(j M / 6) = floor(2 j M / 12): the boundaries of 6 bins are every second one of 12 bins, so
+    the error does not increase from 6 to 12 bins; an ideal code of 6 levels costs log2 6 bits per
+    value, between 2 and 3 bits (Sec. 5: fewer bins compress more)."""
+    x, _ = synth.config0(seed=6, n=20_000)
+    q6, q12 = ref.quantize(x, (0, 100000, 1000, 6)), ref.quantize(x, (0, 100000, 1000, 12))
+    assert np.array_equal(q6["boundaries"], q12["boundaries"][1::2])
+    assert q12["sse"] <= q6["sse"] * (1 + 1e-9)
+    _, _, sc = ref.search(x, [(2, 100000, 1000), (0, 100000, 1000, 6), (3, 100000, 1000)], 1.0)
+    m = sc[0]["n_kept"]
+    assert sc[0]["cost_bits"] - 32 * 4 < sc[1]["cost_bits"] - 32 * 6 < sc[2]["cost_bits"] - 32 * 8
+    import math
+    assert abs((sc[1]["cost_bits"] - 32 * 6 - 32 * sc[1]["n_outlier"]) - m * math.log2(6)) <= 1 + m * 2 ** -17
+
+
+def test_delta_with_bin_counts():
+    rng = np.random.default_rng(11)
+    for Kp, Kc in ((6, 12), (12, 6), (6, 8), (3, 256)):
+        sp = rng.integers(0, Kp + 2, 5000).astype(np.uint16)
+        sc = rng.integers(0, Kc + 2, 5000).astype(np.uint16)
+        d = ref.delta(sp, 0, sc, 0, K_prev=Kp, K_cur=Kc)
+        B = max(Kp, Kc) + 2
+        assert d["delta_bits"] == int(np.ceil(np.log2(B)))
+        assert np.array_equal(d["delta"], ((sp.astype(np.int64) - sc.astype(np.int64)) % B).astype(np.uint16))
+        perm = np.argsort(sp, kind="stable")
+        assert np.array_equal(d["perm"], perm.astype(np.uint32))
+        assert np.array_equal(d["group_off"], np.concatenate([[0], np.cumsum(np.bincount(sp, minlength=Kp + 2))]).astype(np.uint64))
+        back = ref.reconstruct(sp, 0, 0, d["group_off"], d["stream"], K_prev=Kp, K_cur=Kc)
+        assert np.array_equal(back, sc)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -374,3 +455,21 @@ def test_consecutive_checkpoints_mostly_same_bin():
     q1 = ref.quantize(x1, (4, 100000, 1000))
     d = ref.delta(q0["sym"], 4, q1["sym"], 4)
     assert (d["stream"] == 0).mean() > 0.6
+
+
+def test_bfloat16_rounding_of_protected_values():
+    """Sec. 4.2 keeps protected values in bfloat16: against torch's conversion (round to nearest even),
+    with ties, carries into the exponent, denormals and both signs."""
+    import torch
+    rng = np.random.default_rng(13)
+    bits = np.concatenate([
+        rng.integers(0, 0x7f7f0000, 2000, dtype=np.int64),
+        np.array([0x3f808000, 0x3f818000, 0x3f807fff, 0x3f808001, 0x3fffffff, 0x00008000, 0x00018000,
+                  0x00000001, 0x7f7effff, 0], np.int64)]).astype(np.uint32)
+    bits = np.concatenate([bits, bits | np.uint32(0x80000000)])
+    x = bits.view(np.float32)
+    want = torch.from_numpy(x.copy()).to(torch.bfloat16).to(torch.float32).numpy()
+    got = ref.bf16_round(x)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert not (got.view(np.uint32) & 0xFFFF).any()
+    assert np.all(np.abs(got.astype(np.float64) - x.astype(np.float64)) <= np.abs(x.astype(np.float64)) * 2.0 ** -8 + 2.0 ** -133)
