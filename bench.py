@@ -50,10 +50,102 @@ def cpu_baseline(sample, grid, eps, threads):
     return 2 * n * 4 / dt / 1e9, dt
 
 
-# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# bench on the full workload, scaled by the counters' readings for a plain 1 GiB device copy
-# (profiles/bench_llama7b_hbm_traffic.md); counters cannot be read from inside the process.
-MEASURED_TRAFFIC_BYTES = {"k_dscatter": 26.5e9, "k_quant": 34.65e9, "k_gather": 29.95e9}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_llama7b_hbm_traffic.md")
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch (fetched + written) of `kernel` on the full workload, as the tracked
+    summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this bench states them (counters
+    cannot be read from inside the process).  The summary carries one machine-readable line
+    `traffic_bytes: {...}` with the commit its runs were made at.  (None, None) without it."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_bytes:"):
+                d = json.loads(line.split(":", 1)[1])
+                return d.get(kernel), d.get("measured_at")
+    except (OSError, ValueError):
+        pass
+    return None, None
+
+
+def copy_yardstick():
+    """A plain 1 GiB device-to-device copy: the kernel of known size that scales the FETCH_SIZE and
+    WRITE_SIZE counters of `rocprofv3 --pmc` (run this mode under the profiler)."""
+    import torch
+    dev = torch.device("cuda:0")
+    a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / 20
+    t0 = time.perf_counter()
+    for _ in range(20):
+        s = a.sum()
+    torch.cuda.synchronize()
+    dr = (time.perf_counter() - t0) / 20
+    print(json.dumps({"copy_yardstick": "device copies of 1 GiB (1048576 KiB read, 1048576 KiB written each)",
+                      "copy_GB/s_read_plus_write": round(2 * a.numel() * 4 / dt / 1e9, 1),
+                      "read_only_sum_GB/s": round(a.numel() * 4 / dr / 1e9, 1)}))
+
+
+def checkpoint_hash(torch, qs, ds):
+    """Order-sensitive 64-bit hash of all packed symbol words and delta stream words (wrapping
+    integer arithmetic on the device)."""
+    h = 0
+    for k, t in enumerate([q.packed for q in qs] + [d.packed for d in ds]):
+        w = torch.arange(1, t.numel() + 1, dtype=torch.int64, device=t.device) * 2654435761 + k
+        h = (h * 1000003 + int((t * w).sum())) & 0xFFFFFFFFFFFFFFFF
+    return h
+
+
+def validate_batch(torch, ctx, cur, cfgs, grid, eps, q_prev, q_cur, d_out, step):
+    """Untimed checks of the whole batch the timed steps worked on, on the device: class counts add
+    up; the delta stream decodes (Algorithm 6) to the current symbols; every symbol is in range and
+    the protected list holds exactly the elements with symbol 1 (the decoder checks both); every
+    protected value is the input bit for bit; pruned values decode to +0.0; the squared error of
+    the decoded checkpoint equals, per tensor, the score the search gave the chosen configuration;
+    two more steps leave identical bytes."""
+    res = {}
+    res["class_counts_add_up"] = all(q.n_pruned + q.n_outlier + q.n_kept == q.n for q in q_cur)
+    h1 = checkpoint_hash(torch, q_cur, d_out)
+    step()
+    h2 = checkpoint_hash(torch, q_cur, d_out)
+    res["bytes_identical_across_steps"] = h1 == h2
+    res["hash"] = f"{h2:016x}"
+    rec = ctx.reconstruct(q_prev, d_out, [c[0] for c in cfgs])
+    res["reconstructed_equals_current_codes"] = all(torch.equal(r, q.packed) for r, q in zip(rec, q_cur))
+    del rec
+    best, feas, scores = ctx.search(cur, grid, eps, want_scores=True)
+    res["same_choice_with_scores"] = [grid[b] for b in best] == list(cfgs)
+    buf = torch.empty(max(t.numel() for t in cur), dtype=torch.float32, device=cur[0].device)
+    prot_ok = zero_ok = sse_ok = True
+    worst = 0.0
+    for i, (t, q) in enumerate(zip(cur, q_cur)):
+        x = t.reshape(-1)
+        y = buf[:x.numel()]
+        ctx.dequantize([q], out=[y])  # raises on a symbol out of range or a wrong protected list
+        idx = q.outlier_idx.to(torch.int64) & 0xFFFFFFFF
+        prot_ok = prot_ok and torch.equal(x[idx].view(torch.int32), q.outlier_val.view(torch.int32)) \
+            and torch.equal(y[idx].view(torch.int32), q.outlier_val.view(torch.int32))
+        tau = q.tau_prune
+        zero_ok = zero_ok and bool((y[x.abs() < tau].view(torch.int32) == 0).all())
+        sse = float(((x.double() - y.double()) ** 2).sum())
+        sc = scores[i * len(grid) + best[i]]
+        err = abs(sc.sse - sse) / (1e-6 * sse + 1e-12 * sc.sumsq + 1e-300)
+        worst = max(worst, err)
+        sse_ok = sse_ok and err <= 1.0
+    res["protected_values_bit_exact"] = prot_ok
+    res["pruned_decode_to_zero"] = zero_ok
+    res["decoded_error_equals_score"] = sse_ok
+    res["decoded_error_vs_score_worst_over_tolerance"] = round(worst, 4)
+    res["validated"] = all(v for k, v in res.items() if isinstance(v, bool))
+    return res
 
 
 def main():
@@ -67,6 +159,11 @@ def main():
                          "smaller ones (config0 tensor, ResNet-50 / BERT-base / GPT-2-medium shapes "
                          "with Adam state), reported for reference")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-validate", action="store_true",
+                    help="skip the untimed checks of the batch after the timed steps")
+    ap.add_argument("--copy-yardstick", action="store_true",
+                    help="run only a plain 1 GiB device copy (the kernel of known size that scales the "
+                         "HBM traffic counters of rocprofv3 --pmc) and exit")
     ap.add_argument("--restore", action="store_true",
                     help="also time the restore side (reconstruct + dequantize of the checkpoint) after "
                          "the timed steps and report it as an extra object; needs 4 more bytes per value")
@@ -79,6 +176,10 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.copy_yardstick:
+        copy_yardstick()
+        return
 
     import numpy as np
     import torch
@@ -137,12 +238,15 @@ def main():
     torch.cuda.synchronize()
     ctx.profile(True)
     t0 = time.perf_counter()
+    marks = [t0]
     for _ in range(args.steps):
-        cfgs = step()
+        cfgs = step()  # (ends with a synchronisation of the stream)
+        marks.append(time.perf_counter())
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = ctx.profile_read()
     ctx.profile(False)
+    step_ms = sorted((b - a) * 1e3 for a, b in zip(marks, marks[1:]))
 
     ms_per_step = dt / args.steps * 1e3
     value = n_total * 4 / (dt / args.steps) / 1e9
@@ -164,13 +268,19 @@ def main():
     }
     dom_bytes = kernel_bytes.get(dom, 4.0) * n_total
     achieved = dom_bytes / (per_launch[dom] * 1e-3) / 1e9
+    traffic, traffic_at = measured_traffic(dom) if (args.layers == 32 and args.config == 4) else (None, None)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if (args.layers == 32 and args.config == 4) else None,
+                "traffic": traffic, "traffic_measured_at": traffic_at,
                 "avg_launch_ms": round(per_launch[dom], 4),
                 "path_floor_bytes_per_elem": round(a_bytes / n_total, 3),
                 "path_achieved": round(path_gbs, 1), "path_frac": round(path_gbs / HBM_PEAK_GBS, 4),
                 "kernel_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in sorted(prof.items())}}
+
+    validation = None
+    if not args.no_validate:
+        validation = validate_batch(torch, ctx, cur, cfgs, grid, eps, q_prev, q_cur, d_out, step)
+        validation["lds_ordered"] = ctx.lds_ordered
 
     restore = None
     if args.restore:
@@ -315,18 +425,25 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
-        rows = 1 << 20  # the first 2^20 values of the first `threads` 2-D weights
+        rows = 1 << 20  # the first 2^20 values of the first `threads` 2-D weights ...
         picks = [i for i, t in enumerate(cur) if t.numel() >= rows][:threads]
-        sample = [(prev[i][:rows].cpu().numpy(), cur[i][:rows].cpu().numpy()) for i in picks]
+        sample = [(prev[i].reshape(-1)[:rows].cpu().numpy(), cur[i].reshape(-1)[:rows].cpu().numpy()) for i in picks]
+        # ... and every whole tensor the oracle finishes in seconds (a whole 4096 x 4096 weight takes
+        # the sort-based oracle minutes on one core, more than this leg may spend)
+        small = [i for i, t in enumerate(cur) if t.numel() <= 1 << 16]
+        sample += [(prev[i].reshape(-1).cpu().numpy(), cur[i].reshape(-1).cpu().numpy()) for i in small]
         gbs, secs = cpu_baseline(sample, grid, eps, threads)
         cpu = {"value": round(gbs, 5), "unit": "GB/s", "cores": threads, "kind": "oracle",
-               "sample": f"first {rows} values of {len(picks)} weight tensors ({', '.join(names[i] for i in picks[:3])}, ...), "
-                         f"both checkpoints, same 105-config grid, {secs:.1f} s wall"}
+               "sample": f"first {rows} values of {len(picks)} weight tensors ({', '.join(names[i] for i in picks[:3])}, ...) "
+                         f"and {len(small)} whole tensors of at most 65536 values ({', '.join(names[i] for i in small[:2])}, ...), "
+                         f"both checkpoints, same {len(grid)}-config grid, {secs:.1f} s wall"}
 
     out = {
         "metric": "GB/s fp32 checkpoint searched+quantized+delta-encoded; % of HBM roofline",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "ms_step_median": round(step_ms[len(step_ms) // 2], 3), "ms_step_min": round(step_ms[0], 3),
+        "ms_step_max": round(step_ms[-1], 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{what}; {len(cur)} tensors, {n_total} values; grid of {len(grid)} "
                                f"configurations (" + ("bits 2..8 x prune {0,.05,.1,.2,.4} x protect {0,1e-4,1e-3}"
@@ -339,6 +456,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if validation is not None:
+        out["validation"] = validation
     if restore is not None:
         out["restore"] = restore
     if sketch is not None:

@@ -74,12 +74,21 @@ void inshr_destroy(inshr_ctx *ctx);
 const char *inshr_strerror(int code);
 const char *inshr_last_device_error(const inshr_ctx *ctx);
 int inshr_sync(inshr_ctx *ctx);
+/* 1 when the context ranks equal symbols (delta regrouping, group sort of the search) with one
+ * returning LDS add per element, which needs same-address LDS atomics to be served in lane order:
+ * checked on the device when the context is created and cross-checked against ballot ranks inside
+ * the kernels on a quarter of the tiles; 0 when the ballot-ranked kernels are in use
+ * (INSHR_NO_LDS_ORDER=1, or the check at creation failed). */
+int inshr_lds_ordered(const inshr_ctx *ctx);
 
 typedef struct {
-    uint8_t bits;         /* 1..8; K = 1 << bits bins                               */
+    uint8_t bits;         /* 1..8; K = 1 << bits bins (when bins == 0)               */
+    uint16_t bins;        /* 0, or the number of bins K itself (Sec. 5 lists counts: 4, 6, 8, 12, 16,
+                             32): a power of two up to 256, or 3, 6, 12; bits is then ignored  */
     uint32_t prune_ppm;   /* pruning fraction x 1e6 (floor(n*ppm/1e6) smallest |x|)  */
     uint32_t outlier_ppm; /* protection fraction x 1e6 (largest |x|); sum < 1e6      */
 } inshr_config;
+/* Symbols take the smallest w with 2^w >= K + 2 bits (bits + 1 for K = 2^bits). */
 
 typedef struct {
     const float *data; /* device, 4-byte aligned, read-only, caller-owned */
@@ -90,7 +99,8 @@ typedef struct {
     double sse;   /* sum_pruned x^2 + sum_quantized (x - centre)^2, fp64 */
     double sumsq; /* sum_all x^2 */
     uint64_t n_pruned, n_outlier, n_kept;
-    uint64_t cost_bits; /* n_kept*bits + 32*n_outlier + 32*K: payload model used to rank configs */
+    uint64_t cost_bits; /* payload model used to rank configs: ceil(n_kept * log2 K) + 32*n_outlier +
+                           32*K, log2 K taken in units of 2^-16 (n_kept * bits for K = 2^bits)       */
 } inshr_score;
 
 /* Score all n_cfg configurations on each of n_tensors tensors (Sec. 5).
@@ -110,13 +120,15 @@ typedef struct {
     float *codebook;        /* >= 256 floats; first K are written                                 */
     float *boundaries;      /* >= 255 floats or NULL; first K-1 interior bin boundaries           */
     uint32_t *outlier_idx;  /* protected indices, ascending; capacity outlier_cap (may be NULL    */
-    float *outlier_val;     /*   when outlier_cap == 0); original values, bit-exact               */
+    float *outlier_val;     /*   when outlier_cap == 0); original values, bit-exact (or bfloat16, see
+                                 INSHR_PROTECT_BF16)                                              */
     uint64_t outlier_cap;
     /* filled by the call (host side) */
     uint64_t n_pruned, n_outlier, n_kept;
-    uint32_t sym_bits;      /* bits + 1 */
+    uint32_t sym_bits;      /* width of a symbol: bits + 1 for K = 2^bits */
     float tau_prune;        /* pruned    <=> |x| <  tau_prune   */
     float tau_outlier;      /* protected <=> |x| >  tau_outlier */
+    uint32_t n_bins;        /* K */
 } inshr_quantized;
 
 /* Sizes of the buffers inshr_quantize needs for a tensor of n elements. */
@@ -128,23 +140,32 @@ int inshr_quantize_bound(uint64_t n, const inshr_config *cfg, uint64_t *packed_w
                                  (same pointers, sizes, order) and contained each cfg[i] in its
                                  grid; the data must not have changed since */
 
+#define INSHR_PROTECT_BF16 2u  /* protected values are stored in bfloat16 (Sec. 4.2): out[i].outlier_val
+                                 then receives outlier_cap uint16_t values, the fp32 value rounded to
+                                 nearest even on its upper 16 bits (a magnitude above the largest
+                                 finite bfloat16 becomes infinity, as the format defines).  Scores of
+                                 inshr_search count protected values as exact either way. */
+
 /* Quantize tensors[i] with cfg[i] into out[i] (arrays of n_tensors entries, host). */
 int inshr_quantize(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *cfg,
                    inshr_quantized *out, uint32_t n_tensors, uint32_t flags);
 
 typedef struct {
     const uint64_t *packed; /* device symbol stream */
-    uint32_t sym_bits;      /* bits + 1 */
-    uint8_t bits;
+    uint32_t sym_bits;      /* width of a symbol: bits + 1, or what n_bins of inshr_quantized implies */
+    uint8_t bits;           /* K = 1 << bits when bins == 0 */
+    uint16_t bins;          /* 0, or the number of bins K (2 .. 256) */
     uint64_t n;
 } inshr_codes;
 
 typedef struct {
     uint64_t *packed;       /* device, packed_words words (inshr_delta_bound): stream e[r]        */
     uint64_t packed_words;
-    uint64_t *group_off;    /* device, (1 << prev.bits) + 3 entries: #{i : s_prev[i] < g}          */
+    uint64_t *group_off;    /* device, K_prev + 3 entries: #{i : s_prev[i] < g}                    */
     uint32_t *perm;         /* device [n] or NULL: perm[r] = index of the r-th regrouped element   */
-    uint32_t delta_bits;    /* filled: max(prev.bits, cur.bits) + 1                                */
+    uint32_t delta_bits;    /* filled: width of a symbol of the side with more bins                */
+    uint32_t group_off_entries; /* capacity of group_off in entries, or 0 = not stated; a stated
+                                   capacity below (1 << prev.bits) + 3 gives INSHR_E_CAPACITY      */
 } inshr_delta_out;
 
 int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t *packed_words);
@@ -153,7 +174,11 @@ int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t 
  * stable order of s_prev (Algorithm 5): e[r] = d[perm[r]].  Arrays have n_tensors entries (host).
  * prev_perm: NULL, or host array of n_tensors device pointers (entries may be NULL) holding the
  * permutation of a previous call for the same prev codes; when given it is used instead of being
- * recomputed. */
+ * recomputed (out[t].perm must then be NULL: INSHR_E_ARG).  The call returns after enqueueing; what
+ * its kernels find wrong is reported by the next inshr_sync or inshr_delta on the context:
+ * INSHR_E_ARG when a given permutation holds an index outside its tensor (those elements are left
+ * out of the stream), INSHR_E_INTERNAL when the device did not rank equal symbols in order (see
+ * inshr_lds_ordered). */
 int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *prev_perm,
                 const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors);
 
@@ -166,7 +191,9 @@ typedef struct {
     const float *outlier_val;    /* device, their original values                                 */
     uint64_t n_outlier;
     uint64_t n;
-    uint8_t bits;
+    uint8_t bits;                /* K = 1 << bits when bins == 0 */
+    uint8_t protected_bf16;      /* nonzero: outlier_val holds uint16_t bfloat16 values (INSHR_PROTECT_BF16) */
+    uint16_t bins;               /* 0, or the number of bins K (2 .. 256) */
 } inshr_dequant_in;
 
 /* Inverse of the Quantizer (Sec. 4): out[t][i] = +0.0 for symbol 0, the protected value for symbol
@@ -179,8 +206,9 @@ int inshr_dequantize(inshr_ctx *ctx, const inshr_dequant_in *in, float *const *o
 
 typedef struct {
     uint64_t *packed;      /* device, receives the symbols of the current checkpoint              */
-    uint64_t packed_words; /* >= ceil(n * (bits + 1) / 64)                                         */
-    uint8_t bits;          /* bits of the current checkpoint's configuration                       */
+    uint64_t packed_words; /* >= ceil(n * symbol width / 64)                                        */
+    uint8_t bits;          /* bits of the current checkpoint's configuration (when bins == 0)      */
+    uint16_t bins;         /* 0, or its number of bins K (2 .. 256)                                */
 } inshr_codes_out;
 
 /* Inverse of the Delta Encoder (Sec. 6, Algorithm 6): element i, whose previous symbol is g, takes

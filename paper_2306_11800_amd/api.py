@@ -17,17 +17,30 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
-           "inshr_sync", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
 
 INSHR_REUSE_SEARCH = 1
+INSHR_PROTECT_BF16 = 2
+GROUP_OFF_ENTRIES = 259  # group offsets of a delta: (1 << 8) + 3, whatever the bits of prev
 
 
 class CConfig(C.Structure):
-    _fields_ = [("bits", C.c_uint8), ("prune_ppm", C.c_uint32), ("outlier_ppm", C.c_uint32)]
+    _fields_ = [("bits", C.c_uint8), ("bins", C.c_uint16), ("prune_ppm", C.c_uint32),
+                ("outlier_ppm", C.c_uint32)]
+
+
+def bins_of(cfg) -> int:
+    """Number of bins of a configuration tuple (bits, prune_ppm, outlier_ppm[, bins])."""
+    return int(cfg[3]) if len(cfg) > 3 and cfg[3] else 1 << int(cfg[0])
+
+
+def symbol_bits(K: int) -> int:
+    """Width of a symbol with K bins: K + 2 levels (pruned, protected, the bins)."""
+    return max(1, (K + 1).bit_length())
 
 
 class CTensor(C.Structure):
@@ -44,7 +57,7 @@ class CQuantized(C.Structure):
                 ("boundaries", C.c_void_p), ("outlier_idx", C.c_void_p), ("outlier_val", C.c_void_p),
                 ("outlier_cap", C.c_uint64), ("n_pruned", C.c_uint64), ("n_outlier", C.c_uint64),
                 ("n_kept", C.c_uint64), ("sym_bits", C.c_uint32), ("tau_prune", C.c_float),
-                ("tau_outlier", C.c_float)]
+                ("tau_outlier", C.c_float), ("n_bins", C.c_uint32)]
 
 
 class CSketchParams(C.Structure):
@@ -63,7 +76,7 @@ class CSketchChoice(C.Structure):
 
 class CCodes(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("sym_bits", C.c_uint32), ("bits", C.c_uint8),
-                ("n", C.c_uint64)]
+                ("bins", C.c_uint16), ("n", C.c_uint64)]
 
 
 class CKernelTime(C.Structure):
@@ -72,13 +85,13 @@ class CKernelTime(C.Structure):
 
 class CDeltaOut(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("group_off", C.c_void_p),
-                ("perm", C.c_void_p), ("delta_bits", C.c_uint32)]
+                ("perm", C.c_void_p), ("delta_bits", C.c_uint32), ("group_off_entries", C.c_uint32)]
 
 
 class CDequantIn(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("codebook", C.c_void_p), ("outlier_idx", C.c_void_p),
                 ("outlier_val", C.c_void_p), ("n_outlier", C.c_uint64), ("n", C.c_uint64),
-                ("bits", C.c_uint8)]
+                ("bits", C.c_uint8), ("protected_bf16", C.c_uint8), ("bins", C.c_uint16)]
 
 
 class CEntropyStats(C.Structure):
@@ -86,7 +99,8 @@ class CEntropyStats(C.Structure):
 
 
 class CCodesOut(C.Structure):
-    _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("bits", C.c_uint8)]
+    _fields_ = [("packed", C.c_void_p), ("packed_words", C.c_uint64), ("bits", C.c_uint8),
+                ("bins", C.c_uint16)]
 
 
 _lib = None
@@ -108,6 +122,7 @@ def load_library() -> C.CDLL:
     lib.inshr_last_device_error.argtypes = [C.c_void_p]
     lib.inshr_last_device_error.restype = C.c_char_p
     lib.inshr_sync.argtypes = [C.c_void_p]
+    lib.inshr_lds_ordered.argtypes = [C.c_void_p]
     lib.inshr_search.argtypes = [C.c_void_p, C.POINTER(CTensor), C.c_uint32, C.POINTER(CConfig),
                                  C.c_uint32, C.c_double, C.POINTER(C.c_uint32),
                                  C.POINTER(C.c_uint8), C.POINTER(CScore)]
@@ -153,9 +168,9 @@ class Quantized:
     """Device-side result of quantizing one tensor.  The tensors are views of buffers allocated at
     the capacity inshr_quantize_bound gives; the views are made when they are asked for.  Counts,
     thresholds and the symbol width are read from the C struct that inshr_quantize filled."""
-    __slots__ = ("n", "_bufs", "_ptrs", "_c", "_keep")
+    __slots__ = ("n", "_bufs", "_ptrs", "_c", "_keep", "bf16")
 
-    def __init__(self, n, bits, bufs, c_entry=None, keep=None):
+    def __init__(self, n, bits, bufs, c_entry=None, keep=None, bins=0):
         if c_entry is None:
             c_entry = CQuantized()
         self.n = n
@@ -163,10 +178,13 @@ class Quantized:
         self._ptrs = tuple(b.data_ptr() for b in bufs)
         self._c = c_entry                                   # element of the CQuantized array
         self._keep = keep                                   # the array itself
-        c_entry.sym_bits = bits + 1
+        self.bf16 = False                                   # protected values stored as bfloat16
+        c_entry.n_bins = bins if bins else 1 << bits
+        c_entry.sym_bits = symbol_bits(c_entry.n_bins)
 
     sym_bits = property(lambda self: self._c.sym_bits)
-    bits = property(lambda self: self._c.sym_bits - 1)
+    bits = property(lambda self: self._c.sym_bits - 1)      # of a power-of-two bin count
+    K = property(lambda self: self._c.n_bins)               # number of bins
     n_pruned = property(lambda self: self._c.n_pruned)
     n_kept = property(lambda self: self._c.n_kept)
     tau_prune = property(lambda self: self._c.tau_prune)
@@ -186,18 +204,20 @@ class Quantized:
 
     @property
     def codebook(self) -> torch.Tensor:      # float32 [K]
-        return self._bufs[1][:1 << self.bits]
+        return self._bufs[1][:self.K]
 
     @property
     def boundaries(self) -> torch.Tensor:    # float32 [K-1]
-        return self._bufs[2][:(1 << self.bits) - 1]
+        return self._bufs[2][:self.K - 1]
 
     @property
     def outlier_idx(self) -> torch.Tensor:   # int32 (bit pattern of u32) [n_outlier]
         return self._bufs[3][:self.n_outlier]
 
     @property
-    def outlier_val(self) -> torch.Tensor:   # float32 [n_outlier]
+    def outlier_val(self) -> torch.Tensor:   # float32 [n_outlier], or bfloat16 when stored so
+        if self.bf16:
+            return self._bufs[4].view(torch.bfloat16)[:self.n_outlier]
         return self._bufs[4][:self.n_outlier]
 
 
@@ -222,8 +242,9 @@ class Delta:
     n: int
     delta_bits: int
     packed: torch.Tensor        # int64 words
-    group_off: torch.Tensor     # int64 [(1 << bits_prev) + 3]
+    group_off: torch.Tensor     # int64 [(1 << bits_prev) + 3]: a view of goff_buf
     perm: Optional[torch.Tensor]  # int32 (bit pattern of u32) [n] or None
+    goff_buf: Optional[torch.Tensor] = None  # int64 [GROUP_OFF_ENTRIES]: room for any bits of prev
 
 
 def _tensor_array(tensors: Sequence[torch.Tensor]):
@@ -239,8 +260,8 @@ def _tensor_array(tensors: Sequence[torch.Tensor]):
 
 def _config_array(cfgs):
     arr = (CConfig * len(cfgs))()
-    for i, (b, p, o) in enumerate(cfgs):
-        arr[i] = CConfig(int(b), int(p), int(o))
+    for i, cfg in enumerate(cfgs):
+        arr[i] = CConfig(int(cfg[0]), int(cfg[3]) if len(cfg) > 3 else 0, int(cfg[1]), int(cfg[2]))
     return arr
 
 
@@ -279,6 +300,11 @@ class Context:
     def sync(self):
         self._check(self.lib.inshr_sync(self.h))
 
+    @property
+    def lds_ordered(self) -> bool:
+        """Whether equal symbols are ranked by returning LDS adds (True) or by ballots (False)."""
+        return bool(self.lib.inshr_lds_ordered(self.h))
+
     def profile(self, enable: bool):
         self._check(self.lib.inshr_profile(self.h, 1 if enable else 0))
 
@@ -311,7 +337,7 @@ class Context:
 
     # -- inshr_quantize -------------------------------------------------------------------
     def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False,
-                 out: Optional[List[Quantized]] = None) -> List[Quantized]:
+                 out: Optional[List[Quantized]] = None, protect_bf16: bool = False) -> List[Quantized]:
         """`out` may carry the list an earlier call returned for tensors of the same sizes; its
         device buffers are then written again.  When that call sized them for the largest
         configuration (8 bits and the largest protect fraction in use), nothing is marshalled
@@ -319,10 +345,12 @@ class Context:
         nT = len(tensors)
         ta = _tensor_array(tensors)
         ca = _config_array(cfgs)
-        flags = INSHR_REUSE_SEARCH if reuse_search else 0
+        flags = (INSHR_REUSE_SEARCH if reuse_search else 0) | (INSHR_PROTECT_BF16 if protect_bf16 else 0)
         if isinstance(out, QuantizedBatch) and out._sizes == tuple(t.numel() for t in tensors):
             # the C side checks every buffer against what the configuration needs
             self._check(self.lib.inshr_quantize(self.h, ta, ca, out._qa, nT, flags))
+            for q in out:
+                q.bf16 = protect_bf16
             return out
         qa = (CQuantized * nT)()
         res = QuantizedBatch()
@@ -334,14 +362,14 @@ class Context:
                 q = out[i]
                 if q.n != n or q._bufs[0].numel() < words or q._bufs[3].numel() < cap:
                     raise ValueError("pre-allocated buffers are too small")
-                q = Quantized(n, int(cfg[0]), q._bufs, e, qa)
+                q = Quantized(n, int(cfg[0]), q._bufs, e, qa, bins=bins_of(cfg))
             else:
                 q = Quantized(n, int(cfg[0]), (
                     torch.empty(words, dtype=torch.int64, device=t.device),
                     torch.empty(256, dtype=torch.float32, device=t.device),
                     torch.empty(255, dtype=torch.float32, device=t.device),
                     torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
-                    torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa)
+                    torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa, bins=bins_of(cfg))
             e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
             e.packed_words = q._bufs[0].numel()
             e.outlier_cap = q._bufs[3].numel()
@@ -349,6 +377,8 @@ class Context:
         res._qa = qa
         res._sizes = tuple(q.n for q in res)
         self._check(self.lib.inshr_quantize(self.h, ta, ca, qa, nT, flags))
+        for q in res:
+            q.bf16 = protect_bf16
         return res
 
     # -- inshr_quantize_sketch -------------------------------------------------------------
@@ -442,7 +472,7 @@ class Context:
         return res, choices, [(int(i.n_buckets), int(i.rounds)) for i in info]
 
     def _bound(self, n, ccfg, cfg):
-        key = (n, int(cfg[0]), int(cfg[1]), int(cfg[2]))
+        key = (n, bins_of(cfg), int(cfg[1]), int(cfg[2]))
         hit = self._bounds.get(key)
         if hit is None:
             words, cap = C.c_uint64(), C.c_uint64()
@@ -462,9 +492,10 @@ class Context:
                 and not want_perm):
             pa, ca, oa = out._pa, out._ca, out._oa
             for i in range(nT):
-                a, b = prev[i]._c.sym_bits, cur[i]._c.sym_bits
-                pa[i].sym_bits, pa[i].bits = a, a - 1
-                ca[i].sym_bits, ca[i].bits = b, b - 1
+                pa[i].sym_bits, pa[i].bins = prev[i]._c.sym_bits, prev[i]._c.n_bins
+                ca[i].sym_bits, ca[i].bins = cur[i]._c.sym_bits, cur[i]._c.n_bins
+                if out[i].group_off.numel() != pa[i].bins + 3:  # prev was quantized again with other bins
+                    out[i].group_off = out[i].goff_buf[:pa[i].bins + 3]
             self._check(self.lib.inshr_delta(self.h, pa, None, ca, oa, nT))
             for i in range(nT):
                 out[i].delta_bits = int(oa[i].delta_bits)
@@ -475,9 +506,9 @@ class Context:
         pp = (C.c_void_p * nT)() if prev_perm is not None else None
         res = DeltaBatch()
         for i, (p, c) in enumerate(zip(prev, cur)):
-            pa[i] = CCodes(p._ptrs[0], p.sym_bits, p.bits, p.n)
-            ca[i] = CCodes(c._ptrs[0], c.sym_bits, c.bits, c.n)
-            key = (p.n, p.sym_bits, p.bits, c.n, c.sym_bits, c.bits)
+            pa[i] = CCodes(p._ptrs[0], p.sym_bits, 0, p.K, p.n)
+            ca[i] = CCodes(c._ptrs[0], c.sym_bits, 0, c.K, c.n)
+            key = (p.n, p.K, c.n, c.K)
             need = self._bounds.get(key)
             if need is None:
                 words = C.c_uint64()
@@ -487,15 +518,19 @@ class Context:
                 d = out[i]
             else:
                 dev = p._bufs[0].device
-                d = Delta(n=p.n, delta_bits=max(p.bits, c.bits) + 1,
+                d = Delta(n=p.n, delta_bits=symbol_bits(max(p.K, c.K)),
                           packed=torch.empty(need, dtype=torch.int64, device=dev),
-                          group_off=torch.empty((1 << p.bits) + 3, dtype=torch.int64, device=dev),
+                          group_off=None, goff_buf=None,
                           perm=torch.empty(p.n, dtype=torch.int32, device=dev) if want_perm else None)
             if d.packed.numel() < need:
                 raise ValueError("pre-allocated delta buffer is too small")
+            if d.goff_buf is None or d.goff_buf.numel() < GROUP_OFF_ENTRIES:
+                d.goff_buf = torch.empty(GROUP_OFF_ENTRIES, dtype=torch.int64, device=d.packed.device)
+            d.group_off = d.goff_buf[:p.K + 3]
             oa[i].packed = d.packed.data_ptr()
             oa[i].packed_words = d.packed.numel()
-            oa[i].group_off = d.group_off.data_ptr()
+            oa[i].group_off = d.goff_buf.data_ptr()
+            oa[i].group_off_entries = d.goff_buf.numel()
             oa[i].perm = d.perm.data_ptr() if d.perm is not None else None
             if pp is not None:
                 pp[i] = prev_perm[i].data_ptr() if prev_perm[i] is not None else None
@@ -515,7 +550,8 @@ class Context:
         oa = (C.c_void_p * nT)()
         res = []
         for i, q in enumerate(qs):
-            ia[i] = CDequantIn(q._ptrs[0], q._ptrs[1], q._ptrs[3], q._ptrs[4], q.n_outlier, q.n, q.bits)
+            ia[i] = CDequantIn(q._ptrs[0], q._ptrs[1], q._ptrs[3], q._ptrs[4], q.n_outlier, q.n, 0,
+                               1 if q.bf16 else 0, q.K)
             x = out[i] if out is not None else torch.empty(q.n, dtype=torch.float32,
                                                            device=q._bufs[0].device)
             if x.dtype != torch.float32 or x.numel() != q.n or not x.is_contiguous():
@@ -527,24 +563,26 @@ class Context:
 
     # -- inshr_reconstruct ----------------------------------------------------------------
     def reconstruct(self, prev: Sequence[Quantized], deltas: Sequence[Delta],
-                    bits_cur: Sequence[int]) -> List[torch.Tensor]:
+                    bits_cur: Sequence[int], bins_cur: Optional[Sequence[int]] = None) -> List[torch.Tensor]:
         """Packed symbols (int64 words) of the current checkpoint from the previous codes and the
-        delta streams; returns after the work has completed."""
+        delta streams; returns after the work has completed.  bins_cur: the numbers of bins of the
+        current checkpoint where they are not 2^bits."""
         nT = len(prev)
         pa = (CCodes * nT)()
         da = (CDeltaOut * nT)()
         ca = (CCodesOut * nT)()
         res = []
         for i, (p, d) in enumerate(zip(prev, deltas)):
-            pa[i] = CCodes(p._ptrs[0], p.sym_bits, p.bits, p.n)
+            pa[i] = CCodes(p._ptrs[0], p.sym_bits, 0, p.K, p.n)
+            Kc = int(bins_cur[i]) if bins_cur is not None and bins_cur[i] else 1 << int(bits_cur[i])
             da[i].packed = d.packed.data_ptr()
             da[i].packed_words = d.packed.numel()
             da[i].group_off = d.group_off.data_ptr() if d.group_off is not None else None
             da[i].perm = None
             da[i].delta_bits = d.delta_bits
-            words = (p.n * (int(bits_cur[i]) + 1) + 63) // 64
+            words = (p.n * symbol_bits(Kc) + 63) // 64
             w = torch.empty(words, dtype=torch.int64, device=p._bufs[0].device)
-            ca[i] = CCodesOut(w.data_ptr(), words, int(bits_cur[i]))
+            ca[i] = CCodesOut(w.data_ptr(), words, 0, Kc)
             res.append(w)
         self._check(self.lib.inshr_reconstruct(self.h, pa, da, ca, nT))
         return res

@@ -37,9 +37,15 @@ struct inshr_ctx {
     // tensors of at least this many elements get a sampled first sweep (INSHR_SAMPLE_MIN_N; 0 = never)
     uint64_t sample_min_n = 16ull << 20;
     bool sample_force_miss = false; // INSHR_SAMPLE_FORCE_MISS=1 (tests): always take the exact sweeps again
+    // keys a wave may gather per tile of its 1024 elements, on average over its tiles (of 1024): the
+    // gather pools are sized by it; a search that finds them too small doubles it and runs again
+    // (INSHR_POOL_WCAP sets the start)
+    uint32_t pool_wcap = 136;
     std::vector<char> batch_sampled;
     std::string last_err;
 
+    u32 *delta_flags = nullptr; // flag word of the delta kernels (DF_*), allocated with the context
+    bool delta_pending = false; // an asynchronous delta call has not had its flags read yet
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
     DevBuf aux_mem;    // quantize descriptors, delta scratch
     DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
@@ -142,6 +148,21 @@ int ensure_dev(inshr_ctx *c, DevBuf &b, size_t bytes)
     return INSHR_OK;
 }
 
+// After the stream has been synchronised: the flags that the kernels of the last inshr_delta raised.
+int take_delta_flags(inshr_ctx *c)
+{
+    if (!c->delta_pending) return INSHR_OK;
+    u32 f = 0;
+    HIPCHK(c, hipMemcpy(&f, c->delta_flags, sizeof(u32), hipMemcpyDeviceToHost));
+    c->delta_pending = false;
+    if (f & DF_ORDER) {
+        c->last_err = "delta: ranks from returning LDS atomics disagree with ballot ranks (set INSHR_NO_LDS_ORDER=1)";
+        return INSHR_E_INTERNAL;
+    }
+    if (f & DF_PERM) return INSHR_E_ARG;
+    return INSHR_OK;
+}
+
 int ensure_host(inshr_ctx *c, HostBuf &b, size_t bytes)
 {
     if (bytes <= b.cap) return INSHR_OK;
@@ -163,9 +184,19 @@ struct Carver { // lays sub-buffers out in one allocation, 256-byte aligned
     }
 };
 
+uint32_t bins_of(const inshr_config &c) { return c.bins ? c.bins : (1u << c.bits); }
+bool same_config(const inshr_config &a, const inshr_config &b)
+{
+    return bins_of(a) == bins_of(b) && a.prune_ppm == b.prune_ppm && a.outlier_ppm == b.outlier_ppm;
+}
+
 int check_config(const inshr_config &c)
 {
-    if (c.bits < 1 || c.bits > 8) return INSHR_E_CONFIG;
+    if (c.bins) {
+        if (!bins_supported(c.bins)) return INSHR_E_CONFIG;
+    } else if (c.bits < 1 || c.bits > 8) {
+        return INSHR_E_CONFIG;
+    }
     if ((uint64_t)c.prune_ppm + (uint64_t)c.outlier_ppm >= 1000000ull) return INSHR_E_CONFIG;
     return INSHR_OK;
 }
@@ -176,6 +207,7 @@ int build_grid(const inshr_config *grid, uint32_t n_cfg, double eps, GridDesc &g
     memset(&g, 0, sizeof(g));
     g.n_cfg = n_cfg;
     g.eps = eps;
+    g.n_bnd = NB8;
     for (uint32_t i = 0; i < n_cfg; i++) {
         int rc = check_config(grid[i]);
         if (rc) return rc;
@@ -202,7 +234,11 @@ int build_grid(const inshr_config *grid, uint32_t n_cfg, double eps, GridDesc &g
             g.n_pairs++;
         }
         g.cfg_pair[i] = q;
-        g.cfg_bits[i] = grid[i].bits;
+        const uint32_t K = bins_of(grid[i]);
+        g.cfg_K[i] = K;
+        g.cfg_bits[i] = symbol_bits(K) - 1u;
+        g.cfg_l16[i] = (uint32_t)std::floor(std::log2((double)K) * 65536.0 + 0.5);
+        if (K & (K - 1u)) g.n_bnd = NBT; // 3, 6 or 12 bins: the twelfths are boundaries too
     }
     return INSHR_OK;
 }
@@ -240,11 +276,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             td[t].data = tensors[t].data;
             td[t].n = tensors[t].n;
             td[t].tile0 = tile;
-            // two gather regions per tensor, each of whole tiles: a wave's share of a region is
-            // 1024 keys per tile, whether or not the tensor's last tile is full
             const u64 padded = (tensors[t].n + TILE - 1) / TILE * TILE;
-            td[t].pool_thr = pool;
-            td[t].pool_cand = pool + padded;
             td[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
             td[t].sampled = (c->sample_min_n && tensors[t].n >= c->sample_min_n && tensors[t].n < (1ull << 31))
                                 ? 1u : 0u;
@@ -252,9 +284,13 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             c->batch_sampled.resize(nT);
             c->batch_sampled[t] = (char)td[t].sampled;
             tile += padded / TILE;
-            pool += 2 * padded;
         }
         for (int w = 0; w <= n_wg; w++) wg_tile0[w] = total_tiles * (u64)w / (u64)n_wg;
+        // Gather pools: every wave of a (workgroup, tensor) unit owns a share of each pool, sized for
+        // pool_wcap keys per tile of the unit plus one full tile (the sweeps stop gathering when the
+        // share cannot take a whole tile any more), and never more than the wave's elements.
+        std::vector<u64> unit_off;
+        std::vector<u32> unit_capw;
         u32 units = 0;
         uint32_t t = 0;
         for (int w = 0; w < n_wg; w++) {
@@ -266,6 +302,18 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             while (true) {
                 t_units[tt].push_back(units++);
                 const u64 t_end = (tt + 1 < nT) ? td[tt + 1].tile0 : total_tiles;
+                const u64 u_lo = std::max(lo, td[tt].tile0), u_hi = std::min(hi, t_end);
+                const u64 tiles_u = u_hi - u_lo;
+                const u64 per_wave = TILE / (BLOCK / 64);
+                const u64 capw = std::min(tiles_u * per_wave, tiles_u * (u64)c->pool_wcap + per_wave);
+                if (t_units[tt].size() == 1) {
+                    td[tt].pool_grp = pool;
+                    td[tt].pool_len = 0;
+                }
+                unit_off.push_back(pool);
+                unit_capw.push_back((u32)capw);
+                td[tt].pool_len += capw * (BLOCK / 64);
+                pool += capw * (BLOCK / 64);
                 if (t_end >= hi) break;
                 tt++;
             }
@@ -279,6 +327,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_tfo = cv.take(sizeof(u32) * (nT + 1));
         const size_t o_tfi = cv.take(sizeof(u32) * units);
         const size_t o_fut = cv.take(sizeof(u32) * units);
+        const size_t o_us = cv.take((size_t)units * 8);
+        const size_t o_usb = cv.take((size_t)units * 4);
         const size_t up_bytes = cv.off;
         const size_t o_ts = cv.take(sizeof(TState) * nT);
         const size_t o_h1 = cv.take((size_t)nT * L1_BINS * 4);
@@ -289,9 +339,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_to = cv.take((size_t)total_tiles * MAX_FRAC * 4);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
-        const size_t o_us = cv.take((size_t)units * 8);
         const size_t o_ut = cv.take((size_t)units * 16 * 4);
-        const size_t o_usb = cv.take((size_t)units * 4);
         const size_t o_bi = cv.take((size_t)nT * L2_BINS * 4);
         const size_t o_cur = cv.take((size_t)nT * CURSOR_STRIDE * 4);
         const size_t o_tb = cv.take((size_t)nT * TGT_STRIDE * 4);
@@ -301,7 +349,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_sq = cv.take((size_t)units * SQ_STRIDE * 8);
         const size_t o_ed = cv.take((size_t)nT * MAX_EDGES * 4);
         const size_t o_sl = cv.take((size_t)nT * (L2_BINS + 64) * 2);
-        const size_t o_pe = cv.take((size_t)nT * MAX_PAIRS * 260 * 2);
+        const size_t o_pe = cv.take((size_t)nT * MAX_PAIRS * EIDX_STRIDE * 2);
         const size_t o_eb = cv.take((size_t)nT * MAX_EDGES * 4);
         const size_t o_ei = cv.take((size_t)nT * MAX_EDGES * 2);
         const size_t o_gel = cv.take((size_t)nT * MAX_GROUPS * 4);
@@ -321,6 +369,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_tkh = cv.take((size_t)nT * TGT_STRIDE * 4);
         const size_t o_gl = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_pool = cv.take((size_t)pool * 4);
+        const size_t o_pool2 = cv.take((size_t)pool * 4);
         rc = ensure_dev(c, c->search_mem, cv.off);
         if (rc) return rc;
         rc = ensure_host(c, c->h_up, up_bytes);
@@ -342,6 +391,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             u32 *fut = (u32 *)(hb + o_fut);
             for (uint32_t tt = 0; tt < nT; tt++)
                 for (u32 u : t_units[tt]) fut[u] = tt;
+            memcpy(hb + o_us, unit_off.data(), sizeof(u64) * units);
+            memcpy(hb + o_usb, unit_capw.data(), sizeof(u32) * units);
         }
         HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, hipMemsetAsync(db + o_ts, 0, zero_end - o_ts, c->stream));
@@ -371,16 +422,16 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.hist1 = (u32 *)(db + o_h1);
         B.hist2 = (u32 *)(db + o_h2);
         B.table2 = (u32 *)(db + o_tab);
-        B.unit_start = (u64 *)(db + o_us);
+        B.unit_off = (const u64 *)(db + o_us);
         B.unit_thr = (u32 *)(db + o_ut);
-        B.unit_sub = (u32 *)(db + o_usb);
+        B.unit_capw = (const u32 *)(db + o_usb);
         B.binfo = (u32 *)(db + o_bi);
         B.cursor2 = (u32 *)(db + o_cur);
         B.tgt_bin = (u32 *)(db + o_tb);
         B.tgt_res = (u32 *)(db + o_tr);
         B.tgt_key = (u32 *)(db + o_tk);
         B.pool = (u32 *)(db + o_pool);
-        B.pool2 = B.pool;
+        B.pool2 = (u32 *)(db + o_pool2);
         B.unit_cand = (u32 *)(db + o_uc);
         B.bin_group = (u16 *)(db + o_bg);
         B.grp_off = (u32 *)(db + o_go);
@@ -425,6 +476,20 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
     const TState *hts = (const TState *)c->h_down.p;
     for (uint32_t t = 0; t < nT; t++) {
         if (hts[t].nonfinite) return INSHR_E_NONFINITE;
+    }
+    for (uint32_t t = 0; t < nT; t++) {
+        if (!hts[t].pool_overflow) continue;
+        // some wave gathered more keys than its share of a pool holds: larger pools, once more
+        const uint32_t full = TILE / (BLOCK / 64);
+        if (c->pool_wcap >= full) {
+            c->last_err = "gather pool overflow with full-size pools on tensor " + std::to_string(t);
+            return INSHR_E_INTERNAL;
+        }
+        c->pool_wcap = std::min<uint32_t>(full, c->pool_wcap * 2);
+        if (getenv("INSHR_SAMPLE_DEBUG"))
+            fprintf(stderr, "inshr_search: gather pools too small (tensor %u, code %u): again with %u keys per wave and tile\n",
+                    t, hts[t].pool_overflow, c->pool_wcap);
+        return run_search(c, tensors, nT, grid, n_cfg, eps, light);
     }
     if (getenv("INSHR_SAMPLE_DEBUG")) { // how many sampled first sweeps had to be repeated exactly
         uint32_t n_sampled = 0, n_redo = 0;
@@ -494,8 +559,16 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
             if (const char *e = getenv(name))
                 if (atoi(e) != 0) c->lds_ordered = false;
     }
+    if (hipMalloc(&c->delta_flags, 256) != hipSuccess) {
+        delete c;
+        return INSHR_E_DEVICE;
+    }
     if (const char *e = getenv("INSHR_SAMPLE_MIN_N")) c->sample_min_n = strtoull(e, nullptr, 10);
     if (const char *e = getenv("INSHR_SAMPLE_FORCE_MISS")) c->sample_force_miss = atoi(e) != 0;
+    if (const char *e = getenv("INSHR_POOL_WCAP")) {
+        const long v = atol(e);
+        if (v >= 1 && v <= TILE / (BLOCK / 64)) c->pool_wcap = (uint32_t)v;
+    }
     *out = c;
     return INSHR_OK;
 }
@@ -508,6 +581,7 @@ void inshr_destroy(inshr_ctx *c)
     if (c->search_mem.p) (void)hipFree(c->search_mem.p);
     if (c->aux_mem.p) (void)hipFree(c->aux_mem.p);
     if (c->sketch_mem.p) (void)hipFree(c->sketch_mem.p);
+    if (c->delta_flags) (void)hipFree(c->delta_flags);
     if (c->h_up.p) (void)hipHostFree(c->h_up.p);
     if (c->h_down.p) (void)hipHostFree(c->h_down.p);
     delete c;
@@ -535,8 +609,10 @@ int inshr_sync(inshr_ctx *c)
     if (!c) return INSHR_E_ARG;
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    return INSHR_OK;
+    return take_delta_flags(c);
 }
+
+int inshr_lds_ordered(const inshr_ctx *c) { return (c && c->lds_ordered) ? 1 : 0; }
 
 int inshr_profile(inshr_ctx *c, int enable)
 {
@@ -595,14 +671,14 @@ int inshr_quantize_bound(uint64_t n, const inshr_config *cfg, uint64_t *packed_w
     if (!cfg || n == 0 || n >= (1ull << 32)) return INSHR_E_ARG;
     int rc = check_config(*cfg);
     if (rc) return rc;
-    if (packed_words) *packed_words = (n * (uint64_t)(cfg->bits + 1) + 63) / 64;
+    if (packed_words) *packed_words = (n * (uint64_t)symbol_bits(bins_of(*cfg)) + 63) / 64;
     if (outlier_cap) *outlier_cap = n * (uint64_t)cfg->outlier_ppm / 1000000ull;
     return INSHR_OK;
 }
 
 static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quantized *out,
                                const uint32_t *which, uint32_t n_sel, const u32 *alt_key = nullptr,
-                               const float *alt_cb = nullptr)
+                               const float *alt_cb = nullptr, bool val_bf16 = false)
 {
     // alt_key / alt_cb: device arrays with 256 entries per tensor of the batch that replace the
     // search's boundaries and centres
@@ -614,9 +690,7 @@ static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quan
         const uint32_t t = which[k];
         uint32_t gi = 0;
         for (gi = 0; gi < c->grid.n_cfg; gi++)
-            if (c->grid_cfgs[gi].bits == cfg[k].bits && c->grid_cfgs[gi].prune_ppm == cfg[k].prune_ppm &&
-                c->grid_cfgs[gi].outlier_ppm == cfg[k].outlier_ppm)
-                break;
+            if (same_config(c->grid_cfgs[gi], cfg[k])) break;
         if (gi == c->grid.n_cfg) return INSHR_E_SHAPE;
         uint64_t words = 0, cap = 0;
         inshr_quantize_bound(c->tensors[t].n, &cfg[k], &words, &cap);
@@ -629,7 +703,7 @@ static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quan
         qd[t].out_val = out[k].outlier_val;
         qd[t].out_cap = out[k].outlier_cap;
         qd[t].cfg = gi;
-        qd[t].tslot = t;
+        qd[t].val_bf16 = val_bf16 ? 1u : 0u;
         qd[t].alt_key = alt_key ? alt_key + (size_t)t * 256 : nullptr;
         qd[t].alt_cb = alt_cb ? alt_cb + (size_t)t * 256 : nullptr;
     }
@@ -656,7 +730,8 @@ static int quantize_with_state(inshr_ctx *c, const inshr_config *cfg, inshr_quan
         out[k].n_pruned = r.n_pruned;
         out[k].n_outlier = r.n_outlier;
         out[k].n_kept = r.n_kept;
-        out[k].sym_bits = cfg[k].bits + 1u;
+        out[k].n_bins = bins_of(cfg[k]);
+        out[k].sym_bits = symbol_bits(out[k].n_bins);
         uint32_t tp = r.tau_p, to = r.tau_o;
         memcpy(&out[k].tau_prune, &tp, 4);
         memcpy(&out[k].tau_outlier, &to, 4);
@@ -686,7 +761,8 @@ int inshr_quantize(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config
             if (c->tensors[t].data != tensors[t].data || c->tensors[t].n != tensors[t].n) return INSHR_E_SHAPE;
             which[t] = t;
         }
-        return quantize_with_state(c, cfg, out, which.data(), n_tensors);
+        return quantize_with_state(c, cfg, out, which.data(), n_tensors, nullptr, nullptr,
+                                   (flags & INSHR_PROTECT_BF16) != 0);
     }
     // stand-alone: one internal single-configuration search per distinct configuration
     std::vector<char> done(n_tensors, 0);
@@ -696,8 +772,7 @@ int inshr_quantize(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config
         std::vector<inshr_config> subcfg;
         std::vector<uint32_t> idx;
         for (uint32_t t = t0; t < n_tensors; t++) {
-            if (!done[t] && cfg[t].bits == cfg[t0].bits && cfg[t].prune_ppm == cfg[t0].prune_ppm &&
-                cfg[t].outlier_ppm == cfg[t0].outlier_ppm) {
+            if (!done[t] && same_config(cfg[t], cfg[t0])) {
                 done[t] = 1;
                 sub.push_back(tensors[t]);
                 subcfg.push_back(cfg[t]);
@@ -712,7 +787,8 @@ int inshr_quantize(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config
             subout[k] = out[idx[k]];
             which[k] = (uint32_t)k;
         }
-        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), (uint32_t)sub.size());
+        rc = quantize_with_state(c, subcfg.data(), subout.data(), which.data(), (uint32_t)sub.size(), nullptr,
+                                 nullptr, (flags & INSHR_PROTECT_BF16) != 0);
         for (size_t k = 0; k < sub.size(); k++) out[idx[k]] = subout[k];
         if (rc) return rc;
     }
@@ -926,6 +1002,7 @@ int inshr_quantize_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr
     for (uint32_t t = 0; t < n_tensors; t++) {
         int rc = check_config(cfg[t]);
         if (rc) return rc;
+        if (cfg[t].bins) return INSHR_E_CONFIG; // the clustered bins come in powers of two, by bits
         for (int r = 0; r < (1 << cfg[t].bits); r++) {
             const double u = params->uniforms[(size_t)t * 256 + r];
             if (!(u >= 0.0 && u < 1.0)) return INSHR_E_ARG;
@@ -992,6 +1069,7 @@ int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_c
     if (!(params->sigma >= 0.0 && params->sigma <= 1.0) || !(eps >= 0.0)) return INSHR_E_CONFIG;
     std::vector<inshr_config> wide(n_tensors); // the tensor's fractions with 8 bits
     for (uint32_t t = 0; t < n_tensors; t++) {
+        if (cfg[t].bins) return INSHR_E_CONFIG;
         wide[t] = cfg[t];
         wide[t].bits = 8;
         int rc = check_config(wide[t]);
@@ -1080,12 +1158,26 @@ int inshr_sketch_buckets(double alpha, int32_t *i_lo, uint32_t *n_buckets, float
     return INSHR_OK;
 }
 
+// number of bins of a symbol stream; nonzero return: not a valid description
+static int codes_bins(const inshr_codes &c, uint32_t &K)
+{
+    if (c.bins) {
+        if (c.bins < 2 || c.bins > 256) return 1;
+        K = c.bins;
+    } else {
+        if (c.bits < 1 || c.bits > 8) return 1;
+        K = 1u << c.bits;
+    }
+    return 0;
+}
+
 int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t *packed_words)
 {
     if (!prev || !cur || !packed_words) return INSHR_E_ARG;
     if (prev->n != cur->n) return INSHR_E_SHAPE;
-    if (prev->bits < 1 || prev->bits > 8 || cur->bits < 1 || cur->bits > 8) return INSHR_E_CONFIG;
-    const uint32_t wB = (uint32_t)std::max(prev->bits, cur->bits) + 1u;
+    uint32_t Kp = 0, Kc = 0;
+    if (codes_bins(*prev, Kp) || codes_bins(*cur, Kc)) return INSHR_E_CONFIG;
+    const uint32_t wB = symbol_bits(std::max(Kp, Kc));
     *packed_words = (prev->n * (uint64_t)wB + 63) / 64;
     return INSHR_OK;
 }
@@ -1104,8 +1196,13 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
         if (rc) return rc;
         const uint64_t n = prev[t].n;
         if (n == 0 || n >= (1ull << 32) || !prev[t].packed || !cur[t].packed) return INSHR_E_ARG;
-        if (prev[t].sym_bits != prev[t].bits + 1u || cur[t].sym_bits != cur[t].bits + 1u) return INSHR_E_CONFIG;
+        uint32_t Kp = 0, Kc = 0;
+        (void)codes_bins(prev[t], Kp); // (checked by inshr_delta_bound)
+        (void)codes_bins(cur[t], Kc);
+        if (prev[t].sym_bits != symbol_bits(Kp) || cur[t].sym_bits != symbol_bits(Kc)) return INSHR_E_CONFIG;
         if (!out[t].packed || !out[t].group_off || out[t].packed_words < words) return INSHR_E_CAPACITY;
+        if (out[t].group_off_entries && out[t].group_off_entries < Kp + 3u) return INSHR_E_CAPACITY;
+        if (prev_perm && prev_perm[t] && out[t].perm) return INSHR_E_ARG; // a given permutation is not written again
         DDesc &d = dd[t];
         memset(&d, 0, sizeof(d));
         d.prev = (const unsigned long long *)prev[t].packed;
@@ -1118,10 +1215,9 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
         d.out_words = words;
         d.wp = prev[t].sym_bits;
         d.wc = cur[t].sym_bits;
-        d.Kp = 1u << prev[t].bits;
-        const uint32_t Kc = 1u << cur[t].bits;
-        d.B = std::max(d.Kp, Kc) + 2u;
-        d.wB = (uint32_t)std::max(prev[t].bits, cur[t].bits) + 1u;
+        d.Kp = Kp;
+        d.B = std::max(Kp, Kc) + 2u;
+        d.wB = symbol_bits(std::max(Kp, Kc));
         out[t].delta_bits = d.wB;
         d.dtile0 = dtile;
         d.chunk0 = chunk;
@@ -1149,13 +1245,17 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
     if (rc) return rc;
     // the staging buffer may still be in flight from an earlier asynchronous delta call
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    rc = take_delta_flags(c); // (of a call whose flags nobody has asked for yet)
+    if (rc) return rc;
     char *hb = (char *)c->h_up.p, *db = (char *)c->aux_mem.p;
     memcpy(hb + o_dd, dd.data(), sizeof(DDesc) * n_tensors);
     memcpy(hb + o_ct, chunk_tensor.data(), sizeof(u32) * chunk_tensor.size());
     HIPCHK(c, hipMemcpyAsync(db, hb, up_bytes, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->delta_flags, 0, sizeof(u32), c->stream));
+    c->delta_pending = true;
     HIPCHK(c, launch_delta((const DDesc *)(db + o_dd), (int)n_tensors, dtile, chunk,
-                           (const u32 *)(db + o_ct), (u32 *)(db + o_ck), any_scatter, any_perm,
-                           any_gather, c->lds_ordered, c->stream));
+                           (const u32 *)(db + o_ct), (u32 *)(db + o_ck), c->delta_flags, any_scatter,
+                           any_perm, any_gather, c->lds_ordered, c->stream));
     return INSHR_OK;
 }
 
@@ -1166,7 +1266,11 @@ int inshr_dequantize(inshr_ctx *c, const inshr_dequant_in *in, float *const *out
     u64 tile = 0, max_out = 0;
     for (uint32_t t = 0; t < n_tensors; t++) {
         const inshr_dequant_in &q = in[t];
-        if (q.bits < 1 || q.bits > 8) return INSHR_E_CONFIG;
+        inshr_codes as_codes;
+        as_codes.bits = q.bits;
+        as_codes.bins = q.bins;
+        uint32_t K = 0;
+        if (codes_bins(as_codes, K)) return INSHR_E_CONFIG;
         if (q.n == 0 || q.n >= (1ull << 32) || !q.packed || !q.codebook || !out[t]) return INSHR_E_ARG;
         if (q.n_outlier && (!q.outlier_idx || !q.outlier_val)) return INSHR_E_ARG;
         if (q.n_outlier > q.n) return INSHR_E_SHAPE;
@@ -1180,8 +1284,9 @@ int inshr_dequantize(inshr_ctx *c, const inshr_dequant_in *in, float *const *out
         d.n = q.n;
         d.n_outlier = q.n_outlier;
         d.tile0 = tile;
-        d.w = q.bits + 1u;
-        d.K = 1u << q.bits;
+        d.w = symbol_bits(K);
+        d.K = K;
+        d.val_bf16 = q.protected_bf16 ? 1u : 0u;
         tile += (q.n + DEQUANT_TILE - 1) / DEQUANT_TILE;
         max_out = std::max<u64>(max_out, q.n_outlier);
     }
@@ -1222,13 +1327,17 @@ int inshr_reconstruct(inshr_ctx *c, const inshr_codes *prev, const inshr_delta_o
     u64 dtile = 0, chunk = 0;
     for (uint32_t t = 0; t < n_tensors; t++) {
         const uint64_t n = prev[t].n;
-        if (prev[t].bits < 1 || prev[t].bits > 8 || cur[t].bits < 1 || cur[t].bits > 8) return INSHR_E_CONFIG;
-        if (prev[t].sym_bits != prev[t].bits + 1u) return INSHR_E_CONFIG;
+        inshr_codes cur_codes;
+        cur_codes.bits = cur[t].bits;
+        cur_codes.bins = cur[t].bins;
+        uint32_t Kp = 0, Kc = 0;
+        if (codes_bins(prev[t], Kp) || codes_bins(cur_codes, Kc)) return INSHR_E_CONFIG;
+        if (prev[t].sym_bits != symbol_bits(Kp)) return INSHR_E_CONFIG;
         if (n == 0 || n >= (1ull << 32) || !prev[t].packed || !delta[t].packed || !cur[t].packed) return INSHR_E_ARG;
-        const uint32_t wB = (uint32_t)std::max(prev[t].bits, cur[t].bits) + 1u;
+        const uint32_t wB = symbol_bits(std::max(Kp, Kc));
         if (delta[t].delta_bits != wB) return INSHR_E_CONFIG;
         if (delta[t].packed_words < (n * wB + 63) / 64) return INSHR_E_CAPACITY;
-        const uint32_t wc = cur[t].bits + 1u;
+        const uint32_t wc = symbol_bits(Kc);
         if (cur[t].packed_words < (n * wc + 63) / 64) return INSHR_E_CAPACITY;
         DDesc &d = dd[t];
         memset(&d, 0, sizeof(d));
@@ -1238,9 +1347,8 @@ int inshr_reconstruct(inshr_ctx *c, const inshr_codes *prev, const inshr_delta_o
         d.out_words = (n * wB + 63) / 64;
         d.wp = prev[t].sym_bits;
         d.wc = wc;
-        d.Kp = 1u << prev[t].bits;
-        const uint32_t Kc = 1u << cur[t].bits;
-        d.B = std::max(d.Kp, Kc) + 2u;
+        d.Kp = Kp;
+        d.B = std::max(Kp, Kc) + 2u;
         d.wB = wB;
         d.dtile0 = dtile;
         d.chunk0 = chunk;
@@ -1285,6 +1393,10 @@ int inshr_reconstruct(inshr_ctx *c, const inshr_codes *prev, const inshr_delta_o
     HIPCHK(c, hipMemcpyAsync(c->h_down.p, flags, sizeof(u32), hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     const u32 f = *(const u32 *)c->h_down.p;
+    if (f & RF_ORDER) {
+        c->last_err = "reconstruct: ranks from returning LDS atomics disagree with ballot ranks (set INSHR_NO_LDS_ORDER=1)";
+        return INSHR_E_INTERNAL;
+    }
     if (f & RF_GROUPS) return INSHR_E_SHAPE;
     if (f & RF_DELTA) return INSHR_E_ARG;
     return INSHR_OK;

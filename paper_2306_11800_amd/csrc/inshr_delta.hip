@@ -222,6 +222,32 @@ __device__ __forceinline__ RunWords run_words(u32 pos, u32 cnt, u32 wB)
     return r;
 }
 
+// Cross-check of the ordered ranking, once per chunk and wave, before the tile loop: the 64 previous
+// symbols of the wave's first row of the chunk's first tile are ranked once with returning adds into
+// the wave's (zero) counter row and once from ballots; the counters are zero again afterwards.  Returns 1 when the two disagree (the
+// device did not serve same-address LDS atomics in lane order).
+__device__ __forceinline__ u32 ordered_rank_check(const u32 *P, u32 *wrow, u32 ebase, u32 cnt, u32 S, u32 wp)
+{
+    const u32 lane = threadIdx.x & 63u;
+    const u32 off = ebase * wp;
+    u32 sp = S; // lanes past the end share the unused symbol S
+    if (ebase < cnt) {
+        sp = __builtin_amdgcn_alignbit(P[(off >> 5) + 1u], P[off >> 5], off & 31u) & ((1u << wp) - 1u);
+        sp = sp < S - 1u ? sp : S - 1u;
+    }
+    const u32 got = atomicAdd(&wrow[sp], 1u);
+    u64 peers = ~0ull;
+#pragma unroll
+    for (int b = 0; b < 9; b++) {
+        const bool bit = (sp >> b) & 1u;
+        const u64 m = __ballot(bit);
+        peers &= bit ? m : ~m;
+    }
+    const u32 bad = got != (u32)__popcll(peers & ((1ull << lane) - 1ull)) ? 1u : 0u;
+    wrow[sp] = 0u; // (after the add: the wave's LDS operations complete in order)
+    return bad;
+}
+
 // Sweep 1 of a tile: stable rank of every element among the equal symbols of its wave's 1024
 // elements.  Row r of a lane is element ebase + 64 r: its bit offset in the packed words moves
 // by 64 w per row, so the shift is a lane constant and the word address advances by 2 w.
@@ -334,7 +360,8 @@ __device__ __forceinline__ void flush_and_commit(ScatterShared &sh, const unsign
 template <bool PERM, bool ORDERED>
 __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict__ dd,
                                                      const u32 *__restrict__ chunk_tensor,
-                                                     const u32 *__restrict__ chunk_tot)
+                                                     const u32 *__restrict__ chunk_tot,
+                                                     u32 *__restrict__ flags)
 {
     __shared__ ScatterShared sh;
     // packed symbols of the current tile (variables of their own: the loads that fill them are
@@ -378,6 +405,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     __syncthreads();
     const u32 hot = __builtin_amdgcn_readfirstlane((u32)sh.hotkey & 511u);
     u32 *wrow = sh.wst + wave * srow;
+    u32 order_bad = 0u;
 
     auto tile_cnt = [&](u64 lt) -> u32 {
         const u64 rem = d.n - lt * (u64)DTILE;
@@ -386,6 +414,10 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
     lds_fetch<NWAVE>(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
     lds_fetch<NWAVE>(gptr(d.cur), lt0 * (u64)DTILE, tile_cnt(lt0), wc, Cw, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the first tile's words
+    if (ORDERED) {
+        __syncthreads(); // all shares of the first tile's words are in LDS
+        order_bad = ordered_rank_check(Pw, wrow, wave * 1024u + lane, tile_cnt(lt0), S, wp);
+    }
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
@@ -553,11 +585,15 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_dscatter(const DDesc *__restrict_
         if (r.tail && part)
             __hip_atomic_fetch_or(out + r.We, part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (ORDERED && order_bad) atomicOr(flags, DF_ORDER);
 }
 
 // regrouping given: e[r] = d[perm[r]] by gathering
+// A given permutation is checked as it is used: an index outside the tensor is skipped and raises
+// DF_PERM; symbols are clamped like those of the scatter, so a delta always fits its field.
 __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
-                                                   const u32 *__restrict__ chunk_tensor)
+                                                   const u32 *__restrict__ chunk_tensor,
+                                                   u32 *__restrict__ flags)
 {
     __shared__ unsigned long long pk[256 * 9];
     const u64 chunk = blockIdx.x;
@@ -565,6 +601,8 @@ __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
     if (!d.prev_perm) return;
     const u32 tid = threadIdx.x;
     const u32 wB = d.wB, Bm = d.B;
+    const u32 smax[2] = {d.Kp + 1u, Bm - 1u}; // largest symbol of either stream that is taken as it is
+    bool bad_index = false;
     const u64 c0 = (chunk - d.chunk0) * CHUNK_ELEMS;
     const u64 c1 = (c0 + CHUNK_ELEMS < d.n) ? c0 + CHUNK_ELEMS : d.n;
     for (u64 r0 = c0; r0 < c1; r0 += HTILE) {
@@ -576,6 +614,10 @@ __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
             const u32 l = tid + j * BLOCK;
             if (l >= cnt) break;
             const u64 i = gptr(d.prev_perm)[r0 + l];
+            if (i >= d.n) { // not a permutation of this tensor
+                bad_index = true;
+                continue;
+            }
             u32 sym[2];
             for (int which = 0; which < 2; which++) {
                 const GLOBAL_AS unsigned long long *src = which ? gptr(d.cur) : gptr(d.prev);
@@ -586,6 +628,7 @@ __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
                 unsigned long long x = src[wd] >> sh;
                 if (sh + w > 64u) x |= src[wd + 1] << (64u - sh);
                 sym[which] = (u32)x & ((1u << w) - 1u);
+                sym[which] = sym[which] < smax[which] ? sym[which] : smax[which];
             }
             u32 dv = sym[0] + Bm - sym[1];
             if (dv >= Bm) dv -= Bm;
@@ -601,6 +644,7 @@ __global__ __launch_bounds__(BLOCK) void k_dgather(const DDesc *__restrict__ dd,
         GLOBAL_AS unsigned long long *dst = gptr(d.out) + r0 * wB / 64u;
         for (u32 k = tid; k < n_words; k += BLOCK) dst[k] = pk[k];
     }
+    if (bad_index) atomicOr(flags, DF_PERM);
 }
 
 // clears the stream words that k_dscatter ORs into: the first word of every (chunk, group) run,
@@ -676,13 +720,17 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
     u32 *wrow = sh.wst + wave * srow;
     const GLOBAL_AS unsigned long long *stream = gptr(d.out);
     const u32 mB = (1u << wB) - 1u;
-    u32 bad = 0u;
+    u32 bad = 0u, order_bad = 0u;
     auto tile_cnt = [&](u64 lt) -> u32 {
         const u64 rem = d.n - lt * (u64)DTILE;
         return rem < (u64)DTILE ? (u32)rem : (u32)DTILE;
     };
     lds_fetch<NWAVE>(gptr(d.prev), lt0 * (u64)DTILE, tile_cnt(lt0), wp, Pw, wave);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (ORDERED) {
+        __syncthreads(); // all shares of the first tile's words are in LDS
+        order_bad = ordered_rank_check(Pw, wrow, wave * 1024u + lane, tile_cnt(lt0), S, wp);
+    }
     for (u64 lt = lt0; lt < lt1; lt++) {
         const u64 e0 = lt * (u64)DTILE;
         const u32 cnt = tile_cnt(lt);
@@ -790,6 +838,7 @@ __global__ __launch_bounds__(DBLOCK, 6) void k_drestore(const DDesc *__restrict_
         }
     }
     if (__ballot(bad != 0u) && lane == 0u) atomicOr(flags, RF_DELTA);
+    if (ORDERED && order_bad) atomicOr(flags, RF_ORDER);
 }
 
 // group offsets that came with the stream against those of the previous symbols
@@ -859,8 +908,8 @@ hipError_t launch_lds_order_check(u32 *violations, hipStream_t s)
 }
 
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
-                        const u32 *chunk_tensor, u32 *chunk_tot, bool any_scatter, bool any_perm,
-                        bool any_gather, bool lds_ordered, hipStream_t s)
+                        const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool any_scatter,
+                        bool any_perm, bool any_gather, bool lds_ordered, hipStream_t s)
 {
     PROF("k_dhist", s, k_dhist<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
     PROF("k_dgroups", s, k_dgroups<<<nT, SS, 0, s>>>(dd, chunk_tot));
@@ -868,17 +917,17 @@ hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
         PROF("k_dzero", s, k_dzero<<<(unsigned)n_chunks, SS, 0, s>>>(dd, chunk_tensor, chunk_tot));
     if (any_scatter) {
         if (lds_ordered)
-            PROF("k_dscatter", s, k_dscatter<false, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+            PROF("k_dscatter", s, k_dscatter<false, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot, flags));
         else
-            PROF("k_dscatter_slots", s, k_dscatter<false, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+            PROF("k_dscatter_slots", s, k_dscatter<false, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot, flags));
     }
     if (any_perm) {
         if (lds_ordered)
-            PROF("k_dscatter_perm", s, k_dscatter<true, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+            PROF("k_dscatter_perm", s, k_dscatter<true, true><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot, flags));
         else
-            PROF("k_dscatter_perm_slots", s, k_dscatter<true, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot));
+            PROF("k_dscatter_perm_slots", s, k_dscatter<true, false><<<(unsigned)n_chunks, DBLOCK, 0, s>>>(dd, chunk_tensor, chunk_tot, flags));
     }
-    if (any_gather) PROF("k_dgather", s, k_dgather<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor));
+    if (any_gather) PROF("k_dgather", s, k_dgather<<<(unsigned)n_chunks, BLOCK, 0, s>>>(dd, chunk_tensor, flags));
     return hipGetLastError();
 }
 

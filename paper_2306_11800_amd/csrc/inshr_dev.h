@@ -37,9 +37,11 @@ constexpr int MAX_FRAC = 8;         // distinct prune fractions, distinct protec
 constexpr int MAX_THR = 2 * MAX_FRAC;
 constexpr int MAX_PAIRS = 15;       // distinct (prune, protect) pairs in a grid
 constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits use a subset
-constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 259 = 3885 fits)
-constexpr int EPP = NB8 + 4;        // edges per pair: 255 boundaries + 4 class edges
-constexpr int EIDX_STRIDE = 260;    // per-pair stride of the edge positions
+constexpr int NBT = NB8 + 8;        // ... plus the boundaries of 12 bins that are not among them (the
+                                    // search space of Sec. 5 has 6 and 12 bins: 3, 6 and 12 bins nest)
+constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 267 = 4005 fits)
+constexpr int EPP = NBT + 4;        // edge items per pair: boundaries 0 .. NBT - 1, class edges NBT .. NBT + 3
+constexpr int EIDX_STRIDE = 268;    // per-pair stride of the edge positions
 constexpr int MAX_CFG = 256;
 constexpr int GROUP_SHIFT = 12;     // gathered keys per group of active bins: about 2^12
 constexpr int MAX_GROUPS = 8192;    // groups per tensor (the shift grows for huge tensors)
@@ -113,6 +115,41 @@ __device__ __forceinline__ u32 lookup_u16(const u16 *table, u32 key, u32 entry16
 #endif
     return *reinterpret_cast<const u16 *>(reinterpret_cast<const char *>(table) + (entry16 >> 5) + sub * 2u);
 }
+// Boundary j (1 .. K - 1) of K equal-frequency bins is the quantized value of rank floor(j M / K)
+// (Sec. 4.4, frequency-only reading).  A pair keeps NBT boundaries: index i < 255 is rank fraction
+// (i + 1) / 256 — every power of two K up to 256 uses a subset, floor(j M / K) =
+// floor(j (256 / K) M / 256) — and indices 255 .. 262 are the twelfths 1, 2, 4, 5, 7, 8, 10, 11 / 12
+// for K = 3, 6, 12 (the twelfths 3, 6, 9 are 64, 128, 192 / 256).
+__host__ __device__ __forceinline__ bool bins_supported(u32 K)
+{
+    return K >= 2u && K <= 256u && ((K & (K - 1u)) == 0u || K == 3u || K == 6u || K == 12u);
+}
+__host__ __device__ __forceinline__ u32 bnd_index(u32 K, u32 j)
+{
+    if ((K & (K - 1u)) == 0u) return j * (256u / K) - 1u;
+    const u32 jj = j * (12u / K);
+    if (jj % 3u == 0u) return (jj / 3u) * 64u - 1u;
+    return 255u + (jj - jj / 3u - 1u);
+}
+__host__ __device__ __forceinline__ void bnd_fraction(u32 i, u32 &num, u32 &den)
+{
+    if (i < (u32)NB8) {
+        num = i + 1u;
+        den = 256u;
+    } else {
+        const u32 k = i - (u32)NB8; // 0 .. 7 -> 1, 2, 4, 5, 7, 8, 10, 11
+        num = k + k / 2u + 1u;
+        den = 12u;
+    }
+}
+// width of a symbol stream with K bins: pruned, protected and K bins need K + 2 levels (Sec. 6)
+__host__ __device__ __forceinline__ u32 symbol_bits(u32 K)
+{
+    u32 w = 1u;
+    while ((1u << w) < K + 2u) w++;
+    return w;
+}
+
 __host__ __device__ __forceinline__ u32 bucket_flag(u32 l1_bin) { return 0x80000000u >> (l1_bin & 7u); }
 __host__ __device__ __forceinline__ bool in_threshold_bucket(u32 key, u32 entry)
 {
@@ -126,8 +163,9 @@ struct TDesc {           // one tensor of a batch
     const float *data;
     u64 n;
     u64 tile0;           // first tile of this tensor in the batch-wide tile numbering
-    u64 pool_thr;        // this tensor's region of the gather pool for threshold buckets (u32 units)
-    u64 pool_cand;       // ... and for the elements of active bins
+    u64 pool_grp;        // where this tensor's keys in bin-group order go in the first pool (u32 units):
+                         // the span of the tensor's (workgroup, tensor) units there, ...
+    u64 pool_len;        // ... and its length
     u32 aligned16;       // data pointer is 16-byte aligned (float4 loads allowed)
     u32 sampled;         // sweep 1 reads one tile in SAMPLE_RATE (large tensors): its histogram only
                          // shapes the second-level table and predicts where the thresholds lie
@@ -139,13 +177,19 @@ struct GridDesc {        // the configuration grid, decomposed
     u32 p_ppm[MAX_FRAC], o_ppm[MAX_FRAC];     // distinct fractions
     u32 pair_p[MAX_PAIRS], pair_o[MAX_PAIRS]; // indices into p_ppm / o_ppm
     u32 cfg_pair[MAX_CFG];
-    u32 cfg_bits[MAX_CFG];
+    u32 cfg_bits[MAX_CFG];                    // (meaningful for K = 2^bits only)
+    u32 cfg_K[MAX_CFG];                       // number of bins
+    u32 cfg_l16[MAX_CFG];                     // log2 K in units of 2^-16, rounded (payload model)
+    u32 n_bnd;                                // boundaries per pair in use: NB8, or NBT when some K is 3, 6 or 12
+    u32 pad;
     double eps;
 };
 
 struct TState {
     u32 nonfinite;
     u32 internal_err;
+    u32 pool_overflow;                 // a wave's share of a gather pool, or the tensor's span for the keys
+                                       // in group order, was too small: the search is repeated with larger pools
     u64 n_neg, n_zero;                 // strictly negative values; exact zeros (after -0 -> +0)
     // thresholds: index t < n_p is the prune threshold of p_ppm[t], t >= n_p the protect
     // threshold of o_ppm[t - n_p]

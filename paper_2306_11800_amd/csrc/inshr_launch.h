@@ -5,7 +5,7 @@
 namespace inshr {
 
 constexpr int CURSOR_STRIDE = L2_BINS + 64; // per-tensor stride of the gather cursors
-constexpr int TGT_STRIDE = 4096;            // per-tensor stride of boundary targets (15 * 255 fits)
+constexpr int TGT_STRIDE = 4096;            // per-tensor stride of boundary targets (15 * NBT fits)
 constexpr int SQ_STRIDE = MAX_FRAC + 1;     // partial sums of squares per (workgroup, tensor) unit
 constexpr int CB_STRIDE = 256;              // codebook entries per configuration
 
@@ -13,17 +13,19 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     TState *ts;
     u32 *hist1;     // [nT][32768]
     u32 *table2;    // [nT][4096]
-    u64 *unit_start; // [units] first element of each (workgroup, tensor) unit inside its tensor
-    u32 *unit_sub;   // [units] one wave's share of the unit's gather regions (1024 per tile)
+    const u64 *unit_off; // [units] start of each (workgroup, tensor) unit's share of a gather pool (u32 units)
+    const u32 *unit_capw; // [units] one wave's share of it: wave w of the unit owns
+                         // [unit_off + w * capw, unit_off + (w + 1) * capw)
     u32 *unit_thr;   // [units][16] threshold-bucket keys each wave of the unit gathered
     u32 *hist2;     // [nT][32768]
     u32 *binfo;     // [nT][32768] offset of an active bin's elements in the gather pool, or INACTIVE
     u32 *cursor2;   // [nT][CURSOR_STRIDE]
-    u32 *tgt_bin;   // [nT][TGT_STRIDE] boundary j of pair q at q*255 + j-1
+    u32 *tgt_bin;   // [nT][TGT_STRIDE] boundary i of pair q at q*NBT + i
     u32 *tgt_res;
     u32 *tgt_key;   // results: boundary keys
-    u32 *pool;      // gathered keys: per tensor a threshold region and an active-bin region, n each
-    u32 *pool2;     // same layout; the threshold region is reused for the keys in bin-group order
+    u32 *pool;      // first gather pool: the keys of the threshold windows (sweep 2), wave-private shares;
+                    // afterwards every tensor's keys of active bins in bin-group order (TDesc::pool_grp)
+    u32 *pool2;     // second gather pool, same layout: the keys of active bins as sweep 3 gathers them
     u32 *unit_cand; // [units][16] active-bin keys each wave of the unit gathered
     u16 *bin_group; // [nT][32768] group of each active bin
     u32 *grp_off;   // [nT][MAX_GROUPS] first / one-past-last position of each group in bin order
@@ -40,7 +42,7 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *edge_bin;  // [nT][MAX_EDGES] second-level bin of each edge
     u16 *edge_item; // [nT][MAX_EDGES] pair * 259 + (boundary j - 1, or 255 + class edge)
     u16 *sl;        // [nT][32768 + 64] slot of every bin without an edge; 0xFFFF for the others
-    u16 *pair_eidx; // [nT][MAX_PAIRS][260] position of each pair's edges in the list
+    u16 *pair_eidx; // [nT][MAX_PAIRS][EIDX_STRIDE] position of each pair's edges in the list
     u32 *grp_elo;   // [nT][MAX_GROUPS] first / one-past-last edge of each group of active bins
     u32 *grp_ehi;
     u32 *seg_cnt;   // [nT][MAX_EDGES] keys per slot that lie in bins without an edge
@@ -85,7 +87,7 @@ struct QDesc { // one tensor of a quantize call (indexed like the batch)
     float *out_val;
     u64 out_cap;
     u32 cfg;   // index into the grid of the search state
-    u32 tslot;
+    u32 val_bf16; // protected values are stored as bfloat16 (u16), rounded to nearest even
     const u32 *alt_key; // NULL, or 256 boundary keys that replace the search's (boundary j of K at
                         // (j << (8 - bits)) - 1) ...
     const float *alt_cb; // ... and the K centres that go with them
@@ -113,6 +115,7 @@ struct RDesc { // one tensor of a dequantize call
     float *dst;
     u64 n, n_outlier, tile0;
     u32 w, K;
+    u32 val_bf16, pad; // out_val holds bfloat16 values (u16)
 };
 constexpr int DEQUANT_TILE = 16384; // elements per workgroup of the decoding kernel (RDesc::tile0 counts these)
 struct XDesc { // one tensor of a reconstruct call: the delta descriptor plus what is checked
@@ -125,10 +128,13 @@ constexpr u32 RF_SYMBOL = 1u;  // a symbol outside 0 .. K + 1
 constexpr u32 RF_LIST = 2u;    // protected list and symbol stream disagree
 constexpr u32 RF_GROUPS = 4u;  // group offsets do not match the previous symbols
 constexpr u32 RF_DELTA = 8u;   // a delta outside 0 .. B - 1, or a result outside 0 .. K_cur + 1
+constexpr u32 RF_ORDER = 16u;  // ranks from returning LDS adds disagree with ranks from ballots
+// bits of the flag word of a delta call
+constexpr u32 DF_PERM = 1u;    // a given permutation holds an index outside its tensor
+constexpr u32 DF_ORDER = 2u;   // ranks from returning LDS adds disagree with ranks from ballots
 constexpr int DELTA_TILE = 12288;
 constexpr int DELTA_CHUNK = 64;
 constexpr int DELTA_SS = 264;
-
 // Optional per-kernel timing with HIP events on the launch stream (off by default).
 void prof_begin(const char *name, hipStream_t s);
 void prof_end(hipStream_t s);
@@ -144,8 +150,8 @@ hipError_t launch_edges(const Batch &bt, hipStream_t s); // edge order, bins wit
 hipError_t launch_score(const Batch &bt, hipStream_t s);
 hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStream_t s);
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
-                        const u32 *chunk_tensor, u32 *chunk_tot, bool any_scatter, bool any_perm,
-                        bool any_gather, bool lds_ordered, hipStream_t s);
+                        const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool any_scatter,
+                        bool any_perm, bool any_gather, bool lds_ordered, hipStream_t s);
 hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
 hipError_t launch_dequantize(const RDesc *rd, int nT, u64 n_tiles, u64 max_outlier, u32 *flags,
                              u32 *ones, int n_cu, hipStream_t s);

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
     const u32 tid = threadIdx.x;
     const TDesc d = td[t];
     const TState *st = B.ts + t;
-    const u32 g = q.cfg, pair = gd->cfg_pair[g], bits = gd->cfg_bits[g], K = 1u << bits;
+    const u32 g = q.cfg, pair = gd->cfg_pair[g], K = gd->cfg_K[g];
     const u32 o = gd->pair_o[pair], n_p = gd->n_p;
     const u64 n_tiles = (d.n + TILE - 1) / TILE;
     u32 carry = 0;
@@ -38,11 +38,11 @@ __global__ __launch_bounds__(BLOCK) void k_qprep(const TDesc *__restrict__ td,
         carry += tot;
         __syncthreads();
     }
-    const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
-    const u32 sh = 8u - bits;
+    // (boundary keys given from outside come as 256 entries, boundary j of K = 2^b at j * 256 / K - 1)
+    const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NBT;
     if (q.boundaries)
         for (u32 j = 1 + tid; j < K; j += BLOCK)
-            gptr(q.boundaries)[j - 1] = __uint_as_float(bits_of_key(tk[(j << sh) - 1u]));
+            gptr(q.boundaries)[j - 1] = __uint_as_float(bits_of_key(tk[bnd_index(K, j)]));
     const float *cb = q.alt_cb ? q.alt_cb : B.codebook + ((size_t)t * gd->n_cfg + g) * CB_STRIDE;
     for (u32 k = tid; k < K; k += BLOCK) gptr(q.codebook)[k] = cb[k];
     if (tid == 0) {
@@ -177,16 +177,16 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             continue;
         }
         const TState *st = B.ts + t;
-        const u32 g = q.cfg, pair = gd->cfg_pair[g], bits = gd->cfg_bits[g], K = 1u << bits;
-        const u32 w = bits + 1u, sh = 8u - bits;
+        const u32 g = q.cfg, pair = gd->cfg_pair[g], K = gd->cfg_K[g];
+        const u32 w = symbol_bits(K);
         const u32 o = gd->pair_o[pair];
         const u32 tau_p = st->thr_mag[gd->pair_p[pair]], tau_o = st->thr_mag[gd->n_p + o];
         const u32 nb2 = st->nb2;
-        const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NB8;
+        const u32 *tk = q.alt_key ? q.alt_key : B.tgt_key + (size_t)t * TGT_STRIDE + pair * NBT;
         const u32 n_bnd = K - 1u, n_bp = n_bnd + 4u;
         __syncthreads();
         for (u32 i = tid; i < (u32)COARSE; i += BLOCK) T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);
-        if (tid < n_bnd) qt.raw[tid] = tk[((tid + 1u) << sh) - 1u];
+        if (tid < n_bnd) qt.raw[tid] = tk[bnd_index(K, tid + 1u)];
         if (tid < 4u) qt.raw[n_bnd + tid] = class_edge_key(tid, tau_p, tau_o);
         __syncthreads();
         if (tid < n_bp) { // sort by counting the smaller ones
@@ -292,7 +292,12 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
                             const u64 pos = obase + r;
                             if (pos < q.out_cap) {
                                 gptr(q.out_idx)[pos] = (u32)(e0 + 4u * (tid + 1024u * j) + c);
-                                gptr(q.out_val)[pos] = vp[i];
+                                if (q.val_bf16) { // upper 16 bits, rounded to nearest even
+                                    const u32 b = __float_as_uint(vp[i]);
+                                    ((GLOBAL_AS u16 *)gptr(q.out_val))[pos] = (u16)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+                                } else {
+                                    gptr(q.out_val)[pos] = vp[i];
+                                }
                             }
                             r++;
                         }

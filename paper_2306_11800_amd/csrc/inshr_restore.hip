@@ -135,7 +135,9 @@ __global__ __launch_bounds__(256) void k_dequant_protected(const RDesc *__restri
             ok = ((u32)x & mask) == 1u;
         }
         if (ok)
-            gptr(d.dst)[i] = gptr(d.out_val)[j];
+            gptr(d.dst)[i] = d.val_bf16
+                                 ? __uint_as_float((u32)((const GLOBAL_AS u16 *)gptr(d.out_val))[j] << 16)
+                                 : gptr(d.out_val)[j];
         else
             atomicOr(flags, RF_LIST);
     }

@@ -31,7 +31,10 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
     TState *st = B.ts + t;
     const u64 n = td[t].n, n_neg = st->n_neg;
     const u32 n_pairs = gd->n_pairs, n_p = gd->n_p;
-    const u32 n_e = n_pairs * EPP;
+    // edge items: pair q has the boundaries q * EPP + 0 .. n_bnd - 1 and the class edges
+    // q * EPP + NBT .. NBT + 3; the list holds n_e = n_pairs * (n_bnd + 4) of them
+    const u32 n_bnd = gd->n_bnd, epp = n_bnd + 4u;
+    const u32 n_e = n_pairs * epp;
     const u32 nb2 = st->nb2, zbin = st->zbin;
     const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
     const u32 *trank = B.tgt_rank + (size_t)t * TGT_STRIDE;
@@ -51,16 +54,17 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
     for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
         u64 v = ~0ull;
         if (i < n_e) {
-            const u32 q = i / EPP, e = i % EPP;
+            const u32 q = i / epp, r = i % epp;
+            const u32 e = r < n_bnd ? r : (u32)NBT + (r - n_bnd);
             u64 below, is_boundary, corder = 0ull;
-            if (e < (u32)NB8) {
-                below = trank[q * NB8 + e];
+            if (e < (u32)NBT) {
+                below = trank[q * NBT + e];
                 is_boundary = 1ull;
             } else {
-                const u32 me = q * 4u + (e - NB8), key = ckey[me];
+                const u32 me = q * 4u + (e - NBT), key = ckey[me];
                 for (u32 j = 0; j < n_pairs * 4u; j++)
                     corder += (ckey[j] < key || (ckey[j] == key && j < me)) ? 1ull : 0ull;
-                switch (e - NB8) {
+                switch (e - NBT) {
                 case 0: below = st->pair_An[q]; break;                 // keys < first quantized negative
                 case 1: below = n_neg - st->pair_Pn[q]; break;         // keys < first pruned
                 case 2: below = n_neg + st->pair_Pp[q]; break;         // keys < first quantized positive
@@ -68,7 +72,7 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
                 }
                 is_boundary = 0ull;
             }
-            v = (((below << 1) | is_boundary) << 18) | (corder << 12) | (u64)i;
+            v = (((below << 1) | is_boundary) << 18) | (corder << 12) | (u64)(q * EPP + e);
         }
         srt[i] = v;
     }
@@ -101,14 +105,14 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
             const u32 item = (u32)(srt[pos] & 4095ull);
             const u32 q = item / EPP, e = item % EPP;
             u32 key = 0u; // a boundary's key is found later, from the gathered keys
-            if (e < (u32)NB8) {
-                bin = tb[q * NB8 + e];
+            if (e < (u32)NBT) {
+                bin = tb[q * NBT + e];
                 if (bin == RESOLVED) {
                     bin = zbin;
                     key = ZERO_KEY;
                 }
             } else {
-                key = class_edge_key(e - NB8, st->thr_mag[gd->pair_p[q]], st->thr_mag[n_p + gd->pair_o[q]]);
+                key = class_edge_key(e - NBT, st->thr_mag[gd->pair_p[q]], st->thr_mag[n_p + gd->pair_o[q]]);
                 bin = l2_bin(key, tab[key >> COARSE_SHIFT]);
             }
             E[pos] = key;
@@ -255,9 +259,9 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         const u32 q = w >> 8, k = w & 255u;
         const u16 *e = pe + q * EIDX_STRIDE;
         // bin k covers slots idx(lo)+1 .. idx(hi) without those of the pruned gap (g_lo, g_hi]
-        const u32 i_lo = (k == 0) ? e[NB8 + 0] : e[k - 1u];
-        const u32 i_hi = (k == 255u) ? e[NB8 + 3] : e[k];
-        const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
+        const u32 i_lo = (k == 0) ? e[NBT + 0] : e[k - 1u];
+        const u32 i_hi = (k == 255u) ? e[NBT + 3] : e[k];
+        const u32 g_lo = e[NBT + 1], g_hi = e[NBT + 2];
         double sk = 0.0;
         for (u32 i = i_lo + 1u; i <= min(i_hi, g_lo); i++) sk += V[i];
         for (u32 i = max(i_lo, g_hi) + 1u; i <= i_hi; i++) sk += V[i];
@@ -270,26 +274,31 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     // one work item per (configuration, bin)
     for (u32 w = tid; w < n_cfg * (u32)CB_STRIDE; w += BLOCK) {
         const u32 g = w / CB_STRIDE, k = w % CB_STRIDE;
-        const u32 bits = gd->cfg_bits[g], K = 1u << bits;
+        const u32 K = gd->cfg_K[g];
         if (k >= K) continue;
         const u32 q = gd->cfg_pair[g];
         const u16 *e = pe + q * EIDX_STRIDE;
-        const u32 sh = 8u - bits;
         // bin k covers keys [lo, hi): slots idx(lo)+1 .. idx(hi); the pruned gap [E2, E3) is left out
-        const u32 i_lo = (k == 0) ? e[NB8 + 0] : e[(k << sh) - 1u];
-        const u32 i_hi = (k == K - 1u) ? e[NB8 + 3] : e[((k + 1u) << sh) - 1u];
-        const u32 g_lo = e[NB8 + 1], g_hi = e[NB8 + 2];
+        const u32 i_lo = (k == 0) ? e[NBT + 0] : e[bnd_index(K, k)];
+        const u32 i_hi = (k == K - 1u) ? e[NBT + 3] : e[bnd_index(K, k + 1u)];
+        const u32 g_lo = e[NBT + 1], g_hi = e[NBT + 2];
         // slots i_lo+1 .. i_hi without those of the pruned gap (g_lo, g_hi]
         u64 nk = C[i_hi] - C[i_lo];
         const u32 a = max(i_lo, g_lo), b = min(i_hi, g_hi);
         if (a < b) nk -= C[b] - C[a];
         double sk = 0.0;
-        for (u32 j = 0; j < (1u << sh); j++) sk += S8[q * 256u + (k << sh) + j];
+        if ((K & (K - 1u)) == 0u) { // a union of 8-bit bins
+            const u32 per = 256u / K;
+            for (u32 j = 0; j < per; j++) sk += S8[q * 256u + k * per + j];
+        } else { // 3, 6 or 12 bins: slot by slot
+            for (u32 i = i_lo + 1u; i <= min(i_hi, g_lo); i++) sk += V[i];
+            for (u32 i = max(i_lo, g_hi) + 1u; i <= i_hi; i++) sk += V[i];
+        }
         float c;
         if (nk)
             c = (float)(sk / (double)nk);
         else
-            c = float_of_key(tk[q * NB8 + (((k == 0 ? 1u : k) << sh) - 1u)]);
+            c = float_of_key(tk[q * NBT + bnd_index(K, k == 0 ? 1u : k)]);
         cb[g * CB_STRIDE + k] = c;
         const double cd = (double)c;
         bt[g * CB_STRIDE + k] = 2.0 * cd * sk - (double)nk * cd * cd;
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     __shared__ double s_sse[MAX_CFG];
     __shared__ u64 s_cost[MAX_CFG];
     for (u32 g = tid; g < n_cfg; g += BLOCK) {
-        const u32 bits = gd->cfg_bits[g], K = 1u << bits, q = gd->cfg_pair[g];
+        const u32 K = gd->cfg_K[g], q = gd->cfg_pair[g];
         double acc = 0.0;
         for (u32 k = 0; k < K; k++) acc += bt[g * CB_STRIDE + k];
         double sse = s_sumsq - s_qout[gd->pair_o[q]] - acc;
@@ -310,7 +319,9 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
         r.n_pruned = st->pair_Pn[q] + st->pair_Pp[q];
         r.n_outlier = st->pair_An[q] + st->pair_Ap[q];
         r.n_kept = st->pair_M[q];
-        r.cost_bits = r.n_kept * (u64)bits + 32ull * r.n_outlier + 32ull * (u64)K;
+        // payload model: log2 K bits per quantized value (in units of 2^-16, rounded up), 32 per
+        // protected value and per centre
+        r.cost_bits = ((r.n_kept * (u64)gd->cfg_l16[g] + 65535ull) >> 16) + 32ull * r.n_outlier + 32ull * (u64)K;
         sc[g] = r;
         s_sse[g] = sse;
         s_cost[g] = r.cost_bits;

@@ -127,10 +127,10 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
         // pool that belongs to this wave alone: the workgroup's region starts at its first element
         // of the tensor, and a wave's share of it is as large as the wave's share of the elements
         // (1024 per tile), so no counter is shared.
-        const u64 unit_start = (tile - d.tile0) * (u64)TILE;
-        const u32 sub = (u32)(stop - tile) * (u32)(TILE / (BLOCK / 64));
-        GLOBAL_AS u32 *gdst = gptr(B.pool) + d.pool_thr + unit_start + (u64)wave * sub;
+        const u32 capw = B.unit_capw[fu];
+        GLOBAL_AS u32 *gdst = gptr(B.pool) + B.unit_off[fu] + (u64)wave * capw;
         u32 gathered = 0u; // wave-uniform
+        bool overflow = false;
         if (LEVEL == 2) {
             for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
         }
@@ -151,6 +151,13 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
                 else
                     hist1_tile<false>(v, mask, h, q_tot, c_zero);
             } else {
+                // A share that cannot take a whole tile any more is too small: the tile's keys go over
+                // the last ones (every share holds at least one tile), and the overflow is reported;
+                // the host then repeats the search with larger pools.
+                if (gathered + (u32)(TILE / (BLOCK / 64)) > capw) {
+                    overflow = true;
+                    gathered = capw - (u32)(TILE / (BLOCK / 64));
+                }
                 if (sampled) {
                     if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
                         hist2_tile<true, true>(v, mask, h, T, gdst, gathered, q_tot, c_zero);
@@ -175,10 +182,9 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const TDesc *__restrict__ td, in
             }
         }
         if (LEVEL == 2) {
-            if (lane == 0u) B.unit_thr[(size_t)fu * 16 + wave] = gathered;
-            if (tid == 0) {
-                B.unit_start[fu] = unit_start;
-                B.unit_sub[fu] = sub;
+            if (lane == 0u) {
+                B.unit_thr[(size_t)fu * 16 + wave] = gathered;
+                if (overflow) atomicOr(&st->pool_overflow, 1u);
             }
         }
         // sum of squares and zeros: from sweep 1, or from sweep 2 when sweep 1 was sampled (the
@@ -639,7 +645,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td
     __syncthreads();
     if (tid < nb) which[st->bucket_magbin[tid]] = (unsigned char)(tid + 1u);
     __syncthreads();
-    const u32 *list = B.pool + td[t].pool_thr + B.unit_start[fu] + (u64)wave * B.unit_sub[fu];
+    const u32 *list = B.pool + B.unit_off[fu] + (u64)wave * B.unit_capw[fu];
     // smallest / largest magnitude among the gathered keys (first pass): for a tensor whose first
     // sweep was sampled the windows of the ranks 0 and n - 1 were gathered, so these are the
     // tensor's own extremes (exact zeros are never gathered: TState::n_zero tells of them)
@@ -822,15 +828,18 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
     }
     for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = 0u;
     __syncthreads();
-    const u32 TG = n_pairs * NB8;
+    const u32 n_bnd = gd->n_bnd;
+    const u32 TG = n_pairs * n_bnd;
     u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
     u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
     u32 *tk = B.tgt_key + (size_t)t * TGT_STRIDE;
     u32 *trank = B.tgt_rank + (size_t)t * TGT_STRIDE;
-    for (u32 i = tid; i < TG; i += BLOCK) {
-        const u32 q = i / NB8, j = i % NB8 + 1u;
+    for (u32 w = tid; w < TG; w += BLOCK) {
+        const u32 q = w / n_bnd, i = q * (u32)NBT + w % n_bnd; // boundary w % n_bnd of pair q
+        u32 num, den;
+        bnd_fraction(w % n_bnd, num, den);
         const u64 M = sM[q];
-        const u64 k = (u64)j * M / 256ull;
+        const u64 k = (u64)num * M / (u64)den;
         const u64 r = (k < sMn[q]) ? sAn[q] + k : sAn[q] + sPP[q] + k;
         trank[i] = (u32)r;
         // first index in [0, nb2] with cum[idx] > r
@@ -875,6 +884,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         cur[i] = binfo[i] ? (h2[i] - ((i == zbin) ? (u32)n_zero : 0u)) : 0u;
     __syncthreads();
     const u32 ctot = block_excl_scan(cur, cur, (int)nb2, tmp);
+    if (tid == 0 && (u64)ctot > d.pool_len) atomicOr(&st->pool_overflow, 2u); // no room for the keys in group order
     // groups: runs of active bins of about 2^gshift gathered keys; at most MAX_GROUPS per tensor
     u32 gshift = GROUP_SHIFT;
     while ((ctot >> gshift) >= (u32)MAX_GROUPS) gshift++;
@@ -906,7 +916,8 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
     // per target: the key range of its bin
     u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
     u32 *thi = B.tgt_khi + (size_t)t * TGT_STRIDE;
-    for (u32 i = tid; i < TG; i += BLOCK) {
+    for (u32 w = tid; w < TG; w += BLOCK) {
+        const u32 i = (w / n_bnd) * (u32)NBT + w % n_bnd;
         const u32 bin = tb[i];
         if (bin == RESOLVED) continue;
         // last 12-bit prefix whose first bin is <= bin
@@ -928,6 +939,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         st->n_groups = n_groups;
         st->gshift = gshift;
     }
+    // (the pairs' boundaries lie NBT apart; those a grid does not use are never read)
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1031,10 +1043,11 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         // keys of active bins go, in arrival order, to a region of the pool that belongs to this
         // wave alone (the workgroup's region starts at its first element of the tensor; a wave's
         // share of it is as large as its share of the elements)
-        const u64 unit_start = (tile - d.tile0) * (u64)TILE;
-        const u32 sub = (u32)(stop - tile) * (u32)(TILE / (BLOCK / 64));
-        GLOBAL_AS u32 *gdst = gptr(B.pool) + d.pool_cand + unit_start + (u64)wave * sub;
+        const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
+        const u32 capw = B.unit_capw[fu];
+        GLOBAL_AS u32 *gdst = gptr(B.pool2) + B.unit_off[fu] + (u64)wave * capw;
         u32 gathered = 0u; // wave-uniform
+        bool overflow = false;
         double q_out[MAX_FRAC];
 #pragma unroll
         for (int o = 0; o < MAX_FRAC; o++) q_out[o] = 0.0;
@@ -1047,6 +1060,10 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
             u32 oc[MAX_FRAC]; // protected values of this wave in this tile (wave-uniform)
 #pragma unroll
             for (int o = 0; o < MAX_FRAC; o++) oc[o] = 0u;
+            if (gathered + (u32)(TILE / (BLOCK / 64)) > capw) { // (as in sweep 2: share too small)
+                overflow = true;
+                gathered = capw - (u32)(TILE / (BLOCK / 64));
+            }
             if (cnt == (u32)TILE) // the same for every lane: the tile code uses ballots
                 gather_tile<true>(v, mask, T, SEG, sx, gdst, gathered, tau_o_min, s_tau_o, n_o, q_out, oc);
             else
@@ -1059,8 +1076,10 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         }
         __syncthreads();
         // flush partial sums of this (workgroup, tensor) unit in a fixed order
-        const u32 fu = wg_fu0[blockIdx.x] + (u32)(t - t_first);
-        if (lane == 0u) B.unit_cand[(size_t)fu * 16 + wave] = gathered;
+        if (lane == 0u) {
+            B.unit_cand[(size_t)fu * 16 + wave] = gathered;
+            if (overflow) atomicOr(&st->pool_overflow, 4u);
+        }
         double *gs = B.mom_sx + (size_t)fu * MAX_EDGES;
         for (u32 i = tid; i < n_slots; i += BLOCK) gs[i] = sx[i];
         double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
@@ -1105,10 +1124,10 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
     const u32 c = B.unit_cand[(size_t)fu * 16 + wave];
     u32 cmax = 0u;
     for (int w = 0; w < BLOCK / 64; w++) cmax = max(cmax, B.unit_cand[(size_t)fu * 16 + w]);
-    if (cmax == 0u) return;
+    if (cmax == 0u || st->pool_overflow) return; // (an overflow: the search is repeated with larger pools)
     const u32 nb2 = st->nb2, G = st->n_groups;
-    const u32 *src = B.pool + d.pool_cand + B.unit_start[fu] + (u64)wave * B.unit_sub[fu];
-    u32 *dst = B.pool2 + d.pool_thr; // the tensor's second region, one key per slot in bin-group order
+    const u32 *src = B.pool2 + B.unit_off[fu] + (u64)wave * B.unit_capw[fu];
+    u32 *dst = B.pool + d.pool_grp; // the tensor's span of the first pool, one key per slot in bin-group order
     const u32 *goff = B.grp_off + (size_t)t * MAX_GROUPS;
     u32 *gcur = B.grp_cur + (size_t)t * MAX_GROUPS;
     for (int i = tid; i < COARSE; i += BLOCK) T[i] = B.table2[(size_t)t * COARSE + i];
@@ -1296,7 +1315,7 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
     auto prefetch = [&](u32 idx2) {
         nxt = group_head(B, grp_list, idx2);
         if (nxt.n && nxt.n <= (u32)BUCKET_CAP) {
-            const GLOBAL_AS u32 *src2 = gptr(B.pool2) + td[nxt.t].pool_thr + nxt.goff;
+            const GLOBAL_AS u32 *src2 = gptr(B.pool) + td[nxt.t].pool_grp + nxt.goff;
 #pragma unroll
             for (int r = 0; r < SORT_ROWS; r++) {
                 const u32 i = tid + r * BB;
@@ -1339,7 +1358,7 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
         if (idx + gridDim.x < total) prefetch(idx + gridDim.x);
         if (elo >= ehi) continue; // no bin falls into this window of the order
         const u32 n_e = ehi - elo;
-        const u32 *src = B.pool2 + td[t].pool_thr + goff;
+        const u32 *src = B.pool + td[t].pool_grp + goff;
         const u32 *tb = B.tgt_bin + (size_t)t * TGT_STRIDE;
         const u32 *tr = B.tgt_res + (size_t)t * TGT_STRIDE;
         const u32 *tlo = B.tgt_klo + (size_t)t * TGT_STRIDE;
@@ -1353,6 +1372,28 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
         u32 *from = bufA, *to = bufB;
         if (sorted && n) {
             __syncthreads();
+            if (ORDERED && (idx & 15u) == 0u) {
+                // Cross-check of the ordered ranking, one group in sixteen: every wave ranks the low
+                // digit of its first 64 keys with returning adds into its (cleared) counters and from
+                // ballots, and leaves the counters cleared.
+                u32 *wc0 = wcount + wave * 256u;
+                for (u32 i = lane; i < 256u; i += 64u) wc0[i] = 0u;
+                const u32 i = wave * 64u + lane;
+                const bool valid = i < n;
+                const u32 digit = valid ? (bufA[i] & 255u) : 0u;
+                u32 got = 0u;
+                if (valid) got = atomicAdd(&wc0[digit], 1u);
+                u64 peers = __ballot(valid);
+#pragma unroll
+                for (int b = 0; b < 8; b++) {
+                    const bool bit = (digit >> b) & 1u;
+                    const u64 m = __ballot(bit);
+                    peers &= bit ? m : ~m;
+                }
+                if (valid && got != (u32)__popcll(peers & ((1ull << lane) - 1ull)))
+                    atomicOr(&st->internal_err, 1024u);
+                __syncthreads(); // (the passes below clear all counters: not before every wave is done here)
+            }
             const u32 dbits = s_or ^ s_and; // bits in which the keys differ
             const u32 rows = (n + BB - 1u) / BB; // rows of 64 keys per wave
             const u32 chunk = rows * 64u;
@@ -1423,8 +1464,8 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                 const u32 item = eitem[elo + j];
                 const u32 q = item / EPP, w = item % EPP;
                 u32 key = ekey[elo + j]; // class edges are known beforehand
-                if (w < (u32)NB8) {
-                    const u32 i = q * NB8 + w;
+                if (w < (u32)NBT) {
+                    const u32 i = q * NBT + w;
                     const u32 bin = tb[i];
                     if (bin == RESOLVED) {
                         key = ZERO_KEY;
@@ -1464,8 +1505,8 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                 const u32 item = eitem[elo + j];
                 const u32 q = item / EPP, w = item % EPP;
                 u32 key = ekey[elo + j];
-                if (w < (u32)NB8) {
-                    const u32 i = q * NB8 + w;
+                if (w < (u32)NBT) {
+                    const u32 i = q * NBT + w;
                     const u32 bin = tb[i];
                     if (bin == RESOLVED) {
                         key = ZERO_KEY;
@@ -1582,7 +1623,7 @@ __global__ __launch_bounds__(256) void k_group_list(int nT, Bufs B, u32 *grp_lis
 {
     __shared__ u32 s_at;
     const int t = blockIdx.x;
-    const u32 G = B.ts[t].n_groups;
+    const u32 G = B.ts[t].pool_overflow ? 0u : B.ts[t].n_groups; // (overflow: nothing valid to sort)
     if (G == 0u) return;
     if (threadIdx.x == 0) s_at = atomicAdd(n_grp_total, G);
     __syncthreads();

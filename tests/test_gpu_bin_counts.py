@@ -1,0 +1,107 @@
+"""GPU parity with numbers of bins that are not powers of two (the search space of Sec. 5 lists
+4, 6, 8, 12, 16 and 32 bins): search over a grid that mixes them, quantize, delta between unequal
+counts, restore; everything against the CPU oracle, bit for bit (centres and errors 1e-6)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2306_11800_amd import synth
+from test_gpu_parity import check_delta, check_quantized, check_scores, dev, run_pipeline, u64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2306_11800_amd import api
+    c = api.Context(torch.device("cuda:0"))
+    yield c
+    c.close()
+
+
+def test_search_space_of_the_paper_on_a_ragged_batch(ctx):
+    rng = np.random.default_rng(61)
+    sizes = [5, 300, 4097, 70_001, 400_003]
+    prevs = [(0.02 * rng.standard_t(4, n)).astype(np.float32) for n in sizes]
+    prevs[2][::3] = 0.0          # a third exact zeros
+    curs = [(p + rng.normal(0, 1e-4, p.size)).astype(np.float32) for p in prevs]
+    grid = synth.grid_paper(prune=(0.0, 0.1, 0.2, 0.3, 0.5))   # 90 configurations, 15 pairs
+    assert len(grid) == 90
+    run_pipeline(ctx, prevs, curs, grid, synth.EPS_DEFAULT)
+    # a tight bound: nothing feasible, the most accurate configuration is chosen
+    run_pipeline(ctx, prevs[:3], curs[:3], grid, 1e-9, want_perm=False)
+
+
+def test_power_of_two_counts_equal_bits(ctx):
+    """bins = 2^b and bits = b are the same configuration."""
+    x = (0.02 * np.random.default_rng(62).standard_t(4, 123_457)).astype(np.float32)
+    t = [dev(x)]
+    for b in (1, 3, 8):
+        qa = ctx.quantize(t, [(b, 100000, 1000)])[0]
+        qb = ctx.quantize(t, [(0, 100000, 1000, 1 << b)])[0]
+        assert qa.sym_bits == qb.sym_bits == b + 1 and qa.K == qb.K == 1 << b
+        assert torch.equal(qa.packed, qb.packed) and torch.equal(qa.codebook, qb.codebook)
+
+
+@pytest.mark.parametrize("K", [3, 6, 12])
+def test_stand_alone_quantize_with_a_bin_count(ctx, K):
+    rng = np.random.default_rng(63 + K)
+    for n in (1, 2, 11, 50_000, 1_000_003):
+        x = (0.02 * rng.standard_t(4, n)).astype(np.float32)
+        cfg = (0, 200000, 1000, K)
+        q = ctx.quantize([dev(x)], [cfg])[0]
+        check_quantized(q, x, cfg)
+
+
+def test_delta_and_restore_between_unequal_counts(ctx):
+    prev, cur = synth.config0(seed=64, n=1_000_003)
+    tp, tc = [dev(prev)], [dev(cur)]
+    for cp, cc in (((0, 100000, 1000, 6), (0, 100000, 1000, 12)), ((0, 0, 0, 12), (2, 0, 0)),
+                   ((8, 200000, 1000), (0, 200000, 1000, 3))):
+        qp, qc = ctx.quantize(tp, [cp]), ctx.quantize(tc, [cc])
+        rp, rc = check_quantized(qp[0], prev, cp), check_quantized(qc[0], cur, cc)
+        d = ctx.delta(qp, qc, want_perm=True)
+        ctx.sync()
+        check_delta(d[0], rp, cp[0], rc, cc[0], True)
+        rec = ctx.reconstruct(qp, d, [cc[0]], bins_cur=[rc["K"]])[0]
+        assert torch.equal(rec, qc[0].packed)
+        xh = ctx.dequantize(qc)[0].cpu().numpy()
+        want = ref.dequantize(rc["sym"], 0, rc["codebook"], rc["outlier_idx"], rc["outlier_val"], K=rc["K"])
+        assert np.array_equal(xh.view(np.uint32), want.view(np.uint32))
+
+
+def test_unsupported_counts_are_rejected(ctx):
+    from paper_2306_11800_amd import api
+    x = dev(np.ones(100, np.float32))
+    for K in (1, 5, 24, 257):
+        with pytest.raises(api.InshrError) as e:
+            ctx.quantize([x], [(0, 0, 0, K)])
+        assert e.value.code == -2
+
+
+def test_protected_values_stored_as_bfloat16(ctx):
+    """Sec. 4.2 stores protected values in bfloat16: same symbols, centres and positions as with
+    fp32 storage; the stored values are the oracle's round-to-nearest-even of the originals, and
+    decoding returns them widened (everything else decodes as before)."""
+    rng = np.random.default_rng(67)
+    for n, cfg in ((9, (3, 0, 300000)), (50_001, (4, 100000, 20000)), (1_000_003, (0, 200000, 1000, 12))):
+        x = (0.02 * rng.standard_t(4, n)).astype(np.float32)
+        x[: min(n, 7)] = [1e-40, -3.0000001, 65504.0, -1e30, 0.1, 2.0 ** -126, 1.00390625][: min(n, 7)]
+        t = [dev(x)]
+        q32 = ctx.quantize(t, [cfg])[0]
+        r = check_quantized(q32, x, cfg)
+        q16 = ctx.quantize(t, [cfg], protect_bf16=True)[0]
+        assert q16.bf16 and torch.equal(q16.packed, q32.packed) and torch.equal(q16.codebook, q32.codebook)
+        assert torch.equal(q16.outlier_idx, q32.outlier_idx) and q16.n_outlier == r["n_outlier"] > 0
+        want16 = ref.bf16_round(r["outlier_val"])
+        got16 = q16.outlier_val.float().cpu().numpy()
+        assert np.array_equal(got16.view(np.uint32), want16.view(np.uint32))
+        assert np.all((want16.view(np.uint32) & 0xFFFF) == 0)
+        xh = ctx.dequantize([q16])[0].cpu().numpy()
+        want = ref.dequantize(r["sym"], cfg[0], r["codebook"], r["outlier_idx"], want16, K=r["K"])
+        assert np.array_equal(xh.view(np.uint32), want.view(np.uint32))
+        # fp32 storage is bit-exact on the same positions
+        xf = ctx.dequantize([q32])[0].cpu().numpy()
+        idx = r["outlier_idx"].astype(np.int64)
+        assert np.array_equal(xf[idx].view(np.uint32), x[idx].view(np.uint32))

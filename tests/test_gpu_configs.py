@@ -3,6 +3,7 @@ recipes and grids, leading dimensions shrunk so that the CPU oracle finishes in 
 ResNet-50-shaped weights with Adam state, BERT-base-shaped tensors whose word embedding moves on a
 Zipf-drawn 5 % of its rows, and a GPT-2-medium-shaped five-step sequence with four deltas."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -66,3 +67,38 @@ def test_gpt2_shaped_five_steps_four_deltas(ctx):
             for i, d in enumerate(ds):
                 check_delta(d, r_prev[i], c_prev[i][0], refs[i], chosen[i][0], False)
         q_prev, r_prev, c_prev = qs, refs, chosen
+
+
+def test_resnet50_shaped_full_size(ctx):
+    """Configuration 1 at its full size (483 tensors, 76.7 M values, the 24-configuration grid),
+    searched, quantized and delta-encoded as one batch; the oracle runs one tensor per thread."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import ref
+    items = list(synth.resnet50_checkpoint())
+    prevs = [p for _, p, _ in items]
+    curs = [c for _, _, c in items]
+    assert len(items) == 483 and sum(p.size for p in prevs) > 76_000_000
+    grid, eps = synth.grid_small(), synth.EPS_DEFAULT
+    ref.lib()
+    work = min(16, os.cpu_count() or 1)
+    sides = []
+    for xs in (prevs, curs):
+        ts = [dev(x) for x in xs]
+        best, feas, scores = ctx.search(ts, grid, eps)
+        with ThreadPoolExecutor(work) as ex:
+            rsearch = list(ex.map(lambda x: ref.search(x, grid, eps), xs))
+        chosen = [grid[check_scores(scores, len(grid), i, x, grid, eps, best[i], feas[i], given=rsearch[i])]
+                  for i, x in enumerate(xs)]
+        qs = ctx.quantize(ts, chosen, reuse_search=True)
+        with ThreadPoolExecutor(work) as ex:
+            rq = list(ex.map(lambda xc: ref.quantize(xc[0], xc[1]), zip(xs, chosen)))
+        refs = [check_quantized(q, x, c, given=r) for q, x, c, r in zip(qs, xs, chosen, rq)]
+        sides.append((qs, refs, chosen))
+        del ts
+    (qp, rp, cp), (qc, rc, cc) = sides
+    ds = ctx.delta(qp, qc)
+    ctx.sync()
+    with ThreadPoolExecutor(work) as ex:
+        rd = list(ex.map(lambda k: ref.delta(rp[k]["sym"], cp[k][0], rc[k]["sym"], cc[k][0]), range(len(ds))))
+    for i, d in enumerate(ds):
+        check_delta(d, rp[i], cp[i][0], rc[i], cc[i][0], False, given=rd[i])

@@ -297,3 +297,61 @@ def test_other_bench_shapes(ctx, n):
         assert torch.equal(q.boundaries[:K - 1].view(torch.int32), r["t"].view(torch.int32))
         got = unpack(q.packed, n, cfg[0] + 1)
         assert torch.equal(got, r["sym"]), int((got != r["sym"]).sum())
+
+
+def test_full_grid_score_table_on_a_sampled_tensor(ctx):
+    """All 105 rows of the score table, and the choice, on one 4096 x 4096 tensor of the bench's
+    recipe (16 Mi values: the first sweep of the search is sampled, as in the bench).  Every
+    configuration is computed on its own from the definitions with torch's library routines:
+    thresholds = order statistics of |x|, boundaries = order statistics of the quantized values at
+    floor(j M / K), bins by bucketize, centres = fp32 of the fp64 mean, squared error in fp64."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(82)
+    n = 4096 * 4096
+    z = torch.randn(4, n, dtype=torch.float32, device=dev, generator=g)
+    x = 0.015 * z[0] / torch.sqrt((z[1] * z[1] + z[2] * z[2] + z[3] * z[3]) / 3.0)
+    del z
+    hot = torch.randperm(4096, device=dev, generator=g)[:4]
+    x.view(-1, 4096)[:, hot] *= 20.0
+    x[x == 0] = 1e-6
+    grid, eps = synth.grid_full(), synth.EPS_DEFAULT
+    best, feas, scores = ctx.search([x], grid, eps, want_scores=True)
+    A = torch.sort(x.abs()).values
+    xd = x.double()
+    sumsq = float((xd * xd).sum())
+    mag = x.abs()
+    rows, border = [], False
+    kept_sorted = {}  # (prune, protect) -> its classes and sorted quantized values (data, shared by the bit widths)
+    for gi, (bits, p_ppm, o_ppm) in enumerate(grid):
+        K = 1 << bits
+        if (p_ppm, o_ppm) not in kept_sorted:
+            tau_p, tau_o = A[n * p_ppm // 1_000_000], A[n - 1 - n * o_ppm // 1_000_000]
+            pruned, prot = mag < tau_p, mag > tau_o
+            xk = x[~(pruned | prot)]
+            kept_sorted[(p_ppm, o_ppm)] = (float((xd[pruned] ** 2).sum()), int(prot.sum()), xk, torch.sort(xk).values)
+            del pruned, prot
+        sq_pruned, n_prot, xk, Y = kept_sorted[(p_ppm, o_ppm)]
+        M = Y.numel()
+        j = torch.arange(1, K, device=dev, dtype=torch.int64)
+        t = Y[(j * M) // K]
+        b = torch.bucketize(xk, t, right=True)
+        cnt = torch.bincount(b, minlength=K).double()
+        sx = torch.bincount(b, weights=xk.double(), minlength=K)
+        c = (sx / cnt.clamp(min=1)).float()
+        sse = sq_pruned + float(((xk.double() - c.double()[b]) ** 2).sum())
+        cost = M * bits + 32 * n_prot + 32 * K
+        s = scores[gi]
+        assert (s.n_pruned, s.n_outlier, s.n_kept, s.cost_bits) == (n - M - n_prot, n_prot, M, cost), grid[gi]
+        assert abs(s.sumsq - sumsq) <= 1e-9 * sumsq
+        assert abs(s.sse - sse) <= 1e-6 * sse + 1e-12 * sumsq, (grid[gi], s.sse, sse)
+        rows.append((sse, cost))
+        border = border or abs(sse / sumsq - eps) <= 4e-6 * eps
+        del b
+    feasible = [i for i, (sse, cost) in enumerate(rows) if sse / sumsq <= eps]
+    if feasible:
+        want = min(feasible, key=lambda i: (rows[i][1], i))
+    else:
+        want = min(range(len(rows)), key=lambda i: (rows[i][0], i))
+    if not border:
+        assert (best[0], feas[0]) == (want, 1 if feasible else 0)

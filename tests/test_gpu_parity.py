@@ -36,8 +36,9 @@ def u32(t):
     return t.cpu().numpy().view(np.uint32)
 
 
-def check_scores(gscores, nC, ti, x, grid, eps, gbest, gfeas):
-    rbest, rfeas, rsc = ref.search(x, grid, eps)
+def check_scores(gscores, nC, ti, x, grid, eps, gbest, gfeas, given=None):
+    # given: what ref.search returned for this tensor, when the caller computed it beforehand
+    rbest, rfeas, rsc = given if given is not None else ref.search(x, grid, eps)
     border = False
     for g in range(nC):
         s, r = gscores[ti * nC + g], rsc[g]
@@ -52,18 +53,17 @@ def check_scores(gscores, nC, ti, x, grid, eps, gbest, gfeas):
     return rbest
 
 
-def check_quantized(q, x, cfg):
-    r = ref.quantize(x, cfg)
-    bits = cfg[0]
-    assert q.sym_bits == bits + 1
+def check_quantized(q, x, cfg, given=None):
+    r = given if given is not None else ref.quantize(x, cfg)
+    assert q.sym_bits == r["sym_bits"] and q.K == r["K"]
     assert (q.n_pruned, q.n_outlier, q.n_kept) == (r["n_pruned"], r["n_outlier"], r["n_kept"])
     assert np.float32(q.tau_prune).view(np.uint32) == r["tau_prune_bits"]
     assert np.float32(q.tau_outlier).view(np.uint32) == r["tau_outlier_bits"]
     assert np.array_equal(u32(q.boundaries), r["boundaries"].view(np.uint32)), cfg
-    want = ref.pack(r["sym"], bits + 1)
+    want = ref.pack(r["sym"], r["sym_bits"])
     got = u64(q.packed)
     if not np.array_equal(got, want):
-        gs = ref.unpack(got, x.size, bits + 1)
+        gs = ref.unpack(got, x.size, r["sym_bits"])
         bad = np.nonzero(gs != r["sym"])[0]
         raise AssertionError(f"symbols differ at {bad[:10]} ({bad.size} of {x.size}) cfg={cfg}: "
                              f"{gs[bad[:10]]} vs {r['sym'][bad[:10]]}")
@@ -74,8 +74,9 @@ def check_quantized(q, x, cfg):
     return r
 
 
-def check_delta(d, rp, bp, rc, bc, want_perm):
-    rd = ref.delta(rp["sym"], bp, rc["sym"], bc)
+def check_delta(d, rp, bp, rc, bc, want_perm, given=None):
+    # (bp, bc: bits of the two sides; the numbers of bins come with the references)
+    rd = given if given is not None else ref.delta(rp["sym"], bp, rc["sym"], bc, K_prev=rp["K"], K_cur=rc["K"])
     assert d.delta_bits == rd["delta_bits"]
     assert np.array_equal(u64(d.group_off), rd["group_off"])
     want = ref.pack(rd["stream"], rd["delta_bits"])
@@ -276,6 +277,7 @@ def test_without_lane_ordered_lds_atomics():
         c = api.Context(torch.device("cuda:0"))
     finally:
         del os.environ["INSHR_NO_LDS_ORDER"]
+    assert c.lds_ordered is False
     rng = np.random.default_rng(12)
     prev, cur = synth.config0(seed=3, n=250_007)
     few = rng.choice(np.array([-0.5, 0.1, 0.7, 0.0, 3.0], np.float32), 30_000)
@@ -327,3 +329,109 @@ def test_reused_batches_give_the_same_bytes(ctx):
             words = (da.n * da.delta_bits + 63) // 64
             assert torch.equal(da.packed[:words], db.packed[:words])
             assert torch.equal(da.group_off, db.group_off)
+
+
+def test_group_offsets_follow_a_prev_that_changes_bits(ctx):
+    """delta(..., out=) after the previous codes were quantized again in place with other bits: the
+    group offsets have (1 << bits) + 3 entries, and their buffer has room for any bits."""
+    from paper_2306_11800_amd import api
+    prev, cur = synth.config0(seed=31, n=90_001)
+    tp, tc = [dev(prev)], [dev(cur)]
+    qp = ctx.quantize(tp, [(8, 0, 1000)])
+    qc = ctx.quantize(tc, [(3, 0, 1000)])
+    r3, r8, rc = ref.quantize(prev, (3, 0, 1000)), ref.quantize(prev, (8, 0, 1000)), ref.quantize(cur, (3, 0, 1000))
+    d = ctx.delta(qp, qc)                           # stream sized for 9-bit deltas
+    ctx.sync()
+    check_delta(d[0], r8, 8, rc, 3, False)
+    for bits, r in ((3, r3), (8, r8), (3, r3)):
+        qp = ctx.quantize(tp, [(bits, 0, 1000)], out=qp)  # the same list, other symbols
+        d = ctx.delta(qp, qc, out=d)
+        ctx.sync()
+        assert d[0].group_off.numel() == (1 << bits) + 3
+        words = (prev.size * d[0].delta_bits + 63) // 64  # (the stream's buffer keeps its first size)
+        view = api.Delta(d[0].n, d[0].delta_bits, d[0].packed[:words], d[0].group_off, None)
+        check_delta(view, r, bits, rc, 3, False)
+
+
+def test_stated_group_offset_capacity_is_checked(ctx):
+    import ctypes as C
+    from paper_2306_11800_amd import api
+    prev, cur = synth.config0(seed=32, n=10_000)
+    qp = ctx.quantize([dev(prev)], [(8, 0, 0)])
+    qc = ctx.quantize([dev(cur)], [(8, 0, 0)])
+    pa = (api.CCodes * 1)(api.CCodes(qp[0]._ptrs[0], 9, 8, 0, 10_000))
+    ca = (api.CCodes * 1)(api.CCodes(qc[0]._ptrs[0], 9, 8, 0, 10_000))
+    out = torch.empty(2000, dtype=torch.int64, device="cuda:0")
+    goff = torch.empty(259, dtype=torch.int64, device="cuda:0")
+    oa = (api.CDeltaOut * 1)()
+    oa[0].packed, oa[0].packed_words, oa[0].group_off = out.data_ptr(), out.numel(), goff.data_ptr()
+    oa[0].group_off_entries = 19  # enough for 4 bits, not for 8
+    assert ctx.lib.inshr_delta(ctx.h, pa, None, ca, oa, 1) == -4
+    oa[0].group_off_entries = 259
+    assert ctx.lib.inshr_delta(ctx.h, pa, None, ca, oa, 1) == 0
+    ctx.sync()
+
+
+def test_foreign_permutation_is_reported_not_followed(ctx):
+    """A permutation that does not belong to the tensor (indices beyond n): the gather skips those
+    elements, and the next synchronisation returns INSHR_E_ARG."""
+    from paper_2306_11800_amd import api
+    prev, cur = synth.config0(seed=33, n=50_000)
+    qp = ctx.quantize([dev(prev)], [(4, 0, 0)])
+    qc = ctx.quantize([dev(cur)], [(4, 0, 0)])
+    d = ctx.delta(qp, qc, want_perm=True)
+    ctx.sync()
+    bad = d[0].perm.clone()
+    bad[123] = 50_000       # one past the end
+    bad[40_000] = -1        # 0xFFFFFFFF
+    ctx.delta(qp, qc, prev_perm=[bad])
+    with pytest.raises(api.InshrError) as e:
+        ctx.sync()
+    assert e.value.code == -1
+    ctx.sync()  # reported once
+    d2 = ctx.delta(qp, qc, prev_perm=[d[0].perm])  # the context works on
+    ctx.sync()
+    assert torch.equal(d2[0].packed, d[0].packed)
+
+
+def test_ranking_path_is_reported(ctx):
+    # returning LDS adds rank equal symbols on this device unless the environment forbids them
+    forced_off = any(os.environ.get(k, "0") not in ("", "0") for k in ("INSHR_NO_LDS_ORDER", "INSHR_DELTA_SLOTS"))
+    assert ctx.lds_ordered == (not forced_off)
+
+
+def test_scratch_limit_and_growing_gather_pools(ctx):
+    """The gather pools hold a fraction of the elements and grow when a search finds them too small:
+    a context that starts with the smallest pools (INSHR_POOL_WCAP=1) gives the same bytes as the
+    default one, within a scratch limit far below 8 bytes per element; a limit below the tables is
+    reported as INSHR_E_CAPACITY."""
+    from paper_2306_11800_amd import api
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(51)
+    n = 40_000_003
+    x = 0.02 * torch.randn(n, device="cuda:0", generator=g)
+    x[::7] = 0.25  # heavy duplicates: one bin gathers far more than an average share
+    small_x = dev((0.02 * np.random.default_rng(52).standard_t(4, 700)).astype(np.float32))
+    ts = [x, small_x]
+    grid = synth.grid_full()
+    best, feas, scores = ctx.search(ts, grid, synth.EPS_DEFAULT)
+    want = ctx.quantize(ts, [grid[b] for b in best], reuse_search=True)
+    os.environ["INSHR_POOL_WCAP"] = "1"
+    try:
+        small = api.Context(torch.device("cuda:0"), scratch_bytes=200 << 20)  # 8 B per element would be 320 MB
+    finally:
+        del os.environ["INSHR_POOL_WCAP"]
+    b2, f2, s2 = small.search(ts, grid, synth.EPS_DEFAULT)
+    assert (b2, f2) == (best, feas)
+    for i in range(len(ts) * len(grid)):
+        assert (s2[i].sse, s2[i].n_kept, s2[i].cost_bits) == (scores[i].sse, scores[i].n_kept, scores[i].cost_bits)
+    got = small.quantize(ts, [grid[b] for b in best], reuse_search=True)
+    for a, b in zip(got, want):
+        assert torch.equal(a.packed, b.packed) and torch.equal(a.codebook, b.codebook)
+        assert torch.equal(a.boundaries, b.boundaries) and torch.equal(a.outlier_idx, b.outlier_idx)
+    small.close()
+    tiny = api.Context(torch.device("cuda:0"), scratch_bytes=1 << 20)
+    with pytest.raises(api.InshrError) as e:
+        tiny.search(ts, grid, synth.EPS_DEFAULT)
+    assert e.value.code == -4
+    tiny.close()

@@ -44,7 +44,6 @@ def check(ctx, xs, cfgs, alpha, sigma, max_iter, seed):
     qs, info = ctx.quantize_sketch([dev(x) for x in xs], cfgs, uni, alpha=alpha, sigma=sigma,
                                    max_iter=max_iter)
     for i, (x, cfg) in enumerate(zip(xs, cfgs)):
-        print("sketch case", seed, i, x.size, cfg, alpha, sigma, flush=True)
         bits = cfg[0]
         K = 1 << bits
         base = ref.quantize(x, cfg)  # classes and thresholds of the exact-threshold oracle
@@ -127,7 +126,6 @@ def check_search(ctx, xs, cfgs, eps, alpha, sigma, max_iter, seed, reuse_grid=No
     qs, choices, info = ctx.search_sketch(dx, cfgs, uni, eps, alpha=alpha, sigma=sigma, max_iter=max_iter,
                                           reuse_search=reuse_grid is not None)
     for i, (x, cfg) in enumerate(zip(xs, cfgs)):
-        print("sketch search case", seed, i, x.size, cfg, eps, flush=True)
         base = ref.quantize(x, (8, cfg[1], cfg[2]))
         r = sk.search_bits(x, base["sym"], alpha, sigma, uni[i], max_iter, eps)
         ch = choices[i]

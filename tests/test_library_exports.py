@@ -25,17 +25,17 @@ def test_bounds_and_errors_without_gpu():
     import ctypes as C
     lib = api.load_library()
     words, cap = C.c_uint64(), C.c_uint64()
-    cfg = api.CConfig(4, 100000, 1000)
+    cfg = api.CConfig(4, 0, 100000, 1000)
     assert lib.inshr_quantize_bound(1000003, C.byref(cfg), C.byref(words), C.byref(cap)) == 0
     assert words.value == (1000003 * 5 + 63) // 64 and cap.value == 1000
-    bad = api.CConfig(9, 0, 0)
+    bad = api.CConfig(9, 0, 0, 0)
     assert lib.inshr_quantize_bound(10, C.byref(bad), C.byref(words), C.byref(cap)) == -2
-    bad = api.CConfig(4, 600000, 400000)
+    bad = api.CConfig(4, 0, 600000, 400000)
     assert lib.inshr_quantize_bound(10, C.byref(bad), C.byref(words), C.byref(cap)) == -2
-    p = api.CCodes(None, 5, 4, 100)
-    c = api.CCodes(None, 9, 8, 100)
+    p = api.CCodes(None, 5, 4, 0, 100)
+    c = api.CCodes(None, 9, 8, 0, 100)
     assert lib.inshr_delta_bound(C.byref(p), C.byref(c), C.byref(words)) == 0
     assert words.value == (100 * 9 + 63) // 64
-    c2 = api.CCodes(None, 9, 8, 101)
+    c2 = api.CCodes(None, 9, 8, 0, 101)
     assert lib.inshr_delta_bound(C.byref(p), C.byref(c2), C.byref(words)) == -5
     assert lib.inshr_strerror(-3).decode().lower().startswith("nan")
