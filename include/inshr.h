@@ -182,6 +182,24 @@ int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t 
 int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *prev_perm,
                 const inshr_codes *cur, inshr_delta_out *out, uint32_t n_tensors);
 
+/* inshr_delta for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same operation, arguments and outputs as inshr_delta without
+ * prev_perm, but the call allocates nothing on the device or through HIP (no hipMalloc, hipFree,
+ * pinned staging or memset node): the descriptors travel as kernel arguments and all scratch (chunk
+ * table, per-chunk symbol populations, flag word) is a static device array of about 2.2 MB that every
+ * GPU the library runs on holds until the process ends.  Limits: at most INSHR_STATIC_MAX_TENSORS
+ * tensors per call and INSHR_STATIC_MAX_ELEMENTS elements in total, each tensor rounded up to whole
+ * chunks of 786432 elements; beyond them the call returns INSHR_E_CAPACITY (inshr_last_device_error
+ * says which limit).  All calls on one GPU share the array, which keeps the last call's contents:
+ * calls that overlap in time on one GPU (two contexts, two streams) race; calls on one stream do
+ * not.  Only kernel launches are enqueued on the context's stream and the call returns at once;
+ * errors found by the kernels are reported by the next inshr_sync / inshr_delta, as for inshr_delta.
+ * Per-kernel timing (inshr_profile) must be off where event creation is not allowed. */
+#define INSHR_STATIC_MAX_TENSORS 16
+#define INSHR_STATIC_MAX_ELEMENTS (2048ull * 786432ull)
+int inshr_delta_static(inshr_ctx *ctx, const inshr_codes *prev, const inshr_codes *cur,
+                       inshr_delta_out *out, uint32_t n_tensors);
+
 /* ---- restore side ------------------------------------------------------------------------- */
 
 typedef struct {

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
-           "inshr_delta_bound", "inshr_delta", "inshr_dequantize", "inshr_reconstruct",
+           "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
 
@@ -142,6 +142,8 @@ def load_library() -> C.CDLL:
     lib.inshr_delta_bound.argtypes = [C.POINTER(CCodes), C.POINTER(CCodes), C.POINTER(C.c_uint64)]
     lib.inshr_delta.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(C.c_void_p),
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
+    lib.inshr_delta_static.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CCodes),
+                                       C.POINTER(CDeltaOut), C.c_uint32]
     lib.inshr_dequantize.argtypes = [C.c_void_p, C.POINTER(CDequantIn), C.POINTER(C.c_void_p),
                                      C.c_uint32]
     lib.inshr_reconstruct.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CDeltaOut),
@@ -540,6 +542,27 @@ class Context:
             res[i].delta_bits = int(oa[i].delta_bits)
         res._pa, res._ca, res._oa, res._prev, res._cur = pa, ca, oa, prev, cur
         return res
+
+    def delta_static(self, prev: Sequence[Quantized], cur: Sequence[Quantized], out: List[Delta]) -> List[Delta]:
+        """inshr_delta_static into the buffers of `out` (a list inshr_delta's binding returned for
+        the same shapes): the library allocates nothing, and neither does this method on the device."""
+        nT = len(prev)
+        pa = (CCodes * nT)()
+        ca = (CCodes * nT)()
+        oa = (CDeltaOut * nT)()
+        for i, (p, c, d) in enumerate(zip(prev, cur, out)):
+            pa[i] = CCodes(p._ptrs[0], p.sym_bits, 0, p.K, p.n)
+            ca[i] = CCodes(c._ptrs[0], c.sym_bits, 0, c.K, c.n)
+            oa[i].packed = d.packed.data_ptr()
+            oa[i].packed_words = d.packed.numel()
+            oa[i].group_off = d.goff_buf.data_ptr()
+            oa[i].group_off_entries = d.goff_buf.numel()
+            oa[i].perm = d.perm.data_ptr() if d.perm is not None else None
+        self._check(self.lib.inshr_delta_static(self.h, pa, ca, oa, nT))
+        for i in range(nT):
+            out[i].delta_bits = int(oa[i].delta_bits)
+            out[i].group_off = out[i].goff_buf[:prev[i].K + 3]
+        return out
 
     # -- inshr_dequantize -----------------------------------------------------------------
     def dequantize(self, qs: Sequence[Quantized],

@@ -46,6 +46,7 @@ struct inshr_ctx {
 
     u32 *delta_flags = nullptr; // flag word of the delta kernels (DF_*), allocated with the context
     bool delta_pending = false; // an asynchronous delta call has not had its flags read yet
+    bool static_pending = false; // the same for inshr_delta_static (its flag word is in its own scratch)
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
     DevBuf aux_mem;    // quantize descriptors, delta scratch
     DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
@@ -151,10 +152,13 @@ int ensure_dev(inshr_ctx *c, DevBuf &b, size_t bytes)
 // After the stream has been synchronised: the flags that the kernels of the last inshr_delta raised.
 int take_delta_flags(inshr_ctx *c)
 {
-    if (!c->delta_pending) return INSHR_OK;
-    u32 f = 0;
-    HIPCHK(c, hipMemcpy(&f, c->delta_flags, sizeof(u32), hipMemcpyDeviceToHost));
-    c->delta_pending = false;
+    if (!c->delta_pending && !c->static_pending) return INSHR_OK;
+    u32 f = 0, g = 0;
+    if (c->delta_pending) HIPCHK(c, hipMemcpy(&f, c->delta_flags, sizeof(u32), hipMemcpyDeviceToHost));
+    if (c->static_pending)
+        HIPCHK(c, hipMemcpy(&g, delta_static_flags(c->device), sizeof(u32), hipMemcpyDeviceToHost));
+    c->delta_pending = c->static_pending = false;
+    f |= g;
     if (f & DF_ORDER) {
         c->last_err = "delta: ranks from returning LDS atomics disagree with ballot ranks (set INSHR_NO_LDS_ORDER=1)";
         return INSHR_E_INTERNAL;
@@ -559,7 +563,7 @@ int inshr_create(inshr_ctx **out, int device, void *hip_stream, uint64_t scratch
             if (const char *e = getenv(name))
                 if (atoi(e) != 0) c->lds_ordered = false;
     }
-    if (hipMalloc(&c->delta_flags, 256) != hipSuccess) {
+    if (hipMalloc(&c->delta_flags, 256) != hipSuccess || delta_static_init(device) != hipSuccess) {
         delete c;
         return INSHR_E_DEVICE;
     }
@@ -1256,6 +1260,68 @@ int inshr_delta(inshr_ctx *c, const inshr_codes *prev, const uint32_t *const *pr
     HIPCHK(c, launch_delta((const DDesc *)(db + o_dd), (int)n_tensors, dtile, chunk,
                            (const u32 *)(db + o_ct), (u32 *)(db + o_ck), c->delta_flags, any_scatter,
                            any_perm, any_gather, c->lds_ordered, c->stream));
+    return INSHR_OK;
+}
+
+int inshr_delta_static(inshr_ctx *c, const inshr_codes *prev, const inshr_codes *cur,
+                       inshr_delta_out *out, uint32_t n_tensors)
+{
+    if (!c || !prev || !cur || !out || n_tensors == 0) return INSHR_E_ARG;
+    if (n_tensors > (uint32_t)DELTA_STATIC_MAX_TENSORS) {
+        c->last_err = "inshr_delta_static: more than " + std::to_string(DELTA_STATIC_MAX_TENSORS) + " tensors";
+        return INSHR_E_CAPACITY;
+    }
+    DeltaStaticArgs a;
+    memset(&a, 0, sizeof(a));
+    a.n_tensors = n_tensors;
+    u64 dtile = 0, chunk = 0;
+    bool any_scatter = false, any_perm = false;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        uint64_t words = 0;
+        int rc = inshr_delta_bound(&prev[t], &cur[t], &words);
+        if (rc) return rc;
+        const uint64_t n = prev[t].n;
+        if (n == 0 || n >= (1ull << 32) || !prev[t].packed || !cur[t].packed) return INSHR_E_ARG;
+        uint32_t Kp = 0, Kc = 0;
+        (void)codes_bins(prev[t], Kp); // (checked by inshr_delta_bound)
+        (void)codes_bins(cur[t], Kc);
+        if (prev[t].sym_bits != symbol_bits(Kp) || cur[t].sym_bits != symbol_bits(Kc)) return INSHR_E_CONFIG;
+        if (!out[t].packed || !out[t].group_off || out[t].packed_words < words) return INSHR_E_CAPACITY;
+        if (out[t].group_off_entries && out[t].group_off_entries < Kp + 3u) return INSHR_E_CAPACITY;
+        DDesc &d = a.dd[t];
+        d.prev = (const unsigned long long *)prev[t].packed;
+        d.cur = (const unsigned long long *)cur[t].packed;
+        d.out = (unsigned long long *)out[t].packed;
+        d.group_off = out[t].group_off;
+        d.perm = out[t].perm;
+        d.n = n;
+        d.out_words = words;
+        d.wp = prev[t].sym_bits;
+        d.wc = cur[t].sym_bits;
+        d.Kp = Kp;
+        d.B = std::max(Kp, Kc) + 2u;
+        d.wB = symbol_bits(std::max(Kp, Kc));
+        out[t].delta_bits = d.wB;
+        d.dtile0 = dtile;
+        d.chunk0 = chunk;
+        const u64 nt = (n + DELTA_TILE - 1) / DELTA_TILE;
+        d.n_chunks = (nt + DELTA_CHUNK - 1) / DELTA_CHUNK;
+        dtile += nt;
+        chunk += d.n_chunks;
+        if (d.perm)
+            any_perm = true;
+        else
+            any_scatter = true;
+    }
+    if (chunk > (u64)DELTA_STATIC_MAX_CHUNKS) {
+        c->last_err = "inshr_delta_static: the tensors need " + std::to_string(chunk) + " chunks of " +
+                      std::to_string((u64)DELTA_TILE * DELTA_CHUNK) + " elements, the static scratch holds " +
+                      std::to_string(DELTA_STATIC_MAX_CHUNKS);
+        return INSHR_E_CAPACITY;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    c->static_pending = true;
+    HIPCHK(c, launch_delta_static(c->device, a, dtile, chunk, any_scatter, any_perm, c->lds_ordered, c->stream));
     return INSHR_OK;
 }
 

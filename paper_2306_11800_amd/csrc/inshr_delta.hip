@@ -907,6 +907,69 @@ hipError_t launch_lds_order_check(u32 *violations, hipStream_t s)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// The delta without any allocation: descriptors, the chunk -> tensor table, the per-chunk symbol
+// populations and the flag word live in one file-scope device array.  Every GPU holds its own copy
+// at its own address; delta_static_init asks for it once per device, and host code uses that
+// pointer only (the array's name is not a device address on the host side).
+// ------------------------------------------------------------------------------------------
+constexpr size_t DST_DD = 0;                                                   // DDesc[MAX_TENSORS]
+constexpr size_t DST_FLAGS = DST_DD + sizeof(DDesc) * DELTA_STATIC_MAX_TENSORS; // u32 flag word
+constexpr size_t DST_CT = (DST_FLAGS + 256) & ~(size_t)255;                    // u32[MAX_CHUNKS]
+constexpr size_t DST_CK = DST_CT + sizeof(u32) * DELTA_STATIC_MAX_CHUNKS;      // u32[MAX_CHUNKS][SS]
+constexpr size_t DST_BYTES = DST_CK + sizeof(u32) * (size_t)DELTA_STATIC_MAX_CHUNKS * DELTA_SS;
+static __device__ __align__(256) unsigned char scratch[DST_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static unsigned char *g_scratch_ptr[MAX_DEVICES]; // per device: where its copy of `scratch` lies
+
+hipError_t delta_static_init(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); // (the current device's copy)
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = (unsigned char *)p;
+    return hipSuccess;
+}
+
+u32 *delta_static_flags(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES || !g_scratch_ptr[device]) return nullptr;
+    return (u32 *)(g_scratch_ptr[device] + DST_FLAGS);
+}
+
+// descriptors from the kernel arguments into the scratch array; tensor of every chunk; flags cleared
+__global__ __launch_bounds__(256) void k_dstatic_setup(DeltaStaticArgs a, DDesc *__restrict__ dd,
+                                                       u32 *__restrict__ chunk_tensor,
+                                                       u32 *__restrict__ flags)
+{
+    const u32 tid = threadIdx.x;
+    if (tid < a.n_tensors) dd[tid] = a.dd[tid];
+    if (tid == 0u) *flags = 0u;
+    for (u32 t = 0; t < a.n_tensors; t++) {
+        const u64 c0 = a.dd[t].chunk0, c1 = c0 + a.dd[t].n_chunks;
+        for (u64 c = c0 + tid; c < c1; c += 256u) chunk_tensor[c] = t;
+    }
+}
+
+hipError_t launch_delta_static(int device, const DeltaStaticArgs &a, u64 n_dtiles, u64 n_chunks,
+                               bool any_scatter, bool any_perm, bool lds_ordered, hipStream_t s)
+{
+    if (device < 0 || device >= MAX_DEVICES || !g_scratch_ptr[device]) return hipErrorNotInitialized;
+    if (a.n_tensors > (u32)DELTA_STATIC_MAX_TENSORS || n_chunks > (u64)DELTA_STATIC_MAX_CHUNKS)
+        return hipErrorInvalidValue;
+    unsigned char *base = g_scratch_ptr[device];
+    DDesc *dd = (DDesc *)(base + DST_DD);
+    u32 *flags = (u32 *)(base + DST_FLAGS);
+    u32 *chunk_tensor = (u32 *)(base + DST_CT);
+    u32 *chunk_tot = (u32 *)(base + DST_CK); // every entry of the chunks in use is written by k_dhist
+    PROF("k_dstatic_setup", s, k_dstatic_setup<<<1, 256, 0, s>>>(a, dd, chunk_tensor, flags));
+    return launch_delta(dd, (int)a.n_tensors, n_dtiles, n_chunks, chunk_tensor, chunk_tot, flags,
+                        any_scatter, any_perm, false, lds_ordered, s);
+}
+
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
                         const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool any_scatter,
                         bool any_perm, bool any_gather, bool lds_ordered, hipStream_t s)

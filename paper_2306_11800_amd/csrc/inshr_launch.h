@@ -135,6 +135,14 @@ constexpr u32 DF_ORDER = 2u;   // ranks from returning LDS adds disagree with ra
 constexpr int DELTA_TILE = 12288;
 constexpr int DELTA_CHUNK = 64;
 constexpr int DELTA_SS = 264;
+// the delta entry point that allocates nothing: its limits, and its descriptors as kernel arguments
+constexpr int DELTA_STATIC_MAX_TENSORS = 16;
+constexpr int DELTA_STATIC_MAX_CHUNKS = 2048; // chunks of DELTA_TILE * DELTA_CHUNK elements, all tensors
+struct DeltaStaticArgs {
+    DDesc dd[DELTA_STATIC_MAX_TENSORS];
+    u32 n_tensors, pad;
+};
+
 // Optional per-kernel timing with HIP events on the launch stream (off by default).
 void prof_begin(const char *name, hipStream_t s);
 void prof_end(hipStream_t s);
@@ -152,6 +160,10 @@ hipError_t launch_quantize(const Batch &bt, const QDesc *qd, QInfo *qi, hipStrea
 hipError_t launch_delta(const DDesc *dd, int nT, u64 n_dtiles, u64 n_chunks,
                         const u32 *chunk_tensor, u32 *chunk_tot, u32 *flags, bool any_scatter,
                         bool any_perm, bool any_gather, bool lds_ordered, hipStream_t s);
+hipError_t delta_static_init(int device); // once per device, with that device current
+u32 *delta_static_flags(int device);      // the flag word of launch_delta_static on that device
+hipError_t launch_delta_static(int device, const DeltaStaticArgs &a, u64 n_dtiles, u64 n_chunks,
+                               bool any_scatter, bool any_perm, bool lds_ordered, hipStream_t s);
 hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
 hipError_t launch_dequantize(const RDesc *rd, int nT, u64 n_tiles, u64 max_outlier, u32 *flags,
                              u32 *ones, int n_cu, hipStream_t s);
