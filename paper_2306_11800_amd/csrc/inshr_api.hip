@@ -359,7 +359,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_gel = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_geh = cv.take((size_t)nT * MAX_GROUPS * 4);
         const size_t o_sgc = cv.take((size_t)nT * MAX_EDGES * 4);
-        const size_t o_ms = cv.take((size_t)units * MAX_EDGES * 8);
+        const size_t o_ms = cv.take((size_t)units * MAX_SUB * 8);
+        const size_t o_sbc = cv.take((size_t)nT * MAX_SUB * 4);
+        const size_t o_sbn = cv.take((size_t)nT * MAX_SUB * 4);
         const size_t o_cb = cv.take((size_t)nT * n_cfg * CB_STRIDE * 4);
         const size_t o_sc = cv.take((size_t)nT * n_cfg * sizeof(Score));
         const size_t o_bt = cv.take((size_t)nT * n_cfg * CB_STRIDE * 8);
@@ -457,7 +459,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         B.seg_cnt = (u32 *)(db + o_sgc);
         B.grp_cnt = (u32 *)(db + o_gcn);
         B.grp_sx = (double *)(db + o_gsx);
-        B.mom_sx = (double *)(db + o_ms);
+        B.mom_sx = (u64 *)(db + o_ms);
+        B.sub_code = (u32 *)(db + o_sbc);
+        B.sub_cnt = (u32 *)(db + o_sbn);
         B.codebook = (float *)(db + o_cb);
         B.scores = (Score *)(db + o_sc);
         B.bin_term = (double *)(db + o_bt);

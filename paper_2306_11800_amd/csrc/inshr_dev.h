@@ -40,6 +40,7 @@ constexpr int NB8 = 255;            // interior boundaries at 8 bits; fewer bits
 constexpr int NBT = NB8 + 8;        // ... plus the boundaries of 12 bins that are not among them (the
                                     // search space of Sec. 5 has 6 and 12 bins: 3, 6 and 12 bins nest)
 constexpr int MAX_EDGES = 4096;     // merged edge list of all pairs (15 * 267 = 4005 fits)
+constexpr int MAX_SUB = 4608;       // sub-slots: slots cut where the exponent changes (4006 + 511 fits)
 constexpr int EPP = NBT + 4;        // edge items per pair: boundaries 0 .. NBT - 1, class edges NBT .. NBT + 3
 constexpr int EIDX_STRIDE = 268;    // per-pair stride of the edge positions
 constexpr int MAX_CFG = 256;
@@ -228,7 +229,7 @@ struct TState {
     u64 pair_An[MAX_PAIRS], pair_Mn[MAX_PAIRS], pair_Pn[MAX_PAIRS], pair_Pp[MAX_PAIRS];
     u64 pair_M[MAX_PAIRS], pair_Ap[MAX_PAIRS];
     // scoring
-    u32 n_edges;
+    u32 n_edges, n_sub;
     double sumsq;                      // sum of x^2
     double thr_sumsq[MAX_THR];         // prune: sum x^2 over mag < tau; protect: over mag > tau
     u32 best, feasible;
@@ -280,9 +281,10 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
-// Exclusive scan of in[0..n) (n <= 32 * BLOCK) into out[0..n], out[n] = total; whole workgroup of
-// BLOCK threads; tmp is LDS scratch of BLOCK/64 + 1 words.  in/out may alias only if equal.
-__device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
+// Exclusive scan of in(0) .. in(n - 1) (n <= 32 * BLOCK) into out[0..n], out[n] = total; whole
+// workgroup of BLOCK threads; tmp is LDS scratch of BLOCK/64 + 1 words.  in may read out[i] only
+// at the index it is asked for.
+template <class F> __device__ inline u32 block_excl_scan_fn(F in, u32 *out, int n, u32 *tmp)
 {
     const int t = threadIdx.x;
     const int per = (n + BLOCK - 1) / BLOCK;
@@ -290,7 +292,7 @@ __device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
     u32 s = 0;
     for (int i = 0; i < per; i++) {
         int idx = lo + i;
-        if (idx < n) s += in[idx];
+        if (idx < n) s += in(idx);
     }
     // inclusive scan of s across the wave
     u32 inc = s;
@@ -315,7 +317,7 @@ __device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
     for (int i = 0; i < per; i++) {
         int idx = lo + i;
         if (idx < n) {
-            u32 v = in[idx];
+            u32 v = in(idx);
             out[idx] = base;
             base += v;
         }
@@ -324,6 +326,11 @@ __device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
     if (t == 0) out[n] = total;
     __syncthreads();
     return total;
+}
+// The same for an array; in and out may alias only if equal.
+__device__ inline u32 block_excl_scan(const u32 *in, u32 *out, int n, u32 *tmp)
+{
+    return block_excl_scan_fn([in](int i) { return in[i]; }, out, n, tmp);
 }
 
 } // namespace inshr

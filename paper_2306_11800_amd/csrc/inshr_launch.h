@@ -41,14 +41,17 @@ struct Bufs { // device pointers, indexed by the tensor's position in the batch 
     u32 *edges;     // [nT][MAX_EDGES] edge keys in that order
     u32 *edge_bin;  // [nT][MAX_EDGES] second-level bin of each edge
     u16 *edge_item; // [nT][MAX_EDGES] pair * 259 + (boundary j - 1, or 255 + class edge)
-    u16 *sl;        // [nT][32768 + 64] slot of every bin without an edge; 0xFFFF for the others
+    u16 *sl;        // [nT][32768 + 64] sub-slot of every bin without an edge; 0xFFFF for the others
+    u32 *sub_code;  // [nT][MAX_SUB] slot << 9 | sign and exponent (key >> 23) of each sub-slot
+    u32 *sub_cnt;   // [nT][MAX_SUB] keys per sub-slot (in bins without an edge)
     u16 *pair_eidx; // [nT][MAX_PAIRS][EIDX_STRIDE] position of each pair's edges in the list
     u32 *grp_elo;   // [nT][MAX_GROUPS] first / one-past-last edge of each group of active bins
     u32 *grp_ehi;
     u32 *seg_cnt;   // [nT][MAX_EDGES] keys per slot that lie in bins without an edge
     u32 *grp_cnt;   // [nT][2][MAX_EDGES] keys per slot from the group of the slot's lower / upper edge
     double *grp_sx; // [nT][2][MAX_EDGES] ... and their sums
-    double *mom_sx; // [units][MAX_EDGES] per slot: sum over the unit's keys in bins without an edge
+    u64 *mom_sx;    // [units][MAX_SUB] per sub-slot: sum of the 23 mantissa bits over the unit's keys in
+                    // bins without an edge
     float *codebook; // [nT][n_cfg][CB_STRIDE]
     Score *scores;  // [nT][n_cfg]
     double *bin_term; // [nT][n_cfg][CB_STRIDE] per-bin 2cS - nc^2

@@ -139,12 +139,28 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
             atomicMax(&ehi[g], pos + 1u);
         }
     }
+    // Slot and sub-slot of every bin.  A bin without an edge lies inside one slot; sweep 3 adds the
+    // mantissas of its keys as integers, which is exact and linear in the value only among keys of
+    // one sign and exponent, so a slot is cut further wherever the exponent changes: sub-slot =
+    // (edges in lower bins) + (key >> 23 of the bin).  Both terms grow with the bin, so the sum
+    // names the pair; it stays below n_e + 512.
+    u32 *subc = smem;                 // [MAX_SUB] keys per sub-slot (the sort words are done with)
+    __shared__ u32 bfirst[512];       // first bin of every sign and exponent
+    __shared__ u32 s_err;
+    const u32 n_sub = n_e + 512u;
+    u32 *sub_code = B.sub_code + (size_t)t * MAX_SUB;
+    // (a table prefix is sign, exponent and three mantissa bits; every prefix has a bin of its own)
+    for (u32 k = tid; k < 512u; k += BLOCK) bfirst[k] = (tab[8u * k] >> 5) & 0x7fffu;
+    for (u32 i = tid; i < (u32)MAX_SUB; i += BLOCK) {
+        subc[i] = 0u;
+        sub_code[i] = 0xFFFFFFFFu; // no bin has this sub-slot
+    }
+    if (tid == 0) s_err = 0u;
+    __syncthreads();
     u16 *sl = B.sl + (size_t)t * (L2_BINS + 64);
+    u32 x = 0u;
     for (u32 b = tid; b < nb2; b += BLOCK) {
-        if (binfo[b] != INACTIVE) {
-            sl[b] = 0xFFFFu;
-            continue;
-        }
+        const u32 bi = binfo[b], hb = h2[b]; // (in flight during the searches)
         u32 lo = 0u, hi = n_e; // edges in lower bins
         while (lo < hi) {
             const u32 mid = (lo + hi) >> 1;
@@ -153,12 +169,35 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
             else
                 hi = mid;
         }
-        sl[b] = (u16)lo;
-        if (h2[b]) atomicAdd(&segc[lo], h2[b]);
+        u32 xh = 511u; // last exponent whose first bin is <= b (not below that of the thread's last bin)
+        while (x < xh) {
+            const u32 mid = (x + xh + 1u) >> 1;
+            if (bfirst[mid] <= b)
+                x = mid;
+            else
+                xh = mid - 1u;
+        }
+        const u32 ss = lo + x;
+        if (bi != INACTIVE) {
+            sl[b] = 0xFFFFu;
+        } else if (ss >= (u32)MAX_SUB) {
+            s_err = 1u;
+            sl[b] = 0xFFFFu;
+        } else {
+            sl[b] = (u16)ss;
+            if (hb) {
+                atomicAdd(&segc[lo], hb);
+                if (atomicAdd(&subc[ss], hb) == 0u) sub_code[ss] = (lo << 9) | x; // first bin to arrive
+            }
+        }
     }
     __syncthreads();
+    if (tid == 0 && s_err) atomicOr(&st->internal_err, 512u);
     u32 *sc = B.seg_cnt + (size_t)t * MAX_EDGES;
     for (u32 i = tid; i <= n_e; i += BLOCK) sc[i] = segc[i];
+    u32 *sub_cnt = B.sub_cnt + (size_t)t * MAX_SUB;
+    for (u32 i = tid; i < (u32)MAX_SUB; i += BLOCK) sub_cnt[i] = subc[i];
+    if (tid == 0) st->n_sub = min(n_sub, (u32)MAX_SUB);
     if (tid == 0) st->n_edges = n_e;
 }
 
@@ -176,6 +215,7 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     double *V = reinterpret_cast<double *>(smem);              // [4096] sum of each slot
     u64 *C = reinterpret_cast<u64 *>(smem + 2 * MAX_EDGES);    // [4096] keys in slots 0..s
     double *S8 = reinterpret_cast<double *>(smem + 4 * MAX_EDGES); // [MAX_PAIRS][256] sums of 8-bit bins
+    double *SV = S8 + MAX_PAIRS * 256;                         // [MAX_SUB] sum of each sub-slot
     __shared__ double s_qout[MAX_FRAC];
     __shared__ double s_sumsq;
 
@@ -196,20 +236,57 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
     // slot and added bin by bin: a difference of prefix sums would lose a bin of small values next
     // to large ones (fp64 carries 16 digits, fp32 values span 83).
     __shared__ u64 w_c[BLOCK / 64];
+    // Keys of bins without an edge: sweep 3 left, per unit and sub-slot, the sum of their 23 mantissa
+    // bits.  All keys of a sub-slot share sign and exponent E, so their values add up to
+    // +-2^(E-150) (2^23 count + sum of mantissas), or +-2^-149 (sum) for E = 0; the integer is
+    // below 2^51 and the conversion exact.
+    const u32 n_sub = st->n_sub;
+    const u32 *sub_code = B.sub_code + (size_t)t * MAX_SUB;
+    const u32 *sub_cnt = B.sub_cnt + (size_t)t * MAX_SUB;
+    // (first and last sub-slot of every slot: kept where the slot's sum goes afterwards)
+    u32 *ss_lo = reinterpret_cast<u32 *>(V), *ss_hi = ss_lo + 1; // [2 * slot]
+    for (u32 i = tid; i <= m; i += BLOCK) {
+        ss_lo[2u * i] = 0xFFFFFFFFu;
+        ss_hi[2u * i] = 0u;
+    }
+    __syncthreads();
+    for (u32 ss = tid; ss < n_sub; ss += BLOCK) {
+        const u32 code = sub_code[ss];
+        double val = 0.0;
+        if (code != 0xFFFFFFFFu) {
+            u64 tot = 0ull;
+            for (u32 u = u0; u < u1; u++) tot += B.mom_sx[(size_t)t_fu_ids[u] * MAX_SUB + ss];
+            const u32 bx = code & 511u; // key >> 23: the top bit is set for values >= 0, else all bits are flipped
+            const bool neg = (bx & 256u) == 0u;
+            const int E = (int)((neg ? ~bx : bx) & 255u);
+            if (E)
+                val = ldexp((double)(((u64)sub_cnt[ss] << 23) + tot), E - 150);
+            else
+                val = ldexp((double)tot, -149);
+            if (neg) val = -val;
+            const u32 slot = code >> 9;
+            if (slot <= m) {
+                atomicMin(&ss_lo[2u * slot], ss);
+                atomicMax(&ss_hi[2u * slot], ss);
+            }
+        }
+        SV[ss] = val;
+    }
+    __syncthreads();
     {
         u64 pc[4];
         u64 run_c = 0;
-        // keys of bins without an edge: per unit, in unit order (a thread's four slots are 32
-        // consecutive bytes of a unit's row; entries past the last slot are never used)
+        // a slot's sub-slots in ascending order (those in between that no bin has hold 0.0)
         double su[4] = {0.0, 0.0, 0.0, 0.0};
-        if (4u * tid <= m) {
-#pragma unroll 4
-            for (u32 u = u0; u < u1; u++) {
-                const double *row = B.mom_sx + (size_t)t_fu_ids[u] * MAX_EDGES + 4u * tid;
 #pragma unroll
-                for (int r = 0; r < 4; r++) su[r] += row[r];
+        for (int r = 0; r < 4; r++) {
+            const u32 i = 4u * tid + (u32)r;
+            if (i <= m) {
+                const u32 a = ss_lo[2u * i], b = ss_hi[2u * i];
+                for (u32 ss = a; ss <= b && a != 0xFFFFFFFFu; ss++) su[r] += SV[ss];
             }
         }
+        __syncthreads(); // V is written next
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             const u32 i = 4u * tid + r;
@@ -354,7 +431,7 @@ __global__ __launch_bounds__(BLOCK) void k_final(const TDesc *__restrict__ td,
 }
 
 constexpr int SM_EDGES = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4;
-constexpr int SM_FINAL = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4 + MAX_PAIRS * 256 * 8;
+constexpr int SM_FINAL = (2 * MAX_EDGES + 2 * MAX_EDGES) * 4 + MAX_PAIRS * 256 * 8 + MAX_SUB * 8;
 
 static bool g_attr_done = false;
 static hipError_t set_attrs()

@@ -949,7 +949,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
 // ------------------------------------------------------------------------------------------
 template <bool FULL>
 __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, const u32 *T, const u16 *SEG,
-                                            double *sx, GLOBAL_AS u32 *gdst, u32 &gathered,
+                                            u64 *sx, GLOBAL_AS u32 *gdst, u32 &gathered,
                                             u32 tau_o_min, const u32 *s_tau_o, u32 n_o,
                                             double (&q_out)[MAX_FRAC], u32 (&oc)[MAX_FRAC])
 {
@@ -972,7 +972,10 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
         // combined or an earlier condition would be rebuilt from a vector register)
         u64 cm = __ballot(key[i] != ZERO_KEY) & __ballot(slot[i] == 0xFFFFu);
         if (!FULL) cm &= __ballot(valid);
-        if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (double)v[i]);
+        // (the keys of a sub-slot share sign and exponent: their values add up as count and sum of
+        // mantissas, exactly and in any order; a 64-bit integer add costs the LDS half of what a
+        // double add does)
+        if (valid && slot[i] != 0xFFFFu) atomicAdd(&sx[slot[i]], (u64)(__float_as_uint(v[i]) & 0x7fffffu));
         if (cand) // (the wave's cursor is a scalar: it goes into the address, not into the rank)
             (gdst + gathered)[__builtin_amdgcn_mbcnt_hi((u32)(cm >> 32), __builtin_amdgcn_mbcnt_lo((u32)cm, 0u))] = key[i];
         gathered += (u32)__popcll(cm);
@@ -997,7 +1000,7 @@ __device__ __forceinline__ void gather_tile(const float (&v)[16], u32 mask, cons
 }
 
 
-constexpr int SM_GATHER = MAX_EDGES * 8 + COARSE * 4 + L2_BINS * 2 + (BLOCK / 64) * 8 + MAX_FRAC * 4;
+constexpr int SM_GATHER = MAX_SUB * 8 + COARSE * 4 + L2_BINS * 2 + (BLOCK / 64) * 8 + MAX_FRAC * 4;
 
 __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, int nT,
                                                   const u64 *__restrict__ wg_tile0,
@@ -1007,9 +1010,9 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
     // one static array (the only one, so it starts at LDS address 0): table offsets then fold into
     // the LDS instructions, which the base of a dynamic array does not allow
     __shared__ __attribute__((aligned(16))) u32 smem[SM_GATHER / 4];
-    double *sx = reinterpret_cast<double *>(smem);             // [MAX_EDGES] sum per slot
-    u32 *T = smem + 2 * MAX_EDGES;                             // [COARSE]
-    u16 *SEG = reinterpret_cast<u16 *>(T + COARSE);            // [L2_BINS] slot of the bin, or 0xFFFF
+    u64 *sx = reinterpret_cast<u64 *>(smem);                   // [MAX_SUB] sum of mantissas per sub-slot
+    u32 *T = smem + 2 * MAX_SUB;                               // [COARSE]
+    u16 *SEG = reinterpret_cast<u16 *>(T + COARSE);            // [L2_BINS] sub-slot of the bin, or 0xFFFF
     // (no static LDS arrays: the tables then start at LDS address 0 and their offsets fold into
     // the instructions)
     double *s_red = reinterpret_cast<double *>(SEG + L2_BINS); // [BLOCK / 64]
@@ -1028,14 +1031,14 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
         const u64 t_end = d.tile0 + n_tiles_t;
         const u64 stop = t_end < tile_hi ? t_end : tile_hi;
         TState *st = B.ts + t;
-        const u32 n_slots = st->n_edges + 1u;
+        const u32 n_slots = st->n_sub;
         {
             const u32 *gseg = reinterpret_cast<const u32 *>(B.sl + (size_t)t * (L2_BINS + 64));
             u32 *seg32 = reinterpret_cast<u32 *>(SEG);
             for (u32 i = tid; i < (u32)L2_BINS / 2; i += BLOCK) seg32[i] = gseg[i];
         }
         for (int i = tid; i < COARSE; i += BLOCK) T[i] = entry_for_u16(B.table2[(size_t)t * COARSE + i]);
-        for (u32 i = tid; i < n_slots; i += BLOCK) sx[i] = 0.0;
+        for (u32 i = tid; i < n_slots; i += BLOCK) sx[i] = 0ull;
         if (tid < MAX_FRAC) s_tau_o[tid] = (tid < n_o) ? st->thr_mag[n_p + tid] : 0x7fffffffu;
         __syncthreads();
         u32 tau_o_min = 0x7fffffffu;
@@ -1080,7 +1083,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
             B.unit_cand[(size_t)fu * 16 + wave] = gathered;
             if (overflow) atomicOr(&st->pool_overflow, 4u);
         }
-        double *gs = B.mom_sx + (size_t)fu * MAX_EDGES;
+        u64 *gs = B.mom_sx + (size_t)fu * MAX_SUB;
         for (u32 i = tid; i < n_slots; i += BLOCK) gs[i] = sx[i];
         double *part = B.sq_part + (size_t)fu * SQ_STRIDE;
 #pragma unroll
