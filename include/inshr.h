@@ -329,6 +329,41 @@ int inshr_entropy_encode(const uint64_t *packed, const uint16_t *values, uint64_
 int inshr_entropy_decode(const uint8_t *in, uint64_t in_bytes, uint64_t n, uint32_t delta_bits,
                          uint32_t n_groups, uint64_t *packed, uint16_t *values, uint64_t *group_off);
 
+/* ---- search-space navigation (host only; Sec. 5) --------------------------------------------- */
+
+/* The configuration cube of Sec. 5: axis 0 = number of bins, ascending; axis 1 = prune fraction,
+ * descending; axis 2 = protect fraction, ascending, so that one step up along any axis raises
+ * quality and cost.  Cell (i, j, k) holds the configuration whose score is
+ * scores[cell_cfg[(i * dims[1] + j) * dims[2] + k]]; scores is one row of inshr_search's score
+ * table (or the caller's sum of rows over a group of tensors: sse, sumsq and cost_bits add).
+ * A cell is feasible when sse <= eps * sumsq.  All pointers are host memory; nothing runs on the
+ * GPU.
+ *
+ * inshr_guided_search (Sec. 5, Alg. 4, guided exhaustive search): evaluates the diagonal of the
+ * cube from its most aggressive corner, takes the cheapest feasible diagonal cell as the incumbent
+ * and splits the cube at it; the part that is more conservative along every axis can only cost
+ * more, the part more aggressive along every axis is infeasible when quality is monotone, and the
+ * remaining parts are searched in the same way.  With scores monotone along every axis the result
+ * has the least cost_bits of all feasible cells; on other tables it is the heuristic's answer.
+ * *best_cell = i, j, k packed as (i << 16 | j << 8 | k), *feasible = 0 when no evaluated cell was
+ * feasible (then *best_cell is the most conservative corner); *trials = distinct cells whose
+ * score was read; visited (dims[0] * dims[1] * dims[2] bytes, may be NULL) is set to 1 for them.
+ *
+ * inshr_neighbourhood_search (Sec. 5, delta-neighbourhood search): the cells at most e steps
+ * (sum over the axes) from prev_cell, without those that are at least as aggressive as prev_cell
+ * along every axis and more aggressive along one, are read in ascending order of cost_bits (ties:
+ * lower configuration index) until one is feasible.  *feasible = 0 when none is: the caller then
+ * falls back to inshr_guided_search.  The pruning-metric probe of Sec. 5 is not part of this call
+ * (one metric, the magnitude, exists here).
+ *
+ * Errors: INSHR_E_ARG for NULL pointers, an axis of length 0 or above 255, or prev_cell outside. */
+int inshr_guided_search(const inshr_score *scores, const uint32_t *cell_cfg, const uint32_t dims[3],
+                        double eps, uint32_t *best_cell, uint32_t *feasible, uint32_t *trials,
+                        uint8_t *visited);
+int inshr_neighbourhood_search(const inshr_score *scores, const uint32_t *cell_cfg,
+                               const uint32_t dims[3], uint32_t prev_cell, uint32_t e, double eps,
+                               uint32_t *best_cell, uint32_t *feasible, uint32_t *trials);
+
 /* Per-kernel timing for benchmarks (not part of the method): when enabled, every kernel launch of
  * this process is bracketed by HIP events on its stream.  inshr_profile(ctx, 1) clears the totals
  * and starts recording, inshr_profile(ctx, 0) stops.  inshr_profile_read synchronises the stream

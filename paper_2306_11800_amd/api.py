@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libinshr.so")
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
            "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
-           "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_dequantize", "inshr_reconstruct",
+           "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_guided_search", "inshr_neighbourhood_search", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
            "inshr_profile", "inshr_profile_read"]
 
@@ -144,6 +144,13 @@ def load_library() -> C.CDLL:
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
     lib.inshr_delta_static.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CCodes),
                                        C.POINTER(CDeltaOut), C.c_uint32]
+    lib.inshr_guided_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                        C.c_double, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                        C.POINTER(C.c_uint32), C.POINTER(C.c_uint8)]
+    lib.inshr_neighbourhood_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32),
+                                               C.POINTER(C.c_uint32), C.c_uint32, C.c_uint32, C.c_double,
+                                               C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                               C.POINTER(C.c_uint32)]
     lib.inshr_dequantize.argtypes = [C.c_void_p, C.POINTER(CDequantIn), C.POINTER(C.c_void_p),
                                      C.c_uint32]
     lib.inshr_reconstruct.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CDeltaOut),
@@ -265,6 +272,53 @@ def _config_array(cfgs):
     for i, cfg in enumerate(cfgs):
         arr[i] = CConfig(int(cfg[0]), int(cfg[3]) if len(cfg) > 3 else 0, int(cfg[1]), int(cfg[2]))
     return arr
+
+
+def cube_of(grid) -> Tuple[List[int], Tuple[int, int, int], tuple]:
+    """Configuration cube (Sec. 5) of a full-factorial grid of (bits, prune_ppm, protect_ppm[, bins]):
+    (cell_cfg, dims, axes) with axis 0 the numbers of bins ascending, axis 1 the prune fractions
+    descending, axis 2 the protect fractions ascending."""
+    ks = sorted({bins_of(g) for g in grid})
+    ps = sorted({g[1] for g in grid}, reverse=True)
+    os_ = sorted({g[2] for g in grid})
+    where = {(bins_of(g), g[1], g[2]): i for i, g in enumerate(grid)}
+    cells = [where[(k, p, o)] for k in ks for p in ps for o in os_]
+    return cells, (len(ks), len(ps), len(os_)), (ks, ps, os_)
+
+
+def _cube_args(scores, cell_cfg, dims):
+    n = len(cell_cfg)
+    if n != dims[0] * dims[1] * dims[2]:
+        raise ValueError("cell_cfg does not fill the cube")
+    return (C.c_uint32 * n)(*cell_cfg), (C.c_uint32 * 3)(*dims)
+
+
+def guided_search(scores, cell_cfg, dims, eps: float):
+    """inshr_guided_search on one row of a score table (a ctypes array of CScore).  Returns
+    ((i, j, k), feasible, trials, visited[list of 0/1 per cell])."""
+    lib = load_library()
+    cc, dd = _cube_args(scores, cell_cfg, dims)
+    best, feas, trials = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    vis = (C.c_uint8 * len(cell_cfg))()
+    rc = lib.inshr_guided_search(scores, cc, dd, float(eps), C.byref(best), C.byref(feas), C.byref(trials), vis)
+    if rc:
+        raise InshrError(rc, "inshr_guided_search")
+    b = best.value
+    return (b >> 16, (b >> 8) & 255, b & 255), bool(feas.value), trials.value, list(vis)
+
+
+def neighbourhood_search(scores, cell_cfg, dims, prev_cell, e: int, eps: float):
+    """inshr_neighbourhood_search; prev_cell = (i, j, k).  Returns ((i, j, k), feasible, trials)."""
+    lib = load_library()
+    cc, dd = _cube_args(scores, cell_cfg, dims)
+    best, feas, trials = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    pc = prev_cell[0] << 16 | prev_cell[1] << 8 | prev_cell[2]
+    rc = lib.inshr_neighbourhood_search(scores, cc, dd, pc, int(e), float(eps), C.byref(best),
+                                        C.byref(feas), C.byref(trials))
+    if rc:
+        raise InshrError(rc, "inshr_neighbourhood_search")
+    b = best.value
+    return (b >> 16, (b >> 8) & 255, b & 255), bool(feas.value), trials.value
 
 
 class Context:

@@ -105,3 +105,41 @@ def test_protected_values_stored_as_bfloat16(ctx):
         xf = ctx.dequantize([q32])[0].cpu().numpy()
         idx = r["outlier_idx"].astype(np.int64)
         assert np.array_equal(xf[idx].view(np.uint32), x[idx].view(np.uint32))
+
+
+def test_navigation_over_the_score_table_of_the_paper_cube(ctx):
+    """The whole search space of Sec. 5 (108 configurations, 18 (prune, protect) pairs: two calls of
+    15 pairs at most), scored by the sweeps; the guided search (Alg. 4) and the neighbourhood search
+    then walk the table.  The table is the oracle's (checked), the walk is checked against brute
+    force over it."""
+    import itertools
+    from paper_2306_11800_amd import api
+    rng = np.random.default_rng(68)
+    x = (0.02 * rng.standard_t(4, 300_007)).astype(np.float32)
+    grid = synth.grid_paper()
+    halves = [[i for i, g in enumerate(grid) if (g[1] < 300000) == lo] for lo in (True, False)]
+    scores = (api.CScore * len(grid))()
+    for idx in halves:
+        sub = [grid[i] for i in idx]
+        best, feas, sc = ctx.search([dev(x)], sub, 0.02)
+        check_scores(sc, len(sub), 0, x, sub, 0.02, best[0], feas[0])
+        for j, i in enumerate(idx):
+            scores[i] = sc[j]
+    cells, dims, axes = api.cube_of(grid)
+    sse = np.array([scores[c].sse / scores[c].sumsq for c in cells]).reshape(dims)
+    cost = np.array([scores[c].cost_bits for c in cells]).reshape(dims)
+    monotone = all(np.all(np.diff(sse, axis=a) <= 0) and np.all(np.diff(cost, axis=a) >= 0) for a in range(3))
+    for eps in (0.002, 0.01, 0.02, 0.05, 0.2):
+        cell, feas, trials, vis = api.guided_search(scores, cells, dims, eps)
+        ok = [(int(cost[ijk]), ijk) for ijk in itertools.product(*(range(d) for d in dims)) if sse[ijk] <= eps]
+        # (with equal-frequency bins light pruning can lower the error, so a real table need not be
+        # monotone along the prune axis; the method's guarantee holds for monotone tables only)
+        assert trials <= 108 and (not feas or ok) and (feas == bool(ok) or not monotone)
+        if feas:
+            assert sse[cell] <= eps and cost[cell] >= min(ok)[0]
+            if monotone:
+                assert cost[cell] == min(ok)[0]
+            near, f2, t2 = api.neighbourhood_search(scores, cells, dims, cell, 1, eps)
+            assert f2 and sse[near] <= eps and cost[near] <= cost[cell] and t2 <= 7
+    # the cost model is monotone by construction (more bins, less pruning, more protection cost more)
+    assert all(np.all(np.diff(cost, axis=a) >= 0) for a in range(3))
