@@ -89,8 +89,18 @@ def copy_yardstick():
         s = a.sum()
     torch.cuda.synchronize()
     dr = (time.perf_counter() - t0) / 20
+    # the same copy as an elementwise kernel (a dispatch of its own in every profiler's list)
+    for _ in range(3):
+        torch.mul(a, 1.0, out=b)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        torch.mul(a, 1.0, out=b)
+    torch.cuda.synchronize()
+    de = (time.perf_counter() - t0) / 20
     print(json.dumps({"copy_yardstick": "device copies of 1 GiB (1048576 KiB read, 1048576 KiB written each)",
                       "copy_GB/s_read_plus_write": round(2 * a.numel() * 4 / dt / 1e9, 1),
+                      "elementwise_copy_GB/s_read_plus_write": round(2 * a.numel() * 4 / de / 1e9, 1),
                       "read_only_sum_GB/s": round(a.numel() * 4 / dr / 1e9, 1)}))
 
 
@@ -210,6 +220,7 @@ def main():
         del items
     n_total = sum(t.numel() for t in cur)
     ctx = api.Context(dev)
+    mem0 = (torch.cuda.mem_get_info()[0], torch.cuda.memory_reserved())
     cur = ctx.batch(cur)  # the binding marshals the tensor list once, not in every step
 
     # previous checkpoint's codes (set-up, untimed)
@@ -248,6 +259,9 @@ def main():
     ctx.profile(False)
     step_ms = sorted((b - a) * 1e3 for a, b in zip(marks, marks[1:]))
 
+    # device memory the library holds for its scratch (what left the device minus what torch reserved
+    # for the inputs' neighbours: codes, delta streams)
+    lib_scratch = (mem0[0] - torch.cuda.mem_get_info()[0]) - (torch.cuda.memory_reserved() - mem0[1])
     ms_per_step = dt / args.steps * 1e3
     value = n_total * 4 / (dt / args.steps) / 1e9
 
@@ -450,7 +464,7 @@ def main():
                                                       if len(grid) == 105 else
                                                       "bits {2,3,4,8} x prune {0,.1,.3} x protect {0,.001}")
                                + f"), eps {eps}",
-                   "bytes_fp32": n_total * 4,
+                   "bytes_fp32": n_total * 4, "library_scratch_bytes": int(lib_scratch),
                    "chosen_configs": {f"b{b}_p{p}_o{o}": sum(1 for c in cfgs if tuple(c) == (b, p, o))
                                       for (b, p, o) in sorted(set(tuple(c) for c in cfgs))}},
         "roofline": roofline,
