@@ -122,18 +122,23 @@ static uint32_t bin_of_key(const uint32_t *tkeys, uint32_t n_t, uint32_t key)
     return lo;
 }
 
-/* One configuration, from the sorted images.  sym / boundaries / codebook / out_* may be NULL. */
-static int quantize_one(const float *x, uint64_t n, const sorted_images *si,
-                        const inshr_ref_config *cfg, uint16_t *sym, float *boundaries,
+/* One configuration, from the sorted images.  sym / boundaries / codebook / out_* may be NULL.
+ * pool / n_pool: the ascending magnitude images of all tensors of the layer type (Sec. 4.2: the
+ * same pruning fraction across all layers of a given type, i.e. thresholds that are quantiles of
+ * the type's pooled values); NULL = the tensor alone. */
+static int quantize_one(const float *x, uint64_t n, const sorted_images *si, const uint32_t *pool,
+                        uint64_t n_pool, const inshr_ref_config *cfg, uint16_t *sym, float *boundaries,
                         float *codebook, uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info)
 {
     const uint32_t K = bins_of(cfg);
-    const uint64_t n_p = n * (uint64_t)cfg->prune_ppm / 1000000ull;
-    const uint64_t n_o = n * (uint64_t)cfg->outlier_ppm / 1000000ull;
+    const uint32_t *A = pool ? pool : si->A;
+    const uint64_t nA = pool ? n_pool : n;
+    const uint64_t n_p = nA * (uint64_t)cfg->prune_ppm / 1000000ull;
+    const uint64_t n_o = nA * (uint64_t)cfg->outlier_ppm / 1000000ull;
 
     /* thresholds: exact order statistics of the magnitudes */
-    const uint32_t tau_p = si->A[n_p];         /* pruned    <=> mag <  tau_p */
-    const uint32_t tau_o = si->A[n - 1 - n_o]; /* protected <=> mag >  tau_o */
+    const uint32_t tau_p = A[n_p];          /* pruned    <=> mag <  tau_p */
+    const uint32_t tau_o = A[nA - 1 - n_o]; /* protected <=> mag >  tau_o */
 
     /* Y: quantized ("kept") values in ascending order = the sorted keys with the pruned and
      * protected ones taken out */
@@ -146,7 +151,12 @@ static int quantize_one(const float *x, uint64_t n, const sorted_images *si,
         if (m < tau_p || m > tau_o) continue;
         Y[M++] = k;
     }
-    /* M >= 1 because tau_p <= tau_o and the element of rank n_p is kept */
+    /* M >= 1 for a tensor alone, because tau_p <= tau_o and the element of rank n_p is kept; pooled
+     * thresholds can leave a tensor without quantized values: no bins can be made for it */
+    if (M == 0) {
+        free(Y);
+        return INSHR_REF_E_EMPTY;
+    }
 
     /* equal-frequency boundaries t_j = Y[floor(j*M/K)] */
     uint32_t tkeys[255];
@@ -243,26 +253,42 @@ float inshr_ref_bf16_round(float x)
     return f;
 }
 
-int inshr_ref_quantize(const float *x, uint64_t n, const inshr_ref_config *cfg, uint16_t *sym,
-                       float *boundaries, float *codebook, uint32_t *out_idx, float *out_val,
-                       inshr_ref_qinfo *info)
+int inshr_ref_quantize_pooled(const float *x, uint64_t n, const uint32_t *pool, uint64_t n_pool,
+                              const inshr_ref_config *cfg, uint16_t *sym, float *boundaries,
+                              float *codebook, uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info)
 {
     if (!x || !cfg || n == 0 || n >= (1ull << 32)) return INSHR_REF_E_ARG;
+    if (pool && n_pool < n) return INSHR_REF_E_ARG;
     int rc = check_config(cfg);
     if (rc) return rc;
     sorted_images si;
     rc = make_sorted_images(x, n, &si);
     if (rc == INSHR_REF_OK)
-        rc = quantize_one(x, n, &si, cfg, sym, boundaries, codebook, out_idx, out_val, info);
+        rc = quantize_one(x, n, &si, pool, n_pool, cfg, sym, boundaries, codebook, out_idx, out_val, info);
     free_sorted_images(&si);
     return rc;
+}
+
+int inshr_ref_quantize(const float *x, uint64_t n, const inshr_ref_config *cfg, uint16_t *sym,
+                       float *boundaries, float *codebook, uint32_t *out_idx, float *out_val,
+                       inshr_ref_qinfo *info)
+{
+    return inshr_ref_quantize_pooled(x, n, NULL, 0, cfg, sym, boundaries, codebook, out_idx, out_val, info);
 }
 
 int inshr_ref_search(const float *x, uint64_t n, const inshr_ref_config *grid, uint32_t n_cfg,
                      double eps, uint32_t *best, uint8_t *feasible, inshr_ref_score *scores)
 {
+    return inshr_ref_search_pooled(x, n, NULL, 0, grid, n_cfg, eps, best, feasible, scores);
+}
+
+int inshr_ref_search_pooled(const float *x, uint64_t n, const uint32_t *pool, uint64_t n_pool,
+                            const inshr_ref_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
+                            uint8_t *feasible, inshr_ref_score *scores)
+{
     if (!x || !grid || !best || !feasible || n == 0 || n >= (1ull << 32) || n_cfg == 0)
         return INSHR_REF_E_ARG;
+    if (pool && n_pool < n) return INSHR_REF_E_ARG;
     for (uint32_t g = 0; g < n_cfg; g++) {
         int rc = check_config(&grid[g]);
         if (rc) return rc;
@@ -280,7 +306,7 @@ int inshr_ref_search(const float *x, uint64_t n, const inshr_ref_config *grid, u
     double best_sse = 0.0;
     for (uint32_t g = 0; g < n_cfg; g++) {
         inshr_ref_qinfo qi;
-        rc = quantize_one(x, n, &si, &grid[g], NULL, NULL, NULL, NULL, NULL, &qi);
+        rc = quantize_one(x, n, &si, pool, n_pool, &grid[g], NULL, NULL, NULL, NULL, NULL, &qi);
         if (rc) break;
         inshr_ref_score sc;
         sc.sse = qi.sse;

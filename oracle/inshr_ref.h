@@ -29,7 +29,8 @@ enum {
     INSHR_REF_E_ARG = -1,       /* null pointer, n == 0, n >= 2^32 */
     INSHR_REF_E_CONFIG = -2,    /* bits outside 1..8 or prune_ppm + outlier_ppm >= 1e6 */
     INSHR_REF_E_NONFINITE = -3, /* NaN or Inf in the input */
-    INSHR_REF_E_SHAPE = -5
+    INSHR_REF_E_SHAPE = -5,
+    INSHR_REF_E_EMPTY = -7      /* pooled thresholds leave the tensor without quantized values */
 };
 
 typedef struct {
@@ -76,6 +77,22 @@ float inshr_ref_bf16_round(float x);
  * sse and *feasible = 0.  scores may be NULL. */
 int inshr_ref_search(const float *x, uint64_t n, const inshr_ref_config *grid, uint32_t n_cfg,
                      double eps, uint32_t *best, uint8_t *feasible, inshr_ref_score *scores);
+
+/* Per-layer-type partition (Sec. 4.2, "Pruning": the same pruning fraction across all layers of a
+ * given type): the thresholds are order statistics of the pooled magnitudes of all tensors of the
+ * type, pool[0..n_pool) = their magnitude images in ascending order (this tensor's among them):
+ * tau_p = pool[floor(n_pool * prune_ppm / 1e6)], tau_o = pool[n_pool - 1 - floor(n_pool *
+ * outlier_ppm / 1e6)]; the tensor is then partitioned by them (pruned <=> mag < tau_p, protected
+ * <=> mag > tau_o) and its quantized values are binned as before.  The protected fraction of one
+ * tensor is no longer bounded by the configuration: out_idx / out_val need room for n entries.
+ * INSHR_REF_E_EMPTY when the thresholds leave the tensor no quantized value.  pool == NULL: the
+ * tensor alone. */
+int inshr_ref_quantize_pooled(const float *x, uint64_t n, const uint32_t *pool, uint64_t n_pool,
+                              const inshr_ref_config *cfg, uint16_t *sym, float *boundaries,
+                              float *codebook, uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info);
+int inshr_ref_search_pooled(const float *x, uint64_t n, const uint32_t *pool, uint64_t n_pool,
+                            const inshr_ref_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
+                            uint8_t *feasible, inshr_ref_score *scores);
 
 /* Decode symbols back to floats: 0 -> +0.0, 1 -> listed original value, 2+b -> codebook[b]. */
 int inshr_ref_dequantize(const uint16_t *sym, uint64_t n, uint32_t bits, const float *codebook,

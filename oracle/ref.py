@@ -70,13 +70,21 @@ class RefError(RuntimeError):
         self.code = code
 
 
-def quantize(x, cfg):
-    """cfg = (bits, prune_ppm, outlier_ppm[, bins]). Returns dict of numpy arrays and scalars."""
+def pool_of(tensors):
+    """Ascending magnitude images (uint32, -0.0 as +0.0) of all values of a group of tensors: the
+    pooled order statistics that per-layer-type thresholds are read from (Sec. 4.2)."""
+    mags = [np.ascontiguousarray(t, np.float32).ravel().view(np.uint32) & np.uint32(0x7fffffff) for t in tensors]
+    return np.sort(np.concatenate(mags), kind="stable")
+
+
+def quantize(x, cfg, pool=None):
+    """cfg = (bits, prune_ppm, outlier_ppm[, bins]). Returns dict of numpy arrays and scalars.
+    pool: pool_of(the tensors of x's layer type); thresholds are then the pooled quantiles."""
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     n = x.size
     o = cfg[2]
     K = bins_of(cfg)
-    cap = max(1, n * int(o) // 1000000)
+    cap = n if pool is not None else max(1, n * int(o) // 1000000)
     sym = np.empty(n, np.uint16)
     bnd = np.empty(max(K - 1, 1), np.float32)
     cb = np.empty(K, np.float32)
@@ -84,9 +92,11 @@ def quantize(x, cfg):
     ov = np.empty(cap, np.float32)
     info = QInfo()
     c = _config(cfg)
-    rc = lib().inshr_ref_quantize(_p(x, C.c_float), C.c_uint64(n), C.byref(c), _p(sym, C.c_uint16),
-                                  _p(bnd, C.c_float), _p(cb, C.c_float), _p(oi, C.c_uint32),
-                                  _p(ov, C.c_float), C.byref(info))
+    pool = None if pool is None else np.ascontiguousarray(pool, np.uint32)
+    rc = lib().inshr_ref_quantize_pooled(_p(x, C.c_float), C.c_uint64(n), _p(pool, C.c_uint32),
+                                         C.c_uint64(0 if pool is None else pool.size), C.byref(c),
+                                         _p(sym, C.c_uint16), _p(bnd, C.c_float), _p(cb, C.c_float),
+                                         _p(oi, C.c_uint32), _p(ov, C.c_float), C.byref(info))
     if rc:
         raise RefError(rc)
     no = int(info.n_outlier)
@@ -106,15 +116,19 @@ def bf16_round(x):
     return np.array([f(float(v)) for v in x.ravel()], np.float32).reshape(x.shape)
 
 
-def search(x, grid, eps):
-    """Returns (best, feasible, scores) with scores a list of dicts, one per grid entry."""
+def search(x, grid, eps, pool=None):
+    """Returns (best, feasible, scores) with scores a list of dicts, one per grid entry.
+    pool: as for quantize."""
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     g = _grid(grid)
     sc = (Score * len(grid))()
     best = C.c_uint32(0)
     feas = C.c_uint8(0)
-    rc = lib().inshr_ref_search(_p(x, C.c_float), C.c_uint64(x.size), g, C.c_uint32(len(grid)),
-                                C.c_double(eps), C.byref(best), C.byref(feas), sc)
+    pool = None if pool is None else np.ascontiguousarray(pool, np.uint32)
+    rc = lib().inshr_ref_search_pooled(_p(x, C.c_float), C.c_uint64(x.size), _p(pool, C.c_uint32),
+                                       C.c_uint64(0 if pool is None else pool.size), g,
+                                       C.c_uint32(len(grid)), C.c_double(eps), C.byref(best),
+                                       C.byref(feas), sc)
     if rc:
         raise RefError(rc)
     scores = [dict(sse=s.sse, sumsq=s.sumsq, n_pruned=s.n_pruned, n_outlier=s.n_outlier,

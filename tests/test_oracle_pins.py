@@ -473,3 +473,89 @@ def test_bfloat16_rounding_of_protected_values():
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     assert not (got.view(np.uint32) & 0xFFFF).any()
     assert np.all(np.abs(got.astype(np.float64) - x.astype(np.float64)) <= np.abs(x.astype(np.float64)) * 2.0 ** -8 + 2.0 ** -133)
+
+
+# ------------------------------------------------------------------------------------------
+# per-layer-type thresholds (Sec. 4.2): quantiles of the pooled magnitudes of a group of tensors
+# ------------------------------------------------------------------------------------------
+def _brute_pooled(xs, cfg):
+    """Pure Python: thresholds from the sorted list of all magnitudes of the group, then every
+    tensor partitioned by them and binned by equal-frequency ranks of its own quantized values."""
+    import struct
+    def mag(v):
+        return struct.unpack("<I", struct.pack("<f", abs(float(v)) + 0.0))[0]
+    pooled = sorted(mag(v) for x in xs for v in x)
+    N = len(pooled)
+    K = ref.bins_of(cfg)
+    tau_p = pooled[N * cfg[1] // 1000000]
+    tau_o = pooled[N - 1 - N * cfg[2] // 1000000]
+    out = []
+    for x in xs:
+        cls = [0 if mag(v) < tau_p else 1 if mag(v) > tau_o else 2 for v in x]
+        Y = sorted(float(v) + 0.0 for v, c in zip(x, cls) if c == 2)
+        if not Y:
+            out.append(None)
+            continue
+        t = [Y[j * len(Y) // K] for j in range(1, K)]
+        sym = [c if c < 2 else 2 + sum(1 for b in t if b <= float(v)) for v, c in zip(x, cls)]
+        out.append((tau_p, tau_o, sym, t))
+    return out
+
+
+def test_pooled_thresholds_brute_force_on_tiny_groups():
+    rng = np.random.default_rng(71)
+    for trial in range(30):
+        sizes = rng.integers(1, 40, int(rng.integers(1, 5)))
+        xs = [np.round(rng.standard_normal(int(n)) * rng.choice([0.01, 1.0, 30.0]), 2).astype(np.float32) for n in sizes]
+        if trial % 4 == 0:
+            xs[0][:] = 0.0                                   # a tensor of zeros inside the group
+        pool = ref.pool_of(xs)
+        for cfg in ((2, 0, 0), (3, 250000, 50000), (0, 400000, 100000, 6), (1, 100000, 300000)):
+            want = _brute_pooled(xs, cfg)
+            for x, w in zip(xs, want):
+                if w is None:
+                    with pytest.raises(ref.RefError) as e:
+                        ref.quantize(x, cfg, pool=pool)
+                    assert e.value.code == -7
+                    continue
+                r = ref.quantize(x, cfg, pool=pool)
+                assert (r["tau_prune_bits"], r["tau_outlier_bits"]) == w[:2]
+                assert r["sym"].tolist() == w[2]
+                assert r["boundaries"].tolist() == [np.float32(b) for b in w[3]]
+                assert r["n_pruned"] + r["n_outlier"] + r["n_kept"] == x.size
+
+
+def test_pooled_thresholds_are_numpy_order_statistics_of_the_concatenation():
+    rng = np.random.default_rng(72)
+    xs = [(s * rng.standard_t(4, n)).astype(np.float32) for s, n in ((0.02, 5000), (0.3, 1200), (0.001, 9000), (1.0, 1))]
+    allmag = np.sort(np.abs(np.concatenate(xs)))
+    N = allmag.size
+    pool = ref.pool_of(xs)
+    assert np.array_equal(pool.view(np.float32), allmag)
+    for cfg in ((4, 200000, 1000), (8, 0, 0), (0, 500000, 10000, 12)):
+        tp, to = allmag[N * cfg[1] // 1000000], allmag[N - 1 - N * cfg[2] // 1000000]
+        tot_p = tot_o = 0
+        for x in xs:
+            try:
+                r = ref.quantize(x, cfg, pool=pool)
+            except ref.RefError as e:
+                assert e.code == -7 and not np.any((np.abs(x) >= tp) & (np.abs(x) <= to))
+                tot_p += int(np.sum(np.abs(x) < tp)); tot_o += int(np.sum(np.abs(x) > to))
+                continue
+            assert np.float32(tp).view(np.uint32) == r["tau_prune_bits"]
+            assert np.float32(to).view(np.uint32) == r["tau_outlier_bits"]
+            assert r["n_pruned"] == int(np.sum(np.abs(x) < tp)) and r["n_outlier"] == int(np.sum(np.abs(x) > to))
+            assert np.array_equal(r["outlier_idx"], np.nonzero(np.abs(x) > to)[0])
+            tot_p += r["n_pruned"]; tot_o += r["n_outlier"]
+        # over the whole group the fractions are met up to ties: at most the asked number pruned / protected
+        assert tot_p <= N * cfg[1] // 1000000 and tot_o <= N * cfg[2] // 1000000
+        assert tot_p == int(np.sum(allmag < tp)) and tot_o == int(np.sum(allmag > to))
+
+
+def test_a_group_of_one_tensor_is_the_tensor_alone():
+    x = (0.02 * np.random.default_rng(73).standard_t(3, 20_001)).astype(np.float32)
+    grid = [(b, p, o) for b in (2, 5, 8) for p in (0, 100000, 400000) for o in (0, 1000)] + [(0, 100000, 1000, 12)]
+    assert ref.search(x, grid, 0.01) == ref.search(x, grid, 0.01, pool=ref.pool_of([x]))
+    for cfg in grid[::5]:
+        a, b = ref.quantize(x, cfg), ref.quantize(x, cfg, pool=ref.pool_of([x]))
+        assert all(np.array_equal(a[k], b[k]) for k in a)
