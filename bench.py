@@ -174,6 +174,8 @@ def main():
     ap.add_argument("--copy-yardstick", action="store_true",
                     help="run only a plain 1 GiB device copy (the kernel of known size that scales the "
                          "HBM traffic counters of rocprofv3 --pmc) and exit")
+    ap.add_argument("--pooled", action="store_true",
+                    help="also time search + quantize with thresholds shared per kind of layer (extra object)")
     ap.add_argument("--restore", action="store_true",
                     help="also time the restore side (reconstruct + dequantize of the checkpoint) after "
                          "the timed steps and report it as an extra object; needs 4 more bytes per value")
@@ -295,6 +297,29 @@ def main():
     if not args.no_validate:
         validation = validate_batch(torch, ctx, cur, cfgs, grid, eps, q_prev, q_cur, d_out, step)
         validation["lds_ordered"] = ctx.lds_ordered
+
+    pooled = None
+    if args.pooled and args.config == 4:
+        # thresholds per layer type: the tensors of one kind in all layers share their thresholds
+        # (the gate / up / down projections are kinds of their own: a group holds fewer than 2^32 values)
+        kinds = {}
+        groups = [kinds.setdefault(nm.split(".", 2)[2] if nm.startswith("layers.") else nm, len(kinds)) for nm in names]
+        for it in range(3):
+            if it == 1:
+                torch.cuda.synchronize()
+                ctx.profile(True)
+                t0 = time.perf_counter()
+            best_g, feas_g, sc_g = ctx.search(cur, grid, eps, want_scores=True, groups=groups)
+            caps = [int(sc_g[i * len(grid) + b].n_outlier) + 1 for i, b in enumerate(best_g)]
+            q_g = ctx.quantize(cur, [grid[b] for b in best_g], reuse_search=True, outlier_caps=caps)
+            ctx.sync()
+        torch.cuda.synchronize()
+        pdt = (time.perf_counter() - t0) / 2
+        pprof = ctx.profile_read()
+        ctx.profile(False)
+        pooled = {"groups": len(kinds), "ms_search_plus_quantize": round(pdt * 1e3, 3),
+                  "kernel_ms": {k: round(v[0] / 2, 4) for k, v in sorted(pprof.items()) if v[0] / 2 > 0.3}}
+        del q_g
 
     restore = None
     if args.restore:
@@ -472,6 +497,8 @@ def main():
     }
     if validation is not None:
         out["validation"] = validation
+    if pooled is not None:
+        out["pooled"] = pooled
     if restore is not None:
         out["restore"] = restore
     if sketch is not None:

@@ -113,6 +113,22 @@ int inshr_search(inshr_ctx *ctx, const inshr_tensor *tensors, uint32_t n_tensors
                  const inshr_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
                  uint8_t *feasible, inshr_score *scores);
 
+/* inshr_search with thresholds per layer type (Sec. 4.2, "Pruning": the same pruning fraction
+ * across all layers of a given type).  group: host array, one number per tensor; tensors with
+ * equal numbers form a group, and a group's prune / protect thresholds are the order statistics
+ * of its pooled magnitudes: tau_p = the value of rank floor(N * prune_ppm / 1e6) among all N values
+ * of the group, tau_o that of rank N - 1 - floor(N * outlier_ppm / 1e6).  Every tensor is then
+ * partitioned by its group's thresholds and binned, scored and chosen as in inshr_search (a group of
+ * one tensor is inshr_search).  Limits: a group holds fewer than 2^32 values; the first sweep of
+ * grouped tensors is never sampled.  A tensor's share of the protected values is no longer bounded
+ * by the fraction: size outlier buffers from the scores' n_outlier (inshr_quantize with
+ * INSHR_REUSE_SEARCH reports INSHR_E_CAPACITY otherwise).  INSHR_E_CONFIG when the thresholds of
+ * some (prune, protect) pair leave a tensor without quantized values (inshr_last_device_error
+ * names it).  Stand-alone inshr_quantize knows no groups. */
+int inshr_search_pooled(inshr_ctx *ctx, const inshr_tensor *tensors, const uint32_t *group,
+                        uint32_t n_tensors, const inshr_config *grid, uint32_t n_cfg, double eps,
+                        uint32_t *best, uint8_t *feasible, inshr_score *scores);
+
 typedef struct {
     /* caller-allocated device buffers */
     uint64_t *packed;       /* symbol stream, packed_words words (inshr_quantize_bound)          */

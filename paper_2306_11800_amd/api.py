@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
-           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_search_pooled", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_guided_search", "inshr_neighbourhood_search", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
@@ -144,6 +144,9 @@ def load_library() -> C.CDLL:
                                 C.POINTER(CCodes), C.POINTER(CDeltaOut), C.c_uint32]
     lib.inshr_delta_static.argtypes = [C.c_void_p, C.POINTER(CCodes), C.POINTER(CCodes),
                                        C.POINTER(CDeltaOut), C.c_uint32]
+    lib.inshr_search_pooled.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(C.c_uint32), C.c_uint32,
+                                        C.POINTER(CConfig), C.c_uint32, C.c_double, C.POINTER(C.c_uint32),
+                                        C.POINTER(C.c_uint8), C.POINTER(CScore)]
     lib.inshr_guided_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.c_double, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint8)]
@@ -351,7 +354,7 @@ class Context:
         if rc:
             text = self.lib.inshr_strerror(rc).decode()
             extra = self.lib.inshr_last_device_error(self.h).decode()
-            raise InshrError(rc, text + (f" ({extra})" if extra and rc in (-6, -7, -4) else ""))
+            raise InshrError(rc, text + (f" ({extra})" if extra and rc in (-6, -7, -4, -2, -1) else ""))
 
     def sync(self):
         self._check(self.lib.inshr_sync(self.h))
@@ -379,21 +382,31 @@ class Context:
         return b
 
     # -- inshr_search ---------------------------------------------------------------------
-    def search(self, tensors: Sequence[torch.Tensor], grid, eps: float, want_scores: bool = True):
+    def search(self, tensors: Sequence[torch.Tensor], grid, eps: float, want_scores: bool = True,
+               groups: Optional[Sequence[int]] = None):
         """Returns (best[list of int], feasible[list of int], scores or None) where scores is a
-        ctypes array of CScore of length len(tensors) * len(grid), row-major by tensor."""
+        ctypes array of CScore of length len(tensors) * len(grid), row-major by tensor.
+        groups: one number per tensor; tensors with equal numbers share their thresholds
+        (inshr_search_pooled)."""
         ta = _tensor_array(tensors)
         ga = _config_array(grid)
         nT, nC = len(tensors), len(grid)
         best = (C.c_uint32 * nT)()
         feas = (C.c_uint8 * nT)()
         scores = (CScore * (nT * nC))() if want_scores else None
-        self._check(self.lib.inshr_search(self.h, ta, nT, ga, nC, float(eps), best, feas, scores))
+        if groups is not None:
+            if len(groups) != nT:
+                raise ValueError("one group number per tensor")
+            ga_ = (C.c_uint32 * nT)(*[int(g) for g in groups])
+            self._check(self.lib.inshr_search_pooled(self.h, ta, ga_, nT, ga, nC, float(eps), best, feas, scores))
+        else:
+            self._check(self.lib.inshr_search(self.h, ta, nT, ga, nC, float(eps), best, feas, scores))
         return list(best), list(feas), scores
 
     # -- inshr_quantize -------------------------------------------------------------------
     def quantize(self, tensors: Sequence[torch.Tensor], cfgs, reuse_search: bool = False,
-                 out: Optional[List[Quantized]] = None, protect_bf16: bool = False) -> List[Quantized]:
+                 out: Optional[List[Quantized]] = None, protect_bf16: bool = False,
+                 outlier_caps: Optional[Sequence[int]] = None) -> List[Quantized]:
         """`out` may carry the list an earlier call returned for tensors of the same sizes; its
         device buffers are then written again.  When that call sized them for the largest
         configuration (8 bits and the largest protect fraction in use), nothing is marshalled
@@ -413,6 +426,8 @@ class Context:
         for i, (t, cfg) in enumerate(zip(tensors, cfgs)):
             n = t.numel()
             words, cap = self._bound(n, ca[i], cfg)
+            if outlier_caps is not None:  # (after a search with shared thresholds a tensor's share
+                cap = int(outlier_caps[i])  # of the protected values is not bounded by the fraction)
             e = qa[i]
             if out is not None:
                 q = out[i]

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 using namespace inshr;
@@ -250,11 +251,33 @@ int build_grid(const inshr_config *grid, uint32_t n_cfg, double eps, GridDesc &g
 // light: thresholds, class counts and the second-level table only (for the sketch quantizer, which
 // brings its own bins and takes the protected counts per tile in its own sweep); the state is then
 // not offered to INSHR_REUSE_SEARCH.
+// group: NULL, or one number per tensor; tensors with equal numbers share their thresholds, which
+// are then order statistics of the group's pooled magnitudes (Sec. 4.2, per-layer-type pruning).
 int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const inshr_config *grid,
-               uint32_t n_cfg, double eps, bool light = false)
+               uint32_t n_cfg, double eps, bool light = false, const uint32_t *group = nullptr)
 {
     c->have_search = false;
     if (!tensors || !grid || nT == 0) return INSHR_E_ARG;
+    // leader of every tensor's group and the group's size
+    std::vector<u32> leader(nT);
+    std::vector<u64> n_pool(nT, 0);
+    std::vector<u32> members(nT, 0);
+    bool any_pooled = false;
+    {
+        std::unordered_map<uint32_t, u32> first;
+        for (uint32_t t = 0; t < nT; t++) {
+            leader[t] = group ? first.emplace(group[t], t).first->second : t;
+            n_pool[leader[t]] += tensors[t].n;
+            members[leader[t]]++;
+        }
+        for (uint32_t t = 0; t < nT; t++) {
+            if (members[leader[t]] > 1) any_pooled = true;
+            if (n_pool[leader[t]] >= (1ull << 32)) {
+                c->last_err = "a group of tensors that share thresholds holds 2^32 values or more";
+                return INSHR_E_ARG;
+            }
+        }
+    }
     GridDesc g;
     int rc = build_grid(grid, n_cfg, eps, g);
     if (rc) return rc;
@@ -282,8 +305,13 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
             td[t].tile0 = tile;
             const u64 padded = (tensors[t].n + TILE - 1) / TILE * TILE;
             td[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
-            td[t].sampled = (c->sample_min_n && tensors[t].n >= c->sample_min_n && tensors[t].n < (1ull << 31))
-                                ? 1u : 0u;
+            td[t].leader = leader[t];
+            td[t].pooled = members[leader[t]] > 1 ? 1u : 0u;
+            td[t].n_pool = n_pool[leader[t]];
+            // (a sampled first sweep predicts where a tensor's own order statistics lie; a group's
+            // come from the exact histograms of all its tensors)
+            td[t].sampled = (!td[t].pooled && c->sample_min_n && tensors[t].n >= c->sample_min_n &&
+                             tensors[t].n < (1ull << 31)) ? 1u : 0u;
             any_sampled = any_sampled || td[t].sampled;
             c->batch_sampled.resize(nT);
             c->batch_sampled[t] = (char)td[t].sampled;
@@ -341,7 +369,9 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         const size_t o_gcn = cv.take((size_t)nT * 2 * MAX_EDGES * 4);
         const size_t o_gsx = cv.take((size_t)nT * 2 * MAX_EDGES * 8);
         const size_t o_to = cv.take((size_t)total_tiles * MAX_FRAC * 4);
+        const size_t o_ph1 = cv.take(any_pooled ? (size_t)nT * L1_BINS * 4 : 0);
         const size_t zero_end = cv.off; // [o_ts, zero_end) is cleared before the sweeps
+        const size_t o_psel = cv.take(any_pooled ? (size_t)nT * 2 * SEL_WORDS * 4 : 0);
         const size_t o_tab = cv.take((size_t)nT * COARSE * 4);
         const size_t o_ut = cv.take((size_t)units * 16 * 4);
         const size_t o_bi = cv.take((size_t)nT * L2_BINS * 4);
@@ -417,6 +447,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         bt.n_bucket_blocks = c->n_cu * 4;
         bt.lds_ordered = c->lds_ordered;
         bt.any_sampled = any_sampled;
+        bt.any_pooled = any_pooled;
         bt.force_miss = c->sample_force_miss;
         bt.nT = (int)nT;
         bt.n_wg = n_wg;
@@ -426,6 +457,8 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         Bufs &B = bt.bufs;
         B.ts = (TState *)(db + o_ts);
         B.hist1 = (u32 *)(db + o_h1);
+        B.pool_h1 = (u32 *)(db + o_ph1);
+        B.pool_sel = (u32 *)(db + o_psel);
         B.hist2 = (u32 *)(db + o_h2);
         B.table2 = (u32 *)(db + o_tab);
         B.unit_off = (const u64 *)(db + o_us);
@@ -486,6 +519,12 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         if (hts[t].nonfinite) return INSHR_E_NONFINITE;
     }
     for (uint32_t t = 0; t < nT; t++) {
+        if (any_pooled && (hts[t].internal_err & 32u)) { // (a tensor alone always keeps the value of rank P)
+            c->last_err = "the shared thresholds leave tensor " + std::to_string(t) + " without quantized values";
+            return INSHR_E_CONFIG;
+        }
+    }
+    for (uint32_t t = 0; t < nT; t++) {
         if (!hts[t].pool_overflow) continue;
         // some wave gathered more keys than its share of a pool holds: larger pools, once more
         const uint32_t full = TILE / (BLOCK / 64);
@@ -497,7 +536,7 @@ int run_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t nT, const ins
         if (getenv("INSHR_SAMPLE_DEBUG"))
             fprintf(stderr, "inshr_search: gather pools too small (tensor %u, code %u): again with %u keys per wave and tile\n",
                     t, hts[t].pool_overflow, c->pool_wcap);
-        return run_search(c, tensors, nT, grid, n_cfg, eps, light);
+        return run_search(c, tensors, nT, grid, n_cfg, eps, light, group);
     }
     if (getenv("INSHR_SAMPLE_DEBUG")) { // how many sampled first sweeps had to be repeated exactly
         uint32_t n_sampled = 0, n_redo = 0;
@@ -670,6 +709,23 @@ int inshr_search(inshr_ctx *c, const inshr_tensor *tensors, uint32_t n_tensors,
         static_assert(sizeof(Score) == sizeof(inshr_score), "score layout");
         memcpy(scores, hsc, sizeof(Score) * (size_t)n_tensors * n_cfg);
     }
+    return INSHR_OK;
+}
+
+int inshr_search_pooled(inshr_ctx *c, const inshr_tensor *tensors, const uint32_t *group,
+                        uint32_t n_tensors, const inshr_config *grid, uint32_t n_cfg, double eps,
+                        uint32_t *best, uint8_t *feasible, inshr_score *scores)
+{
+    if (!c || !best || !feasible || !group) return INSHR_E_ARG;
+    int rc = run_search(c, tensors, n_tensors, grid, n_cfg, eps, false, group);
+    if (rc) return rc;
+    const TState *hts = (const TState *)c->h_down.p;
+    const Score *hsc = (const Score *)((const char *)c->h_down.p + sizeof(TState) * n_tensors);
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        best[t] = hts[t].best;
+        feasible[t] = (uint8_t)hts[t].feasible;
+    }
+    if (scores) memcpy(scores, hsc, sizeof(Score) * (size_t)n_tensors * n_cfg);
     return INSHR_OK;
 }
 

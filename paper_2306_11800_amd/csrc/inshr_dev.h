@@ -170,6 +170,11 @@ struct TDesc {           // one tensor of a batch
     u32 aligned16;       // data pointer is 16-byte aligned (float4 loads allowed)
     u32 sampled;         // sweep 1 reads one tile in SAMPLE_RATE (large tensors): its histogram only
                          // shapes the second-level table and predicts where the thresholds lie
+    // thresholds per layer type (Sec. 4.2): the tensors of a group share the thresholds, which are
+    // order statistics of the group's pooled magnitudes
+    u32 leader;          // first tensor of this tensor's group (itself when it stands alone)
+    u32 pooled;          // the group has more than one tensor
+    u64 n_pool;          // elements of the whole group
 };
 constexpr int SAMPLE_RATE = 8;
 
@@ -209,7 +214,10 @@ struct TState {
     u32 mag_min, mag_max;              // smallest / largest magnitude image (sampled first sweep only:
                                        // the thresholds of rank 0 and n - 1 are these)
     u32 thr_bucket[MAX_THR];
-    u64 thr_res[MAX_THR];              // rank inside the bucket, magnitude order, zeros first
+    u64 thr_res[MAX_THR];              // rank inside the bucket, magnitude order, zeros first (for a pooled
+                                       // tensor: inside the group's bucket)
+    u32 pool_expect[MAX_THR];          // pooled tensor: keys of the whole group in the threshold's bucket
+    u64 pool_zero;                     // group leader: exact zeros of the whole group
     u32 thr_mag[MAX_THR];              // result: magnitude image of the threshold
     u64 thr_lt_neg[MAX_THR], thr_lt_pos[MAX_THR]; // #{mag < tau} by sign
     u64 thr_gt_neg[MAX_THR], thr_gt_pos[MAX_THR]; // #{mag > tau} by sign

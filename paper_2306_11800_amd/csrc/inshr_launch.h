@@ -7,11 +7,14 @@ namespace inshr {
 constexpr int CURSOR_STRIDE = L2_BINS + 64; // per-tensor stride of the gather cursors
 constexpr int TGT_STRIDE = 4096;            // per-tensor stride of boundary targets (15 * NBT fits)
 constexpr int SQ_STRIDE = MAX_FRAC + 1;     // partial sums of squares per (workgroup, tensor) unit
+constexpr int SEL_WORDS = MAX_THR * 1024;    // a tensor's selection histograms ([slot][sign][512])
 constexpr int CB_STRIDE = 256;              // codebook entries per configuration
 
 struct Bufs { // device pointers, indexed by the tensor's position in the batch unless noted
     TState *ts;
     u32 *hist1;     // [nT][32768]
+    u32 *pool_h1;   // [nT][32768] row of a group's leader: the first-level histograms of the group, added up
+    u32 *pool_sel;  // [nT][2][SEL_WORDS] row of a group's leader: the group's selection histograms, per pass
     u32 *table2;    // [nT][4096]
     const u64 *unit_off; // [units] start of each (workgroup, tensor) unit's share of a gather pool (u32 units)
     const u32 *unit_capw; // [units] one wave's share of it: wave w of the unit owns
@@ -76,6 +79,7 @@ struct Batch {
     bool light;          // thresholds and class counts only: no boundaries, no scores (the sketch
                          // quantizer brings its own bins)
     bool any_sampled;    // some tensor's sweep 1 is sampled
+    bool any_pooled;     // some tensors share their thresholds (TDesc::pooled)
     bool force_miss;     // (tests) every sampled tensor is sent through the exact sweeps again
     u32 n_pairs, n_cfg;
     u64 n_tiles;

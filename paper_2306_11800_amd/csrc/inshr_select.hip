@@ -281,6 +281,37 @@ __device__ inline void make_buckets(TState *st, u32 n_thr, const u32 *s_j, const
     st->n_buckets = nb;
 }
 
+// Thresholds per layer type (Sec. 4.2): the first-level histograms and the zero counts of a group's
+// tensors, added up in the row of the group's leader (cleared beforehand).
+__global__ __launch_bounds__(BLOCK) void k_pool_sum(const TDesc *__restrict__ td, Bufs B)
+{
+    const int t = blockIdx.x;
+    const TDesc d = td[t];
+    if (!d.pooled) return;
+    const u32 *h1 = B.hist1 + (size_t)t * L1_BINS;
+    u32 *ph = B.pool_h1 + (size_t)d.leader * L1_BINS;
+    for (u32 i = threadIdx.x; i < (u32)L1_BINS; i += BLOCK) {
+        const u32 c = h1[i];
+        if (c) atomicAdd(&ph[i], c);
+    }
+    if (threadIdx.x == 0)
+        atomicAdd((unsigned long long *)&B.ts[d.leader].pool_zero, (unsigned long long)B.ts[t].n_zero);
+}
+
+// magnitude bin of a rank: last j in [0, 16384) with A[j] <= rank (A: exclusive prefix of the counts)
+__device__ __forceinline__ u32 magbin_of_rank(const u32 *A, u64 rank)
+{
+    int lo = 0, hi = L1_MAGBINS;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if ((u64)A[mid] > rank)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    return (u32)(lo > 0 ? lo - 1 : 0);
+}
+
 // REDO: only the tensors whose sampled sweep 1 mispredicted (their histogram is exact now).
 template <bool REDO>
 __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
@@ -302,6 +333,24 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
     const bool sampled = !REDO && td[t].sampled != 0u;
     const u32 scale = sampled ? (u32)SAMPLE_RATE : 1u; // a sampled histogram stands for the whole
     const u32 *h1 = B.hist1 + (size_t)t * L1_BINS;
+    const bool pooled = td[t].pooled != 0u; // (never sampled)
+    if (pooled) {
+        // the thresholds are order statistics of the group: their bins and the ranks inside them
+        // come from the group's histogram; everything else below is the tensor's own
+        const u32 *ph = B.pool_h1 + (size_t)td[t].leader * L1_BINS;
+        for (int j = tid; j < L1_MAGBINS; j += BLOCK) A[j] = ph[L1_MAGBINS - 1 - j] + ph[L1_MAGBINS + j];
+        __syncthreads();
+        const u32 gtotal = block_excl_scan(A, A, L1_MAGBINS, tmp);
+        if (tid == 0 && (u64)gtotal != td[t].n_pool) atomicOr(&st->internal_err, 1u);
+        if (tid < gd->n_p + gd->n_o) {
+            const u64 R = threshold_rank(gd, tid, td[t].n_pool);
+            const u32 j = magbin_of_rank(A, R);
+            s_j[tid] = j;
+            s_res[tid] = R - (u64)A[j];
+            st->pool_expect[tid] = A[j + 1] - A[j];
+        }
+        __syncthreads();
+    }
     for (int j = tid; j < L1_MAGBINS; j += BLOCK) {
         u32 cn = h1[L1_MAGBINS - 1 - j] * scale, cp = h1[L1_MAGBINS + j] * scale;
         A[j] = cn + cp;
@@ -338,9 +387,9 @@ __global__ __launch_bounds__(BLOCK) void k_plan1(const TDesc *__restrict__ td,
             return (u32)(lo > 0 ? lo - 1 : 0);
         };
         if (!sampled) {
-            const u32 j = bin_of(R);
+            const u32 j = pooled ? s_j[tid] : bin_of(R);
             s_j[tid] = s_jlo[tid] = s_jhi[tid] = j;
-            s_res[tid] = R - (u64)A[j];
+            if (!pooled) s_res[tid] = R - (u64)A[j];
             s_bn[tid] = Bn[j];
             s_bp[tid] = A[j] - Bn[j];
             s_cn[tid] = h1[L1_MAGBINS - 1 - j];
@@ -574,7 +623,7 @@ __global__ __launch_bounds__(BLOCK) void k_plan1b(const TDesc *__restrict__ td,
 // exact thresholds from the gathered buckets
 // ------------------------------------------------------------------------------------------
 constexpr int TSEL = 1024;
-constexpr int SEL_HIST = MAX_THR * 1024; // words of a tensor's selection histograms ([slot][sign][512])
+constexpr int SEL_HIST = SEL_WORDS; // words of a tensor's selection histograms ([slot][sign][512])
 
 // The gathered keys of a tensor lie in 16 fragments (one per wave) per (workgroup, tensor) unit,
 // all buckets mixed.  Every threshold wants the k-th smallest magnitude among the keys of its
@@ -588,12 +637,17 @@ constexpr int SEL_HIST = MAX_THR * 1024; // words of a tensor's selection histog
 // needed).  After each pass one workgroup per tensor picks the bins (wave q scans threshold q); the
 // histograms are kept per sign, so the counts of the classes fall out of them: keys below = bins
 // below the chosen one in pass 1 + digits below the chosen one in pass 2.
-__global__ __launch_bounds__(TSEL) void k_thr_setup(Bufs B)
+__global__ __launch_bounds__(TSEL) void k_thr_setup(const TDesc *__restrict__ td, Bufs B)
 {
     const int t = blockIdx.x;
     TState *st = B.ts + t;
     u32 *gh = B.hist1 + (size_t)t * L1_BINS;
     for (u32 i = threadIdx.x; i < (u32)SEL_HIST; i += TSEL) gh[i] = 0u;
+    const bool pooled = td[t].pooled != 0u;
+    if (pooled && td[t].leader == (u32)t) { // the group's histograms of both passes
+        u32 *ps = B.pool_sel + (size_t)t * 2 * SEL_HIST;
+        for (u32 i = threadIdx.x; i < 2u * (u32)SEL_HIST; i += TSEL) ps[i] = 0u;
+    }
     if (threadIdx.x != 0) return;
     const u32 n_thr = st->n_thr;
     for (u32 b = 0; b < (u32)MAX_THR; b++) st->sel_nmem[b] = 0u;
@@ -605,8 +659,9 @@ __global__ __launch_bounds__(TSEL) void k_thr_setup(Bufs B)
         const u32 bq = st->thr_bucket[q];
         if (bq == NO_BUCKET) continue; // rank 0 or n - 1 of a tensor whose first sweep was sampled
         const u32 mb = st->bucket_magbin[bq];
-        const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
-        const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
+        // (a pooled tensor: rank, zeros and bucket population of the whole group)
+        const u64 zeros = (mb == 0u) ? (pooled ? B.ts[td[t].leader].pool_zero : st->n_zero) : 0ull;
+        const u64 expect = (pooled ? (u64)st->pool_expect[q] : (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq]) - zeros;
         const u64 res = st->thr_res[q];
         if (res < zeros) continue; // the threshold is 0
         if (res - zeros >= expect) {
@@ -690,9 +745,13 @@ __global__ __launch_bounds__(TSEL) void k_thr_count(const TDesc *__restrict__ td
     }
     __syncthreads();
     u32 *gh = B.hist1 + (size_t)t * L1_BINS;
+    u32 *ps = td[t].pooled ? B.pool_sel + ((size_t)td[t].leader * 2 + ROUND) * SEL_HIST : nullptr;
     for (u32 i = tid; i < n_slots; i += TSEL) {
         const u32 v = hist[i];
-        if (v) atomicAdd(&gh[i], v);
+        if (v) {
+            atomicAdd(&gh[i], v);
+            if (ps) atomicAdd(&ps[i], v); // the group's histogram chooses, the tensor's own counts
+        }
     }
 }
 
@@ -704,28 +763,34 @@ __global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td,
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 n_thr = st->n_thr;
     u32 *gh = B.hist1 + (size_t)t * L1_BINS;
+    const bool pooled = td[t].pooled != 0u;
+    const u32 *ps = pooled ? B.pool_sel + ((size_t)td[t].leader * 2 + ROUND) * SEL_HIST : gh;
     if (wave < n_thr && st->sel_want[wave] != 0xFFFFFFFFu) { // wave q scans the histogram of threshold q
         const u32 q = wave;
-        const u32 *hq = gh + (ROUND == 0 ? st->thr_bucket[q] : q) * 1024u;
+        const u32 slot = ROUND == 0 ? st->thr_bucket[q] : q;
+        const u32 *hq = gh + slot * 1024u;  // the tensor's own keys: they are counted
+        const u32 *hs = ps + slot * 1024u;  // the keys the rank refers to (the group's when pooled): they choose
         const u32 k = st->sel_k[q];
-        u32 ln[8], lp[8], sn = 0, sp = 0; // 8 bins per lane
+        u32 ln[8], lp[8], gs[8], sn = 0, sp = 0, sg = 0; // 8 bins per lane
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             ln[j] = hq[lane * 8u + j];
             lp[j] = hq[512u + lane * 8u + j];
+            gs[j] = pooled ? hs[lane * 8u + j] + hs[512u + lane * 8u + j] : ln[j] + lp[j];
             sn += ln[j];
             sp += lp[j];
+            sg += gs[j];
         }
-        const u32 incn = wave_incl_scan(sn), incp = wave_incl_scan(sp);
+        const u32 incn = wave_incl_scan(sn), incp = wave_incl_scan(sp), incg = wave_incl_scan(sg);
         const u32 totn = __builtin_amdgcn_readlane(incn, 63), totp = __builtin_amdgcn_readlane(incp, 63);
-        u32 bn = incn - sn, bp = incp - sp; // keys in the bins before this lane's
+        u32 bn = incn - sn, bp = incp - sp, bg = incg - sg; // keys in the bins before this lane's
         if (ROUND == 0 && lane == 63u) st->sel_seen[q] = incn + incp;
-        if (k >= bn + bp && k < incn + incp) {
+        if (k >= bg && k < incg) {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                if (k >= bn + bp && k < bn + bp + ln[j] + lp[j]) {
+                if (k >= bg && k < bg + gs[j]) {
                     const u32 digit = lane * 8u + j;
-                    st->sel_k[q] = k - (bn + bp);
+                    st->sel_k[q] = k - bg;
                     st->sel_cn[q][0] += bn;                   // below the chosen bin, by sign
                     st->sel_cn[q][1] += bp;
                     st->sel_cn[q][2] += totn - bn - ln[j];    // above it
@@ -739,6 +804,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td,
                 }
                 bn += ln[j];
                 bp += lp[j];
+                bg += gs[j];
             }
         }
     }
@@ -761,6 +827,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td,
         }
         const u32 mb = st->bucket_magbin[bq];
         const u64 zeros = (mb == 0u) ? st->n_zero : 0ull;
+        const u64 zeros_ranked = (mb == 0u && pooled) ? B.ts[td[t].leader].pool_zero : zeros;
         u32 tau = 0u;
         // keys of the bucket below / above the threshold, by sign (the zeros were not gathered)
         u32 cn[4] = {0u, 0u, st->bucket_cnt_neg[bq], (u32)(st->bucket_cnt_pos[bq] - zeros)};
@@ -769,7 +836,7 @@ __global__ __launch_bounds__(TSEL) void k_thr_pick(const TDesc *__restrict__ td,
             for (int i = 0; i < 4; i++) cn[i] = st->sel_cn[q][i];
             const u64 expect = (u64)st->bucket_cnt_neg[bq] + st->bucket_cnt_pos[bq] - zeros;
             if ((u64)st->sel_seen[q] != expect) atomicOr(&st->internal_err, 4u);
-        } else if (st->thr_res[q] >= zeros) {
+        } else if (st->thr_res[q] >= zeros_ranked) {
             return; // (rank beyond the bucket: the error bit is set)
         }
         const u64 n = td[t].n, n_neg = st->n_neg, n_pos = n - n_neg;
@@ -824,7 +891,12 @@ __global__ __launch_bounds__(BLOCK) void k_plan2(const TDesc *__restrict__ td,
         sMn[tid] = Mn;
         sPP[tid] = Pn + Pp;
         sM[tid] = Mn + Mp;
-        if (Mn + Mp == 0ull || Mn > n || Mp > n) atomicOr(&st->internal_err, 32u);
+        if (Mn + Mp == 0ull || Mn > n || Mp > n) {
+            // (shared thresholds can leave a tensor without quantized values: reported, and the
+            // tensor's gathered keys are not processed)
+            atomicOr(&st->internal_err, 32u);
+            atomicOr(&st->pool_overflow, 8u);
+        }
     }
     for (u32 i = tid; i < nb2; i += BLOCK) binfo[i] = 0u;
     __syncthreads();
@@ -1664,6 +1736,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
     if (e) return e;
     const Bufs &B = bt.bufs;
     PROF("k_hist1", s, (k_hist<1, false><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
+    if (bt.any_pooled) PROF("k_pool_sum", s, k_pool_sum<<<bt.nT, BLOCK, 0, s>>>(bt.td, B));
     PROF("k_plan1", s, k_plan1<false><<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
     PROF("k_hist2", s, (k_hist<2, false><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
     if (bt.any_sampled) {
@@ -1674,7 +1747,7 @@ hipError_t launch_select(const Batch &bt, hipStream_t s)
         PROF("k_plan1_redo", s, k_plan1<true><<<bt.nT, BLOCK, SM_PLAN1, s>>>(bt.td, bt.gd, B));
         PROF("k_hist2_redo", s, (k_hist<2, true><<<bt.n_wg, BLOCK, 0, s>>>(bt.td, bt.nT, bt.wg_tile0, bt.wg_fu0, B)));
     }
-    PROF("k_thr_setup", s, k_thr_setup<<<bt.nT, TSEL, 0, s>>>(B));
+    PROF("k_thr_setup", s, k_thr_setup<<<bt.nT, TSEL, 0, s>>>(bt.td, B));
     PROF("k_thr_count", s, k_thr_count<0><<<bt.n_units, TSEL, 0, s>>>(bt.td, bt.fu_tensor, B));
     PROF("k_thr_pick", s, k_thr_pick<0><<<bt.nT, TSEL, 0, s>>>(bt.td, B));
     PROF("k_thr_count", s, k_thr_count<1><<<bt.n_units, TSEL, 0, s>>>(bt.td, bt.fu_tensor, B));
