@@ -339,6 +339,118 @@ int inshr_ref_search_pooled(const float *x, uint64_t n, const uint32_t *pool, ui
     return INSHR_REF_OK;
 }
 
+int inshr_ref_quantize_sens(const float *x, const float *g, uint64_t n, const inshr_ref_config *cfg,
+                            int prune_by_sensitivity, uint16_t *sym, float *boundaries, float *codebook,
+                            uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info,
+                            uint32_t *tau_outlier_sens_bits)
+{
+    if (!x || !g || !cfg || n == 0 || n >= (1ull << 32)) return INSHR_REF_E_ARG;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    const uint32_t K = bins_of(cfg);
+    const uint64_t n_p = n * (uint64_t)cfg->prune_ppm / 1000000ull;
+    const uint64_t n_o = n * (uint64_t)cfg->outlier_ppm / 1000000ull;
+    uint32_t *mag = (uint32_t *)malloc(n * 4), *sc = (uint32_t *)malloc(n * 4);
+    uint32_t *A = (uint32_t *)malloc(n * 4), *S = (uint32_t *)malloc(n * 4), *Y = (uint32_t *)malloc(n * 4);
+    uint8_t *cls = (uint8_t *)malloc(n);
+    rc = (mag && sc && A && S && Y && cls) ? INSHR_REF_OK : INSHR_REF_E_ARG;
+    for (uint64_t i = 0; rc == INSHR_REF_OK && i < n; i++) {
+        const uint32_t b = canon_bits(x[i]);
+        volatile float prod = g[i] * x[i]; /* one fp32 multiplication, rounded to fp32 */
+        const uint32_t sb = mag_of_bits(canon_bits(prod));
+        if ((b & 0x7f800000u) == 0x7f800000u || (sb & 0x7f800000u) == 0x7f800000u ||
+            (canon_bits(g[i]) & 0x7f800000u) == 0x7f800000u)
+            rc = INSHR_REF_E_NONFINITE;
+        mag[i] = A[i] = mag_of_bits(b);
+        sc[i] = S[i] = sb; /* the bit image of a non-negative float orders like the float */
+    }
+    if (rc == INSHR_REF_OK) {
+        qsort(A, n, 4, cmp_u32);
+        qsort(S, n, 4, cmp_u32);
+        const uint32_t tau_om = A[n - 1 - n_o], tau_os = S[n - 1 - n_o];
+        const uint32_t tau_p = prune_by_sensitivity ? S[n_p] : A[n_p];
+        uint64_t M = 0, n_pruned = 0, n_outlier = 0;
+        for (uint64_t i = 0; i < n; i++) {
+            const uint32_t m = prune_by_sensitivity ? sc[i] : mag[i];
+            if (mag[i] > tau_om || sc[i] > tau_os) {
+                cls[i] = 1;
+                if (out_idx) out_idx[n_outlier] = (uint32_t)i;
+                if (out_val) out_val[n_outlier] = x[i];
+                n_outlier++;
+            } else if (m < tau_p) {
+                cls[i] = 0;
+                n_pruned++;
+            } else {
+                cls[i] = 2;
+                Y[M++] = key_of_bits(canon_bits(x[i]));
+            }
+        }
+        if (M == 0) rc = INSHR_REF_E_EMPTY;
+        if (rc == INSHR_REF_OK) {
+            qsort(Y, M, 4, cmp_u32);
+            uint32_t tkeys[255];
+            for (uint32_t j = 1; j < K; j++) tkeys[j - 1] = Y[(uint64_t)j * M / K];
+            double bsum[256];
+            uint64_t bcnt[256];
+            for (uint32_t k = 0; k < K; k++) {
+                bsum[k] = 0.0;
+                bcnt[k] = 0;
+            }
+            for (uint64_t i = 0; i < n; i++) {
+                uint16_t s = cls[i];
+                if (cls[i] == 2) {
+                    const uint32_t bin = bin_of_key(tkeys, K - 1, key_of_bits(canon_bits(x[i])));
+                    s = (uint16_t)(2 + bin);
+                    bsum[bin] += (double)x[i];
+                    bcnt[bin]++;
+                }
+                if (sym) sym[i] = s;
+            }
+            float cb[256];
+            for (uint32_t k = 0; k < K; k++) {
+                if (bcnt[k])
+                    cb[k] = (float)(bsum[k] / (double)bcnt[k]);
+                else
+                    cb[k] = (k == 0) ? float_of_key(Y[0]) : float_of_key(tkeys[k - 1]);
+            }
+            double sse = 0.0, sumsq = 0.0;
+            for (uint64_t i = 0; i < n; i++) {
+                const double xd = (double)x[i];
+                sumsq += xd * xd;
+                if (cls[i] == 0) {
+                    sse += xd * xd;
+                } else if (cls[i] == 2) {
+                    const uint32_t bin = bin_of_key(tkeys, K - 1, key_of_bits(canon_bits(x[i])));
+                    const double e = xd - (double)cb[bin];
+                    sse += e * e;
+                }
+            }
+            if (boundaries)
+                for (uint32_t j = 0; j + 1 < K; j++) boundaries[j] = float_of_key(tkeys[j]);
+            if (codebook)
+                for (uint32_t k = 0; k < K; k++) codebook[k] = cb[k];
+            if (info) {
+                info->n_pruned = n_pruned;
+                info->n_outlier = n_outlier;
+                info->n_kept = M;
+                info->sym_bits = inshr_ref_symbol_bits(K);
+                info->tau_prune_bits = tau_p;
+                info->tau_outlier_bits = tau_om;
+                info->sse = sse;
+                info->sumsq = sumsq;
+            }
+            if (tau_outlier_sens_bits) *tau_outlier_sens_bits = tau_os;
+        }
+    }
+    free(mag);
+    free(sc);
+    free(A);
+    free(S);
+    free(Y);
+    free(cls);
+    return rc;
+}
+
 int inshr_ref_dequantize(const uint16_t *sym, uint64_t n, uint32_t bits, const float *codebook,
                          const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,
                          float *xhat)

@@ -94,6 +94,24 @@ int inshr_ref_search_pooled(const float *x, uint64_t n, const uint32_t *pool, ui
                             const inshr_ref_config *grid, uint32_t n_cfg, double eps, uint32_t *best,
                             uint8_t *feasible, inshr_ref_score *scores);
 
+/* Partition by magnitude and sensitivity (Sec. 4.1, 4.2).  g[i] is the gradient of the loss with
+ * respect to x[i]; the sensitivity score is s_i = |g_i * x_i|, one fp32 multiplication.
+ *   protected <=> |x_i| > tau_om  or  s_i > tau_os, where tau_om and tau_os are the values of rank
+ *                 n - 1 - floor(n * outlier_ppm / 1e6) of the magnitudes and of the scores ("a small
+ *                 fraction of both the highest magnitude and sensitivity parameters");
+ *   pruned    <=> not protected and m_i < tau_p, where m is the pruning metric (the magnitudes, or
+ *                 the scores when prune_by_sensitivity != 0) and tau_p its value of rank
+ *                 floor(n * prune_ppm / 1e6);
+ *   everything else is quantized: bins, centres, symbols and errors as in inshr_ref_quantize, over
+ *   these values.  info->tau_prune_bits is the bit image of tau_p (a magnitude image or a score),
+ *   tau_outlier_bits that of tau_om; *tau_outlier_sens_bits receives that of tau_os.
+ * out_idx / out_val need room for n entries.  INSHR_REF_E_EMPTY when nothing is left to quantize,
+ * INSHR_REF_E_NONFINITE also for a non-finite gradient or score. */
+int inshr_ref_quantize_sens(const float *x, const float *g, uint64_t n, const inshr_ref_config *cfg,
+                            int prune_by_sensitivity, uint16_t *sym, float *boundaries, float *codebook,
+                            uint32_t *out_idx, float *out_val, inshr_ref_qinfo *info,
+                            uint32_t *tau_outlier_sens_bits);
+
 /* Decode symbols back to floats: 0 -> +0.0, 1 -> listed original value, 2+b -> codebook[b]. */
 int inshr_ref_dequantize(const uint16_t *sym, uint64_t n, uint32_t bits, const float *codebook,
                          const uint32_t *out_idx, const float *out_val, uint64_t n_outlier,

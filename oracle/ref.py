@@ -107,6 +107,37 @@ def quantize(x, cfg, pool=None):
                 sse=float(info.sse), sumsq=float(info.sumsq))
 
 
+def quantize_sens(x, g, cfg, by_sens):
+    """Partition by magnitude and sensitivity (Sec. 4.1-4.2): g = gradients, by_sens = the pruning
+    metric is the sensitivity score.  Returns the dict of quantize plus tau_outlier_sens_bits."""
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    g = np.ascontiguousarray(g, dtype=np.float32).ravel()
+    n = x.size
+    if g.size != n:
+        raise RefError(-5)
+    K = bins_of(cfg)
+    sym = np.empty(n, np.uint16)
+    bnd = np.empty(max(K - 1, 1), np.float32)
+    cb = np.empty(K, np.float32)
+    oi = np.empty(n, np.uint32)
+    ov = np.empty(n, np.float32)
+    info = QInfo()
+    tos = C.c_uint32(0)
+    c = _config(cfg)
+    rc = lib().inshr_ref_quantize_sens(_p(x, C.c_float), _p(g, C.c_float), C.c_uint64(n), C.byref(c),
+                                       C.c_int(1 if by_sens else 0), _p(sym, C.c_uint16), _p(bnd, C.c_float),
+                                       _p(cb, C.c_float), _p(oi, C.c_uint32), _p(ov, C.c_float),
+                                       C.byref(info), C.byref(tos))
+    if rc:
+        raise RefError(rc)
+    no = int(info.n_outlier)
+    return dict(sym=sym, boundaries=bnd[:K - 1], codebook=cb, outlier_idx=oi[:no].copy(),
+                outlier_val=ov[:no].copy(), n_pruned=int(info.n_pruned), n_outlier=no,
+                n_kept=int(info.n_kept), sym_bits=int(info.sym_bits), K=K,
+                tau_prune_bits=int(info.tau_prune_bits), tau_outlier_bits=int(info.tau_outlier_bits),
+                tau_outlier_sens_bits=int(tos.value), sse=float(info.sse), sumsq=float(info.sumsq))
+
+
 def bf16_round(x):
     """Protected values as Sec. 4.2 stores them: rounded to bfloat16 (returned as float32)."""
     x = np.ascontiguousarray(x, np.float32)

@@ -559,3 +559,88 @@ def test_a_group_of_one_tensor_is_the_tensor_alone():
     for cfg in grid[::5]:
         a, b = ref.quantize(x, cfg), ref.quantize(x, cfg, pool=ref.pool_of([x]))
         assert all(np.array_equal(a[k], b[k]) for k in a)
+
+
+# ------------------------------------------------------------------------------------------
+# partition by magnitude and sensitivity (Sec. 4.1-4.2)
+# ------------------------------------------------------------------------------------------
+def _numpy_sens(x, g, cfg, by_sens):
+    n = x.size
+    K = ref.bins_of(cfg)
+    mag = np.abs(x)
+    s = np.abs((g * x).astype(np.float32))
+    n_p, n_o = n * cfg[1] // 1000000, n * cfg[2] // 1000000
+    tau_om, tau_os = np.sort(mag)[n - 1 - n_o], np.sort(s)[n - 1 - n_o]
+    metric = s if by_sens else mag
+    tau_p = np.sort(metric)[n_p]
+    prot = (mag > tau_om) | (s > tau_os)
+    pruned = ~prot & (metric < tau_p)
+    kept = ~prot & ~pruned
+    Y = np.sort(x[kept] + np.float32(0.0))
+    t = np.array([Y[j * Y.size // K] for j in range(1, K)], np.float32)
+    sym = (np.searchsorted(t, x + np.float32(0.0), side="right") + 2).astype(np.uint16)
+    sym[pruned], sym[prot] = 0, 1
+    return dict(sym=sym, t=t, prot=np.nonzero(prot)[0], tau=(tau_p, tau_om, tau_os), M=int(kept.sum()))
+
+
+def test_sensitivity_partition_against_numpy():
+    rng = np.random.default_rng(91)
+    for n in (1, 7, 100, 20_001):
+        x = (0.02 * rng.standard_t(4, n)).astype(np.float32)
+        g = (1e-3 * rng.standard_normal(n) * (1 + 5 * (rng.random(n) < 0.02))).astype(np.float32)
+        if n > 50:
+            x[::17] = 0.0
+            g[::29] = 0.0
+        for cfg in ((3, 0, 0), (4, 200000, 10000), (0, 400000, 1000, 12), (8, 100000, 50000)):
+            for by_sens in (False, True):
+                want = _numpy_sens(x, g, cfg, by_sens)
+                if want["M"] == 0:
+                    with pytest.raises(ref.RefError):
+                        ref.quantize_sens(x, g, cfg, by_sens)
+                    continue
+                r = ref.quantize_sens(x, g, cfg, by_sens)
+                assert np.array_equal(r["sym"], want["sym"]), (n, cfg, by_sens)
+                assert np.array_equal(r["boundaries"], want["t"])
+                assert np.array_equal(r["outlier_idx"], want["prot"])
+                assert np.array_equal(r["outlier_val"].view(np.uint32), x[want["prot"]].view(np.uint32))
+                assert r["tau_prune_bits"] == np.float32(want["tau"][0]).view(np.uint32)
+                assert r["tau_outlier_bits"] == np.float32(want["tau"][1]).view(np.uint32)
+                assert r["tau_outlier_sens_bits"] == np.float32(want["tau"][2]).view(np.uint32)
+                # centres and error by definition
+                dec = np.zeros(n)
+                kept = r["sym"] >= 2
+                for k in range(r["K"]):
+                    mk = r["sym"] == k + 2
+                    if mk.any():
+                        assert abs(float(r["codebook"][k]) - x[mk].astype(np.float64).mean()) <= 1e-6 * abs(x[mk].astype(np.float64).mean()) + 1e-12
+                dec[kept] = r["codebook"][r["sym"][kept] - 2]
+                dec[r["sym"] == 1] = x[r["sym"] == 1]
+                assert abs(r["sse"] - float(((x.astype(np.float64) - dec) ** 2).sum())) <= 1e-9 * r["sumsq"] + 1e-30
+
+
+def test_sensitivity_with_a_constant_gradient_is_the_magnitude_partition():
+    """s = |2 x| orders like |x| (an exact doubling), so both protection sets coincide and pruning by
+    either metric is the magnitude partition of Sec. 4.2."""
+    x = (0.02 * np.random.default_rng(92).standard_t(3, 30_001)).astype(np.float32)
+    x[::11] = 0.0
+    g = np.full_like(x, 2.0)
+    for cfg in ((5, 300000, 1000), (2, 0, 0), (0, 100000, 20000, 6)):
+        a = ref.quantize(x, cfg)
+        for by_sens in (False, True):
+            b = ref.quantize_sens(x, g, cfg, by_sens)
+            for k in ("sym", "boundaries", "codebook", "outlier_idx", "outlier_val", "n_pruned", "n_outlier", "n_kept"):
+                assert np.array_equal(a[k], b[k]), (cfg, by_sens, k)
+            assert a["sse"] == b["sse"]
+
+
+def test_sensitivity_protects_what_magnitude_alone_would_not():
+    x = np.array([0.001, 0.5, -0.4, 0.3, 0.2, -0.1, 0.05, 0.02, 0.01, 0.003], np.float32)
+    g = np.array([900.0, 0.1, 0.1, 0.1, 0.1, 0.1, 0.1, 0.1, 0.1, 0.1], np.float32)   # the smallest weight matters most
+    r = ref.quantize_sens(x, g, (1, 0, 100000), False)      # one value protected per metric
+    assert r["outlier_idx"].tolist() == [0, 1] and r["n_pruned"] == 0
+    r = ref.quantize_sens(x, g, (1, 200000, 100000), True)  # pruning by sensitivity: the two lowest scores
+    assert np.nonzero(r["sym"] == 0)[0].tolist() == [8, 9]
+    r = ref.quantize_sens(x, g, (1, 200000, 100000), False) # by magnitude: 0.001 is protected, so only 0.003 goes
+    assert np.nonzero(r["sym"] == 0)[0].tolist() == [9]
+    with pytest.raises(ref.RefError):
+        ref.quantize_sens(x, np.array([np.inf] + [0.0] * 9, np.float32), (1, 0, 0), False)
