@@ -216,6 +216,31 @@ int inshr_delta(inshr_ctx *ctx, const inshr_codes *prev, const uint32_t *const *
 int inshr_delta_static(inshr_ctx *ctx, const inshr_codes *prev, const inshr_codes *cur,
                        inshr_delta_out *out, uint32_t n_tensors);
 
+/* ---- partition by magnitude and sensitivity (Sec. 4.1, 4.2) --------------------------------- */
+
+typedef struct {
+    float tau_outlier_sens; /* protect threshold of the sensitivity score                          */
+    double sse, sumsq;      /* error of the decoded tensor as inshr_score defines it, sum of x^2   */
+} inshr_sens_info;
+
+/* One configuration per tensor, with gradients: grads[t] (device, n floats, 4-byte aligned) is the
+ * gradient of the loss with respect to tensors[t].  The sensitivity score of an element is
+ * s = |g * x| (one fp32 multiplication).  protected <=> |x| > tau_om or s > tau_os, the values of
+ * rank n - 1 - floor(n * outlier_ppm / 1e6) of the magnitudes and of the scores; pruned <=> not
+ * protected and m < tau_p, where m is the pruning metric (the magnitude, or the score where
+ * prune_by_sensitivity[t] != 0; the array may be NULL) and tau_p its value of rank
+ * floor(n * prune_ppm / 1e6); the rest is quantized with equal-frequency bins over exactly these
+ * values.  out as for inshr_quantize (tau_prune is the image of tau_p in its metric, tau_outlier is
+ * tau_om); up to 2 * floor(n * outlier_ppm / 1e6) values can be protected, and outlier_cap must hold
+ * them (INSHR_E_CAPACITY).  info may be NULL.  The call synchronises, runs three searches inside
+ * (thresholds of the scores, thresholds of the weights, bins of the quantized values) and leaves no
+ * state for INSHR_REUSE_SEARCH.  INSHR_E_NONFINITE also for a non-finite gradient or score,
+ * INSHR_E_CONFIG when a tensor is left without quantized values or the call names more distinct
+ * fractions than one grid takes. */
+int inshr_quantize_sens(inshr_ctx *ctx, const inshr_tensor *tensors, const float *const *grads,
+                        const inshr_config *cfg, const uint8_t *prune_by_sensitivity,
+                        inshr_quantized *out, inshr_sens_info *info, uint32_t n_tensors);
+
 /* ---- restore side ------------------------------------------------------------------------- */
 
 typedef struct {

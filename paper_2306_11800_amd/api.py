@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
-           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_search_pooled", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_search_pooled", "inshr_quantize_sens", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_guided_search", "inshr_neighbourhood_search", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
@@ -50,6 +50,10 @@ class CTensor(C.Structure):
 class CScore(C.Structure):
     _fields_ = [("sse", C.c_double), ("sumsq", C.c_double), ("n_pruned", C.c_uint64),
                 ("n_outlier", C.c_uint64), ("n_kept", C.c_uint64), ("cost_bits", C.c_uint64)]
+
+
+class CSensInfo(C.Structure):
+    _fields_ = [("tau_outlier_sens", C.c_float), ("sse", C.c_double), ("sumsq", C.c_double)]
 
 
 class CQuantized(C.Structure):
@@ -147,6 +151,9 @@ def load_library() -> C.CDLL:
     lib.inshr_search_pooled.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(C.c_uint32), C.c_uint32,
                                         C.POINTER(CConfig), C.c_uint32, C.c_double, C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint8), C.POINTER(CScore)]
+    lib.inshr_quantize_sens.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(C.c_void_p), C.POINTER(CConfig),
+                                        C.POINTER(C.c_uint8), C.POINTER(CQuantized), C.POINTER(CSensInfo),
+                                        C.c_uint32]
     lib.inshr_guided_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.c_double, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint8)]
@@ -451,6 +458,41 @@ class Context:
         for q in res:
             q.bf16 = protect_bf16
         return res
+
+    # -- inshr_quantize_sens ---------------------------------------------------------------
+    def quantize_sens(self, tensors: Sequence[torch.Tensor], grads: Sequence[torch.Tensor], cfgs,
+                      by_sens: Sequence[bool]):
+        """Partition by magnitude and sensitivity (gradients given).  Returns (list of Quantized,
+        list of (tau_outlier_sens, sse, sumsq))."""
+        nT = len(tensors)
+        ta = _tensor_array(tensors)
+        ca = _config_array(cfgs)
+        gp = (C.c_void_p * nT)(*[g.data_ptr() for g in grads])
+        bs = (C.c_uint8 * nT)(*[1 if b else 0 for b in by_sens])
+        qa = (CQuantized * nT)()
+        info = (CSensInfo * nT)()
+        res = QuantizedBatch()
+        for i, (t, g, cfg) in enumerate(zip(tensors, grads, cfgs)):
+            n = t.numel()
+            if g.numel() != n or g.dtype != torch.float32 or not g.is_contiguous():
+                raise ValueError("one contiguous float32 gradient per tensor, of its size")
+            words, cap = self._bound(n, ca[i], cfg)
+            cap = 2 * cap + 1  # either metric may protect its fraction
+            e = qa[i]
+            q = Quantized(n, int(cfg[0]), (
+                torch.empty(words, dtype=torch.int64, device=t.device),
+                torch.empty(256, dtype=torch.float32, device=t.device),
+                torch.empty(255, dtype=torch.float32, device=t.device),
+                torch.empty(cap, dtype=torch.int32, device=t.device),
+                torch.empty(cap, dtype=torch.float32, device=t.device)), e, qa, bins=bins_of(cfg))
+            e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
+            e.packed_words = q._bufs[0].numel()
+            e.outlier_cap = cap
+            res.append(q)
+        res._qa = qa
+        res._sizes = tuple(q.n for q in res)
+        self._check(self.lib.inshr_quantize_sens(self.h, ta, gp, ca, bs, qa, info, nT))
+        return res, [(float(i.tau_outlier_sens), float(i.sse), float(i.sumsq)) for i in info]
 
     # -- inshr_quantize_sketch -------------------------------------------------------------
     def quantize_sketch(self, tensors: Sequence[torch.Tensor], cfgs, uniforms, alpha: float = 0.01,

@@ -51,6 +51,7 @@ struct inshr_ctx {
     DevBuf search_mem; // everything a search leaves behind for inshr_quantize
     DevBuf aux_mem;    // quantize descriptors, delta scratch
     DevBuf sketch_mem; // sketch tables, histograms, bucket lists and the centres they give
+    DevBuf sens_mem;   // scores, compacted values and block counts of inshr_quantize_sens
     double sketch_alpha = 0.0;                 // the bucket tables last built, and for which alpha
     int sketch_i_lo = 0;
     std::vector<u32> sketch_cell, sketch_tops;
@@ -628,6 +629,7 @@ void inshr_destroy(inshr_ctx *c)
     if (c->search_mem.p) (void)hipFree(c->search_mem.p);
     if (c->aux_mem.p) (void)hipFree(c->aux_mem.p);
     if (c->sketch_mem.p) (void)hipFree(c->sketch_mem.p);
+    if (c->sens_mem.p) (void)hipFree(c->sens_mem.p);
     if (c->delta_flags) (void)hipFree(c->delta_flags);
     if (c->h_up.p) (void)hipHostFree(c->h_up.p);
     if (c->h_down.p) (void)hipHostFree(c->h_down.p);
@@ -1233,6 +1235,167 @@ static int codes_bins(const inshr_codes &c, uint32_t &K)
         K = 1u << c.bits;
     }
     return 0;
+}
+
+int inshr_quantize_sens(inshr_ctx *c, const inshr_tensor *tensors, const float *const *grads,
+                        const inshr_config *cfg, const uint8_t *prune_by_sensitivity,
+                        inshr_quantized *out, inshr_sens_info *info, uint32_t n_tensors)
+{
+    if (!c || !tensors || !grads || !cfg || !out || n_tensors == 0 || n_tensors > 65535u) return INSHR_E_ARG;
+    const uint32_t nT = n_tensors;
+    c->have_search = false;
+    // the distinct configurations: their fractions for the two threshold searches, their numbers
+    // of bins for the search over the quantized values
+    std::vector<inshr_config> frac_grid, bin_grid;
+    std::vector<uint32_t> frac_of(nT), bin_of_t(nT);
+    u64 n_total = 0, n_blocks = 0;
+    for (uint32_t t = 0; t < nT; t++) {
+        int rc = check_config(cfg[t]);
+        if (rc) return rc;
+        if (!tensors[t].data || !grads[t] || tensors[t].n == 0 || tensors[t].n >= (1ull << 32)) return INSHR_E_ARG;
+        if (((uintptr_t)tensors[t].data | (uintptr_t)grads[t]) & 3u) return INSHR_E_ARG;
+        if (!out[t].packed || !out[t].codebook) return INSHR_E_ARG;
+        if (out[t].outlier_cap && (!out[t].outlier_idx || !out[t].outlier_val)) return INSHR_E_ARG;
+        if (out[t].packed_words < (tensors[t].n * (u64)symbol_bits(bins_of(cfg[t])) + 63) / 64) return INSHR_E_CAPACITY;
+        inshr_config f = cfg[t], b = cfg[t];
+        f.bits = 1;
+        f.bins = 0;
+        b.prune_ppm = b.outlier_ppm = 0;
+        size_t i;
+        for (i = 0; i < frac_grid.size(); i++)
+            if (same_config(frac_grid[i], f)) break;
+        if (i == frac_grid.size()) frac_grid.push_back(f);
+        frac_of[t] = (uint32_t)i;
+        for (i = 0; i < bin_grid.size(); i++)
+            if (same_config(bin_grid[i], b)) break;
+        if (i == bin_grid.size()) bin_grid.push_back(b);
+        bin_of_t[t] = (uint32_t)i;
+        n_total += tensors[t].n;
+        n_blocks += (tensors[t].n + 1023) / 1024;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    Carver cv;
+    const size_t o_sd = cv.take(sizeof(SDesc) * nT);
+    const size_t o_si = cv.take(sizeof(SInfo) * nT);
+    const size_t o_fl = cv.take(256);
+    const size_t o_bk = cv.take(n_blocks * 4);
+    const size_t o_bp = cv.take(n_blocks * 4);
+    const size_t o_bq = cv.take(n_blocks * 16);
+    const size_t o_S = cv.take(n_total * 4 + 64ull * nT);
+    const size_t o_W = cv.take(n_total * 4 + 64ull * nT);
+    int rc = ensure_dev(c, c->sens_mem, cv.off);
+    if (rc) return rc;
+    char *db = (char *)c->sens_mem.p;
+    std::vector<SDesc> sd(nT);
+    {
+        u64 blk = 0, off = 0;
+        for (uint32_t t = 0; t < nT; t++) {
+            memset(&sd[t], 0, sizeof(SDesc));
+            sd[t].w = tensors[t].data;
+            sd[t].g = grads[t];
+            sd[t].n = tensors[t].n;
+            sd[t].blk0 = blk;
+            sd[t].S = (float *)(db + o_S) + off;
+            sd[t].Wm = (float *)(db + o_W) + off;
+            sd[t].by_sens = (prune_by_sensitivity && prune_by_sensitivity[t]) ? 1u : 0u;
+            blk += (tensors[t].n + 1023) / 1024;
+            off += (tensors[t].n + 15) / 16 * 16; // every tensor's scratch starts 64-byte aligned
+        }
+    }
+    auto upload = [&]() -> int {
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        HIPCHK(c, hipMemcpy(db + o_sd, sd.data(), sizeof(SDesc) * nT, hipMemcpyHostToDevice));
+        return INSHR_OK;
+    };
+    if ((rc = upload())) return rc;
+    HIPCHK(c, launch_sens_score((const SDesc *)(db + o_sd), (int)nT, n_blocks, c->stream));
+
+    // thresholds: order statistics of the scores, then of the weights (threshold searches only)
+    std::vector<inshr_tensor> sub(nT);
+    for (int pass = 0; pass < 2; pass++) {
+        for (uint32_t t = 0; t < nT; t++) {
+            sub[t].data = pass == 0 ? sd[t].S : tensors[t].data;
+            sub[t].n = tensors[t].n;
+        }
+        rc = run_search(c, sub.data(), nT, frac_grid.data(), (uint32_t)frac_grid.size(), 0.0, true);
+        if (rc) return rc;
+        const TState *hts = (const TState *)c->h_down.p;
+        for (uint32_t t = 0; t < nT; t++) {
+            uint32_t qp = 0, qo = 0;
+            while (qp < c->grid.n_p && c->grid.p_ppm[qp] != cfg[t].prune_ppm) qp++;
+            while (qo < c->grid.n_o && c->grid.o_ppm[qo] != cfg[t].outlier_ppm) qo++;
+            if (qp == c->grid.n_p || qo == c->grid.n_o) return INSHR_E_INTERNAL;
+            const u32 tp = hts[t].thr_mag[qp], to = hts[t].thr_mag[c->grid.n_p + qo];
+            if (pass == 0) {
+                sd[t].tau_os = to;
+                if (sd[t].by_sens) sd[t].tau_p = tp;
+            } else {
+                sd[t].tau_om = to;
+                if (!sd[t].by_sens) sd[t].tau_p = tp;
+            }
+        }
+    }
+    c->have_search = false;
+    if ((rc = upload())) return rc;
+    HIPCHK(c, launch_sens_partition((const SDesc *)(db + o_sd), (int)nT, n_blocks, (u32 *)(db + o_bk),
+                                    (u32 *)(db + o_bp), (double *)(db + o_bq), (SInfo *)(db + o_si), c->stream));
+    std::vector<SInfo> si(nT);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(si.data(), db + o_si, sizeof(SInfo) * nT, hipMemcpyDeviceToHost));
+    for (uint32_t t = 0; t < nT; t++) {
+        if (si[t].n_kept == 0) {
+            c->last_err = "the thresholds leave tensor " + std::to_string(t) + " without quantized values";
+            return INSHR_E_CONFIG;
+        }
+        if (si[t].n_outlier > out[t].outlier_cap) return INSHR_E_CAPACITY;
+        sub[t].data = sd[t].Wm;
+        sub[t].n = si[t].n_kept;
+    }
+    // the bins: the quantized values as tensors of their own, nothing pruned, nothing protected
+    rc = run_search(c, sub.data(), nT, bin_grid.data(), (uint32_t)bin_grid.size(), 0.0, false);
+    if (rc) return rc;
+    c->have_search = false; // (the state describes the compacted values, not the caller's tensors)
+    const Score *hsc = (const Score *)((const char *)c->h_down.p + sizeof(TState) * nT);
+    const uint32_t n_bg = (uint32_t)bin_grid.size();
+    std::vector<double> sse_q(nT), sq_q(nT);
+    for (uint32_t t = 0; t < nT; t++) {
+        const uint32_t gi = bin_of_t[t];
+        sse_q[t] = hsc[(size_t)t * n_bg + gi].sse;
+        sq_q[t] = hsc[(size_t)t * n_bg + gi].sumsq;
+        sd[t].packed = (unsigned long long *)out[t].packed;
+        sd[t].out_idx = out[t].outlier_idx;
+        sd[t].out_val = out[t].outlier_val;
+        sd[t].out_cap = out[t].outlier_cap;
+        sd[t].codebook = out[t].codebook;
+        sd[t].boundaries = out[t].boundaries;
+        sd[t].bkeys = c->batch.bufs.tgt_key + (size_t)t * TGT_STRIDE; // (one pair: nothing pruned or protected)
+        sd[t].cb = c->batch.bufs.codebook + ((size_t)t * n_bg + gi) * CB_STRIDE;
+        sd[t].K = bins_of(cfg[t]);
+        sd[t].sym_bits = symbol_bits(sd[t].K);
+    }
+    if ((rc = upload())) return rc;
+    HIPCHK(c, hipMemsetAsync(db + o_fl, 0, 4, c->stream));
+    HIPCHK(c, launch_sens_quant((const SDesc *)(db + o_sd), (int)nT, n_blocks, (const u32 *)(db + o_bp),
+                                (u32 *)(db + o_fl), c->stream));
+    u32 fl = 0;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(&fl, db + o_fl, 4, hipMemcpyDeviceToHost));
+    if (fl & 2u) return INSHR_E_CAPACITY;
+    for (uint32_t t = 0; t < nT; t++) {
+        out[t].n_pruned = si[t].n_pruned;
+        out[t].n_outlier = si[t].n_outlier;
+        out[t].n_kept = si[t].n_kept;
+        out[t].n_bins = sd[t].K;
+        out[t].sym_bits = sd[t].sym_bits;
+        memcpy(&out[t].tau_prune, &sd[t].tau_p, 4);
+        memcpy(&out[t].tau_outlier, &sd[t].tau_om, 4);
+        if (info) {
+            memcpy(&info[t].tau_outlier_sens, &sd[t].tau_os, 4);
+            info[t].sse = sse_q[t] + si[t].sq_pruned;
+            info[t].sumsq = sq_q[t] + si[t].sq_pruned + si[t].sq_prot;
+        }
+    }
+    return INSHR_OK;
 }
 
 int inshr_delta_bound(const inshr_codes *prev, const inshr_codes *cur, uint64_t *packed_words)

@@ -104,6 +104,29 @@ struct QInfo {
     u32 tau_p, tau_o, flags, pad;
 };
 
+struct SDesc { // one tensor of a call that partitions by magnitude and sensitivity
+    const float *w, *g;
+    float *S;           // scratch: the sensitivity scores |g * w|
+    float *Wm;          // scratch: the quantized values in index order
+    u64 n;
+    u64 blk0;           // first 1024-element block of this tensor in the call-wide numbering
+    u32 tau_p;          // prune threshold: image of the pruning metric (magnitude or score bits)
+    u32 tau_om, tau_os; // protect thresholds: magnitude image, score bits
+    u32 by_sens;        // the pruning metric is the score
+    unsigned long long *packed;
+    u32 *out_idx;
+    float *out_val;
+    u64 out_cap;
+    float *codebook, *boundaries;
+    const u32 *bkeys;   // the compact tensor's boundary keys (one pair: NBT candidates)
+    const float *cb;    // ... and the centres of the chosen number of bins
+    u32 K, sym_bits;
+};
+struct SInfo {
+    u64 n_pruned, n_outlier, n_kept;
+    double sq_pruned, sq_prot; // sums of squares of the pruned / protected values
+};
+
 struct DDesc { // one tensor of a delta call
     const unsigned long long *prev, *cur;
     unsigned long long *out;
@@ -171,6 +194,11 @@ hipError_t delta_static_init(int device); // once per device, with that device c
 u32 *delta_static_flags(int device);      // the flag word of launch_delta_static on that device
 hipError_t launch_delta_static(int device, const DeltaStaticArgs &a, u64 n_dtiles, u64 n_chunks,
                                bool any_scatter, bool any_perm, bool lds_ordered, hipStream_t s);
+hipError_t launch_sens_score(const SDesc *sd, int nT, u64 n_blocks, hipStream_t s);
+hipError_t launch_sens_partition(const SDesc *sd, int nT, u64 n_blocks, u32 *blk_kept, u32 *blk_prot,
+                                 double *blk_sq, SInfo *info, hipStream_t s);
+hipError_t launch_sens_quant(const SDesc *sd, int nT, u64 n_blocks, const u32 *blk_prot, u32 *flags,
+                             hipStream_t s);
 hipError_t launch_lds_order_check(u32 *violations, hipStream_t s);
 hipError_t launch_dequantize(const RDesc *rd, int nT, u64 n_tiles, u64 max_outlier, u32 *flags,
                              u32 *ones, int n_cu, hipStream_t s);
