@@ -74,7 +74,7 @@ def test_chunk_boundaries_of_the_delta(ctx):
 
 
 @pytest.mark.parametrize("mode", ["sampled", "sampled_all_missed"])
-def test_sampled_first_sweep(mode):
+def test_sampled_first_sweep(mode, monkeypatch):
     """Large tensors read one tile in eight in the first sweep and predict where the thresholds
     fall; INSHR_SAMPLE_MIN_N=1 does that for every tensor, INSHR_SAMPLE_FORCE_MISS=1 treats every
     prediction as wrong (both exact sweeps are then repeated).  The last tensor's sampled tiles are
@@ -85,12 +85,10 @@ def test_sampled_first_sweep(mode):
     env = {"INSHR_SAMPLE_MIN_N": "1"}
     if mode == "sampled_all_missed":
         env["INSHR_SAMPLE_FORCE_MISS"] = "1"
-    os.environ.update(env)
-    try:
+    with monkeypatch.context() as m:  # (whatever the variables were before comes back afterwards)
+        for k, v in env.items():
+            m.setenv(k, v)
         c = api.Context(torch.device("cuda:0"))
-    finally:
-        for k in env:
-            del os.environ[k]
     rng = np.random.default_rng(105)
     sizes = [5, 16_384, 40_000, 131_072, 200_003, 300_001, 16_384 * 24 + 77]
     prevs = [family(rng, k, n) for k, n in zip([0, 5, 3, 6, 8, 9, 0], sizes)]

@@ -268,15 +268,13 @@ def test_protected_values_in_the_last_lanes_of_a_ragged_tile(ctx):
     run_pipeline(ctx, [prev], [cur], synth.grid_small(), synth.EPS_DEFAULT)
 
 
-def test_without_lane_ordered_lds_atomics():
+def test_without_lane_ordered_lds_atomics(monkeypatch):
     """The group sort and the delta scatter have a ballot-based path for devices whose LDS atomics
     do not return in lane order; INSHR_NO_LDS_ORDER=1 selects it."""
     from paper_2306_11800_amd import api
-    os.environ["INSHR_NO_LDS_ORDER"] = "1"
-    try:
+    with monkeypatch.context() as m:  # (whatever the variable was before comes back afterwards)
+        m.setenv("INSHR_NO_LDS_ORDER", "1")
         c = api.Context(torch.device("cuda:0"))
-    finally:
-        del os.environ["INSHR_NO_LDS_ORDER"]
     assert c.lds_ordered is False
     rng = np.random.default_rng(12)
     prev, cur = synth.config0(seed=3, n=250_007)
@@ -400,7 +398,7 @@ def test_ranking_path_is_reported(ctx):
     assert ctx.lds_ordered == (not forced_off)
 
 
-def test_scratch_limit_and_growing_gather_pools(ctx):
+def test_scratch_limit_and_growing_gather_pools(ctx, monkeypatch):
     """The gather pools hold a fraction of the elements and grow when a search finds them too small:
     a context that starts with the smallest pools (INSHR_POOL_WCAP=1) gives the same bytes as the
     default one, within a scratch limit far below 8 bytes per element; a limit below the tables is
@@ -416,11 +414,9 @@ def test_scratch_limit_and_growing_gather_pools(ctx):
     grid = synth.grid_full()
     best, feas, scores = ctx.search(ts, grid, synth.EPS_DEFAULT)
     want = ctx.quantize(ts, [grid[b] for b in best], reuse_search=True)
-    os.environ["INSHR_POOL_WCAP"] = "1"
-    try:
+    with monkeypatch.context() as m:
+        m.setenv("INSHR_POOL_WCAP", "1")
         small = api.Context(torch.device("cuda:0"), scratch_bytes=200 << 20)  # 8 B per element would be 320 MB
-    finally:
-        del os.environ["INSHR_POOL_WCAP"]
     b2, f2, s2 = small.search(ts, grid, synth.EPS_DEFAULT)
     assert (b2, f2) == (best, feas)
     for i in range(len(ts) * len(grid)):

@@ -90,13 +90,11 @@ def test_reconstruct_matches_the_oracle_and_closes_the_round_trip(ctx):
                 assert np.array_equal(u64(rec[i]), ref.pack(want, cc[0] + 1)), (cp, cc, xp.size)
 
 
-def test_reconstruct_without_lane_ordered_lds_atomics():
+def test_reconstruct_without_lane_ordered_lds_atomics(monkeypatch):
     from paper_2306_11800_amd import api
-    os.environ["INSHR_NO_LDS_ORDER"] = "1"
-    try:
+    with monkeypatch.context() as m:
+        m.setenv("INSHR_NO_LDS_ORDER", "1")
         c = api.Context(torch.device("cuda:0"))
-    finally:
-        del os.environ["INSHR_NO_LDS_ORDER"]
     prev, cur = synth.config0(seed=34, n=900_001)
     qp = c.quantize([dev(prev)], [(5, 100000, 1000)])
     qc = c.quantize([dev(cur)], [(4, 100000, 1000)])
