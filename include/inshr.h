@@ -313,6 +313,16 @@ int inshr_quantize_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const ins
                           const inshr_sketch_params *params, inshr_quantized *out,
                           inshr_sketch_info *info, uint32_t n_tensors, uint32_t flags);
 
+/* The sketch as the quantile estimator (Sec. 4.3, Algorithm 1): one sweep counts the magnitudes of
+ * every tensor per bucket of the law below; the estimate of the magnitude of rank floor(q (n - 1))
+ * is the value of the bucket in which the running count (zeros first, then ascending buckets) passes
+ * the rank: within a factor 1 +- alpha of the exact order statistic.  q: host array of n_q numbers in
+ * [0, 1]; estimates: host array [n_tensors][n_q].  The hot path's thresholds stay exact; this call is
+ * the paper's estimator on its own (prune / protect thresholds are q = prune fraction and
+ * q = 1 - protect fraction).  0.01 <= alpha <= 0.5.  Synchronises. */
+int inshr_sketch_quantiles(inshr_ctx *ctx, const inshr_tensor *tensors, uint32_t n_tensors, const double *q,
+                           uint32_t n_q, double alpha, double *estimates);
+
 /* Host only (no GPU work): the bucket law the sketch calls use for alpha.  Bucket index i_lo + b
  * (b = 0 .. n_buckets - 1) holds the magnitudes above tops[b - 1] up to tops[b], the largest fp32
  * number not above gamma^(i_lo + b), and stands for values[b] = 2 gamma^(i_lo + b) / (gamma + 1).

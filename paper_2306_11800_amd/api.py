@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
-           "inshr_sync", "inshr_lds_ordered", "inshr_search", "inshr_search_pooled", "inshr_quantize_sens", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_sync", "inshr_lds_ordered", "inshr_sketch_quantiles", "inshr_search", "inshr_search_pooled", "inshr_quantize_sens", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_guided_search", "inshr_neighbourhood_search", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
@@ -154,6 +154,8 @@ def load_library() -> C.CDLL:
     lib.inshr_quantize_sens.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(C.c_void_p), C.POINTER(CConfig),
                                         C.POINTER(C.c_uint8), C.POINTER(CQuantized), C.POINTER(CSensInfo),
                                         C.c_uint32]
+    lib.inshr_sketch_quantiles.argtypes = [C.c_void_p, C.POINTER(CTensor), C.c_uint32, C.POINTER(C.c_double),
+                                           C.c_uint32, C.c_double, C.POINTER(C.c_double)]
     lib.inshr_guided_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.c_double, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint8)]
@@ -458,6 +460,16 @@ class Context:
         for q in res:
             q.bf16 = protect_bf16
         return res
+
+    # -- inshr_sketch_quantiles ------------------------------------------------------------
+    def sketch_quantiles(self, tensors: Sequence[torch.Tensor], q: Sequence[float], alpha: float = 0.01):
+        """The sketch's estimates of the magnitudes of rank floor(q (n - 1)): list (per tensor) of lists."""
+        nT, nq = len(tensors), len(q)
+        ta = _tensor_array(tensors)
+        qa = (C.c_double * nq)(*[float(v) for v in q])
+        out = (C.c_double * (nT * nq))()
+        self._check(self.lib.inshr_sketch_quantiles(self.h, ta, nT, qa, nq, float(alpha), out))
+        return [[out[t * nq + k] for k in range(nq)] for t in range(nT)]
 
     # -- inshr_quantize_sens ---------------------------------------------------------------
     def quantize_sens(self, tensors: Sequence[torch.Tensor], grads: Sequence[torch.Tensor], cfgs,

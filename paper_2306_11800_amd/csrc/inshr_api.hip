@@ -1224,6 +1224,74 @@ int inshr_sketch_buckets(double alpha, int32_t *i_lo, uint32_t *n_buckets, float
     return INSHR_OK;
 }
 
+int inshr_sketch_quantiles(inshr_ctx *c, const inshr_tensor *tensors, uint32_t n_tensors, const double *q,
+                           uint32_t n_q, double alpha, double *estimates)
+{
+    if (!c || !tensors || !q || !estimates || n_tensors == 0 || n_q == 0 || n_q > 4096u) return INSHR_E_ARG;
+    SketchTables T;
+    int rc = build_sketch_tables(c, alpha, T);
+    if (rc) return rc;
+    const uint32_t nT = n_tensors;
+    const size_t n_idx = T.tops.size();
+    std::vector<MagDesc> md(nT);
+    std::vector<u64> ranks((size_t)nT * n_q);
+    u64 chunks = 0;
+    for (uint32_t t = 0; t < nT; t++) {
+        if (!tensors[t].data || tensors[t].n == 0 || tensors[t].n >= (1ull << 32)) return INSHR_E_ARG;
+        if ((uintptr_t)tensors[t].data & 3u) return INSHR_E_ARG;
+        md[t].x = tensors[t].data;
+        md[t].n = tensors[t].n;
+        md[t].chunk0 = chunks;
+        md[t].aligned16 = (((uintptr_t)tensors[t].data & 15u) == 0) ? 1u : 0u;
+        md[t].pad = 0u;
+        chunks += (tensors[t].n + SK_MAG_CHUNK - 1) / SK_MAG_CHUNK;
+        for (uint32_t k = 0; k < n_q; k++) {
+            if (!(q[k] >= 0.0 && q[k] <= 1.0)) return INSHR_E_ARG;
+            ranks[(size_t)t * n_q + k] = (u64)floor(q[k] * (double)(tensors[t].n - 1)); // rank floor(q (n - 1))
+        }
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    Carver cv;
+    const size_t o_cell = cv.take(sizeof(u32) * SK_CELLS);
+    const size_t o_tops = cv.take(sizeof(u32) * n_idx);
+    const size_t o_rep = cv.take(sizeof(double) * n_idx);
+    const size_t o_md = cv.take(sizeof(MagDesc) * nT);
+    const size_t o_rk = cv.take(sizeof(u64) * ranks.size());
+    const size_t upload = cv.off;
+    const size_t o_hist = cv.take(sizeof(u32) * SK_MAG_HIST * nT);
+    const size_t o_nf = cv.take(256);
+    const size_t zero_end = cv.off;
+    const size_t o_est = cv.take(sizeof(double) * ranks.size());
+    rc = ensure_dev(c, c->sketch_mem, cv.off);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_up, upload);
+    if (rc) return rc;
+    rc = ensure_host(c, c->h_down, sizeof(double) * ranks.size() + 256);
+    if (rc) return rc;
+    char *hb = (char *)c->h_up.p, *db = (char *)c->sketch_mem.p;
+    HIPCHK(c, hipStreamSynchronize(c->stream)); // the staging buffer may still be in flight
+    memcpy(hb + o_cell, T.cell.data(), sizeof(u32) * SK_CELLS);
+    memcpy(hb + o_tops, T.tops.data(), sizeof(u32) * n_idx);
+    memcpy(hb + o_rep, T.rep.data(), sizeof(double) * n_idx);
+    memcpy(hb + o_md, md.data(), sizeof(MagDesc) * nT);
+    memcpy(hb + o_rk, ranks.data(), sizeof(u64) * ranks.size());
+    HIPCHK(c, hipMemcpyAsync(db, hb, upload, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemsetAsync(db + o_hist, 0, zero_end - o_hist, c->stream));
+    HIPCHK(c, launch_sketch_quantiles((const MagDesc *)(db + o_md), (int)nT, chunks, c->n_cu, (const u32 *)(db + o_cell),
+                                      (const u32 *)(db + o_tops), (const double *)(db + o_rep), (u32)n_idx,
+                                      (u32 *)(db + o_hist), (u32 *)(db + o_nf), (const u64 *)(db + o_rk), n_q,
+                                      (double *)(db + o_est), c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_down.p, db + o_est, sizeof(double) * ranks.size(), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync((char *)c->h_down.p + sizeof(double) * ranks.size(), db + o_nf, 4,
+                             hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    u32 nf = 0;
+    memcpy(&nf, (const char *)c->h_down.p + sizeof(double) * ranks.size(), 4);
+    if (nf) return INSHR_E_NONFINITE;
+    memcpy(estimates, c->h_down.p, sizeof(double) * ranks.size());
+    return INSHR_OK;
+}
+
 // number of bins of a symbol stream; nonzero return: not a valid description
 static int codes_bins(const inshr_codes &c, uint32_t &K)
 {

@@ -56,5 +56,19 @@ struct SketchParams {
 };
 
 hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s);
+// The sketch as the quantile estimator (Sec. 4.3): histogram of all magnitudes of a tensor by bucket,
+// then the bucket that holds a rank.
+constexpr int SK_MAG_HIST = SK_MAX_IDX + 1;  // zeros at 0, bucket b at 1 + b
+constexpr int SK_MAG_CHUNK = 65536;          // elements per workgroup
+struct MagDesc {
+    const float *x;
+    u64 n;
+    u64 chunk0; // first chunk of this tensor in the call-wide numbering
+    u32 aligned16, pad;
+};
+hipError_t launch_sketch_quantiles(const MagDesc *md, int nT, u64 n_chunks, int n_wg, const u32 *cell, const u32 *tops,
+                                   const double *rep, u32 n_idx, u32 *hist, u32 *nonfinite,
+                                   const u64 *ranks, u32 n_q, double *est, hipStream_t s);
+
 
 } // namespace inshr

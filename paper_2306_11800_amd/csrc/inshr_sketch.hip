@@ -650,6 +650,138 @@ __global__ __launch_bounds__(256) void k_sketch_choose(const TDesc *__restrict__
     P.final_cb[(size_t)t * 256 + tid] = P.alt_cb[((size_t)t * SK_SETS + best) * 256 + tid];
 }
 
+// ------------------------------------------------------------------------------------------
+// The sketch as the quantile estimator (Sec. 4.3, Algorithm 1): one sweep counts the magnitudes of
+// a tensor per bucket; the estimate of the magnitude of a rank is the value of the bucket in which
+// the running count passes the rank (relative error alpha).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_sketch_maghist(const MagDesc *__restrict__ md, int nT, u64 n_chunks,
+                                                          const u32 *__restrict__ gcell,
+                                                          const u32 *__restrict__ tops, u32 n_idx,
+                                                          u32 *__restrict__ hist, u32 *__restrict__ nonfinite)
+{
+    __shared__ u32 smem[SK_CELLS + SK_MAG_HIST];
+    u32 *cell = smem, *h = smem + SK_CELLS;
+    const u32 tid = threadIdx.x;
+    // every workgroup takes an equal share of the chunks, in order; its counts go to a tensor's
+    // histogram when the share moves on to the next tensor
+    const u64 c_lo = n_chunks * (u64)blockIdx.x / gridDim.x, c_hi = n_chunks * ((u64)blockIdx.x + 1u) / gridDim.x;
+    if (c_lo >= c_hi) return;
+    int t = 0, hi = nT - 1; // last tensor whose first chunk is <= c_lo
+    while (t < hi) {
+        const int mid = (t + hi + 1) >> 1;
+        if (md[mid].chunk0 <= c_lo)
+            t = mid;
+        else
+            hi = mid - 1;
+    }
+    for (int i = tid; i < SK_CELLS; i += BLOCK) cell[i] = gcell[i];
+    for (int i = tid; i < SK_MAG_HIST; i += BLOCK) h[i] = 0u;
+    __syncthreads();
+    bool bad = false;
+    u64 c = c_lo;
+    while (c < c_hi) {
+        const MagDesc d = md[t];
+        const u64 t_end = d.chunk0 + (d.n + SK_MAG_CHUNK - 1) / SK_MAG_CHUNK;
+        const u64 stop = t_end < c_hi ? t_end : c_hi;
+        for (; c < stop; c++) {
+            TDesc td1; // (the tile loader of the sweeps: 16-byte loads where the address allows)
+            td1.data = d.x;
+            td1.n = d.n;
+            td1.aligned16 = d.aligned16;
+#pragma unroll 1
+            for (u32 tl = 0; tl < (u32)SK_MAG_CHUNK / TILE; tl++) {
+                const u64 e0 = (c - d.chunk0) * (u64)SK_MAG_CHUNK + (u64)tl * TILE;
+                if (e0 >= d.n) break;
+                const u64 rem = d.n - e0;
+                const u32 cnt = rem < (u64)TILE ? (u32)rem : (u32)TILE;
+                float v[16];
+                const u32 mask = load_tile(td1, e0, cnt, v);
+#pragma unroll
+                for (int j = 0; j < 16; j++) {
+                    if (!((mask >> j) & 1u)) continue; // past the end
+                    const u32 mag = __float_as_uint(v[j]) & 0x7fffffffu;
+                    if (mag >= 0x7f800000u) {
+                        bad = true;
+                    } else if (mag >= 0x00800000u) {
+                        // entry = first bucket of the cell << 17 | (2^17 - 1 - low bits of that bucket's
+                        // largest magnitude): the sum carries into the bucket field when the magnitude
+                        // lies above it
+                        atomicAdd(&h[1u + ((cell[mag >> 17] + (mag & 0x1FFFFu)) >> 17)], 1u);
+                    } else if (mag == 0u) {
+                        atomicAdd(&h[0], 1u);
+                    } else { // a denormal: first bucket whose largest magnitude reaches it
+                        u32 a = 0u, b = n_idx - 1u;
+                        while (a < b) {
+                            const u32 mid = (a + b) >> 1;
+                            if (tops[mid] >= mag)
+                                b = mid;
+                            else
+                                a = mid + 1u;
+                        }
+                        atomicAdd(&h[1u + a], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        u32 *gh = hist + (size_t)t * SK_MAG_HIST;
+        for (int i = tid; i < SK_MAG_HIST; i += BLOCK) {
+            const u32 v = h[i];
+            if (v) {
+                atomicAdd(&gh[i], v);
+                h[i] = 0u;
+            }
+        }
+        __syncthreads();
+        t++;
+    }
+    if (bad) atomicOr(nonfinite, 1u);
+}
+
+__global__ __launch_bounds__(256) void k_sketch_quantile_pick(const MagDesc *__restrict__ md,
+                                                              const u32 *__restrict__ hist,
+                                                              const double *__restrict__ rep, u32 n_idx,
+                                                              const u64 *__restrict__ ranks, u32 n_q,
+                                                              double *__restrict__ est)
+{
+    __shared__ u32 cum[SK_MAG_HIST + 1]; // keys in the buckets before each one (n < 2^32)
+    const int t = blockIdx.x;
+    const u32 *gh = hist + (size_t)t * SK_MAG_HIST;
+    if (threadIdx.x == 0) {
+        u32 run = 0u;
+        for (u32 i = 0; i <= n_idx; i++) {
+            cum[i] = run;
+            run += gh[i];
+        }
+        cum[n_idx + 1u] = run;
+    }
+    __syncthreads();
+    for (u32 k = threadIdx.x; k < n_q; k += 256u) {
+        const u64 rank = ranks[(size_t)t * n_q + k];
+        u32 lo = 0u, hi = n_idx; // first bucket (in magnitude order, zeros first) whose running count passes the rank
+        while (lo < hi) {
+            const u32 mid = (lo + hi) >> 1;
+            if ((u64)cum[mid + 1u] > rank)
+                hi = mid;
+            else
+                lo = mid + 1u;
+        }
+        est[(size_t)t * n_q + k] = lo == 0u ? 0.0 : rep[lo - 1u];
+    }
+    (void)md;
+}
+
+hipError_t launch_sketch_quantiles(const MagDesc *md, int nT, u64 n_chunks, int n_wg, const u32 *cell, const u32 *tops,
+                                   const double *rep, u32 n_idx, u32 *hist, u32 *nonfinite,
+                                   const u64 *ranks, u32 n_q, double *est, hipStream_t s)
+{
+    const unsigned grid = (unsigned)(n_chunks < (u64)n_wg ? n_chunks : (u64)n_wg);
+    PROF("k_sketch_maghist", s, k_sketch_maghist<<<grid, BLOCK, 0, s>>>(md, nT, n_chunks, cell, tops, n_idx, hist, nonfinite));
+    PROF("k_sketch_quantile_pick", s, k_sketch_quantile_pick<<<nT, 256, 0, s>>>(md, hist, rep, n_idx, ranks, n_q, est));
+    return hipGetLastError();
+}
+
 hipError_t launch_sketch(const Batch &bt, const SketchDesc *sd, const SketchParams &P, hipStream_t s)
 {
     if (P.light)

@@ -218,3 +218,35 @@ def test_restore_round_trip(ctx):
     m = sym >= 2
     d = np.abs(x[m].astype(np.float64)[:, None] - cb[:16].astype(np.float64)[None, :])
     assert np.all(np.abs(y[m].astype(np.float64) - x[m]) <= d.min(axis=1) * (1 + 1e-12))
+
+
+def test_sketch_quantile_estimates_equal_the_oracle(ctx):
+    """Sec. 4.3: the sketch as the quantile estimator, on its own: the bucket that holds the rank is
+    an integer decision, so the estimates equal the oracle's to the last bit; and they lie within
+    alpha of numpy's order statistic."""
+    rng = np.random.default_rng(140)
+    qs = [0.0, 0.05, 0.1, 0.2, 0.4, 0.5, 0.9, 0.999, 0.9999, 1.0]
+    xs = [(0.02 * rng.standard_t(4, n)).astype(np.float32) for n in (1, 7, 65_536, 65_537, 300_001)]
+    xs[2][::3] = 0.0
+    xs[3][:100] = np.float32(1e-41)           # denormals
+    xs.append(np.zeros(1000, np.float32))
+    for alpha in (0.01, 0.05):
+        got = ctx.sketch_quantiles([dev(x) for x in xs], qs, alpha)
+        for x, row in zip(xs, got):
+            mag = np.sort(np.abs(x))
+            for q, est in zip(qs, row):
+                assert est == sk.quantile_estimate(np.abs(x), q, alpha), (x.size, q, alpha)
+                exact = float(mag[int(np.floor(q * (x.size - 1)))])
+                assert abs(est - exact) <= alpha * exact * (1 + 1e-6)
+    # a tensor that does not start at a 16-byte boundary
+    t = dev(xs[4])
+    got = ctx.sketch_quantiles([t[1:]], qs, 0.01)[0]
+    assert got == [sk.quantile_estimate(np.abs(xs[4][1:]), q, 0.01) for q in qs]
+    from paper_2306_11800_amd import api
+    bad = xs[1].copy()
+    bad[3] = np.nan
+    with pytest.raises(api.InshrError) as e:
+        ctx.sketch_quantiles([dev(bad)], [0.5], 0.01)
+    assert e.value.code == -3
+    with pytest.raises(api.InshrError):
+        ctx.sketch_quantiles([dev(xs[1])], [1.5], 0.01)
