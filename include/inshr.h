@@ -352,6 +352,20 @@ int inshr_search_sketch(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr
                         inshr_sketch_choice *choice, inshr_sketch_info *info, uint32_t n_tensors,
                         uint32_t flags);
 
+/* The search of Sec. 5 with the bins of inshr_quantize_sketch over (prune, protect) pairs as well:
+ * pairs[q] names the fractions (bits and bins ignored); every pair is searched over 2 .. 8 bits as
+ * by inshr_search_sketch, one pair after the other (each costs that call's sweeps), and among all
+ * (pair, width) within eps the least payload n_kept * bits + 32 * n_protected + 32 * 2^bits wins
+ * (ties: the lower pair; within a pair the fewest feasible bits are the cheapest); when none is
+ * within eps, the pair whose 8-bit error is least, with 8 bits.  out[t] (sized for 8 bits and the
+ * largest protect fraction) receives the winner's codes, best_pair[t] its index, choice[t] the
+ * winner's row; table (host, [n_tensors][n_pairs], may be NULL) all rows.  params->uniforms holds
+ * 256 numbers per tensor, used for every pair. */
+int inshr_search_sketch_grid(inshr_ctx *ctx, const inshr_tensor *tensors, const inshr_config *pairs,
+                             uint32_t n_pairs, const inshr_sketch_params *params, double eps,
+                             inshr_quantized *out, uint32_t *best_pair, inshr_sketch_choice *choice,
+                             inshr_sketch_choice *table, uint32_t n_tensors);
+
 /* ---- entropy stage of the delta (host memory only, outside the timed path) ------------------- */
 
 typedef struct {

@@ -259,3 +259,26 @@ def search_bits(x, sym_class, alpha, sigma, uniforms, max_iter, eps, bits_range=
             best, feasible = b, True
             break
     return dict(best_bits=best, feasible=feasible, sse=sse, sumsq=sumsq, runs=runs)
+
+
+def search_grid(x, classes_of_pair, alpha, sigma, uniforms, max_iter, eps):
+    """Sec. 5 with the bins of Algorithm 2 over the whole space: for every (prune, protect) pair
+    (classes_of_pair[q] = the symbol classes 0 / 1 / 2 of x under pair q) every bit width is scored
+    as in search_bits; among all (pair, width) whose error is at most eps * sum x^2 the one with
+    the least payload n_kept * bits + 32 * n_protected + 32 * 2^bits is chosen (ties: the lower pair,
+    then the fewer bits); when none qualifies, the pair whose 8-bit error is least, with 8 bits and
+    feasible = False.  Returns dict(pair, bits, feasible, per_pair=[search_bits results])."""
+    per = [search_bits(x, c, alpha, sigma, uniforms, max_iter, eps) for c in classes_of_pair]
+    best = None
+    for q, (r, c) in enumerate(zip(per, classes_of_pair)):
+        c = np.asarray(c)
+        kept, prot = int(np.sum(c >= 2)), int(np.sum(c == 1))
+        for b in sorted(r["sse"]):
+            if r["sse"][b] <= eps * r["sumsq"]:
+                cost = kept * b + 32 * prot + 32 * (1 << b)
+                if best is None or cost < best[0]:
+                    best = (cost, q, b)
+    if best is not None:
+        return dict(pair=best[1], bits=best[2], feasible=True, per_pair=per)
+    q = min(range(len(per)), key=lambda i: (per[i]["sse"][8], i))
+    return dict(pair=q, bits=8, feasible=False, per_pair=per)

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinshr.so")
 
 EXPORTS = ["inshr_create", "inshr_destroy", "inshr_strerror", "inshr_last_device_error",
-           "inshr_sync", "inshr_lds_ordered", "inshr_sketch_quantiles", "inshr_search", "inshr_search_pooled", "inshr_quantize_sens", "inshr_quantize_bound", "inshr_quantize",
+           "inshr_sync", "inshr_lds_ordered", "inshr_sketch_quantiles", "inshr_search_sketch_grid", "inshr_search", "inshr_search_pooled", "inshr_quantize_sens", "inshr_quantize_bound", "inshr_quantize",
            "inshr_quantize_sketch", "inshr_search_sketch", "inshr_sketch_buckets",
            "inshr_delta_bound", "inshr_delta", "inshr_delta_static", "inshr_guided_search", "inshr_neighbourhood_search", "inshr_dequantize", "inshr_reconstruct",
            "inshr_entropy_encode", "inshr_entropy_decode",
@@ -156,6 +156,10 @@ def load_library() -> C.CDLL:
                                         C.c_uint32]
     lib.inshr_sketch_quantiles.argtypes = [C.c_void_p, C.POINTER(CTensor), C.c_uint32, C.POINTER(C.c_double),
                                            C.c_uint32, C.c_double, C.POINTER(C.c_double)]
+    lib.inshr_search_sketch_grid.argtypes = [C.c_void_p, C.POINTER(CTensor), C.POINTER(CConfig), C.c_uint32,
+                                             C.POINTER(CSketchParams), C.c_double, C.POINTER(CQuantized),
+                                             C.POINTER(C.c_uint32), C.POINTER(CSketchChoice),
+                                             C.POINTER(CSketchChoice), C.c_uint32]
     lib.inshr_guided_search.argtypes = [C.POINTER(CScore), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.c_double, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint8)]
@@ -595,6 +599,49 @@ class Context:
         choices = [dict(best_bits=int(c.best_bits), feasible=bool(c.feasible), sse=list(c.sse),
                         sumsq=float(c.sumsq), rounds=list(c.rounds)) for c in choice]
         return res, choices, [(int(i.n_buckets), int(i.rounds)) for i in info]
+
+    # -- inshr_search_sketch_grid ----------------------------------------------------------
+    def search_sketch_grid(self, tensors: Sequence[torch.Tensor], pairs, uniforms, eps: float,
+                           alpha: float = 0.01, sigma: float = 0.2, max_iter: int = 100):
+        """pairs: (prune_ppm, outlier_ppm) tuples.  Returns (list of Quantized of the winners, list
+        of winning pair indices, list of dicts of the winners' rows, table[t][q] of dicts)."""
+        import numpy as np
+        nT, nP = len(tensors), len(pairs)
+        ta = _tensor_array(tensors)
+        pa = _config_array([(8, int(p), int(o)) for p, o in pairs])
+        u = np.ascontiguousarray(uniforms, dtype=np.float64)
+        if u.shape != (nT, 256):
+            raise ValueError("uniforms must have shape [len(tensors), 256]")
+        o_max = max(int(o) for _, o in pairs)
+        qa = (CQuantized * nT)()
+        res = QuantizedBatch()
+        for i, t in enumerate(tensors):
+            n = t.numel()
+            wide = (8, 0, o_max)
+            words, cap = self._bound(n, _config_array([wide])[0], wide)
+            e = qa[i]
+            q = Quantized(n, 8, (
+                torch.empty(words, dtype=torch.int64, device=t.device),
+                torch.empty(256, dtype=torch.float32, device=t.device),
+                torch.empty(255, dtype=torch.float32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.int32, device=t.device),
+                torch.empty(max(cap, 1), dtype=torch.float32, device=t.device)), e, qa)
+            e.packed, e.codebook, e.boundaries, e.outlier_idx, e.outlier_val = q._ptrs
+            e.packed_words = q._bufs[0].numel()
+            e.outlier_cap = q._bufs[3].numel()
+            res.append(q)
+        res._qa = qa
+        res._sizes = tuple(q.n for q in res)
+        par = CSketchParams(float(alpha), float(sigma), int(max_iter), u.ctypes.data)
+        best = (C.c_uint32 * nT)()
+        choice = (CSketchChoice * nT)()
+        table = (CSketchChoice * (nT * nP))()
+        self._check(self.lib.inshr_search_sketch_grid(self.h, ta, pa, nP, C.byref(par), float(eps), qa, best,
+                                                      choice, table, nT))
+        row = lambda c: dict(best_bits=int(c.best_bits), feasible=bool(c.feasible), sse=list(c.sse),
+                             sumsq=float(c.sumsq), rounds=list(c.rounds))
+        return (res, list(best), [row(c) for c in choice],
+                [[row(table[t * nP + q]) for q in range(nP)] for t in range(nT)])
 
     def _bound(self, n, ccfg, cfg):
         key = (n, bins_of(cfg), int(cfg[1]), int(cfg[2]))

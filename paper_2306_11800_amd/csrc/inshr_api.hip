@@ -1207,6 +1207,89 @@ int inshr_search_sketch(inshr_ctx *c, const inshr_tensor *tensors, const inshr_c
     return INSHR_OK;
 }
 
+int inshr_search_sketch_grid(inshr_ctx *c, const inshr_tensor *tensors, const inshr_config *pairs,
+                             uint32_t n_pairs, const inshr_sketch_params *params, double eps,
+                             inshr_quantized *out, uint32_t *best_pair, inshr_sketch_choice *choice,
+                             inshr_sketch_choice *table, uint32_t n_tensors)
+{
+    if (!c || !tensors || !pairs || !params || !out || !best_pair || !choice || n_tensors == 0 || n_pairs == 0)
+        return INSHR_E_ARG;
+    const uint32_t nT = n_tensors;
+    std::vector<inshr_config> cfg(nT);
+    std::vector<inshr_sketch_choice> ch(nT);
+    std::vector<inshr_quantized> tmp(nT);
+    struct Best {
+        bool any = false, feasible = false;
+        uint64_t cost = 0;
+        double sse8 = 0.0;
+        uint32_t pair = 0;
+    };
+    std::vector<Best> best(nT);
+    // every pair in turn: all widths of the pair scored for all tensors (the outputs are scratch here)
+    for (uint32_t q = 0; q < n_pairs; q++) {
+        for (uint32_t t = 0; t < nT; t++) {
+            cfg[t] = pairs[q];
+            cfg[t].bits = 8;
+            cfg[t].bins = 0;
+            tmp[t] = out[t];
+        }
+        int rc = inshr_search_sketch(c, tensors, cfg.data(), params, eps, tmp.data(), ch.data(), nullptr, nT, 0);
+        if (rc) return rc;
+        for (uint32_t t = 0; t < nT; t++) {
+            if (table) table[(size_t)t * n_pairs + q] = ch[t];
+            Best &b = best[t];
+            if (ch[t].feasible) {
+                const uint32_t bits = ch[t].best_bits; // the fewest feasible bits of a pair are its cheapest
+                const uint64_t cost = tmp[t].n_kept * bits + 32ull * tmp[t].n_outlier + (32ull << bits);
+                if (!b.feasible || cost < b.cost) {
+                    b.feasible = true;
+                    b.cost = cost;
+                    b.pair = q;
+                }
+            } else if (!b.feasible && (!b.any || ch[t].sse[6] < b.sse8)) {
+                b.sse8 = ch[t].sse[6];
+                b.pair = q;
+            }
+            b.any = true;
+        }
+    }
+    // the winners once more, pair by pair, into the caller's buffers (same uniforms: same result)
+    std::vector<char> done(nT, 0);
+    for (uint32_t t0 = 0; t0 < nT; t0++) {
+        if (done[t0]) continue;
+        std::vector<inshr_tensor> sub;
+        std::vector<inshr_config> subcfg;
+        std::vector<inshr_quantized> subout;
+        std::vector<uint32_t> idx;
+        std::vector<double> uni;
+        for (uint32_t t = t0; t < nT; t++) {
+            if (!done[t] && best[t].pair == best[t0].pair) {
+                done[t] = 1;
+                sub.push_back(tensors[t]);
+                inshr_config k = pairs[best[t].pair];
+                k.bits = 8;
+                k.bins = 0;
+                subcfg.push_back(k);
+                subout.push_back(out[t]);
+                idx.push_back(t);
+                uni.insert(uni.end(), params->uniforms + (size_t)t * 256, params->uniforms + (size_t)t * 256 + 256);
+            }
+        }
+        inshr_sketch_params p2 = *params;
+        p2.uniforms = uni.data();
+        std::vector<inshr_sketch_choice> ch2(sub.size());
+        int rc = inshr_search_sketch(c, sub.data(), subcfg.data(), &p2, eps, subout.data(), ch2.data(), nullptr,
+                                     (uint32_t)sub.size(), 0);
+        if (rc) return rc;
+        for (size_t k = 0; k < sub.size(); k++) {
+            out[idx[k]] = subout[k];
+            choice[idx[k]] = ch2[k];
+            best_pair[idx[k]] = best[idx[k]].pair;
+        }
+    }
+    return INSHR_OK;
+}
+
 int inshr_sketch_buckets(double alpha, int32_t *i_lo, uint32_t *n_buckets, float *tops, double *values,
                          uint32_t cap)
 {

@@ -250,3 +250,43 @@ def test_sketch_quantile_estimates_equal_the_oracle(ctx):
     assert e.value.code == -3
     with pytest.raises(api.InshrError):
         ctx.sketch_quantiles([dev(xs[1])], [1.5], 0.01)
+
+
+def test_search_over_pairs_and_bits(ctx):
+    """Sec. 5 with the bins of Algorithm 2 over (prune, protect) pairs as well as the bit width: every
+    row of the table against the oracle's search over the bits for that pair, the winner against the
+    oracle's rule (least payload within the bound, else the least 8-bit error), and the winner's codes
+    against the oracle's quantizer."""
+    rng = np.random.default_rng(150)
+    fam = families(rng, 30001)
+    xs = [fam["t3"], fam["zeros"], fam["positive"][:5000], fam["t3"][:9]]
+    pairs = [(0, 0), (100000, 0), (100000, 1000), (300000, 1000), (500000, 10000)]
+    uni = rng.uniform(size=(len(xs), 256))
+    for eps in (1e-2, 2e-4, 1e-9):
+        qs, best, rows, table = ctx.search_sketch_grid([dev(x) for x in xs], pairs, uni, eps, alpha=0.01, sigma=0.2)
+        for i, x in enumerate(xs):
+            bases = [ref.quantize(x, (8, p, o)) for p, o in pairs]
+            classes = [np.minimum(b["sym"], 2) for b in bases]
+            want = sk.search_grid(x, classes, 0.01, 0.2, uni[i], 100, eps)
+            border = False
+            for q in range(len(pairs)):
+                r, ch = want["per_pair"][q], table[i][q]
+                for b in range(2, 9):
+                    assert abs(ch["sse"][b - 2] - r["sse"][b]) <= 1e-6 * r["sse"][b] + 1e-12 * r["sumsq"]
+                    if r["sumsq"] > 0 and abs(r["sse"][b] / r["sumsq"] - eps) <= 4e-6 * eps:
+                        border = True
+                if not border:
+                    assert (ch["best_bits"], ch["feasible"]) == (r["best_bits"], r["feasible"])
+            if border:
+                continue
+            # (an 8-bit error that ties between pairs to the last digits may fall either way)
+            if not want["feasible"]:
+                e8 = sorted(want["per_pair"][q]["sse"][8] for q in range(len(pairs)))
+                if len(e8) > 1 and e8[1] - e8[0] <= 1e-6 * e8[0] + 1e-12 * want["per_pair"][0]["sumsq"]:
+                    continue
+            assert (best[i], rows[i]["best_bits"], rows[i]["feasible"]) == (want["pair"], want["bits"], want["feasible"]), (i, eps)
+            run = want["per_pair"][want["pair"]]["runs"][want["bits"]]
+            got = ref.unpack(qs[i].packed.cpu().numpy().view(np.uint64), x.size, want["bits"] + 1)
+            assert np.array_equal(got, run["sym"])
+            np.testing.assert_allclose(qs[i].codebook.cpu().numpy(), run["codebook"], rtol=1e-6, atol=0)
+            assert np.array_equal(qs[i].outlier_idx.cpu().numpy().view(np.uint32), bases[want["pair"]]["outlier_idx"])

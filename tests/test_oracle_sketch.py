@@ -307,3 +307,32 @@ def test_search_over_bits():
     assert loose["feasible"] is True and loose["best_bits"] == 2
     # more bins never hurt much here: 8 bits are far better than 2
     assert r["sse"][8] < 0.05 * r["sse"][2]
+
+
+def test_search_over_pairs_picks_the_least_payload_within_the_bound():
+    """search_grid against a direct enumeration: quantize every (pair, width), decode, measure."""
+    from oracle import ref
+    rng = np.random.default_rng(61)
+    x = (0.02 * rng.standard_t(3, 4000)).astype(np.float32)
+    uni = rng.uniform(size=256)
+    pairs = [(0, 0), (200000, 0), (200000, 5000), (500000, 5000)]
+    classes = [np.minimum(ref.quantize(x, (8, p, o))["sym"], 2) for p, o in pairs]
+    sumsq = float(np.sum(x.astype(np.float64) ** 2))
+    for eps in (5e-2, 5e-3, 1e-12):
+        got = sk.search_grid(x, classes, 0.01, 0.2, uni, 100, eps)
+        cand = []
+        for q, c in enumerate(classes):
+            for b in range(2, 9):
+                r = sk.quantize_values(x, c, 1 << b, 0.01, 0.2, uni, 100)
+                dec = np.zeros(x.size)
+                kept = c >= 2
+                dec[kept] = r["codebook"].astype(np.float64)[r["sym"][kept].astype(np.int64) - 2]
+                dec[c == 1] = x[c == 1]
+                err = float(np.sum((x.astype(np.float64) - dec) ** 2))
+                cand.append((err, int(kept.sum()) * b + 32 * int((c == 1).sum()) + 32 * (1 << b), q, b))
+        ok = [(cost, q, b) for err, cost, q, b in cand if err <= eps * sumsq]
+        if ok:
+            assert got["feasible"] and (got["pair"], got["bits"]) == min(ok)[1:]
+        else:
+            assert not got["feasible"] and got["bits"] == 8
+            assert got["pair"] == min((err, q) for err, cost, q, b in cand if b == 8)[1]
