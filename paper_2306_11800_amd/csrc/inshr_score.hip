@@ -51,7 +51,10 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
         ckey[tid] = class_edge_key(tid & 3u, st->thr_mag[gd->pair_p[tid >> 2]],
                                    st->thr_mag[n_p + gd->pair_o[tid >> 2]]);
     __syncthreads();
-    for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
+    u64 w[MAX_EDGES / BLOCK]; // this thread's words: positions tid + m * BLOCK of the list
+#pragma unroll
+    for (int m = 0; m < MAX_EDGES / BLOCK; m++) {
+        const u32 i = tid + (u32)m * BLOCK;
         u64 v = ~0ull;
         if (i < n_e) {
             const u32 q = i / epp, r = i % epp;
@@ -74,24 +77,60 @@ __global__ __launch_bounds__(BLOCK) void k_edges(const TDesc *__restrict__ td,
             }
             v = (((below << 1) | is_boundary) << 18) | (corder << 12) | (u64)(q * EPP + e);
         }
-        srt[i] = v;
+        w[m] = v;
     }
-    __syncthreads();
-    for (u32 k = 2; k <= (u32)MAX_EDGES; k <<= 1) { // bitonic sort
-        for (u32 j = k >> 1; j > 0; j >>= 1) {
-            for (u32 i = tid; i < (u32)MAX_EDGES; i += BLOCK) {
-                const u32 l = i ^ j;
-                if (l > i) {
-                    const u64 a = srt[i], b = srt[l];
-                    const bool up = (i & k) == 0;
-                    if ((a > b) == up) {
-                        srt[i] = b;
-                        srt[l] = a;
+    // Bitonic sort.  Position i = tid + m * BLOCK: a partner i ^ j lies in the same thread for
+    // j >= BLOCK (registers), in the same wave for j < 64 (a lane exchange), and only for the strides
+    // in between in another wave (through LDS, two buffers in turn, one barrier per step): 18 of the
+    // 78 steps.  With a barrier after every step the sort took two thirds of this kernel.
+    {
+        u64 *buf[2] = {srt, reinterpret_cast<u64 *>(smem + 2 * MAX_EDGES)}; // (ebin and segc are not in use yet)
+        int cur = 0;
+        for (u32 k = 2; k <= (u32)MAX_EDGES; k <<= 1) {
+            for (u32 j = k >> 1; j > 0; j >>= 1) {
+                if (j >= (u32)BLOCK) {
+                    const u32 dm = j / BLOCK;
+#pragma unroll
+                    for (u32 m = 0; m < (u32)(MAX_EDGES / BLOCK); m++) {
+                        const u32 mm = m ^ dm;
+                        if (mm > m) {
+                            const u32 i = tid + m * BLOCK;
+                            const bool up = (i & k) == 0u;
+                            const u64 a = w[m], b = w[mm];
+                            if ((a > b) == up) {
+                                w[m] = b;
+                                w[mm] = a;
+                            }
+                        }
                     }
+                } else if (j < 64u) {
+#pragma unroll
+                    for (u32 m = 0; m < (u32)(MAX_EDGES / BLOCK); m++) {
+                        const u32 i = tid + m * BLOCK;
+                        const u64 a = w[m], b = __shfl_xor(a, (int)j);
+                        const bool keep_small = ((i & j) == 0u) == ((i & k) == 0u);
+                        w[m] = keep_small ? (a < b ? a : b) : (a > b ? a : b);
+                    }
+                } else {
+                    u64 *sb = buf[cur];
+#pragma unroll
+                    for (u32 m = 0; m < (u32)(MAX_EDGES / BLOCK); m++) sb[tid + m * BLOCK] = w[m];
+                    __syncthreads();
+#pragma unroll
+                    for (u32 m = 0; m < (u32)(MAX_EDGES / BLOCK); m++) {
+                        const u32 i = tid + m * BLOCK;
+                        const u64 a = w[m], b = sb[i ^ j];
+                        const bool keep_small = ((i & j) == 0u) == ((i & k) == 0u);
+                        w[m] = keep_small ? (a < b ? a : b) : (a > b ? a : b);
+                    }
+                    cur ^= 1; // (the next exchange writes the other buffer: no second barrier)
                 }
             }
-            __syncthreads();
         }
+        __syncthreads();
+#pragma unroll
+        for (u32 m = 0; m < (u32)(MAX_EDGES / BLOCK); m++) srt[tid + m * BLOCK] = w[m];
+        __syncthreads();
     }
     u32 *E = B.edges + (size_t)t * MAX_EDGES;
     u32 *eb = B.edge_bin + (size_t)t * MAX_EDGES;
