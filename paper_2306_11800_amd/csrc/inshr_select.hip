@@ -1473,8 +1473,17 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
             const u32 rows = (n + BB - 1u) / BB; // rows of 64 keys per wave
             const u32 chunk = rows * 64u;
             u32 *wcnt = wcount + wave * 256u;
-            for (u32 shift = 0; shift < 32u && (dbits >> shift) != 0u; shift += 8u) {
-                if (((dbits >> shift) & 255u) == 0u) continue; // this digit is the same in all keys
+            // The keys differ in the bits b_lo .. b_hi only.  These are cut into digits of equal
+            // width, at most 8 bits: with fixed 8-bit digits the last one is often two or three bits
+            // wide, a wave's 64 keys then share a handful of digit values, and the returning adds on
+            // one counter serialise (the top pass took as long as the other two together).
+            const u32 b_lo = dbits ? (u32)__ffs((int)dbits) - 1u : 0u;
+            const u32 n_bits = dbits ? 32u - (u32)__clz((int)dbits) - b_lo : 0u;
+            const u32 n_pass = (n_bits + 7u) >> 3;
+            const u32 dwidth = n_pass ? (n_bits + n_pass - 1u) / n_pass : 0u;
+            const u32 dmask = (1u << dwidth) - 1u;
+            for (u32 pass = 0; pass < n_pass; pass++) {
+                const u32 shift = b_lo + pass * dwidth;
                 for (u32 i = tid; i < (BB / 64) * 256u; i += BB) wcount[i] = 0u;
                 __syncthreads();
                 u32 kreg[SORT_ROWS], rreg[SORT_ROWS];
@@ -1487,7 +1496,7 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                         const bool valid = i < n;
                         const u32 k = valid ? from[i] : 0u;
                         kreg[r] = k;
-                        rreg[r] = digit_rank<ORDERED>(wcnt, (k >> shift) & 255u, valid);
+                        rreg[r] = digit_rank<ORDERED>(wcnt, (k >> shift) & dmask, valid);
                     }
                 }
                 __syncthreads();
@@ -1519,7 +1528,7 @@ __global__ __launch_bounds__(BB) void k_bucket(const TDesc *__restrict__ td, int
                 for (u32 r = 0; r < (u32)SORT_ROWS; r++) {
                     if (r < rows) {
                         const u32 i = wave * chunk + r * 64u + lane;
-                        if (i < n) to[wcnt[(kreg[r] >> shift) & 255u] + rreg[r]] = kreg[r];
+                        if (i < n) to[wcnt[(kreg[r] >> shift) & dmask] + rreg[r]] = kreg[r];
                     }
                 }
                 __syncthreads();
