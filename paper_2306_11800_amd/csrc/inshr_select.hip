@@ -1180,6 +1180,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather(const TDesc *__restrict__ td, 
 // ------------------------------------------------------------------------------------------
 constexpr int SPLIT_PER = 8; // keys per thread per step
 constexpr int SPLIT_PARTS = 4; // workgroups that share one unit (they take its steps in turn)
+constexpr int STAGE_G = 1536;   // most groups of a tensor for the staged stores of the split
 
 __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
                                                  const u32 *__restrict__ fu_tensor, Bufs B)
@@ -1209,6 +1210,19 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
     for (u32 i = tid; i < nb2; i += BLOCK) gtab[i] = B.bin_group[(size_t)t * L2_BINS + i];
     for (u32 g = tid; g < G; g += BLOCK) gcount[g] = 0u;
     __syncthreads();
+    // With at most STAGE_G groups the keys of a step are first put in group order in LDS and stored
+    // from there: a wave's 64 stores then go to a few runs of consecutive addresses instead of 64
+    // places (the stores of a step were what the kernel waited for).
+    const bool staged = G <= (u32)STAGE_G;
+    // (then counters and starts take STAGE_G entries each of the two MAX_GROUPS arrays, and the
+    // stage what is left of them)
+    constexpr int STEP_KEYS = 64 * SPLIT_PER * (BLOCK / 64);
+    u16 *glp = reinterpret_cast<u16 *>(gcount + 2 * STAGE_G);    // [STAGE_G] first staged place of each group
+    u32 *stage_key = gcount + 2 * STAGE_G + STAGE_G / 2;         // [STEP_KEYS]
+    u16 *stage_g = reinterpret_cast<u16 *>(stage_key + STEP_KEYS); // [STEP_KEYS] group of each staged key
+    static_assert(2 * STAGE_G + STAGE_G / 2 + STEP_KEYS + STEP_KEYS / 2 <= 2 * MAX_GROUPS, "the stage fits the group arrays");
+    __shared__ u32 s_part[BLOCK / 64 + 1];
+    if (staged) gbase = gcount + STAGE_G;
     for (u32 base = blockIdx.y * 64u * SPLIT_PER; base < cmax; base += SPLIT_PARTS * 64u * SPLIT_PER) {
         u32 key[SPLIT_PER], gr[SPLIT_PER]; // group << 16 | rank inside (step, group)
 #pragma unroll
@@ -1226,18 +1240,58 @@ __global__ __launch_bounds__(BLOCK) void k_split(const TDesc *__restrict__ td,
             }
         }
         __syncthreads();
-        for (u32 g = tid; g < G; g += BLOCK) {
-            const u32 k = gcount[g];
-            if (k) {
-                gbase[g] = goff[g] + atomicAdd(&gcur[g], k);
+        if (!staged) {
+            for (u32 g = tid; g < G; g += BLOCK) {
+                const u32 k = gcount[g];
+                if (k) {
+                    gbase[g] = goff[g] + atomicAdd(&gcur[g], k);
+                    gcount[g] = 0u;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < SPLIT_PER; j++) {
+                const u32 i = base + lane + j * 64u;
+                if (i < c && gr[j] != 0xFFFFFFFFu) dst[gbase[gr[j] >> 16] + (gr[j] & 0xFFFFu)] = key[j];
+            }
+            __syncthreads();
+            continue;
+        }
+        // two groups per thread: where their keys go in the tensor's group order, and in the stage
+        u32 k2[2], tot2 = 0u;
+#pragma unroll
+        for (u32 h = 0; h < 2u; h++) {
+            const u32 g = 2u * tid + h;
+            k2[h] = g < G ? gcount[g] : 0u;
+            if (k2[h]) {
+                gbase[g] = goff[g] + atomicAdd(&gcur[g], k2[h]);
                 gcount[g] = 0u;
             }
+            tot2 += k2[h];
         }
+        const u32 inc = wave_incl_scan(tot2);
+        if (lane == 63u) s_part[wave] = inc;
+        __syncthreads();
+        u32 before = inc - tot2;
+        for (u32 w = 0; w < wave; w++) before += s_part[w];
+        u32 staged_total = 0u;
+        for (u32 w = 0; w < (u32)(BLOCK / 64); w++) staged_total += s_part[w];
+        if (2u * tid < G) glp[2u * tid] = (u16)before;
+        if (2u * tid + 1u < G) glp[2u * tid + 1u] = (u16)(before + k2[0]);
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < SPLIT_PER; j++) {
             const u32 i = base + lane + j * 64u;
-            if (i < c && gr[j] != 0xFFFFFFFFu) dst[gbase[gr[j] >> 16] + (gr[j] & 0xFFFFu)] = key[j];
+            if (i < c && gr[j] != 0xFFFFFFFFu) {
+                const u32 g = gr[j] >> 16, at = (u32)glp[g] + (gr[j] & 0xFFFFu);
+                stage_key[at] = key[j];
+                stage_g[at] = (u16)g;
+            }
+        }
+        __syncthreads();
+        for (u32 at = tid; at < staged_total; at += BLOCK) {
+            const u32 g = stage_g[at];
+            dst[gbase[g] + (at - (u32)glp[g])] = stage_key[at];
         }
         __syncthreads();
     }
