@@ -1417,7 +1417,7 @@ __device__ __forceinline__ GroupHead group_head(const Bufs &B, const u32 *grp_li
 }
 
 // One group of active bins per step: its keys are sorted in LDS (least significant digit first,
-// 8 bits per pass, only the digits in which the keys differ).  Every boundary of the group is read
+// digits of equal width of at most 8 bits over the bits in which the keys differ).  Every boundary of the group is read
 // at its rank (offset of its bin inside the group + residual rank inside the bin); then all edges
 // of the group are known, and the group's keys are counted and summed per slot.  The slot below
 // the group's first edge is shared with the group before it: its figures go to the "upper" half
