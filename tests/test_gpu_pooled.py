@@ -139,3 +139,24 @@ def test_delta_after_a_pooled_search(ctx):
         rp = ref.quantize(prevs[i], cp[i], pool=pp[1])
         rc = ref.quantize(curs[i], cc[i], pool=pc[1])
         check_delta(d[i], rp, cp[i][0], rc, cc[i][0], True)
+
+
+def test_protected_share_beyond_the_fraction_needs_room(ctx):
+    """With shared thresholds one tensor can hold most of the group's protected values: buffers sized
+    by the fraction alone are refused (INSHR_E_CAPACITY), never overrun."""
+    from paper_2306_11800_amd import api
+    rng = np.random.default_rng(86)
+    small = (0.02 * rng.standard_normal(200_000)).astype(np.float32)
+    large = (0.5 * rng.standard_normal(3_000)).astype(np.float32)     # holds the group's largest magnitudes
+    ts = [dev(small), dev(large)]
+    cfg = (4, 100000, 5000)
+    best, feas, sc = ctx.search(ts, [cfg], 0.01, groups=[1, 1])
+    assert sc[1].n_outlier > large.size * cfg[2] // 1000000           # more than its own fraction
+    with pytest.raises(api.InshrError) as e:
+        ctx.quantize(ts, [cfg, cfg], reuse_search=True)               # capacity from the fraction
+    assert e.value.code == -4
+    best, feas, sc = ctx.search(ts, [cfg], 0.01, groups=[1, 1])
+    qs = ctx.quantize(ts, [cfg, cfg], reuse_search=True, outlier_caps=[int(sc[0].n_outlier) + 1, int(sc[1].n_outlier)])
+    pool = ref.pool_of([small, large])
+    for q, x in zip(qs, (small, large)):
+        check_quantized(q, x, cfg, given=ref.quantize(x, cfg, pool=pool))
