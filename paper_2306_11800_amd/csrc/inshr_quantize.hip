@@ -266,10 +266,18 @@ __global__ __launch_bounds__(BLOCK) void k_quant(const TDesc *__restrict__ td, i
             // the tile's words leave, and the buffer is clean for the tile after the next
             const u32 n_words = (cnt * w_ + 63u) >> 6;
             GLOBAL_AS unsigned long long *dst = packed + (tl - d.tile0) * (u64)(256u * w_);
-            for (u32 k = tid; k < 256u * w_; k += BLOCK) {
-                const unsigned long long x = pk[k];
-                if (k < n_words) dst[k] = x;
-                pk[k] = 0ull;
+            // (at most 9 * 256 words: three per thread, read together, so the LDS latency is paid once)
+            unsigned long long xw[3];
+#pragma unroll
+            for (u32 j = 0; j < 3u; j++) {
+                const u32 k = tid + j * BLOCK;
+                xw[j] = k < 256u * w_ ? pk[k] : 0ull;
+            }
+#pragma unroll
+            for (u32 j = 0; j < 3u; j++) {
+                const u32 k = tid + j * BLOCK;
+                if (k < n_words) dst[k] = xw[j];
+                if (k < 256u * w_) pk[k] = 0ull;
             }
             // protected values in ascending index: quarter j, wave, lane, c
             const u32 wc = wcnt[lane];
